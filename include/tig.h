@@ -1,0 +1,192 @@
+/*
+ * libtig -- the chronological mini-batch step of a memory-based temporal-interaction-graph
+ * (TIG) model on one AMD MI355X (gfx950), as a C ABI.
+ *
+ * The step is the encoder/decoder data flow of the paper's Sec. II-C ("Training approach for
+ * TIGs") on the shape one GPU's partition sees under the paper's partition-parallel training
+ * (Sec. II-C "Distributed Parallel Training": one sub-graph, one N^(k) x d memory and one model
+ * replica per GPU):
+ *
+ *   memory fetch -> message [s_self | s_other | Phi(dt) | e_ij] -> last message per node ->
+ *   GRU state update -> memory overwrite -> attention embedding over the K most recent
+ *   neighbours (history strictly before the event time, Sec. II-A) -> MLP link decoder.
+ *
+ * Conventions
+ *   - every call returns TIG_OK (0) or a negative tig_status; nothing throws or aborts;
+ *   - structs are plain data and start with `struct_size = sizeof(the struct)`;
+ *   - the CALLER owns all device memory: the two workspaces handed to tig_init and every
+ *     output buffer.  The library allocates no device memory;
+ *   - pointers documented "host or device" are resolved through HIP's unified addressing;
+ *     pointers documented "device" must be device memory readable by kernels;
+ *   - a context is not thread-safe; distinct contexts are independent;
+ *   - all validation that can be done on the host happens before anything is launched, and a
+ *     call that fails leaves the model state (memory, last_update) unchanged.
+ */
+#ifndef TIG_H
+#define TIG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TIG_API __attribute__((visibility("default")))
+
+typedef enum tig_status {
+    TIG_OK = 0,
+    TIG_EINVAL = -1,    /* NULL pointer, bad struct_size, dimension out of the supported range */
+    TIG_ERANGE = -2,    /* a node id or event id is out of range */
+    TIG_EUNSORTED = -3, /* event times are not non-decreasing */
+    TIG_ESELFLOOP = -4, /* an event has src == dst */
+    TIG_ENOSPACE = -5,  /* a workspace is smaller than tig_workspace_bytes reports */
+    TIG_EHIP = -6,      /* a HIP call failed; text via tig_last_error */
+    TIG_ENOMEM = -7     /* host allocation of the context failed */
+} tig_status;
+
+typedef enum tig_precision {
+    TIG_FP32 = 0,      /* fp32 operands, fp32 accumulation on the matrix cores */
+    TIG_BF16_MFMA = 1  /* weight matrices and matrix-core operands rounded to bf16 (RNE), fp32
+                          accumulation; biases, gates, softmax, time encoding, state stay fp32 */
+} tig_precision;
+
+/* Model / launch shape.  Notation: M memory width, T time-encoding width, F edge-feature
+ * width, E embedding width, K neighbours, H heads, B events per batch.
+ * D_msg = 2M+T+F, d_a = M+T (must be divisible by H), d_kv = M+F+T.
+ * Limits: 1 <= M,T,F,E <= 512; 1 <= K <= 64; H in {1,2,4}; 1 <= max_batch <= 65536. */
+typedef struct tig_config {
+    uint32_t struct_size;
+    int32_t mem_dim;       /* M */
+    int32_t time_dim;      /* T */
+    int32_t feat_dim;      /* F */
+    int32_t emb_dim;       /* E */
+    int32_t num_neighbors; /* K */
+    int32_t num_heads;     /* H */
+    int32_t max_batch;     /* largest `count` tig_step will be given */
+    int32_t precision;     /* tig_precision, fixed for the life of the context */
+} tig_config;
+
+/* The temporal interaction graph G = (V, E) of Sec. II-A: events (i, j, t) with a feature row
+ * each, listed in chronological order; event id = position in the list.  All arrays: host or
+ * device.  The library copies what it needs; the caller may free its copies after tig_init. */
+typedef struct tig_graph {
+    uint32_t struct_size;
+    uint32_t reserved;
+    int64_t num_nodes;      /* N: ids are 0..N-1 */
+    int64_t num_events;     /* < 2^30 */
+    const int32_t *src;     /* [num_events] */
+    const int32_t *dst;     /* [num_events], dst != src */
+    const double *ts;       /* [num_events], non-decreasing */
+    const float *edge_feat; /* [num_events x F] row-major */
+} tig_graph;
+
+/* Model parameters, fp32, row-major [out x in]; host or device.
+ *   time encoding      Phi(x)_k = cos(time_w[k] * x + time_b[k])              [T], [T]
+ *   GRU (gates r,z,n)  W_i [3M x D_msg], b_i [3M], W_h [3M x M], b_h [3M]
+ *   attention          W_Q [d_a x d_a], W_K, W_V [d_a x d_kv], W_O [d_a x d_a], biases [d_a]
+ *   merge MLP          W_m1 [E x (d_a+M)], b_m1 [E], W_m2 [E x E], b_m2 [E]
+ *   decoder MLP        W_d1 [E x 2E], b_d1 [E], w_d2 [E], b_d2 [1]
+ * Message layout is [s_self (M) | s_other (M) | Phi (T) | e_ij (F)]; key/value rows are
+ * [s_neighbour (M) | e (F) | Phi (T)]; the query row is [s_node (M) | Phi(0) (T)]. */
+typedef struct tig_weights {
+    uint32_t struct_size;
+    uint32_t reserved;
+    const float *time_w, *time_b;
+    const float *W_i, *b_i, *W_h, *b_h;
+    const float *W_Q, *b_Q, *W_K, *b_K, *W_V, *b_V, *W_O, *b_O;
+    const float *W_m1, *b_m1, *W_m2, *b_m2;
+    const float *W_d1, *b_d1, *w_d2, *b_d2;
+} tig_weights;
+
+/* One chronological mini-batch: the `count` events first_eid .. first_eid+count-1. */
+typedef struct tig_batch {
+    uint32_t struct_size;
+    int32_t count;          /* 1 .. max_batch */
+    int64_t first_eid;      /* first_eid + count <= num_events */
+    const int32_t *neg_dst; /* device, [count]: one negative destination per event, or NULL
+                               (then no negative rows and no score_neg are produced) */
+} tig_batch;
+
+/* Outputs, all device memory owned by the caller.  Q = 3*count with negatives, else 2*count;
+ * query rows are ordered [sources | destinations | negatives].  NULL = not wanted. */
+typedef struct tig_out {
+    uint32_t struct_size;
+    uint32_t reserved;
+    float *emb;         /* [Q x E] embeddings emb_i(t)                      (required) */
+    float *score_pos;   /* [count] logit g(emb_src, emb_dst)                (required) */
+    float *score_neg;   /* [count] logit g(emb_src, emb_neg); required iff neg_dst != NULL */
+    int32_t *nbr_node;  /* [Q x K] neighbour ids, slot 0 most recent, -1 = unused slot */
+    int32_t *nbr_eid;   /* [Q x K] their event ids, -1 = unused */
+    double *nbr_ts;     /* [Q x K] their event times, 0.0 = unused */
+    int32_t *nbr_cnt;   /* [Q] number of used slots */
+    uint8_t *is_winner; /* [2*count] entry 2*b+role (role 0 = source): 1 if that occurrence
+                           supplied the node's (last) message of this batch */
+} tig_out;
+
+typedef struct tig_ctx tig_ctx;
+
+/*
+ * Sizes of the two device buffers the caller must allocate (256-byte aligned) for tig_init.
+ * `persistent` holds the graph copy, the temporal adjacency, the model state and the prepared
+ * weights for the life of the context; `scratch` holds per-step intermediates (and transient
+ * data during tig_init).  Only num_nodes / num_events of `graph` are read (pointers may be NULL).
+ */
+TIG_API int tig_workspace_bytes(const tig_config *cfg, const tig_graph *graph,
+                                size_t *persistent_bytes, size_t *scratch_bytes);
+
+/*
+ * Creates a context: copies graph and weights into `persistent`, validates the graph on the
+ * device (ids in range -> TIG_ERANGE, times non-decreasing -> TIG_EUNSORTED, no self-loops ->
+ * TIG_ESELFLOOP), builds the per-node time-ordered adjacency over ALL events (each event is
+ * listed under both endpoints), prepares the weights for the matrix cores, and zeroes the
+ * state (memory and last_update), which is the state after a reset (Alg. 2).
+ * `hip_stream` is a hipStream_t (NULL = the default stream); every later call enqueues on it.
+ * Synchronous: returns after the device has finished.  On failure *out is NULL.
+ */
+TIG_API int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *weights,
+                     void *persistent, size_t persistent_bytes, void *scratch, size_t scratch_bytes,
+                     void *hip_stream, tig_ctx **out);
+
+/*
+ * One batch step (Sec. II-C), enqueued on the context's stream; does NOT synchronise.
+ *   1. messages are built from the memory as it stands when the step starts;
+ *   2. per node, the occurrence with the greatest (time, event id) supplies the message;
+ *   3. GRU update; memory rows and last_update of exactly those nodes are overwritten;
+ *   4. for every query (node, t_event): the K most recent incident events with time < t_event,
+ *      taken from the whole graph given at tig_init, ordered by (time, event id) descending;
+ *   5. attention over them with the UPDATED memory, merge MLP -> emb; decoder -> scores.
+ * Errors (nothing is launched): TIG_EINVAL for NULL required pointers or count out of 1..max_batch,
+ * TIG_ERANGE if the event range leaves the graph.  neg_dst values must be valid node ids (they
+ * are not checked on the device; an id outside 0..N-1 is treated as a node without history and
+ * with zero memory).
+ */
+TIG_API int tig_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *out);
+
+/* Memory reset at the start of a data cycle (Alg. 2): memory <- 0, last_update <- 0. Async. */
+TIG_API int tig_reset(tig_ctx *ctx);
+
+/*
+ * Backup / restore of the node memory (end-of-cycle backup and end-of-epoch restore, Sec. II-C
+ * and Alg. 2).  mem: [N x M] fp32 row-major, last_update: [N] fp64; host or device.
+ * Synchronous (they wait for the stream, copy, and return).
+ */
+TIG_API int tig_state_export(tig_ctx *ctx, float *mem_out, double *last_update_out);
+TIG_API int tig_state_import(tig_ctx *ctx, const float *mem_in, const double *last_update_in);
+
+/* Frees the host-side context.  Device buffers belong to the caller and are not touched. */
+TIG_API void tig_destroy(tig_ctx *ctx);
+
+/* Static text for a status code / detail of the last failure on this context ("" if none). */
+TIG_API const char *tig_strerror(int status);
+TIG_API const char *tig_last_error(const tig_ctx *ctx);
+
+/* Number of kernels one tig_step enqueues and the dynamic LDS bytes of the two tile kernels
+ * (for reports); any pointer may be NULL. */
+TIG_API int tig_launch_info(const tig_ctx *ctx, int32_t *kernels_per_step, int32_t *gru_lds_bytes,
+                            int32_t *embed_lds_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TIG_H */

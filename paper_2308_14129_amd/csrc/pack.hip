@@ -1,0 +1,373 @@
+// Weight preparation (once, in tig_init): algebraic folding in fp64, zero padding to matrix-core
+// tile sizes, and re-ordering so that every wavefront operand load is one contiguous 1 KiB read.
+//
+// Foldings (exact algebra on the attention embedding f and merge MLP of Sec. II-C):
+//   * scores: <Q_h, W_K,h kv + b_K,h> / sqrt(d_h) = <q~_h, kv> + const, with
+//       q~_h = (W_K,h^T W_Q[h, :M] / sqrt(d_h)) s_u + W_K,h^T (W_Q[h, M:] Phi(0) + b_Q,h) / sqrt(d_h);
+//     the constant is the same for every neighbour slot and cancels in the softmax;
+//   * values: sum_k a_k (W_V,h kv_k + b_V,h) = W_V,h (sum_k a_k kv_k) + b_V,h   (sum_k a_k = 1);
+//   * out-projection and the first merge layer are linear in that sum, so
+//       W_m1 [attn | s_u] + b_m1 = sum_h (W_m1a W_O[:, h] W_V,h) kvbar_h + W_m1m s_u
+//                                  + b_m1 + W_m1a (W_O b_V + b_O);
+//   * GRU: the hidden products of the r and z gates act on s_u, which is also the first M
+//     entries of the message, so W_hr / W_hz are added onto those columns of W_ir / W_iz.
+#include <hip/hip_runtime.h>
+
+#include "tig_internal.h"
+
+namespace tig {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+struct Carver {
+    char *base;
+    size_t off = 0;
+    explicit Carver(void *p) : base((char *)p) {}
+    template <typename T>
+    T *take(size_t count)
+    {
+        T *p = base ? (T *)(base + off) : nullptr;
+        off += align_up(sizeof(T) * count);
+        return p;
+    }
+};
+
+// C[i*ldc + j] = beta * C[..] + alpha * sum_k A[i*ars + k*acs] * B[k*brs + j*bcs]   (fp64 accumulate)
+template <typename TA, typename TB>
+__global__ void k_gemm64(double *C, int ldc, const TA *A, int ars, int acs, const TB *B, int brs,
+                         int bcs, int m, int n, int kdim, double alpha, double beta)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= m * n)
+        return;
+    const int i = idx / n, j = idx % n;
+    double acc = 0.0;
+    for (int k = 0; k < kdim; ++k)
+        acc += (double)A[(size_t)i * ars + (size_t)k * acs] * (double)B[(size_t)k * brs + (size_t)j * bcs];
+    double *c = C + (size_t)i * ldc + j;
+    *c = (beta != 0.0 ? beta * *c : 0.0) + alpha * acc;
+}
+
+template <typename TA, typename TB>
+hipError_t gemm64(hipStream_t s, double *C, int ldc, const TA *A, int ars, int acs, const TB *B,
+                  int brs, int bcs, int m, int n, int kdim, double alpha, double beta)
+{
+    const int total = m * n;
+    hipLaunchKernelGGL((k_gemm64<TA, TB>), dim3((total + kThreads - 1) / kThreads), dim3(kThreads), 0,
+                       s, C, ldc, A, ars, acs, B, brs, bcs, m, n, kdim, alpha, beta);
+    return hipGetLastError();
+}
+
+// out[i] = a[i] (+ b[i]) as double / as float, zero beyond n up to n_pad
+__global__ void k_vec_f32(float *out, int n_pad, int n, const double *a, const float *b, const float *c)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_pad)
+        return;
+    double v = 0.0;
+    if (i < n) {
+        if (a)
+            v += a[i];
+        if (b)
+            v += (double)b[i];
+        if (c)
+            v += (double)c[i];
+    }
+    out[i] = (float)v;
+}
+
+__global__ void k_phi0(double *out, const float *time_b, int T)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < T)
+        out[i] = cos((double)time_b[i]);
+}
+
+// D[i*ld + j] = (double)A[i*lda + j] + (j < cols_b ? B[i*ldb + j] : 0)
+__global__ void k_add_cols(double *D, int ld, const float *A, int lda, const float *B, int ldb,
+                           int rows, int cols, int cols_b)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= rows * cols)
+        return;
+    const int i = idx / cols, j = idx % cols;
+    double v = (double)A[(size_t)i * lda + j];
+    if (j < cols_b)
+        v += (double)B[(size_t)i * ldb + j];
+    D[(size_t)i * ld + j] = v;
+}
+
+__global__ void k_copy_block(double *D, int ld, const float *A, int lda, int rows, int cols)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= rows * cols)
+        return;
+    const int i = idx / cols, j = idx % cols;
+    D[(size_t)i * ld + j] = (double)A[(size_t)i * lda + j];
+}
+
+__device__ inline uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Lane-ordered layout read by the tile GEMMs: for output tile nt (16 rows of W), k-block kb,
+// lane l: VL consecutive k's  W[nt*16 + l%16][kb*KB + VL*(l/16) + 0..VL-1], VL = KB/4.
+// One wavefront operand load = 64 lanes x 16 bytes, contiguous.
+template <typename TS, bool BF16>
+__global__ void k_pack(void *out, const TS *W, int ld, int rows, int cols, int rows_p, int cols_p)
+{
+    constexpr int KB = BF16 ? 32 : 16;
+    constexpr int VL = KB / 4;
+    const size_t total = (size_t)rows_p * cols_p;
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total)
+        return;
+    const int s = (int)(idx % VL);
+    const int lane = (int)((idx / VL) % 64);
+    const size_t blk = idx / (VL * 64);
+    const int kbs = cols_p / KB;
+    const int kb = (int)(blk % kbs);
+    const int nt = (int)(blk / kbs);
+    const int r = nt * 16 + (lane % 16);
+    const int c = kb * KB + VL * (lane / 16) + s;
+    float v = 0.0f;
+    if (r < rows && c < cols)
+        v = (float)W[(size_t)r * ld + c];
+    if (BF16)
+        ((uint16_t *)out)[idx] = f32_to_bf16_rne(v);
+    else
+        ((float *)out)[idx] = v;
+}
+
+template <typename TS>
+hipError_t pack(hipStream_t s, int prec, void *out, const TS *W, int ld, int rows, int cols,
+                int rows_p, int cols_p)
+{
+    const size_t total = (size_t)rows_p * cols_p;
+    const dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
+    if (prec == TIG_BF16_MFMA)
+        hipLaunchKernelGGL((k_pack<TS, true>), grid, dim3(kThreads), 0, s, out, W, ld, rows, cols,
+                           rows_p, cols_p);
+    else
+        hipLaunchKernelGGL((k_pack<TS, false>), grid, dim3(kThreads), 0, s, out, W, ld, rows, cols,
+                           rows_p, cols_p);
+    return hipGetLastError();
+}
+
+struct PackedLayout {
+    float *time_w, *time_b;
+    void *gru_Wr, *gru_Wz, *gru_Win, *gru_Whn;
+    float *gru_br, *gru_bz, *gru_bin, *gru_bhn;
+    void *emb_A1;
+    float *emb_a1;
+    void *emb_PR;
+    float *emb_c, *emb_c0;
+    void *emb_Wm2;
+    float *emb_bm2;
+    void *dec_W;
+    float *dec_b1, *dec_w2, *dec_b2;
+    size_t bytes;
+};
+
+PackedLayout layout(const Dims &d, void *base)
+{
+    Carver c(base);
+    PackedLayout L;
+    const size_t e = (size_t)d.esz;
+    L.time_w = c.take<float>(d.T);
+    L.time_b = c.take<float>(d.T);
+    L.gru_Wr = c.take<char>(e * d.Ng * d.Kg);
+    L.gru_Wz = c.take<char>(e * d.Ng * d.Kg);
+    L.gru_Win = c.take<char>(e * d.Ng * d.Kg);
+    L.gru_Whn = c.take<char>(e * d.Ng * d.Khn);
+    L.gru_br = c.take<float>(d.Ng);
+    L.gru_bz = c.take<float>(d.Ng);
+    L.gru_bin = c.take<float>(d.Ng);
+    L.gru_bhn = c.take<float>(d.Ng);
+    L.emb_A1 = c.take<char>(e * d.N1 * d.Mq);
+    L.emb_a1 = c.take<float>(d.N1);
+    L.emb_PR = c.take<char>(e * d.Ep * d.K2);
+    L.emb_c = c.take<float>(d.Ep);
+    L.emb_c0 = c.take<float>(d.Ep);
+    L.emb_Wm2 = c.take<char>(e * d.Ep * d.Ek);
+    L.emb_bm2 = c.take<float>(d.Ep);
+    L.dec_W = c.take<char>(e * 2 * d.Ep * d.Ek);
+    L.dec_b1 = c.take<float>(d.Ep);
+    L.dec_w2 = c.take<float>(d.Ep);
+    L.dec_b2 = c.take<float>(1);
+    L.bytes = c.off;
+    return L;
+}
+
+struct ScratchLayout {
+    double *phi0, *cQ, *A1, *a1, *G, *PR, *cvec, *gv, *Wr, *Wz, *dec;
+    size_t bytes;
+};
+
+ScratchLayout scratch_layout(const Dims &d, void *base)
+{
+    Carver c(base);
+    ScratchLayout S;
+    S.phi0 = c.take<double>(d.T);
+    S.cQ = c.take<double>(d.da);
+    S.A1 = c.take<double>((size_t)d.N1 * d.M);
+    S.a1 = c.take<double>(d.N1);
+    S.G = c.take<double>((size_t)d.E * d.da);
+    S.PR = c.take<double>((size_t)d.E * (d.H * d.dkvp + d.M));
+    S.cvec = c.take<double>(d.E);
+    S.gv = c.take<double>(d.da);
+    S.Wr = c.take<double>((size_t)d.M * d.Dmsg);
+    S.Wz = c.take<double>((size_t)d.M * d.Dmsg);
+    S.dec = c.take<double>((size_t)2 * d.Ep * d.E);
+    S.bytes = c.off;
+    return S;
+}
+
+#define TIG_TRY(expr)              \
+    do {                           \
+        hipError_t e_ = (expr);    \
+        if (e_ != hipSuccess)      \
+            return e_;             \
+    } while (0)
+
+}  // namespace
+
+size_t pack_scratch_bytes(const Dims &d) { return scratch_layout(d, nullptr).bytes; }
+size_t packed_weights_bytes(const Dims &d) { return layout(d, nullptr).bytes; }
+
+hipError_t pack_weights(const Dims &d, const tig_weights &w, void *dst, void *scratch,
+                        PackedWeights *pw, hipStream_t s)
+{
+    const PackedLayout L = layout(d, dst);
+    const ScratchLayout S = scratch_layout(d, scratch);
+    const int M = d.M, T = d.T, E = d.E, H = d.H, da = d.da, dh = d.dh, dkv = d.dkv;
+    const int Dmsg = d.Dmsg;
+    const dim3 blk(kThreads);
+    auto grid = [](size_t n) { return dim3((unsigned)((n + kThreads - 1) / kThreads)); };
+
+    TIG_TRY(launch_fill_zero(dst, L.bytes, s));
+    TIG_TRY(launch_fill_zero(scratch, S.bytes, s));
+
+    // time encoding parameters as they are
+    hipLaunchKernelGGL(k_vec_f32, grid(T), blk, 0, s, L.time_w, T, T, (const double *)nullptr, w.time_w,
+                       (const float *)nullptr);
+    hipLaunchKernelGGL(k_vec_f32, grid(T), blk, 0, s, L.time_b, T, T, (const double *)nullptr, w.time_b,
+                       (const float *)nullptr);
+
+    // ---- GRU: gates r, z with the hidden weights folded onto the s_self columns ------------
+    const float *W_ir = w.W_i, *W_iz = w.W_i + (size_t)M * Dmsg, *W_in = w.W_i + (size_t)2 * M * Dmsg;
+    const float *W_hr = w.W_h, *W_hz = w.W_h + (size_t)M * M, *W_hn = w.W_h + (size_t)2 * M * M;
+    hipLaunchKernelGGL(k_add_cols, grid((size_t)M * Dmsg), blk, 0, s, S.Wr, Dmsg, W_ir, Dmsg, W_hr, M, M,
+                       Dmsg, M);
+    hipLaunchKernelGGL(k_add_cols, grid((size_t)M * Dmsg), blk, 0, s, S.Wz, Dmsg, W_iz, Dmsg, W_hz, M, M,
+                       Dmsg, M);
+    TIG_TRY(hipGetLastError());
+    TIG_TRY(pack<double>(s, d.prec, L.gru_Wr, S.Wr, Dmsg, M, Dmsg, d.Ng, d.Kg));
+    TIG_TRY(pack<double>(s, d.prec, L.gru_Wz, S.Wz, Dmsg, M, Dmsg, d.Ng, d.Kg));
+    TIG_TRY(pack<float>(s, d.prec, L.gru_Win, W_in, Dmsg, M, Dmsg, d.Ng, d.Kg));
+    TIG_TRY(pack<float>(s, d.prec, L.gru_Whn, W_hn, M, M, M, d.Ng, d.Khn));
+    hipLaunchKernelGGL(k_vec_f32, grid(d.Ng), blk, 0, s, L.gru_br, d.Ng, M, (const double *)nullptr,
+                       w.b_i, w.b_h);
+    hipLaunchKernelGGL(k_vec_f32, grid(d.Ng), blk, 0, s, L.gru_bz, d.Ng, M, (const double *)nullptr,
+                       w.b_i + M, w.b_h + M);
+    hipLaunchKernelGGL(k_vec_f32, grid(d.Ng), blk, 0, s, L.gru_bin, d.Ng, M, (const double *)nullptr,
+                       w.b_i + 2 * M, (const float *)nullptr);
+    hipLaunchKernelGGL(k_vec_f32, grid(d.Ng), blk, 0, s, L.gru_bhn, d.Ng, M, (const double *)nullptr,
+                       w.b_h + 2 * M, (const float *)nullptr);
+    TIG_TRY(hipGetLastError());
+
+    // ---- attention query fold ---------------------------------------------------------------
+    // cQ = W_Q[:, M:] Phi(0) + b_Q
+    hipLaunchKernelGGL(k_phi0, grid(T), blk, 0, s, S.phi0, w.time_b, T);
+    hipLaunchKernelGGL(k_copy_block, grid(da), blk, 0, s, S.cQ, 1, w.b_Q, 1, da, 1);
+    TIG_TRY(hipGetLastError());
+    TIG_TRY((gemm64<float, double>(s, S.cQ, 1, w.W_Q + M, da, 1, S.phi0, 1, 1, da, 1, T, 1.0, 1.0)));
+    const double scale = 1.0 / sqrt((double)dh);
+    for (int h = 0; h < H; ++h) {
+        const float *WK_h = w.W_K + (size_t)h * dh * dkv;   // [dh x dkv]
+        const float *WQm_h = w.W_Q + (size_t)h * dh * da;   // [dh x da], first M columns used
+        // A1_h[j][m] = scale * sum_r W_K[h*dh + r][j] * W_Q[h*dh + r][m]
+        TIG_TRY((gemm64<float, float>(s, S.A1 + (size_t)h * d.dkvp * M, M, WK_h, 1, dkv, WQm_h, da, 1,
+                                      dkv, M, dh, scale, 0.0)));
+        // a1_h[j] = scale * sum_r W_K[h*dh + r][j] * cQ[h*dh + r]
+        TIG_TRY((gemm64<float, double>(s, S.a1 + (size_t)h * d.dkvp, 1, WK_h, 1, dkv, S.cQ + h * dh, 1,
+                                       1, dkv, 1, dh, scale, 0.0)));
+    }
+    TIG_TRY(pack<double>(s, d.prec, L.emb_A1, S.A1, M, d.N1, M, d.N1, d.Mq));
+    hipLaunchKernelGGL(k_vec_f32, grid(d.N1), blk, 0, s, L.emb_a1, d.N1, d.N1, (const double *)S.a1,
+                       (const float *)nullptr, (const float *)nullptr);
+    TIG_TRY(hipGetLastError());
+
+    // ---- value / out-projection / merge layer-1 fold ---------------------------------------
+    // G = W_m1[:, :da] W_O   [E x da]
+    const int ld_m1 = da + M;
+    TIG_TRY((gemm64<float, float>(s, S.G, da, w.W_m1, ld_m1, 1, w.W_O, da, 1, E, da, da, 1.0, 0.0)));
+    const int ldPR = H * d.dkvp + M;
+    for (int h = 0; h < H; ++h) {
+        // P_h = G[:, h*dh:(h+1)*dh] W_V[h*dh:(h+1)*dh, :]   [E x dkv]
+        TIG_TRY((gemm64<double, float>(s, S.PR + (size_t)h * d.dkvp, ldPR, S.G + h * dh, da, 1,
+                                       w.W_V + (size_t)h * dh * dkv, dkv, 1, E, dkv, dh, 1.0, 0.0)));
+    }
+    hipLaunchKernelGGL(k_copy_block, grid((size_t)E * M), blk, 0, s, S.PR + (size_t)H * d.dkvp, ldPR,
+                       w.W_m1 + da, ld_m1, E, M);
+    TIG_TRY(hipGetLastError());
+    TIG_TRY(pack<double>(s, d.prec, L.emb_PR, S.PR, ldPR, E, ldPR, d.Ep, d.K2));
+    // c = b_m1 + W_m1a b_O + G b_V ;  c0 = b_m1
+    TIG_TRY((gemm64<float, float>(s, S.cvec, 1, w.W_m1, ld_m1, 1, w.b_O, 1, 1, E, 1, da, 1.0, 0.0)));
+    TIG_TRY((gemm64<double, float>(s, S.cvec, 1, S.G, da, 1, w.b_V, 1, 1, E, 1, da, 1.0, 1.0)));
+    hipLaunchKernelGGL(k_vec_f32, grid(d.Ep), blk, 0, s, L.emb_c, d.Ep, E, (const double *)S.cvec, w.b_m1,
+                       (const float *)nullptr);
+    hipLaunchKernelGGL(k_vec_f32, grid(d.Ep), blk, 0, s, L.emb_c0, d.Ep, E, (const double *)nullptr,
+                       w.b_m1, (const float *)nullptr);
+    TIG_TRY(hipGetLastError());
+
+    // ---- merge layer 2 and decoder -----------------------------------------------------------
+    TIG_TRY(pack<float>(s, d.prec, L.emb_Wm2, w.W_m2, E, E, E, d.Ep, d.Ek));
+    hipLaunchKernelGGL(k_vec_f32, grid(d.Ep), blk, 0, s, L.emb_bm2, d.Ep, E, (const double *)nullptr,
+                       w.b_m2, (const float *)nullptr);
+    // decoder layer 1 split by operand: rows 0..E-1 <- W_d1[:, :E], rows Ep..Ep+E-1 <- W_d1[:, E:]
+    hipLaunchKernelGGL(k_copy_block, grid((size_t)E * E), blk, 0, s, S.dec, E, w.W_d1, 2 * E, E, E);
+    hipLaunchKernelGGL(k_copy_block, grid((size_t)E * E), blk, 0, s, S.dec + (size_t)d.Ep * E, E,
+                       w.W_d1 + E, 2 * E, E, E);
+    TIG_TRY(hipGetLastError());
+    TIG_TRY(pack<double>(s, d.prec, L.dec_W, S.dec, E, 2 * d.Ep, E, 2 * d.Ep, d.Ek));
+    hipLaunchKernelGGL(k_vec_f32, grid(d.Ep), blk, 0, s, L.dec_b1, d.Ep, E, (const double *)nullptr,
+                       w.b_d1, (const float *)nullptr);
+    hipLaunchKernelGGL(k_vec_f32, grid(d.Ep), blk, 0, s, L.dec_w2, d.Ep, E, (const double *)nullptr,
+                       w.w_d2, (const float *)nullptr);
+    hipLaunchKernelGGL(k_vec_f32, grid(1), blk, 0, s, L.dec_b2, 1, 1, (const double *)nullptr, w.b_d2,
+                       (const float *)nullptr);
+    TIG_TRY(hipGetLastError());
+
+    pw->time_w = L.time_w;
+    pw->time_b = L.time_b;
+    pw->gru_Wr = L.gru_Wr;
+    pw->gru_Wz = L.gru_Wz;
+    pw->gru_Win = L.gru_Win;
+    pw->gru_Whn = L.gru_Whn;
+    pw->gru_br = L.gru_br;
+    pw->gru_bz = L.gru_bz;
+    pw->gru_bin = L.gru_bin;
+    pw->gru_bhn = L.gru_bhn;
+    pw->emb_A1 = L.emb_A1;
+    pw->emb_a1 = L.emb_a1;
+    pw->emb_PR = L.emb_PR;
+    pw->emb_c = L.emb_c;
+    pw->emb_c0 = L.emb_c0;
+    pw->emb_Wm2 = L.emb_Wm2;
+    pw->emb_bm2 = L.emb_bm2;
+    pw->dec_W = L.dec_W;
+    pw->dec_b1 = L.dec_b1;
+    pw->dec_w2 = L.dec_w2;
+    pw->dec_b2 = L.dec_b2;
+    return hipSuccess;
+}
+
+}  // namespace tig

@@ -1,0 +1,70 @@
+"""The C-ABI library loads and exports every symbol include/tig.h declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2308_14129_amd import tig
+    if not os.path.exists(tig.LIB_PATH):
+        from paper_2308_14129_amd import build
+        build.build()
+    return tig.load_library()
+
+
+def test_header_symbols_are_exported(lib):
+    from paper_2308_14129_amd import tig
+    header = open(os.path.join(ROOT, "include", "tig.h")).read()
+    declared = set(re.findall(r"TIG_API\s+[\w\s\*]+?\b(tig_\w+)\s*\(", header))
+    assert declared == set(tig.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_struct_sizes_match_header_layout():
+    from paper_2308_14129_amd import tig
+    assert ctypes.sizeof(tig.tig_config) == 36
+    assert ctypes.sizeof(tig.tig_graph) == 56
+    assert ctypes.sizeof(tig.tig_weights) == 8 + 22 * 8
+    assert ctypes.sizeof(tig.tig_batch) == 24
+    assert ctypes.sizeof(tig.tig_out) == 8 + 8 * 8
+
+
+def test_strerror_and_host_side_validation(lib):
+    from paper_2308_14129_amd import tig
+    assert lib.tig_strerror(0) == b"success"
+    assert b"sorted" in lib.tig_strerror(tig.TIG_EUNSORTED) or b"decreasing" in lib.tig_strerror(tig.TIG_EUNSORTED)
+    cfg = tig.make_config(32, 16, 16, 32, 10, 2, 200)
+    p, s = tig.workspace_bytes(cfg, 1000, 10000)
+    # persistent holds at least: events, features, adjacency, memory
+    assert p >= 10000 * (4 + 4 + 8 + 16 * 4) + 2 * 10000 * 16 + 1000 * 32 * 4
+    assert s > 0
+    for bad in (dict(num_heads=3), dict(num_neighbors=65), dict(mem_dim=0), dict(max_batch=0),
+                dict(mem_dim=33, time_dim=16, num_heads=2), dict(precision=7)):
+        kw = dict(mem_dim=32, time_dim=16, feat_dim=16, emb_dim=32, num_neighbors=10, num_heads=2,
+                  max_batch=200, precision="fp32")
+        kw.update(bad)
+        with pytest.raises(tig.TigError) as ei:
+            tig.workspace_bytes(tig.make_config(**kw), 1000, 10000)
+        assert ei.value.status == tig.TIG_EINVAL
+    with pytest.raises(tig.TigError):
+        tig.workspace_bytes(cfg, 0, 10)
+    # NULL context is rejected, not dereferenced
+    assert lib.tig_reset(None) == tig.TIG_EINVAL
+    assert lib.tig_step(None, None, None) == tig.TIG_EINVAL
+
+
+def test_workspace_sizes_of_the_five_workloads():
+    import tig_synth as S
+    from paper_2308_14129_amd import tig
+    for w in S.WORKLOADS.values():
+        for prec in ("fp32", "bf16"):
+            cfg = tig.make_config(w.mem_dim, w.time_dim, w.feat_dim, w.emb_dim, w.num_neighbors,
+                                  w.num_heads, w.batch_size, prec)
+            p, s = tig.workspace_bytes(cfg, w.num_nodes, w.num_events)
+            assert p < 40e9 and s < 40e9
