@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the TIG batch step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--precision fp32|bf16]
+
+A "step" is one tig_step call: the whole hot path (winner scatter, neighbour lookup, message +
+GRU, memory overwrite, attention embedding + decoder) over one chronological batch of the
+synthetic workload.  The graph, the warm state and every batch's negatives are resident in HBM
+before the timed region starts.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(w, count, roles, nbr_cnt_sum, winners):
+    """Bytes the method itself must move per step, by kernel (fp32 state, fp64 times, int32 ids).
+    Uses the actual number of filled neighbour slots and of distinct updated nodes."""
+    M, F, E, K = w.mem_dim, w.feat_dim, w.emb_dim, w.num_neighbors
+    Q = roles * count
+    entries = 2 * count
+    return {
+        # event (src, dst, ts) reads + one 8-byte key update per entry
+        "k_scatter_keys": entries * (4 + 8 + 8),
+        # per query: node id, time, two offsets, the K-entry window; writes of the K slots + count
+        "k_nbr_lookup": Q * (4 + 8 + 16 + 16 * K) + Q * (16 * K + 4),
+        # per entry key check; per winner two memory rows, last_update, edge feature; new row out
+        "k_gru": entries * (4 + 8 + 8) + winners * ((2 * M + F) * 4 + 8) + winners * M * 4,
+        # per winner: staged row in, memory row + last_update + key out
+        "k_commit": entries * (4 + 8 + 8) + winners * (2 * M * 4 + 16),
+        # per query: own memory row, neighbour table; per filled slot a memory row + an edge
+        # feature row; embedding and scores out
+        "k_embed": Q * (M * 4 + 4 + 4) + nbr_cnt_sum * ((M + F) * 4 + 16) + Q * E * 4 + (roles - 1) * count * 4,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c5_gpu_partition")
+    ap.add_argument("--precision", default=None, choices=[None, "fp32", "bf16"])
+    ap.add_argument("--window", type=float, default=0.5, help="start of the timed window, fraction of the stream")
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-steps", type=int, default=2)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import tig_synth as S
+    from paper_2308_14129_amd import tig
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    tig.load_library()  # fails loudly if libtig.so is missing
+
+    w = S.WORKLOADS[args.workload]
+    precision = args.precision or w.precision
+    B = args.batch or w.batch_size
+    K, W_ = args.steps, args.warmup
+    t0 = time.time()
+    log(f"generating {w.name}: {w.num_nodes} nodes, {w.num_events} events ...")
+    g = S.make_graph(w)
+    weights = S.make_weights(w)
+    log(f"generated in {time.time() - t0:.1f} s")
+
+    total_steps = W_ + K
+    first = int(w.num_events * args.window) // B * B
+    if first + total_steps * B > w.num_events:
+        first = max(0, (w.num_events - total_steps * B) // B * B)
+    batches = list(S.batches(w.num_events, B, first=first, stop=first + total_steps * B))
+    assert len(batches) == total_steps, "workload too short for the requested steps"
+
+    cfg = tig.make_config(w.mem_dim, w.time_dim, w.feat_dim, w.emb_dim, w.num_neighbors, w.num_heads, B,
+                          precision)
+    t0 = time.time()
+    ctx = tig.TigContext(cfg, g.num_nodes, g.src, g.dst, g.ts, g.edge_feat, weights, device="cuda:0")
+    torch.cuda.synchronize()
+    log(f"tig_init in {time.time() - t0:.1f} s (persistent {ctx.persistent_bytes / 1e9:.2f} GB, "
+        f"scratch {ctx.scratch_bytes / 1e9:.2f} GB)")
+
+    mem0, lu0 = S.make_warm_state(w, g, first)
+    negs = torch.from_numpy(np.stack([S.make_negatives(w, g, f, c) for f, c in batches])).to("cuda:0")
+    out = ctx.alloc_outputs(B, with_neg=True, inspect=False)
+    torch.cuda.synchronize()
+
+    def run(lo, hi):
+        for i in range(lo, hi):
+            ctx.step(batches[i][0], batches[i][1], negs[i], out)
+
+    # ---- throughput: W warm-up steps, then exactly K timed steps ---------------------------------
+    ctx.state_import(mem0, lu0)
+    run(0, W_)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_start = time.perf_counter()
+    ev0.record()
+    run(W_, total_steps)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_s = time.perf_counter() - t_start
+    gpu_ms = ev0.elapsed_time(ev1)
+    events = sum(c for _, c in batches[W_:])
+    ms_per_step = wall_s * 1e3 / K
+    value = events / wall_s
+
+    # ---- per-kernel durations (HIP events around every kernel, same stream, same batches) --------
+    ctx.state_import(mem0, lu0)
+    run(0, W_)
+    torch.cuda.synchronize()
+    insp = ctx.alloc_outputs(B, with_neg=True, inspect=True)
+    names = ctx.KERNEL_NAMES
+    sums = np.zeros(len(names))
+    byte_sums = {n: 0.0 for n in names}
+    n_prof = min(K, 50)
+    for i in range(W_, W_ + n_prof):
+        ms = ctx.step_profiled(batches[i][0], batches[i][1], negs[i], insp)
+        sums += np.array(ms)
+        cnt_sum = int(insp.nbr_cnt.sum().item())
+        winners = int(insp.is_winner.sum().item())
+        for n, v in algorithmic_bytes(w, batches[i][1], 3, cnt_sum, winners).items():
+            byte_sums[n] += v
+    avg_ms = sums / n_prof
+    dom = int(np.argmax(avg_ms))
+    dom_name = names[dom]
+    dom_bytes = byte_sums[dom_name] / n_prof
+    achieved = dom_bytes / (avg_ms[dom] * 1e-3) / 1e9
+    stages = {n: {"avg_us": round(float(avg_ms[i]) * 1e3, 2),
+                  "alg_bytes": int(byte_sums[n] / n_prof),
+                  "GBps": round(byte_sums[n] / n_prof / (float(avg_ms[i]) * 1e-3) / 1e9, 1)}
+              for i, n in enumerate(names)}
+    roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
+                "avg_kernel_us": round(float(avg_ms[dom]) * 1e3, 2), "alg_bytes_per_launch": int(dom_bytes),
+                "profiled_steps": n_prof}
+
+    # ---- CPU baseline: the oracle, as it stands, single thread, on a bounded sample ---------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from threadpoolctl import threadpool_limits
+        from oracle import tig_oracle as O
+        log("building the oracle's neighbour index ...")
+        ix = O.NeighbourIndex(g.num_nodes, g.src, g.dst, g.ts)
+        st = O.OracleState(mem0.copy(), lu0.copy())
+        n_cpu = max(1, min(args.cpu_steps, K))
+        with threadpool_limits(limits=1):
+            t0 = time.perf_counter()
+            for i in range(W_, W_ + n_cpu):
+                f, c = batches[i]
+                O.step(st, g.src, g.dst, g.ts, g.edge_feat, weights, f, c, negs[i].cpu().numpy(),
+                       w.num_neighbors, w.num_heads, index=ix)
+            cpu_s = time.perf_counter() - t0
+        cpu_events = sum(c for _, c in batches[W_:W_ + n_cpu])
+        cpu = {"value": round(cpu_events / cpu_s, 1), "unit": "events/s", "cores": 1, "kind": "oracle",
+               "sample": f"{n_cpu} steps of {B} events of the same window (float64 NumPy oracle, "
+                         f"indexed neighbour lookup, index build excluded), {cpu_s:.1f} s"}
+
+    info = ctx.launch_info()
+    line = {
+        "metric": "events/sec per TGN batch step (1 MI355X)",
+        "value": round(value, 1),
+        "unit": "events/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W_,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if precision == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "num_nodes": w.num_nodes, "num_events": w.num_events,
+                   "batch": B, "K": w.num_neighbors, "heads": w.num_heads, "mem_dim": w.mem_dim,
+                   "time_dim": w.time_dim, "feat_dim": w.feat_dim, "emb_dim": w.emb_dim,
+                   "precision": "bf16 hi/lo split MFMA operands, fp32 accumulate" if precision == "bf16"
+                   else "fp32 MFMA", "window_first_eid": first, "queries_per_event": 3},
+        "gpu_ms_per_step_events": round(gpu_ms / K, 5),
+        "kernels_per_step": info["kernels_per_step"],
+        "roofline": roofline,
+        "stages": stages,
+        "cpu_baseline": cpu,
+    }
+    ctx.close()
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -47,8 +47,11 @@ typedef enum tig_status {
 
 typedef enum tig_precision {
     TIG_FP32 = 0,      /* fp32 operands, fp32 accumulation on the matrix cores */
-    TIG_BF16_MFMA = 1  /* weight matrices and matrix-core operands rounded to bf16 (RNE), fp32
-                          accumulation; biases, gates, softmax, time encoding, state stay fp32 */
+    TIG_BF16_MFMA = 1  /* bf16 matrix cores, fp32 accumulation.  Weights and matrix-core
+                          activations are held as bf16 pairs x = hi + lo (hi = bf16(x) RNE,
+                          lo = bf16(x - hi)) and a product is hi*hi + lo*hi + hi*lo: three bf16
+                          MFMAs instead of eight fp32 ones per 32-deep block.  Biases, gates,
+                          softmax, time encoding and the stored state stay fp32 */
 } tig_precision;
 
 /* Model / launch shape.  Notation: M memory width, T time-encoding width, F edge-feature
@@ -163,6 +166,17 @@ TIG_API int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_we
  */
 TIG_API int tig_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *out);
 
+/*
+ * The same step with a HIP event recorded on the context's stream before the first and after
+ * every kernel; waits for the step to finish and writes the five kernel durations in
+ * milliseconds to kernel_ms[0..4] (host), in launch order: last-message key scatter, neighbour
+ * lookup, message + GRU, memory overwrite, attention embedding + decoder.  For measurement:
+ * the event records add gaps between kernels, so time throughput with tig_step.
+ */
+#define TIG_NUM_STEP_KERNELS 5
+TIG_API int tig_step_profiled(tig_ctx *ctx, const tig_batch *batch, const tig_out *out,
+                              float *kernel_ms);
+
 /* Memory reset at the start of a data cycle (Alg. 2): memory <- 0, last_update <- 0. Async. */
 TIG_API int tig_reset(tig_ctx *ctx);
 
@@ -177,7 +191,8 @@ TIG_API int tig_state_import(tig_ctx *ctx, const float *mem_in, const double *la
 /* Frees the host-side context.  Device buffers belong to the caller and are not touched. */
 TIG_API void tig_destroy(tig_ctx *ctx);
 
-/* Static text for a status code / detail of the last failure on this context ("" if none). */
+/* Static text for a status code / detail of the last failure on this context ("" if none);
+ * tig_last_error(NULL) gives the detail of the last failed tig_init on the calling thread. */
 TIG_API const char *tig_strerror(int status);
 TIG_API const char *tig_last_error(const tig_ctx *ctx);
 

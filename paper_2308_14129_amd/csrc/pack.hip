@@ -119,7 +119,9 @@ __device__ inline uint16_t f32_to_bf16_rne(float f)
 
 // Lane-ordered layout read by the tile GEMMs: for output tile nt (16 rows of W), k-block kb,
 // lane l: VL consecutive k's  W[nt*16 + l%16][kb*KB + VL*(l/16) + 0..VL-1], VL = KB/4.
-// One wavefront operand load = 64 lanes x 16 bytes, contiguous.
+// fp32: 4 floats per lane.  bf16: 8 values per lane, split as x = hi + lo with hi = bf16(x),
+// lo = bf16(x - hi): 8 hi values (16 bytes) followed by the 8 lo values (16 bytes).
+// Either way an element takes 4 bytes and one wavefront operand load is contiguous.
 template <typename TS, bool BF16>
 __global__ void k_pack(void *out, const TS *W, int ld, int rows, int cols, int rows_p, int cols_p)
 {
@@ -140,10 +142,14 @@ __global__ void k_pack(void *out, const TS *W, int ld, int rows, int cols, int r
     float v = 0.0f;
     if (r < rows && c < cols)
         v = (float)W[(size_t)r * ld + c];
-    if (BF16)
-        ((uint16_t *)out)[idx] = f32_to_bf16_rne(v);
-    else
+    if (BF16) {
+        uint16_t *o = (uint16_t *)out + (blk * 64 + lane) * 16 + s;
+        const uint16_t hi = f32_to_bf16_rne(v);
+        o[0] = hi;
+        o[8] = f32_to_bf16_rne(v - __uint_as_float((uint32_t)hi << 16));
+    } else {
         ((float *)out)[idx] = v;
+    }
 }
 
 template <typename TS>

@@ -7,8 +7,8 @@
 //   k_embed         attention over neighbours (folded projections), merge MLP, link decoder
 //
 // Tile GEMM convention (16x16 output tiles on the matrix cores, wave64):
-//   operand A: activations in LDS, row-major; lane l supplies row l%16, VL consecutive k's at
-//              k0 + VL*(l/16);
+//   operand A: activations in LDS, row-major; lane l supplies row l%16 and KB/4 consecutive k's
+//              starting at k0 + (KB/4)*(l/16);
 //   operand B: prepared weights, already lane-ordered in global memory (pack.hip);
 //   result   : lane l holds rows 4*(l/16)+v (v = 0..3) of column l%16.
 #include <hip/hip_runtime.h>
@@ -29,34 +29,70 @@ constexpr int kMaxHeads = 4;
 
 template <int PREC>
 struct Prec;
+
+// fp32 operands: one k-block = 16 k's = four 16x16x4 MFMAs fed by one 16-byte load per lane.
 template <>
 struct Prec<TIG_FP32> {
-    using elem = float;
-    using frag = floatx4;
-    static constexpr int KB = 16, VL = 4;
-    static __device__ inline elem from_float(float v) { return v; }
+    struct frag {
+        floatx4 v;
+    };
+    static constexpr int KB = 16;
+    // activation element k of an LDS row
+    static __device__ inline void store_a(char *row, int k, float v) { ((float *)row)[k] = v; }
+    // lane's operand of k-block kb: 4 consecutive k's starting at kb*16 + 4*g, g = lane/16
+    static __device__ inline frag load_a(const char *row, int kb, int g)
+    {
+        return frag{*(const floatx4 *)(row + (size_t)(kb * 16 + 4 * g) * 4)};
+    }
+    static __device__ inline frag load_w(const void *W, size_t idx) { return frag{((const floatx4 *)W)[idx]}; }
     static __device__ inline void mma(floatx4 &acc, const frag &a, const frag &b)
     {
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], b[0], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], b[1], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], b[2], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], b[3], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.v[0], b.v[0], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.v[1], b.v[1], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.v[2], b.v[2], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.v[3], b.v[3], acc, 0, 0, 0);
     }
 };
+
+// bf16 matrix cores with split operands: x = hi + lo, hi = bf16(x), lo = bf16(x - hi), for
+// activations and weights alike; a*w ~ a_hi*w_hi + a_lo*w_hi + a_hi*w_lo (the dropped lo*lo term
+// is ~2^-18 relative), accumulated in fp32.  One k-block = 32 k's = three 16x16x32 MFMAs.
+// Storage: groups of 8 k's, 8 hi values (16 bytes) followed by their 8 lo values (16 bytes), so
+// an element still takes 4 bytes and a lane's operand is one contiguous 32-byte read.
 template <>
 struct Prec<TIG_BF16_MFMA> {
-    using elem = uint16_t;
-    using frag = bf16x8;
-    static constexpr int KB = 32, VL = 8;
-    static __device__ inline elem from_float(float v)
+    struct frag {
+        bf16x8 hi, lo;
+    };
+    static constexpr int KB = 32;
+    static __device__ inline uint16_t bf16_rne(float v)
     {
         uint32_t u = __float_as_uint(v);
-        u += 0x7FFFu + ((u >> 16) & 1u);  // round to nearest even
+        u += 0x7FFFu + ((u >> 16) & 1u);
         return (uint16_t)(u >> 16);
+    }
+    static __device__ inline void store_a(char *row, int k, float v)
+    {
+        uint16_t *p = (uint16_t *)row + ((k >> 3) << 4) + (k & 7);
+        const uint16_t hi = bf16_rne(v);
+        p[0] = hi;
+        p[8] = bf16_rne(v - __uint_as_float((uint32_t)hi << 16));
+    }
+    static __device__ inline frag load_a(const char *row, int kb, int g)
+    {
+        const char *p = row + (size_t)(kb * 4 + g) * 32;
+        return frag{*(const bf16x8 *)p, *(const bf16x8 *)(p + 16)};
+    }
+    static __device__ inline frag load_w(const void *W, size_t idx)
+    {
+        const char *p = (const char *)W + idx * 32;
+        return frag{*(const bf16x8 *)p, *(const bf16x8 *)(p + 16)};
     }
     static __device__ inline void mma(floatx4 &acc, const frag &a, const frag &b)
     {
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.lo, b.hi, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.hi, b.lo, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.hi, b.hi, acc, 0, 0, 0);
     }
 };
 
@@ -194,40 +230,39 @@ __global__ void __launch_bounds__(256) k_nbr_lookup(StepArgs a, int K)
 }
 
 // ------------------------------------------------------------------------------------------
-// acc[mt] += A[16*mt .. 16*mt+15][kb0*KB ..) x W[nt]^T over `kblocks` k-blocks.
-// A: LDS, `lda` elements per row.  W: lane-ordered blocks, `w_kblocks` per output tile,
-// starting at k-block `w_kb0`.
+// acc[mt] += A[16*mt .. 16*mt+15][0 .. kblocks*KB) x W[nt]^T.
+// A: LDS rows of `lda` BYTES (4 bytes per element in either precision).  W: lane-ordered blocks,
+// `w_kblocks` per output tile, starting at k-block `w_kb0`.
 template <int PREC, int MT>
-__device__ inline void tile_gemm(floatx4 (&acc)[MT], const typename Prec<PREC>::elem *A, int lda,
-                                 const void *W, int w_kblocks, int w_kb0, int kblocks, int nt,
-                                 int m_tiles)
+__device__ inline void tile_gemm(floatx4 (&acc)[MT], const char *A, int lda, const void *W,
+                                 int w_kblocks, int w_kb0, int kblocks, int nt, int m_tiles)
 {
     using P = Prec<PREC>;
     using frag = typename P::frag;
     const int lane = lane_id();
-    const frag *wp = (const frag *)W + ((size_t)nt * w_kblocks + w_kb0) * kWave + lane;
-    const typename P::elem *ap = A + (lane & 15) * lda + P::VL * (lane >> 4);
+    const size_t w0 = ((size_t)nt * w_kblocks + w_kb0) * kWave + lane;
+    const char *ap = A + (size_t)(lane & 15) * lda;
+    const int g = lane >> 4;
     for (int kb = 0; kb < kblocks; ++kb) {
-        const frag bfrag = wp[(size_t)kb * kWave];
+        const frag bfrag = P::load_w(W, w0 + (size_t)kb * kWave);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             if (mt < m_tiles) {
-                const frag afrag = *(const frag *)(ap + mt * 16 * lda + kb * P::KB);
+                const frag afrag = P::load_a(ap + (size_t)mt * 16 * lda, kb, g);
                 P::mma(acc[mt], afrag, bfrag);
             }
         }
     }
 }
 
-// Row stride (in elements) >= width whose 16-byte chunk count is odd: the 16 rows read by one
+// Row stride in bytes >= 4*width whose 16-byte chunk count is odd: the 16 rows read by one
 // operand load then fall into distinct LDS bank groups.
-__host__ __device__ inline int lds_stride(int width_elems, int elem_bytes)
+__host__ __device__ inline int lds_row_bytes(int width_elems)
 {
-    const int per16 = 16 / elem_bytes;
-    int chunks = (width_elems + per16 - 1) / per16;
+    int chunks = (width_elems * 4 + 15) / 16;
     if ((chunks & 1) == 0)
         ++chunks;
-    return chunks * per16;
+    return chunks * 16;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -235,7 +270,7 @@ __host__ __device__ inline int lds_stride(int width_elems, int elem_bytes)
 struct GruParams {
     int M, T, F, Dmsg;
     int Kg, Khn, Ng;
-    int ldx;  // LDS row stride of the message tile, elements
+    int ldx;  // LDS row stride of the message tile, bytes
 };
 
 template <int PREC, int MT>
@@ -243,12 +278,11 @@ __global__ void __launch_bounds__(kTileThreads)
 k_gru(StepArgs a, PackedWeights w, GruParams g)
 {
     using P = Prec<PREC>;
-    using elem = typename P::elem;
     constexpr int EC = 16 * MT;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int *row_entry = (int *)smem;            // [EC]
     int *n_rows_p = row_entry + EC;          // [1]
-    elem *X = (elem *)(smem + 512);          // [EC x ldx]
+    char *X = smem + 512;                    // [EC rows x ldx bytes]
 
     const int lane = lane_id();
     const int wave = wave_id();
@@ -280,7 +314,7 @@ k_gru(StepArgs a, PackedWeights w, GruParams g)
 
     // 2. message rows [s_self | s_other | Phi(t - last_update[self]) | e] from batch-start memory
     for (int r = wave; r < m_tiles * 16; r += kTileWaves) {
-        elem *xr = X + (size_t)r * g.ldx;
+        char *xr = X + (size_t)r * g.ldx;
         if (r < n_rows) {
             const int i = row_entry[r];
             const int64_t eid = a.first_eid + (i >> 1);
@@ -301,11 +335,11 @@ k_gru(StepArgs a, PackedWeights w, GruParams g)
                     v = time_enc(w.time_w[j - 2 * g.M], w.time_b[j - 2 * g.M], dt);
                 else if (j < g.Dmsg)
                     v = ef[j - 2 * g.M - g.T];
-                xr[j] = P::from_float(v);
+                P::store_a(xr, j, v);
             }
         } else {
             for (int j = lane; j < g.Kg; j += kWave)
-                xr[j] = P::from_float(0.0f);
+                P::store_a(xr, j, 0.0f);
         }
     }
     __syncthreads();
@@ -381,7 +415,7 @@ struct EmbedParams {
     int TE;         // events per workgroup; rows = roles * TE <= 16 * MT
     int row_bytes;  // LDS bytes per query row of the main buffer
     int mem_off;    // byte offset of the s_u operand inside a row
-    int ld1;        // element stride of the E-wide buffers
+    int ld1;        // row stride of the E-wide buffers, bytes
     int off_h1, off_meta;  // byte offsets in LDS
     int dec_off;    // byte offset of the decoder pre-activations (inside the main buffer)
 };
@@ -391,12 +425,11 @@ __global__ void __launch_bounds__(kTileThreads)
 k_embed(StepArgs a, PackedWeights w, EmbedParams p)
 {
     using P = Prec<PREC>;
-    using elem = typename P::elem;
     constexpr int ROWS = 16 * MT;
     constexpr int KC = (64 / NPL) < 16 ? (64 / NPL) : 16;  // neighbour rows in flight per chunk
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char *rowbuf = smem;
-    elem *h1buf = (elem *)(smem + p.off_h1);
+    char *h1buf = smem + p.off_h1;
     int *row_q = (int *)(smem + p.off_meta);  // [ROWS] query index or -1
     int *row_cnt = row_q + ROWS;              // [ROWS]
     int *row_node = row_cnt + ROWS;           // [ROWS]
@@ -404,7 +437,6 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     const int lane = lane_id();
     const int wave = wave_id();
     const int ev0 = blockIdx.x * p.TE;
-    const int lda_row = p.row_bytes / (int)sizeof(elem);  // main-buffer row stride in elements
 
     // ---- A. query rows: node, query index, s_u (post-update memory) -------------------------
     for (int r = wave; r < ROWS; r += kTileWaves) {
@@ -419,12 +451,12 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
             q = role * a.count + b;
         }
         const bool has_row = u >= 0 && (int64_t)u < a.num_nodes;
-        elem *mrow = (elem *)(rowbuf + (size_t)r * p.row_bytes + p.mem_off);
+        char *mrow = rowbuf + (size_t)r * p.row_bytes + p.mem_off;
         for (int j = lane; j < p.Mq; j += kWave) {
             float v = 0.0f;
             if (has_row && j < p.M)
                 v = a.mem[(size_t)u * p.M + j];
-            mrow[j] = P::from_float(v);
+            P::store_a(mrow, j, v);
         }
         if (lane == 0) {
             row_q[r] = q;
@@ -440,7 +472,7 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
             acc[mt] = floatx4{0, 0, 0, 0};
-        tile_gemm<PREC, MT>(acc, (const elem *)(rowbuf + p.mem_off), lda_row, w.emb_A1, p.Mq / P::KB, 0,
+        tile_gemm<PREC, MT>(acc, rowbuf + p.mem_off, p.row_bytes, w.emb_A1, p.Mq / P::KB, 0,
                             p.Mq / P::KB, nt, MT);
         const int col = nt * 16 + (lane & 15);
         const float bias = w.emb_a1[col];
@@ -471,7 +503,7 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                 continue;
             const int cnt = row_cnt[r];
             float *qrow = (float *)(rowbuf + (size_t)r * p.row_bytes);
-            elem *arow = (elem *)(rowbuf + (size_t)r * p.row_bytes);
+            char *arow = rowbuf + (size_t)r * p.row_bytes;
             float qv[kMaxHeads][NPL], accv[kMaxHeads][NPL];
             float mx[kMaxHeads], den[kMaxHeads];
 #pragma unroll
@@ -561,7 +593,7 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                     for (int n = 0; n < NPL; ++n) {
                         const int j = lane + kWave * n;
                         if (j < p.dkvp)
-                            arow[h * p.dkvp + j] = P::from_float(accv[h][n] * inv);
+                            P::store_a(arow, h * p.dkvp + j, accv[h][n] * inv);
                     }
                 }
             }
@@ -576,8 +608,8 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
         for (int mt = 0; mt < MT; ++mt)
             acc[mt] = floatx4{0, 0, 0, 0};
         const int kb1 = p.N1 / P::KB, kb2 = p.Mq / P::KB;
-        tile_gemm<PREC, MT>(acc, (const elem *)rowbuf, lda_row, w.emb_PR, kb1 + kb2, 0, kb1, nt, MT);
-        tile_gemm<PREC, MT>(acc, (const elem *)(rowbuf + p.mem_off), lda_row, w.emb_PR, kb1 + kb2, kb1, kb2,
+        tile_gemm<PREC, MT>(acc, rowbuf, p.row_bytes, w.emb_PR, kb1 + kb2, 0, kb1, nt, MT);
+        tile_gemm<PREC, MT>(acc, rowbuf + p.mem_off, p.row_bytes, w.emb_PR, kb1 + kb2, kb1, kb2,
                             nt, MT);
         const int col = nt * 16 + (lane & 15);
         const float c = w.emb_c[col], c0 = w.emb_c0[col];
@@ -587,18 +619,18 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
             for (int v = 0; v < 4; ++v) {
                 const int row = mt * 16 + 4 * (lane >> 4) + v;
                 const float x = acc[mt][v] + (row_cnt[row] > 0 ? c : c0);
-                h1buf[(size_t)row * p.ld1 + col] = P::from_float(fmaxf(x, 0.0f));
+                P::store_a(h1buf + (size_t)row * p.ld1, col, fmaxf(x, 0.0f));
             }
     }
     // k-depth padding of the E-wide buffers (columns Ep..Ek-1)
     for (int idx = threadIdx.x; idx < ROWS * (p.Ek - p.Ep); idx += kTileThreads) {
         const int row = idx / (p.Ek - p.Ep), col = p.Ep + idx % (p.Ek - p.Ep);
-        h1buf[(size_t)row * p.ld1 + col] = P::from_float(0.0f);
+        P::store_a(h1buf + (size_t)row * p.ld1, col, 0.0f);
     }
     __syncthreads();
 
     // ---- E. merge layer 2: emb = W_m2 h1 + b_m2 -> global, and kept as the decoder operand ---
-    elem *embbuf = (elem *)rowbuf;  // [ROWS x ld1], the main buffer is free again
+    char *embbuf = rowbuf;  // [ROWS rows x ld1 bytes], the main buffer is free again
     for (int nt = wave; nt < p.Ep / 16; nt += kTileWaves) {
         floatx4 acc[MT];
 #pragma unroll
@@ -616,12 +648,12 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                 const int q = row_q[row];
                 if (q >= 0 && col < p.E)
                     a.emb[(size_t)q * p.E + col] = x;
-                embbuf[(size_t)row * p.ld1 + col] = P::from_float(x);
+                P::store_a(embbuf + (size_t)row * p.ld1, col, x);
             }
     }
     for (int idx = threadIdx.x; idx < ROWS * (p.Ek - p.Ep); idx += kTileThreads) {
         const int row = idx / (p.Ek - p.Ep), col = p.Ep + idx % (p.Ek - p.Ep);
-        embbuf[(size_t)row * p.ld1 + col] = P::from_float(0.0f);
+        P::store_a(embbuf + (size_t)row * p.ld1, col, 0.0f);
     }
     __syncthreads();
 
@@ -683,11 +715,11 @@ GruParams gru_params(const Dims &d)
     g.Kg = d.Kg;
     g.Khn = d.Khn;
     g.Ng = d.Ng;
-    g.ldx = lds_stride(d.Kg, d.esz);
+    g.ldx = lds_row_bytes(d.Kg);
     return g;
 }
 
-int gru_lds_bytes(const Dims &d, int mt) { return 512 + 16 * mt * lds_stride(d.Kg, d.esz) * d.esz; }
+int gru_lds_bytes(const Dims &d, int mt) { return 512 + 16 * mt * lds_row_bytes(d.Kg); }
 
 EmbedParams embed_params(const Dims &d, int mt, int roles)
 {
@@ -709,13 +741,9 @@ EmbedParams embed_params(const Dims &d, int mt, int roles)
     p.TE = rows / roles;
     // main buffer row: q~ (fp32, N1) / kvbar (operand elements, N1) first, then s_u (Mq elements)
     p.mem_off = 4 * d.N1;
-    int rb = p.mem_off + d.esz * d.Mq;
-    int chunks = (rb + 15) / 16;
-    if ((chunks & 1) == 0)
-        ++chunks;
-    p.row_bytes = chunks * 16;
-    p.ld1 = lds_stride(d.Ek, d.esz);
-    const int emb_bytes = rows * p.ld1 * d.esz;
+    p.row_bytes = lds_row_bytes(d.N1 + d.Mq);
+    p.ld1 = lds_row_bytes(d.Ek);
+    const int emb_bytes = rows * p.ld1;
     p.dec_off = (emb_bytes + 15) / 16 * 16;
     int main_bytes = rows * p.row_bytes;
     const int tail_bytes = p.dec_off + rows * 2 * d.Ep * 4;
@@ -723,7 +751,7 @@ EmbedParams embed_params(const Dims &d, int mt, int roles)
         main_bytes = tail_bytes;
     main_bytes = (main_bytes + 15) / 16 * 16;
     p.off_h1 = main_bytes;
-    p.off_meta = p.off_h1 + (rows * p.ld1 * d.esz + 15) / 16 * 16;
+    p.off_meta = p.off_h1 + rows * p.ld1;
     return p;
 }
 
@@ -840,17 +868,21 @@ hipError_t launch_fill_zero(void *ptr, size_t bytes, hipStream_t s)
 }
 
 hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw,
-                       const StepArgs &a, hipStream_t s)
+                       const StepArgs &a, hipStream_t s, hipEvent_t *marks)
 {
     const int entries = 2 * a.count;
     const int Q = a.roles * a.count;
     hipError_t e;
+    int mark = 0;
+    auto stamp = [&]() -> hipError_t { return marks ? hipEventRecord(marks[mark++], s) : hipSuccess; };
 
+    if ((e = stamp()) != hipSuccess)
+        return e;
     hipLaunchKernelGGL(k_scatter_keys, dim3((entries + 255) / 256), dim3(256), 0, s, a);
-    if ((e = hipGetLastError()) != hipSuccess)
+    if ((e = hipGetLastError()) != hipSuccess || (e = stamp()) != hipSuccess)
         return e;
     hipLaunchKernelGGL(k_nbr_lookup, dim3((Q + 3) / 4), dim3(256), 0, s, a, d.K);
-    if ((e = hipGetLastError()) != hipSuccess)
+    if ((e = hipGetLastError()) != hipSuccess || (e = stamp()) != hipSuccess)
         return e;
     {
         StepArgs aa = a;
@@ -860,11 +892,11 @@ hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeight
         const int grid = (entries + plan.gru_entries - 1) / plan.gru_entries;
         e = hipLaunchKernel(gru_kernel(d, plan.gru_mt), dim3(grid), dim3(kTileThreads), args,
                             (size_t)plan.gru_lds, s);
-        if (e != hipSuccess)
+        if (e != hipSuccess || (e = stamp()) != hipSuccess)
             return e;
     }
     hipLaunchKernelGGL(k_commit, dim3((entries + 3) / 4), dim3(256), 0, s, a, d.M);
-    if ((e = hipGetLastError()) != hipSuccess)
+    if ((e = hipGetLastError()) != hipSuccess || (e = stamp()) != hipSuccess)
         return e;
     {
         StepArgs aa = a;
@@ -874,7 +906,7 @@ hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeight
         const int grid = (a.count + p.TE - 1) / p.TE;
         e = hipLaunchKernel(embed_kernel(d, plan.emb_mt), dim3(grid), dim3(kTileThreads), args,
                             (size_t)plan.emb_lds, s);
-        if (e != hipSuccess)
+        if (e != hipSuccess || (e = stamp()) != hipSuccess)
             return e;
     }
     return hipSuccess;

@@ -29,6 +29,8 @@ struct tig_ctx {
     int32_t *nbr_node, *nbr_eid, *nbr_cnt;
     double *nbr_ts;
     float *staging;
+    hipEvent_t marks[kNumStepKernels + 1];
+    bool have_marks;
     char err[256];
 };
 
@@ -83,7 +85,7 @@ Dims make_dims(const tig_config &c)
     d.dkv = d.M + d.F + d.T;
     d.prec = c.precision;
     d.KB = d.prec == TIG_BF16_MFMA ? 32 : 16;
-    d.esz = d.prec == TIG_BF16_MFMA ? 2 : 4;
+    d.esz = 4;  // fp32, or a bf16 (hi, lo) pair
     d.Kg = round_up(d.Dmsg, d.KB);
     d.Khn = round_up(d.M, d.KB);
     d.Ng = round_up(d.M, 16);
@@ -368,7 +370,7 @@ int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *w
     return TIG_OK;
 }
 
-int tig_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *out)
+static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, hipEvent_t *marks)
 {
     if (!ctx)
         return TIG_EINVAL;
@@ -405,9 +407,42 @@ int tig_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *out)
     a.emb = out->emb;
     a.score_pos = out->score_pos;
     a.score_neg = out->score_neg;
-    const hipError_t e = launch_step(ctx->d, ctx->plan, ctx->pw, a, ctx->stream);
+    const hipError_t e = launch_step(ctx->d, ctx->plan, ctx->pw, a, ctx->stream, marks);
     if (e != hipSuccess)
         return fail(ctx, TIG_EHIP, "tig_step launch", e);
+    return TIG_OK;
+}
+
+int tig_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *out)
+{
+    return step_impl(ctx, batch, out, nullptr);
+}
+
+int tig_step_profiled(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, float *kernel_ms)
+{
+    if (!ctx)
+        return TIG_EINVAL;
+    if (!kernel_ms)
+        return fail(ctx, TIG_EINVAL, "tig_step_profiled: kernel_ms is NULL");
+    if (!ctx->have_marks) {
+        for (int i = 0; i <= kNumStepKernels; ++i) {
+            const hipError_t e = hipEventCreate(&ctx->marks[i]);
+            if (e != hipSuccess) {
+                for (int j = 0; j < i; ++j)
+                    (void)hipEventDestroy(ctx->marks[j]);
+                return fail(ctx, TIG_EHIP, "hipEventCreate", e);
+            }
+        }
+        ctx->have_marks = true;
+    }
+    const int rc = step_impl(ctx, batch, out, ctx->marks);
+    if (rc != TIG_OK)
+        return rc;
+    hipError_t e = hipEventSynchronize(ctx->marks[kNumStepKernels]);
+    for (int i = 0; i < kNumStepKernels && e == hipSuccess; ++i)
+        e = hipEventElapsedTime(&kernel_ms[i], ctx->marks[i], ctx->marks[i + 1]);
+    if (e != hipSuccess)
+        return fail(ctx, TIG_EHIP, "tig_step_profiled timing", e);
     return TIG_OK;
 }
 
@@ -459,7 +494,15 @@ int tig_state_import(tig_ctx *ctx, const float *mem_in, const double *last_updat
     return TIG_OK;
 }
 
-void tig_destroy(tig_ctx *ctx) { delete ctx; }
+void tig_destroy(tig_ctx *ctx)
+{
+    if (!ctx)
+        return;
+    if (ctx->have_marks)
+        for (int i = 0; i <= kNumStepKernels; ++i)
+            (void)hipEventDestroy(ctx->marks[i]);
+    delete ctx;
+}
 
 const char *tig_strerror(int status)
 {
@@ -484,7 +527,7 @@ int tig_launch_info(const tig_ctx *ctx, int32_t *kernels_per_step, int32_t *gru_
     if (!ctx)
         return TIG_EINVAL;
     if (kernels_per_step)
-        *kernels_per_step = 5;
+        *kernels_per_step = kNumStepKernels;
     if (gru_lds_bytes)
         *gru_lds_bytes = ctx->plan.gru_lds;
     if (embed_lds_bytes)

@@ -20,13 +20,13 @@ struct __attribute__((aligned(16))) CsrEntry {
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 // Derived dimensions.  KB = depth of one matrix-core k-block (16 for fp32: four 16x16x4 MFMAs
-// fed by one 16-byte operand load per lane; 32 for bf16: one 16x16x32 MFMA).
+// fed by one 16-byte operand load per lane; 32 for bf16: 16x16x32 MFMAs on hi/lo split operands).
 struct Dims {
     int M, T, F, E, K, H;
     int Dmsg, da, dh, dkv;
     int prec;     // tig_precision
     int KB;       // 16 | 32
-    int esz;      // bytes per matrix-core operand element: 4 | 2
+    int esz;      // bytes per stored matrix-core operand element: 4 (fp32, or a bf16 hi/lo pair)
     // GRU tile GEMM: A row = [s_self | s_other | Phi | e] padded to Kg; per gate Ng output cols
     int Kg, Khn, Ng;
     // embedding tile GEMMs
@@ -107,8 +107,10 @@ hipError_t pack_weights(const Dims &d, const tig_weights &w_dev_f32, void *dst, 
 
 bool plan_launch(const Dims &d, int lds_limit, LaunchPlan *plan);
 hipError_t prepare_kernels(const Dims &d, const LaunchPlan &plan);
+constexpr int kNumStepKernels = 5;
+// `marks`: NULL, or kNumStepKernels + 1 events recorded before the first and after every kernel.
 hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw,
-                       const StepArgs &a, hipStream_t s);
+                       const StepArgs &a, hipStream_t s, hipEvent_t *marks);
 hipError_t launch_fill_zero(void *ptr, size_t bytes, hipStream_t s);
 
 }  // namespace tig

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 TOL = {"fp32": 1e-4, "bf16": 2e-2}
 
 
-def _ctx(w, g, W, precision, max_batch=None):
+def make_ctx(w, g, W, precision, max_batch=None):
     import torch
     from paper_2308_14129_amd import tig
     assert torch.cuda.is_available()
@@ -24,16 +24,30 @@ def _ctx(w, g, W, precision, max_batch=None):
     return tig.TigContext(cfg, g.num_nodes, g.src, g.dst, g.ts, g.edge_feat, W, device="cuda:0")
 
 
-def _run(w, precision, batches, locked, state0=None, with_neg=True, g=None, W=None, ix=None):
+class Bundle:
+    """Graph + weights + oracle index of one workload, built once per module."""
+
+    def __init__(self, w):
+        self.w = w
+        self.g = S.make_graph(w)
+        self.W = S.make_weights(w)
+        self.ix = O.NeighbourIndex(self.g.num_nodes, self.g.src, self.g.dst, self.g.ts)
+
+
+def run(bundle, precision, batches, locked, warm_at=None, with_neg=True, ctx=None):
     """Runs the batches on both sides.  locked=True loads the oracle's state into the GPU before
-    every step (step-locked parity); otherwise both sides run freely from the same start."""
+    every step (step-locked parity); otherwise both sides run freely from the same start, which
+    is the state after a reset or, with warm_at, the seeded warm state of a mid-stream window."""
     import torch
-    g = g if g is not None else S.make_graph(w)
-    W = W if W is not None else S.make_weights(w)
-    ix = ix if ix is not None else O.NeighbourIndex(g.num_nodes, g.src, g.dst, g.ts)
-    ctx = _ctx(w, g, W, precision, max(c for _, c in batches))
-    st = O.OracleState.zeros(g.num_nodes, w.mem_dim) if state0 is None else state0
-    if state0 is not None:
+    w, g, W, ix = bundle.w, bundle.g, bundle.W, bundle.ix
+    own = ctx is None
+    if own:
+        ctx = make_ctx(w, g, W, precision, max(c for _, c in batches))
+    if warm_at is None:
+        st = O.OracleState.zeros(g.num_nodes, w.mem_dim)
+        ctx.reset()
+    else:
+        st = O.OracleState(*S.make_warm_state(w, g, warm_at))
         ctx.state_import(st.mem, st.last_update)
     worst = {}
     for first, count in batches:
@@ -50,21 +64,101 @@ def _run(w, precision, batches, locked, state0=None, with_neg=True, g=None, W=No
         for k, v in res.items():
             worst[k] = max(worst.get(k, 0.0), v)
     print(f"[{w.name} {precision}] worst gate ratios: {worst}", flush=True)
-    ctx.close()
+    if own:
+        ctx.close()
     return worst
 
 
-def test_c1_tiny_whole_stream_free_running_fp32():
-    w = S.WORKLOADS["c1_tiny"]
-    _run(w, "fp32", list(S.batches(w.num_events, w.batch_size)), locked=False)
+def window(w, frac, steps, batch=None):
+    B = batch or w.batch_size
+    first = int(w.num_events * frac) // B * B
+    return first, list(S.batches(w.num_events, B, first=first, stop=first + steps * B))
 
 
-def test_c1_tiny_step_locked_fp32_and_ragged_tail():
-    w = S.WORKLOADS["c1_tiny"]
-    # batch 136 leaves ragged tiles in both tile kernels and a short last batch
-    _run(w, "fp32", list(S.batches(w.num_events, 136))[:12] + [(9990, 10)], locked=True)
+# ------------------------------------------------------------------------------------- C1
 
 
-def test_c1_tiny_without_negatives():
-    w = S.WORKLOADS["c1_tiny"]
-    _run(w, "fp32", list(S.batches(w.num_events, 200))[:4], locked=False, with_neg=False)
+@pytest.fixture(scope="module")
+def c1():
+    return Bundle(S.WORKLOADS["c1_tiny"])
+
+
+def test_c1_whole_stream_free_running_fp32(c1):
+    run(c1, "fp32", list(S.batches(c1.w.num_events, c1.w.batch_size)), locked=False)
+
+
+def test_c1_step_locked_fp32_ragged_tiles_and_short_tail(c1):
+    # batch 136 leaves ragged tiles in both tile kernels; the last batch has 10 events
+    run(c1, "fp32", list(S.batches(c1.w.num_events, 136))[:12] + [(9990, 10)], locked=True)
+
+
+def test_c1_without_negatives(c1):
+    run(c1, "fp32", list(S.batches(c1.w.num_events, 200))[:4], locked=False, with_neg=False)
+
+
+def test_c1_whole_stream_free_running_bf16(c1):
+    run(c1, "bf16", list(S.batches(c1.w.num_events, c1.w.batch_size)), locked=False)
+
+
+def test_c1_single_event_batches(c1):
+    run(c1, "fp32", [(e, 1) for e in range(3000, 3006)], locked=False, warm_at=3000)
+
+
+# ------------------------------------------------------------------------------------- C2
+
+
+@pytest.fixture(scope="module")
+def c2():
+    return Bundle(S.WORKLOADS["c2_bipartite_medium"])
+
+
+def test_c2_from_reset_free_running_fp32(c2):
+    run(c2, "fp32", list(S.batches(c2.w.num_events, 200))[:12], locked=False)
+
+
+def test_c2_windows_and_last_short_batch_fp32(c2):
+    w = c2.w
+    for frac in (0.5, 0.9):
+        first, bs = window(w, frac, 3)
+        run(c2, "fp32", bs, locked=False, warm_at=first)
+    last = (w.num_events // 200) * 200            # 157,474 = 787 * 200 + 74
+    assert w.num_events - last == 74
+    run(c2, "fp32", [(last - 200, 200), (last, 74)], locked=True, warm_at=last - 200)
+
+
+def test_c2_window_bf16(c2):
+    first, bs = window(c2.w, 0.5, 3)
+    run(c2, "bf16", bs, locked=False, warm_at=first)
+
+
+# ------------------------------------------------------------------------------------- C3
+
+
+@pytest.fixture(scope="module")
+def c3():
+    return Bundle(S.WORKLOADS["c3_bipartite_dense"])
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+@pytest.mark.parametrize("batch", [200, 2000])
+def test_c3_windows(c3, precision, batch):
+    steps = 3 if batch == 200 else 2
+    for frac in (0.1, 0.5, 0.9):
+        first, bs = window(c3.w, frac, steps, batch)
+        run(c3, precision, bs, locked=False, warm_at=first)
+
+
+# ------------------------------------------------------------------------------------- C4
+
+
+@pytest.fixture(scope="module")
+def c4():
+    return Bundle(S.WORKLOADS["c4_million_node"])
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("precision", ["bf16", "fp32"])
+def test_c4_windows(c4, precision):
+    for frac in (0.1, 0.9):
+        first, bs = window(c4.w, frac, 2)
+        run(c4, precision, bs, locked=False, warm_at=first)
