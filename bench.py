@@ -34,14 +34,15 @@ def algorithmic_bytes(w, count, roles, nbr_cnt_sum, winners):
     Q = roles * count
     entries = 2 * count
     return {
-        # event (src, dst, ts) reads + one 8-byte key update per entry
-        "k_scatter_keys": entries * (4 + 8 + 8),
-        # per query: node id, time, two offsets, the K-entry window; writes of the K slots + count
-        "k_nbr_lookup": Q * (4 + 8 + 16 + 16 * K) + Q * (16 * K + 4),
-        # per entry key check; per winner two memory rows, last_update, edge feature; new row out
-        "k_gru": entries * (4 + 8 + 8) + winners * ((2 * M + F) * 4 + 8) + winners * M * 4,
+        # scatter: event (src, dst, ts) reads + one 8-byte key update per entry; lookup: per query
+        # node id, time, two offsets, the K-entry window; writes of the K slots + count
+        "k_pre": entries * (4 + 8 + 8) + Q * (4 + 8 + 16 + 16 * K) + Q * (16 * K + 4),
+        # per entry: event read, key read, list write for winners
+        "k_select": entries * (4 + 8 + 8) + winners * 4,
+        # per winner two memory rows, last_update, edge feature; new row out
+        "k_gru": winners * (4 + 16 + (2 * M + F) * 4 + 8) + winners * M * 4,
         # per winner: staged row in, memory row + last_update + key out
-        "k_commit": entries * (4 + 8 + 8) + winners * (2 * M * 4 + 16),
+        "k_commit": winners * (4 + 16 + 2 * M * 4 + 16),
         # per query: own memory row, neighbour table; per filled slot a memory row + an edge
         # feature row; embedding and scores out
         "k_embed": Q * (M * 4 + 4 + 4) + nbr_cnt_sum * ((M + F) * 4 + 16) + Q * E * 4 + (roles - 1) * count * 4,

@@ -296,15 +296,25 @@ hipError_t pack_weights(const Dims &d, const tig_weights &w, void *dst, void *sc
     TIG_TRY(hipGetLastError());
     TIG_TRY((gemm64<float, double>(s, S.cQ, 1, w.W_Q + M, da, 1, S.phi0, 1, 1, da, 1, T, 1.0, 1.0)));
     const double scale = 1.0 / sqrt((double)dh);
+    // The embedding kernel holds a key/value row in the order [Phi (T) | s_v (M) | e (F)] (time
+    // encoding first, so that its lanes are densely packed); the model's order is
+    // [s_v | e | Phi].  seg[] maps each run of model columns to its place in the kernel's order.
+    const int F = d.F;
+    const int seg_src[3] = {M + F, 0, M};
+    const int seg_dst[3] = {0, T, T + M};
+    const int seg_len[3] = {T, M, F};
     for (int h = 0; h < H; ++h) {
         const float *WK_h = w.W_K + (size_t)h * dh * dkv;   // [dh x dkv]
         const float *WQm_h = w.W_Q + (size_t)h * dh * da;   // [dh x da], first M columns used
-        // A1_h[j][m] = scale * sum_r W_K[h*dh + r][j] * W_Q[h*dh + r][m]
-        TIG_TRY((gemm64<float, float>(s, S.A1 + (size_t)h * d.dkvp * M, M, WK_h, 1, dkv, WQm_h, da, 1,
-                                      dkv, M, dh, scale, 0.0)));
-        // a1_h[j] = scale * sum_r W_K[h*dh + r][j] * cQ[h*dh + r]
-        TIG_TRY((gemm64<float, double>(s, S.a1 + (size_t)h * d.dkvp, 1, WK_h, 1, dkv, S.cQ + h * dh, 1,
-                                       1, dkv, 1, dh, scale, 0.0)));
+        for (int g = 0; g < 3; ++g) {
+            // A1_h[j][m] = scale * sum_r W_K[h*dh + r][j] * W_Q[h*dh + r][m]
+            TIG_TRY((gemm64<float, float>(s, S.A1 + ((size_t)h * d.dkvp + seg_dst[g]) * M, M,
+                                          WK_h + seg_src[g], 1, dkv, WQm_h, da, 1, seg_len[g], M, dh,
+                                          scale, 0.0)));
+            // a1_h[j] = scale * sum_r W_K[h*dh + r][j] * cQ[h*dh + r]
+            TIG_TRY((gemm64<float, double>(s, S.a1 + (size_t)h * d.dkvp + seg_dst[g], 1, WK_h + seg_src[g],
+                                           1, dkv, S.cQ + h * dh, 1, 1, seg_len[g], 1, dh, scale, 0.0)));
+        }
     }
     TIG_TRY(pack<double>(s, d.prec, L.emb_A1, S.A1, M, d.N1, M, d.N1, d.Mq));
     hipLaunchKernelGGL(k_vec_f32, grid(d.N1), blk, 0, s, L.emb_a1, d.N1, d.N1, (const double *)S.a1,
@@ -318,8 +328,10 @@ hipError_t pack_weights(const Dims &d, const tig_weights &w, void *dst, void *sc
     const int ldPR = H * d.dkvp + M;
     for (int h = 0; h < H; ++h) {
         // P_h = G[:, h*dh:(h+1)*dh] W_V[h*dh:(h+1)*dh, :]   [E x dkv]
-        TIG_TRY((gemm64<double, float>(s, S.PR + (size_t)h * d.dkvp, ldPR, S.G + h * dh, da, 1,
-                                       w.W_V + (size_t)h * dh * dkv, dkv, 1, E, dkv, dh, 1.0, 0.0)));
+        for (int g = 0; g < 3; ++g)
+            TIG_TRY((gemm64<double, float>(s, S.PR + (size_t)h * d.dkvp + seg_dst[g], ldPR, S.G + h * dh,
+                                           da, 1, w.W_V + (size_t)h * dh * dkv + seg_src[g], dkv, 1, E,
+                                           seg_len[g], dh, 1.0, 0.0)));
     }
     hipLaunchKernelGGL(k_copy_block, grid((size_t)E * M), blk, 0, s, S.PR + (size_t)H * d.dkvp, ldPR,
                        w.W_m1 + da, ld_m1, E, M);

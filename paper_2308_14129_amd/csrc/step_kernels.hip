@@ -1,7 +1,9 @@
 // The kernels of one batch step (paper Sec. II-C, "Training approach for TIGs"), gfx950 only.
 //
-//   k_scatter_keys  last-message aggregation: 64-bit (time, event id) atomicMax per node
-//   k_nbr_lookup    most-recent-K temporal neighbours, one wavefront per query, 64-way search
+//   k_pre           two jobs in one launch: last-message aggregation (64-bit (time, event id)
+//                   atomicMax per node) and most-recent-K temporal neighbours (one wavefront
+//                   per query, 64-way search)
+//   k_select        winners = entries whose key survived; compacted list
 //   k_gru           message gather + time encoding -> LDS tile -> MFMA gate GEMMs -> new rows
 //   k_commit        memory overwrite M <- s_i(t), last_update, key clear
 //   k_embed         attention over neighbours (folded projections), merge MLP, link decoder
@@ -107,6 +109,27 @@ __device__ inline float wave_sum(float v)
     return v;
 }
 
+template <int CTRL, int ROW_MASK, int BANK_MASK>
+__device__ inline float dpp_or_zero(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, BANK_MASK, true));
+}
+
+// Sum over the 64 lanes, returned as a wave-uniform value: a prefix sum inside each row of 16
+// lanes (row_shr 1, 2, 4, 8; lanes shifted in from outside the row read as 0), then the row
+// totals are carried forward (row_bcast 15, row_bcast 31) so that lane 63 holds the total.
+// All 64 lanes must be active.
+__device__ inline float wave_sum_uniform(float v)
+{
+    v += dpp_or_zero<0x111, 0xf, 0xf>(v);
+    v += dpp_or_zero<0x112, 0xf, 0xf>(v);
+    v += dpp_or_zero<0x114, 0xf, 0xf>(v);
+    v += dpp_or_zero<0x118, 0xf, 0xf>(v);
+    v += dpp_or_zero<0x142, 0xa, 0xf>(v);
+    v += dpp_or_zero<0x143, 0xc, 0xf>(v);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
 // Phi(x)_k = cos(w*x + b): argument and reduction to [-pi/4, pi/4] + quadrant in fp64 (the
 // argument reaches ~1e6 rad, beyond fp32), polynomial in fp32 (truncation < 3e-8).
 __device__ inline float time_enc(float w, float b, double x)
@@ -135,45 +158,73 @@ __device__ inline unsigned long long winner_key(double t, int32_t eid, int role)
 }
 
 // ------------------------------------------------------------------------------------------
-// Last-message aggregation, part 1.  One thread per (event, role) entry; lanes of a wavefront
-// that hit the same node are merged first (hub nodes take thousands of entries per batch), so
-// at most one atomic per distinct node per wavefront reaches memory.
-__global__ void __launch_bounds__(256) k_scatter_keys(StepArgs a)
+// First launch of a step, two independent jobs side by side (block-uniform choice):
+//
+//  * blocks [0, n_scatter): last-message aggregation, part 1.  Each block takes 1024 (event,
+//    role) entries.  Lanes of a wavefront that hit the same node are merged first, then the
+//    block merges across wavefronts in an LDS hash table (hub nodes take thousands of entries
+//    per batch, and same-address device atomics serialise), and finally issues one 64-bit
+//    atomicMax of the (time, event id) key per distinct node of the block.
+//  * remaining blocks: most-recent-K neighbours before the query time.  One wavefront per query:
+//    64-way search for the first adjacency entry with time >= t, then lanes 0..K-1 read the K
+//    entries below it.
+constexpr int kScatterEntries = 1024;
+constexpr int kHashSlots = 2048;  // power of two, >= 2 * kScatterEntries: never fills up
+
+__device__ inline void scatter_keys_block(const StepArgs &a, int block)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    const bool active = i < 2 * a.count;
-    int32_t node = -1;
-    unsigned long long key = 0;
-    if (active) {
-        const int64_t eid = a.first_eid + (i >> 1);
-        const int role = i & 1;
-        node = role ? a.dst[eid] : a.src[eid];
-        key = winner_key(a.ts[eid], (int32_t)eid, role);
+    __shared__ int32_t t_node[kHashSlots];
+    __shared__ unsigned long long t_key[kHashSlots];
+    for (int sidx = threadIdx.x; sidx < kHashSlots; sidx += blockDim.x) {
+        t_node[sidx] = -1;
+        t_key[sidx] = 0ull;
     }
-    unsigned long long todo = __ballot(active);
+    if (block == 0 && threadIdx.x == 0)
+        *a.n_win = 0;  // counter of the compaction that follows in the next launch
+    __syncthreads();
     const int lane = lane_id();
-    while (todo) {
-        const int leader = __ffsll((long long)todo) - 1;
-        const int32_t n0 = __shfl(node, leader, kWave);
-        const bool same = active && node == n0;
-        const unsigned long long grp = __ballot(same);
-        // keys grow with the entry index (time-sorted events): the highest lane holds the max
-        const int top = 63 - __clzll((long long)grp);
-        if (lane == top)
-            atomicMax(a.key + n0, key);
-        todo &= ~grp;
+    for (int it = 0; it < kScatterEntries / 256; ++it) {
+        const int i = block * kScatterEntries + it * 256 + threadIdx.x;
+        const bool active = i < 2 * a.count;
+        int32_t node = -1;
+        unsigned long long key = 0;
+        if (active) {
+            const int64_t eid = a.first_eid + (i >> 1);
+            const int role = i & 1;
+            node = role ? a.dst[eid] : a.src[eid];
+            key = winner_key(a.ts[eid], (int32_t)eid, role);
+        }
+        unsigned long long todo = __ballot(active);
+        bool insert = false;
+        while (todo) {
+            const int leader = __ffsll((long long)todo) - 1;
+            const int32_t n0 = __shfl(node, leader, kWave);
+            const unsigned long long grp = __ballot(active && node == n0);
+            // keys grow with the entry index (time-sorted events): the highest lane holds the max
+            if (lane == 63 - __clzll((long long)grp))
+                insert = true;
+            todo &= ~grp;
+        }
+        if (insert) {
+            uint32_t h = ((uint32_t)node * 2654435761u) >> 21;  // 11 bits
+            while (true) {
+                const int32_t prev = atomicCAS(&t_node[h], -1, node);
+                if (prev == -1 || prev == node) {
+                    atomicMax(&t_key[h], key);
+                    break;
+                }
+                h = (h + 1) & (kHashSlots - 1);
+            }
+        }
     }
+    __syncthreads();
+    for (int sidx = threadIdx.x; sidx < kHashSlots; sidx += blockDim.x)
+        if (t_node[sidx] >= 0)
+            atomicMax(a.key + t_node[sidx], t_key[sidx]);
 }
 
-// ------------------------------------------------------------------------------------------
-// Most-recent-K neighbours before the query time.  One wavefront per query: 64-way search for
-// the first adjacency entry with time >= t, then lanes 0..K-1 read the K entries below it.
-__global__ void __launch_bounds__(256) k_nbr_lookup(StepArgs a, int K)
+__device__ inline void nbr_lookup_wave(const StepArgs &a, int K, int q)
 {
-    const int q = blockIdx.x * (blockDim.x / kWave) + wave_id();
-    const int Q = a.roles * a.count;
-    if (q >= Q)
-        return;
     const int lane = lane_id();
     const int role = q / a.count;
     const int b = q - role * a.count;
@@ -229,6 +280,44 @@ __global__ void __launch_bounds__(256) k_nbr_lookup(StepArgs a, int K)
         a.nbr_cnt[q] = (int32_t)(avail < K ? avail : K);
 }
 
+__global__ void __launch_bounds__(256) k_pre(StepArgs a, int K, int n_scatter)
+{
+    if ((int)blockIdx.x < n_scatter) {
+        scatter_keys_block(a, blockIdx.x);
+    } else {
+        const int q = ((int)blockIdx.x - n_scatter) * (256 / kWave) + wave_id();
+        if (q < a.roles * a.count)
+            nbr_lookup_wave(a, K, q);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Last-message aggregation, part 2: an entry supplies its node's message iff the node's key is
+// the entry's own.  Winners are compacted into win_list (order irrelevant: rows are independent).
+__global__ void __launch_bounds__(256) k_select(StepArgs a)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    bool win = false;
+    if (i < 2 * a.count) {
+        const int64_t eid = a.first_eid + (i >> 1);
+        const int role = i & 1;
+        const int32_t node = role ? a.dst[eid] : a.src[eid];
+        win = a.key[node] == winner_key(a.ts[eid], (int32_t)eid, role);
+        if (a.is_winner)
+            a.is_winner[i] = win ? 1 : 0;
+    }
+    const unsigned long long mask = __ballot(win);
+    if (mask == 0ull)
+        return;
+    const int lane = lane_id();
+    int base = 0;
+    if (lane == 0)
+        base = atomicAdd(a.n_win, __popcll(mask));
+    base = __shfl(base, 0, kWave);
+    if (win)
+        a.win_list[base + __popcll(mask & ((1ull << lane) - 1ull))] = i;
+}
+
 // ------------------------------------------------------------------------------------------
 // acc[mt] += A[16*mt .. 16*mt+15][0 .. kblocks*KB) x W[nt]^T.
 // A: LDS rows of `lda` BYTES (4 bytes per element in either precision).  W: lane-ordered blocks,
@@ -243,7 +332,26 @@ __device__ inline void tile_gemm(floatx4 (&acc)[MT], const char *A, int lda, con
     const size_t w0 = ((size_t)nt * w_kblocks + w_kb0) * kWave + lane;
     const char *ap = A + (size_t)(lane & 15) * lda;
     const int g = lane >> 4;
-    for (int kb = 0; kb < kblocks; ++kb) {
+    // weight operands come from L2: keep kPrefetch loads in flight ahead of the MFMAs
+    constexpr int kPrefetch = 4;
+    int kb = 0;
+    for (; kb + kPrefetch <= kblocks; kb += kPrefetch) {
+        frag bfrag[kPrefetch];
+#pragma unroll
+        for (int u = 0; u < kPrefetch; ++u)
+            bfrag[u] = P::load_w(W, w0 + (size_t)(kb + u) * kWave);
+#pragma unroll
+        for (int u = 0; u < kPrefetch; ++u) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                if (mt < m_tiles) {
+                    const frag afrag = P::load_a(ap + (size_t)mt * 16 * lda, kb + u, g);
+                    P::mma(acc[mt], afrag, bfrag[u]);
+                }
+            }
+        }
+    }
+    for (; kb < kblocks; ++kb) {
         const frag bfrag = P::load_w(W, w0 + (size_t)kb * kWave);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -281,35 +389,20 @@ k_gru(StepArgs a, PackedWeights w, GruParams g)
     constexpr int EC = 16 * MT;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int *row_entry = (int *)smem;            // [EC]
-    int *n_rows_p = row_entry + EC;          // [1]
     char *X = smem + 512;                    // [EC rows x ldx bytes]
 
     const int lane = lane_id();
     const int wave = wave_id();
-    const int entry0 = blockIdx.x * EC;
 
-    // 1. which entries of this chunk supply their node's message (ordered compaction)
-    if (wave == 0) {
-        const int i = entry0 + lane;
-        bool win = false;
-        if (lane < EC && i < 2 * a.count) {
-            const int64_t eid = a.first_eid + (i >> 1);
-            const int role = i & 1;
-            const int32_t node = role ? a.dst[eid] : a.src[eid];
-            win = a.key[node] == winner_key(a.ts[eid], (int32_t)eid, role);
-            if (a.is_winner)
-                a.is_winner[i] = win ? 1 : 0;
-        }
-        const unsigned long long mask = __ballot(win);
-        if (win)
-            row_entry[__popcll(mask & ((1ull << lane) - 1ull))] = i;
-        if (lane == 0)
-            *n_rows_p = __popcll(mask);
-    }
-    __syncthreads();
-    const int n_rows = *n_rows_p;
-    if (n_rows == 0)
+    // 1. this block's slice of the compacted winner list
+    const int n_win = *a.n_win;
+    const int r0 = blockIdx.x * EC;
+    if (r0 >= n_win)
         return;
+    const int n_rows = n_win - r0 < EC ? n_win - r0 : EC;
+    if (threadIdx.x < n_rows)
+        row_entry[threadIdx.x] = a.win_list[r0 + threadIdx.x];
+    __syncthreads();
     const int m_tiles = (n_rows + 15) / 16;
 
     // 2. message rows [s_self | s_other | Phi(t - last_update[self]) | e] from batch-start memory
@@ -385,24 +478,21 @@ k_gru(StepArgs a, PackedWeights w, GruParams g)
 }
 
 // ------------------------------------------------------------------------------------------
-// Memory overwrite for the winners (after every message has read the batch-start memory).
-// One wavefront per entry.
+// Memory overwrite M <- s_i(t) for the winners (after every message has read the batch-start
+// memory), last_update, and key clear.  One wavefront per winner.
 __global__ void __launch_bounds__(256) k_commit(StepArgs a, int M)
 {
-    const int i = blockIdx.x * (blockDim.x / kWave) + wave_id();
-    if (i >= 2 * a.count)
+    const int r = blockIdx.x * (blockDim.x / kWave) + wave_id();
+    if (r >= *a.n_win)
         return;
     const int lane = lane_id();
+    const int i = a.win_list[r];
     const int64_t eid = a.first_eid + (i >> 1);
-    const int role = i & 1;
-    const int32_t node = role ? a.dst[eid] : a.src[eid];
-    const double t = a.ts[eid];
-    if (a.key[node] != winner_key(t, (int32_t)eid, role))
-        return;  // another occurrence of the node is later (it alone clears the key)
+    const int32_t node = (i & 1) ? a.dst[eid] : a.src[eid];
     for (int j = lane; j < M; j += kWave)
         a.mem[(size_t)node * M + j] = a.staging[(size_t)i * M + j];
     if (lane == 0) {
-        a.lu[node] = t;
+        a.lu[node] = a.ts[eid];
         a.key[node] = 0ull;
     }
 }
@@ -488,14 +578,14 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
 
     // ---- C. attention over the neighbours: scores <q~_h, kv_k>, softmax, kvbar_h = sum a_k kv_k
     {
-        // per-lane view of the key/value row [s_v (M) | e (F) | Phi (T) | 0]: dims j = lane + 64 n
+        // per-lane view of the key/value row, kernel order [Phi (T) | s_v (M) | e (F) | 0]:
+        // lane owns dims j = lane + 64 n.  (Time encoding first: its lanes are densely packed.)
         float tw[NPL], tb[NPL];
 #pragma unroll
         for (int n = 0; n < NPL; ++n) {
             const int j = lane + kWave * n;
-            const bool is_phi = j >= p.M + p.F && j < p.dkv;
-            tw[n] = is_phi ? w.time_w[j - p.M - p.F] : 0.0f;
-            tb[n] = is_phi ? w.time_b[j - p.M - p.F] : 0.0f;
+            tw[n] = j < p.T ? w.time_w[j] : 0.0f;
+            tb[n] = j < p.T ? w.time_b[j] : 0.0f;
         }
         for (int r = wave; r < ROWS; r += kTileWaves) {
             const int q = row_q[r];
@@ -538,9 +628,9 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                     const int32_t e = __shfl(nb_e, k & 63, kWave);
 #pragma unroll
                     for (int n = 0; n < NPL; ++n) {
-                        const int j = lane + kWave * n;
+                        const int j = lane + kWave * n - p.T;
                         float x = 0.0f;
-                        if (k < cnt) {
+                        if (k < cnt && j >= 0) {
                             if (j < p.M)
                                 x = a.mem[(size_t)v * p.M + j];
                             else if (j < p.M + p.F)
@@ -549,38 +639,60 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                         raw[kk][n] = x;
                     }
                 }
+                // time encoding of t - t_k, then every score of the chunk (independent reductions)
+                float sc[KC][kMaxHeads];
 #pragma unroll
                 for (int kk = 0; kk < KC; ++kk) {
                     const int k = c0 + kk;
+#pragma unroll
+                    for (int h = 0; h < kMaxHeads; ++h)
+                        sc[kk][h] = -INFINITY;
                     if (k < cnt) {  // wave-uniform
                         const double dt = __shfl(dt_lane, k & 63, kWave);
-                        float part[kMaxHeads];
-#pragma unroll
-                        for (int h = 0; h < kMaxHeads; ++h)
-                            part[h] = 0.0f;
 #pragma unroll
                         for (int n = 0; n < NPL; ++n) {
-                            const int j = lane + kWave * n;
-                            if (j >= p.M + p.F && j < p.dkv)
-                                raw[kk][n] = time_enc(tw[n], tb[n], dt);
-#pragma unroll
-                            for (int h = 0; h < kMaxHeads; ++h)
-                                part[h] += qv[h][n] * raw[kk][n];
+                            if (kWave * n < p.T) {  // uniform: this register holds Phi dims
+                                if (lane + kWave * n < p.T)
+                                    raw[kk][n] = time_enc(tw[n], tb[n], dt);
+                            }
                         }
 #pragma unroll
                         for (int h = 0; h < kMaxHeads; ++h) {
                             if (h < p.H) {  // uniform
-                                const float s = wave_sum(part[h]);
-                                const float mnew = fmaxf(mx[h], s);
-                                const float corr = expf(mx[h] - mnew);
-                                const float pk = expf(s - mnew);
-                                den[h] = den[h] * corr + pk;
+                                float part = 0.0f;
 #pragma unroll
                                 for (int n = 0; n < NPL; ++n)
-                                    accv[h][n] = accv[h][n] * corr + pk * raw[kk][n];
-                                mx[h] = mnew;
+                                    part += qv[h][n] * raw[kk][n];
+                                sc[kk][h] = wave_sum_uniform(part);
                             }
                         }
+                    }
+                }
+                // softmax across the chunk, merged with earlier chunks by rescaling
+#pragma unroll
+                for (int h = 0; h < kMaxHeads; ++h) {
+                    if (h < p.H) {
+                        float mnew = mx[h];
+#pragma unroll
+                        for (int kk = 0; kk < KC; ++kk)
+                            mnew = fmaxf(mnew, sc[kk][h]);
+                        const float corr = expf(mx[h] - mnew);  // first chunk: exp(-inf) = 0
+                        float dsum = den[h] * corr;
+#pragma unroll
+                        for (int n = 0; n < NPL; ++n)
+                            accv[h][n] *= corr;
+#pragma unroll
+                        for (int kk = 0; kk < KC; ++kk) {
+                            if (c0 + kk < cnt) {
+                                const float pk = expf(sc[kk][h] - mnew);
+                                dsum += pk;
+#pragma unroll
+                                for (int n = 0; n < NPL; ++n)
+                                    accv[h][n] += pk * raw[kk][n];
+                            }
+                        }
+                        den[h] = dsum;
+                        mx[h] = mnew;
                     }
                 }
             }
@@ -825,8 +937,11 @@ bool plan_launch(const Dims &d, int lds_limit, LaunchPlan *plan)
 {
     if (d.dkvp > 512)
         return false;
+    // GRU rows are the compacted winners (often a small fraction of the 2B entries): small
+    // tiles spread them over many compute units; very large batches use tall tiles so that the
+    // gate weights are streamed from L2 fewer times.
     plan->gru_mt = 0;
-    for (int mt = 4; mt >= 1; --mt)
+    for (int mt = (2 * d.max_batch <= 16384 ? 1 : 4); mt >= 1; --mt)
         if (gru_lds_bytes(d, mt) <= lds_limit) {
             plan->gru_mt = mt;
             break;
@@ -878,10 +993,11 @@ hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeight
 
     if ((e = stamp()) != hipSuccess)
         return e;
-    hipLaunchKernelGGL(k_scatter_keys, dim3((entries + 255) / 256), dim3(256), 0, s, a);
+    const int n_scatter = (entries + kScatterEntries - 1) / kScatterEntries;
+    hipLaunchKernelGGL(k_pre, dim3(n_scatter + (Q + 3) / 4), dim3(256), 0, s, a, d.K, n_scatter);
     if ((e = hipGetLastError()) != hipSuccess || (e = stamp()) != hipSuccess)
         return e;
-    hipLaunchKernelGGL(k_nbr_lookup, dim3((Q + 3) / 4), dim3(256), 0, s, a, d.K);
+    hipLaunchKernelGGL(k_select, dim3((entries + 255) / 256), dim3(256), 0, s, a);
     if ((e = hipGetLastError()) != hipSuccess || (e = stamp()) != hipSuccess)
         return e;
     {

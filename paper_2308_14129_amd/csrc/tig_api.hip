@@ -29,6 +29,7 @@ struct tig_ctx {
     int32_t *nbr_node, *nbr_eid, *nbr_cnt;
     double *nbr_ts;
     float *staging;
+    int32_t *win_list, *n_win;
     hipEvent_t marks[kNumStepKernels + 1];
     bool have_marks;
     char err[256];
@@ -136,6 +137,7 @@ struct StepScratch {
     int32_t *nbr_node, *nbr_eid, *nbr_cnt;
     double *nbr_ts;
     float *staging;
+    int32_t *win_list, *n_win;
     size_t bytes;
 };
 
@@ -149,6 +151,8 @@ StepScratch step_scratch(const Dims &d, void *base)
     S.nbr_ts = c.take<double>(Q * d.K);
     S.nbr_cnt = c.take<int32_t>(Q);
     S.staging = c.take<float>((size_t)2 * d.max_batch * d.M);
+    S.win_list = c.take<int32_t>((size_t)2 * d.max_batch);
+    S.n_win = c.take<int32_t>(1);
     S.bytes = c.off;
     return S;
 }
@@ -366,6 +370,8 @@ int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *w
     ctx->nbr_ts = S.nbr_ts;
     ctx->nbr_cnt = S.nbr_cnt;
     ctx->staging = S.staging;
+    ctx->win_list = S.win_list;
+    ctx->n_win = S.n_win;
     *out = ctx;
     return TIG_OK;
 }
@@ -403,6 +409,8 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     a.nbr_ts = out->nbr_ts ? out->nbr_ts : ctx->nbr_ts;
     a.nbr_cnt = out->nbr_cnt ? out->nbr_cnt : ctx->nbr_cnt;
     a.staging = ctx->staging;
+    a.win_list = ctx->win_list;
+    a.n_win = ctx->n_win;
     a.is_winner = out->is_winner;
     a.emb = out->emb;
     a.score_pos = out->score_pos;

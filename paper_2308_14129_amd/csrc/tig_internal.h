@@ -77,6 +77,8 @@ struct StepArgs {
     int32_t *nbr_node, *nbr_eid, *nbr_cnt;
     double *nbr_ts;
     float *staging;  // [2*count x M] new memory rows of the winners, by entry 2b+role
+    int32_t *win_list;  // [2*count] entries that supply their node's message (compacted)
+    int32_t *n_win;     // [1] their number
     uint8_t *is_winner;  // may be NULL
     // outputs
     float *emb, *score_pos, *score_neg;
