@@ -1,0 +1,524 @@
+// k_embed: temporal attention embedding, merge MLP and link decoder of one batch step
+// (embedding module f and decoder g of the paper's Sec. II-C), fused in one kernel.  gfx950 only.
+//
+// One workgroup (16 wavefronts) owns TE consecutive events x {source, destination, negative}
+// query rows, 16*MT rows in all, and keeps every intermediate of those rows in LDS:
+//   A  query rows: node, query index, neighbour count, s_u (the UPDATED memory row)
+//   B  folded query  q~ = A1 s_u + a1                        (matrix cores; fp32 result)
+//   C  per row: gather the K neighbour rows [Phi(t - t_k) | s_v | e], scores <q~_h, kv_k>,
+//      softmax over the filled slots, kvbar_h = sum_k a_k kv_k   (vector ALU, one wavefront/row)
+//   D  h1 = relu(P kvbar + R s_u + c)                         (matrix cores, k split over 2 waves)
+//   E  emb = W_m2 h1 + b_m2 -> global                         (matrix cores)
+//   F  decoder layer 1 split by operand: [W_a emb | W_b emb]  (matrix cores)
+//   G  logit = w_d2 . relu(W_a emb_src + W_b emb_other + b_d1) + b_d2
+// The projections W_Q, W_K, W_V, W_O and the first merge layer are folded into A1 and P at init
+// (pack.hip), which removes the per-neighbour key/value projections.
+#include <hip/hip_runtime.h>
+
+#include "kernels_common.h"
+
+namespace tig {
+
+#ifdef TIG_PHASE_CLOCKS
+__device__ unsigned long long g_phase_clocks[8192 * 8];
+extern "C" __attribute__((visibility("default"))) int tig_debug_phase_clocks(unsigned long long *out, int n)
+{
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase_clocks), sizeof(unsigned long long) * (size_t)n);
+}
+#endif
+
+namespace {
+
+// Wavefronts per workgroup: 16 (128 registers per lane) unless a key/value row needs more than
+// four registers per lane, then 8 (256 registers per lane).
+template <int NPL>
+struct EmbedShape {
+    static constexpr int kThreads = NPL >= 8 ? 512 : 1024;
+    static constexpr int kWaves = kThreads / kWave;
+};
+
+struct EmbedParams {
+    int M, T, F, E, K;
+    int dkv, dkvp, Mq, N1, K2, Ep, Ek;
+    int TE;         // events per workgroup; rows = roles * TE <= 16 * MT
+    int row_bytes;  // LDS bytes per query row of the main buffer: [q~ / kvbar (N1) | s_u (Mq)]
+    int ld1;        // row stride of the E-wide buffers, bytes
+    int off_h1, off_meta;  // byte offsets in LDS
+    int dec_off;    // byte offset of the decoder pre-activations (inside the main buffer)
+};
+
+template <int PREC, int MT, int NPL, int H>
+__global__ void __launch_bounds__(EmbedShape<NPL>::kThreads)
+k_embed(StepArgs a, PackedWeights w, EmbedParams p)
+{
+    using P = Prec<PREC>;
+    constexpr int kEmbedThreads = EmbedShape<NPL>::kThreads;
+    constexpr int kEmbedWaves = EmbedShape<NPL>::kWaves;
+    constexpr int ROWS = 16 * MT;
+    constexpr int RPW = (ROWS + kEmbedWaves - 1) / kEmbedWaves;  // rows per wavefront in phase C
+    constexpr int KC = NPL >= 8 ? 5 : (NPL == 4 ? 10 : 16);      // neighbour rows in flight
+    constexpr int NPHI = NPL;  // registers that may hold time-encoding dims (T <= 64 * NPL)
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char *rowbuf = smem;
+    char *h1buf = smem + p.off_h1;
+    int *row_q = (int *)(smem + p.off_meta);  // [ROWS] query index or -1
+    int *row_cnt = row_q + ROWS;              // [ROWS]
+    int *row_node = row_cnt + ROWS;           // [ROWS]
+    double *row_t = (double *)(row_node + ROWS);  // [ROWS] query time
+    double *tw_tab = row_t + ROWS;                // [T][2] time-encoding (w_rev, b_rev)
+
+    const int lane = lane_id();
+    const int wave = wave_id();
+    const int ev0 = blockIdx.x * p.TE;
+    const int mem_off = 4 * p.N1;
+
+    TIG_MARK(0);
+    // ---- A. query rows ------------------------------------------------------------------------
+    if (threadIdx.x < ROWS) {
+        const int r = threadIdx.x;
+        const int role = r / p.TE;
+        const int b = ev0 + (r - role * p.TE);
+        const bool act = role < a.roles && b < a.count;
+        int32_t u = -1;
+        int q = -1, cnt = 0;
+        double t = 0.0;
+        if (act) {
+            const int64_t eid = a.first_eid + b;
+            u = role == 0 ? a.src[eid] : (role == 1 ? a.dst[eid] : a.neg[b]);
+            q = role * a.count + b;
+            cnt = a.nbr_cnt[q];
+            t = a.ts[eid];
+        }
+        row_q[r] = q;
+        row_node[r] = (u >= 0 && (int64_t)u < a.num_nodes) ? u : -1;
+        row_cnt[r] = cnt;
+        row_t[r] = t;
+    }
+    for (int j = threadIdx.x; j < p.T; j += kEmbedThreads) {
+        tw_tab[2 * j] = w.time_w_rev[j];
+        tw_tab[2 * j + 1] = w.time_b_rev[j];
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < ROWS * p.Mq; idx += kEmbedThreads) {
+        const int r = idx / p.Mq;
+        const int j = idx - r * p.Mq;
+        const int u = row_node[r];
+        float v = 0.0f;
+        if (u >= 0 && j < p.M)
+            v = a.mem[(size_t)u * p.M + j];
+        P::store_a(rowbuf + (size_t)r * p.row_bytes + mem_off, j, v);
+    }
+    __syncthreads();
+
+    TIG_MARK(1);
+    // ---- B. folded query: q~ = A1 s_u + a1  (fp32, [H x dkvp] per row) -----------------------
+    for (int nt = wave; nt < p.N1 / 16; nt += kEmbedWaves) {
+        floatx4 acc[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+            acc[mt] = floatx4{0, 0, 0, 0};
+        tile_gemm<PREC, MT, 4>(acc, rowbuf, p.row_bytes, p.N1 / P::KB, w.emb_A1, p.Mq / P::KB, 0,
+                               p.Mq / P::KB, nt);
+        const int col = nt * 16 + (lane & 15);
+        const float bias = w.emb_a1[col];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = mt * 16 + 4 * (lane >> 4) + v;
+                ((float *)(rowbuf + (size_t)row * p.row_bytes))[col] = acc[mt][v] + bias;
+            }
+    }
+    __syncthreads();
+
+    TIG_MARK(2);
+    // ---- C. attention over the neighbours ------------------------------------------------------
+    {
+        // per-lane view of a key/value row, kernel order [Phi (T) | s_v (M) | e (F) | 0]: the lane
+        // owns dims j = lane + 64 n.  (Time encoding first: its lanes are densely packed.)
+        int goff[NPL];  // >= 0: offset in the neighbour's memory row; <= -2: -(2 + offset in the
+                        // edge-feature row); -1: nothing to load
+#pragma unroll
+        for (int n = 0; n < NPL; ++n) {
+            const int jj = lane + kWave * n - p.T;
+            goff[n] = jj < 0 ? -1 : (jj < p.M ? jj : (jj < p.M + p.F ? -(2 + jj - p.M) : -1));
+        }
+        // neighbour tables of this wavefront's rows: slot k lives in lane k
+        int32_t nb_v[RPW], nb_e[RPW];
+        double nb_dt[RPW];
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const int r = wave + i * kEmbedWaves;
+            nb_v[i] = -1;
+            nb_e[i] = -1;
+            nb_dt[i] = 0.0;
+            if (r < ROWS) {
+                const int q = row_q[r];
+                if (q >= 0 && lane < row_cnt[r]) {
+                    nb_v[i] = a.nbr_node[(size_t)q * p.K + lane];
+                    nb_e[i] = a.nbr_eid[(size_t)q * p.K + lane];
+                    nb_dt[i] = row_t[r] - a.nbr_ts[(size_t)q * p.K + lane];
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) {
+            const int r = wave + i * kEmbedWaves;
+            if (r >= ROWS)
+                break;
+            if (row_q[r] < 0)
+                continue;
+            const int cnt = row_cnt[r];
+            const float *qrow = (const float *)(rowbuf + (size_t)r * p.row_bytes);
+            char *arow = rowbuf + (size_t)r * p.row_bytes;
+            float qv[H][NPL], accv[H][NPL];
+            float mx[H], den[H];
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                mx[h] = -INFINITY;
+                den[h] = 0.0f;
+#pragma unroll
+                for (int n = 0; n < NPL; ++n) {
+                    const int j = lane + kWave * n;
+                    qv[h][n] = j < p.dkvp ? qrow[h * p.dkvp + j] : 0.0f;
+                    accv[h][n] = 0.0f;
+                }
+            }
+            for (int c0 = 0; c0 < cnt; c0 += KC) {
+                float raw[KC][NPL];
+                // issue every gather of the chunk before using any of them
+#pragma unroll
+                for (int kk = 0; kk < KC; ++kk) {
+                    const int k = c0 + kk;
+                    const int32_t v = __builtin_amdgcn_readlane(nb_v[i], k & 63);
+                    const int32_t e = __builtin_amdgcn_readlane(nb_e[i], k & 63);
+                    const float *mrow = a.mem + (size_t)(v < 0 ? 0 : v) * p.M;
+                    const float *erow = a.edge_feat + (size_t)(e < 0 ? 0 : e) * p.F;
+#pragma unroll
+                    for (int n = 0; n < NPL; ++n) {
+                        float x = 0.0f;
+                        if (k < cnt) {
+                            if (goff[n] >= 0)
+                                x = mrow[goff[n]];
+                            else if (goff[n] <= -2)
+                                x = erow[-2 - goff[n]];
+                        }
+                        raw[kk][n] = x;
+                    }
+                }
+                // time encoding of t - t_k, then every score of the chunk (independent reductions)
+                float sc[KC][H];
+#pragma unroll
+                for (int kk = 0; kk < KC; ++kk) {
+                    const int k = c0 + kk;
+#pragma unroll
+                    for (int h = 0; h < H; ++h)
+                        sc[kk][h] = -INFINITY;
+                    if (k < cnt) {  // wave-uniform
+                        const double dt = __shfl(nb_dt[i], k & 63, kWave);
+#pragma unroll
+                        for (int n = 0; n < NPHI; ++n) {
+                            if (kWave * n < p.T) {  // uniform: this register holds Phi dims
+                                const int j = lane + kWave * n < p.T ? lane + kWave * n : 0;
+                                const float ph = time_enc(tw_tab[2 * j], tw_tab[2 * j + 1], dt);
+                                if (lane + kWave * n < p.T)
+                                    raw[kk][n] = ph;
+                            }
+                        }
+#pragma unroll
+                        for (int h = 0; h < H; ++h) {
+                            float part = 0.0f;
+#pragma unroll
+                            for (int n = 0; n < NPL; ++n)
+                                part += qv[h][n] * raw[kk][n];
+                            sc[kk][h] = wave_sum_uniform(part);
+                        }
+                    }
+                }
+                // softmax across the chunk, merged with earlier chunks by rescaling
+#pragma unroll
+                for (int h = 0; h < H; ++h) {
+                    float mnew = mx[h];
+#pragma unroll
+                    for (int kk = 0; kk < KC; ++kk)
+                        mnew = fmaxf(mnew, sc[kk][h]);
+                    const float corr = __expf(mx[h] - mnew);  // first chunk: exp(-inf) = 0
+                    float dsum = den[h] * corr;
+#pragma unroll
+                    for (int n = 0; n < NPL; ++n)
+                        accv[h][n] *= corr;
+#pragma unroll
+                    for (int kk = 0; kk < KC; ++kk) {
+                        if (c0 + kk < cnt) {
+                            const float pk = __expf(sc[kk][h] - mnew);
+                            dsum += pk;
+#pragma unroll
+                            for (int n = 0; n < NPL; ++n)
+                                accv[h][n] += pk * raw[kk][n];
+                        }
+                    }
+                    den[h] = dsum;
+                    mx[h] = mnew;
+                }
+            }
+            // kvbar overwrites q~ in place (as matrix-core operand elements)
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                const float inv = cnt > 0 ? 1.0f / den[h] : 0.0f;
+#pragma unroll
+                for (int n = 0; n < NPL; ++n) {
+                    const int j = lane + kWave * n;
+                    if (j < p.dkvp)
+                        P::store_a(arow, h * p.dkvp + j, accv[h][n] * inv);
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    TIG_MARK(3);
+    // ---- D. merge layer 1: h1 = relu(P kvbar + R s_u + c)   (c0 when there is no neighbour) ---
+    // The row [kvbar | s_u] is one contiguous K2-deep operand.  The k range is split over two
+    // wavefronts per output tile when that fills more of the workgroup; the upper half hands its
+    // partial sums over through LDS (the h1 buffer, not yet written).
+    {
+        const int n_tiles = p.Ep / 16;
+        const int kbT = p.K2 / P::KB;
+        const int ksplit = (2 * n_tiles <= kEmbedWaves && kbT >= 8) ? 2 : 1;
+        const int kb_half = (kbT + ksplit - 1) / ksplit;
+        float *red = (float *)h1buf;  // [ROWS][ld1/4] partial sums of the upper k half
+        floatx4 acc[MT];
+        int my_nt = -1, my_ks = 0;
+        for (int base = 0; base < n_tiles * ksplit; base += kEmbedWaves) {  // at most one round if split
+            const int unit = base + wave;
+            const bool on = unit < n_tiles * ksplit;
+            my_nt = on ? unit % n_tiles : -1;
+            my_ks = on ? unit / n_tiles : 0;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                acc[mt] = floatx4{0, 0, 0, 0};
+            if (on) {
+                const int kb0 = my_ks * kb_half;
+                const int nkb = (kbT - kb0) < kb_half ? (kbT - kb0) : kb_half;
+                tile_gemm<PREC, MT, 4>(acc, rowbuf, p.row_bytes, kb0, w.emb_PR, kbT, kb0, nkb, my_nt);
+            }
+            if (ksplit == 2) {
+                if (on && my_ks == 1) {
+                    const int col = my_nt * 16 + (lane & 15);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int row = mt * 16 + 4 * (lane >> 4) + v;
+                            red[(size_t)row * (p.ld1 / 4) + col] = acc[mt][v];
+                        }
+                }
+                __syncthreads();
+            }
+            if (on && my_ks == 0) {
+                const int col = my_nt * 16 + (lane & 15);
+                const float c = w.emb_c[col], c0 = w.emb_c0[col];
+                float part[MT][4];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int row = mt * 16 + 4 * (lane >> 4) + v;
+                        part[mt][v] = ksplit == 2 ? red[(size_t)row * (p.ld1 / 4) + col] : 0.0f;
+                    }
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int row = mt * 16 + 4 * (lane >> 4) + v;
+                        const float x = acc[mt][v] + part[mt][v] + (row_cnt[row] > 0 ? c : c0);
+                        P::store_a(h1buf + (size_t)row * p.ld1, col, fmaxf(x, 0.0f));
+                    }
+            }
+        }
+    }
+    // k-depth padding of the E-wide buffers (columns Ep..Ek-1)
+    for (int idx = threadIdx.x; idx < ROWS * (p.Ek - p.Ep); idx += kEmbedThreads) {
+        const int row = idx / (p.Ek - p.Ep), col = p.Ep + idx % (p.Ek - p.Ep);
+        P::store_a(h1buf + (size_t)row * p.ld1, col, 0.0f);
+    }
+    __syncthreads();
+
+    TIG_MARK(4);
+    // ---- E. merge layer 2: emb = W_m2 h1 + b_m2 -> global, and kept as the decoder operand ---
+    char *embbuf = rowbuf;  // [ROWS rows x ld1 bytes], the main buffer is free again
+    for (int nt = wave; nt < p.Ep / 16; nt += kEmbedWaves) {
+        floatx4 acc[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+            acc[mt] = floatx4{0, 0, 0, 0};
+        tile_gemm<PREC, MT, 4>(acc, h1buf, p.ld1, 0, w.emb_Wm2, p.Ek / P::KB, 0, p.Ek / P::KB, nt);
+        const int col = nt * 16 + (lane & 15);
+        const float bias = w.emb_bm2[col];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = mt * 16 + 4 * (lane >> 4) + v;
+                const float x = acc[mt][v] + bias;
+                const int q = row_q[row];
+                if (q >= 0 && col < p.E)
+                    a.emb[(size_t)q * p.E + col] = x;
+                P::store_a(embbuf + (size_t)row * p.ld1, col, x);
+            }
+    }
+    for (int idx = threadIdx.x; idx < ROWS * (p.Ek - p.Ep); idx += kEmbedThreads) {
+        const int row = idx / (p.Ek - p.Ep), col = p.Ep + idx % (p.Ek - p.Ep);
+        P::store_a(embbuf + (size_t)row * p.ld1, col, 0.0f);
+    }
+    __syncthreads();
+
+    TIG_MARK(5);
+    // ---- F. decoder layer 1, split by operand: [W_a emb | W_b emb] for every row -------------
+    float *decbuf = (float *)(rowbuf + p.dec_off);  // [ROWS x 2Ep]
+    for (int nt = wave; nt < 2 * p.Ep / 16; nt += kEmbedWaves) {
+        floatx4 acc[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+            acc[mt] = floatx4{0, 0, 0, 0};
+        tile_gemm<PREC, MT, 4>(acc, embbuf, p.ld1, 0, w.dec_W, p.Ek / P::KB, 0, p.Ek / P::KB, nt);
+        const int col = nt * 16 + (lane & 15);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = mt * 16 + 4 * (lane >> 4) + v;
+                decbuf[(size_t)row * 2 * p.Ep + col] = acc[mt][v];
+            }
+    }
+    __syncthreads();
+
+    TIG_MARK(6);
+    // ---- G. logits: w_d2 . relu(W_a emb_src + W_b emb_other + b_d1) + b_d2 --------------------
+    const int pairs = p.TE * (a.roles - 1);
+    for (int pr = wave; pr < pairs; pr += kEmbedWaves) {
+        const int which = pr / p.TE;  // 0: destination, 1: negative
+        const int ev = pr - which * p.TE;
+        const int b = ev0 + ev;
+        if (b >= a.count)
+            continue;
+        const float *da = decbuf + (size_t)ev * 2 * p.Ep;
+        const float *db = decbuf + (size_t)((which + 1) * p.TE + ev) * 2 * p.Ep + p.Ep;
+        float part = 0.0f;
+        for (int j = lane; j < p.E; j += kWave)
+            part += w.dec_w2[j] * fmaxf(da[j] + db[j] + w.dec_b1[j], 0.0f);
+        const float s = wave_sum_uniform(part) + w.dec_b2[0];
+        if (lane == 0)
+            (which == 0 ? a.score_pos : a.score_neg)[b] = s;
+    }
+    TIG_MARK(7);
+}
+
+// ------------------------------------------------------------------------------------------
+// host side
+
+EmbedParams embed_params(const Dims &d, int mt, int roles)
+{
+    EmbedParams p;
+    p.M = d.M;
+    p.T = d.T;
+    p.F = d.F;
+    p.E = d.E;
+    p.K = d.K;
+    p.dkv = d.dkv;
+    p.dkvp = d.dkvp;
+    p.Mq = d.Mq;
+    p.N1 = d.N1;
+    p.K2 = d.K2;
+    p.Ep = d.Ep;
+    p.Ek = d.Ek;
+    const int rows = 16 * mt;
+    p.TE = rows / roles;
+    p.row_bytes = lds_row_bytes(d.N1 + d.Mq);
+    p.ld1 = lds_row_bytes(d.Ek);
+    const int emb_bytes = rows * p.ld1;
+    p.dec_off = (emb_bytes + 15) / 16 * 16;
+    int main_bytes = rows * p.row_bytes;
+    const int tail_bytes = p.dec_off + rows * 2 * d.Ep * 4;
+    if (tail_bytes > main_bytes)
+        main_bytes = tail_bytes;
+    main_bytes = (main_bytes + 15) / 16 * 16;
+    p.off_h1 = main_bytes;
+    p.off_meta = p.off_h1 + rows * p.ld1;
+    return p;
+}
+
+int npl_for(const Dims &d)
+{
+    const int need = (d.dkvp + 63) / 64;
+    int npl = 1;
+    while (npl < need)
+        npl *= 2;
+    return npl;
+}
+
+template <int PREC, int MT, int NPL>
+const void *pick_h(int H)
+{
+    switch (H) {
+    case 1: return (const void *)k_embed<PREC, MT, NPL, 1>;
+    case 2: return (const void *)k_embed<PREC, MT, NPL, 2>;
+    default: return (const void *)k_embed<PREC, MT, NPL, 4>;
+    }
+}
+
+template <int PREC, int MT>
+const void *pick_npl(int npl, int H)
+{
+    switch (npl) {
+    case 1: return pick_h<PREC, MT, 1>(H);
+    case 2: return pick_h<PREC, MT, 2>(H);
+    case 4: return pick_h<PREC, MT, 4>(H);
+    default: return pick_h<PREC, MT, 8>(H);
+    }
+}
+
+template <int PREC>
+const void *pick_mt(int mt, int npl, int H)
+{
+    switch (mt) {
+    case 1: return pick_npl<PREC, 1>(npl, H);
+    case 2: return pick_npl<PREC, 2>(npl, H);
+    default: return pick_npl<PREC, 3>(npl, H);
+    }
+}
+
+const void *embed_kernel(const Dims &d, int mt)
+{
+    const int npl = npl_for(d);
+    return d.prec == TIG_BF16_MFMA ? pick_mt<TIG_BF16_MFMA>(mt, npl, d.H) : pick_mt<TIG_FP32>(mt, npl, d.H);
+}
+
+}  // namespace
+
+int embed_lds_bytes(const Dims &d, int mt)
+{
+    const EmbedParams p = embed_params(d, mt, 3);
+    return p.off_meta + 16 * mt * (3 * 4 + 8) + d.T * 16;
+}
+
+hipError_t prepare_embed(const Dims &d, const LaunchPlan &plan)
+{
+    return hipFuncSetAttribute(embed_kernel(d, plan.emb_mt), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               plan.emb_lds);
+}
+
+hipError_t launch_embed(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
+                        hipStream_t s)
+{
+    StepArgs aa = a;
+    PackedWeights ww = pw;
+    EmbedParams p = embed_params(d, plan.emb_mt, a.roles);
+    void *args[] = {&aa, &ww, &p};
+    const int grid = (a.count + p.TE - 1) / p.TE;
+    const int threads = npl_for(d) >= 8 ? EmbedShape<8>::kThreads : EmbedShape<1>::kThreads;
+    return hipLaunchKernel(embed_kernel(d, plan.emb_mt), dim3(grid), dim3(threads), args,
+                           (size_t)plan.emb_lds, s);
+}
+
+}  // namespace tig

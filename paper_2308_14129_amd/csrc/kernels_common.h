@@ -1,0 +1,202 @@
+// Device-side building blocks shared by the step kernels (gfx950, wave64).
+//
+// Tile GEMM convention (16x16 output tiles on the matrix cores):
+//   operand A: activations in LDS, row-major; lane l supplies row l%16 and KB/4 consecutive k's
+//              starting at k0 + (KB/4)*(l/16);
+//   operand B: prepared weights, already lane-ordered in global memory (pack.hip);
+//   result   : lane l holds rows 4*(l/16)+v (v = 0..3) of column l%16.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "tig_internal.h"
+
+namespace tig {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+#ifdef TIG_PHASE_CLOCKS
+// Debug build only: per-block timestamps (100 MHz real-time counter) at phase boundaries.  The
+// translation unit that uses TIG_MARK defines g_phase_clocks.
+#define TIG_MARK(slot)                                                    \
+    do {                                                                  \
+        if (threadIdx.x == 0 && blockIdx.x < 8192)                        \
+            g_phase_clocks[blockIdx.x * 8 + (slot)] = wall_clock64();     \
+    } while (0)
+#else
+#define TIG_MARK(slot) \
+    do {               \
+    } while (0)
+#endif
+
+constexpr int kWave = 64;
+
+template <int PREC>
+struct Prec;
+
+// fp32 operands: one k-block = 16 k's = four 16x16x4 MFMAs fed by one 16-byte load per lane.
+template <>
+struct Prec<TIG_FP32> {
+    struct frag {
+        floatx4 v;
+    };
+    static constexpr int KB = 16;
+    // activation element k of an LDS row
+    static __device__ inline void store_a(char *row, int k, float v) { ((float *)row)[k] = v; }
+    // lane's operand of k-block kb: 4 consecutive k's starting at kb*16 + 4*g, g = lane/16
+    static __device__ inline frag load_a(const char *row, int kb, int g)
+    {
+        return frag{*(const floatx4 *)(row + (size_t)(kb * 16 + 4 * g) * 4)};
+    }
+    static __device__ inline frag load_w(const void *W, size_t idx) { return frag{((const floatx4 *)W)[idx]}; }
+    static __device__ inline void mma(floatx4 &acc, const frag &a, const frag &b)
+    {
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.v[0], b.v[0], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.v[1], b.v[1], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.v[2], b.v[2], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.v[3], b.v[3], acc, 0, 0, 0);
+    }
+};
+
+// bf16 matrix cores with split operands: x = hi + lo, hi = bf16(x), lo = bf16(x - hi), for
+// activations and weights alike; a*w ~ a_hi*w_hi + a_lo*w_hi + a_hi*w_lo (the dropped lo*lo term
+// is ~2^-18 relative), accumulated in fp32.  One k-block = 32 k's = three 16x16x32 MFMAs.
+// Storage: groups of 8 k's, 8 hi values (16 bytes) followed by their 8 lo values (16 bytes), so
+// an element still takes 4 bytes and a lane's operand is one contiguous 32-byte read.
+template <>
+struct Prec<TIG_BF16_MFMA> {
+    struct frag {
+        bf16x8 hi, lo;
+    };
+    static constexpr int KB = 32;
+    static __device__ inline void store_a(char *row, int k, float v)
+    {
+        __bf16 *p = (__bf16 *)row + ((k >> 3) << 4) + (k & 7);
+        const __bf16 hi = (__bf16)v;  // round to nearest even
+        p[0] = hi;
+        p[8] = (__bf16)(v - (float)hi);
+    }
+    static __device__ inline frag load_a(const char *row, int kb, int g)
+    {
+        const char *p = row + (size_t)(kb * 4 + g) * 32;
+        return frag{*(const bf16x8 *)p, *(const bf16x8 *)(p + 16)};
+    }
+    static __device__ inline frag load_w(const void *W, size_t idx)
+    {
+        const char *p = (const char *)W + idx * 32;
+        return frag{*(const bf16x8 *)p, *(const bf16x8 *)(p + 16)};
+    }
+    static __device__ inline void mma(floatx4 &acc, const frag &a, const frag &b)
+    {
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.lo, b.hi, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.hi, b.lo, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.hi, b.hi, acc, 0, 0, 0);
+    }
+};
+
+__device__ inline int lane_id() { return threadIdx.x & (kWave - 1); }
+__device__ inline int wave_id() { return threadIdx.x / kWave; }
+
+template <int CTRL, int ROW_MASK, int BANK_MASK>
+__device__ inline float dpp_or_zero(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, BANK_MASK, true));
+}
+
+// Sum over the 64 lanes, returned as a wave-uniform value: a prefix sum inside each row of 16
+// lanes (row_shr 1, 2, 4, 8; lanes shifted in from outside the row read as 0), then the row
+// totals are carried forward (row_bcast 15, row_bcast 31) so that lane 63 holds the total.
+// All 64 lanes must be active.
+__device__ inline float wave_sum_uniform(float v)
+{
+    v += dpp_or_zero<0x111, 0xf, 0xf>(v);
+    v += dpp_or_zero<0x112, 0xf, 0xf>(v);
+    v += dpp_or_zero<0x114, 0xf, 0xf>(v);
+    v += dpp_or_zero<0x118, 0xf, 0xf>(v);
+    v += dpp_or_zero<0x142, 0xa, 0xf>(v);
+    v += dpp_or_zero<0x143, 0xc, 0xf>(v);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+// Phi(x)_k = cos(w_k x + b_k) (the time encoding of Sec. II-C).  The phase is formed in
+// revolutions in fp64 -- w_rev = w / 2pi, b_rev = b / 2pi prepared at init; the argument reaches
+// ~1e6 rad, far beyond fp32 -- reduced to [0, 1) in fp64, and the hardware cosine (input in
+// revolutions, measured max abs error 1.3e-7 on [0, 1)) is applied to the fp32 fraction.
+// Total abs error < 6e-7.
+__device__ inline float time_enc(double w_rev, double b_rev, double x)
+{
+    const double phase = fma(w_rev, x, b_rev);
+    return __builtin_amdgcn_cosf((float)__builtin_amdgcn_fract(phase));
+}
+
+// (time, event id, role) -> 64-bit key whose unsigned order is the lexicographic order of
+// (float(time), event id).  Events are time-sorted, so this equals the (time, event id) order.
+// Always non-zero for finite times; 0 means "no message for this node".
+__device__ inline unsigned long long winner_key(double t, int32_t eid, int role)
+{
+    const uint32_t bits = __float_as_uint((float)t);
+    const uint32_t mono = (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
+    return ((unsigned long long)mono << 32) | (unsigned long long)(((uint32_t)eid << 1) | (uint32_t)role);
+}
+
+// acc[mt] += A[16*mt .. 16*mt+15][k-blocks kb0 .. kb0+kblocks) x W[nt]^T.
+// A: LDS rows of `lda` BYTES (4 bytes per element in either precision); A's k-block kb0+i pairs
+// with W's k-block w_kb0+i.  W: lane-ordered blocks, `w_kblocks` per output tile.
+// Weight operands come from L2 and the loop is latency-bound, so up to DEPTH operand loads are
+// issued before the first MFMA of a group.
+template <int PREC, int MT, int DEPTH>
+__device__ inline void tile_gemm(floatx4 (&acc)[MT], const char *A, int lda, int a_kb0, const void *W,
+                                 int w_kblocks, int w_kb0, int kblocks, int nt)
+{
+    using P = Prec<PREC>;
+    using frag = typename P::frag;
+    const int lane = lane_id();
+    const size_t w0 = ((size_t)nt * w_kblocks + w_kb0) * kWave + lane;
+    const char *ap = A + (size_t)(lane & 15) * lda;
+    const int g = lane >> 4;
+    int kb = 0;
+    for (; kb + DEPTH <= kblocks; kb += DEPTH) {
+        frag bfrag[DEPTH];
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u)
+            bfrag[u] = P::load_w(W, w0 + (size_t)(kb + u) * kWave);
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const frag afrag = P::load_a(ap + (size_t)mt * 16 * lda, a_kb0 + kb + u, g);
+                P::mma(acc[mt], afrag, bfrag[u]);
+            }
+        }
+    }
+    if (kb < kblocks) {  // remainder: same depth, predicated
+        frag bfrag[DEPTH];
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u)
+            if (kb + u < kblocks)
+                bfrag[u] = P::load_w(W, w0 + (size_t)(kb + u) * kWave);
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u) {
+            if (kb + u < kblocks) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const frag afrag = P::load_a(ap + (size_t)mt * 16 * lda, a_kb0 + kb + u, g);
+                    P::mma(acc[mt], afrag, bfrag[u]);
+                }
+            }
+        }
+    }
+}
+
+// Row stride in bytes >= 4*width whose 16-byte chunk count is odd: the 16 rows read by one
+// operand load then fall into distinct LDS bank groups.
+__host__ __device__ inline int lds_row_bytes(int width_elems)
+{
+    int chunks = (width_elems * 4 + 15) / 16;
+    if ((chunks & 1) == 0)
+        ++chunks;
+    return chunks * 16;
+}
+
+}  // namespace tig

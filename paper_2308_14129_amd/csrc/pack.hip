@@ -80,6 +80,13 @@ __global__ void k_vec_f32(float *out, int n_pad, int n, const double *a, const f
     out[i] = (float)v;
 }
 
+__global__ void k_to_revolutions(double *out, const float *in, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n)
+        out[i] = (double)in[i] / 6.283185307179586476925286766559;
+}
+
 __global__ void k_phi0(double *out, const float *time_b, int T)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -168,7 +175,7 @@ hipError_t pack(hipStream_t s, int prec, void *out, const TS *W, int ld, int row
 }
 
 struct PackedLayout {
-    float *time_w, *time_b;
+    double *time_w_rev, *time_b_rev;
     void *gru_Wr, *gru_Wz, *gru_Win, *gru_Whn;
     float *gru_br, *gru_bz, *gru_bin, *gru_bhn;
     void *emb_A1;
@@ -187,8 +194,8 @@ PackedLayout layout(const Dims &d, void *base)
     Carver c(base);
     PackedLayout L;
     const size_t e = (size_t)d.esz;
-    L.time_w = c.take<float>(d.T);
-    L.time_b = c.take<float>(d.T);
+    L.time_w_rev = c.take<double>(d.T);
+    L.time_b_rev = c.take<double>(d.T);
     L.gru_Wr = c.take<char>(e * d.Ng * d.Kg);
     L.gru_Wz = c.take<char>(e * d.Ng * d.Kg);
     L.gru_Win = c.take<char>(e * d.Ng * d.Kg);
@@ -261,11 +268,9 @@ hipError_t pack_weights(const Dims &d, const tig_weights &w, void *dst, void *sc
     TIG_TRY(launch_fill_zero(dst, L.bytes, s));
     TIG_TRY(launch_fill_zero(scratch, S.bytes, s));
 
-    // time encoding parameters as they are
-    hipLaunchKernelGGL(k_vec_f32, grid(T), blk, 0, s, L.time_w, T, T, (const double *)nullptr, w.time_w,
-                       (const float *)nullptr);
-    hipLaunchKernelGGL(k_vec_f32, grid(T), blk, 0, s, L.time_b, T, T, (const double *)nullptr, w.time_b,
-                       (const float *)nullptr);
+    // time encoding parameters in revolutions: the kernels take cos(2 pi (w_rev x + b_rev))
+    hipLaunchKernelGGL(k_to_revolutions, grid(T), blk, 0, s, L.time_w_rev, w.time_w, T);
+    hipLaunchKernelGGL(k_to_revolutions, grid(T), blk, 0, s, L.time_b_rev, w.time_b, T);
 
     // ---- GRU: gates r, z with the hidden weights folded onto the s_self columns ------------
     const float *W_ir = w.W_i, *W_iz = w.W_i + (size_t)M * Dmsg, *W_in = w.W_i + (size_t)2 * M * Dmsg;
@@ -364,8 +369,8 @@ hipError_t pack_weights(const Dims &d, const tig_weights &w, void *dst, void *sc
                        (const float *)nullptr);
     TIG_TRY(hipGetLastError());
 
-    pw->time_w = L.time_w;
-    pw->time_b = L.time_b;
+    pw->time_w_rev = L.time_w_rev;
+    pw->time_b_rev = L.time_b_rev;
     pw->gru_Wr = L.gru_Wr;
     pw->gru_Wz = L.gru_Wz;
     pw->gru_Win = L.gru_Win;

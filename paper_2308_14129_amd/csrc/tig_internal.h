@@ -41,7 +41,7 @@ struct Dims {
 
 // Prepared (folded, padded, lane-ordered) weights in `persistent`.
 struct PackedWeights {
-    const float *time_w, *time_b;              // [T]
+    const double *time_w_rev, *time_b_rev;     // [T] time-encoding frequency / phase in revolutions (w/2pi, b/2pi)
     const void *gru_Wr, *gru_Wz, *gru_Win;     // [Ng x Kg] packed
     const void *gru_Whn;                       // [Ng x Khn] packed
     const float *gru_br, *gru_bz, *gru_bin, *gru_bhn;  // [Ng]
@@ -108,6 +108,17 @@ hipError_t pack_weights(const Dims &d, const tig_weights &w_dev_f32, void *dst, 
                         PackedWeights *pw, hipStream_t s);
 
 bool plan_launch(const Dims &d, int lds_limit, LaunchPlan *plan);
+int gru_lds_bytes(const Dims &d, int mt);
+int embed_lds_bytes(const Dims &d, int mt);
+hipError_t prepare_gru(const Dims &d, const LaunchPlan &plan);
+hipError_t prepare_embed(const Dims &d, const LaunchPlan &plan);
+hipError_t launch_pre(const StepArgs &a, int K, hipStream_t s);
+hipError_t launch_select(const StepArgs &a, hipStream_t s);
+hipError_t launch_gru(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
+                      hipStream_t s);
+hipError_t launch_commit(const StepArgs &a, int M, hipStream_t s);
+hipError_t launch_embed(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
+                        hipStream_t s);
 hipError_t prepare_kernels(const Dims &d, const LaunchPlan &plan);
 constexpr int kNumStepKernels = 5;
 // `marks`: NULL, or kNumStepKernels + 1 events recorded before the first and after every kernel.

@@ -14,7 +14,7 @@ from ctypes import POINTER, Structure, c_double, c_float, c_int32, c_int64, c_si
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libtig.so")
+LIB_PATH = os.environ.get("TIG_LIB_PATH") or os.path.join(_HERE, "libtig.so")
 
 TIG_OK = 0
 TIG_EINVAL, TIG_ERANGE, TIG_EUNSORTED, TIG_ESELFLOOP, TIG_ENOSPACE, TIG_EHIP, TIG_ENOMEM = (
