@@ -22,6 +22,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 
+# HBM bytes per launch of the dominant kernel (k_embed), from two rocprofv3 --pmc runs (FETCH_SIZE,
+# WRITE_SIZE), each scaled by what the counter reads for a plain 256 MiB device copy; see
+# profiles/hbm_traffic_c5_gpu_partition_bf16.md.  Only known for the combinations measured.
+MEASURED_TRAFFIC_BYTES = {("c5_gpu_partition", "bf16", 4000): 19.7e6}
+
 
 def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
@@ -36,13 +41,15 @@ def algorithmic_bytes(w, count, roles, nbr_cnt_sum, winners):
     return {
         # scatter: event (src, dst, ts) reads + one 8-byte key update per entry; lookup: per query
         # node id, time, two offsets, the K-entry window; writes of the K slots + count
-        "k_pre": entries * (4 + 8 + 8) + Q * (4 + 8 + 16 + 16 * K) + Q * (16 * K + 4),
-        # per entry: event read, key read, list write for winners
-        "k_select": entries * (4 + 8 + 8) + winners * 4,
-        # per winner two memory rows, last_update, edge feature; new row out
-        "k_gru": winners * (4 + 16 + (2 * M + F) * 4 + 8) + winners * M * 4,
-        # per winner: staged row in, memory row + last_update + key out
-        "k_commit": winners * (4 + 16 + 2 * M * 4 + 16),
+        "k_scatter": entries * (4 + 8 + 8) * 2 + entries * 8 + winners * (8 + 32),
+        # own launch only for batches above 4096 events (otherwise fused into k_scatter)
+        "k_select": 0,
+        # per winner: descriptor, two memory rows, edge feature; new row out.  Per query (lookup,
+        # same launch): node id, time, two offsets, position, the K-entry window; K slots + count out
+        "k_gru": winners * (32 + (2 * M + F) * 4) + winners * M * 4
+                 + Q * (4 + 8 + 16 + 4 + 16 * K) + Q * (16 * K + 4),
+        # per winner: descriptor and staged row in, memory row + last_update + key out
+        "k_commit": winners * (32 + 2 * M * 4 + 16),
         # per query: own memory row, neighbour table; per filled slot a memory row + an edge
         # feature row; embedding and scores out
         "k_embed": Q * (M * 4 + 4 + 4) + nbr_cnt_sum * ((M + F) * 4 + 16) + Q * E * 4 + (roles - 1) * count * 4,
@@ -60,6 +67,9 @@ def main():
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=2)
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run three plain 256 MiB device copies (known HBM traffic) so that a "
+                         "rocprofv3 --pmc run of this command can scale FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1",
@@ -152,7 +162,8 @@ def main():
                   "GBps": round(byte_sums[n] / n_prof / (float(avg_ms[i]) * 1e-3) / 1e9, 1)}
               for i, n in enumerate(names)}
     roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
+                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, precision, B)) if dom_name == "k_embed" else None,
                 "avg_kernel_us": round(float(avg_ms[dom]) * 1e3, 2), "alg_bytes_per_launch": int(dom_bytes),
                 "profiled_steps": n_prof}
 
@@ -176,6 +187,15 @@ def main():
         cpu = {"value": round(cpu_events / cpu_s, 1), "unit": "events/s", "cores": 1, "kind": "oracle",
                "sample": f"{n_cpu} steps of {B} events of the same window (float64 NumPy oracle, "
                          f"indexed neighbour lookup, index build excluded), {cpu_s:.1f} s"}
+
+    if args.pmc_calibration:
+        n = 256 << 20
+        src_buf = torch.full((n,), 1, dtype=torch.uint8, device="cuda:0")
+        dst_buf = torch.empty_like(src_buf)
+        for _ in range(3):
+            dst_buf.copy_(src_buf)   # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src_buf, dst_buf
 
     info = ctx.launch_info()
     line = {

@@ -169,8 +169,10 @@ TIG_API int tig_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *out);
 /*
  * The same step with a HIP event recorded on the context's stream before the first and after
  * every kernel; waits for the step to finish and writes the five kernel durations in
- * milliseconds to kernel_ms[0..4] (host), in launch order: key scatter + neighbour lookup (one
- * launch), winner selection, message + GRU, memory overwrite, attention embedding + decoder.  For measurement:
+ * milliseconds to kernel_ms[0..4] (host), in launch order: key scatter (with the winner selection
+ * fused in for batches of up to 4096 events), winner selection as its own launch (larger batches;
+ * otherwise ~0), message + GRU together with the neighbour lookup, memory overwrite, attention
+ * embedding + decoder.  For measurement:
  * the event records add gaps between kernels, so time throughput with tig_step.
  */
 #define TIG_NUM_STEP_KERNELS 5

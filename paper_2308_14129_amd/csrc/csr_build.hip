@@ -50,7 +50,8 @@ __global__ void k_fill_pairs(const int32_t *__restrict__ src, const int32_t *__r
 
 __global__ void k_fill_csr(const int32_t *__restrict__ src, const int32_t *__restrict__ dst,
                            const double *__restrict__ ts, int64_t num_entries,
-                           const uint32_t *__restrict__ vals_sorted, CsrEntry *__restrict__ csr)
+                           const uint32_t *__restrict__ vals_sorted, CsrEntry *__restrict__ csr,
+                           int32_t *__restrict__ pos)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < num_entries; p += stride) {
@@ -61,6 +62,7 @@ __global__ void k_fill_csr(const int32_t *__restrict__ src, const int32_t *__res
         ent.eid = e;
         ent.ts = ts[e];
         csr[p] = ent;
+        pos[i] = (int32_t)p;  // where entry 2*eid + role sits in the adjacency array
     }
 }
 
@@ -125,7 +127,7 @@ size_t csr_build_scratch_bytes(int64_t num_events, int64_t num_nodes)
 }
 
 hipError_t csr_build(const int32_t *src, const int32_t *dst, const double *ts, int64_t num_events,
-                     int64_t num_nodes, int64_t *indptr, CsrEntry *csr, void *scratch,
+                     int64_t num_nodes, int64_t *indptr, CsrEntry *csr, int32_t *pos, void *scratch,
                      size_t scratch_bytes, hipStream_t s)
 {
     const int64_t n2 = 2 * num_events;
@@ -157,7 +159,7 @@ hipError_t csr_build(const int32_t *src, const int32_t *dst, const double *ts, i
     if (err != hipSuccess)
         return err;
     hipLaunchKernelGGL(k_fill_csr, dim3(grid_for(n2)), dim3(kThreads), 0, s, src, dst, ts, n2,
-                       (const uint32_t *)vals.current(), csr);
+                       (const uint32_t *)vals.current(), csr, pos);
     err = hipGetLastError();
     if (err != hipSuccess)
         return err;

@@ -1,5 +1,8 @@
 // k_gru: message build and GRU state update (message module, state-update module and memory
 // fetch of the paper's Sec. II-C) for the compacted winners of one batch.  gfx950 only.
+// The same launch carries the neighbour lookup of every query in extra workgroups (lookup.h):
+// it depends on nothing the GRU produces, and both are chains of dependent memory round trips,
+// so they hide each other's latency.
 //
 // One workgroup (16 wavefronts) takes 16*MT winners:
 //   1  row descriptors: node, partner, event, dt = t - last_update[node]
@@ -13,6 +16,7 @@
 #include <hip/hip_runtime.h>
 
 #include "kernels_common.h"
+#include "lookup.h"
 
 namespace tig {
 
@@ -65,8 +69,14 @@ __device__ inline void tile_gemm2(floatx4 (&acc1)[MT], floatx4 (&acc2)[MT], cons
 
 template <int PREC, int MT>
 __global__ void __launch_bounds__(kGruThreads)
-k_gru(StepArgs a, PackedWeights w, GruParams g)
+k_gru(StepArgs a, PackedWeights w, GruParams g, int n_gru_blocks, int K)
 {
+    if ((int)blockIdx.x >= n_gru_blocks) {  // lookup workgroup: one query per wavefront
+        const int q = ((int)blockIdx.x - n_gru_blocks) * kGruWaves + wave_id();
+        if (q < a.roles * a.count)
+            nbr_lookup_wave(a, K, q);
+        return;
+    }
     using P = Prec<PREC>;
     constexpr int EC = 16 * MT;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -81,9 +91,13 @@ k_gru(StepArgs a, PackedWeights w, GruParams g)
     const int lane = lane_id();
     const int wave = wave_id();
 
-    // 1. this block's slice of the compacted winner list
-    const int n_win = *a.n_win;
+    // 1. this block's slice of the compacted winner list (descriptor and count are read in the
+    //    same round trip; slots beyond the count hold stale but in-range descriptors)
     const int r0 = blockIdx.x * EC;
+    WinDesc d0;
+    if (threadIdx.x < EC)
+        d0 = a.win[r0 + threadIdx.x];
+    const int n_win = *a.n_win;
     if (r0 >= n_win)
         return;
     const int n_rows = n_win - r0 < EC ? n_win - r0 : EC;
@@ -92,13 +106,11 @@ k_gru(StepArgs a, PackedWeights w, GruParams g)
         int i = 0, u = 0, o = 0, b = 0;
         double dt = 0.0;
         if (r < n_rows) {
-            i = a.win_list[r0 + r];
-            b = i >> 1;
-            const int64_t eid = a.first_eid + b;
-            const int32_t s = a.src[eid], d = a.dst[eid];
-            u = (i & 1) ? d : s;
-            o = (i & 1) ? s : d;
-            dt = a.ts[eid] - a.lu[u];
+            i = d0.entry;
+            u = d0.node;
+            o = d0.other;
+            b = d0.b;
+            dt = d0.dt;
         }
         row_i[r] = i;
         row_u[r] = u;
@@ -145,7 +157,7 @@ k_gru(StepArgs a, PackedWeights w, GruParams g)
         const int col = ct * 16 + (lane & 15);
         if (on) {
             if (half == 0) {
-                tile_gemm2<PREC, MT, 4>(acc1, acc2, X, g.ldx, w.gru_Wr, w.gru_Wz, kblocks, kblocks, kblocks, ct);
+                tile_gemm2<PREC, MT, 5>(acc1, acc2, X, g.ldx, w.gru_Wr, w.gru_Wz, kblocks, kblocks, kblocks, ct);
                 const float br = w.gru_br[col], bz = w.gru_bz[col];
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
@@ -158,9 +170,9 @@ k_gru(StepArgs a, PackedWeights w, GruParams g)
                     }
             } else {
                 // input part over the whole message, hidden part over s_self (the first Khn k's)
-                tile_gemm2<PREC, MT, 4>(acc1, acc2, X, g.ldx, w.gru_Win, w.gru_Whn, kblocks, kblocks_hn,
+                tile_gemm2<PREC, MT, 5>(acc1, acc2, X, g.ldx, w.gru_Win, w.gru_Whn, kblocks, kblocks_hn,
                                         kblocks_hn, ct);
-                tile_gemm<PREC, MT, 4>(acc1, X, g.ldx, kblocks_hn, w.gru_Win, kblocks, kblocks_hn,
+                tile_gemm<PREC, MT, 6>(acc1, X, g.ldx, kblocks_hn, w.gru_Win, kblocks, kblocks_hn,
                                        kblocks - kblocks_hn, ct);
             }
         }
@@ -175,7 +187,7 @@ k_gru(StepArgs a, PackedWeights w, GruParams g)
                     if (row < n_rows) {
                         const float *i2 = rz + ((size_t)row * g.Ng + col) * 2;
                         const float r = i2[0], z = i2[1];
-                        const float h = a.mem[(size_t)row_u[row] * g.M + col];
+                        const float h = P::load_elem(X + (size_t)row * g.ldx, col);  // s_self
                         const float x = acc1[mt][v] + bin + r * (acc2[mt][v] + bhn);
                         const float e2 = __expf(2.0f * x);          // tanh(x) = 1 - 2 / (e^{2x} + 1)
                         const float n = 1.0f - 2.0f / (e2 + 1.0f);
@@ -233,11 +245,13 @@ hipError_t launch_gru(const Dims &d, const LaunchPlan &plan, const PackedWeights
     StepArgs aa = a;
     PackedWeights ww = pw;
     GruParams g = gru_params(d, plan.gru_mt);
-    void *args[] = {&aa, &ww, &g};
     const int entries = 2 * a.count;
-    const int grid = (entries + plan.gru_entries - 1) / plan.gru_entries;
-    return hipLaunchKernel(gru_kernel(d, plan.gru_mt), dim3(grid), dim3(kGruThreads), args,
-                           (size_t)plan.gru_lds, s);
+    int n_gru_blocks = (entries + plan.gru_entries - 1) / plan.gru_entries;
+    int K = d.K;
+    const int n_lookup_blocks = (a.roles * a.count + kGruWaves - 1) / kGruWaves;
+    void *args[] = {&aa, &ww, &g, &n_gru_blocks, &K};
+    return hipLaunchKernel(gru_kernel(d, plan.gru_mt), dim3(n_gru_blocks + n_lookup_blocks),
+                           dim3(kGruThreads), args, (size_t)plan.gru_lds, s);
 }
 
 }  // namespace tig

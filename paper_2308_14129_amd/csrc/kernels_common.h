@@ -44,6 +44,7 @@ struct Prec<TIG_FP32> {
     static constexpr int KB = 16;
     // activation element k of an LDS row
     static __device__ inline void store_a(char *row, int k, float v) { ((float *)row)[k] = v; }
+    static __device__ inline float load_elem(const char *row, int k) { return ((const float *)row)[k]; }
     // lane's operand of k-block kb: 4 consecutive k's starting at kb*16 + 4*g, g = lane/16
     static __device__ inline frag load_a(const char *row, int kb, int g)
     {
@@ -76,6 +77,11 @@ struct Prec<TIG_BF16_MFMA> {
         const __bf16 hi = (__bf16)v;  // round to nearest even
         p[0] = hi;
         p[8] = (__bf16)(v - (float)hi);
+    }
+    static __device__ inline float load_elem(const char *row, int k)  // hi + lo: v to ~2^-17 relative
+    {
+        const __bf16 *p = (const __bf16 *)row + ((k >> 3) << 4) + (k & 7);
+        return (float)p[0] + (float)p[8];
     }
     static __device__ inline frag load_a(const char *row, int kb, int g)
     {

@@ -34,7 +34,9 @@ bool plan_launch(const Dims &d, int lds_limit, LaunchPlan *plan)
 
 hipError_t prepare_kernels(const Dims &d, const LaunchPlan &plan)
 {
-    const hipError_t e = prepare_gru(d, plan);
+    hipError_t e = prepare_small();
+    if (e == hipSuccess)
+        e = prepare_gru(d, plan);
     return e != hipSuccess ? e : prepare_embed(d, plan);
 }
 
@@ -47,9 +49,12 @@ hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeight
 
     if ((e = stamp()) != hipSuccess)
         return e;
-    if ((e = launch_pre(a, d.K, s)) != hipSuccess || (e = stamp()) != hipSuccess)
+    bool needs_select = false;
+    if ((e = launch_scatter(a, s, &needs_select)) != hipSuccess || (e = stamp()) != hipSuccess)
         return e;
-    if ((e = launch_select(a, s)) != hipSuccess || (e = stamp()) != hipSuccess)
+    if (needs_select && (e = launch_select(a, s)) != hipSuccess)
+        return e;
+    if ((e = stamp()) != hipSuccess)
         return e;
     if ((e = launch_gru(d, plan, pw, a, s)) != hipSuccess || (e = stamp()) != hipSuccess)
         return e;

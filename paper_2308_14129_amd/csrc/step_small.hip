@@ -1,162 +1,261 @@
-// The small kernels of one batch step (paper Sec. II-C), gfx950 only:
-//   k_pre     two jobs in one launch: last-message aggregation (64-bit (time, event id) atomicMax
-//             per node) and most-recent-K temporal neighbours (one wavefront per query)
-//   k_select  winners = entries whose key survived; compacted list
-//   k_commit  memory overwrite M <- s_i(t), last_update, key clear
+// The small kernels of one batch step (paper Sec. II-C), gfx950 only.
+//
+// Last-message aggregation (all messages of a node within a batch are aggregated; this build
+// keeps the last one): per node, the (event, role) entry with the greatest 64-bit
+// (time, event id) key wins, found with atomicMax.
+//   k_winners  batches of up to 4096 events: ONE workgroup holds the keys of the whole batch in
+//              an LDS hash table (atomicMax in LDS), selects the winners and writes their
+//              descriptors in entry order.  No global atomics, two memory round trips in all.
+//   k_scatter + k_select  larger batches: keys go to a per-node array in memory, pre-reduced per
+//              wavefront and per workgroup; a second launch selects and compacts the winners.
+//   k_commit   memory overwrite M <- s_i(t), last_update (and key clear on the second path)
 #include <hip/hip_runtime.h>
 
 #include "kernels_common.h"
 
 namespace tig {
 
+#ifdef TIG_PHASE_CLOCKS
+static __device__ unsigned long long g_phase_clocks[8192 * 8];
+extern "C" __attribute__((visibility("default"))) int tig_debug_phase_clocks_small(unsigned long long *out, int n)
+{
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase_clocks), sizeof(unsigned long long) * (size_t)n);
+}
+#endif
+
 namespace {
 
-// ------------------------------------------------------------------------------------------
-// First launch of a step, two independent jobs side by side (block-uniform choice):
-//
-//  * blocks [0, n_scatter): last-message aggregation, part 1.  Each block takes 1024 (event,
-//    role) entries.  Lanes of a wavefront that hit the same node are merged first, then the
-//    block merges across wavefronts in an LDS hash table (hub nodes take thousands of entries
-//    per batch, and same-address device atomics serialise), and finally issues one 64-bit
-//    atomicMax of the (time, event id) key per distinct node of the block.
-//  * remaining blocks: most-recent-K neighbours before the query time.  One wavefront per query:
-//    64-way search for the first adjacency entry with time >= t, then lanes 0..K-1 read the K
-//    entries below it.
-constexpr int kScatterEntries = 1024;
-constexpr int kHashSlots = 2048;  // power of two, >= 2 * kScatterEntries: never fills up
+constexpr int kScatterThreads = 1024;  // one (event, role) entry per thread and iteration
+constexpr int kScatterWaves = kScatterThreads / kWave;
+constexpr int kHashSlots = 2048;       // k_scatter: power of two, 2 x entries per workgroup
+constexpr int kOneIters = 8;           // k_winners: up to 8 entries per thread
+constexpr int kOneMaxEntries = kOneIters * kScatterThreads;
+constexpr int kOneSlots = 12288;       // k_winners: 1.5 x the most distinct nodes, never fills up
+constexpr int kOneLds = kOneSlots * 12 + (kOneIters * kScatterWaves + 1) * 4;
 
-__device__ inline void scatter_keys_block(const StepArgs &a, int block)
+struct Entry {
+    int32_t node, other;
+    double t;
+    unsigned long long key;
+};
+
+__device__ inline Entry load_entry(const StepArgs &a, int i)
 {
-    __shared__ int32_t t_node[kHashSlots];
-    __shared__ unsigned long long t_key[kHashSlots];
-    for (int sidx = threadIdx.x; sidx < kHashSlots; sidx += blockDim.x) {
+    Entry e;
+    const int64_t eid = a.first_eid + (i >> 1);
+    const int role = i & 1;
+    const int32_t s = a.src[eid], d = a.dst[eid];
+    e.node = role ? d : s;
+    e.other = role ? s : d;
+    e.t = a.ts[eid];
+    e.key = winner_key(e.t, (int32_t)eid, role);
+    return e;
+}
+
+// Among the active lanes of the wavefront, true for the one lane per distinct node that holds
+// that node's greatest key.  Keys grow with the entry index (time-sorted events), and entries
+// grow with the lane, so that is the highest lane of each group.
+// Only the first kRounds distinct nodes of the wavefront are merged this way (heavy hitters show
+// up early); lanes of any other node all answer true and meet in the hash table instead.
+__device__ inline bool wave_leader_of_node(bool active, int32_t node)
+{
+    constexpr int kRounds = 4;
+    const int lane = lane_id();
+    unsigned long long todo = __ballot(active);
+    bool leader = active;
+#pragma unroll
+    for (int round = 0; round < kRounds; ++round) {
+        if (todo == 0ull)
+            break;
+        const int first = __ffsll((long long)todo) - 1;
+        const int32_t n0 = __builtin_amdgcn_readlane(node, first);
+        const bool mine = active && node == n0;
+        const unsigned long long grp = __ballot(mine);
+        if (mine)
+            leader = lane == 63 - __clzll((long long)grp);
+        todo &= ~grp;
+    }
+    return leader;
+}
+
+template <int SLOTS>
+__device__ inline uint32_t hash_slot(int32_t node)
+{
+    return (uint32_t)(((uint32_t)node * 2654435761u) >> 8) % (uint32_t)SLOTS;
+}
+
+// insert (node, key) with max-merge into an open-addressing LDS table that is never full
+template <int SLOTS>
+__device__ inline void table_insert_max(int32_t *t_node, unsigned long long *t_key, int32_t node,
+                                        unsigned long long key)
+{
+    uint32_t h = hash_slot<SLOTS>(node);
+    while (true) {
+        const int32_t prev = atomicCAS(&t_node[h], -1, node);
+        if (prev == -1 || prev == node) {
+            atomicMax(&t_key[h], key);
+            return;
+        }
+        h = h + 1 == (uint32_t)SLOTS ? 0u : h + 1;
+    }
+}
+
+__global__ void __launch_bounds__(kScatterThreads) k_winners(StepArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    unsigned long long *t_key = (unsigned long long *)smem;   // [kOneSlots]
+    int32_t *t_node = (int32_t *)(smem + kOneSlots * 8);      // [kOneSlots]
+    int *s_cnt = (int *)(smem + kOneSlots * 12);              // [kOneIters * waves + 1]
+    const int lane = lane_id();
+    const int wave = wave_id();
+    const int n_entries = 2 * a.count;
+
+    TIG_MARK(0);
+    for (int sidx = threadIdx.x; sidx < kOneSlots; sidx += kScatterThreads) {
         t_node[sidx] = -1;
         t_key[sidx] = 0ull;
     }
-    if (block == 0 && threadIdx.x == 0)
-        *a.n_win = 0;  // counter of the compaction that follows in the next launch
+    TIG_MARK(1);
+    // the thread owns entries it*1024 + tid; all of their loads are issued together
+    Entry ent[kOneIters];
+#pragma unroll
+    for (int it = 0; it < kOneIters; ++it) {
+        const int i = it * kScatterThreads + threadIdx.x;
+        ent[it].node = -1;
+        ent[it].other = 0;
+        ent[it].t = 0.0;
+        ent[it].key = 0ull;
+        if (i < n_entries)
+            ent[it] = load_entry(a, i);
+    }
     __syncthreads();
-    const int lane = lane_id();
-    for (int it = 0; it < kScatterEntries / 256; ++it) {
-        const int i = block * kScatterEntries + it * 256 + threadIdx.x;
-        const bool active = i < 2 * a.count;
-        int32_t node = -1;
-        unsigned long long key = 0;
-        if (active) {
-            const int64_t eid = a.first_eid + (i >> 1);
-            const int role = i & 1;
-            node = role ? a.dst[eid] : a.src[eid];
-            key = winner_key(a.ts[eid], (int32_t)eid, role);
-        }
-        unsigned long long todo = __ballot(active);
-        bool insert = false;
-        while (todo) {
-            const int leader = __ffsll((long long)todo) - 1;
-            const int32_t n0 = __shfl(node, leader, kWave);
-            const unsigned long long grp = __ballot(active && node == n0);
-            // keys grow with the entry index (time-sorted events): the highest lane holds the max
-            if (lane == 63 - __clzll((long long)grp))
-                insert = true;
-            todo &= ~grp;
-        }
-        if (insert) {
-            uint32_t h = ((uint32_t)node * 2654435761u) >> 21;  // 11 bits
-            while (true) {
-                const int32_t prev = atomicCAS(&t_node[h], -1, node);
-                if (prev == -1 || prev == node) {
-                    atomicMax(&t_key[h], key);
-                    break;
-                }
-                h = (h + 1) & (kHashSlots - 1);
-            }
+    TIG_MARK(2);
+#pragma unroll
+    for (int it = 0; it < kOneIters; ++it) {
+        if (it * kScatterThreads < n_entries) {  // uniform
+            const bool active = it * kScatterThreads + threadIdx.x < n_entries;
+            if (wave_leader_of_node(active, ent[it].node))
+                table_insert_max<kOneSlots>(t_node, t_key, ent[it].node, ent[it].key);
         }
     }
     __syncthreads();
-    for (int sidx = threadIdx.x; sidx < kHashSlots; sidx += blockDim.x)
+    TIG_MARK(3);
+    // an entry supplies its node's message iff the node's key is the entry's own
+    bool win[kOneIters];
+    double lu[kOneIters];
+#pragma unroll
+    for (int it = 0; it < kOneIters; ++it) {
+        win[it] = false;
+        lu[it] = 0.0;
+        if (it * kScatterThreads + threadIdx.x < n_entries) {
+            uint32_t h = hash_slot<kOneSlots>(ent[it].node);
+            while (t_node[h] != ent[it].node)
+                h = h + 1 == (uint32_t)kOneSlots ? 0u : h + 1;
+            win[it] = t_key[h] == ent[it].key;
+            if (win[it])
+                lu[it] = a.lu[ent[it].node];
+        }
+    }
+    TIG_MARK(4);
+    // ordered compaction: counts per (iteration, wavefront), exclusive prefix, then the writes
+    int rank[kOneIters];
+#pragma unroll
+    for (int it = 0; it < kOneIters; ++it) {
+        const unsigned long long m = __ballot(win[it]);
+        rank[it] = __popcll(m & ((1ull << lane) - 1ull));
+        if (lane == 0)
+            s_cnt[it * kScatterWaves + wave] = __popcll(m);
+    }
+    __syncthreads();
+    if (wave == 0) {
+        constexpr int kPer = kOneIters * kScatterWaves / kWave;  // counts per lane
+        int c[kPer], sum = 0;
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            c[j] = s_cnt[lane * kPer + j];
+            sum += c[j];
+        }
+        int incl = sum;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const int up = __shfl_up(incl, off, kWave);
+            if (lane >= off)
+                incl += up;
+        }
+        int run = incl - sum;
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            s_cnt[lane * kPer + j] = run;
+            run += c[j];
+        }
+        if (lane == kWave - 1)
+            *a.n_win = incl;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < kOneIters; ++it) {
+        const int i = it * kScatterThreads + threadIdx.x;
+        if (i < n_entries && a.is_winner)
+            a.is_winner[i] = win[it] ? 1 : 0;
+        if (win[it]) {
+            WinDesc d;
+            d.entry = i;
+            d.node = ent[it].node;
+            d.other = ent[it].other;
+            d.b = i >> 1;
+            d.dt = ent[it].t - lu[it];
+            d.t = ent[it].t;
+            a.win[s_cnt[it * kScatterWaves + wave] + rank[it]] = d;
+        }
+    }
+    TIG_MARK(5);
+}
+
+// Larger batches, part 1: keys to the per-node array in memory.  Lanes of a wavefront that hit
+// the same node are merged first, then the workgroup merges across wavefronts in an LDS hash
+// table (hub nodes take thousands of entries per batch, and same-address device atomics
+// serialise), and finally one atomicMax per distinct node of the workgroup goes to memory.
+__global__ void __launch_bounds__(kScatterThreads) k_scatter(StepArgs a)
+{
+    __shared__ int32_t t_node[kHashSlots];
+    __shared__ unsigned long long t_key[kHashSlots];
+    for (int sidx = threadIdx.x; sidx < kHashSlots; sidx += kScatterThreads) {
+        t_node[sidx] = -1;
+        t_key[sidx] = 0ull;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+        *a.n_win = 0;  // counter of k_select, which follows
+    __syncthreads();
+    const int i = blockIdx.x * kScatterThreads + threadIdx.x;
+    const bool active = i < 2 * a.count;
+    Entry e;
+    e.node = -1;
+    e.key = 0ull;
+    if (active)
+        e = load_entry(a, i);
+    if (wave_leader_of_node(active, e.node))
+        table_insert_max<kHashSlots>(t_node, t_key, e.node, e.key);
+    __syncthreads();
+    for (int sidx = threadIdx.x; sidx < kHashSlots; sidx += kScatterThreads)
         if (t_node[sidx] >= 0)
             atomicMax(a.key + t_node[sidx], t_key[sidx]);
 }
 
-__device__ inline void nbr_lookup_wave(const StepArgs &a, int K, int q)
-{
-    const int lane = lane_id();
-    const int role = q / a.count;
-    const int b = q - role * a.count;
-    const int64_t eid = a.first_eid + b;
-    const int32_t u = role == 0 ? a.src[eid] : (role == 1 ? a.dst[eid] : a.neg[b]);
-    const double t = a.ts[eid];
-    int64_t lo = 0, hi = 0;
-    if (u >= 0 && (int64_t)u < a.num_nodes) {
-        lo = a.indptr[u];
-        hi = a.indptr[u + 1];
-    }
-    const int64_t base = lo;
-    // invariant: entries below lo have time < t; entries at or above hi have time >= t
-    while (hi - lo > kWave) {
-        const int64_t step = (hi - lo + kWave - 1) / kWave;
-        int64_t idx = lo + (int64_t)(lane + 1) * step - 1;
-        if (idx > hi - 1)
-            idx = hi - 1;
-        const bool less = a.csr[idx].ts < t;
-        const int c = __popcll(__ballot(less));  // lists are time-ordered: lanes 0..c-1 are true
-        int64_t nlo = lo + (int64_t)c * step;
-        if (nlo > hi)
-            nlo = hi;
-        if (c < kWave) {
-            int64_t nhi = lo + (int64_t)(c + 1) * step - 1;
-            if (nhi > hi - 1)
-                nhi = hi - 1;
-            hi = nhi;
-        }
-        lo = nlo;
-    }
-    {
-        const int64_t idx = lo + lane;
-        const bool less = idx < hi && a.csr[idx].ts < t;
-        lo += __popcll(__ballot(less));
-    }
-    const int64_t avail = lo - base;
-    if (lane < K) {
-        const int64_t p = lo - 1 - lane;
-        const size_t o = (size_t)q * K + lane;
-        if (p >= base) {
-            const CsrEntry e = a.csr[p];
-            a.nbr_node[o] = e.nbr;
-            a.nbr_eid[o] = e.eid;
-            a.nbr_ts[o] = e.ts;
-        } else {
-            a.nbr_node[o] = -1;
-            a.nbr_eid[o] = -1;
-            a.nbr_ts[o] = 0.0;
-        }
-    }
-    if (lane == 0)
-        a.nbr_cnt[q] = (int32_t)(avail < K ? avail : K);
-}
-
-__global__ void __launch_bounds__(256) k_pre(StepArgs a, int K, int n_scatter)
-{
-    if ((int)blockIdx.x < n_scatter) {
-        scatter_keys_block(a, blockIdx.x);
-    } else {
-        const int q = ((int)blockIdx.x - n_scatter) * (256 / kWave) + wave_id();
-        if (q < a.roles * a.count)
-            nbr_lookup_wave(a, K, q);
-    }
-}
-
-// ------------------------------------------------------------------------------------------
-// Last-message aggregation, part 2: an entry supplies its node's message iff the node's key is
-// the entry's own.  Winners are compacted into win_list (order irrelevant: rows are independent).
+// Larger batches, part 2: an entry supplies its node's message iff the node's key is the entry's
+// own.  Winners are compacted
+// through an atomic counter; their order is irrelevant (rows are independent).
 __global__ void __launch_bounds__(256) k_select(StepArgs a)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     bool win = false;
+    Entry e;
+    e.node = 0;
+    e.other = 0;
+    e.t = 0.0;
+    e.key = 0ull;
     if (i < 2 * a.count) {
-        const int64_t eid = a.first_eid + (i >> 1);
-        const int role = i & 1;
-        const int32_t node = role ? a.dst[eid] : a.src[eid];
-        win = a.key[node] == winner_key(a.ts[eid], (int32_t)eid, role);
+        e = load_entry(a, i);
+        win = a.key[e.node] == e.key;
         if (a.is_winner)
             a.is_winner[i] = win ? 1 : 0;
     }
@@ -168,27 +267,33 @@ __global__ void __launch_bounds__(256) k_select(StepArgs a)
     if (lane == 0)
         base = atomicAdd(a.n_win, __popcll(mask));
     base = __shfl(base, 0, kWave);
-    if (win)
-        a.win_list[base + __popcll(mask & ((1ull << lane) - 1ull))] = i;
+    if (win) {
+        WinDesc d;
+        d.entry = i;
+        d.node = e.node;
+        d.other = e.other;
+        d.b = i >> 1;
+        d.dt = e.t - a.lu[e.node];
+        d.t = e.t;
+        a.win[base + __popcll(mask & ((1ull << lane) - 1ull))] = d;
+    }
 }
 
-// ------------------------------------------------------------------------------------------
 // Memory overwrite M <- s_i(t) for the winners (after every message has read the batch-start
 // memory), last_update, and key clear.  One wavefront per winner.
-__global__ void __launch_bounds__(256) k_commit(StepArgs a, int M)
+__global__ void __launch_bounds__(256) k_commit(StepArgs a, int M, int clear_keys)
 {
     const int r = blockIdx.x * (blockDim.x / kWave) + wave_id();
+    const WinDesc d = a.win[r];  // r < 2*count: in range; read together with the count
     if (r >= *a.n_win)
         return;
     const int lane = lane_id();
-    const int i = a.win_list[r];
-    const int64_t eid = a.first_eid + (i >> 1);
-    const int32_t node = (i & 1) ? a.dst[eid] : a.src[eid];
     for (int j = lane; j < M; j += kWave)
-        a.mem[(size_t)node * M + j] = a.staging[(size_t)i * M + j];
+        a.mem[(size_t)d.node * M + j] = a.staging[(size_t)d.entry * M + j];
     if (lane == 0) {
-        a.lu[node] = a.ts[eid];
-        a.key[node] = 0ull;
+        a.lu[d.node] = d.t;
+        if (clear_keys)
+            a.key[d.node] = 0ull;
     }
 }
 
@@ -213,12 +318,22 @@ hipError_t launch_fill_zero(void *ptr, size_t bytes, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_pre(const StepArgs &a, int K, hipStream_t s)
+hipError_t prepare_small()
+{
+    return hipFuncSetAttribute((const void *)k_winners, hipFuncAttributeMaxDynamicSharedMemorySize, kOneLds);
+}
+
+bool winners_in_one_launch(int count) { return 2 * count <= kOneMaxEntries; }
+
+hipError_t launch_scatter(const StepArgs &a, hipStream_t s, bool *needs_select)
 {
     const int entries = 2 * a.count;
-    const int Q = a.roles * a.count;
-    const int n_scatter = (entries + kScatterEntries - 1) / kScatterEntries;
-    hipLaunchKernelGGL(k_pre, dim3(n_scatter + (Q + 3) / 4), dim3(256), 0, s, a, K, n_scatter);
+    *needs_select = !winners_in_one_launch(a.count);
+    if (!*needs_select)
+        hipLaunchKernelGGL(k_winners, dim3(1), dim3(kScatterThreads), kOneLds, s, a);
+    else
+        hipLaunchKernelGGL(k_scatter, dim3((entries + kScatterThreads - 1) / kScatterThreads),
+                           dim3(kScatterThreads), 0, s, a);
     return hipGetLastError();
 }
 
@@ -230,7 +345,8 @@ hipError_t launch_select(const StepArgs &a, hipStream_t s)
 
 hipError_t launch_commit(const StepArgs &a, int M, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_commit, dim3((2 * a.count + 3) / 4), dim3(256), 0, s, a, M);
+    const int clear_keys = winners_in_one_launch(a.count) ? 0 : 1;
+    hipLaunchKernelGGL(k_commit, dim3((2 * a.count + 3) / 4), dim3(256), 0, s, a, M, clear_keys);
     return hipGetLastError();
 }
 

@@ -29,7 +29,9 @@ struct tig_ctx {
     int32_t *nbr_node, *nbr_eid, *nbr_cnt;
     double *nbr_ts;
     float *staging;
-    int32_t *win_list, *n_win;
+    WinDesc *win;
+    int32_t *n_win;
+    int32_t *pos;
     hipEvent_t marks[kNumStepKernels + 1];
     bool have_marks;
     char err[256];
@@ -108,6 +110,7 @@ struct PersistentLayout {
     float *edge_feat;
     int64_t *indptr;
     CsrEntry *csr;
+    int32_t *pos;
     float *mem;
     double *lu;
     unsigned long long *key;
@@ -125,6 +128,7 @@ PersistentLayout persistent_layout(const Dims &d, int64_t N, int64_t E, void *ba
     L.edge_feat = c.take<float>((size_t)E * d.F);
     L.indptr = c.take<int64_t>((size_t)N + 1);
     L.csr = c.take<CsrEntry>((size_t)2 * E);
+    L.pos = c.take<int32_t>((size_t)2 * E);
     L.mem = c.take<float>((size_t)N * d.M);
     L.lu = c.take<double>((size_t)N);
     L.key = c.take<unsigned long long>((size_t)N);
@@ -137,7 +141,8 @@ struct StepScratch {
     int32_t *nbr_node, *nbr_eid, *nbr_cnt;
     double *nbr_ts;
     float *staging;
-    int32_t *win_list, *n_win;
+    WinDesc *win;
+    int32_t *n_win;
     size_t bytes;
 };
 
@@ -151,7 +156,7 @@ StepScratch step_scratch(const Dims &d, void *base)
     S.nbr_ts = c.take<double>(Q * d.K);
     S.nbr_cnt = c.take<int32_t>(Q);
     S.staging = c.take<float>((size_t)2 * d.max_batch * d.M);
-    S.win_list = c.take<int32_t>((size_t)2 * d.max_batch);
+    S.win = c.take<WinDesc>((size_t)2 * d.max_batch);
     S.n_win = c.take<int32_t>(1);
     S.bytes = c.off;
     return S;
@@ -318,6 +323,7 @@ int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *w
     ctx->edge_feat = L.edge_feat;
     ctx->indptr = L.indptr;
     ctx->csr = L.csr;
+    ctx->pos = L.pos;
     ctx->mem = L.mem;
     ctx->lu = L.lu;
     ctx->key = L.key;
@@ -355,7 +361,7 @@ int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *w
     }
 
     // temporal adjacency
-    INIT_TRY(csr_build(L.src, L.dst, L.ts, E, N, L.indptr, L.csr, scratch, scratch_bytes, s), "adjacency build");
+    INIT_TRY(csr_build(L.src, L.dst, L.ts, E, N, L.indptr, L.csr, L.pos, scratch, scratch_bytes, s), "adjacency build");
 
     // state after a reset
     INIT_TRY(launch_fill_zero(L.mem, sizeof(float) * (size_t)N * d.M, s), "zero memory");
@@ -370,8 +376,17 @@ int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *w
     ctx->nbr_ts = S.nbr_ts;
     ctx->nbr_cnt = S.nbr_cnt;
     ctx->staging = S.staging;
-    ctx->win_list = S.win_list;
+    ctx->win = S.win;
     ctx->n_win = S.n_win;
+    {
+        const hipError_t e = launch_fill_zero(S.n_win, 256, s);
+        const hipError_t e2 = e == hipSuccess ? hipStreamSynchronize(s) : e;
+        if (e2 != hipSuccess) {
+            snprintf(g_init_err, sizeof(g_init_err), "clear counters: %s", hipGetErrorString(e2));
+            delete ctx;
+            return TIG_EHIP;
+        }
+    }
     *out = ctx;
     return TIG_OK;
 }
@@ -409,8 +424,9 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     a.nbr_ts = out->nbr_ts ? out->nbr_ts : ctx->nbr_ts;
     a.nbr_cnt = out->nbr_cnt ? out->nbr_cnt : ctx->nbr_cnt;
     a.staging = ctx->staging;
-    a.win_list = ctx->win_list;
+    a.win = ctx->win;
     a.n_win = ctx->n_win;
+    a.pos = ctx->pos;
     a.is_winner = out->is_winner;
     a.emb = out->emb;
     a.score_pos = out->score_pos;

@@ -56,6 +56,16 @@ struct PackedWeights {
     const float *dec_b2;                       // [1]
 };
 
+// One winner of the last-message aggregation: everything the GRU and the memory overwrite need.
+struct __attribute__((aligned(16))) WinDesc {
+    int32_t entry;  // 2*b + role within the batch
+    int32_t node;   // the node whose memory is updated
+    int32_t other;  // the partner of the event
+    int32_t b;      // event position in the batch
+    double dt;      // t - last_update[node] at batch start
+    double t;       // event time
+};
+
 struct StepArgs {
     // graph (device)
     const int32_t *src, *dst;
@@ -63,6 +73,7 @@ struct StepArgs {
     const float *edge_feat;
     const int64_t *indptr;
     const CsrEntry *csr;
+    const int32_t *pos;  // [2E] adjacency position of entry 2*eid + role (in its node's list)
     int64_t num_nodes;
     // state (device)
     float *mem;
@@ -77,7 +88,7 @@ struct StepArgs {
     int32_t *nbr_node, *nbr_eid, *nbr_cnt;
     double *nbr_ts;
     float *staging;  // [2*count x M] new memory rows of the winners, by entry 2b+role
-    int32_t *win_list;  // [2*count] entries that supply their node's message (compacted)
+    WinDesc *win;       // [2*count] entries that supply their node's message (compacted)
     int32_t *n_win;     // [1] their number
     uint8_t *is_winner;  // may be NULL
     // outputs
@@ -98,7 +109,7 @@ hipError_t launch_validate_graph(const int32_t *src, const int32_t *dst, const d
                                  hipStream_t s);
 size_t csr_build_scratch_bytes(int64_t num_events, int64_t num_nodes);
 hipError_t csr_build(const int32_t *src, const int32_t *dst, const double *ts, int64_t num_events,
-                     int64_t num_nodes, int64_t *indptr, CsrEntry *csr, void *scratch,
+                     int64_t num_nodes, int64_t *indptr, CsrEntry *csr, int32_t *pos, void *scratch,
                      size_t scratch_bytes, hipStream_t s);
 
 size_t pack_scratch_bytes(const Dims &d);
@@ -112,8 +123,11 @@ int gru_lds_bytes(const Dims &d, int mt);
 int embed_lds_bytes(const Dims &d, int mt);
 hipError_t prepare_gru(const Dims &d, const LaunchPlan &plan);
 hipError_t prepare_embed(const Dims &d, const LaunchPlan &plan);
-hipError_t launch_pre(const StepArgs &a, int K, hipStream_t s);
+hipError_t prepare_small();
+// winners of the batch in one launch when it is small enough; otherwise scatter + *needs_select
+hipError_t launch_scatter(const StepArgs &a, hipStream_t s, bool *needs_select);
 hipError_t launch_select(const StepArgs &a, hipStream_t s);
+// GRU tiles and, in the same launch, the neighbour lookup of every query
 hipError_t launch_gru(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
                       hipStream_t s);
 hipError_t launch_commit(const StepArgs &a, int M, hipStream_t s);

@@ -200,7 +200,7 @@ class TigContext:
                     _addr(out.is_winner))
         self._check(self.lib.tig_step(self.handle, ctypes.byref(b), ctypes.byref(o)))
 
-    KERNEL_NAMES = ("k_pre", "k_select", "k_gru", "k_commit", "k_embed")
+    KERNEL_NAMES = ("k_scatter", "k_select", "k_gru", "k_commit", "k_embed")
 
     def step_profiled(self, first_eid: int, count: int, neg_dst, out: StepOutputs):
         """One step with HIP events around every kernel; returns the five durations in ms."""

@@ -148,6 +148,12 @@ def test_c3_windows(c3, precision, batch):
         run(c3, precision, bs, locked=False, warm_at=first)
 
 
+def test_c3_batch_above_the_fused_selection_limit(c3):
+    # more than 4096 events per batch: the winner selection runs as a launch of its own
+    first, bs = window(c3.w, 0.5, 1, 5000)
+    run(c3, "fp32", bs, locked=False, warm_at=first)
+
+
 # ------------------------------------------------------------------------------------- C4
 
 
