@@ -213,7 +213,7 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                     const int k = c0 + kk;
 #pragma unroll
                     for (int h = 0; h < H; ++h)
-                        sc[kk][h] = -INFINITY;
+                        sc[kk][h] = 0.0f;
                     if (k < cnt) {  // wave-uniform
                         const double dt = __shfl(nb_dt[i], k & 63, kWave);
 #pragma unroll
@@ -231,10 +231,50 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
 #pragma unroll
                             for (int n = 0; n < NPL; ++n)
                                 part += qv[h][n] * raw[kk][n];
-                            sc[kk][h] = wave_sum_uniform(part);
+                            sc[kk][h] = part;  // this lane's share; summed over the wavefront below
                         }
                     }
                 }
+                // wavefront sums of all partial scores of the chunk, one DPP step at a time across
+                // every value: consecutive instructions are independent, so no step waits on the
+                // previous one (see wave_sum_uniform for the step sequence)
+#pragma unroll
+                for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+                    for (int h = 0; h < H; ++h)
+                        sc[kk][h] += dpp_or_zero<0x111, 0xf, 0xf>(sc[kk][h]);
+#pragma unroll
+                for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+                    for (int h = 0; h < H; ++h)
+                        sc[kk][h] += dpp_or_zero<0x112, 0xf, 0xf>(sc[kk][h]);
+#pragma unroll
+                for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+                    for (int h = 0; h < H; ++h)
+                        sc[kk][h] += dpp_or_zero<0x114, 0xf, 0xf>(sc[kk][h]);
+#pragma unroll
+                for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+                    for (int h = 0; h < H; ++h)
+                        sc[kk][h] += dpp_or_zero<0x118, 0xf, 0xf>(sc[kk][h]);
+#pragma unroll
+                for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+                    for (int h = 0; h < H; ++h)
+                        sc[kk][h] += dpp_or_zero<0x142, 0xa, 0xf>(sc[kk][h]);
+#pragma unroll
+                for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+                    for (int h = 0; h < H; ++h)
+                        sc[kk][h] += dpp_or_zero<0x143, 0xc, 0xf>(sc[kk][h]);
+#pragma unroll
+                for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+                    for (int h = 0; h < H; ++h) {
+                        const float tot = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sc[kk][h]), 63));
+                        sc[kk][h] = c0 + kk < cnt ? tot : -INFINITY;
+                    }
                 // softmax across the chunk, merged with earlier chunks by rescaling
 #pragma unroll
                 for (int h = 0; h < H; ++h) {
