@@ -16,6 +16,7 @@
 #include <hip/hip_runtime.h>
 
 #include "kernels_common.h"
+#include "winners.h"
 
 namespace tig {
 
@@ -45,6 +46,7 @@ struct EmbedParams {
     int ld1;        // row stride of the E-wide buffers, bytes
     int off_h1, off_meta;  // byte offsets in LDS
     int dec_off;    // byte offset of the decoder pre-activations (inside the main buffer)
+    int n_tiles;    // workgroups that own query rows; one more selects the next batch's winners
 };
 
 template <int PREC, int MT, int NPL, int H>
@@ -59,6 +61,13 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     constexpr int KC = NPL >= 8 ? 5 : (NPL == 4 ? 10 : 16);      // neighbour rows in flight
     constexpr int NPHI = NPL;  // registers that may hold time-encoding dims (T <= 64 * NPL)
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    if ((int)blockIdx.x >= p.n_tiles) {
+        // The workgroup beyond the last tile: last-message selection for the batch expected to
+        // follow, on a compute unit this launch leaves idle (launched only with 1024 threads).
+        if constexpr (kEmbedThreads == kScatterThreads)
+            winners_block(winners_job(a, true), smem);
+        return;
+    }
     char *rowbuf = smem;
     char *h1buf = smem + p.off_h1;
     int *row_q = (int *)(smem + p.off_meta);  // [ROWS] query index or -1
@@ -544,8 +553,18 @@ int embed_lds_bytes(const Dims &d, int mt)
 
 hipError_t prepare_embed(const Dims &d, const LaunchPlan &plan)
 {
-    return hipFuncSetAttribute(embed_kernel(d, plan.emb_mt), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               plan.emb_lds);
+    const int lds = npl_for(d) < 8 && plan.emb_lds < kOneLds ? kOneLds : plan.emb_lds;
+    return hipFuncSetAttribute(embed_kernel(d, plan.emb_mt), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+}
+
+bool embed_can_select_ahead(const Dims &d, const LaunchPlan &plan, int roles, int count, int next_count,
+                            int num_cus)
+{
+    if (npl_for(d) >= 8 || next_count < 1 || 2 * next_count > kOneMaxEntries)
+        return false;
+    // every tile and the extra workgroup must start at once, each on a compute unit of its own
+    const EmbedParams p = embed_params(d, plan.emb_mt, roles);
+    return (count + p.TE - 1) / p.TE + 1 <= num_cus;
 }
 
 hipError_t launch_embed(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
@@ -554,11 +573,13 @@ hipError_t launch_embed(const Dims &d, const LaunchPlan &plan, const PackedWeigh
     StepArgs aa = a;
     PackedWeights ww = pw;
     EmbedParams p = embed_params(d, plan.emb_mt, a.roles);
+    p.n_tiles = (a.count + p.TE - 1) / p.TE;
     void *args[] = {&aa, &ww, &p};
-    const int grid = (a.count + p.TE - 1) / p.TE;
+    const bool ahead = a.next_count > 0;
     const int threads = npl_for(d) >= 8 ? EmbedShape<8>::kThreads : EmbedShape<1>::kThreads;
-    return hipLaunchKernel(embed_kernel(d, plan.emb_mt), dim3(grid), dim3(threads), args,
-                           (size_t)plan.emb_lds, s);
+    const int lds = ahead && plan.emb_lds < kOneLds ? kOneLds : plan.emb_lds;
+    return hipLaunchKernel(embed_kernel(d, plan.emb_mt), dim3(p.n_tiles + (ahead ? 1 : 0)), dim3(threads), args,
+                           (size_t)lds, s);
 }
 
 }  // namespace tig

@@ -5,7 +5,7 @@
 // so they hide each other's latency.
 //
 // One workgroup (16 wavefronts) takes 16*MT winners:
-//   1  row descriptors: node, partner, event, dt = t - last_update[node]
+//   1  row descriptors: node, partner, event, event time (dt = t - last_update[node] in step 2)
 //   2  message rows [s_self | s_other | Phi(dt) | e] gathered from the batch-START memory into an
 //      LDS tile (every element of every row is an independent load: one round of latency)
 //   3  gate pre-activations on the matrix cores.  Per 16-column tile two wavefronts work side by
@@ -84,7 +84,7 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int n_gru_blocks, int K)
     int *row_u = row_i + EC;                   // [EC] node
     int *row_o = row_u + EC;                   // [EC] partner
     int *row_e = row_o + EC;                   // [EC] event id - first_eid
-    double *row_dt = (double *)(row_e + EC);   // [EC]
+    double *row_t = (double *)(row_e + EC);    // [EC] event time
     char *X = smem + EC * 24;                  // [EC rows x ldx bytes]
     float *rz = (float *)(smem + g.off_rz);    // [EC][Ng][2]
 
@@ -104,19 +104,19 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int n_gru_blocks, int K)
     if (threadIdx.x < EC) {
         const int r = threadIdx.x;
         int i = 0, u = 0, o = 0, b = 0;
-        double dt = 0.0;
+        double t = 0.0;
         if (r < n_rows) {
             i = d0.entry;
             u = d0.node;
             o = d0.other;
             b = d0.b;
-            dt = d0.dt;
+            t = d0.t;
         }
         row_i[r] = i;
         row_u[r] = u;
         row_o[r] = o;
         row_e[r] = b;
-        row_dt[r] = dt;
+        row_t[r] = t;
     }
     __syncthreads();
 
@@ -131,7 +131,8 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int n_gru_blocks, int K)
             else if (j < 2 * g.M)
                 v = a.mem[(size_t)row_o[r] * g.M + (j - g.M)];
             else if (j < 2 * g.M + g.T)
-                v = time_enc(w.time_w_rev[j - 2 * g.M], w.time_b_rev[j - 2 * g.M], row_dt[r]);
+                v = time_enc(w.time_w_rev[j - 2 * g.M], w.time_b_rev[j - 2 * g.M],
+                             row_t[r] - a.lu[row_u[r]]);  // dt since the node's last update
             else if (j < g.Dmsg)
                 v = a.edge_feat[(size_t)(a.first_eid + row_e[r]) * g.F + (j - 2 * g.M - g.T)];
         }

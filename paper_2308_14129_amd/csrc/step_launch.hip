@@ -41,7 +41,7 @@ hipError_t prepare_kernels(const Dims &d, const LaunchPlan &plan)
 }
 
 hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw,
-                       const StepArgs &a, hipStream_t s, hipEvent_t *marks)
+                       const StepArgs &a, hipStream_t s, hipEvent_t *marks, bool winners_ready)
 {
     hipError_t e;
     int mark = 0;
@@ -50,7 +50,9 @@ hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeight
     if ((e = stamp()) != hipSuccess)
         return e;
     bool needs_select = false;
-    if ((e = launch_scatter(a, s, &needs_select)) != hipSuccess || (e = stamp()) != hipSuccess)
+    if (!winners_ready && (e = launch_scatter(a, s, &needs_select)) != hipSuccess)
+        return e;
+    if ((e = stamp()) != hipSuccess)
         return e;
     if (needs_select && (e = launch_select(a, s)) != hipSuccess)
         return e;

@@ -12,203 +12,18 @@
 #include <hip/hip_runtime.h>
 
 #include "kernels_common.h"
+#include "winners.h"
 
 namespace tig {
 
-#ifdef TIG_PHASE_CLOCKS
-static __device__ unsigned long long g_phase_clocks[8192 * 8];
-extern "C" __attribute__((visibility("default"))) int tig_debug_phase_clocks_small(unsigned long long *out, int n)
-{
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase_clocks), sizeof(unsigned long long) * (size_t)n);
-}
-#endif
-
 namespace {
 
-constexpr int kScatterThreads = 1024;  // one (event, role) entry per thread and iteration
-constexpr int kScatterWaves = kScatterThreads / kWave;
 constexpr int kHashSlots = 2048;       // k_scatter: power of two, 2 x entries per workgroup
-constexpr int kOneIters = 8;           // k_winners: up to 8 entries per thread
-constexpr int kOneMaxEntries = kOneIters * kScatterThreads;
-constexpr int kOneSlots = 12288;       // k_winners: 1.5 x the most distinct nodes, never fills up
-constexpr int kOneLds = kOneSlots * 12 + (kOneIters * kScatterWaves + 1) * 4;
 
-struct Entry {
-    int32_t node, other;
-    double t;
-    unsigned long long key;
-};
-
-__device__ inline Entry load_entry(const StepArgs &a, int i)
-{
-    Entry e;
-    const int64_t eid = a.first_eid + (i >> 1);
-    const int role = i & 1;
-    const int32_t s = a.src[eid], d = a.dst[eid];
-    e.node = role ? d : s;
-    e.other = role ? s : d;
-    e.t = a.ts[eid];
-    e.key = winner_key(e.t, (int32_t)eid, role);
-    return e;
-}
-
-// Among the active lanes of the wavefront, true for the one lane per distinct node that holds
-// that node's greatest key.  Keys grow with the entry index (time-sorted events), and entries
-// grow with the lane, so that is the highest lane of each group.
-// Only the first kRounds distinct nodes of the wavefront are merged this way (heavy hitters show
-// up early); lanes of any other node all answer true and meet in the hash table instead.
-__device__ inline bool wave_leader_of_node(bool active, int32_t node)
-{
-    constexpr int kRounds = 4;
-    const int lane = lane_id();
-    unsigned long long todo = __ballot(active);
-    bool leader = active;
-#pragma unroll
-    for (int round = 0; round < kRounds; ++round) {
-        if (todo == 0ull)
-            break;
-        const int first = __ffsll((long long)todo) - 1;
-        const int32_t n0 = __builtin_amdgcn_readlane(node, first);
-        const bool mine = active && node == n0;
-        const unsigned long long grp = __ballot(mine);
-        if (mine)
-            leader = lane == 63 - __clzll((long long)grp);
-        todo &= ~grp;
-    }
-    return leader;
-}
-
-template <int SLOTS>
-__device__ inline uint32_t hash_slot(int32_t node)
-{
-    return (uint32_t)(((uint32_t)node * 2654435761u) >> 8) % (uint32_t)SLOTS;
-}
-
-// insert (node, key) with max-merge into an open-addressing LDS table that is never full
-template <int SLOTS>
-__device__ inline void table_insert_max(int32_t *t_node, unsigned long long *t_key, int32_t node,
-                                        unsigned long long key)
-{
-    uint32_t h = hash_slot<SLOTS>(node);
-    while (true) {
-        const int32_t prev = atomicCAS(&t_node[h], -1, node);
-        if (prev == -1 || prev == node) {
-            atomicMax(&t_key[h], key);
-            return;
-        }
-        h = h + 1 == (uint32_t)SLOTS ? 0u : h + 1;
-    }
-}
-
-__global__ void __launch_bounds__(kScatterThreads) k_winners(StepArgs a)
+__global__ void __launch_bounds__(kScatterThreads) k_winners(WinnersJob j)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    unsigned long long *t_key = (unsigned long long *)smem;   // [kOneSlots]
-    int32_t *t_node = (int32_t *)(smem + kOneSlots * 8);      // [kOneSlots]
-    int *s_cnt = (int *)(smem + kOneSlots * 12);              // [kOneIters * waves + 1]
-    const int lane = lane_id();
-    const int wave = wave_id();
-    const int n_entries = 2 * a.count;
-
-    TIG_MARK(0);
-    for (int sidx = threadIdx.x; sidx < kOneSlots; sidx += kScatterThreads) {
-        t_node[sidx] = -1;
-        t_key[sidx] = 0ull;
-    }
-    TIG_MARK(1);
-    // the thread owns entries it*1024 + tid; all of their loads are issued together
-    Entry ent[kOneIters];
-#pragma unroll
-    for (int it = 0; it < kOneIters; ++it) {
-        const int i = it * kScatterThreads + threadIdx.x;
-        ent[it].node = -1;
-        ent[it].other = 0;
-        ent[it].t = 0.0;
-        ent[it].key = 0ull;
-        if (i < n_entries)
-            ent[it] = load_entry(a, i);
-    }
-    __syncthreads();
-    TIG_MARK(2);
-#pragma unroll
-    for (int it = 0; it < kOneIters; ++it) {
-        if (it * kScatterThreads < n_entries) {  // uniform
-            const bool active = it * kScatterThreads + threadIdx.x < n_entries;
-            if (wave_leader_of_node(active, ent[it].node))
-                table_insert_max<kOneSlots>(t_node, t_key, ent[it].node, ent[it].key);
-        }
-    }
-    __syncthreads();
-    TIG_MARK(3);
-    // an entry supplies its node's message iff the node's key is the entry's own
-    bool win[kOneIters];
-    double lu[kOneIters];
-#pragma unroll
-    for (int it = 0; it < kOneIters; ++it) {
-        win[it] = false;
-        lu[it] = 0.0;
-        if (it * kScatterThreads + threadIdx.x < n_entries) {
-            uint32_t h = hash_slot<kOneSlots>(ent[it].node);
-            while (t_node[h] != ent[it].node)
-                h = h + 1 == (uint32_t)kOneSlots ? 0u : h + 1;
-            win[it] = t_key[h] == ent[it].key;
-            if (win[it])
-                lu[it] = a.lu[ent[it].node];
-        }
-    }
-    TIG_MARK(4);
-    // ordered compaction: counts per (iteration, wavefront), exclusive prefix, then the writes
-    int rank[kOneIters];
-#pragma unroll
-    for (int it = 0; it < kOneIters; ++it) {
-        const unsigned long long m = __ballot(win[it]);
-        rank[it] = __popcll(m & ((1ull << lane) - 1ull));
-        if (lane == 0)
-            s_cnt[it * kScatterWaves + wave] = __popcll(m);
-    }
-    __syncthreads();
-    if (wave == 0) {
-        constexpr int kPer = kOneIters * kScatterWaves / kWave;  // counts per lane
-        int c[kPer], sum = 0;
-#pragma unroll
-        for (int j = 0; j < kPer; ++j) {
-            c[j] = s_cnt[lane * kPer + j];
-            sum += c[j];
-        }
-        int incl = sum;
-#pragma unroll
-        for (int off = 1; off < kWave; off <<= 1) {
-            const int up = __shfl_up(incl, off, kWave);
-            if (lane >= off)
-                incl += up;
-        }
-        int run = incl - sum;
-#pragma unroll
-        for (int j = 0; j < kPer; ++j) {
-            s_cnt[lane * kPer + j] = run;
-            run += c[j];
-        }
-        if (lane == kWave - 1)
-            *a.n_win = incl;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int it = 0; it < kOneIters; ++it) {
-        const int i = it * kScatterThreads + threadIdx.x;
-        if (i < n_entries && a.is_winner)
-            a.is_winner[i] = win[it] ? 1 : 0;
-        if (win[it]) {
-            WinDesc d;
-            d.entry = i;
-            d.node = ent[it].node;
-            d.other = ent[it].other;
-            d.b = i >> 1;
-            d.dt = ent[it].t - lu[it];
-            d.t = ent[it].t;
-            a.win[s_cnt[it * kScatterWaves + wave] + rank[it]] = d;
-        }
-    }
-    TIG_MARK(5);
+    winners_block(j, smem);
 }
 
 // Larger batches, part 1: keys to the per-node array in memory.  Lanes of a wavefront that hit
@@ -232,7 +47,7 @@ __global__ void __launch_bounds__(kScatterThreads) k_scatter(StepArgs a)
     e.node = -1;
     e.key = 0ull;
     if (active)
-        e = load_entry(a, i);
+        e = load_entry(a.src, a.dst, a.ts, a.first_eid, i);
     if (wave_leader_of_node(active, e.node))
         table_insert_max<kHashSlots>(t_node, t_key, e.node, e.key);
     __syncthreads();
@@ -254,7 +69,7 @@ __global__ void __launch_bounds__(256) k_select(StepArgs a)
     e.t = 0.0;
     e.key = 0ull;
     if (i < 2 * a.count) {
-        e = load_entry(a, i);
+        e = load_entry(a.src, a.dst, a.ts, a.first_eid, i);
         win = a.key[e.node] == e.key;
         if (a.is_winner)
             a.is_winner[i] = win ? 1 : 0;
@@ -273,7 +88,6 @@ __global__ void __launch_bounds__(256) k_select(StepArgs a)
         d.node = e.node;
         d.other = e.other;
         d.b = i >> 1;
-        d.dt = e.t - a.lu[e.node];
         d.t = e.t;
         a.win[base + __popcll(mask & ((1ull << lane) - 1ull))] = d;
     }
@@ -330,7 +144,7 @@ hipError_t launch_scatter(const StepArgs &a, hipStream_t s, bool *needs_select)
     const int entries = 2 * a.count;
     *needs_select = !winners_in_one_launch(a.count);
     if (!*needs_select)
-        hipLaunchKernelGGL(k_winners, dim3(1), dim3(kScatterThreads), kOneLds, s, a);
+        hipLaunchKernelGGL(k_winners, dim3(1), dim3(kScatterThreads), kOneLds, s, winners_job(a, false));
     else
         hipLaunchKernelGGL(k_scatter, dim3((entries + kScatterThreads - 1) / kScatterThreads),
                            dim3(kScatterThreads), 0, s, a);

@@ -29,8 +29,13 @@ struct tig_ctx {
     int32_t *nbr_node, *nbr_eid, *nbr_cnt;
     double *nbr_ts;
     float *staging;
-    WinDesc *win;
-    int32_t *n_win;
+    WinDesc *win[2];   // winner lists: this step's, and the one selected ahead for the next
+    int32_t *n_win[2];
+    int cur;           // list used by the last step
+    bool ahead_valid;  // win[cur ^ 1] holds the winners of batch (ahead_first, ahead_count)
+    int64_t ahead_first;
+    int32_t ahead_count;
+    int num_cus;
     int32_t *pos;
     hipEvent_t marks[kNumStepKernels + 1];
     bool have_marks;
@@ -141,8 +146,8 @@ struct StepScratch {
     int32_t *nbr_node, *nbr_eid, *nbr_cnt;
     double *nbr_ts;
     float *staging;
-    WinDesc *win;
-    int32_t *n_win;
+    WinDesc *win[2];
+    int32_t *n_win[2];
     size_t bytes;
 };
 
@@ -156,8 +161,10 @@ StepScratch step_scratch(const Dims &d, void *base)
     S.nbr_ts = c.take<double>(Q * d.K);
     S.nbr_cnt = c.take<int32_t>(Q);
     S.staging = c.take<float>((size_t)2 * d.max_batch * d.M);
-    S.win = c.take<WinDesc>((size_t)2 * d.max_batch);
-    S.n_win = c.take<int32_t>(1);
+    for (int i = 0; i < 2; ++i) {
+        S.win[i] = c.take<WinDesc>((size_t)2 * d.max_batch);
+        S.n_win[i] = c.take<int32_t>(1);
+    }
     S.bytes = c.off;
     return S;
 }
@@ -315,6 +322,11 @@ int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *w
         return TIG_EINVAL;
     }
     INIT_TRY(prepare_kernels(d, ctx->plan), "hipFuncSetAttribute");
+    {
+        int dev = 0;
+        INIT_TRY(hipGetDevice(&dev), "hipGetDevice");
+        INIT_TRY(hipDeviceGetAttribute(&ctx->num_cus, hipDeviceAttributeMultiprocessorCount, dev), "compute unit count");
+    }
 
     const PersistentLayout L = persistent_layout(d, N, E, persistent);
     ctx->src = L.src;
@@ -376,10 +388,16 @@ int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *w
     ctx->nbr_ts = S.nbr_ts;
     ctx->nbr_cnt = S.nbr_cnt;
     ctx->staging = S.staging;
-    ctx->win = S.win;
-    ctx->n_win = S.n_win;
+    for (int i = 0; i < 2; ++i) {
+        ctx->win[i] = S.win[i];
+        ctx->n_win[i] = S.n_win[i];
+    }
+    ctx->cur = 0;
+    ctx->ahead_valid = false;
     {
-        const hipError_t e = launch_fill_zero(S.n_win, 256, s);
+        hipError_t e = launch_fill_zero(S.n_win[0], 256, s);
+        if (e == hipSuccess)
+            e = launch_fill_zero(S.n_win[1], 256, s);
         const hipError_t e2 = e == hipSuccess ? hipStreamSynchronize(s) : e;
         if (e2 != hipSuccess) {
             snprintf(g_init_err, sizeof(g_init_err), "clear counters: %s", hipGetErrorString(e2));
@@ -424,16 +442,43 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     a.nbr_ts = out->nbr_ts ? out->nbr_ts : ctx->nbr_ts;
     a.nbr_cnt = out->nbr_cnt ? out->nbr_cnt : ctx->nbr_cnt;
     a.staging = ctx->staging;
-    a.win = ctx->win;
-    a.n_win = ctx->n_win;
     a.pos = ctx->pos;
     a.is_winner = out->is_winner;
     a.emb = out->emb;
     a.score_pos = out->score_pos;
     a.score_neg = out->score_neg;
-    const hipError_t e = launch_step(ctx->d, ctx->plan, ctx->pw, a, ctx->stream, marks);
+
+    // Winner list of this batch: selected ahead by the previous step's embedding launch if that
+    // step guessed this batch (the selection depends on the event stream only, so state changes
+    // in between do not matter).  A caller that asks for the per-entry flags gets a fresh run.
+    const bool ready = ctx->ahead_valid && ctx->ahead_first == batch->first_eid &&
+                       ctx->ahead_count == batch->count && !out->is_winner && !marks;
+    if (ready)
+        ctx->cur ^= 1;
+    a.win = ctx->win[ctx->cur];
+    a.n_win = ctx->n_win[ctx->cur];
+    // Chronological training and evaluation pass consecutive batches of one size: guess that the
+    // next call continues where this one ends, and let the embedding launch select its winners.
+    // (The profiled step keeps every kernel to its own work.)
+    a.next_first_eid = batch->first_eid + batch->count;
+    a.next_count = 0;
+    a.next_win = ctx->win[ctx->cur ^ 1];
+    a.next_n_win = ctx->n_win[ctx->cur ^ 1];
+    if (!marks && a.next_first_eid < ctx->num_events) {
+        const int64_t left = ctx->num_events - a.next_first_eid;
+        const int32_t guess = left < batch->count ? (int32_t)left : batch->count;
+        if (embed_can_select_ahead(ctx->d, ctx->plan, a.roles, batch->count, guess, ctx->num_cus))
+            a.next_count = guess;
+    }
+    ctx->ahead_valid = false;
+    const hipError_t e = launch_step(ctx->d, ctx->plan, ctx->pw, a, ctx->stream, marks, ready);
     if (e != hipSuccess)
         return fail(ctx, TIG_EHIP, "tig_step launch", e);
+    if (a.next_count > 0) {
+        ctx->ahead_valid = true;
+        ctx->ahead_first = a.next_first_eid;
+        ctx->ahead_count = a.next_count;
+    }
     return TIG_OK;
 }
 

@@ -57,12 +57,11 @@ struct PackedWeights {
 };
 
 // One winner of the last-message aggregation: everything the GRU and the memory overwrite need.
-struct __attribute__((aligned(16))) WinDesc {
+struct __attribute__((aligned(8))) WinDesc {
     int32_t entry;  // 2*b + role within the batch
     int32_t node;   // the node whose memory is updated
     int32_t other;  // the partner of the event
     int32_t b;      // event position in the batch
-    double dt;      // t - last_update[node] at batch start
     double t;       // event time
 };
 
@@ -91,6 +90,12 @@ struct StepArgs {
     WinDesc *win;       // [2*count] entries that supply their node's message (compacted)
     int32_t *n_win;     // [1] their number
     uint8_t *is_winner;  // may be NULL
+    // the batch expected to follow (next_count 0: none): its winners are selected by one extra
+    // workgroup of this step's embedding launch
+    int64_t next_first_eid;
+    int32_t next_count;
+    WinDesc *next_win;
+    int32_t *next_n_win;
     // outputs
     float *emb, *score_pos, *score_neg;
 };
@@ -133,11 +138,16 @@ hipError_t launch_gru(const Dims &d, const LaunchPlan &plan, const PackedWeights
 hipError_t launch_commit(const StepArgs &a, int M, hipStream_t s);
 hipError_t launch_embed(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
                         hipStream_t s);
+// whether the embedding launch of a batch of `count` events can carry one more workgroup that
+// selects the winners of a following batch of `next_count` events without delaying anything
+bool embed_can_select_ahead(const Dims &d, const LaunchPlan &plan, int roles, int count, int next_count,
+                            int num_cus);
 hipError_t prepare_kernels(const Dims &d, const LaunchPlan &plan);
 constexpr int kNumStepKernels = 5;
 // `marks`: NULL, or kNumStepKernels + 1 events recorded before the first and after every kernel.
+// `winners_ready`: a.win / a.n_win already hold the winners of this batch.
 hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw,
-                       const StepArgs &a, hipStream_t s, hipEvent_t *marks);
+                       const StepArgs &a, hipStream_t s, hipEvent_t *marks, bool winners_ready);
 hipError_t launch_fill_zero(void *ptr, size_t bytes, hipStream_t s);
 
 }  // namespace tig

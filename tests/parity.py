@@ -24,12 +24,15 @@ def gate(got: np.ndarray, ref: np.ndarray, tol: float, name: str) -> float:
 
 
 def compare_step(ctx, out, ref, oracle_state, tol, check_state=True):
-    """Neighbour tables and winners bit-exact; embeddings, scores and state within `tol`."""
+    """Neighbour tables and winners bit-exact; embeddings, scores and state within `tol`.
+    Without the per-entry winner flags the winners are still pinned through last_update, which
+    must equal the oracle's bit for bit over all nodes."""
     np.testing.assert_array_equal(out.nbr_cnt.cpu().numpy(), ref["nbr_cnt"], err_msg="nbr_cnt")
     np.testing.assert_array_equal(out.nbr_node.cpu().numpy(), ref["nbr_node"], err_msg="nbr_node")
     np.testing.assert_array_equal(out.nbr_eid.cpu().numpy(), ref["nbr_eid"], err_msg="nbr_eid")
     np.testing.assert_array_equal(out.nbr_ts.cpu().numpy(), ref["nbr_ts"], err_msg="nbr_ts")
-    np.testing.assert_array_equal(out.is_winner.cpu().numpy(), ref["is_winner"], err_msg="is_winner")
+    if out.is_winner is not None:
+        np.testing.assert_array_equal(out.is_winner.cpu().numpy(), ref["is_winner"], err_msg="is_winner")
     res = {"emb": gate(out.emb.cpu().numpy(), ref["emb"], tol, "emb"),
            "score_pos": gate(out.score_pos.cpu().numpy(), ref["score_pos"], tol, "score_pos")}
     if ref["score_neg"] is not None:

@@ -43,6 +43,10 @@ def c5_ctx(c5):
 def test_c5_steps_match_oracle(c5, c5_ctx, precision):
     first, bs = window(c5.w, 0.5, 2)
     run(c5, precision, bs, locked=False, warm_at=first, ctx=c5_ctx(precision))
+    # as bench.py calls it: no winner flags, so the second and third step use the winners that
+    # the step before selected ahead
+    first, bs = window(c5.w, 0.7, 3)
+    run(c5, precision, bs, locked=False, warm_at=first, ctx=c5_ctx(precision), flags=False)
 
 
 def test_c5_sampled_queries_against_bruteforce_definition(c5, c5_ctx):

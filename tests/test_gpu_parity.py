@@ -34,10 +34,12 @@ class Bundle:
         self.ix = O.NeighbourIndex(self.g.num_nodes, self.g.src, self.g.dst, self.g.ts)
 
 
-def run(bundle, precision, batches, locked, warm_at=None, with_neg=True, ctx=None):
+def run(bundle, precision, batches, locked, warm_at=None, with_neg=True, ctx=None, flags=True):
     """Runs the batches on both sides.  locked=True loads the oracle's state into the GPU before
     every step (step-locked parity); otherwise both sides run freely from the same start, which
-    is the state after a reset or, with warm_at, the seeded warm state of a mid-stream window."""
+    is the state after a reset or, with warm_at, the seeded warm state of a mid-stream window.
+    flags=False leaves out the per-entry winner flags, as a training loop does: only then does a
+    step use the winners that the previous step's embedding launch selected ahead."""
     import torch
     w, g, W, ix = bundle.w, bundle.g, bundle.W, bundle.ix
     own = ctx is None
@@ -58,6 +60,8 @@ def run(bundle, precision, batches, locked, warm_at=None, with_neg=True, ctx=Non
         ref = O.step(st, g.src, g.dst, g.ts, g.edge_feat, W, first, count, neg, w.num_neighbors,
                      w.num_heads, index=ix)
         out = ctx.alloc_outputs(count, with_neg=with_neg, inspect=True)
+        if not flags:
+            out.is_winner = None
         ctx.step(first, count, torch.from_numpy(neg).to("cuda:0") if with_neg else None, out)
         torch.cuda.synchronize()
         res = compare_step(ctx, out, ref, st, TOL[precision])
@@ -104,6 +108,31 @@ def test_c1_single_event_batches(c1):
     run(c1, "fp32", [(e, 1) for e in range(3000, 3006)], locked=False, warm_at=3000)
 
 
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_c1_consecutive_batches_with_winners_selected_ahead(c1, precision):
+    # whole stream incl. the short last batch (10,000 = 73 * 136 + 72), free running and step-locked
+    bs = list(S.batches(c1.w.num_events, 136))
+    assert bs[-1][1] == 72
+    run(c1, precision, bs, locked=False, flags=False)
+    run(c1, "fp32", bs[:6], locked=True, flags=False)
+
+
+def test_c1_wrong_guesses_of_the_next_batch(c1):
+    # batches that do not continue the previous one: revisits, gaps, changing sizes, and a
+    # request for the flags in between; every step must still equal the oracle's
+    import torch
+    w, g, W = c1.w, c1.g, c1.W
+    ctx = make_ctx(w, g, W, "fp32", 300)
+    seq = [(0, 200), (200, 200), (200, 200), (400, 100), (500, 300), (1000, 300), (1300, 300),
+           (1600, 7), (1607, 7), (1614, 300), (0, 200), (200, 200)]
+    run(c1, "fp32", seq[:5], locked=True, ctx=ctx, flags=False)
+    run(c1, "fp32", seq[5:10], locked=True, ctx=ctx, flags=False)
+    run(c1, "fp32", seq[10:], locked=False, ctx=ctx, flags=False)   # reset in between
+    run(c1, "fp32", [(0, 200), (200, 200)], locked=False, ctx=ctx, flags=True)
+    run(c1, "fp32", [(400, 200), (600, 200)], locked=True, ctx=ctx, flags=False)
+    ctx.close()
+
+
 # ------------------------------------------------------------------------------------- C2
 
 
@@ -129,6 +158,7 @@ def test_c2_windows_and_last_short_batch_fp32(c2):
 def test_c2_window_bf16(c2):
     first, bs = window(c2.w, 0.5, 3)
     run(c2, "bf16", bs, locked=False, warm_at=first)
+    run(c2, "bf16", bs, locked=False, warm_at=first, flags=False)
 
 
 # ------------------------------------------------------------------------------------- C3
@@ -152,6 +182,10 @@ def test_c3_batch_above_the_fused_selection_limit(c3):
     # more than 4096 events per batch: the winner selection runs as a launch of its own
     first, bs = window(c3.w, 0.5, 1, 5000)
     run(c3, "fp32", bs, locked=False, warm_at=first)
+    # ... and is never done ahead; 4096 -> 5000 -> 3000 crosses the limit in both directions
+    first, bs = window(c3.w, 0.5, 1, 4096)
+    seq = bs + [(first + 4096, 5000), (first + 9096, 3000), (first + 12096, 3000)]
+    run(c3, "fp32", seq, locked=False, warm_at=first, flags=False)
 
 
 # ------------------------------------------------------------------------------------- C4
