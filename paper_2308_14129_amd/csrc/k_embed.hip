@@ -47,13 +47,51 @@ struct EmbedParams {
     int off_h1, off_meta;  // byte offsets in LDS
     int dec_off;    // byte offset of the decoder pre-activations (inside the main buffer)
     int n_tiles;    // workgroups that own query rows; one more selects the next batch's winners
+    // bit n set: register n of a key/value row (dims 64 n .. 64 n + 63 of [Phi | s_v | e]) holds
+    // at least one dim of the time encoding / of the neighbour's memory / of the edge feature
+    int phi_regs, mem_regs, feat_regs;
 };
 
-template <int PREC, int MT, int NPL, int H>
+// Key/value row shapes compiled in (0: taken from the launch parameters).  With a fixed shape
+// every "which register holds which segment" decision of phase C is made by the compiler.
+template <int SHAPE>
+struct RowShape {
+    static constexpr bool kFixed = false;
+    static constexpr int T = 0, M = 0, F = 0, H = 0;
+};
+template <>
+struct RowShape<1> {  // memory, time encoding and embedding of 100 dims, 8-dim edge features
+    static constexpr bool kFixed = true;
+    static constexpr int T = 100, M = 100, F = 8, H = 2;
+};
+template <>
+struct RowShape<2> {  // the same with 172-dim edge features
+    static constexpr bool kFixed = true;
+    static constexpr int T = 100, M = 100, F = 172, H = 2;
+};
+
+// bit n set: register n (dims 64 n .. 64 n + 63) holds at least one dim of [lo, hi)
+constexpr int regs_touching(int lo, int hi, int dims)
+{
+    int m = 0;
+    for (int n = 0; n * kWave < dims; ++n)
+        if (n * kWave + kWave > lo && n * kWave < hi)
+            m |= 1 << n;
+    return m;
+}
+
+template <int PREC, int MT, int NPL, int H, int SHAPE>
 __global__ void __launch_bounds__(EmbedShape<NPL>::kThreads)
 k_embed(StepArgs a, PackedWeights w, EmbedParams p)
 {
     using P = Prec<PREC>;
+    using SH = RowShape<SHAPE>;
+    // segment sizes and segment-to-register maps of a key/value row, as phase C uses them
+    const int cT = SH::kFixed ? SH::T : p.T, cM = SH::kFixed ? SH::M : p.M, cF = SH::kFixed ? SH::F : p.F;
+    const int phi_regs = SH::kFixed ? regs_touching(0, SH::T, kWave * NPL) : p.phi_regs;
+    const int mem_regs = SH::kFixed ? regs_touching(SH::T, SH::T + SH::M, kWave * NPL) : p.mem_regs;
+    const int feat_regs =
+        SH::kFixed ? regs_touching(SH::T + SH::M, SH::T + SH::M + SH::F, kWave * NPL) : p.feat_regs;
     constexpr int kEmbedThreads = EmbedShape<NPL>::kThreads;
     constexpr int kEmbedWaves = EmbedShape<NPL>::kWaves;
     constexpr int ROWS = 16 * MT;
@@ -143,23 +181,26 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     TIG_MARK(2);
     // ---- C. attention over the neighbours ------------------------------------------------------
     {
-        // per-lane view of a key/value row, kernel order [Phi (T) | s_v (M) | e (F) | 0]: the lane
+        // Per-lane view of a key/value row, kernel order [Phi (T) | s_v (M) | e (F) | 0]: the lane
         // owns dims j = lane + 64 n.  (Time encoding first: its lanes are densely packed.)
-        int goff[NPL];  // >= 0: offset in the neighbour's memory row; <= -2: -(2 + offset in the
-                        // edge-feature row); -1: nothing to load
+        // Neighbour rows are read through buffer descriptors built per row in scalar registers
+        // (base = the row, extent = the row): a lane whose dim lies outside the row reads 0, so
+        // the gathers need no per-lane predication and no per-lane 64-bit address.
+        uint32_t offm[NPL];  // byte offset of the lane's dim inside the memory row, or out of range
 #pragma unroll
         for (int n = 0; n < NPL; ++n) {
-            const int jj = lane + kWave * n - p.T;
-            goff[n] = jj < 0 ? -1 : (jj < p.M ? jj : (jj < p.M + p.F ? -(2 + jj - p.M) : -1));
+            const int jj = lane + kWave * n - cT;
+            offm[n] = jj < 0 ? 0xffffffffu : (uint32_t)jj * 4u;
         }
+        const uint32_t m_bytes = (uint32_t)cM * 4u, f_bytes = (uint32_t)cF * 4u;
         // neighbour tables of this wavefront's rows: slot k lives in lane k
         int32_t nb_v[RPW], nb_e[RPW];
         double nb_dt[RPW];
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
             const int r = wave + i * kEmbedWaves;
-            nb_v[i] = -1;
-            nb_e[i] = -1;
+            nb_v[i] = 0;
+            nb_e[i] = 0;
             nb_dt[i] = 0.0;
             if (r < ROWS) {
                 const int q = row_q[r];
@@ -175,9 +216,9 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
             const int r = wave + i * kEmbedWaves;
             if (r >= ROWS)
                 break;
-            if (row_q[r] < 0)
+            if (__builtin_amdgcn_readfirstlane(row_q[r]) < 0)
                 continue;
-            const int cnt = row_cnt[r];
+            const int cnt = __builtin_amdgcn_readfirstlane(row_cnt[r]);
             const float *qrow = (const float *)(rowbuf + (size_t)r * p.row_bytes);
             char *arow = rowbuf + (size_t)r * p.row_bytes;
             float qv[H][NPL], accv[H][NPL];
@@ -195,95 +236,106 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
             }
             for (int c0 = 0; c0 < cnt; c0 += KC) {
                 float raw[KC][NPL];
+                float mix[KC];  // edge-feature lanes of the one register that also holds s_v dims
                 // issue every gather of the chunk before using any of them
 #pragma unroll
                 for (int kk = 0; kk < KC; ++kk) {
                     const int k = c0 + kk;
-                    const int32_t v = __builtin_amdgcn_readlane(nb_v[i], k & 63);
-                    const int32_t e = __builtin_amdgcn_readlane(nb_e[i], k & 63);
-                    const float *mrow = a.mem + (size_t)(v < 0 ? 0 : v) * p.M;
-                    const float *erow = a.edge_feat + (size_t)(e < 0 ? 0 : e) * p.F;
+                    mix[kk] = 0.0f;
+                    if (k < cnt) {  // scalar
+                        const int32_t v = __builtin_amdgcn_readlane(nb_v[i], k & 63);
+                        const int32_t e = __builtin_amdgcn_readlane(nb_e[i], k & 63);
+                        const __amdgpu_buffer_rsrc_t rm = __builtin_amdgcn_make_buffer_rsrc(
+                            (void *)(a.mem + (size_t)v * cM), 0, (int)m_bytes, kBufferFlags);
+                        const __amdgpu_buffer_rsrc_t re = __builtin_amdgcn_make_buffer_rsrc(
+                            (void *)(a.edge_feat + (size_t)e * cF), 0, (int)f_bytes, kBufferFlags);
 #pragma unroll
-                    for (int n = 0; n < NPL; ++n) {
-                        float x = 0.0f;
-                        if (k < cnt) {
-                            if (goff[n] >= 0)
-                                x = mrow[goff[n]];
-                            else if (goff[n] <= -2)
-                                x = erow[-2 - goff[n]];
+                        for (int n = 0; n < NPL; ++n) {
+                            const bool has_m = (mem_regs >> n) & 1, has_e = (feat_regs >> n) & 1;  // scalar
+                            float x = 0.0f;
+                            if (has_m)
+                                x = buffer_load_f32(rm, offm[n]);
+                            else if (has_e)
+                                x = buffer_load_f32(re, offm[n] - m_bytes);
+                            if (has_m && has_e)  // at most one register: the one with dim T + M inside
+                                mix[kk] = buffer_load_f32(re, offm[n] - m_bytes);
+                            raw[kk][n] = x;
                         }
-                        raw[kk][n] = x;
                     }
                 }
-                // time encoding of t - t_k, then every score of the chunk (independent reductions)
+                // time encoding of t - t_k and the lane's share of every score; slots in pairs so
+                // that the wavefront sums of a pair interleave
                 float sc[KC][H];
 #pragma unroll
                 for (int kk = 0; kk < KC; ++kk) {
-                    const int k = c0 + kk;
 #pragma unroll
                     for (int h = 0; h < H; ++h)
-                        sc[kk][h] = 0.0f;
-                    if (k < cnt) {  // wave-uniform
-                        const double dt = __shfl(nb_dt[i], k & 63, kWave);
+                        sc[kk][h] = -INFINITY;
+                }
 #pragma unroll
-                        for (int n = 0; n < NPHI; ++n) {
-                            if (kWave * n < p.T) {  // uniform: this register holds Phi dims
-                                const int j = lane + kWave * n < p.T ? lane + kWave * n : 0;
-                                const float ph = time_enc(tw_tab[2 * j], tw_tab[2 * j + 1], dt);
-                                if (lane + kWave * n < p.T)
-                                    raw[kk][n] = ph;
+                for (int k2 = 0; k2 < KC; k2 += 2) {
+                    if (c0 + k2 < cnt) {  // scalar
+                        float part[2][H];
+#pragma unroll
+                        for (int u = 0; u < 2; ++u) {
+                            const int kk = k2 + u < KC ? k2 + u : KC - 1;
+                            const int k = c0 + kk;
+#pragma unroll
+                            for (int h = 0; h < H; ++h)
+                                part[u][h] = 0.0f;
+                            if (k2 + u < KC && k < cnt) {  // scalar
+                                const double dt = readlane_f64(nb_dt[i], k & 63);
+#pragma unroll
+                                for (int n = 0; n < NPL; ++n) {
+                                    if ((mem_regs & feat_regs) >> n & 1)  // scalar
+                                        raw[kk][n] += mix[kk];  // disjoint lanes; the other side read 0
+                                }
+#pragma unroll
+                                for (int n = 0; n < NPHI; ++n) {
+                                    if ((phi_regs >> n) & 1) {  // scalar: this register holds Phi dims
+                                        const int j = lane + kWave * n < cT ? lane + kWave * n : 0;
+                                        const float ph = time_enc(tw_tab[2 * j], tw_tab[2 * j + 1], dt);
+                                        if (lane + kWave * n < cT)
+                                            raw[kk][n] = ph;
+                                    }
+                                }
+#pragma unroll
+                                for (int h = 0; h < H; ++h) {
+#pragma unroll
+                                    for (int n = 0; n < NPL; ++n)
+                                        part[u][h] += qv[h][n] * raw[kk][n];
+                                }
                             }
                         }
+                        // wavefront sums of the pair, one DPP step at a time across its 2H values
+                        // (see wave_sum_uniform for the step sequence)
+#define TIG_DPP_STEP(CTRL, ROWS_)                                          \
+    _Pragma("unroll") for (int u = 0; u < 2; ++u)                          \
+        _Pragma("unroll") for (int h = 0; h < H; ++h)                      \
+            part[u][h] += dpp_or_zero<CTRL, ROWS_, 0xf>(part[u][h]);
+                        TIG_DPP_STEP(0x111, 0xf)
+                        TIG_DPP_STEP(0x112, 0xf)
+                        TIG_DPP_STEP(0x114, 0xf)
+                        TIG_DPP_STEP(0x118, 0xf)
+                        if constexpr (H == 1) {
+                            add_row_bcasts(part[0][0], part[1][0]);
+                        } else {
 #pragma unroll
-                        for (int h = 0; h < H; ++h) {
-                            float part = 0.0f;
+                            for (int h = 0; h < H; h += 2)
+                                add_row_bcasts(part[0][h], part[0][h + 1], part[1][h], part[1][h + 1]);
+                        }
+#undef TIG_DPP_STEP
 #pragma unroll
-                            for (int n = 0; n < NPL; ++n)
-                                part += qv[h][n] * raw[kk][n];
-                            sc[kk][h] = part;  // this lane's share; summed over the wavefront below
+                        for (int u = 0; u < 2; ++u) {
+                            if (k2 + u < KC && c0 + k2 + u < cnt) {  // scalar
+#pragma unroll
+                                for (int h = 0; h < H; ++h)
+                                    sc[k2 + u < KC ? k2 + u : KC - 1][h] =
+                                        __int_as_float(__builtin_amdgcn_readlane(__float_as_int(part[u][h]), 63));
+                            }
                         }
                     }
                 }
-                // wavefront sums of all partial scores of the chunk, one DPP step at a time across
-                // every value: consecutive instructions are independent, so no step waits on the
-                // previous one (see wave_sum_uniform for the step sequence)
-#pragma unroll
-                for (int kk = 0; kk < KC; ++kk)
-#pragma unroll
-                    for (int h = 0; h < H; ++h)
-                        sc[kk][h] += dpp_or_zero<0x111, 0xf, 0xf>(sc[kk][h]);
-#pragma unroll
-                for (int kk = 0; kk < KC; ++kk)
-#pragma unroll
-                    for (int h = 0; h < H; ++h)
-                        sc[kk][h] += dpp_or_zero<0x112, 0xf, 0xf>(sc[kk][h]);
-#pragma unroll
-                for (int kk = 0; kk < KC; ++kk)
-#pragma unroll
-                    for (int h = 0; h < H; ++h)
-                        sc[kk][h] += dpp_or_zero<0x114, 0xf, 0xf>(sc[kk][h]);
-#pragma unroll
-                for (int kk = 0; kk < KC; ++kk)
-#pragma unroll
-                    for (int h = 0; h < H; ++h)
-                        sc[kk][h] += dpp_or_zero<0x118, 0xf, 0xf>(sc[kk][h]);
-#pragma unroll
-                for (int kk = 0; kk < KC; ++kk)
-#pragma unroll
-                    for (int h = 0; h < H; ++h)
-                        sc[kk][h] += dpp_or_zero<0x142, 0xa, 0xf>(sc[kk][h]);
-#pragma unroll
-                for (int kk = 0; kk < KC; ++kk)
-#pragma unroll
-                    for (int h = 0; h < H; ++h)
-                        sc[kk][h] += dpp_or_zero<0x143, 0xc, 0xf>(sc[kk][h]);
-#pragma unroll
-                for (int kk = 0; kk < KC; ++kk)
-#pragma unroll
-                    for (int h = 0; h < H; ++h) {
-                        const float tot = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sc[kk][h]), 63));
-                        sc[kk][h] = c0 + kk < cnt ? tot : -INFINITY;
-                    }
                 // softmax across the chunk, merged with earlier chunks by rescaling
 #pragma unroll
                 for (int h = 0; h < H; ++h) {
@@ -298,7 +350,7 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                         accv[h][n] *= corr;
 #pragma unroll
                     for (int kk = 0; kk < KC; ++kk) {
-                        if (c0 + kk < cnt) {
+                        if (c0 + kk < cnt) {  // scalar
                             const float pk = __expf(sc[kk][h] - mnew);
                             dsum += pk;
 #pragma unroll
@@ -494,6 +546,17 @@ EmbedParams embed_params(const Dims &d, int mt, int roles)
     main_bytes = (main_bytes + 15) / 16 * 16;
     p.off_h1 = main_bytes;
     p.off_meta = p.off_h1 + rows * p.ld1;
+    p.n_tiles = 0;
+    p.phi_regs = p.mem_regs = p.feat_regs = 0;
+    for (int n = 0; n * kWave < d.dkvp; ++n) {
+        const int lo = n * kWave, hi = lo + kWave;
+        if (lo < d.T)
+            p.phi_regs |= 1 << n;
+        if (hi > d.T && lo < d.T + d.M)
+            p.mem_regs |= 1 << n;
+        if (hi > d.T + d.M && lo < d.T + d.M + d.F)
+            p.feat_regs |= 1 << n;
+    }
     return p;
 }
 
@@ -510,10 +573,37 @@ template <int PREC, int MT, int NPL>
 const void *pick_h(int H)
 {
     switch (H) {
-    case 1: return (const void *)k_embed<PREC, MT, NPL, 1>;
-    case 2: return (const void *)k_embed<PREC, MT, NPL, 2>;
-    default: return (const void *)k_embed<PREC, MT, NPL, 4>;
+    case 1: return (const void *)k_embed<PREC, MT, NPL, 1, 0>;
+    case 2: return (const void *)k_embed<PREC, MT, NPL, 2, 0>;
+    default: return (const void *)k_embed<PREC, MT, NPL, 4, 0>;
     }
+}
+
+constexpr int npl_of_dims(int dims)
+{
+    int npl = 1;
+    while (npl * kWave < dims)
+        npl *= 2;
+    return npl;
+}
+
+template <int PREC, int SHAPE>
+const void *pick_fixed(int mt)
+{
+    using SH = RowShape<SHAPE>;
+    constexpr int NPL = npl_of_dims(SH::T + SH::M + SH::F);
+    switch (mt) {
+    case 1: return (const void *)k_embed<PREC, 1, NPL, SH::H, SHAPE>;
+    case 2: return (const void *)k_embed<PREC, 2, NPL, SH::H, SHAPE>;
+    default: return (const void *)k_embed<PREC, 3, NPL, SH::H, SHAPE>;
+    }
+}
+
+template <int SHAPE>
+bool shape_is(const Dims &d)
+{
+    using SH = RowShape<SHAPE>;
+    return d.T == SH::T && d.M == SH::M && d.F == SH::F && d.H == SH::H;
 }
 
 template <int PREC, int MT>
@@ -540,7 +630,12 @@ const void *pick_mt(int mt, int npl, int H)
 const void *embed_kernel(const Dims &d, int mt)
 {
     const int npl = npl_for(d);
-    return d.prec == TIG_BF16_MFMA ? pick_mt<TIG_BF16_MFMA>(mt, npl, d.H) : pick_mt<TIG_FP32>(mt, npl, d.H);
+    const bool bf16 = d.prec == TIG_BF16_MFMA;
+    if (shape_is<1>(d))
+        return bf16 ? pick_fixed<TIG_BF16_MFMA, 1>(mt) : pick_fixed<TIG_FP32, 1>(mt);
+    if (shape_is<2>(d))
+        return bf16 ? pick_fixed<TIG_BF16_MFMA, 2>(mt) : pick_fixed<TIG_FP32, 2>(mt);
+    return bf16 ? pick_mt<TIG_BF16_MFMA>(mt, npl, d.H) : pick_mt<TIG_FP32>(mt, npl, d.H);
 }
 
 }  // namespace

@@ -110,6 +110,53 @@ __device__ inline float dpp_or_zero(float v)
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, BANK_MASK, true));
 }
 
+// The two cross-row steps of wave_sum_uniform for several values at once, as fused DPP adds: rows
+// outside the row mask keep their value, which the compiler does not express in one instruction.
+// The leading s_nop covers the two wait states a DPP read needs after a vector-ALU write of the
+// same register; inside the block two instructions on one register are far enough apart.
+__device__ inline void add_row_bcasts(float &a, float &b)
+{
+    asm volatile("s_nop 1\n\t"
+                 "v_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+                 "v_add_f32_dpp %1, %1, %1 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+                 "s_nop 0\n\t"
+                 "v_add_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+                 "v_add_f32_dpp %1, %1, %1 row_bcast:31 row_mask:0xc bank_mask:0xf"
+                 : "+v"(a), "+v"(b));
+}
+
+__device__ inline void add_row_bcasts(float &a, float &b, float &c, float &d)
+{
+    asm volatile("s_nop 1\n\t"
+                 "v_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+                 "v_add_f32_dpp %1, %1, %1 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+                 "v_add_f32_dpp %2, %2, %2 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+                 "v_add_f32_dpp %3, %3, %3 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+                 "v_add_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+                 "v_add_f32_dpp %1, %1, %1 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+                 "v_add_f32_dpp %2, %2, %2 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+                 "v_add_f32_dpp %3, %3, %3 row_bcast:31 row_mask:0xc bank_mask:0xf"
+                 : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+}
+
+// Raw buffer descriptor word 3 for gfx950: 32-bit data format, no swizzle.  With stride 0 a lane
+// whose byte offset is not inside [0, extent - 4] reads 0.
+constexpr int kBufferFlags = 0x00020000;
+
+__device__ inline float buffer_load_f32(__amdgpu_buffer_rsrc_t rsrc, uint32_t byte_offset)
+{
+    return __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)byte_offset, 0, 0));
+}
+
+// value of lane `src` (wave-uniform) as a scalar
+__device__ inline double readlane_f64(double v, int src)
+{
+    const long long b = __double_as_longlong(v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(b & 0xffffffffll), src);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(b >> 32), src);
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+
 // Sum over the 64 lanes, returned as a wave-uniform value: a prefix sum inside each row of 16
 // lanes (row_shr 1, 2, 4, 8; lanes shifted in from outside the row read as 0), then the row
 // totals are carried forward (row_bcast 15, row_bcast 31) so that lane 63 holds the total.
