@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # HBM bytes per launch of the dominant kernel (k_embed), from two rocprofv3 --pmc runs (FETCH_SIZE,
 # WRITE_SIZE), each scaled by what the counter reads for a plain 256 MiB device copy; see
 # profiles/hbm_traffic_c5_gpu_partition_bf16.md.  Only known for the combinations measured.
-MEASURED_TRAFFIC_BYTES = {("c5_gpu_partition", "bf16", 4000): 19.7e6}
+MEASURED_TRAFFIC_BYTES = {("c5_gpu_partition", "bf16", 4000): 17.4e6}
 
 
 def log(msg):
@@ -41,15 +41,15 @@ def algorithmic_bytes(w, count, roles, nbr_cnt_sum, winners):
     return {
         # scatter: event (src, dst, ts) reads + one 8-byte key update per entry; lookup: per query
         # node id, time, two offsets, the K-entry window; writes of the K slots + count
-        "k_scatter": entries * (4 + 8 + 8) * 2 + entries * 8 + winners * (8 + 32),
+        "k_scatter": entries * (4 + 8 + 8) * 2 + entries * 8 + winners * (8 + 24),
         # own launch only for batches above 4096 events (otherwise fused into k_scatter)
         "k_select": 0,
         # per winner: descriptor, two memory rows, edge feature; new row out.  Per query (lookup,
         # same launch): node id, time, two offsets, position, the K-entry window; K slots + count out
-        "k_gru": winners * (32 + (2 * M + F) * 4) + winners * M * 4
+        "k_gru": winners * (24 + 8 + (2 * M + F) * 4) + winners * M * 4
                  + Q * (4 + 8 + 16 + 4 + 16 * K) + Q * (16 * K + 4),
         # per winner: descriptor and staged row in, memory row + last_update + key out
-        "k_commit": winners * (32 + 2 * M * 4 + 16),
+        "k_commit": winners * (24 + 2 * M * 4 + 16),
         # per query: own memory row, neighbour table; per filled slot a memory row + an edge
         # feature row; embedding and scores out
         "k_embed": Q * (M * 4 + 4 + 4) + nbr_cnt_sum * ((M + F) * 4 + 16) + Q * E * 4 + (roles - 1) * count * 4,

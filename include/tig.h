@@ -163,6 +163,12 @@ TIG_API int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_we
  * TIG_ERANGE if the event range leaves the graph.  neg_dst values must be valid node ids (they
  * are not checked on the device; an id outside 0..N-1 is treated as a node without history and
  * with zero memory).
+ * Chronological passes hand over consecutive batches of one size, so every step also selects,
+ * inside its embedding launch, the step-2 winners of the batch that would follow it
+ * (first_eid + count, same count, clipped at the end of the stream).  That selection reads the
+ * event stream only, never the model state; the next call uses it if its batch is exactly that
+ * one and out->is_winner is NULL, and otherwise selects its winners itself.  Results do not
+ * depend on whether the guess was right, and tig_reset / tig_state_import in between are fine.
  */
 TIG_API int tig_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *out);
 
