@@ -42,7 +42,8 @@ typedef enum tig_status {
     TIG_ESELFLOOP = -4, /* an event has src == dst */
     TIG_ENOSPACE = -5,  /* a workspace is smaller than tig_workspace_bytes reports */
     TIG_EHIP = -6,      /* a HIP call failed; text via tig_last_error */
-    TIG_ENOMEM = -7     /* host allocation of the context failed */
+    TIG_ENOMEM = -7,    /* host allocation of the context failed */
+    TIG_EORDER = -8     /* the batch starts before the end of the previous one (no reset / import between) */
 } tig_status;
 
 typedef enum tig_precision {
@@ -159,8 +160,11 @@ TIG_API int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_we
  *   4. for every query (node, t_event): the K most recent incident events with time < t_event,
  *      taken from the whole graph given at tig_init, ordered by (time, event id) descending;
  *   5. attention over them with the UPDATED memory, merge MLP -> emb; decoder -> scores.
- * Errors (nothing is launched): TIG_EINVAL for NULL required pointers or count out of 1..max_batch,
- * TIG_ERANGE if the event range leaves the graph.  neg_dst values must be valid node ids (they
+ * Steps run chronologically: a batch must not start before the end of the previous one unless
+ * tig_reset or tig_state_import was called in between (they rewind the cursor to event 0).
+ * Errors (nothing is launched, the state is unchanged): TIG_EINVAL for NULL required pointers or
+ * count out of 1..max_batch, TIG_ERANGE if the event range leaves the graph, TIG_EORDER for a batch
+ * that starts before the cursor.  neg_dst values must be valid node ids (they
  * are not checked on the device; an id outside 0..N-1 is treated as a node without history and
  * with zero memory).
  * Chronological passes hand over consecutive batches of one size, so every step also selects,

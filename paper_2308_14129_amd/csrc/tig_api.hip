@@ -36,6 +36,7 @@ struct tig_ctx {
     int64_t ahead_first;
     int32_t ahead_count;
     int num_cus;
+    int64_t cursor;    // end of the last batch stepped since the last reset / import
     int32_t *pos;
     hipEvent_t marks[kNumStepKernels + 1];
     bool have_marks;
@@ -421,6 +422,8 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
         return fail(ctx, TIG_ERANGE, "tig_step: event range leaves the graph");
     if (!out->emb || !out->score_pos || (batch->neg_dst && !out->score_neg))
         return fail(ctx, TIG_EINVAL, "tig_step: required output pointer is NULL");
+    if (batch->first_eid < ctx->cursor)
+        return fail(ctx, TIG_EORDER, "tig_step: batch starts before the end of the previous one");
 
     StepArgs a;
     a.src = ctx->src;
@@ -474,6 +477,7 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     const hipError_t e = launch_step(ctx->d, ctx->plan, ctx->pw, a, ctx->stream, marks, ready);
     if (e != hipSuccess)
         return fail(ctx, TIG_EHIP, "tig_step launch", e);
+    ctx->cursor = batch->first_eid + batch->count;
     if (a.next_count > 0) {
         ctx->ahead_valid = true;
         ctx->ahead_first = a.next_first_eid;
@@ -524,6 +528,7 @@ int tig_reset(tig_ctx *ctx)
         e = launch_fill_zero(ctx->lu, sizeof(double) * (size_t)ctx->num_nodes, ctx->stream);
     if (e != hipSuccess)
         return fail(ctx, TIG_EHIP, "tig_reset", e);
+    ctx->cursor = 0;
     return TIG_OK;
 }
 
@@ -560,6 +565,7 @@ int tig_state_import(tig_ctx *ctx, const float *mem_in, const double *last_updat
         e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess)
         return fail(ctx, TIG_EHIP, "tig_state_import", e);
+    ctx->cursor = 0;
     return TIG_OK;
 }
 
@@ -584,6 +590,7 @@ const char *tig_strerror(int status)
     case TIG_ENOSPACE: return "workspace too small";
     case TIG_EHIP: return "HIP runtime error";
     case TIG_ENOMEM: return "out of host memory";
+    case TIG_EORDER: return "batch out of chronological order";
     default: return "unknown status";
     }
 }

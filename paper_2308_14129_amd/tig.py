@@ -17,8 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("TIG_LIB_PATH") or os.path.join(_HERE, "libtig.so")
 
 TIG_OK = 0
-TIG_EINVAL, TIG_ERANGE, TIG_EUNSORTED, TIG_ESELFLOOP, TIG_ENOSPACE, TIG_EHIP, TIG_ENOMEM = (
-    -1, -2, -3, -4, -5, -6, -7)
+TIG_EINVAL, TIG_ERANGE, TIG_EUNSORTED, TIG_ESELFLOOP, TIG_ENOSPACE, TIG_EHIP, TIG_ENOMEM, TIG_EORDER = (
+    -1, -2, -3, -4, -5, -6, -7, -8)
 TIG_FP32, TIG_BF16_MFMA = 0, 1
 PRECISIONS = {"fp32": TIG_FP32, "bf16": TIG_BF16_MFMA}
 

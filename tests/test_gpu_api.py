@@ -99,6 +99,22 @@ def test_step_argument_errors_leave_state_unchanged(c1):
         assert ctx.lib.tig_last_error(ctx.handle) != b""
     mem1, lu1 = ctx.state_export()
     assert np.array_equal(mem0, mem1) and np.array_equal(lu0, lu1)
+    # chronological order: after a step over [5000, 5200) a batch may start at 5200 or later, not
+    # before, until a reset or an import rewinds the cursor
+    good_b = tig.tig_batch(sz_b, 200, 5000, neg.data_ptr())
+    assert ctx.step_raw(good_b, good_o) == tig.TIG_OK
+    torch.cuda.synchronize()
+    mem2, lu2 = ctx.state_export()
+    for first in (5000, 5199, 0):
+        assert ctx.step_raw(tig.tig_batch(sz_b, 100, first, neg.data_ptr()), good_o) == tig.TIG_EORDER
+    mem3, lu3 = ctx.state_export()
+    assert np.array_equal(mem2, mem3) and np.array_equal(lu2, lu3)
+    assert ctx.step_raw(tig.tig_batch(sz_b, 100, 5300, neg.data_ptr()), good_o) == tig.TIG_OK   # gaps are fine
+    ctx.state_import(mem0, lu0)
+    assert ctx.step_raw(good_b, good_o) == tig.TIG_OK
+    ctx.reset()
+    assert ctx.step_raw(tig.tig_batch(sz_b, 100, 0, neg.data_ptr()), good_o) == tig.TIG_OK
+    torch.cuda.synchronize()
     ctx.close()
 
 
