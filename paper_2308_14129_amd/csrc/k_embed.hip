@@ -30,11 +30,11 @@ extern "C" __attribute__((visibility("default"))) int tig_debug_phase_clocks(uns
 
 namespace {
 
-// Wavefronts per workgroup: 16 (128 registers per lane) unless a key/value row needs more than
-// four registers per lane, then 8 (256 registers per lane).
-template <int NPL>
+// Wavefronts per workgroup: 16 (128 registers per lane) unless the query and accumulator rows of
+// all heads need 64 registers per lane or more, then 8 (256 registers per lane).
+template <int NPL, int H>
 struct EmbedShape {
-    static constexpr int kThreads = NPL >= 8 ? 512 : 1024;
+    static constexpr int kThreads = (NPL >= 8 && H >= 4) ? 512 : 1024;
     static constexpr int kWaves = kThreads / kWave;
 };
 
@@ -65,9 +65,9 @@ struct RowShape<1> {  // memory, time encoding and embedding of 100 dims, 8-dim 
     static constexpr int T = 100, M = 100, F = 8, H = 2;
 };
 template <>
-struct RowShape<2> {  // the same with 172-dim edge features
+struct RowShape<2> {  // 172-dim memory and edge features, 100-dim time encoding
     static constexpr bool kFixed = true;
-    static constexpr int T = 100, M = 100, F = 172, H = 2;
+    static constexpr int T = 100, M = 172, F = 172, H = 2;
 };
 
 // bit n set: register n (dims 64 n .. 64 n + 63) holds at least one dim of [lo, hi)
@@ -81,7 +81,7 @@ constexpr int regs_touching(int lo, int hi, int dims)
 }
 
 template <int PREC, int MT, int NPL, int H, int SHAPE>
-__global__ void __launch_bounds__(EmbedShape<NPL>::kThreads)
+__global__ void __launch_bounds__((EmbedShape<NPL, H>::kThreads))
 k_embed(StepArgs a, PackedWeights w, EmbedParams p)
 {
     using P = Prec<PREC>;
@@ -92,8 +92,8 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     const int mem_regs = SH::kFixed ? regs_touching(SH::T, SH::T + SH::M, kWave * NPL) : p.mem_regs;
     const int feat_regs =
         SH::kFixed ? regs_touching(SH::T + SH::M, SH::T + SH::M + SH::F, kWave * NPL) : p.feat_regs;
-    constexpr int kEmbedThreads = EmbedShape<NPL>::kThreads;
-    constexpr int kEmbedWaves = EmbedShape<NPL>::kWaves;
+    constexpr int kEmbedThreads = EmbedShape<NPL, H>::kThreads;
+    constexpr int kEmbedWaves = EmbedShape<NPL, H>::kWaves;
     constexpr int ROWS = 16 * MT;
     constexpr int RPW = (ROWS + kEmbedWaves - 1) / kEmbedWaves;  // rows per wavefront in phase C
     constexpr int KC = NPL >= 8 ? 5 : (NPL == 4 ? 10 : 16);      // neighbour rows in flight
@@ -569,6 +569,9 @@ int npl_for(const Dims &d)
     return npl;
 }
 
+// must agree with EmbedShape (heads other than 1 and 2 run the 4-head kernels)
+int embed_threads(const Dims &d) { return npl_for(d) >= 8 && d.H > 2 ? 512 : 1024; }
+
 template <int PREC, int MT, int NPL>
 const void *pick_h(int H)
 {
@@ -646,20 +649,40 @@ int embed_lds_bytes(const Dims &d, int mt)
     return p.off_meta + 16 * mt * (3 * 4 + 8) + d.T * 16;
 }
 
-hipError_t prepare_embed(const Dims &d, const LaunchPlan &plan)
+// 16-row tiles per workgroup for a batch of `count` events: a workgroup's latency grows with its
+// rows, so small batches take the smallest tile count whose grid still starts at once (one
+// workgroup per compute unit, one unit spare for the winner selection of the next batch); large
+// batches take the largest, which streams the weights least often.
+static int embed_tiles(const LaunchPlan &plan, int roles, int count)
 {
-    const int lds = npl_for(d) < 8 && plan.emb_lds < kOneLds ? kOneLds : plan.emb_lds;
-    return hipFuncSetAttribute(embed_kernel(d, plan.emb_mt), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    for (int mt = 1; mt < plan.emb_mt; ++mt) {
+        const int te = 16 * mt / roles;
+        if ((count + te - 1) / te + 1 <= plan.num_cus)
+            return mt;
+    }
+    return plan.emb_mt;
 }
 
-bool embed_can_select_ahead(const Dims &d, const LaunchPlan &plan, int roles, int count, int next_count,
-                            int num_cus)
+hipError_t prepare_embed(const Dims &d, const LaunchPlan &plan)
 {
-    if (npl_for(d) >= 8 || next_count < 1 || 2 * next_count > kOneMaxEntries)
+    for (int mt = 1; mt <= plan.emb_mt; ++mt) {
+        const int own = embed_lds_bytes(d, mt);
+        const int lds = embed_threads(d) == kScatterThreads && own < kOneLds ? kOneLds : own;
+        const hipError_t e =
+            hipFuncSetAttribute(embed_kernel(d, mt), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess)
+            return e;
+    }
+    return hipSuccess;
+}
+
+bool embed_can_select_ahead(const Dims &d, const LaunchPlan &plan, int roles, int count, int next_count)
+{
+    if (embed_threads(d) != kScatterThreads || next_count < 1 || 2 * next_count > kOneMaxEntries)
         return false;
     // every tile and the extra workgroup must start at once, each on a compute unit of its own
-    const EmbedParams p = embed_params(d, plan.emb_mt, roles);
-    return (count + p.TE - 1) / p.TE + 1 <= num_cus;
+    const int te = 16 * embed_tiles(plan, roles, count) / roles;
+    return (count + te - 1) / te + 1 <= plan.num_cus;
 }
 
 hipError_t launch_embed(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
@@ -667,13 +690,15 @@ hipError_t launch_embed(const Dims &d, const LaunchPlan &plan, const PackedWeigh
 {
     StepArgs aa = a;
     PackedWeights ww = pw;
-    EmbedParams p = embed_params(d, plan.emb_mt, a.roles);
+    const int mt = embed_tiles(plan, a.roles, a.count);
+    EmbedParams p = embed_params(d, mt, a.roles);
     p.n_tiles = (a.count + p.TE - 1) / p.TE;
     void *args[] = {&aa, &ww, &p};
     const bool ahead = a.next_count > 0;
-    const int threads = npl_for(d) >= 8 ? EmbedShape<8>::kThreads : EmbedShape<1>::kThreads;
-    const int lds = ahead && plan.emb_lds < kOneLds ? kOneLds : plan.emb_lds;
-    return hipLaunchKernel(embed_kernel(d, plan.emb_mt), dim3(p.n_tiles + (ahead ? 1 : 0)), dim3(threads), args,
+    const int threads = embed_threads(d);
+    const int own = embed_lds_bytes(d, mt);
+    const int lds = ahead && own < kOneLds ? kOneLds : own;
+    return hipLaunchKernel(embed_kernel(d, mt), dim3(p.n_tiles + (ahead ? 1 : 0)), dim3(threads), args,
                            (size_t)lds, s);
 }
 

@@ -19,6 +19,7 @@ bool plan_launch(const Dims &d, int lds_limit, LaunchPlan *plan)
             break;
         }
     plan->emb_mt = 0;
+    plan->num_cus = 0;
     for (int mt = 3; mt >= 1; --mt)
         if (embed_lds_bytes(d, mt) <= lds_limit) {
             plan->emb_mt = mt;

@@ -327,6 +327,7 @@ int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *w
         int dev = 0;
         INIT_TRY(hipGetDevice(&dev), "hipGetDevice");
         INIT_TRY(hipDeviceGetAttribute(&ctx->num_cus, hipDeviceAttributeMultiprocessorCount, dev), "compute unit count");
+        ctx->plan.num_cus = ctx->num_cus;
     }
 
     const PersistentLayout L = persistent_layout(d, N, E, persistent);
@@ -470,7 +471,7 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     if (!marks && a.next_first_eid < ctx->num_events) {
         const int64_t left = ctx->num_events - a.next_first_eid;
         const int32_t guess = left < batch->count ? (int32_t)left : batch->count;
-        if (embed_can_select_ahead(ctx->d, ctx->plan, a.roles, batch->count, guess, ctx->num_cus))
+        if (embed_can_select_ahead(ctx->d, ctx->plan, a.roles, batch->count, guess))
             a.next_count = guess;
     }
     ctx->ahead_valid = false;

@@ -104,7 +104,8 @@ struct LaunchPlan {
     int gru_entries;     // entries (event, role) per GRU workgroup: 16*gru_mt
     int gru_mt;          // 16-row tiles per GRU workgroup
     int gru_lds;         // bytes
-    int emb_mt;          // 16-row tiles per embedding workgroup
+    int emb_mt;          // most 16-row tiles per embedding workgroup (what LDS holds)
+    int num_cus;         // compute units of the device (0 until known)
     int emb_lds;         // bytes
 };
 
@@ -140,8 +141,7 @@ hipError_t launch_embed(const Dims &d, const LaunchPlan &plan, const PackedWeigh
                         hipStream_t s);
 // whether the embedding launch of a batch of `count` events can carry one more workgroup that
 // selects the winners of a following batch of `next_count` events without delaying anything
-bool embed_can_select_ahead(const Dims &d, const LaunchPlan &plan, int roles, int count, int next_count,
-                            int num_cus);
+bool embed_can_select_ahead(const Dims &d, const LaunchPlan &plan, int roles, int count, int next_count);
 hipError_t prepare_kernels(const Dims &d, const LaunchPlan &plan);
 constexpr int kNumStepKernels = 5;
 // `marks`: NULL, or kNumStepKernels + 1 events recorded before the first and after every kernel.
