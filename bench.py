@@ -70,6 +70,9 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 256 MiB device copies (known HBM traffic) so that a "
                          "rocprofv3 --pmc run of this command can scale FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="also time a plain 1 GiB device copy (read + write) and report the measured "
+                         "HBM bandwidth of this GPU beside the published peak")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1",
@@ -196,6 +199,24 @@ def main():
             dst_buf.copy_(src_buf)   # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del src_buf, dst_buf
+
+    measured_copy_gbs = None
+    if args.ceilings:
+        n = 1 << 30
+        src_buf = torch.full((n,), 1, dtype=torch.uint8, device="cuda:0")
+        dst_buf = torch.empty_like(src_buf)
+        for _ in range(3):
+            dst_buf.copy_(src_buf)
+        torch.cuda.synchronize()
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
+        for _ in range(10):
+            dst_buf.copy_(src_buf)
+        c1.record()
+        torch.cuda.synchronize()
+        measured_copy_gbs = round(10 * 2 * n / (c0.elapsed_time(c1) * 1e-3) / 1e9, 1)  # bytes read + written
+        del src_buf, dst_buf
+        roofline["measured_copy_GBps"] = measured_copy_gbs
 
     info = ctx.launch_info()
     line = {

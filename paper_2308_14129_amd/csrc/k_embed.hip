@@ -70,6 +70,12 @@ struct RowShape<2> {  // 172-dim memory and edge features, 100-dim time encoding
     static constexpr int T = 100, M = 172, F = 172, H = 2;
 };
 
+template <>
+struct RowShape<3> {  // 100-dim memory and time encoding, 16-dim edge features
+    static constexpr bool kFixed = true;
+    static constexpr int T = 100, M = 100, F = 16, H = 2;
+};
+
 // bit n set: register n (dims 64 n .. 64 n + 63) holds at least one dim of [lo, hi)
 constexpr int regs_touching(int lo, int hi, int dims)
 {
@@ -638,6 +644,8 @@ const void *embed_kernel(const Dims &d, int mt)
         return bf16 ? pick_fixed<TIG_BF16_MFMA, 1>(mt) : pick_fixed<TIG_FP32, 1>(mt);
     if (shape_is<2>(d))
         return bf16 ? pick_fixed<TIG_BF16_MFMA, 2>(mt) : pick_fixed<TIG_FP32, 2>(mt);
+    if (shape_is<3>(d))
+        return bf16 ? pick_fixed<TIG_BF16_MFMA, 3>(mt) : pick_fixed<TIG_FP32, 3>(mt);
     return bf16 ? pick_mt<TIG_BF16_MFMA>(mt, npl, d.H) : pick_mt<TIG_FP32>(mt, npl, d.H);
 }
 

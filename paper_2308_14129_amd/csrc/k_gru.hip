@@ -20,6 +20,14 @@
 
 namespace tig {
 
+#ifdef TIG_PHASE_CLOCKS
+static __device__ unsigned long long g_phase_clocks[8192 * 8];
+extern "C" __attribute__((visibility("default"))) int tig_debug_phase_clocks_gru(unsigned long long *out, int n)
+{
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase_clocks), sizeof(unsigned long long) * (size_t)n);
+}
+#endif
+
 namespace {
 
 constexpr int kGruThreads = 1024;
@@ -71,10 +79,12 @@ template <int PREC, int MT>
 __global__ void __launch_bounds__(kGruThreads)
 k_gru(StepArgs a, PackedWeights w, GruParams g, int n_gru_blocks, int K)
 {
+    TIG_MARK(0);
     if ((int)blockIdx.x >= n_gru_blocks) {  // lookup workgroup: one query per wavefront
         const int q = ((int)blockIdx.x - n_gru_blocks) * kGruWaves + wave_id();
         if (q < a.roles * a.count)
             nbr_lookup_wave(a, K, q);
+        TIG_MARK(1);
         return;
     }
     using P = Prec<PREC>;
@@ -119,6 +129,7 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int n_gru_blocks, int K)
         row_t[r] = t;
     }
     __syncthreads();
+    TIG_MARK(1);
 
     // 2. message rows from batch-start memory; rows beyond n_rows are zero
     for (int idx = threadIdx.x; idx < EC * g.Kg; idx += kGruThreads) {
@@ -139,6 +150,7 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int n_gru_blocks, int K)
         P::store_a(X + (size_t)r * g.ldx, j, v);
     }
     __syncthreads();
+    TIG_MARK(2);
 
     // 3. + 4. gates
     const int kblocks = g.Kg / P::KB;
@@ -178,6 +190,7 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int n_gru_blocks, int K)
             }
         }
         __syncthreads();
+        TIG_MARK(3);
         if (on && half == 1 && col < g.M) {
             const float bin = w.gru_bin[col], bhn = w.gru_bhn[col];
 #pragma unroll
@@ -198,6 +211,7 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int n_gru_blocks, int K)
         }
         __syncthreads();  // rz is reused by the next round
     }
+    TIG_MARK(4);
 }
 
 GruParams gru_params(const Dims &d, int mt)
