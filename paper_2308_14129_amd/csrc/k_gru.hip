@@ -38,6 +38,8 @@ struct GruParams {
     int Kg, Khn, Ng;
     int ldx;     // LDS row stride of the message tile, bytes
     int off_rz;  // byte offset of the r/z exchange buffer in LDS
+    int cs;      // workgroups per row tile: each takes `tpp` consecutive 16-column tiles of the gates
+    int tpp;
 };
 
 // acc1 += A x W1[nt]^T and acc2 += A x W2[nt]^T over k-blocks [0, kblocks): both weight streams
@@ -102,8 +104,11 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int n_gru_blocks, int K)
     const int wave = wave_id();
 
     // 1. this block's slice of the compacted winner list (descriptor and count are read in the
-    //    same round trip; slots beyond the count hold stale but in-range descriptors)
-    const int r0 = blockIdx.x * EC;
+    //    same round trip; slots beyond the count hold stale but in-range descriptors).  The g.cs
+    //    workgroups of a row tile gather the same rows and split the gate columns: each streams
+    //    only its share of the gate weights.
+    const int r0 = ((int)blockIdx.x / g.cs) * EC;
+    const int ct_lo = ((int)blockIdx.x % g.cs) * g.tpp;
     WinDesc d0;
     if (threadIdx.x < EC)
         d0 = a.win[r0 + threadIdx.x];
@@ -155,9 +160,9 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int n_gru_blocks, int K)
     // 3. + 4. gates
     const int kblocks = g.Kg / P::KB;
     const int kblocks_hn = g.Khn / P::KB;
-    const int n_ct = g.Ng / 16;
+    const int n_ct = g.Ng / 16 < ct_lo + g.tpp ? g.Ng / 16 : ct_lo + g.tpp;  // end of this block's tiles
     constexpr int kPairs = kGruWaves / 2;  // column tiles per round
-    for (int base = 0; base < n_ct; base += kPairs) {
+    for (int base = ct_lo; base < n_ct; base += kPairs) {
         const int ct = base + (wave % kPairs);
         const int half = wave / kPairs;  // 0: r and z gates, 1: n gate
         const bool on = ct < n_ct;
@@ -226,6 +231,8 @@ GruParams gru_params(const Dims &d, int mt)
     g.Ng = d.Ng;
     g.ldx = lds_row_bytes(d.Kg);
     g.off_rz = (16 * mt * 24 + 16 * mt * g.ldx + 15) / 16 * 16;
+    g.cs = 1;
+    g.tpp = d.Ng / 16;
     return g;
 }
 
@@ -250,8 +257,13 @@ int gru_lds_bytes(const Dims &d, int mt)
 
 hipError_t prepare_gru(const Dims &d, const LaunchPlan &plan)
 {
-    return hipFuncSetAttribute(gru_kernel(d, plan.gru_mt), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               plan.gru_lds);
+    for (int mt = 1; mt <= plan.gru_mt; ++mt) {
+        const hipError_t e = hipFuncSetAttribute(gru_kernel(d, mt), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                 gru_lds_bytes(d, mt));
+        if (e != hipSuccess)
+            return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_gru(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
@@ -259,14 +271,26 @@ hipError_t launch_gru(const Dims &d, const LaunchPlan &plan, const PackedWeights
 {
     StepArgs aa = a;
     PackedWeights ww = pw;
-    GruParams g = gru_params(d, plan.gru_mt);
     const int entries = 2 * a.count;
-    int n_gru_blocks = (entries + plan.gru_entries - 1) / plan.gru_entries;
+    // Column split.  Every workgroup streams the gate weights of its columns from L2, which bounds
+    // its run time, so when the 16-row tiles do not fill the device the columns of a tile are
+    // split over as many workgroups as it takes at once.  Only the tiles below the winner count
+    // do any work.  (32-row tiles with halved columns measured slower at large batches.)
+    const int cus = plan.num_cus > 0 ? plan.num_cus : 256;
+    const int mt = 1;
+    GruParams g = gru_params(d, mt);
+    const int tiles = (entries + 16 * mt - 1) / (16 * mt);
+    const int n_ct = d.Ng / 16;
+    int cs = 2 * cus / tiles;
+    cs = cs < 1 ? 1 : (cs > n_ct ? n_ct : cs);
+    g.tpp = (n_ct + cs - 1) / cs;
+    g.cs = (n_ct + g.tpp - 1) / g.tpp;
+    int n_gru_blocks = tiles * g.cs;
     int K = d.K;
     const int n_lookup_blocks = (a.roles * a.count + kGruWaves - 1) / kGruWaves;
     void *args[] = {&aa, &ww, &g, &n_gru_blocks, &K};
-    return hipLaunchKernel(gru_kernel(d, plan.gru_mt), dim3(n_gru_blocks + n_lookup_blocks),
-                           dim3(kGruThreads), args, (size_t)plan.gru_lds, s);
+    return hipLaunchKernel(gru_kernel(d, mt), dim3(n_gru_blocks + n_lookup_blocks), dim3(kGruThreads), args,
+                           (size_t)gru_lds_bytes(d, mt), s);
 }
 
 }  // namespace tig

@@ -9,11 +9,8 @@ bool plan_launch(const Dims &d, int lds_limit, LaunchPlan *plan)
 {
     if (d.dkvp > 512)
         return false;
-    // GRU rows are the compacted winners (often a small fraction of the 2B entries): 16-row tiles
-    // spread them over many compute units; very large batches use 32-row tiles so that the gate
-    // weights are streamed from L2 half as often.
     plan->gru_mt = 0;
-    for (int mt = (2 * d.max_batch <= 16384 ? 1 : 2); mt >= 1; --mt)
+    for (int mt = 1; mt >= 1; --mt)
         if (gru_lds_bytes(d, mt) <= lds_limit) {
             plan->gru_mt = mt;
             break;

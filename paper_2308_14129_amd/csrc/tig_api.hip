@@ -163,7 +163,7 @@ StepScratch step_scratch(const Dims &d, void *base)
     S.nbr_cnt = c.take<int32_t>(Q);
     S.staging = c.take<float>((size_t)2 * d.max_batch * d.M);
     for (int i = 0; i < 2; ++i) {
-        S.win[i] = c.take<WinDesc>((size_t)2 * d.max_batch);
+        S.win[i] = c.take<WinDesc>((size_t)2 * d.max_batch + 32);  // GRU tiles read whole 32-row slices
         S.n_win[i] = c.take<int32_t>(1);
     }
     S.bytes = c.off;
