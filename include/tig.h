@@ -208,8 +208,10 @@ TIG_API void tig_destroy(tig_ctx *ctx);
 TIG_API const char *tig_strerror(int status);
 TIG_API const char *tig_last_error(const tig_ctx *ctx);
 
-/* Number of kernels one tig_step enqueues and the dynamic LDS bytes of the two tile kernels
- * (for reports); any pointer may be NULL. */
+/* For reports: the number of kernels the last tig_step enqueued (3 when the previous step had
+ * selected this batch's winners ahead, 4 otherwise, 5 for batches above 4096 events; 0 before the
+ * first step) and the dynamic LDS bytes of the two tile kernels at their largest tile count.
+ * Any pointer may be NULL. */
 TIG_API int tig_launch_info(const tig_ctx *ctx, int32_t *kernels_per_step, int32_t *gru_lds_bytes,
                             int32_t *embed_lds_bytes);
 

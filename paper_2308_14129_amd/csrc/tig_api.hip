@@ -37,6 +37,7 @@ struct tig_ctx {
     int32_t ahead_count;
     int num_cus;
     int64_t cursor;    // end of the last batch stepped since the last reset / import
+    int last_launches; // kernels enqueued by the last tig_step
     int32_t *pos;
     hipEvent_t marks[kNumStepKernels + 1];
     bool have_marks;
@@ -479,6 +480,8 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     if (e != hipSuccess)
         return fail(ctx, TIG_EHIP, "tig_step launch", e);
     ctx->cursor = batch->first_eid + batch->count;
+    if (!marks)
+        ctx->last_launches = (ready ? 0 : (2 * batch->count <= 8192 ? 1 : 2)) + 3;
     if (a.next_count > 0) {
         ctx->ahead_valid = true;
         ctx->ahead_first = a.next_first_eid;
@@ -604,7 +607,7 @@ int tig_launch_info(const tig_ctx *ctx, int32_t *kernels_per_step, int32_t *gru_
     if (!ctx)
         return TIG_EINVAL;
     if (kernels_per_step)
-        *kernels_per_step = kNumStepKernels;
+        *kernels_per_step = ctx->last_launches;
     if (gru_lds_bytes)
         *gru_lds_bytes = ctx->plan.gru_lds;
     if (embed_lds_bytes)

@@ -166,6 +166,26 @@ def test_reset_export_import_roundtrip_and_determinism(c1):
     ctx.close()
 
 
+def test_launches_per_step(c1):
+    """A step whose batch continues the previous one runs three kernels (its winners were selected
+    inside the previous embedding launch); any other step selects them in a launch of its own."""
+    import torch
+    w, g, W = c1.w, c1.g, c1.W
+    ctx = make_ctx(w, g, W, "fp32")
+    assert ctx.launch_info()["kernels_per_step"] == 0
+    out = ctx.alloc_outputs(200)
+    flagged = ctx.alloc_outputs(200, inspect=True)
+    seen = []
+    for first, o in ((0, out), (200, out), (400, out), (800, out), (1000, flagged), (1200, out)):
+        neg = torch.from_numpy(S.make_negatives(w, g, first, 200)).to("cuda:0")
+        ctx.step(first, 200, neg, o)
+        seen.append(ctx.launch_info()["kernels_per_step"])
+    torch.cuda.synchronize()
+    # first step; two that continue; a gap; one that asks for the winner flags; one that continues
+    assert seen == [4, 3, 3, 4, 4, 3]
+    ctx.close()
+
+
 def test_untouched_rows_are_bit_identical(c1):
     import torch
     w, g, W = c1.w, c1.g, c1.W
