@@ -70,6 +70,9 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 256 MiB device copies (known HBM traffic) so that a "
                          "rocprofv3 --pmc run of this command can scale FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--order", default="update_first", choices=["update_first", "deferred"],
+                    help="message order of the step: apply this batch's messages before embedding "
+                         "(default, the headline configuration) or the previous batch's (training order)")
     ap.add_argument("--ceilings", action="store_true",
                     help="also time a plain 1 GiB device copy (read + write) and report the measured "
                          "HBM bandwidth of this GPU beside the published peak")
@@ -107,7 +110,7 @@ def main():
     assert len(batches) == total_steps, "workload too short for the requested steps"
 
     cfg = tig.make_config(w.mem_dim, w.time_dim, w.feat_dim, w.emb_dim, w.num_neighbors, w.num_heads, B,
-                          precision)
+                          precision, args.order)
     t0 = time.time()
     ctx = tig.TigContext(cfg, g.num_nodes, g.src, g.dst, g.ts, g.edge_feat, weights, device="cuda:0")
     torch.cuda.synchronize()
@@ -184,7 +187,7 @@ def main():
             for i in range(W_, W_ + n_cpu):
                 f, c = batches[i]
                 O.step(st, g.src, g.dst, g.ts, g.edge_feat, weights, f, c, negs[i].cpu().numpy(),
-                       w.num_neighbors, w.num_heads, index=ix)
+                       w.num_neighbors, w.num_heads, index=ix, deferred=args.order == "deferred")
             cpu_s = time.perf_counter() - t0
         cpu_events = sum(c for _, c in batches[W_:W_ + n_cpu])
         cpu = {"value": round(cpu_events / cpu_s, 1), "unit": "events/s", "cores": 1, "kind": "oracle",
@@ -236,7 +239,8 @@ def main():
                    "batch": B, "K": w.num_neighbors, "heads": w.num_heads, "mem_dim": w.mem_dim,
                    "time_dim": w.time_dim, "feat_dim": w.feat_dim, "emb_dim": w.emb_dim,
                    "precision": "bf16 hi/lo split MFMA operands, fp32 accumulate" if precision == "bf16"
-                   else "fp32 MFMA", "window_first_eid": first, "queries_per_event": 3},
+                   else "fp32 MFMA", "window_first_eid": first, "queries_per_event": 3,
+                   "message_order": args.order},
         "gpu_ms_per_step_events": round(gpu_ms / K, 5),
         "kernels_per_step": info["kernels_per_step"],
         "roofline": roofline,

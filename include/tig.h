@@ -59,6 +59,16 @@ typedef enum tig_precision {
  * width, E embedding width, K neighbours, H heads, B events per batch.
  * D_msg = 2M+T+F, d_a = M+T (must be divisible by H), d_kv = M+F+T.
  * Limits: 1 <= M,T,F,E <= 512; 1 <= K <= 64; H in {1,2,4}; 1 <= max_batch <= 65536. */
+/* Order of memory update and embedding inside a step (Sec. II-C describes the update-first data
+ * flow; the deferred order is the one a training loop uses so that a prediction never sees its
+ * own event through the memory). */
+typedef enum tig_message_order {
+    TIG_UPDATE_FIRST = 0, /* the step applies the messages of ITS batch, then embeds */
+    TIG_DEFERRED = 1      /* the step applies the messages of the PREVIOUS step's batch (built from the
+                             memory as it stands now), embeds, and keeps its own batch's last-message
+                             winners for the next step; tig_reset / tig_state_import drop what is kept */
+} tig_message_order;
+
 typedef struct tig_config {
     uint32_t struct_size;
     int32_t mem_dim;       /* M */
@@ -69,6 +79,7 @@ typedef struct tig_config {
     int32_t num_heads;     /* H */
     int32_t max_batch;     /* largest `count` tig_step will be given */
     int32_t precision;     /* tig_precision, fixed for the life of the context */
+    int32_t message_order; /* tig_message_order, fixed for the life of the context */
 } tig_config;
 
 /* The temporal interaction graph G = (V, E) of Sec. II-A: events (i, j, t) with a feature row

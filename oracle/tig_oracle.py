@@ -30,6 +30,15 @@ whole-step invariants (untouched rows, no future leakage, batch-order
 independence).  The architecture choices themselves (update-before-embed order,
 GRU variant, attention widths, empty-neighbourhood rule, initialisation) are
 fixed by this build, not by the paper: parity unpinned for those choices.
+
+Deferred order (step(..., deferred=True)): the step first applies the winners
+that the PREVIOUS step kept (messages built from the memory as it stands now),
+then embeds, then keeps its own batch's winners for the next step -- the order a
+training loop uses so that a prediction never sees its own event through the
+memory.  Pins: the memory after deferred steps over batches b1, b2 equals the
+memory after the update-first step over b1; with a GRU that keeps the state
+(z = 1) both orders give the same embeddings; the first step after a reset
+applies nothing.
 """
 from __future__ import annotations
 
@@ -235,6 +244,12 @@ def neighbours_bruteforce_batch(src, dst, ts, nodes, times, K):
 class OracleState:
     mem: np.ndarray          # float32 [N, M]   node memory (the memory module of Sec. II-C)
     last_update: np.ndarray  # float64 [N]      time of each node's last memory update
+    # deferred order only: winners (node, partner, event id, time) kept for the next step
+    pending: list = None
+
+    def __post_init__(self):
+        if self.pending is None:
+            self.pending = []
 
     @staticmethod
     def zeros(num_nodes, mem_dim):
@@ -243,10 +258,30 @@ class OracleState:
                            np.zeros(num_nodes, dtype=f64))
 
     def copy(self):
-        return OracleState(self.mem.copy(), self.last_update.copy())
+        st = OracleState(self.mem.copy(), self.last_update.copy())
+        st.pending = list(self.pending)
+        return st
+
+    def drop_pending(self):
+        """What a reset or a restore of the memory does to the winners kept by a deferred step."""
+        self.pending = []
 
 
-def step(state, src, dst, ts, edge_feat, W, first_eid, count, neg_dst, K, H, index=None):
+def apply_messages(state, winners, edge_feat, W):
+    """Message, state update and memory overwrite (MSG, UPD and M <- s_i(t) of Sec. II-C) for a
+    list of (node, partner, event id, time); every message reads the memory as it stands at
+    the start of the call."""
+    mem0 = state.mem.copy()
+    lu0 = state.last_update.copy()
+    for u, other, eid, t in winners:
+        phi = time_encode(t - lu0[u], W["time_w"], W["time_b"])
+        msg = np.concatenate([mem0[u], mem0[other], phi, edge_feat[eid]]).astype(f32)
+        h_new = gru_cell(msg, mem0[u], W["W_i"], W["b_i"], W["W_h"], W["b_h"])
+        state.mem[u] = h_new.astype(f32)
+        state.last_update[u] = t
+
+
+def step(state, src, dst, ts, edge_feat, W, first_eid, count, neg_dst, K, H, index=None, deferred=False):
     """One chronological batch step; updates `state` in place and returns a dict with
     emb [Q, E], score_pos [count], score_neg [count] (or None), the neighbour tables, and
     is_winner [2*count] (entry 2*b + role).  Q = 3*count with negatives, else 2*count; query
@@ -257,23 +292,20 @@ def step(state, src, dst, ts, edge_feat, W, first_eid, count, neg_dst, K, H, ind
     eids = np.arange(first_eid, first_eid + count)
     s_b, d_b, t_b = src[eids], dst[eids], ts[eids]
 
-    # 1. previous states are fetched from the memory as it stands at the start of the batch
-    mem0 = state.mem.copy()
-    lu0 = state.last_update.copy()
-
     # 2. aggregation: last message per node
     win = find_winners(s_b, d_b, t_b, eids)
     is_winner = np.zeros(2 * count, dtype=np.uint8)
-
-    # 3.-5. message, GRU update, overwrite memory
+    winners = []
     for u, (b, role) in win.items():
         is_winner[2 * b + role] = 1
         other = int(d_b[b]) if role == 0 else int(s_b[b])
-        phi = time_encode(t_b[b] - lu0[u], W["time_w"], W["time_b"])
-        msg = np.concatenate([mem0[u], mem0[other], phi, edge_feat[eids[b]]]).astype(f32)
-        h_new = gru_cell(msg, mem0[u], W["W_i"], W["b_i"], W["W_h"], W["b_h"])
-        state.mem[u] = h_new.astype(f32)
-        state.last_update[u] = t_b[b]
+        winners.append((int(u), other, int(eids[b]), float(t_b[b])))
+
+    # 1., 3.-5. previous states are fetched from the memory as it stands at the start of the
+    # step; message, GRU update, overwrite memory -- for this batch's winners, or in the deferred
+    # order for the winners the previous step kept (this batch's are kept for the next step)
+    apply_messages(state, state.pending if deferred else winners, edge_feat, W)
+    state.pending = winners if deferred else []
 
     # 6. neighbours of every query, from the whole graph, strictly before the query time
     if neg_dst is not None:

@@ -150,7 +150,7 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int n_gru_blocks, int K)
                 v = time_enc(w.time_w_rev[j - 2 * g.M], w.time_b_rev[j - 2 * g.M],
                              row_t[r] - a.lu[row_u[r]]);  // dt since the node's last update
             else if (j < g.Dmsg)
-                v = a.edge_feat[(size_t)(a.first_eid + row_e[r]) * g.F + (j - 2 * g.M - g.T)];
+                v = a.edge_feat[(size_t)(a.msg_first_eid + row_e[r]) * g.F + (j - 2 * g.M - g.T)];
         }
         P::store_a(X + (size_t)r * g.ldx, j, v);
     }
@@ -271,7 +271,7 @@ hipError_t launch_gru(const Dims &d, const LaunchPlan &plan, const PackedWeights
 {
     StepArgs aa = a;
     PackedWeights ww = pw;
-    const int entries = 2 * a.count;
+    const int entries = 2 * a.msg_count;  // 0 in a deferred step with nothing to apply: lookup only
     // Column split.  Every workgroup streams the gate weights of its columns from L2, which bounds
     // its run time, so when the 16-row tiles do not fill the device the columns of a tile are
     // split over as many workgroups as it takes at once.  Only the tiles below the winner count
@@ -281,7 +281,7 @@ hipError_t launch_gru(const Dims &d, const LaunchPlan &plan, const PackedWeights
     GruParams g = gru_params(d, mt);
     const int tiles = (entries + 16 * mt - 1) / (16 * mt);
     const int n_ct = d.Ng / 16;
-    int cs = 2 * cus / tiles;
+    int cs = tiles > 0 ? 2 * cus / tiles : 1;
     cs = cs < 1 ? 1 : (cs > n_ct ? n_ct : cs);
     g.tpp = (n_ct + cs - 1) / cs;
     g.cs = (n_ct + g.tpp - 1) / g.tpp;

@@ -39,7 +39,7 @@ hipError_t prepare_kernels(const Dims &d, const LaunchPlan &plan)
 }
 
 hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw,
-                       const StepArgs &a, hipStream_t s, hipEvent_t *marks, bool winners_ready)
+                       const StepArgs &a, const StepArgs *sel, hipStream_t s, hipEvent_t *marks)
 {
     hipError_t e;
     int mark = 0;
@@ -48,11 +48,11 @@ hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeight
     if ((e = stamp()) != hipSuccess)
         return e;
     bool needs_select = false;
-    if (!winners_ready && (e = launch_scatter(a, s, &needs_select)) != hipSuccess)
+    if (sel && (e = launch_scatter(*sel, s, &needs_select)) != hipSuccess)
         return e;
     if ((e = stamp()) != hipSuccess)
         return e;
-    if (needs_select && (e = launch_select(a, s)) != hipSuccess)
+    if (needs_select && (e = launch_select(*sel, s)) != hipSuccess)
         return e;
     if ((e = stamp()) != hipSuccess)
         return e;

@@ -159,8 +159,10 @@ hipError_t launch_select(const StepArgs &a, hipStream_t s)
 
 hipError_t launch_commit(const StepArgs &a, int M, hipStream_t s)
 {
-    const int clear_keys = winners_in_one_launch(a.count) ? 0 : 1;
-    hipLaunchKernelGGL(k_commit, dim3((2 * a.count + 3) / 4), dim3(256), 0, s, a, M, clear_keys);
+    if (a.msg_count <= 0)
+        return hipSuccess;
+    const int clear_keys = winners_in_one_launch(a.msg_count) ? 0 : 1;
+    hipLaunchKernelGGL(k_commit, dim3((2 * a.msg_count + 3) / 4), dim3(256), 0, s, a, M, clear_keys);
     return hipGetLastError();
 }
 

@@ -38,6 +38,10 @@ struct tig_ctx {
     int num_cus;
     int64_t cursor;    // end of the last batch stepped since the last reset / import
     int last_launches; // kernels enqueued by the last tig_step
+    // deferred order: win[cur] holds the winners of batch (pend_first, pend_count), not yet applied
+    bool pend_valid;
+    int64_t pend_first;
+    int32_t pend_count;
     int32_t *pos;
     hipEvent_t marks[kNumStepKernels + 1];
     bool have_marks;
@@ -77,6 +81,8 @@ int check_config(const tig_config *c)
         return TIG_EINVAL;
     if (c->precision != TIG_FP32 && c->precision != TIG_BF16_MFMA)
         return TIG_EINVAL;
+    if (c->message_order != TIG_UPDATE_FIRST && c->message_order != TIG_DEFERRED)
+        return TIG_EINVAL;
     return TIG_OK;
 }
 
@@ -106,6 +112,7 @@ Dims make_dims(const tig_config &c)
     d.Ep = round_up(d.E, 16);
     d.Ek = round_up(d.E, d.KB);
     d.max_batch = c.max_batch;
+    d.deferred = c.message_order == TIG_DEFERRED ? 1 : 0;
     return d;
 }
 
@@ -453,36 +460,81 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     a.score_pos = out->score_pos;
     a.score_neg = out->score_neg;
 
-    // Winner list of this batch: selected ahead by the previous step's embedding launch if that
-    // step guessed this batch (the selection depends on the event stream only, so state changes
-    // in between do not matter).  A caller that asks for the per-entry flags gets a fresh run.
-    const bool ready = ctx->ahead_valid && ctx->ahead_first == batch->first_eid &&
-                       ctx->ahead_count == batch->count && !out->is_winner && !marks;
-    if (ready)
-        ctx->cur ^= 1;
-    a.win = ctx->win[ctx->cur];
-    a.n_win = ctx->n_win[ctx->cur];
-    // Chronological training and evaluation pass consecutive batches of one size: guess that the
-    // next call continues where this one ends, and let the embedding launch select its winners.
-    // (The profiled step keeps every kernel to its own work.)
-    a.next_first_eid = batch->first_eid + batch->count;
-    a.next_count = 0;
-    a.next_win = ctx->win[ctx->cur ^ 1];
-    a.next_n_win = ctx->n_win[ctx->cur ^ 1];
-    if (!marks && a.next_first_eid < ctx->num_events) {
-        const int64_t left = ctx->num_events - a.next_first_eid;
-        const int32_t guess = left < batch->count ? (int32_t)left : batch->count;
-        if (embed_can_select_ahead(ctx->d, ctx->plan, a.roles, batch->count, guess))
-            a.next_count = guess;
+    a.next_is_winner = nullptr;
+    const bool one_launch = 2 * batch->count <= 8192;  // selection in one workgroup
+    StepArgs sel;
+    const StepArgs *selp = nullptr;
+    int launches = 0;
+    if (ctx->d.deferred) {
+        // Deferred order: the GRU and the memory overwrite apply the winners kept by the previous
+        // step; this step's winners go to the other list, selected by one extra workgroup of the
+        // embedding launch when it can carry it, else by a selection of its own up front (it
+        // reads the event stream only).
+        a.win = ctx->win[ctx->cur];
+        a.n_win = ctx->n_win[ctx->cur];
+        a.msg_first_eid = ctx->pend_first;
+        a.msg_count = ctx->pend_valid ? ctx->pend_count : 0;
+        a.is_winner = nullptr;
+        a.next_first_eid = batch->first_eid;
+        a.next_count = 0;
+        a.next_win = ctx->win[ctx->cur ^ 1];
+        a.next_n_win = ctx->n_win[ctx->cur ^ 1];
+        a.next_is_winner = out->is_winner;
+        if (!marks && embed_can_select_ahead(ctx->d, ctx->plan, a.roles, batch->count, batch->count)) {
+            a.next_count = batch->count;
+        } else {
+            sel = a;
+            sel.win = a.next_win;
+            sel.n_win = a.next_n_win;
+            sel.is_winner = out->is_winner;
+            selp = &sel;
+            launches += one_launch ? 1 : 2;
+        }
+        launches += a.msg_count > 0 ? 3 : 2;
+    } else {
+        // Winner list of this batch: selected ahead by the previous step's embedding launch if that
+        // step guessed this batch (the selection depends on the event stream only, so state changes
+        // in between do not matter).  A caller that asks for the per-entry flags gets a fresh run.
+        const bool ready = ctx->ahead_valid && ctx->ahead_first == batch->first_eid &&
+                           ctx->ahead_count == batch->count && !out->is_winner && !marks;
+        if (ready)
+            ctx->cur ^= 1;
+        a.win = ctx->win[ctx->cur];
+        a.n_win = ctx->n_win[ctx->cur];
+        a.msg_first_eid = batch->first_eid;
+        a.msg_count = batch->count;
+        // Chronological training and evaluation pass consecutive batches of one size: guess that the
+        // next call continues where this one ends, and let the embedding launch select its winners.
+        // (The profiled step keeps every kernel to its own work.)
+        a.next_first_eid = batch->first_eid + batch->count;
+        a.next_count = 0;
+        a.next_win = ctx->win[ctx->cur ^ 1];
+        a.next_n_win = ctx->n_win[ctx->cur ^ 1];
+        if (!marks && a.next_first_eid < ctx->num_events) {
+            const int64_t left = ctx->num_events - a.next_first_eid;
+            const int32_t guess = left < batch->count ? (int32_t)left : batch->count;
+            if (embed_can_select_ahead(ctx->d, ctx->plan, a.roles, batch->count, guess))
+                a.next_count = guess;
+        }
+        if (!ready) {
+            selp = &a;
+            launches += one_launch ? 1 : 2;
+        }
+        launches += 3;
     }
     ctx->ahead_valid = false;
-    const hipError_t e = launch_step(ctx->d, ctx->plan, ctx->pw, a, ctx->stream, marks, ready);
+    const hipError_t e = launch_step(ctx->d, ctx->plan, ctx->pw, a, selp, ctx->stream, marks);
     if (e != hipSuccess)
         return fail(ctx, TIG_EHIP, "tig_step launch", e);
     ctx->cursor = batch->first_eid + batch->count;
     if (!marks)
-        ctx->last_launches = (ready ? 0 : (2 * batch->count <= 8192 ? 1 : 2)) + 3;
-    if (a.next_count > 0) {
+        ctx->last_launches = launches;
+    if (ctx->d.deferred) {
+        ctx->cur ^= 1;  // the list just selected is the one the next step applies
+        ctx->pend_valid = true;
+        ctx->pend_first = batch->first_eid;
+        ctx->pend_count = batch->count;
+    } else if (a.next_count > 0) {
         ctx->ahead_valid = true;
         ctx->ahead_first = a.next_first_eid;
         ctx->ahead_count = a.next_count;
@@ -523,6 +575,17 @@ int tig_step_profiled(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, 
     return TIG_OK;
 }
 
+// Deferred order: forgets the winners kept for the next step.  A selection of more than 4096 events
+// left its keys in the per-node array (the overwrite that would have cleared them never runs).
+static hipError_t drop_pending(tig_ctx *ctx)
+{
+    hipError_t e = hipSuccess;
+    if (ctx->pend_valid && 2 * ctx->pend_count > 8192)
+        e = launch_fill_zero(ctx->key, sizeof(unsigned long long) * (size_t)ctx->num_nodes, ctx->stream);
+    ctx->pend_valid = false;
+    return e;
+}
+
 int tig_reset(tig_ctx *ctx)
 {
     if (!ctx)
@@ -530,6 +593,8 @@ int tig_reset(tig_ctx *ctx)
     hipError_t e = launch_fill_zero(ctx->mem, sizeof(float) * (size_t)ctx->num_nodes * ctx->d.M, ctx->stream);
     if (e == hipSuccess)
         e = launch_fill_zero(ctx->lu, sizeof(double) * (size_t)ctx->num_nodes, ctx->stream);
+    if (e == hipSuccess)
+        e = drop_pending(ctx);
     if (e != hipSuccess)
         return fail(ctx, TIG_EHIP, "tig_reset", e);
     ctx->cursor = 0;
@@ -567,6 +632,8 @@ int tig_state_import(tig_ctx *ctx, const float *mem_in, const double *last_updat
                            hipMemcpyDefault, ctx->stream);
     if (e == hipSuccess)
         e = hipStreamSynchronize(ctx->stream);
+    if (e == hipSuccess)
+        e = drop_pending(ctx);
     if (e != hipSuccess)
         return fail(ctx, TIG_EHIP, "tig_state_import", e);
     ctx->cursor = 0;

@@ -37,6 +37,7 @@ struct Dims {
     int Ep;       // E padded to 16 (output cols)
     int Ek;       // E padded to KB (k depth of the E-wide layers)
     int max_batch;
+    int deferred;  // message order: 0 update first, 1 deferred
 };
 
 // Prepared (folded, padded, lane-ordered) weights in `persistent`.
@@ -83,6 +84,10 @@ struct StepArgs {
     int32_t count;
     int32_t roles;  // 2 | 3
     const int32_t *neg;
+    // the batch whose winners (`win`) feed the GRU and the memory overwrite: this batch, or the
+    // previous step's in the deferred order (msg_count 0: nothing to apply)
+    int64_t msg_first_eid;
+    int32_t msg_count;
     // intermediates (device)
     int32_t *nbr_node, *nbr_eid, *nbr_cnt;
     double *nbr_ts;
@@ -96,6 +101,7 @@ struct StepArgs {
     int32_t next_count;
     WinDesc *next_win;
     int32_t *next_n_win;
+    uint8_t *next_is_winner;  // may be NULL
     // outputs
     float *emb, *score_pos, *score_neg;
 };
@@ -145,9 +151,10 @@ bool embed_can_select_ahead(const Dims &d, const LaunchPlan &plan, int roles, in
 hipError_t prepare_kernels(const Dims &d, const LaunchPlan &plan);
 constexpr int kNumStepKernels = 5;
 // `marks`: NULL, or kNumStepKernels + 1 events recorded before the first and after every kernel.
-// `winners_ready`: a.win / a.n_win already hold the winners of this batch.
+// `sel`: NULL, or the arguments of a last-message selection to run first (its first_eid / count /
+// win / n_win / is_winner name the batch and where the winners go).
 hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw,
-                       const StepArgs &a, hipStream_t s, hipEvent_t *marks, bool winners_ready);
+                       const StepArgs &a, const StepArgs *sel, hipStream_t s, hipEvent_t *marks);
 hipError_t launch_fill_zero(void *ptr, size_t bytes, hipStream_t s);
 
 }  // namespace tig

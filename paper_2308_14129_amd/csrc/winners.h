@@ -37,7 +37,7 @@ __host__ __device__ inline WinnersJob winners_job(const StepArgs &a, bool follow
     j.count = following ? a.next_count : a.count;
     j.win = following ? a.next_win : a.win;
     j.n_win = following ? a.next_n_win : a.n_win;
-    j.is_winner = following ? nullptr : a.is_winner;
+    j.is_winner = following ? a.next_is_winner : a.is_winner;
     return j;
 }
 

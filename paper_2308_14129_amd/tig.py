@@ -21,6 +21,8 @@ TIG_EINVAL, TIG_ERANGE, TIG_EUNSORTED, TIG_ESELFLOOP, TIG_ENOSPACE, TIG_EHIP, TI
     -1, -2, -3, -4, -5, -6, -7, -8)
 TIG_FP32, TIG_BF16_MFMA = 0, 1
 PRECISIONS = {"fp32": TIG_FP32, "bf16": TIG_BF16_MFMA}
+TIG_UPDATE_FIRST, TIG_DEFERRED = 0, 1
+MESSAGE_ORDERS = {"update_first": TIG_UPDATE_FIRST, "deferred": TIG_DEFERRED}
 
 WEIGHT_NAMES = ("time_w", "time_b", "W_i", "b_i", "W_h", "b_h", "W_Q", "b_Q", "W_K", "b_K", "W_V",
                 "b_V", "W_O", "b_O", "W_m1", "b_m1", "W_m2", "b_m2", "W_d1", "b_d1", "w_d2", "b_d2")
@@ -29,7 +31,8 @@ WEIGHT_NAMES = ("time_w", "time_b", "W_i", "b_i", "W_h", "b_h", "W_Q", "b_Q", "W
 class tig_config(Structure):
     _fields_ = [("struct_size", c_uint32), ("mem_dim", c_int32), ("time_dim", c_int32),
                 ("feat_dim", c_int32), ("emb_dim", c_int32), ("num_neighbors", c_int32),
-                ("num_heads", c_int32), ("max_batch", c_int32), ("precision", c_int32)]
+                ("num_heads", c_int32), ("max_batch", c_int32), ("precision", c_int32),
+                ("message_order", c_int32)]
 
 
 class tig_graph(Structure):
@@ -98,10 +101,11 @@ def load_library() -> ctypes.CDLL:
 
 
 def make_config(mem_dim, time_dim, feat_dim, emb_dim, num_neighbors, num_heads, max_batch,
-                precision="fp32") -> tig_config:
+                precision="fp32", message_order="update_first") -> tig_config:
     prec = PRECISIONS[precision] if isinstance(precision, str) else int(precision)
+    order = MESSAGE_ORDERS[message_order] if isinstance(message_order, str) else int(message_order)
     return tig_config(ctypes.sizeof(tig_config), mem_dim, time_dim, feat_dim, emb_dim, num_neighbors,
-                      num_heads, max_batch, prec)
+                      num_heads, max_batch, prec, order)
 
 
 def workspace_bytes(cfg: tig_config, num_nodes: int, num_events: int):

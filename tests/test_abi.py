@@ -28,7 +28,7 @@ def test_header_symbols_are_exported(lib):
 
 def test_struct_sizes_match_header_layout():
     from paper_2308_14129_amd import tig
-    assert ctypes.sizeof(tig.tig_config) == 36
+    assert ctypes.sizeof(tig.tig_config) == 40
     assert ctypes.sizeof(tig.tig_graph) == 56
     assert ctypes.sizeof(tig.tig_weights) == 8 + 22 * 8
     assert ctypes.sizeof(tig.tig_batch) == 24

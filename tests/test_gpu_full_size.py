@@ -26,6 +26,11 @@ def c5_ctx(c5):
     ctxs = {}
 
     def get(precision):
+        if precision == "close":        # make room for a context of another kind
+            for c in ctxs.values():
+                c.close()
+            ctxs.clear()
+            return None
         if precision not in ctxs:
             for c in ctxs.values():     # one 30 GB context at a time
                 c.close()
@@ -47,6 +52,14 @@ def test_c5_steps_match_oracle(c5, c5_ctx, precision):
     # the step before selected ahead
     first, bs = window(c5.w, 0.7, 3)
     run(c5, precision, bs, locked=False, warm_at=first, ctx=c5_ctx(precision), flags=False)
+
+
+def test_c5_deferred_order(c5, c5_ctx):
+    c5_ctx("close")
+    ctx = make_ctx(c5.w, c5.g, c5.W, "bf16", order="deferred")
+    first, bs = window(c5.w, 0.3, 3)
+    run(c5, "bf16", bs, locked=False, warm_at=first, ctx=ctx, order="deferred", flags=False)
+    ctx.close()
 
 
 def test_c5_sampled_queries_against_bruteforce_definition(c5, c5_ctx):

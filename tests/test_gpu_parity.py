@@ -15,12 +15,12 @@ pytestmark = pytest.mark.gpu
 TOL = {"fp32": 1e-4, "bf16": 2e-2}
 
 
-def make_ctx(w, g, W, precision, max_batch=None):
+def make_ctx(w, g, W, precision, max_batch=None, order="update_first"):
     import torch
     from paper_2308_14129_amd import tig
     assert torch.cuda.is_available()
     cfg = tig.make_config(w.mem_dim, w.time_dim, w.feat_dim, w.emb_dim, w.num_neighbors, w.num_heads,
-                          max_batch or w.batch_size, precision)
+                          max_batch or w.batch_size, precision, order)
     return tig.TigContext(cfg, g.num_nodes, g.src, g.dst, g.ts, g.edge_feat, W, device="cuda:0")
 
 
@@ -34,17 +34,21 @@ class Bundle:
         self.ix = O.NeighbourIndex(self.g.num_nodes, self.g.src, self.g.dst, self.g.ts)
 
 
-def run(bundle, precision, batches, locked, warm_at=None, with_neg=True, ctx=None, flags=True):
+def run(bundle, precision, batches, locked, warm_at=None, with_neg=True, ctx=None, flags=True,
+        order="update_first"):
     """Runs the batches on both sides.  locked=True loads the oracle's state into the GPU before
     every step (step-locked parity); otherwise both sides run freely from the same start, which
     is the state after a reset or, with warm_at, the seeded warm state of a mid-stream window.
     flags=False leaves out the per-entry winner flags, as a training loop does: only then does a
-    step use the winners that the previous step's embedding launch selected ahead."""
+    step use the winners that the previous step's embedding launch selected ahead.
+    order="deferred": both sides apply the previous step's winners before embedding (a state
+    import drops what is kept, on both sides)."""
     import torch
     w, g, W, ix = bundle.w, bundle.g, bundle.W, bundle.ix
     own = ctx is None
+    deferred = order == "deferred"
     if own:
-        ctx = make_ctx(w, g, W, precision, max(c for _, c in batches))
+        ctx = make_ctx(w, g, W, precision, max(c for _, c in batches), order)
     if warm_at is None:
         st = O.OracleState.zeros(g.num_nodes, w.mem_dim)
         ctx.reset()
@@ -57,8 +61,9 @@ def run(bundle, precision, batches, locked, warm_at=None, with_neg=True, ctx=Non
         neg = S.make_negatives(w, g, first, count) if with_neg else None
         if locked:
             ctx.state_import(st.mem, st.last_update)
+            st.drop_pending()
         ref = O.step(st, g.src, g.dst, g.ts, g.edge_feat, W, first, count, neg, w.num_neighbors,
-                     w.num_heads, index=ix)
+                     w.num_heads, index=ix, deferred=deferred)
         out = ctx.alloc_outputs(count, with_neg=with_neg, inspect=True)
         if not flags:
             out.is_winner = None
@@ -133,6 +138,25 @@ def test_c1_wrong_guesses_of_the_next_batch(c1):
     ctx.close()
 
 
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_c1_deferred_order_whole_stream(c1, precision):
+    # the step applies the previous batch's winners, embeds, keeps its own; incl. the short last batch
+    bs = list(S.batches(c1.w.num_events, 136))
+    run(c1, precision, bs, locked=False, order="deferred")
+    run(c1, precision, bs[:8], locked=False, order="deferred", flags=False, with_neg=False)
+
+
+def test_c1_deferred_order_gaps_sizes_and_imports(c1):
+    # batches of changing size with gaps; a state import in between drops what is kept
+    ctx = make_ctx(c1.w, c1.g, c1.W, "fp32", 300, "deferred")
+    run(c1, "fp32", [(0, 200), (200, 200), (500, 300), (1000, 7), (1007, 7), (1014, 300)], locked=False,
+        ctx=ctx, order="deferred")
+    run(c1, "fp32", [(3000, 100), (3100, 100), (3200, 100)], locked=False, warm_at=3000, ctx=ctx,
+        order="deferred")
+    run(c1, "fp32", [(4000, 100), (4100, 100)], locked=True, warm_at=4000, ctx=ctx, order="deferred")
+    ctx.close()
+
+
 # ------------------------------------------------------------------------------------- C2
 
 
@@ -186,6 +210,7 @@ def test_c3_batch_above_the_fused_selection_limit(c3):
     first, bs = window(c3.w, 0.5, 1, 4096)
     seq = bs + [(first + 4096, 5000), (first + 9096, 3000), (first + 12096, 3000)]
     run(c3, "fp32", seq, locked=False, warm_at=first, flags=False)
+    run(c3, "fp32", seq, locked=False, warm_at=first, order="deferred")
 
 
 # ------------------------------------------------------------------------------------- C4

@@ -235,3 +235,72 @@ def test_reset_state_is_zero():
     st = O.OracleState.zeros(5, 3)
     assert st.mem.dtype == np.float32 and st.last_update.dtype == np.float64
     assert not st.mem.any() and not st.last_update.any()
+
+
+# ------------------------------------------------------------------------ deferred order
+
+
+def _c1_setup():
+    w = S.WORKLOADS["c1_tiny"].scaled(num_events=1200)
+    g = S.make_graph(w)
+    W = S.make_weights(w)
+    return w, g, W
+
+
+def test_deferred_memory_equals_update_first_of_the_previous_batch():
+    """After deferred steps over batches b1, b2 the memory is what the update-first step over b1
+    leaves (b2's messages are still waiting), and after b3 what update-first over b1, b2 leaves;
+    the first deferred step after a reset applies nothing."""
+    w, g, W = _c1_setup()
+    bs = [(200, 100), (300, 100), (400, 150)]
+    a = O.OracleState(*S.make_warm_state(w, g, 200))
+    b = a.copy()
+    mem_start, lu_start = a.mem.copy(), a.last_update.copy()
+    kw = dict(K=w.num_neighbors, H=w.num_heads)
+    O.step(a, g.src, g.dst, g.ts, g.edge_feat, W, *bs[0], None, deferred=True, **kw)
+    assert np.array_equal(a.mem, mem_start) and np.array_equal(a.last_update, lu_start)
+    assert len(a.pending) > 0
+    for k in (1, 2):
+        O.step(a, g.src, g.dst, g.ts, g.edge_feat, W, *bs[k], None, deferred=True, **kw)
+        O.step(b, g.src, g.dst, g.ts, g.edge_feat, W, *bs[k - 1], None, **kw)
+        assert np.array_equal(a.mem, b.mem) and np.array_equal(a.last_update, b.last_update)
+    # what is kept are the winners of the last batch: one per distinct node, its last occurrence
+    nodes = {u for u, _, _, _ in a.pending}
+    first, count = bs[2]
+    assert nodes == set(g.src[first:first + count]) | set(g.dst[first:first + count])
+    for u, other, eid, t in a.pending:
+        later = [e for e in range(eid + 1, first + count) if g.src[e] == u or g.dst[e] == u]
+        assert not later and t == g.ts[eid] and {u, other} == {int(g.src[eid]), int(g.dst[eid])}
+
+
+def test_deferred_embeds_from_the_memory_the_applied_messages_leave():
+    """The deferred step over b2 embeds from the memory that the update-first step over b1 leaves.
+    An update-first step over b2 on that memory, with a GRU whose update gate is stuck at 1 (so
+    its own update keeps every row), produces exactly the embedding function on that memory."""
+    w, g, W = _c1_setup()
+    b1, b2 = (200, 100), (300, 100)
+    neg = S.make_negatives(w, g, *b2)
+    kw = dict(K=w.num_neighbors, H=w.num_heads)
+    a = O.OracleState(*S.make_warm_state(w, g, 200))
+    ref = a.copy()
+    O.step(a, g.src, g.dst, g.ts, g.edge_feat, W, *b1, None, deferred=True, **kw)
+    out_a = O.step(a, g.src, g.dst, g.ts, g.edge_feat, W, *b2, neg, deferred=True, **kw)
+    O.step(ref, g.src, g.dst, g.ts, g.edge_feat, W, *b1, None, **kw)
+    keep = {k: v.copy() for k, v in W.items()}
+    keep["b_i"][w.mem_dim:2 * w.mem_dim] = 400.0        # z = sigmoid(+large) = 1  ->  h' = h
+    mem_before = ref.mem.copy()
+    out_r = O.step(ref, g.src, g.dst, g.ts, g.edge_feat, keep, *b2, neg, **kw)
+    assert np.array_equal(ref.mem, mem_before)
+    for name in ("emb", "score_pos", "score_neg", "nbr_node", "nbr_eid", "nbr_cnt", "is_winner"):
+        assert np.array_equal(out_a[name], out_r[name]), name
+
+
+def test_dropping_what_is_kept():
+    w, g, W = _c1_setup()
+    kw = dict(K=w.num_neighbors, H=w.num_heads)
+    a = O.OracleState(*S.make_warm_state(w, g, 200))
+    O.step(a, g.src, g.dst, g.ts, g.edge_feat, W, 200, 100, None, deferred=True, **kw)
+    a.drop_pending()
+    before = a.mem.copy()
+    O.step(a, g.src, g.dst, g.ts, g.edge_feat, W, 300, 100, None, deferred=True, **kw)
+    assert np.array_equal(a.mem, before)
