@@ -113,7 +113,9 @@ __device__ inline float dpp_or_zero(float v)
 // The two cross-row steps of wave_sum_uniform for several values at once, as fused DPP adds: rows
 // outside the row mask keep their value, which the compiler does not express in one instruction.
 // The leading s_nop covers the two wait states a DPP read needs after a vector-ALU write of the
-// same register; inside the block two instructions on one register are far enough apart.
+// same register, and the trailing one keeps whatever the compiler places next (it does not see
+// inside the block) clear of the last results; inside the block two instructions on one register
+// are far enough apart.
 __device__ inline void add_row_bcasts(float &a, float &b)
 {
     asm volatile("s_nop 1\n\t"
@@ -121,7 +123,8 @@ __device__ inline void add_row_bcasts(float &a, float &b)
                  "v_add_f32_dpp %1, %1, %1 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
                  "s_nop 0\n\t"
                  "v_add_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
-                 "v_add_f32_dpp %1, %1, %1 row_bcast:31 row_mask:0xc bank_mask:0xf"
+                 "v_add_f32_dpp %1, %1, %1 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+                 "s_nop 1"
                  : "+v"(a), "+v"(b));
 }
 
@@ -135,7 +138,8 @@ __device__ inline void add_row_bcasts(float &a, float &b, float &c, float &d)
                  "v_add_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
                  "v_add_f32_dpp %1, %1, %1 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
                  "v_add_f32_dpp %2, %2, %2 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
-                 "v_add_f32_dpp %3, %3, %3 row_bcast:31 row_mask:0xc bank_mask:0xf"
+                 "v_add_f32_dpp %3, %3, %3 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+                 "s_nop 1"
                  : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
 }
 
