@@ -101,7 +101,6 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     constexpr int kEmbedThreads = EmbedShape<NPL, H>::kThreads;
     constexpr int kEmbedWaves = EmbedShape<NPL, H>::kWaves;
     constexpr int ROWS = 16 * MT;
-    constexpr int RPW = (ROWS + kEmbedWaves - 1) / kEmbedWaves;  // rows per wavefront in phase C
     constexpr int KC = NPL >= 8 ? 5 : (NPL == 4 ? 10 : 16);      // neighbour rows in flight
     constexpr int NPHI = NPL;  // registers that may hold time-encoding dims (T <= 64 * NPL)
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -119,6 +118,7 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     int *row_node = row_cnt + ROWS;           // [ROWS]
     double *row_t = (double *)(row_node + ROWS);  // [ROWS] query time
     double *tw_tab = row_t + ROWS;                // [T][2] time-encoding (w_rev, b_rev)
+    int *next_row = (int *)(tw_tab + 2 * p.T);    // [1] row counter of phase C
 
     const int lane = lane_id();
     const int wave = wave_id();
@@ -147,6 +147,8 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
         row_cnt[r] = cnt;
         row_t[r] = t;
     }
+    if (threadIdx.x == 0)
+        *next_row = 0;
     for (int j = threadIdx.x; j < p.T; j += kEmbedThreads) {
         tw_tab[2 * j] = w.time_w_rev[j];
         tw_tab[2 * j + 1] = w.time_b_rev[j];
@@ -199,34 +201,48 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
             offm[n] = jj < 0 ? 0xffffffffu : (uint32_t)jj * 4u;
         }
         const uint32_t m_bytes = (uint32_t)cM * 4u, f_bytes = (uint32_t)cF * 4u;
-        // neighbour tables of this wavefront's rows: slot k lives in lane k
-        int32_t nb_v[RPW], nb_e[RPW];
-        double nb_dt[RPW];
-#pragma unroll
-        for (int i = 0; i < RPW; ++i) {
-            const int r = wave + i * kEmbedWaves;
-            nb_v[i] = 0;
-            nb_e[i] = 0;
-            nb_dt[i] = 0.0;
+        // Rows are handed out through an LDS counter, heaviest roles first (sources, destinations,
+        // negatives), so that wavefronts with short rows take more of them.  The neighbour table
+        // of a row (slot k lives in lane k) is fetched when the row before it is started.
+        auto grab = [&]() -> int {
+            int r = 0;
+            if (lane == 0)
+                r = atomicAdd(next_row, 1);
+            return __builtin_amdgcn_readfirstlane(r);
+        };
+        auto load_nb = [&](int r, int32_t &v, int32_t &e, double &dt) {
+            v = 0;
+            e = 0;
+            dt = 0.0;
             if (r < ROWS) {
                 const int q = row_q[r];
                 if (q >= 0 && lane < row_cnt[r]) {
-                    nb_v[i] = a.nbr_node[(size_t)q * p.K + lane];
-                    nb_e[i] = a.nbr_eid[(size_t)q * p.K + lane];
-                    nb_dt[i] = row_t[r] - a.nbr_ts[(size_t)q * p.K + lane];
+                    v = a.nbr_node[(size_t)q * p.K + lane];
+                    e = a.nbr_eid[(size_t)q * p.K + lane];
+                    dt = row_t[r] - a.nbr_ts[(size_t)q * p.K + lane];
                 }
             }
-        }
-#pragma unroll
-        for (int i = 0; i < RPW; ++i) {
-            const int r = wave + i * kEmbedWaves;
-            if (r >= ROWS)
-                break;
-            if (__builtin_amdgcn_readfirstlane(row_q[r]) < 0)
+        };
+        int r = grab();
+        int32_t nb_v1, nb_e1, nb_v2, nb_e2;
+        double nb_dt1, nb_dt2;
+        load_nb(r, nb_v2, nb_e2, nb_dt2);
+#pragma unroll 1
+        while (r < ROWS) {
+            const int32_t nb_vc = nb_v2, nb_ec = nb_e2;
+            const double nb_dtc = nb_dt2;
+            const int r_next = grab();
+            load_nb(r_next, nb_v1, nb_e1, nb_dt1);
+            const int r_cur = r;
+            r = r_next;
+            nb_v2 = nb_v1;
+            nb_e2 = nb_e1;
+            nb_dt2 = nb_dt1;
+            if (__builtin_amdgcn_readfirstlane(row_q[r_cur]) < 0)
                 continue;
-            const int cnt = __builtin_amdgcn_readfirstlane(row_cnt[r]);
-            const float *qrow = (const float *)(rowbuf + (size_t)r * p.row_bytes);
-            char *arow = rowbuf + (size_t)r * p.row_bytes;
+            const int cnt = __builtin_amdgcn_readfirstlane(row_cnt[r_cur]);
+            const float *qrow = (const float *)(rowbuf + (size_t)r_cur * p.row_bytes);
+            char *arow = rowbuf + (size_t)r_cur * p.row_bytes;
             float qv[H][NPL], accv[H][NPL];
             float mx[H], den[H];
 #pragma unroll
@@ -249,8 +265,8 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                     const int k = c0 + kk;
                     mix[kk] = 0.0f;
                     if (k < cnt) {  // scalar
-                        const int32_t v = __builtin_amdgcn_readlane(nb_v[i], k & 63);
-                        const int32_t e = __builtin_amdgcn_readlane(nb_e[i], k & 63);
+                        const int32_t v = __builtin_amdgcn_readlane(nb_vc, k & 63);
+                        const int32_t e = __builtin_amdgcn_readlane(nb_ec, k & 63);
                         const __amdgpu_buffer_rsrc_t rm = __builtin_amdgcn_make_buffer_rsrc(
                             (void *)(a.mem + (size_t)v * cM), 0, (int)m_bytes, kBufferFlags);
                         const __amdgpu_buffer_rsrc_t re = __builtin_amdgcn_make_buffer_rsrc(
@@ -290,7 +306,7 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                             for (int h = 0; h < H; ++h)
                                 part[u][h] = 0.0f;
                             if (k2 + u < KC && k < cnt) {  // scalar
-                                const double dt = readlane_f64(nb_dt[i], k & 63);
+                                const double dt = readlane_f64(nb_dtc, k & 63);
 #pragma unroll
                                 for (int n = 0; n < NPL; ++n) {
                                     if ((mem_regs & feat_regs) >> n & 1)  // scalar
@@ -654,7 +670,7 @@ const void *embed_kernel(const Dims &d, int mt)
 int embed_lds_bytes(const Dims &d, int mt)
 {
     const EmbedParams p = embed_params(d, mt, 3);
-    return p.off_meta + 16 * mt * (3 * 4 + 8) + d.T * 16;
+    return p.off_meta + 16 * mt * (3 * 4 + 8) + d.T * 16 + 16;
 }
 
 // 16-row tiles per workgroup for a batch of `count` events: a workgroup's latency grows with its
