@@ -41,11 +41,12 @@ def test_strerror_and_host_side_validation(lib):
     assert b"sorted" in lib.tig_strerror(tig.TIG_EUNSORTED) or b"decreasing" in lib.tig_strerror(tig.TIG_EUNSORTED)
     cfg = tig.make_config(32, 16, 16, 32, 10, 2, 200)
     p, s = tig.workspace_bytes(cfg, 1000, 10000)
+    assert tig.workspace_bytes(tig.make_config(32, 16, 16, 32, 10, 2, 200, "bf16", "deferred"), 1000, 10000)[0] > 0
     # persistent holds at least: events, features, adjacency, memory
     assert p >= 10000 * (4 + 4 + 8 + 16 * 4) + 2 * 10000 * 16 + 1000 * 32 * 4
     assert s > 0
     for bad in (dict(num_heads=3), dict(num_neighbors=65), dict(mem_dim=0), dict(max_batch=0),
-                dict(mem_dim=33, time_dim=16, num_heads=2), dict(precision=7)):
+                dict(mem_dim=33, time_dim=16, num_heads=2), dict(precision=7), dict(message_order=2)):
         kw = dict(mem_dim=32, time_dim=16, feat_dim=16, emb_dim=32, num_neighbors=10, num_heads=2,
                   max_batch=200, precision="fp32")
         kw.update(bad)
