@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # HBM bytes per launch of the dominant kernel (k_embed), from two rocprofv3 --pmc runs (FETCH_SIZE,
 # WRITE_SIZE), each scaled by what the counter reads for a plain 256 MiB device copy; see
 # profiles/hbm_traffic_c5_gpu_partition_bf16.md.  Only known for the combinations measured.
-MEASURED_TRAFFIC_BYTES = {("c5_gpu_partition", "bf16", 4000): 17.4e6}
+MEASURED_TRAFFIC_BYTES = {("c5_gpu_partition", "bf16", 4000): 17.2e6}
 
 
 def log(msg):
