@@ -154,14 +154,38 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
         tw_tab[2 * j + 1] = w.time_b_rev[j];
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < ROWS * p.Mq; idx += kEmbedThreads) {
-        const int r = idx / p.Mq;
-        const int j = idx - r * p.Mq;
-        const int u = row_node[r];
-        float v = 0.0f;
-        if (u >= 0 && j < p.M)
-            v = a.mem[(size_t)u * p.M + j];
-        P::store_a(rowbuf + (size_t)r * p.row_bytes + mem_off, j, v);
+    {
+        // one wavefront per row, lanes along the row (no index arithmetic per element); the loads
+        // of all of a wavefront's rows are requested before the first is stored
+        constexpr int kRowsPerWave = (ROWS + kEmbedWaves - 1) / kEmbedWaves;
+        constexpr int kAhead = 2;  // 128 floats of a row per lane pair of loads
+        float v[kRowsPerWave][kAhead];
+#pragma unroll
+        for (int i = 0; i < kRowsPerWave; ++i) {
+            const int r = wave + i * kEmbedWaves;
+            const int node = r < ROWS ? row_node[r] : -1;
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) {
+                const int j = lane + kWave * u;
+                v[i][u] = 0.0f;
+                if (node >= 0 && j < p.M)
+                    v[i][u] = a.mem[(size_t)node * p.M + j];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kRowsPerWave; ++i) {
+            const int r = wave + i * kEmbedWaves;
+            if (r < ROWS) {
+                char *dst = rowbuf + (size_t)r * p.row_bytes + mem_off;
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u)
+                    if (lane + kWave * u < p.Mq)
+                        P::store_a(dst, lane + kWave * u, v[i][u]);
+                const int node = row_node[r];
+                for (int j = lane + kWave * kAhead; j < p.Mq; j += kWave)  // rows beyond 128 floats
+                    P::store_a(dst, j, node >= 0 && j < p.M ? a.mem[(size_t)node * p.M + j] : 0.0f);
+            }
+        }
     }
     __syncthreads();
 

@@ -136,23 +136,49 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int n_gru_blocks, int K)
     __syncthreads();
     TIG_MARK(1);
 
-    // 2. message rows from batch-start memory; rows beyond n_rows are zero
-    for (int idx = threadIdx.x; idx < EC * g.Kg; idx += kGruThreads) {
-        const int r = idx / g.Kg;
-        const int j = idx - r * g.Kg;
-        float v = 0.0f;
-        if (r < n_rows) {
-            if (j < g.M)
-                v = a.mem[(size_t)row_u[r] * g.M + j];
-            else if (j < 2 * g.M)
-                v = a.mem[(size_t)row_o[r] * g.M + (j - g.M)];
-            else if (j < 2 * g.M + g.T)
-                v = time_enc(w.time_w_rev[j - 2 * g.M], w.time_b_rev[j - 2 * g.M],
-                             row_t[r] - a.lu[row_u[r]]);  // dt since the node's last update
-            else if (j < g.Dmsg)
-                v = a.edge_feat[(size_t)(a.msg_first_eid + row_e[r]) * g.F + (j - 2 * g.M - g.T)];
+    // 2. message rows from batch-start memory; rows beyond n_rows are zero.  One wavefront per
+    //    row, lanes along the row (no index arithmetic per element); all loads of a row are
+    //    requested before its first element is converted and stored.
+    for (int r = wave; r < EC; r += kGruWaves) {
+        const bool live = r < n_rows;
+        const int u = row_u[r], o = row_o[r];
+        const float *self = a.mem + (size_t)u * g.M;
+        const float *other = a.mem + (size_t)o * g.M;
+        const float *feat = a.edge_feat + (size_t)(a.msg_first_eid + row_e[r]) * g.F;
+        const double lu = live ? a.lu[u] : 0.0;
+        constexpr int kAhead = 8;  // 512 elements of a message row per pass
+        for (int base = 0; base < g.Kg; base += kWave * kAhead) {
+            float v[kAhead];
+            double tw[kAhead], tb[kAhead];
+#pragma unroll
+            for (int k = 0; k < kAhead; ++k) {
+                const int j = base + lane + kWave * k;
+                v[k] = 0.0f;
+                tw[k] = tb[k] = 0.0;
+                if (live && j < g.Dmsg) {
+                    if (j < g.M)
+                        v[k] = self[j];
+                    else if (j < 2 * g.M)
+                        v[k] = other[j - g.M];
+                    else if (j < 2 * g.M + g.T) {
+                        tw[k] = w.time_w_rev[j - 2 * g.M];
+                        tb[k] = w.time_b_rev[j - 2 * g.M];
+                    } else
+                        v[k] = feat[j - 2 * g.M - g.T];
+                }
+            }
+            const double dt = row_t[r] - lu;  // since the node's last update
+#pragma unroll
+            for (int k = 0; k < kAhead; ++k) {
+                const int j = base + lane + kWave * k;
+                if (j < g.Kg) {
+                    float x = v[k];
+                    if (live && j >= 2 * g.M && j < 2 * g.M + g.T)
+                        x = time_enc(tw[k], tb[k], dt);
+                    P::store_a(X + (size_t)r * g.ldx, j, x);
+                }
+            }
         }
-        P::store_a(X + (size_t)r * g.ldx, j, v);
     }
     __syncthreads();
     TIG_MARK(2);
