@@ -191,22 +191,38 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
 
     TIG_MARK(1);
     // ---- B. folded query: q~ = A1 s_u + a1  (fp32, [H x dkvp] per row) -----------------------
-    for (int nt = wave; nt < p.N1 / 16; nt += kEmbedWaves) {
-        floatx4 acc[MT];
+    {
+        const int ntB = p.N1 / 16, kbB = p.Mq / P::KB, a_kb0 = p.N1 / P::KB;
+        auto put = [&](const floatx4 (&acc)[MT], int nt, float bias) {
+            const int col = nt * 16 + (lane & 15);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-            acc[mt] = floatx4{0, 0, 0, 0};
-        tile_gemm<PREC, MT, 4>(acc, rowbuf, p.row_bytes, p.N1 / P::KB, w.emb_A1, p.Mq / P::KB, 0,
-                               p.Mq / P::KB, nt);
-        const int col = nt * 16 + (lane & 15);
-        const float bias = w.emb_a1[col];
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+                for (int v = 0; v < 4; ++v) {
+                    const int row = mt * 16 + 4 * (lane >> 4) + v;
+                    ((float *)(rowbuf + (size_t)row * p.row_bytes))[col] = acc[mt][v] + bias;
+                }
+        };
+        // two output tiles per pass where the wavefront has two: they share the reads of s_u
+        for (int nt = wave; nt < ntB; nt += 2 * kEmbedWaves) {
+            const int nt2 = nt + kEmbedWaves;
+            floatx4 acc1[MT], acc2[MT];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int row = mt * 16 + 4 * (lane >> 4) + v;
-                ((float *)(rowbuf + (size_t)row * p.row_bytes))[col] = acc[mt][v] + bias;
+            for (int mt = 0; mt < MT; ++mt) {
+                acc1[mt] = floatx4{0, 0, 0, 0};
+                acc2[mt] = floatx4{0, 0, 0, 0};
             }
+            const float bias1 = w.emb_a1[nt * 16 + (lane & 15)];
+            if (nt2 < ntB) {
+                const float bias2 = w.emb_a1[nt2 * 16 + (lane & 15)];
+                tile_gemm_two<PREC, MT, 2>(acc1, acc2, rowbuf, p.row_bytes, a_kb0, w.emb_A1, kbB, kbB, nt, nt2);
+                put(acc1, nt, bias1);
+                put(acc2, nt2, bias2);
+            } else {
+                tile_gemm<PREC, MT, 4>(acc1, rowbuf, p.row_bytes, a_kb0, w.emb_A1, kbB, 0, kbB, nt);
+                put(acc1, nt, bias1);
+            }
+        }
     }
     __syncthreads();
 

@@ -246,6 +246,41 @@ __device__ inline void tile_gemm(floatx4 (&acc)[MT], const char *A, int lda, int
     }
 }
 
+// The same for two output tiles nt1, nt2 of one weight matrix: every operand of A is read from
+// LDS once and meets the weights of both tiles (the A reads, not the matrix cores, bound these
+// small products).
+template <int PREC, int MT, int DEPTH>
+__device__ inline void tile_gemm_two(floatx4 (&acc1)[MT], floatx4 (&acc2)[MT], const char *A, int lda, int a_kb0,
+                                     const void *W, int w_kblocks, int kblocks, int nt1, int nt2)
+{
+    using P = Prec<PREC>;
+    using frag = typename P::frag;
+    const int lane = lane_id();
+    const size_t w1 = (size_t)nt1 * w_kblocks * kWave + lane;
+    const size_t w2 = (size_t)nt2 * w_kblocks * kWave + lane;
+    const char *ap = A + (size_t)(lane & 15) * lda;
+    const int g = lane >> 4;
+    for (int kb = 0; kb < kblocks; kb += DEPTH) {
+        frag b1[DEPTH], b2[DEPTH];
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u)
+            if (kb + u < kblocks) {
+                b1[u] = P::load_w(W, w1 + (size_t)(kb + u) * kWave);
+                b2[u] = P::load_w(W, w2 + (size_t)(kb + u) * kWave);
+            }
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u)
+            if (kb + u < kblocks) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const frag afrag = P::load_a(ap + (size_t)mt * 16 * lda, a_kb0 + kb + u, g);
+                    P::mma(acc1[mt], afrag, b1[u]);
+                    P::mma(acc2[mt], afrag, b2[u]);
+                }
+            }
+    }
+}
+
 // Row stride in bytes >= 4*width whose 16-byte chunk count is odd: the 16 rows read by one
 // operand load then fall into distinct LDS bank groups.
 __host__ __device__ inline int lds_row_bytes(int width_elems)
