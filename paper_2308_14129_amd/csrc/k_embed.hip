@@ -460,7 +460,12 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
                 acc[mt] = floatx4{0, 0, 0, 0};
+            float c = 0.0f, c0 = 0.0f;  // requested with the first weight operands, used in the epilogue
             if (on) {
+                if (my_ks == 0) {
+                    c = w.emb_c[my_nt * 16 + (lane & 15)];
+                    c0 = w.emb_c0[my_nt * 16 + (lane & 15)];
+                }
                 const int kb0 = my_ks * kb_half;
                 const int nkb = (kbT - kb0) < kb_half ? (kbT - kb0) : kb_half;
                 tile_gemm<PREC, MT, 4>(acc, rowbuf, p.row_bytes, kb0, w.emb_PR, kbT, kb0, nkb, my_nt);
@@ -480,7 +485,6 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
             }
             if (on && my_ks == 0) {
                 const int col = my_nt * 16 + (lane & 15);
-                const float c = w.emb_c[col], c0 = w.emb_c0[col];
                 float part[MT][4];
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
@@ -515,9 +519,9 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
             acc[mt] = floatx4{0, 0, 0, 0};
-        tile_gemm<PREC, MT, 4>(acc, h1buf, p.ld1, 0, w.emb_Wm2, p.Ek / P::KB, 0, p.Ek / P::KB, nt);
         const int col = nt * 16 + (lane & 15);
-        const float bias = w.emb_bm2[col];
+        const float bias = w.emb_bm2[col];  // requested with the first weight operands
+        tile_gemm<PREC, MT, 4>(acc, h1buf, p.ld1, 0, w.emb_Wm2, p.Ek / P::KB, 0, p.Ek / P::KB, nt);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -539,6 +543,15 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     TIG_MARK(5);
     // ---- F. decoder layer 1, split by operand: [W_a emb | W_b emb] for every row -------------
     float *decbuf = (float *)(rowbuf + p.dec_off);  // [ROWS x 2Ep]
+    // decoder layer 2 parameters of the first 128 dims, requested here and used in phase G
+    float g_w2[2], g_b1[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int j = lane + kWave * u;
+        g_w2[u] = j < p.E ? w.dec_w2[j] : 0.0f;
+        g_b1[u] = j < p.E ? w.dec_b1[j] : 0.0f;
+    }
+    const float g_b2 = w.dec_b2[0];
     for (int nt = wave; nt < 2 * p.Ep / 16; nt += kEmbedWaves) {
         floatx4 acc[MT];
 #pragma unroll
@@ -568,9 +581,15 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
         const float *da = decbuf + (size_t)ev * 2 * p.Ep;
         const float *db = decbuf + (size_t)((which + 1) * p.TE + ev) * 2 * p.Ep + p.Ep;
         float part = 0.0f;
-        for (int j = lane; j < p.E; j += kWave)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int j = lane + kWave * u;
+            if (j < p.E)
+                part += g_w2[u] * fmaxf(da[j] + db[j] + g_b1[u], 0.0f);
+        }
+        for (int j = lane + 2 * kWave; j < p.E; j += kWave)
             part += w.dec_w2[j] * fmaxf(da[j] + db[j] + w.dec_b1[j], 0.0f);
-        const float s = wave_sum_uniform(part) + w.dec_b2[0];
+        const float s = wave_sum_uniform(part) + g_b2;
         if (lane == 0)
             (which == 0 ? a.score_pos : a.score_neg)[b] = s;
     }
