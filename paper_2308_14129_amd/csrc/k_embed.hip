@@ -94,6 +94,8 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     using SH = RowShape<SHAPE>;
     // segment sizes and segment-to-register maps of a key/value row, as phase C uses them
     const int cT = SH::kFixed ? SH::T : p.T, cM = SH::kFixed ? SH::M : p.M, cF = SH::kFixed ? SH::F : p.F;
+    // d_kv padded to whole k-blocks of the precision's matrix-core operand
+    const int cDkvp = SH::kFixed ? (SH::T + SH::M + SH::F + P::KB - 1) / P::KB * P::KB : p.dkvp;
     const int phi_regs = SH::kFixed ? regs_touching(0, SH::T, kWave * NPL) : p.phi_regs;
     const int mem_regs = SH::kFixed ? regs_touching(SH::T, SH::T + SH::M, kWave * NPL) : p.mem_regs;
     const int feat_regs =
@@ -292,7 +294,7 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
 #pragma unroll
                 for (int n = 0; n < NPL; ++n) {
                     const int j = lane + kWave * n;
-                    qv[h][n] = j < p.dkvp ? qrow[h * p.dkvp + j] : 0.0f;
+                    qv[h][n] = j < cDkvp ? qrow[h * cDkvp + j] : 0.0f;
                     accv[h][n] = 0.0f;
                 }
             }
@@ -369,31 +371,46 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                                 }
                             }
                         }
-                        // wavefront sums of the pair, one DPP step at a time across its 2H values
-                        // (see wave_sum_uniform for the step sequence)
+                        if constexpr (H % 2 == 0) {
+                            // four wavefront sums (2 slots x 2 heads) for the price of one: the
+                            // half- and quarter-wave swaps fold them into the four 16-lane rows of
+                            // one register, which the row shifts then sum
+#pragma unroll
+                            for (int h = 0; h < H; h += 2) {
+                                const float z = wave_sum_four(part[0][h], part[1][h], part[0][h + 1], part[1][h + 1]);
+#pragma unroll
+                                for (int u = 0; u < 2; ++u) {
+                                    if (k2 + u < KC && c0 + k2 + u < cnt) {  // scalar
+                                        const int kk = k2 + u < KC ? k2 + u : KC - 1;
+                                        sc[kk][h] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(z), 15 + 16 * u));
+                                        sc[kk][h + 1] =
+                                            __int_as_float(__builtin_amdgcn_readlane(__float_as_int(z), 47 + 16 * u));
+                                    }
+                                }
+                            }
+                        } else {
+                            // wavefront sums of the pair, one DPP step at a time across its 2H values
+                            // (see wave_sum_uniform for the step sequence)
 #define TIG_DPP_STEP(CTRL, ROWS_)                                          \
     _Pragma("unroll") for (int u = 0; u < 2; ++u)                          \
         _Pragma("unroll") for (int h = 0; h < H; ++h)                      \
             part[u][h] += dpp_or_zero<CTRL, ROWS_, 0xf>(part[u][h]);
-                        TIG_DPP_STEP(0x111, 0xf)
-                        TIG_DPP_STEP(0x112, 0xf)
-                        TIG_DPP_STEP(0x114, 0xf)
-                        TIG_DPP_STEP(0x118, 0xf)
-                        if constexpr (H == 1) {
-                            add_row_bcasts(part[0][0], part[1][0]);
-                        } else {
-#pragma unroll
-                            for (int h = 0; h < H; h += 2)
-                                add_row_bcasts(part[0][h], part[0][h + 1], part[1][h], part[1][h + 1]);
-                        }
+                            TIG_DPP_STEP(0x111, 0xf)
+                            TIG_DPP_STEP(0x112, 0xf)
+                            TIG_DPP_STEP(0x114, 0xf)
+                            TIG_DPP_STEP(0x118, 0xf)
 #undef TIG_DPP_STEP
 #pragma unroll
-                        for (int u = 0; u < 2; ++u) {
-                            if (k2 + u < KC && c0 + k2 + u < cnt) {  // scalar
+                            for (int h = 0; h < H; ++h)
+                                add_row_bcasts(part[0][h], part[1][h]);
 #pragma unroll
-                                for (int h = 0; h < H; ++h)
-                                    sc[k2 + u < KC ? k2 + u : KC - 1][h] =
-                                        __int_as_float(__builtin_amdgcn_readlane(__float_as_int(part[u][h]), 63));
+                            for (int u = 0; u < 2; ++u) {
+                                if (k2 + u < KC && c0 + k2 + u < cnt) {  // scalar
+#pragma unroll
+                                    for (int h = 0; h < H; ++h)
+                                        sc[k2 + u < KC ? k2 + u : KC - 1][h] =
+                                            __int_as_float(__builtin_amdgcn_readlane(__float_as_int(part[u][h]), 63));
+                                }
                             }
                         }
                     }
@@ -427,12 +444,12 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
             // kvbar overwrites q~ in place (as matrix-core operand elements)
 #pragma unroll
             for (int h = 0; h < H; ++h) {
-                const float inv = cnt > 0 ? 1.0f / den[h] : 0.0f;
+                const float inv = cnt > 0 ? __builtin_amdgcn_rcpf(den[h]) : 0.0f;  // den >= 1; 1 ulp
 #pragma unroll
                 for (int n = 0; n < NPL; ++n) {
                     const int j = lane + kWave * n;
-                    if (j < p.dkvp)
-                        P::store_a(arow, h * p.dkvp + j, accv[h][n] * inv);
+                    if (j < cDkvp)
+                        P::store_a(arow, h * cDkvp + j, accv[h][n] * inv);
                 }
             }
         }

@@ -143,6 +143,25 @@ __device__ inline void add_row_bcasts(float &a, float &b, float &c, float &d)
                  : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
 }
 
+// Wavefront sums of four values at once: returns a register whose lanes 15, 31, 47 and 63 hold
+// the sums over all 64 lanes of a, b, c and d.  v_permlane32_swap exchanges the upper half of its
+// first operand with the lower half of its second, v_permlane16_swap the odd 16-lane rows of the
+// first with the even rows of the second; an add after each folds two registers into one.
+__device__ inline float wave_sum_four(float a, float b, float c, float d)
+{
+    const auto ac = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(c), false, false);
+    const auto bd = __builtin_amdgcn_permlane32_swap(__float_as_uint(b), __float_as_uint(d), false, false);
+    const float x = __uint_as_float(ac[0]) + __uint_as_float(ac[1]);  // [a | c], 32 partial sums each
+    const float y = __uint_as_float(bd[0]) + __uint_as_float(bd[1]);  // [b | d]
+    const auto xy = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(y), false, false);
+    float z = __uint_as_float(xy[0]) + __uint_as_float(xy[1]);        // rows [a, b, c, d], 16 partial sums each
+    z += dpp_or_zero<0x111, 0xf, 0xf>(z);
+    z += dpp_or_zero<0x112, 0xf, 0xf>(z);
+    z += dpp_or_zero<0x114, 0xf, 0xf>(z);
+    z += dpp_or_zero<0x118, 0xf, 0xf>(z);
+    return z;
+}
+
 // Raw buffer descriptor word 3 for gfx950: 32-bit data format, no swizzle.  With stride 0 a lane
 // whose byte offset is not inside [0, extent - 4] reads 0.
 constexpr int kBufferFlags = 0x00020000;
