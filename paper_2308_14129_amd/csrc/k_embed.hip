@@ -13,6 +13,7 @@
 //   G  logit = w_d2 . relu(W_a emb_src + W_b emb_other + b_d1) + b_d2
 // The projections W_Q, W_K, W_V, W_O and the first merge layer are folded into A1 and P at init
 // (pack.hip), which removes the per-neighbour key/value projections.
+#include <type_traits>
 #include <hip/hip_runtime.h>
 
 #include "kernels_common.h"
@@ -298,7 +299,11 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                     accv[h][n] = 0.0f;
                 }
             }
-            for (int c0 = 0; c0 < cnt; c0 += KC) {
+            // One chunk of up to KC neighbour slots starting at slot c0.  FULL: the row has exactly
+            // KC neighbours (the usual case once the adjacency is deep), so no slot is conditional
+            // and there is no earlier chunk to merge with.
+            auto chunk = [&](const int c0, auto full_tag) {
+                constexpr bool FULL = decltype(full_tag)::value;
                 float raw[KC][NPL];
                 float mix[KC];  // edge-feature lanes of the one register that also holds s_v dims
                 // issue every gather of the chunk before using any of them
@@ -306,7 +311,7 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                 for (int kk = 0; kk < KC; ++kk) {
                     const int k = c0 + kk;
                     mix[kk] = 0.0f;
-                    if (k < cnt) {  // scalar
+                    if (FULL || k < cnt) {  // scalar
                         const int32_t v = __builtin_amdgcn_readlane(nb_vc, k & 63);
                         const int32_t e = __builtin_amdgcn_readlane(nb_ec, k & 63);
                         const __amdgpu_buffer_rsrc_t rm = __builtin_amdgcn_make_buffer_rsrc(
@@ -338,7 +343,7 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                 }
 #pragma unroll
                 for (int k2 = 0; k2 < KC; k2 += 2) {
-                    if (c0 + k2 < cnt) {  // scalar
+                    if (FULL || c0 + k2 < cnt) {  // scalar
                         float part[2][H];
 #pragma unroll
                         for (int u = 0; u < 2; ++u) {
@@ -347,7 +352,7 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
 #pragma unroll
                             for (int h = 0; h < H; ++h)
                                 part[u][h] = 0.0f;
-                            if (k2 + u < KC && k < cnt) {  // scalar
+                            if (k2 + u < KC && (FULL || k < cnt)) {  // scalar
                                 const double dt = readlane_f64(nb_dtc, k & 63);
 #pragma unroll
                                 for (int n = 0; n < NPL; ++n) {
@@ -380,7 +385,7 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                                 const float z = wave_sum_four(part[0][h], part[1][h], part[0][h + 1], part[1][h + 1]);
 #pragma unroll
                                 for (int u = 0; u < 2; ++u) {
-                                    if (k2 + u < KC && c0 + k2 + u < cnt) {  // scalar
+                                    if (k2 + u < KC && (FULL || c0 + k2 + u < cnt)) {  // scalar
                                         const int kk = k2 + u < KC ? k2 + u : KC - 1;
                                         sc[kk][h] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(z), 15 + 16 * u));
                                         sc[kk][h + 1] =
@@ -405,7 +410,7 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                                 add_row_bcasts(part[0][h], part[1][h]);
 #pragma unroll
                             for (int u = 0; u < 2; ++u) {
-                                if (k2 + u < KC && c0 + k2 + u < cnt) {  // scalar
+                                if (k2 + u < KC && (FULL || c0 + k2 + u < cnt)) {  // scalar
 #pragma unroll
                                     for (int h = 0; h < H; ++h)
                                         sc[k2 + u < KC ? k2 + u : KC - 1][h] =
@@ -422,14 +427,17 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
 #pragma unroll
                     for (int kk = 0; kk < KC; ++kk)
                         mnew = fmaxf(mnew, sc[kk][h]);
-                    const float corr = __expf(mx[h] - mnew);  // first chunk: exp(-inf) = 0
-                    float dsum = den[h] * corr;
+                    float dsum = 0.0f;
+                    if constexpr (!FULL) {
+                        const float corr = __expf(mx[h] - mnew);  // first chunk: exp(-inf) = 0
+                        dsum = den[h] * corr;
 #pragma unroll
-                    for (int n = 0; n < NPL; ++n)
-                        accv[h][n] *= corr;
+                        for (int n = 0; n < NPL; ++n)
+                            accv[h][n] *= corr;
+                    }
 #pragma unroll
                     for (int kk = 0; kk < KC; ++kk) {
-                        if (c0 + kk < cnt) {  // scalar
+                        if (FULL || c0 + kk < cnt) {  // scalar
                             const float pk = __expf(sc[kk][h] - mnew);
                             dsum += pk;
 #pragma unroll
@@ -440,6 +448,12 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                     den[h] = dsum;
                     mx[h] = mnew;
                 }
+            };
+            if (cnt == KC) {
+                chunk(0, std::true_type{});
+            } else {
+                for (int c0 = 0; c0 < cnt; c0 += KC)
+                    chunk(c0, std::false_type{});
             }
             // kvbar overwrites q~ in place (as matrix-core operand elements)
 #pragma unroll
