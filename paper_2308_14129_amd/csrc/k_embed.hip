@@ -266,6 +266,18 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                 }
             }
         };
+        // time-encoding parameters of the lane's Phi dims, kept in registers for compiled-in shapes
+        double tw_reg[NPHI], tb_reg[NPHI];
+#pragma unroll
+        for (int n = 0; n < NPHI; ++n) {
+            tw_reg[n] = 0.0;
+            tb_reg[n] = 0.0;
+            if (SH::kFixed && ((phi_regs >> n) & 1)) {
+                const int j = lane + kWave * n < cT ? lane + kWave * n : 0;
+                tw_reg[n] = tw_tab[2 * j];
+                tb_reg[n] = tw_tab[2 * j + 1];
+            }
+        }
         int r = grab();
         int32_t nb_v1, nb_e1, nb_v2, nb_e2;
         double nb_dt1, nb_dt2;
@@ -363,9 +375,16 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                                 for (int n = 0; n < NPHI; ++n) {
                                     if ((phi_regs >> n) & 1) {  // scalar: this register holds Phi dims
                                         const int j = lane + kWave * n < cT ? lane + kWave * n : 0;
-                                        const float ph = time_enc(tw_tab[2 * j], tw_tab[2 * j + 1], dt);
-                                        if (lane + kWave * n < cT)
+                                        float ph = SH::kFixed ? time_enc(tw_reg[n], tb_reg[n], dt)
+                                                              : time_enc(tw_tab[2 * j], tw_tab[2 * j + 1], dt);
+                                        if (SH::kFixed && kWave * n + kWave > cT) {
+                                            // every lane evaluates, the others keep their dim: no
+                                            // branch, so the whole chunk stays one scheduling region
+                                            asm volatile("" : "+v"(ph));
+                                            raw[kk][n] = lane + kWave * n < cT ? ph : raw[kk][n];
+                                        } else if (lane + kWave * n < cT) {
                                             raw[kk][n] = ph;
+                                        }
                                     }
                                 }
 #pragma unroll
