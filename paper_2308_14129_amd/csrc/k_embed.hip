@@ -316,6 +316,11 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
             // and there is no earlier chunk to merge with.
             auto chunk = [&](const int c0, auto full_tag) {
                 constexpr bool FULL = decltype(full_tag)::value;
+                constexpr bool VEC = FULL && H % 2 == 0 && KC % 2 == 0 && KC <= 32;  // softmax across lanes
+                float S[H / 2 > 0 ? H / 2 : 1];
+#pragma unroll
+                for (int h = 0; h < H / 2; ++h)
+                    S[h] = -INFINITY;
                 float raw[KC][NPL];
                 float mix[KC];  // edge-feature lanes of the one register that also holds s_v dims
                 // issue every gather of the chunk before using any of them
@@ -402,6 +407,13 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
 #pragma unroll
                             for (int h = 0; h < H; h += 2) {
                                 const float z = wave_sum_four(part[0][h], part[1][h], part[0][h + 1], part[1][h + 1]);
+                                if constexpr (VEC) {
+                                    // lane 15 - (pair index) of each row collects the row's sum
+                                    const int pr = k2 / 2;
+                                    const float moved = row_shl(z, pr);
+                                    S[h / 2] = (lane & 15) == 15 - pr ? moved : S[h / 2];
+                                    continue;
+                                }
 #pragma unroll
                                 for (int u = 0; u < 2; ++u) {
                                     if (k2 + u < KC && (FULL || c0 + k2 + u < cnt)) {  // scalar
@@ -438,6 +450,35 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                             }
                         }
                     }
+                }
+                if constexpr (VEC) {
+                    // softmax with one score per lane: register S[h/2] holds, in its rows 0..3, the
+                    // scores of (even slots, head h), (odd slots, head h), (even, h+1), (odd, h+1);
+                    // slot pair i sits in lane 15 - i of the row, every other lane is -inf
+#pragma unroll
+                    for (int h = 0; h < H; h += 2) {
+                        float m = row_max_all(S[h / 2]);
+                        max_row_bcast15(m);  // rows 1 and 3 now hold the maximum of their head
+                        const float m0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), 31));
+                        const float m1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), 63));
+                        const float e = __expf(S[h / 2] - (lane < 32 ? m0 : m1));
+                        float sum = row_sum_all(e);
+                        add_row_bcast15(sum);
+                        den[h] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sum), 31));
+                        den[h + 1] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sum), 63));
+#pragma unroll
+                        for (int kk = 0; kk < KC; ++kk) {
+                            const int src = 16 * (kk & 1) + 15 - kk / 2;
+                            const float p0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(e), src));
+                            const float p1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(e), 32 + src));
+#pragma unroll
+                            for (int n = 0; n < NPL; ++n) {
+                                accv[h][n] += p0 * raw[kk][n];
+                                accv[h + 1][n] += p1 * raw[kk][n];
+                            }
+                        }
+                    }
+                    return;
                 }
                 // softmax across the chunk, merged with earlier chunks by rescaling
 #pragma unroll

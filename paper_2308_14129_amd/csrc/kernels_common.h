@@ -143,6 +143,70 @@ __device__ inline void add_row_bcasts(float &a, float &b, float &c, float &d)
                  : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
 }
 
+// One cross-row step on a single register: rows 1 and 3 combine with lane 15 of rows 0 and 2,
+// rows 0 and 2 keep their value.  (s_nop: see add_row_bcasts.)
+__device__ inline void add_row_bcast15(float &a)
+{
+    asm volatile("s_nop 1\n\t"
+                 "v_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+                 "s_nop 1"
+                 : "+v"(a));
+}
+__device__ inline void max_row_bcast15(float &a)
+{
+    asm volatile("s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+                 "s_nop 1"
+                 : "+v"(a));
+}
+
+// lane i of each 16-lane row takes lane i + n of the same row (0 beyond the row's end)
+__device__ inline float row_shl(float v, int n)
+{
+    switch (n) {
+    case 0: return v;
+    case 1: return dpp_or_zero<0x101, 0xf, 0xf>(v);
+    case 2: return dpp_or_zero<0x102, 0xf, 0xf>(v);
+    case 3: return dpp_or_zero<0x103, 0xf, 0xf>(v);
+    case 4: return dpp_or_zero<0x104, 0xf, 0xf>(v);
+    case 5: return dpp_or_zero<0x105, 0xf, 0xf>(v);
+    case 6: return dpp_or_zero<0x106, 0xf, 0xf>(v);
+    case 7: return dpp_or_zero<0x107, 0xf, 0xf>(v);
+    case 8: return dpp_or_zero<0x108, 0xf, 0xf>(v);
+    case 9: return dpp_or_zero<0x109, 0xf, 0xf>(v);
+    case 10: return dpp_or_zero<0x10a, 0xf, 0xf>(v);
+    case 11: return dpp_or_zero<0x10b, 0xf, 0xf>(v);
+    case 12: return dpp_or_zero<0x10c, 0xf, 0xf>(v);
+    case 13: return dpp_or_zero<0x10d, 0xf, 0xf>(v);
+    case 14: return dpp_or_zero<0x10e, 0xf, 0xf>(v);
+    default: return dpp_or_zero<0x10f, 0xf, 0xf>(v);
+    }
+}
+
+// every lane of a 16-lane row takes the maximum / the sum over the row (rotations: no lane is empty)
+__device__ inline float row_max_all(float v)
+{
+    // written out: the compiler would canonicalise both operands of every maximum
+    asm volatile("s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 row_ror:1 row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 row_ror:2 row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 row_ror:4 row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %0, %0 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+                 "s_nop 1"
+                 : "+v"(v));
+    return v;
+}
+__device__ inline float row_sum_all(float v)
+{
+    v += dpp_or_zero<0x121, 0xf, 0xf>(v);
+    v += dpp_or_zero<0x122, 0xf, 0xf>(v);
+    v += dpp_or_zero<0x124, 0xf, 0xf>(v);
+    return v + dpp_or_zero<0x128, 0xf, 0xf>(v);
+}
+
 // Wavefront sums of four values at once: returns a register whose lanes 15, 31, 47 and 63 hold
 // the sums over all 64 lanes of a, b, c and d.  v_permlane32_swap exchanges the upper half of its
 // first operand with the lower half of its second, v_permlane16_swap the odd 16-lane rows of the
