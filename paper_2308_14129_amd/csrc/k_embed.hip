@@ -408,10 +408,10 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                             for (int h = 0; h < H; h += 2) {
                                 const float z = wave_sum_four(part[0][h], part[1][h], part[0][h + 1], part[1][h + 1]);
                                 if constexpr (VEC) {
-                                    // lane 15 - (pair index) of each row collects the row's sum
-                                    const int pr = k2 / 2;
-                                    const float moved = row_shl(z, pr);
-                                    S[h / 2] = (lane & 15) == 15 - pr ? moved : S[h / 2];
+                                    // lane 15 - (pair index) of each row collects the row's sum: pair
+                                    // i shifts in from the right and leaves the i lanes before it
+                                    // alone (the lanes to the left are cleared after the last pair)
+                                    S[h / 2] = row_shl_keep(S[h / 2], z, k2 / 2);
                                     continue;
                                 }
 #pragma unroll
@@ -457,6 +457,7 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                     // slot pair i sits in lane 15 - i of the row, every other lane is -inf
 #pragma unroll
                     for (int h = 0; h < H; h += 2) {
+                        S[h / 2] = (lane & 15) >= 16 - KC / 2 ? S[h / 2] : -INFINITY;
                         float m = row_max_all(S[h / 2]);
                         max_row_bcast15(m);  // rows 1 and 3 now hold the maximum of their head
                         const float m0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), 31));

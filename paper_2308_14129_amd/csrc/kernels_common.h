@@ -160,26 +160,32 @@ __device__ inline void max_row_bcast15(float &a)
                  : "+v"(a));
 }
 
-// lane i of each 16-lane row takes lane i + n of the same row (0 beyond the row's end)
-__device__ inline float row_shl(float v, int n)
+// lane i of each 16-lane row takes lane i + n of v's row; the last n lanes of the row keep `old`
+template <int N>
+__device__ inline float row_shl_keep_n(float old, float v)
+{
+    return __int_as_float(
+        __builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), 0x100 + N, 0xf, 0xf, false));
+}
+__device__ inline float row_shl_keep(float old, float v, int n)
 {
     switch (n) {
     case 0: return v;
-    case 1: return dpp_or_zero<0x101, 0xf, 0xf>(v);
-    case 2: return dpp_or_zero<0x102, 0xf, 0xf>(v);
-    case 3: return dpp_or_zero<0x103, 0xf, 0xf>(v);
-    case 4: return dpp_or_zero<0x104, 0xf, 0xf>(v);
-    case 5: return dpp_or_zero<0x105, 0xf, 0xf>(v);
-    case 6: return dpp_or_zero<0x106, 0xf, 0xf>(v);
-    case 7: return dpp_or_zero<0x107, 0xf, 0xf>(v);
-    case 8: return dpp_or_zero<0x108, 0xf, 0xf>(v);
-    case 9: return dpp_or_zero<0x109, 0xf, 0xf>(v);
-    case 10: return dpp_or_zero<0x10a, 0xf, 0xf>(v);
-    case 11: return dpp_or_zero<0x10b, 0xf, 0xf>(v);
-    case 12: return dpp_or_zero<0x10c, 0xf, 0xf>(v);
-    case 13: return dpp_or_zero<0x10d, 0xf, 0xf>(v);
-    case 14: return dpp_or_zero<0x10e, 0xf, 0xf>(v);
-    default: return dpp_or_zero<0x10f, 0xf, 0xf>(v);
+    case 1: return row_shl_keep_n<1>(old, v);
+    case 2: return row_shl_keep_n<2>(old, v);
+    case 3: return row_shl_keep_n<3>(old, v);
+    case 4: return row_shl_keep_n<4>(old, v);
+    case 5: return row_shl_keep_n<5>(old, v);
+    case 6: return row_shl_keep_n<6>(old, v);
+    case 7: return row_shl_keep_n<7>(old, v);
+    case 8: return row_shl_keep_n<8>(old, v);
+    case 9: return row_shl_keep_n<9>(old, v);
+    case 10: return row_shl_keep_n<10>(old, v);
+    case 11: return row_shl_keep_n<11>(old, v);
+    case 12: return row_shl_keep_n<12>(old, v);
+    case 13: return row_shl_keep_n<13>(old, v);
+    case 14: return row_shl_keep_n<14>(old, v);
+    default: return row_shl_keep_n<15>(old, v);
     }
 }
 
