@@ -217,6 +217,10 @@ def _custom(name, **kw):
     dict(mem_dim=7, time_dim=5, feat_dim=3, emb_dim=9, num_heads=1, num_neighbors=3),
     dict(mem_dim=33, time_dim=31, feat_dim=1, emb_dim=17, num_heads=4, num_neighbors=64),
     dict(mem_dim=200, time_dim=56, feat_dim=256, emb_dim=130, num_heads=2, num_neighbors=5, batch_size=70),
+    # rows with a full set of neighbours take the across-lanes softmax: four heads (two score
+    # registers), and sixteen slots in one chunk (eight slot pairs per register row)
+    dict(mem_dim=100, time_dim=60, feat_dim=40, emb_dim=48, num_heads=4, num_neighbors=10, alpha_src=2.0),
+    dict(mem_dim=32, time_dim=16, feat_dim=16, emb_dim=32, num_heads=2, num_neighbors=16, alpha_src=2.0),
 ])
 @pytest.mark.parametrize("precision", ["fp32", "bf16"])
 def test_odd_shapes(shape, precision):
