@@ -605,35 +605,13 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
 
     TIG_MARK(4);
     // ---- E. merge layer 2: emb = W_m2 h1 + b_m2 -> global, and kept as the decoder operand ---
-    char *embbuf = rowbuf;  // [ROWS rows x ld1 bytes], the main buffer is free again
-    for (int nt = wave; nt < p.Ep / 16; nt += kEmbedWaves) {
-        floatx4 acc[MT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-            acc[mt] = floatx4{0, 0, 0, 0};
-        const int col = nt * 16 + (lane & 15);
-        const float bias = w.emb_bm2[col];  // requested with the first weight operands
-        tile_gemm<PREC, MT, 4>(acc, h1buf, p.ld1, 0, w.emb_Wm2, p.Ek / P::KB, 0, p.Ek / P::KB, nt);
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int row = mt * 16 + 4 * (lane >> 4) + v;
-                const float x = acc[mt][v] + bias;
-                const int q = row_q[row];
-                if (q >= 0 && col < p.E)
-                    a.emb[(size_t)q * p.E + col] = x;
-                P::store_a(embbuf + (size_t)row * p.ld1, col, x);
-            }
-    }
-    for (int idx = threadIdx.x; idx < ROWS * (p.Ek - p.Ep); idx += kEmbedThreads) {
-        const int row = idx / (p.Ek - p.Ep), col = p.Ep + idx % (p.Ek - p.Ep);
-        P::store_a(embbuf + (size_t)row * p.ld1, col, 0.0f);
-    }
-    __syncthreads();
-
-    TIG_MARK(5);
     // ---- F. decoder layer 1, split by operand: [W_a emb | W_b emb] for every row -------------
+    // When the row tiles are whole roles (16 sources, 16 destinations, 16 negatives) both run as one
+    // phase from h1: merge layer 2 is folded into the decoder weights, the source tile takes only
+    // W_a and the other two only W_b, and seven wavefronts do each half.
+    const int nE = p.Ep / 16;
+    const bool fused = MT == 3 && a.roles == 3 && p.TE == 16 && 2 * nE <= kEmbedWaves;
+    const float *dec_b1 = fused ? w.dec_b1f : w.dec_b1;
     float *decbuf = (float *)(rowbuf + p.dec_off);  // [ROWS x 2Ep]
     // decoder layer 2 parameters of the first 128 dims, requested here and used in phase G
     float g_w2[2], g_b1[2];
@@ -641,25 +619,97 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     for (int u = 0; u < 2; ++u) {
         const int j = lane + kWave * u;
         g_w2[u] = j < p.E ? w.dec_w2[j] : 0.0f;
-        g_b1[u] = j < p.E ? w.dec_b1[j] : 0.0f;
+        g_b1[u] = j < p.E ? dec_b1[j] : 0.0f;
     }
     const float g_b2 = w.dec_b2[0];
-    for (int nt = wave; nt < 2 * p.Ep / 16; nt += kEmbedWaves) {
-        floatx4 acc[MT];
+    if (fused) {
+        if constexpr (MT == 3) {
+            const int kbE = p.Ek / P::KB;
+            if (wave < nE) {
+                floatx4 acc[MT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-            acc[mt] = floatx4{0, 0, 0, 0};
-        tile_gemm<PREC, MT, 4>(acc, embbuf, p.ld1, 0, w.dec_W, p.Ek / P::KB, 0, p.Ek / P::KB, nt);
-        const int col = nt * 16 + (lane & 15);
+                for (int mt = 0; mt < MT; ++mt)
+                    acc[mt] = floatx4{0, 0, 0, 0};
+                const int col = wave * 16 + (lane & 15);
+                const float bias = w.emb_bm2[col];  // requested with the first weight operands
+                tile_gemm<PREC, MT, 4>(acc, h1buf, p.ld1, 0, w.emb_Wm2, kbE, 0, kbE, wave);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+                for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int row = mt * 16 + 4 * (lane >> 4) + v;
-                decbuf[(size_t)row * 2 * p.Ep + col] = acc[mt][v];
+                    for (int v = 0; v < 4; ++v) {
+                        const int row = mt * 16 + 4 * (lane >> 4) + v;
+                        const int q = row_q[row];
+                        if (q >= 0 && col < p.E)
+                            a.emb[(size_t)q * p.E + col] = acc[mt][v] + bias;
+                    }
+            } else if (wave < 2 * nE) {
+                const int j = wave - nE;
+                floatx4 acc_a[1], acc_b[2];
+                acc_a[0] = floatx4{0, 0, 0, 0};
+                acc_b[0] = floatx4{0, 0, 0, 0};
+                acc_b[1] = floatx4{0, 0, 0, 0};
+                tile_gemm<PREC, 1, 4>(acc_a, h1buf, p.ld1, 0, w.dec_WF, kbE, 0, kbE, j);
+                tile_gemm<PREC, 2, 4>(acc_b, h1buf + (size_t)16 * p.ld1, p.ld1, 0, w.dec_WF, kbE, 0, kbE, nE + j);
+                const int col = j * 16 + (lane & 15);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int row = 4 * (lane >> 4) + v;
+                    decbuf[(size_t)row * 2 * p.Ep + col] = acc_a[0][v];
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt)
+                        decbuf[(size_t)(16 + mt * 16 + row) * 2 * p.Ep + p.Ep + col] = acc_b[mt][v];
+                }
             }
+        }
+        __syncthreads();
+        TIG_MARK(5);
+    } else {
+        char *embbuf = rowbuf;  // [ROWS rows x ld1 bytes], the main buffer is free again
+        for (int nt = wave; nt < p.Ep / 16; nt += kEmbedWaves) {
+            floatx4 acc[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                acc[mt] = floatx4{0, 0, 0, 0};
+            const int col = nt * 16 + (lane & 15);
+            const float bias = w.emb_bm2[col];  // requested with the first weight operands
+            tile_gemm<PREC, MT, 4>(acc, h1buf, p.ld1, 0, w.emb_Wm2, p.Ek / P::KB, 0, p.Ek / P::KB, nt);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int row = mt * 16 + 4 * (lane >> 4) + v;
+                    const float x = acc[mt][v] + bias;
+                    const int q = row_q[row];
+                    if (q >= 0 && col < p.E)
+                        a.emb[(size_t)q * p.E + col] = x;
+                    P::store_a(embbuf + (size_t)row * p.ld1, col, x);
+                }
+        }
+        for (int idx = threadIdx.x; idx < ROWS * (p.Ek - p.Ep); idx += kEmbedThreads) {
+            const int row = idx / (p.Ek - p.Ep), col = p.Ep + idx % (p.Ek - p.Ep);
+            P::store_a(embbuf + (size_t)row * p.ld1, col, 0.0f);
+        }
+        __syncthreads();
+
+        TIG_MARK(5);
+        // ---- F. decoder layer 1, split by operand: [W_a emb | W_b emb] for every row -------------
+        for (int nt = wave; nt < 2 * p.Ep / 16; nt += kEmbedWaves) {
+            floatx4 acc[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                acc[mt] = floatx4{0, 0, 0, 0};
+            tile_gemm<PREC, MT, 4>(acc, embbuf, p.ld1, 0, w.dec_W, p.Ek / P::KB, 0, p.Ek / P::KB, nt);
+            const int col = nt * 16 + (lane & 15);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int row = mt * 16 + 4 * (lane >> 4) + v;
+                    decbuf[(size_t)row * 2 * p.Ep + col] = acc[mt][v];
+                }
+        }
+        __syncthreads();
     }
-    __syncthreads();
 
     TIG_MARK(6);
     // ---- G. logits: w_d2 . relu(W_a emb_src + W_b emb_other + b_d1) + b_d2 --------------------
@@ -680,7 +730,7 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                 part += g_w2[u] * fmaxf(da[j] + db[j] + g_b1[u], 0.0f);
         }
         for (int j = lane + 2 * kWave; j < p.E; j += kWave)
-            part += w.dec_w2[j] * fmaxf(da[j] + db[j] + w.dec_b1[j], 0.0f);
+            part += w.dec_w2[j] * fmaxf(da[j] + db[j] + dec_b1[j], 0.0f);
         const float s = wave_sum_uniform(part) + g_b2;
         if (lane == 0)
             (which == 0 ? a.score_pos : a.score_neg)[b] = s;

@@ -184,8 +184,8 @@ struct PackedLayout {
     float *emb_c, *emb_c0;
     void *emb_Wm2;
     float *emb_bm2;
-    void *dec_W;
-    float *dec_b1, *dec_w2, *dec_b2;
+    void *dec_W, *dec_WF;
+    float *dec_b1, *dec_b1f, *dec_w2, *dec_b2;
     size_t bytes;
 };
 
@@ -213,6 +213,8 @@ PackedLayout layout(const Dims &d, void *base)
     L.emb_bm2 = c.take<float>(d.Ep);
     L.dec_W = c.take<char>(e * 2 * d.Ep * d.Ek);
     L.dec_b1 = c.take<float>(d.Ep);
+    L.dec_WF = c.take<char>(e * 2 * d.Ep * d.Ek);
+    L.dec_b1f = c.take<float>(d.Ep);
     L.dec_w2 = c.take<float>(d.Ep);
     L.dec_b2 = c.take<float>(1);
     L.bytes = c.off;
@@ -220,7 +222,7 @@ PackedLayout layout(const Dims &d, void *base)
 }
 
 struct ScratchLayout {
-    double *phi0, *cQ, *A1, *a1, *G, *PR, *cvec, *gv, *Wr, *Wz, *dec;
+    double *phi0, *cQ, *A1, *a1, *G, *PR, *cvec, *gv, *Wr, *Wz, *dec, *decF, *bvec;
     size_t bytes;
 };
 
@@ -239,6 +241,8 @@ ScratchLayout scratch_layout(const Dims &d, void *base)
     S.Wr = c.take<double>((size_t)d.M * d.Dmsg);
     S.Wz = c.take<double>((size_t)d.M * d.Dmsg);
     S.dec = c.take<double>((size_t)2 * d.Ep * d.E);
+    S.decF = c.take<double>((size_t)2 * d.Ep * d.E);
+    S.bvec = c.take<double>(d.E);
     S.bytes = c.off;
     return S;
 }
@@ -363,6 +367,14 @@ hipError_t pack_weights(const Dims &d, const tig_weights &w, void *dst, void *sc
     TIG_TRY(pack<double>(s, d.prec, L.dec_W, S.dec, E, 2 * d.Ep, E, 2 * d.Ep, d.Ek));
     hipLaunchKernelGGL(k_vec_f32, grid(d.Ep), blk, 0, s, L.dec_b1, d.Ep, E, (const double *)nullptr,
                        w.b_d1, (const float *)nullptr);
+    // The same layer applied to h1 directly (merge layer 2 folded in), for launches whose row tiles
+    // are whole roles: W_d1a W_m2, W_d1b W_m2 and b_d1 + (W_d1a + W_d1b) b_m2.
+    TIG_TRY((gemm64<double, float>(s, S.decF, E, S.dec, E, 1, w.W_m2, E, 1, 2 * d.Ep, E, E, 1.0, 0.0)));
+    TIG_TRY((gemm64<double, float>(s, S.bvec, 1, S.dec, E, 1, w.b_m2, 1, 1, E, 1, E, 1.0, 0.0)));
+    TIG_TRY((gemm64<double, float>(s, S.bvec, 1, S.dec + (size_t)d.Ep * E, E, 1, w.b_m2, 1, 1, E, 1, E, 1.0, 1.0)));
+    TIG_TRY(pack<double>(s, d.prec, L.dec_WF, S.decF, E, 2 * d.Ep, E, 2 * d.Ep, d.Ek));
+    hipLaunchKernelGGL(k_vec_f32, grid(d.Ep), blk, 0, s, L.dec_b1f, d.Ep, E, (const double *)S.bvec, w.b_d1,
+                       (const float *)nullptr);
     hipLaunchKernelGGL(k_vec_f32, grid(d.Ep), blk, 0, s, L.dec_w2, d.Ep, E, (const double *)nullptr,
                        w.w_d2, (const float *)nullptr);
     hipLaunchKernelGGL(k_vec_f32, grid(1), blk, 0, s, L.dec_b2, 1, 1, (const double *)nullptr, w.b_d2,
@@ -388,6 +400,8 @@ hipError_t pack_weights(const Dims &d, const tig_weights &w, void *dst, void *sc
     pw->emb_bm2 = L.emb_bm2;
     pw->dec_W = L.dec_W;
     pw->dec_b1 = L.dec_b1;
+    pw->dec_WF = L.dec_WF;
+    pw->dec_b1f = L.dec_b1f;
     pw->dec_w2 = L.dec_w2;
     pw->dec_b2 = L.dec_b2;
     return hipSuccess;

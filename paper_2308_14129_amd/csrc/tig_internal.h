@@ -54,6 +54,8 @@ struct PackedWeights {
     const float *emb_bm2;                      // [Ep]
     const void *dec_W;                         // [2Ep x Ek] packed: W_d1[:, :E] ; W_d1[:, E:]
     const float *dec_b1, *dec_w2;              // [Ep]
+    const void *dec_WF;                        // [2Ep x Ek] packed: the same times W_m2 (acts on h1)
+    const float *dec_b1f;                      // [Ep] b_d1 + (W_d1[:, :E] + W_d1[:, E:]) b_m2
     const float *dec_b2;                       // [1]
 };
 
