@@ -215,6 +215,30 @@ def test_merge_decoder_against_float64_matmul():
     assert O.decoder(ea, eb, W) == pytest.approx(want, abs=1e-13)
 
 
+def test_decoder_layer_one_folded_through_merge_layer_two():
+    """Decoder layer 1 applied to the merge hidden layer h1 through W_d1a W_m2, W_d1b W_m2 and
+    b_d1 + (W_d1a + W_d1b) b_m2 (the form one phase of the embedding kernel computes) is the
+    decoder of the two embeddings."""
+    rng = np.random.default_rng(16)
+    M, T, F, E = 6, 4, 3, 5
+    W = _rand_weights(rng, M, T, F, E)
+    f64 = np.float64
+    Wm2, bm2 = W["W_m2"].astype(f64), W["b_m2"].astype(f64)
+    Wa, Wb = W["W_d1"].astype(f64)[:, :E], W["W_d1"].astype(f64)[:, E:]
+    bias = W["b_d1"].astype(f64) + (Wa + Wb) @ bm2
+    for _ in range(5):
+        rows = []
+        for _ in range(2):
+            attn, mem_u = rng.normal(size=M + T), rng.normal(size=M).astype(np.float32)
+            h1 = np.maximum(W["W_m1"].astype(f64) @ np.concatenate([attn, mem_u.astype(f64)])
+                            + W["b_m1"].astype(f64), 0.0)
+            rows.append((O.merge(attn, mem_u, W), h1))
+        (emb_a, h1_a), (emb_b, h1_b) = rows
+        folded = W["w_d2"].astype(f64) @ np.maximum((Wa @ Wm2) @ h1_a + (Wb @ Wm2) @ h1_b + bias, 0.0) \
+            + W["b_d2"].astype(f64)[0]
+        assert O.decoder(emb_a, emb_b, W) == pytest.approx(float(folded), abs=1e-12)
+
+
 # ----------------------------------------------------------------------------- winners
 
 
