@@ -19,8 +19,11 @@
  *   - pointers documented "host or device" are resolved through HIP's unified addressing;
  *     pointers documented "device" must be device memory readable by kernels;
  *   - a context is not thread-safe; distinct contexts are independent;
- *   - all validation that can be done on the host happens before anything is launched, and a
- *     call that fails leaves the model state (memory, last_update) unchanged.
+ *   - all validation that can be done on the host happens before anything is launched: a call
+ *     that fails with an argument error (TIG_EINVAL, TIG_ERANGE, TIG_EORDER, TIG_ENOSPACE) leaves
+ *     the model state (memory, last_update) unchanged.  TIG_EHIP from a step means a launch failed
+ *     after earlier kernels of that step may have been enqueued: the state is then undefined until
+ *     tig_reset or tig_state_import.
  */
 #ifndef TIG_H
 #define TIG_H
@@ -199,6 +202,27 @@ TIG_API int tig_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *out);
 #define TIG_NUM_STEP_KERNELS 5
 TIG_API int tig_step_profiled(tig_ctx *ctx, const tig_batch *batch, const tig_out *out,
                               float *kernel_ms);
+
+/*
+ * tig_step for callers that must not allocate device memory or touch an allocator while stepping
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc) and want the
+ * step's intermediates out of their own workspace: the same step, same kernels, but every per-step
+ * intermediate (neighbour tables, staged rows, winner lists, counters) lives in an array that the
+ * library holds statically on each GPU (TIG_STATIC_SCRATCH_BYTES per GPU, from library load to
+ * process end; its device address is resolved once per device in tig_init).  Inputs, outputs and
+ * the model state stay where tig_init put them.  The call allocates nothing and calls no
+ * allocating routine.
+ *   - only contexts with message_order = TIG_UPDATE_FIRST (else TIG_EINVAL);
+ *   - TIG_ENOSPACE if the intermediates of the context's configuration (they grow with
+ *     max_batch * (24 * num_neighbors + 8 * mem_dim)) exceed TIG_STATIC_SCRATCH_BYTES;
+ *   - the winners are selected by the call itself and nothing is kept in the array for a later
+ *     call, so calls may be mixed freely with tig_step on any context;
+ *   - every call on one GPU uses the same array: calls whose kernels may overlap on one GPU (two
+ *     contexts on different streams) race and must be serialised by the caller.
+ * Otherwise as tig_step (arguments, outputs, errors, chronological order).
+ */
+#define TIG_STATIC_SCRATCH_BYTES (32u << 20)
+TIG_API int tig_step_static(tig_ctx *ctx, const tig_batch *batch, const tig_out *out);
 
 /* Memory reset at the start of a data cycle (Alg. 2): memory <- 0, last_update <- 0. Async. */
 TIG_API int tig_reset(tig_ctx *ctx);

@@ -9,6 +9,29 @@
 
 using namespace tig;
 
+// Per-step intermediates of tig_step_static: one array per GPU, held until the process ends.
+// The name below is a host-side stand-in, not a device address: host code resolves the array's
+// address on each device once (static_scratch_of) and only ever uses that pointer.
+static __device__ __align__(256) unsigned char g_static_scratch[TIG_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static void *g_static_ptr[kMaxDevices];  // device address of the array on each GPU, NULL until resolved
+
+// Address of the static scratch array on the CURRENT device `dev` (resolved on first use).
+static hipError_t static_scratch_of(int dev, void **out)
+{
+    if (dev < 0 || dev >= kMaxDevices)
+        return hipErrorInvalidDevice;
+    if (!g_static_ptr[dev]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch));
+        if (e != hipSuccess)
+            return e;
+        g_static_ptr[dev] = p;
+    }
+    *out = g_static_ptr[dev];
+    return hipSuccess;
+}
+
 struct tig_ctx {
     Dims d;
     LaunchPlan plan;
@@ -43,6 +66,7 @@ struct tig_ctx {
     int64_t pend_first;
     int32_t pend_count;
     int32_t *pos;
+    void *static_scratch;  // this device's copy of g_static_scratch
     hipEvent_t marks[kNumStepKernels + 1];
     bool have_marks;
     char err[256];
@@ -336,6 +360,7 @@ int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *w
         INIT_TRY(hipGetDevice(&dev), "hipGetDevice");
         INIT_TRY(hipDeviceGetAttribute(&ctx->num_cus, hipDeviceAttributeMultiprocessorCount, dev), "compute unit count");
         ctx->plan.num_cus = ctx->num_cus;
+        INIT_TRY(static_scratch_of(dev, &ctx->static_scratch), "hipGetSymbolAddress(static scratch)");
     }
 
     const PersistentLayout L = persistent_layout(d, N, E, persistent);
@@ -419,7 +444,11 @@ int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *w
     return TIG_OK;
 }
 
-static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, hipEvent_t *marks)
+// `use_static`: every per-step intermediate lives in this device's static scratch array instead of
+// the context's scratch workspace, the winners are selected up front by the call itself, and
+// nothing is kept there for a later call.
+static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, hipEvent_t *marks,
+                     bool use_static = false)
 {
     if (!ctx)
         return TIG_EINVAL;
@@ -433,6 +462,15 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
         return fail(ctx, TIG_EINVAL, "tig_step: required output pointer is NULL");
     if (batch->first_eid < ctx->cursor)
         return fail(ctx, TIG_EORDER, "tig_step: batch starts before the end of the previous one");
+    StepScratch st;
+    if (use_static) {
+        if (ctx->d.deferred)
+            return fail(ctx, TIG_EINVAL, "tig_step_static: the context runs the deferred message order");
+        if (step_scratch(ctx->d, nullptr).bytes > (size_t)TIG_STATIC_SCRATCH_BYTES)
+            return fail(ctx, TIG_ENOSPACE, "tig_step_static: the per-step intermediates of this configuration "
+                                           "exceed TIG_STATIC_SCRATCH_BYTES");
+        st = step_scratch(ctx->d, ctx->static_scratch);
+    }
 
     StepArgs a;
     a.src = ctx->src;
@@ -449,11 +487,11 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     a.count = batch->count;
     a.roles = batch->neg_dst ? 3 : 2;
     a.neg = batch->neg_dst;
-    a.nbr_node = out->nbr_node ? out->nbr_node : ctx->nbr_node;
-    a.nbr_eid = out->nbr_eid ? out->nbr_eid : ctx->nbr_eid;
-    a.nbr_ts = out->nbr_ts ? out->nbr_ts : ctx->nbr_ts;
-    a.nbr_cnt = out->nbr_cnt ? out->nbr_cnt : ctx->nbr_cnt;
-    a.staging = ctx->staging;
+    a.nbr_node = out->nbr_node ? out->nbr_node : (use_static ? st.nbr_node : ctx->nbr_node);
+    a.nbr_eid = out->nbr_eid ? out->nbr_eid : (use_static ? st.nbr_eid : ctx->nbr_eid);
+    a.nbr_ts = out->nbr_ts ? out->nbr_ts : (use_static ? st.nbr_ts : ctx->nbr_ts);
+    a.nbr_cnt = out->nbr_cnt ? out->nbr_cnt : (use_static ? st.nbr_cnt : ctx->nbr_cnt);
+    a.staging = use_static ? st.staging : ctx->staging;
     a.pos = ctx->pos;
     a.is_winner = out->is_winner;
     a.emb = out->emb;
@@ -465,7 +503,20 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     StepArgs sel;
     const StepArgs *selp = nullptr;
     int launches = 0;
-    if (ctx->d.deferred) {
+    int new_cur = ctx->cur;
+    if (use_static) {
+        // everything in the static array; this batch's winners are selected first, none ahead
+        a.win = st.win[0];
+        a.n_win = st.n_win[0];
+        a.msg_first_eid = batch->first_eid;
+        a.msg_count = batch->count;
+        a.next_first_eid = batch->first_eid + batch->count;
+        a.next_count = 0;
+        a.next_win = st.win[1];
+        a.next_n_win = st.n_win[1];
+        selp = &a;
+        launches += (one_launch ? 1 : 2) + 3;
+    } else if (ctx->d.deferred) {
         // Deferred order: the GRU and the memory overwrite apply the winners kept by the previous
         // step; this step's winners go to the other list, selected by one extra workgroup of the
         // embedding launch when it can carry it, else by a selection of its own up front (it
@@ -497,10 +548,9 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
         // in between do not matter).  A caller that asks for the per-entry flags gets a fresh run.
         const bool ready = ctx->ahead_valid && ctx->ahead_first == batch->first_eid &&
                            ctx->ahead_count == batch->count && !out->is_winner && !marks;
-        if (ready)
-            ctx->cur ^= 1;
-        a.win = ctx->win[ctx->cur];
-        a.n_win = ctx->n_win[ctx->cur];
+        new_cur = ready ? ctx->cur ^ 1 : ctx->cur;  // takes effect once the launches have succeeded
+        a.win = ctx->win[new_cur];
+        a.n_win = ctx->n_win[new_cur];
         a.msg_first_eid = batch->first_eid;
         a.msg_count = batch->count;
         // Chronological training and evaluation pass consecutive batches of one size: guess that the
@@ -508,8 +558,8 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
         // (The profiled step keeps every kernel to its own work.)
         a.next_first_eid = batch->first_eid + batch->count;
         a.next_count = 0;
-        a.next_win = ctx->win[ctx->cur ^ 1];
-        a.next_n_win = ctx->n_win[ctx->cur ^ 1];
+        a.next_win = ctx->win[new_cur ^ 1];
+        a.next_n_win = ctx->n_win[new_cur ^ 1];
         if (!marks && a.next_first_eid < ctx->num_events) {
             const int64_t left = ctx->num_events - a.next_first_eid;
             const int32_t guess = left < batch->count ? (int32_t)left : batch->count;
@@ -522,14 +572,24 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
         }
         launches += 3;
     }
-    ctx->ahead_valid = false;
     const hipError_t e = launch_step(ctx->d, ctx->plan, ctx->pw, a, selp, ctx->stream, marks);
-    if (e != hipSuccess)
+    if (e != hipSuccess) {
+        // kernels of this step may already be enqueued: the list bookkeeping stays as it was, the
+        // model state is undefined until tig_reset / tig_state_import
+        if (!use_static)
+            ctx->ahead_valid = false;
         return fail(ctx, TIG_EHIP, "tig_step launch", e);
+    }
+    if (!use_static) {
+        ctx->ahead_valid = false;
+        ctx->cur = new_cur;
+    }
     ctx->cursor = batch->first_eid + batch->count;
     if (!marks)
         ctx->last_launches = launches;
-    if (ctx->d.deferred) {
+    if (use_static) {
+        // the context's own lists are untouched: a list selected ahead stays usable
+    } else if (ctx->d.deferred) {
         ctx->cur ^= 1;  // the list just selected is the one the next step applies
         ctx->pend_valid = true;
         ctx->pend_first = batch->first_eid;
@@ -545,6 +605,11 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
 int tig_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *out)
 {
     return step_impl(ctx, batch, out, nullptr);
+}
+
+int tig_step_static(tig_ctx *ctx, const tig_batch *batch, const tig_out *out)
+{
+    return step_impl(ctx, batch, out, nullptr, true);
 }
 
 int tig_step_profiled(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, float *kernel_ms)

@@ -57,7 +57,7 @@ class tig_out(Structure):
                 ("is_winner", c_void_p)]
 
 
-EXPORTS = ("tig_workspace_bytes", "tig_init", "tig_step", "tig_step_profiled", "tig_reset", "tig_state_export",
+EXPORTS = ("tig_workspace_bytes", "tig_init", "tig_step", "tig_step_static", "tig_step_profiled", "tig_reset", "tig_state_export",
            "tig_state_import", "tig_destroy", "tig_strerror", "tig_last_error", "tig_launch_info")
 
 _lib = None
@@ -82,6 +82,7 @@ def load_library() -> ctypes.CDLL:
     lib.tig_init.argtypes = [POINTER(tig_config), POINTER(tig_graph), POINTER(tig_weights), c_void_p,
                              c_size_t, c_void_p, c_size_t, c_void_p, POINTER(c_void_p)]
     lib.tig_step.argtypes = [c_void_p, POINTER(tig_batch), POINTER(tig_out)]
+    lib.tig_step_static.argtypes = [c_void_p, POINTER(tig_batch), POINTER(tig_out)]
     lib.tig_step_profiled.argtypes = [c_void_p, POINTER(tig_batch), POINTER(tig_out), POINTER(c_float)]
     lib.tig_reset.argtypes = [c_void_p]
     lib.tig_state_export.argtypes = [c_void_p, c_void_p, c_void_p]
@@ -93,7 +94,7 @@ def load_library() -> ctypes.CDLL:
     lib.tig_last_error.argtypes = [c_void_p]
     lib.tig_last_error.restype = ctypes.c_char_p
     lib.tig_launch_info.argtypes = [c_void_p, POINTER(c_int32), POINTER(c_int32), POINTER(c_int32)]
-    for n in ("tig_workspace_bytes", "tig_init", "tig_step", "tig_step_profiled", "tig_reset", "tig_state_export",
+    for n in ("tig_workspace_bytes", "tig_init", "tig_step", "tig_step_static", "tig_step_profiled", "tig_reset", "tig_state_export",
               "tig_state_import", "tig_launch_info"):
         getattr(lib, n).restype = ctypes.c_int
     _lib = lib
@@ -196,13 +197,15 @@ class TigContext:
         return StepOutputs(emb, sp, sn, nn_, ne, nt, nc, iw)
 
     # -- the C calls -------------------------------------------------------------------------
-    def step(self, first_eid: int, count: int, neg_dst, out: StepOutputs):
-        """Enqueues one batch step on the context's stream (does not synchronise)."""
+    def step(self, first_eid: int, count: int, neg_dst, out: StepOutputs, static: bool = False):
+        """Enqueues one batch step on the context's stream (does not synchronise).
+        static=True calls tig_step_static (intermediates in the library's static device array)."""
         b = tig_batch(ctypes.sizeof(tig_batch), count, first_eid, _addr(neg_dst))
         o = tig_out(ctypes.sizeof(tig_out), 0, _addr(out.emb), _addr(out.score_pos), _addr(out.score_neg),
                     _addr(out.nbr_node), _addr(out.nbr_eid), _addr(out.nbr_ts), _addr(out.nbr_cnt),
                     _addr(out.is_winner))
-        self._check(self.lib.tig_step(self.handle, ctypes.byref(b), ctypes.byref(o)))
+        fn = self.lib.tig_step_static if static else self.lib.tig_step
+        self._check(fn(self.handle, ctypes.byref(b), ctypes.byref(o)))
 
     KERNEL_NAMES = ("k_scatter", "k_select", "k_gru", "k_commit", "k_embed")
 
