@@ -20,40 +20,109 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
+BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
+FP32_MFMA_PEAK_TFLOPS = 157.3
 
-# HBM bytes per launch of the dominant kernel (k_embed), from two rocprofv3 --pmc runs (FETCH_SIZE,
-# WRITE_SIZE), each scaled by what the counter reads for a plain 256 MiB device copy; see
-# profiles/hbm_traffic_c5_gpu_partition_bf16.md.  Only known for the combinations measured.
-MEASURED_TRAFFIC_BYTES = {("c5_gpu_partition", "bf16", 4000): 17.2e6}
+CSRC = os.path.join(ROOT, "paper_2308_14129_amd", "csrc")
+PROFILES = os.path.join(ROOT, "profiles")
 
 
 def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(w, count, roles, nbr_cnt_sum, winners):
-    """Bytes the method itself must move per step, by kernel (fp32 state, fp64 times, int32 ids).
-    Uses the actual number of filled neighbour slots and of distinct updated nodes."""
+def kernel_source_id():
+    """Hash of the kernel sources: counter figures under profiles/ name the sources they were
+    measured on and are reported only while the sources are still those."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(CSRC)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(CSRC, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def counter_figures(workload, precision, batch):
+    """key: value lines of profiles/counters_<workload>_<precision>.md (written from the rocprofv3
+    --pmc runs described there); {} if there is none, it is for another batch size, or the kernel
+    sources have changed since."""
+    path = os.path.join(PROFILES, f"counters_{workload}_{precision}.md")
+    if not os.path.exists(path):
+        return {}
+    vals = {}
+    for line in open(path):
+        line = line.strip()
+        if line.startswith("- `") and "`:" in line:
+            k, v = line[3:].split("`:", 1)
+            vals[k.strip()] = v.strip()
+    if vals.get("kernel_source_id") != kernel_source_id() or vals.get("batch") != str(batch):
+        return {}
+    return vals
+
+
+def distinct_queries(g, first, count, nbr_cnt):
+    """Rows the embedding kernel computes for the batch: one per distinct (node, t) among the
+    sources and destinations (each taken once, with its neighbour count) plus one per negative.
+    Returns (rows, filled neighbour slots over those rows)."""
+    import numpy as np
+    nodes = np.concatenate([g.src[first:first + count], g.dst[first:first + count]]).astype(np.int64)
+    times = np.concatenate([g.ts[first:first + count]] * 2)
+    _, idx = np.unique(np.stack([nodes.astype(np.float64), times], 1), axis=0, return_index=True)
+    rows = len(idx) + count
+    slots = int(nbr_cnt[idx].sum()) + int(nbr_cnt[2 * count:].sum())
+    return rows, slots
+
+
+def algorithmic_bytes(w, count, rows_u, slots_u, winners):
+    """Bytes the method itself must move per step, by kernel (fp32 state, fp64 times, int32 ids),
+    counted over the DISTINCT queries of the batch: rows_u rows with slots_u filled neighbour
+    slots (the same (node, t) is looked up and embedded once), `winners` updated nodes."""
     M, F, E, K = w.mem_dim, w.feat_dim, w.emb_dim, w.num_neighbors
-    Q = roles * count
+    Q = 3 * count
     entries = 2 * count
+    src_dst_rows = rows_u - count
+    lookup = 4 + 8 + 16 + 4 + 16 * K + 16 * K + 4  # id, time, two offsets, position, window in; slots + count out
     return {
-        # scatter: event (src, dst, ts) reads + one 8-byte key update per entry; lookup: per query
-        # node id, time, two offsets, the K-entry window; writes of the K slots + count
-        "k_scatter": entries * (4 + 8 + 8) * 2 + entries * 8 + winners * (8 + 24),
-        # own launch only for batches above 4096 events (otherwise fused into k_scatter)
-        "k_select": 0,
-        # per winner: descriptor, two memory rows, edge feature; new row out.  Per query (lookup,
-        # same launch): node id, time, two offsets, position, the K-entry window; K slots + count out
-        "k_gru": winners * (24 + 8 + (2 * M + F) * 4) + winners * M * 4
-                 + Q * (4 + 8 + 16 + 4 + 16 * K) + Q * (16 * K + 4),
-        # per winner: descriptor and staged row in, memory row + last_update + key out
-        "k_commit": winners * (24 + 2 * M * 4 + 16),
-        # per query: own memory row, neighbour table; per filled slot a memory row + an edge
-        # feature row; embedding and scores out
-        "k_embed": Q * (M * 4 + 4 + 4) + nbr_cnt_sum * ((M + F) * 4 + 16) + Q * E * 4 + (roles - 1) * count * 4,
+        "k_scatter": 0, "k_select": 0,  # launches of their own only for batches above 4096 events
+        # (inside the previous embedding launch in a chronological pass) winners: event reads, one
+        # key per entry, descriptors out; queries: event reads and one lookup per distinct pair
+        "k_prepare": entries * (4 + 8 + 8) * 2 + winners * (8 + 24) + src_dst_rows * lookup,
+        # per winner: descriptor, last_update, two memory rows, edge feature in, new row out;
+        # negatives' lookups; one key read and one reference per filled slot and per row
+        "k_gru": winners * (24 + 8 + (2 * M + F) * 4 + M * 4) + count * lookup + (slots_u + rows_u) * 12,
+        # per distinct query: own state row, descriptors; per filled slot a state row, an edge
+        # feature row, reference, event id, time; embedding and the two decoder halves out
+        "k_embed": rows_u * (M * 4 + 24) + slots_u * ((M + F) * 4 + 16) + rows_u * 3 * E * 4,
+        # per event: three embedding rows and three decoder halves in, three embedding rows and
+        # the scores out; per winner: staged row in, memory row and last_update out
+        "k_decode": count * 6 * E * 4 + Q * E * 4 + 2 * count * 4 + winners * (24 + 2 * M * 4 + 8),
     }
+
+
+def mfma_flops(w, rows_u, winners, precision):
+    """Multiply-adds x 2 the matrix cores execute per launch for the padded tile shapes, and the
+    useful part (unpadded, one product per multiply instead of three for split bf16 operands)."""
+    def up(x, m):
+        return (x + m - 1) // m * m
+    kb = 32 if precision == "bf16" else 16
+    split = 3 if precision == "bf16" else 1
+    M, T, F, E, H = w.mem_dim, w.time_dim, w.feat_dim, w.emb_dim, w.num_heads
+    dkv = M + F + T
+    dkvp, Mq, Ep, Ek, Ng = up(dkv, kb), up(M, kb), up(E, 16), up(E, kb), up(M, 16)
+    Kg, Khn = up(2 * M + T + F, kb), up(M, kb)
+    rows16 = up(rows_u, 16)
+    win16 = up(winners, 16)
+    issued = {
+        "k_gru": 2 * win16 * (3 * Ng * Kg + Ng * Khn) * split,
+        "k_embed": 2 * rows16 * (H * dkvp * Mq + Ep * (H * dkvp + Mq) + 3 * Ep * Ek) * split,
+    }
+    useful = {
+        "k_gru": 2 * winners * (3 * M * (2 * M + T + F) + M * M),
+        "k_embed": 2 * rows_u * (H * dkv * M + E * (H * dkv + M) + 3 * E * E),
+    }
+    return issued, useful
 
 
 def main():
@@ -142,7 +211,8 @@ def main():
     ms_per_step = wall_s * 1e3 / K
     value = events / wall_s
 
-    # ---- per-kernel durations (HIP events around every kernel, same stream, same batches) --------
+    # ---- per-kernel durations: HIP events on the context's stream around every kernel of the SAME
+    # launch sequence the timed region ran (same batches, prepared ahead in the same way) ----------
     ctx.state_import(mem0, lu0)
     run(0, W_)
     torch.cuda.synchronize()
@@ -151,12 +221,16 @@ def main():
     sums = np.zeros(len(names))
     byte_sums = {n: 0.0 for n in names}
     n_prof = min(K, 50)
+    rows_sum = slots_sum = win_sum = 0
+    launches_prof = set()
     for i in range(W_, W_ + n_prof):
         ms = ctx.step_profiled(batches[i][0], batches[i][1], negs[i], insp)
+        launches_prof.add(ctx.launch_info()["kernels_per_step"])
         sums += np.array(ms)
-        cnt_sum = int(insp.nbr_cnt.sum().item())
+        rows_u, slots_u = distinct_queries(g, batches[i][0], batches[i][1], insp.nbr_cnt.cpu().numpy())
         winners = int(insp.is_winner.sum().item())
-        for n, v in algorithmic_bytes(w, batches[i][1], 3, cnt_sum, winners).items():
+        rows_sum, slots_sum, win_sum = rows_sum + rows_u, slots_sum + slots_u, win_sum + winners
+        for n, v in algorithmic_bytes(w, batches[i][1], rows_u, slots_u, winners).items():
             byte_sums[n] += v
     avg_ms = sums / n_prof
     dom = int(np.argmax(avg_ms))
@@ -165,13 +239,29 @@ def main():
     achieved = dom_bytes / (avg_ms[dom] * 1e-3) / 1e9
     stages = {n: {"avg_us": round(float(avg_ms[i]) * 1e3, 2),
                   "alg_bytes": int(byte_sums[n] / n_prof),
-                  "GBps": round(byte_sums[n] / n_prof / (float(avg_ms[i]) * 1e-3) / 1e9, 1)}
-              for i, n in enumerate(names)}
+                  "GBps": round(byte_sums[n] / n_prof / max(float(avg_ms[i]), 1e-9) / 1e6, 1)}
+              for i, n in enumerate(names) if avg_ms[i] > 1e-4 or byte_sums[n] > 0}
+    figs = counter_figures(w.name, precision, B)
+    traffic = float(figs["k_embed_hbm_bytes_per_launch"]) if dom_name == "k_embed" and \
+        "k_embed_hbm_bytes_per_launch" in figs else None
     roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
-                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, precision, B)) if dom_name == "k_embed" else None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic,
                 "avg_kernel_us": round(float(avg_ms[dom]) * 1e3, 2), "alg_bytes_per_launch": int(dom_bytes),
-                "profiled_steps": n_prof}
+                "profiled_steps": n_prof, "kernels_per_profiled_step": sorted(launches_prof),
+                "distinct_query_rows": round(rows_sum / n_prof, 1), "queries": 3 * B,
+                "winners": round(win_sum / n_prof, 1)}
+    issued, useful = mfma_flops(w, rows_sum / n_prof, win_sum / n_prof, precision)
+    peak_tf = BF16_PEAK_TFLOPS if precision == "bf16" else FP32_MFMA_PEAK_TFLOPS
+    mfma = {}
+    for n in ("k_gru", "k_embed"):
+        t_s = float(avg_ms[names.index(n)]) * 1e-3
+        mfma[n] = {"issued_GFLOP": round(issued[n] / 1e9, 3), "useful_GFLOP": round(useful[n] / 1e9, 3),
+                   "issued_frac_of_peak": round(issued[n] / t_s / 1e12 / peak_tf, 5),
+                   "useful_frac_of_peak": round(useful[n] / t_s / 1e12 / peak_tf, 5)}
+    mfma["peak_TFLOPs"] = peak_tf
+    for k in ("k_embed_mfma_busy_frac", "k_gru_mfma_busy_frac"):
+        if k in figs:
+            mfma[k] = float(figs[k])
 
     # ---- CPU baseline: the oracle, as it stands, single thread, on a bounded sample ---------------
     cpu = None
@@ -244,6 +334,7 @@ def main():
         "gpu_ms_per_step_events": round(gpu_ms / K, 5),
         "kernels_per_step": info["kernels_per_step"],
         "roofline": roofline,
+        "mfma_util": mfma,
         "stages": stages,
         "cpu_baseline": cpu,
     }

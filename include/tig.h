@@ -181,25 +181,32 @@ TIG_API int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_we
  * that starts before the cursor.  neg_dst values must be valid node ids (they
  * are not checked on the device; an id outside 0..N-1 is treated as a node without history and
  * with zero memory).
- * Chronological passes hand over consecutive batches of one size, so every step also selects,
- * inside its embedding launch, the step-2 winners of the batch that would follow it
- * (first_eid + count, same count, clipped at the end of the stream).  That selection reads the
- * event stream only, never the model state; the next call uses it if its batch is exactly that
- * one and out->is_winner is NULL, and otherwise selects its winners itself.  Results do not
- * depend on whether the guess was right, and tig_reset / tig_state_import in between are fine.
+ * The embedding of a query depends on (node, t_event) only, and the sources and destinations of a
+ * batch repeat the same pairs many times (hub nodes, events sharing a timestamp): every distinct
+ * pair is embedded once and its row is handed to every query that asked for it, so equal queries
+ * get bit-identical embeddings.  Negatives are not merged.
+ * Chronological passes hand over consecutive batches of one size, so every step also prepares,
+ * inside its embedding launch, the batch that would follow it (first_eid + count, same count,
+ * clipped at the end of the stream): its step-2 winners and the neighbour lists of its distinct
+ * source / destination queries.  That preparation reads the event stream and the adjacency only,
+ * never the model state; the next call uses it if its batch is exactly that one, and otherwise
+ * prepares its batch itself in one more launch.  Results do not depend on whether the guess was
+ * right, and tig_reset / tig_state_import in between are fine.
  */
 TIG_API int tig_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *out);
 
 /*
- * The same step with a HIP event recorded on the context's stream before the first and after
- * every kernel; waits for the step to finish and writes the five kernel durations in
- * milliseconds to kernel_ms[0..4] (host), in launch order: key scatter (with the winner selection
- * fused in for batches of up to 4096 events), winner selection as its own launch (larger batches;
- * otherwise ~0), message + GRU together with the neighbour lookup, memory overwrite, attention
- * embedding + decoder.  For measurement:
- * the event records add gaps between kernels, so time throughput with tig_step.
+ * The same step, same launches, with a HIP event recorded on the context's stream before the first
+ * and after every kernel; waits for the step to finish and writes the kernel durations in
+ * milliseconds to kernel_ms[0..TIG_NUM_STEP_KERNELS-1] (host), in launch order:
+ *   0, 1  key scatter and winner selection of a batch above 4096 events (else ~0)
+ *   2     preparation of a batch that the previous step did not prepare (else ~0)
+ *   3     message + GRU, with the negatives' neighbour lookups and the row references
+ *   4     attention embedding, merge MLP, first decoder layer (and the next batch's preparation)
+ *   5     scores, per-query embedding rows, memory overwrite
+ * For measurement: the event records add gaps between kernels, so time throughput with tig_step.
  */
-#define TIG_NUM_STEP_KERNELS 5
+#define TIG_NUM_STEP_KERNELS 6
 TIG_API int tig_step_profiled(tig_ctx *ctx, const tig_batch *batch, const tig_out *out,
                               float *kernel_ms);
 
@@ -207,16 +214,17 @@ TIG_API int tig_step_profiled(tig_ctx *ctx, const tig_batch *batch, const tig_ou
  * tig_step for callers that must not allocate device memory or touch an allocator while stepping
  * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc) and want the
  * step's intermediates out of their own workspace: the same step, same kernels, but every per-step
- * intermediate (neighbour tables, staged rows, winner lists, counters) lives in an array that the
+ * intermediate (query rows, staged rows, winner lists, counters) lives in an array that the
  * library holds statically on each GPU (TIG_STATIC_SCRATCH_BYTES per GPU, from library load to
  * process end; its device address is resolved once per device in tig_init).  Inputs, outputs and
  * the model state stay where tig_init put them.  The call allocates nothing and calls no
  * allocating routine.
  *   - only contexts with message_order = TIG_UPDATE_FIRST (else TIG_EINVAL);
- *   - TIG_ENOSPACE if the intermediates of the context's configuration (they grow with
- *     max_batch * (24 * num_neighbors + 8 * mem_dim)) exceed TIG_STATIC_SCRATCH_BYTES;
- *   - the winners are selected by the call itself and nothing is kept in the array for a later
- *     call, so calls may be mixed freely with tig_step on any context;
+ *   - TIG_ENOSPACE if the intermediates of the context's configuration (about
+ *     max_batch * (120 * num_neighbors + 8 * mem_dim + 36 * emb_dim + 250) bytes) exceed
+ *     TIG_STATIC_SCRATCH_BYTES;
+ *   - the call prepares its batch itself (winners, queries) and keeps nothing in the array for a
+ *     later call, so calls may be mixed freely with tig_step on any context;
  *   - every call on one GPU uses the same array: calls whose kernels may overlap on one GPU (two
  *     contexts on different streams) race and must be serialised by the caller.
  * Otherwise as tig_step (arguments, outputs, errors, chronological order).
@@ -243,9 +251,9 @@ TIG_API void tig_destroy(tig_ctx *ctx);
 TIG_API const char *tig_strerror(int status);
 TIG_API const char *tig_last_error(const tig_ctx *ctx);
 
-/* For reports: the number of kernels the last tig_step enqueued (3 when the previous step had
- * selected this batch's winners ahead, 4 otherwise, 5 for batches above 4096 events; 0 before the
- * first step) and the dynamic LDS bytes of the two tile kernels at their largest tile count.
+/* For reports: the number of kernels the last step enqueued (3 when the previous step had
+ * prepared this batch, 4 otherwise, 6 for batches above 4096 events; 0 before the first step) and
+ * the dynamic LDS bytes of the two tile kernels at their largest tile count.
  * Any pointer may be NULL. */
 TIG_API int tig_launch_info(const tig_ctx *ctx, int32_t *kernels_per_step, int32_t *gru_lds_bytes,
                             int32_t *embed_lds_bytes);

@@ -1,22 +1,31 @@
-// k_embed: temporal attention embedding, merge MLP and link decoder of one batch step
-// (embedding module f and decoder g of the paper's Sec. II-C), fused in one kernel.  gfx950 only.
+// k_embed: temporal attention embedding and merge MLP of one batch step (embedding module f of
+// the paper's Sec. II-C) and the first decoder layer (decoder g), fused in one kernel, for the
+// DISTINCT queries (node, t) of the batch (prepare.h).  gfx950 only.
 //
-// One workgroup (16 wavefronts) owns TE consecutive events x {source, destination, negative}
-// query rows, 16*MT rows in all, and keeps every intermediate of those rows in LDS:
-//   A  query rows: node, query index, neighbour count, s_u (the UPDATED memory row)
+// One workgroup (16 wavefronts) takes 16*MT rows of the query set at a time and keeps every
+// intermediate of those rows in LDS:
+//   A  row descriptors: row reference of the node's state, neighbour count, time; s_u
 //   B  folded query  q~ = A1 s_u + a1                        (matrix cores; fp32 result)
 //   C  per row: gather the K neighbour rows [Phi(t - t_k) | s_v | e], scores <q~_h, kv_k>,
 //      softmax over the filled slots, kvbar_h = sum_k a_k kv_k   (vector ALU, one wavefront/row)
 //   D  h1 = relu(P kvbar + R s_u + c)                         (matrix cores, k split over 2 waves)
-//   E  emb = W_m2 h1 + b_m2 -> global                         (matrix cores)
-//   F  decoder layer 1 split by operand: [W_a emb | W_b emb]  (matrix cores)
-//   G  logit = w_d2 . relu(W_a emb_src + W_b emb_other + b_d1) + b_d2
+//   E  from h1 in one pass: emb = W_m2 h1 + b_m2 and both halves of decoder layer 1,
+//      W_d1[:, :E] emb and W_d1[:, E:] emb (merge layer 2 folded into the decoder weights)
+//      -> per-row arrays in global memory; the decode kernel pairs them up per event
+// State rows are read through row references: the memory table, or the staged GRU output for a
+// node this step updates (the memory overwrite runs after this kernel, beside the decode).
 // The projections W_Q, W_K, W_V, W_O and the first merge layer are folded into A1 and P at init
 // (pack.hip), which removes the per-neighbour key/value projections.
+// The number of rows is known on the device only: the grid has a tile for every 16*MT rows the
+// batch could have, and the tiles beyond the actual row count return at once.  Row r of tile p is
+// query row p + (number of tiles in use) * r, which spreads the heavy rows (sources /
+// destinations, first in the set) over all tiles.  Workgroups beyond the tiles prepare the batch expected next:
+// one selects its last-message winners, the others merge and look up its queries.
 #include <type_traits>
 #include <hip/hip_runtime.h>
 
 #include "kernels_common.h"
+#include "prepare.h"
 #include "winners.h"
 
 namespace tig {
@@ -42,12 +51,10 @@ struct EmbedShape {
 struct EmbedParams {
     int M, T, F, E, K;
     int dkv, dkvp, Mq, N1, K2, Ep, Ek;
-    int TE;         // events per workgroup; rows = roles * TE <= 16 * MT
     int row_bytes;  // LDS bytes per query row of the main buffer: [q~ / kvbar (N1) | s_u (Mq)]
     int ld1;        // row stride of the E-wide buffers, bytes
     int off_h1, off_meta;  // byte offsets in LDS
-    int dec_off;    // byte offset of the decoder pre-activations (inside the main buffer)
-    int n_tiles;    // workgroups that own query rows; one more selects the next batch's winners
+    int n_tiles;    // workgroups that take row tiles; the ones beyond prepare the next batch
     // bit n set: register n of a key/value row (dims 64 n .. 64 n + 63 of [Phi | s_v | e]) holds
     // at least one dim of the time encoding / of the neighbour's memory / of the edge feature
     int phi_regs, mem_regs, feat_regs;
@@ -108,47 +115,50 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     constexpr int NPHI = NPL;  // registers that may hold time-encoding dims (T <= 64 * NPL)
     extern __shared__ __attribute__((aligned(16))) char smem[];
     if ((int)blockIdx.x >= p.n_tiles) {
-        // The workgroup beyond the last tile: last-message selection for the batch expected to
-        // follow, on a compute unit this launch leaves idle (launched only with 1024 threads).
-        if constexpr (kEmbedThreads == kScatterThreads)
-            winners_block(winners_job(a, true), smem);
+        // The workgroups beyond the tiles, on compute units this launch leaves idle (launched only
+        // with 1024 threads): last-message selection and query preparation for a later step.
+        if constexpr (kEmbedThreads == kScatterThreads) {
+            int x = (int)blockIdx.x - p.n_tiles;
+            if (a.sel.count > 0) {
+                if (x == 0) {
+                    winners_block(a, a.sel, smem);
+                    return;
+                }
+                --x;
+            }
+            if (a.ded.count > 0 && x < a.ded.n_wgs)
+                dedup_block(a, a.ded, p.K, x, smem);
+        }
         return;
     }
     char *rowbuf = smem;
     char *h1buf = smem + p.off_h1;
-    int *row_q = (int *)(smem + p.off_meta);  // [ROWS] query index or -1
+    int *row_q = (int *)(smem + p.off_meta);  // [ROWS] row of the query set or -1
     int *row_cnt = row_q + ROWS;              // [ROWS]
-    int *row_node = row_cnt + ROWS;           // [ROWS]
-    double *row_t = (double *)(row_node + ROWS);  // [ROWS] query time
+    int *row_ref = row_cnt + ROWS;            // [ROWS] row reference of the node's own state
+    double *row_t = (double *)(row_ref + ROWS);   // [ROWS] query time
     double *tw_tab = row_t + ROWS;                // [T][2] time-encoding (w_rev, b_rev)
     int *next_row = (int *)(tw_tab + 2 * p.T);    // [1] row counter of phase C
 
     const int lane = lane_id();
     const int wave = wave_id();
-    const int ev0 = blockIdx.x * p.TE;
     const int mem_off = 4 * p.N1;
+    const int n_rows = *a.qs.n_u + (a.roles == 3 ? a.count : 0);
+    const int n_passes = (n_rows + ROWS - 1) / ROWS;
 
+    const int pass = (int)blockIdx.x;
+    if (pass >= n_passes)
+        return;  // fewer distinct queries than the grid was sized for
     TIG_MARK(0);
     // ---- A. query rows ------------------------------------------------------------------------
     if (threadIdx.x < ROWS) {
         const int r = threadIdx.x;
-        const int role = r / p.TE;
-        const int b = ev0 + (r - role * p.TE);
-        const bool act = role < a.roles && b < a.count;
-        int32_t u = -1;
-        int q = -1, cnt = 0;
-        double t = 0.0;
-        if (act) {
-            const int64_t eid = a.first_eid + b;
-            u = role == 0 ? a.src[eid] : (role == 1 ? a.dst[eid] : a.neg[b]);
-            q = role * a.count + b;
-            cnt = a.nbr_cnt[q];
-            t = a.ts[eid];
-        }
-        row_q[r] = q;
-        row_node[r] = (u >= 0 && (int64_t)u < a.num_nodes) ? u : -1;
-        row_cnt[r] = cnt;
-        row_t[r] = t;
+        const int q = pass + n_passes * r;
+        const bool act = q < n_rows;
+        row_q[r] = act ? q : -1;
+        row_ref[r] = act ? a.qs.self_ref[q] : kRefNone;
+        row_cnt[r] = act ? a.qs.cnt[q] : 0;
+        row_t[r] = act ? a.qs.t[q] : 0.0;
     }
     if (threadIdx.x == 0)
         *next_row = 0;
@@ -163,16 +173,19 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
         constexpr int kRowsPerWave = (ROWS + kEmbedWaves - 1) / kEmbedWaves;
         constexpr int kAhead = 2;  // 128 floats of a row per lane pair of loads
         float v[kRowsPerWave][kAhead];
+        const float *src_row[kRowsPerWave];
 #pragma unroll
         for (int i = 0; i < kRowsPerWave; ++i) {
             const int r = wave + i * kEmbedWaves;
-            const int node = r < ROWS ? row_node[r] : -1;
+            const int ref = r < ROWS ? row_ref[r] : kRefNone;
+            src_row[i] = ref == kRefNone ? nullptr
+                                         : (ref >= 0 ? a.mem + (size_t)ref * p.M : a.staging + (size_t)(~ref) * p.M);
 #pragma unroll
             for (int u = 0; u < kAhead; ++u) {
                 const int j = lane + kWave * u;
                 v[i][u] = 0.0f;
-                if (node >= 0 && j < p.M)
-                    v[i][u] = a.mem[(size_t)node * p.M + j];
+                if (src_row[i] && j < p.M)
+                    v[i][u] = src_row[i][j];
             }
         }
 #pragma unroll
@@ -184,9 +197,8 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                 for (int u = 0; u < kAhead; ++u)
                     if (lane + kWave * u < p.Mq)
                         P::store_a(dst, lane + kWave * u, v[i][u]);
-                const int node = row_node[r];
                 for (int j = lane + kWave * kAhead; j < p.Mq; j += kWave)  // rows beyond 128 floats
-                    P::store_a(dst, j, node >= 0 && j < p.M ? a.mem[(size_t)node * p.M + j] : 0.0f);
+                    P::store_a(dst, j, src_row[i] && j < p.M ? src_row[i][j] : 0.0f);
             }
         }
     }
@@ -260,9 +272,9 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
             if (r < ROWS) {
                 const int q = row_q[r];
                 if (q >= 0 && lane < row_cnt[r]) {
-                    v = a.nbr_node[(size_t)q * p.K + lane];
-                    e = a.nbr_eid[(size_t)q * p.K + lane];
-                    dt = row_t[r] - a.nbr_ts[(size_t)q * p.K + lane];
+                    v = a.qs.ref[(size_t)q * p.K + lane];  // row reference of the neighbour's state
+                    e = a.qs.eid[(size_t)q * p.K + lane];
+                    dt = row_t[r] - a.qs.ts[(size_t)q * p.K + lane];
                 }
             }
         };
@@ -331,8 +343,9 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                     if (FULL || k < cnt) {  // scalar
                         const int32_t v = __builtin_amdgcn_readlane(nb_vc, k & 63);
                         const int32_t e = __builtin_amdgcn_readlane(nb_ec, k & 63);
-                        const __amdgpu_buffer_rsrc_t rm = __builtin_amdgcn_make_buffer_rsrc(
-                            (void *)(a.mem + (size_t)v * cM), 0, (int)m_bytes, kBufferFlags);
+                        const float *vrow = v >= 0 ? a.mem + (size_t)v * cM : a.staging + (size_t)(~v) * cM;
+                        const __amdgpu_buffer_rsrc_t rm =
+                            __builtin_amdgcn_make_buffer_rsrc((void *)vrow, 0, (int)m_bytes, kBufferFlags);
                         const __amdgpu_buffer_rsrc_t re = __builtin_amdgcn_make_buffer_rsrc(
                             (void *)(a.edge_feat + (size_t)e * cF), 0, (int)f_bytes, kBufferFlags);
 #pragma unroll
@@ -604,144 +617,59 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     __syncthreads();
 
     TIG_MARK(4);
-    // ---- E. merge layer 2: emb = W_m2 h1 + b_m2 -> global, and kept as the decoder operand ---
-    // ---- F. decoder layer 1, split by operand: [W_a emb | W_b emb] for every row -------------
-    // When the row tiles are whole roles (16 sources, 16 destinations, 16 negatives) both run as one
-    // phase from h1: merge layer 2 is folded into the decoder weights, the source tile takes only
-    // W_a and the other two only W_b, and seven wavefronts do each half.
-    const int nE = p.Ep / 16;
-    const bool fused = MT == 3 && a.roles == 3 && p.TE == 16 && 2 * nE <= kEmbedWaves;
-    const float *dec_b1 = fused ? w.dec_b1f : w.dec_b1;
-    float *decbuf = (float *)(rowbuf + p.dec_off);  // [ROWS x 2Ep]
-    // decoder layer 2 parameters of the first 128 dims, requested here and used in phase G
-    float g_w2[2], g_b1[2];
+    // ---- E. from h1: emb = W_m2 h1 + b_m2, and decoder layer 1 split by operand, W_a emb and
+    // W_b emb, through the decoder weights folded with merge layer 2 -> per-row arrays in global
+    // memory.  3 * Ep / 16 output tiles; a wavefront takes two at a time where it has two, which
+    // share the reads of h1.
+    {
+        const int nE = p.Ep / 16, kbE = p.Ek / P::KB;
+        const int n_out = 3 * nE;
+        auto put = [&](const floatx4 (&acc)[MT], int ot) {
+            const int grp = ot / nE;  // 0: embedding, 1: source half, 2: second-operand half
+            const int col = (ot - grp * nE) * 16 + (lane & 15);
+            const float bias = grp == 0 ? w.emb_bm2[col] : 0.0f;
+            float *dst = grp == 0 ? a.emb_u : (grp == 1 ? a.dec_a : a.dec_b);
+            const int ld = grp == 0 ? p.E : p.Ep;
+            if (grp == 0 && col >= p.E)
+                return;
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        const int j = lane + kWave * u;
-        g_w2[u] = j < p.E ? w.dec_w2[j] : 0.0f;
-        g_b1[u] = j < p.E ? dec_b1[j] : 0.0f;
-    }
-    const float g_b2 = w.dec_b2[0];
-    if (fused) {
-        if constexpr (MT == 3) {
-            const int kbE = p.Ek / P::KB;
-            if (wave < nE) {
-                floatx4 acc[MT];
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-                    acc[mt] = floatx4{0, 0, 0, 0};
-                const int col = wave * 16 + (lane & 15);
-                const float bias = w.emb_bm2[col];  // requested with the first weight operands
-                tile_gemm<PREC, MT, 4>(acc, h1buf, p.ld1, 0, w.emb_Wm2, kbE, 0, kbE, wave);
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int row = mt * 16 + 4 * (lane >> 4) + v;
-                        const int q = row_q[row];
-                        if (q >= 0 && col < p.E)
-                            a.emb[(size_t)q * p.E + col] = acc[mt][v] + bias;
-                    }
-            } else if (wave < 2 * nE) {
-                const int j = wave - nE;
-                floatx4 acc_a[1], acc_b[2];
-                acc_a[0] = floatx4{0, 0, 0, 0};
-                acc_b[0] = floatx4{0, 0, 0, 0};
-                acc_b[1] = floatx4{0, 0, 0, 0};
-                tile_gemm<PREC, 1, 4>(acc_a, h1buf, p.ld1, 0, w.dec_WF, kbE, 0, kbE, j);
-                tile_gemm<PREC, 2, 4>(acc_b, h1buf + (size_t)16 * p.ld1, p.ld1, 0, w.dec_WF, kbE, 0, kbE, nE + j);
-                const int col = j * 16 + (lane & 15);
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int row = 4 * (lane >> 4) + v;
-                    decbuf[(size_t)row * 2 * p.Ep + col] = acc_a[0][v];
-#pragma unroll
-                    for (int mt = 0; mt < 2; ++mt)
-                        decbuf[(size_t)(16 + mt * 16 + row) * 2 * p.Ep + p.Ep + col] = acc_b[mt][v];
+                    const int row = mt * 16 + 4 * (lane >> 4) + v;
+                    const int q = row_q[row];
+                    if (q >= 0)
+                        dst[(size_t)q * ld + col] = acc[mt][v] + bias;
                 }
+        };
+        auto weights_of = [&](int ot) -> const void * { return ot < nE ? w.emb_Wm2 : w.dec_WF; };
+        auto tile_of = [&](int ot) -> int { return ot < nE ? ot : ot - nE; };
+        for (int ot = wave; ot < n_out; ot += 2 * kEmbedWaves) {
+            const int ot2 = ot + kEmbedWaves;
+            floatx4 acc1[MT], acc2[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                acc1[mt] = floatx4{0, 0, 0, 0};
+                acc2[mt] = floatx4{0, 0, 0, 0};
+            }
+            if (ot2 < n_out) {
+                tile_gemm_pair<PREC, MT, 4>(acc1, acc2, h1buf, p.ld1, weights_of(ot), weights_of(ot2), kbE,
+                                            tile_of(ot), tile_of(ot2));
+                put(acc1, ot);
+                put(acc2, ot2);
+            } else {
+                tile_gemm<PREC, MT, 4>(acc1, h1buf, p.ld1, 0, weights_of(ot), kbE, 0, kbE, tile_of(ot));
+                put(acc1, ot);
             }
         }
-        __syncthreads();
-        TIG_MARK(5);
-    } else {
-        char *embbuf = rowbuf;  // [ROWS rows x ld1 bytes], the main buffer is free again
-        for (int nt = wave; nt < p.Ep / 16; nt += kEmbedWaves) {
-            floatx4 acc[MT];
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-                acc[mt] = floatx4{0, 0, 0, 0};
-            const int col = nt * 16 + (lane & 15);
-            const float bias = w.emb_bm2[col];  // requested with the first weight operands
-            tile_gemm<PREC, MT, 4>(acc, h1buf, p.ld1, 0, w.emb_Wm2, p.Ek / P::KB, 0, p.Ek / P::KB, nt);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int row = mt * 16 + 4 * (lane >> 4) + v;
-                    const float x = acc[mt][v] + bias;
-                    const int q = row_q[row];
-                    if (q >= 0 && col < p.E)
-                        a.emb[(size_t)q * p.E + col] = x;
-                    P::store_a(embbuf + (size_t)row * p.ld1, col, x);
-                }
-        }
-        for (int idx = threadIdx.x; idx < ROWS * (p.Ek - p.Ep); idx += kEmbedThreads) {
-            const int row = idx / (p.Ek - p.Ep), col = p.Ep + idx % (p.Ek - p.Ep);
-            P::store_a(embbuf + (size_t)row * p.ld1, col, 0.0f);
-        }
-        __syncthreads();
-
-        TIG_MARK(5);
-        // ---- F. decoder layer 1, split by operand: [W_a emb | W_b emb] for every row -------------
-        for (int nt = wave; nt < 2 * p.Ep / 16; nt += kEmbedWaves) {
-            floatx4 acc[MT];
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-                acc[mt] = floatx4{0, 0, 0, 0};
-            tile_gemm<PREC, MT, 4>(acc, embbuf, p.ld1, 0, w.dec_W, p.Ek / P::KB, 0, p.Ek / P::KB, nt);
-            const int col = nt * 16 + (lane & 15);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int row = mt * 16 + 4 * (lane >> 4) + v;
-                    decbuf[(size_t)row * 2 * p.Ep + col] = acc[mt][v];
-                }
-        }
-        __syncthreads();
     }
-
-    TIG_MARK(6);
-    // ---- G. logits: w_d2 . relu(W_a emb_src + W_b emb_other + b_d1) + b_d2 --------------------
-    const int pairs = p.TE * (a.roles - 1);
-    for (int pr = wave; pr < pairs; pr += kEmbedWaves) {
-        const int which = pr / p.TE;  // 0: destination, 1: negative
-        const int ev = pr - which * p.TE;
-        const int b = ev0 + ev;
-        if (b >= a.count)
-            continue;
-        const float *da = decbuf + (size_t)ev * 2 * p.Ep;
-        const float *db = decbuf + (size_t)((which + 1) * p.TE + ev) * 2 * p.Ep + p.Ep;
-        float part = 0.0f;
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int j = lane + kWave * u;
-            if (j < p.E)
-                part += g_w2[u] * fmaxf(da[j] + db[j] + g_b1[u], 0.0f);
-        }
-        for (int j = lane + 2 * kWave; j < p.E; j += kWave)
-            part += w.dec_w2[j] * fmaxf(da[j] + db[j] + dec_b1[j], 0.0f);
-        const float s = wave_sum_uniform(part) + g_b2;
-        if (lane == 0)
-            (which == 0 ? a.score_pos : a.score_neg)[b] = s;
-    }
-    TIG_MARK(7);
+    TIG_MARK(5);
 }
 
 // ------------------------------------------------------------------------------------------
 // host side
 
-EmbedParams embed_params(const Dims &d, int mt, int roles)
+EmbedParams embed_params(const Dims &d, int mt)
 {
     EmbedParams p;
     p.M = d.M;
@@ -757,17 +685,9 @@ EmbedParams embed_params(const Dims &d, int mt, int roles)
     p.Ep = d.Ep;
     p.Ek = d.Ek;
     const int rows = 16 * mt;
-    p.TE = rows / roles;
     p.row_bytes = lds_row_bytes(d.N1 + d.Mq);
     p.ld1 = lds_row_bytes(d.Ek);
-    const int emb_bytes = rows * p.ld1;
-    p.dec_off = (emb_bytes + 15) / 16 * 16;
-    int main_bytes = rows * p.row_bytes;
-    const int tail_bytes = p.dec_off + rows * 2 * d.Ep * 4;
-    if (tail_bytes > main_bytes)
-        main_bytes = tail_bytes;
-    main_bytes = (main_bytes + 15) / 16 * 16;
-    p.off_h1 = main_bytes;
+    p.off_h1 = (rows * p.row_bytes + 15) / 16 * 16;
     p.off_meta = p.off_h1 + rows * p.ld1;
     p.n_tiles = 0;
     p.phi_regs = p.mem_regs = p.feat_regs = 0;
@@ -870,21 +790,18 @@ const void *embed_kernel(const Dims &d, int mt)
 
 int embed_lds_bytes(const Dims &d, int mt)
 {
-    const EmbedParams p = embed_params(d, mt, 3);
+    const EmbedParams p = embed_params(d, mt);
     return p.off_meta + 16 * mt * (3 * 4 + 8) + d.T * 16 + 16;
 }
 
-// 16-row tiles per workgroup for a batch of `count` events: a workgroup's latency grows with its
-// rows, so small batches take the smallest tile count whose grid still starts at once (one
-// workgroup per compute unit, one unit spare for the winner selection of the next batch); large
-// batches take the largest, which streams the weights least often.
-static int embed_tiles(const LaunchPlan &plan, int roles, int count)
+// 16-row tiles per workgroup for a batch of `count` events.  A workgroup's latency grows with its
+// rows, so the smallest tile count is taken whose tiles, one per workgroup, cover the most rows
+// the batch can have (no repeated query) on the compute units at hand.
+static int embed_tiles(const LaunchPlan &plan, int roles, int count, int units)
 {
-    for (int mt = 1; mt < plan.emb_mt; ++mt) {
-        const int te = 16 * mt / roles;
-        if ((count + te - 1) / te + 1 <= plan.num_cus)
+    for (int mt = 1; mt < plan.emb_mt; ++mt)
+        if ((roles * count + 16 * mt - 1) / (16 * mt) <= units)
             return mt;
-    }
     return plan.emb_mt;
 }
 
@@ -901,13 +818,27 @@ hipError_t prepare_embed(const Dims &d, const LaunchPlan &plan)
     return hipSuccess;
 }
 
-bool embed_can_select_ahead(const Dims &d, const LaunchPlan &plan, int roles, int count, int next_count)
+// Workgroups of the preparation of a batch of `count` events.  When it shares a launch, every
+// workgroup occupies a compute unit (the launch's LDS size applies to all of its workgroups), so
+// there are few, each wavefront with several entries; on its own, four entries per wavefront.
+int prepare_workgroups(int count, bool shared)
 {
-    if (embed_threads(d) != kScatterThreads || next_count < 1 || 2 * next_count > kOneMaxEntries)
-        return false;
-    // every tile and the extra workgroup must start at once, each on a compute unit of its own
-    const int te = 16 * embed_tiles(plan, roles, count) / roles;
-    return (count + te - 1) / te + 1 <= plan.num_cus;
+    const int entries = 2 * count;
+    int n = shared ? (entries + kPrepWaves - 1) / kPrepWaves : (entries + 4 * kPrepWaves - 1) / (4 * kPrepWaves);
+    if (shared && n > 63)
+        n = 63;
+    const int least = (entries + kPrepThreads - 1) / kPrepThreads;  // one entry per thread at most
+    return n < least ? least : n;
+}
+
+int embed_spare_workgroups(const Dims &d, const LaunchPlan &plan, int roles, int count)
+{
+    if (embed_threads(d) != kScatterThreads)
+        return 0;
+    // the selection workgroup and the preparation workgroups of a batch of the same size; the row
+    // tiles keep at least three quarters of the compute units
+    const int want = 1 + prepare_workgroups(count, true);
+    return want <= plan.num_cus / 4 ? want : 0;
 }
 
 hipError_t launch_embed(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
@@ -915,16 +846,17 @@ hipError_t launch_embed(const Dims &d, const LaunchPlan &plan, const PackedWeigh
 {
     StepArgs aa = a;
     PackedWeights ww = pw;
-    const int mt = embed_tiles(plan, a.roles, a.count);
-    EmbedParams p = embed_params(d, mt, a.roles);
-    p.n_tiles = (a.count + p.TE - 1) / p.TE;
+    const int extra = (a.sel.count > 0 ? 1 : 0) + (a.ded.count > 0 ? a.ded.n_wgs : 0);
+    const int cus = plan.num_cus > 0 ? plan.num_cus : 256;
+    const int units = cus - extra > 16 ? cus - extra : 16;
+    const int mt = embed_tiles(plan, a.roles, a.count, units);
+    EmbedParams p = embed_params(d, mt);
+    p.n_tiles = (a.roles * a.count + 16 * mt - 1) / (16 * mt);  // tiles in use if no query repeats
     void *args[] = {&aa, &ww, &p};
-    const bool ahead = a.next_count > 0;
     const int threads = embed_threads(d);
     const int own = embed_lds_bytes(d, mt);
-    const int lds = ahead && own < kOneLds ? kOneLds : own;
-    return hipLaunchKernel(embed_kernel(d, mt), dim3(p.n_tiles + (ahead ? 1 : 0)), dim3(threads), args,
-                           (size_t)lds, s);
+    const int lds = a.sel.count > 0 && own < kOneLds ? kOneLds : (own < kPrepLds ? kPrepLds : own);
+    return hipLaunchKernel(embed_kernel(d, mt), dim3(p.n_tiles + extra), dim3(threads), args, (size_t)lds, s);
 }
 
 }  // namespace tig

@@ -1,22 +1,27 @@
 // k_gru: message build and GRU state update (message module, state-update module and memory
 // fetch of the paper's Sec. II-C) for the compacted winners of one batch.  gfx950 only.
-// The same launch carries the neighbour lookup of every query in extra workgroups (lookup.h):
-// it depends on nothing the GRU produces, and both are chains of dependent memory round trips,
-// so they hide each other's latency.
+// The same launch carries, in extra workgroups, what is left of the query preparation
+// (prepare.h): the lookups of the negatives and the row references.  They depend on nothing the
+// GRU produces, and both are chains of dependent memory round trips, so they hide each other.
 //
-// One workgroup (16 wavefronts) takes 16*MT winners:
+// The number of winners is only known on the device (hub nodes make it a small fraction of the
+// 2B entries), so the GRU workgroups are a fixed grid that divides the work itself: 16-row tiles
+// of winners x slices of the gate columns, as many column slices per tile as keep the grid busy
+// (every workgroup streams only its slice of the gate weights; all slices of a tile gather the
+// same rows).  One work item (16 wavefronts):
 //   1  row descriptors: node, partner, event, event time (dt = t - last_update[node] in step 2)
 //   2  message rows [s_self | s_other | Phi(dt) | e] gathered from the batch-START memory into an
 //      LDS tile (every element of every row is an independent load: one round of latency)
-//   3  gate pre-activations on the matrix cores.  Per 16-column tile two wavefronts work side by
-//      side: one computes the r and z gates, the other the two halves of the n gate (input part
-//      over the whole message, hidden part over s_self); r and z cross over through LDS
-//   4  h' = (1 - z) n + z h  -> staging rows (memory is overwritten by k_commit afterwards)
+//   3  gate pre-activations on the matrix cores: the 16 wavefronts are 8 pairs, one wavefront of
+//      a pair for the r and z gates, the other for the two halves of the n gate (input part over
+//      the whole message, hidden part over s_self); the pairs split the item's column tiles and,
+//      when there are fewer column tiles than pairs, the k range of each; partial sums meet in LDS
+//   4  h' = (1 - z) n + z h  -> staging rows (memory is overwritten after the embedding)
 // W_hr and W_hz are folded onto the s_self columns of W_ir / W_iz at init (pack.hip).
 #include <hip/hip_runtime.h>
 
 #include "kernels_common.h"
-#include "lookup.h"
+#include "prepare.h"
 
 namespace tig {
 
@@ -32,22 +37,24 @@ namespace {
 
 constexpr int kGruThreads = 1024;
 constexpr int kGruWaves = kGruThreads / kWave;
+constexpr int kPairs = kGruWaves / 2;  // wavefront pairs: (r, z) | n
+constexpr int EC = 16;                 // winners per tile
 
 struct GruParams {
     int M, T, F, Dmsg;
     int Kg, Khn, Ng;
-    int ldx;     // LDS row stride of the message tile, bytes
-    int off_rz;  // byte offset of the r/z exchange buffer in LDS
-    int cs;      // workgroups per row tile: each takes `tpp` consecutive 16-column tiles of the gates
-    int tpp;
+    int ldx;       // LDS row stride of the message tile, bytes
+    int off_part;  // byte offset of the partial-sum buffer in LDS
+    int n_gru;     // GRU workgroups (the first blocks of the grid)
+    int n_finish;  // wavefronts of the finishing pass
 };
 
-// acc1 += A x W1[nt]^T and acc2 += A x W2[nt]^T over k-blocks [0, kblocks): both weight streams
-// are loaded DEPTH blocks ahead and share the A operand.
-template <int PREC, int MT, int DEPTH>
-__device__ inline void tile_gemm2(floatx4 (&acc1)[MT], floatx4 (&acc2)[MT], const char *A, int lda,
-                                  const void *W1, const void *W2, int w1_kblocks, int w2_kblocks,
-                                  int kblocks, int nt)
+// acc1 += A x W1[nt]^T over W1's k-blocks [kb_lo, kb_hi) and acc2 += A x W2[nt]^T over W2's
+// k-blocks [kb_lo, min(kb_hi, w2_kblocks)): both weight streams are loaded DEPTH blocks ahead and
+// share the A operand.
+template <int PREC, int DEPTH>
+__device__ inline void tile_gemm2(floatx4 &acc1, floatx4 &acc2, const char *A, int lda, const void *W1,
+                                  const void *W2, int w1_kblocks, int w2_kblocks, int kb_lo, int kb_hi, int nt)
 {
     using P = Prec<PREC>;
     using frag = typename P::frag;
@@ -56,41 +63,43 @@ __device__ inline void tile_gemm2(floatx4 (&acc1)[MT], floatx4 (&acc2)[MT], cons
     const size_t w2 = (size_t)nt * w2_kblocks * kWave + lane;
     const char *ap = A + (size_t)(lane & 15) * lda;
     const int g = lane >> 4;
-    for (int kb = 0; kb < kblocks; kb += DEPTH) {
+    const int kb_hi2 = kb_hi < w2_kblocks ? kb_hi : w2_kblocks;
+    for (int kb = kb_lo; kb < kb_hi; kb += DEPTH) {
         frag b1[DEPTH], b2[DEPTH];
 #pragma unroll
-        for (int u = 0; u < DEPTH; ++u)
-            if (kb + u < kblocks) {
+        for (int u = 0; u < DEPTH; ++u) {
+            if (kb + u < kb_hi)
                 b1[u] = P::load_w(W1, w1 + (size_t)(kb + u) * kWave);
+            if (kb + u < kb_hi2)
                 b2[u] = P::load_w(W2, w2 + (size_t)(kb + u) * kWave);
-            }
+        }
 #pragma unroll
         for (int u = 0; u < DEPTH; ++u)
-            if (kb + u < kblocks) {
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    const frag afrag = P::load_a(ap + (size_t)mt * 16 * lda, kb + u, g);
-                    P::mma(acc1[mt], afrag, b1[u]);
-                    P::mma(acc2[mt], afrag, b2[u]);
-                }
+            if (kb + u < kb_hi) {
+                const frag afrag = P::load_a(ap, kb + u, g);
+                P::mma(acc1, afrag, b1[u]);
+                if (kb + u < kb_hi2)
+                    P::mma(acc2, afrag, b2[u]);
             }
     }
 }
 
-template <int PREC, int MT>
+template <int PREC>
 __global__ void __launch_bounds__(kGruThreads)
-k_gru(StepArgs a, PackedWeights w, GruParams g, int n_gru_blocks, int K)
+k_gru(StepArgs a, PackedWeights w, GruParams g, int K)
 {
     TIG_MARK(0);
-    if ((int)blockIdx.x >= n_gru_blocks) {  // lookup workgroup: one query per wavefront
-        const int q = ((int)blockIdx.x - n_gru_blocks) * kGruWaves + wave_id();
-        if (q < a.roles * a.count)
-            nbr_lookup_wave(a, K, q);
+    if ((int)blockIdx.x >= g.n_gru) {  // finishing pass of the query preparation
+        const int x = (int)blockIdx.x - g.n_gru;
+        if (x == 0 && threadIdx.x == 0 && a.n_u_next)
+            *a.n_u_next = 0;  // the query set the next preparation fills; nothing reads it meanwhile
+        const int fw = x * kGruWaves + wave_id();
+        if (fw < g.n_finish)
+            finish_wave(a, K, fw);
         TIG_MARK(1);
         return;
     }
     using P = Prec<PREC>;
-    constexpr int EC = 16 * MT;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int *row_i = (int *)smem;                  // [EC] entry 2b + role
     int *row_u = row_i + EC;                   // [EC] node
@@ -98,154 +107,160 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int n_gru_blocks, int K)
     int *row_e = row_o + EC;                   // [EC] event id - first_eid
     double *row_t = (double *)(row_e + EC);    // [EC] event time
     char *X = smem + EC * 24;                  // [EC rows x ldx bytes]
-    float *rz = (float *)(smem + g.off_rz);    // [EC][Ng][2]
+    float *part = (float *)(smem + g.off_part);  // [2 halves][kPairs][2 streams][16 x 16]
 
     const int lane = lane_id();
     const int wave = wave_id();
 
-    // 1. this block's slice of the compacted winner list (descriptor and count are read in the
-    //    same round trip; slots beyond the count hold stale but in-range descriptors).  The g.cs
-    //    workgroups of a row tile gather the same rows and split the gate columns: each streams
-    //    only its share of the gate weights.
-    const int r0 = ((int)blockIdx.x / g.cs) * EC;
-    const int ct_lo = ((int)blockIdx.x % g.cs) * g.tpp;
-    WinDesc d0;
-    if (threadIdx.x < EC)
-        d0 = a.win[r0 + threadIdx.x];
+    // the work: tiles x column slices, as many slices as keep the GRU workgroups busy
     const int n_win = *a.n_win;
-    if (r0 >= n_win)
+    const int tiles = (n_win + EC - 1) / EC;
+    if (tiles == 0)
         return;
-    const int n_rows = n_win - r0 < EC ? n_win - r0 : EC;
-    if (threadIdx.x < EC) {
-        const int r = threadIdx.x;
-        int i = 0, u = 0, o = 0, b = 0;
-        double t = 0.0;
-        if (r < n_rows) {
-            i = d0.entry;
-            u = d0.node;
-            o = d0.other;
-            b = d0.b;
-            t = d0.t;
-        }
-        row_i[r] = i;
-        row_u[r] = u;
-        row_o[r] = o;
-        row_e[r] = b;
-        row_t[r] = t;
-    }
-    __syncthreads();
-    TIG_MARK(1);
-
-    // 2. message rows from batch-start memory; rows beyond n_rows are zero.  One wavefront per
-    //    row, lanes along the row (no index arithmetic per element); all loads of a row are
-    //    requested before its first element is converted and stored.
-    for (int r = wave; r < EC; r += kGruWaves) {
-        const bool live = r < n_rows;
-        const int u = row_u[r], o = row_o[r];
-        const float *self = a.mem + (size_t)u * g.M;
-        const float *other = a.mem + (size_t)o * g.M;
-        const float *feat = a.edge_feat + (size_t)(a.msg_first_eid + row_e[r]) * g.F;
-        const double lu = live ? a.lu[u] : 0.0;
-        constexpr int kAhead = 8;  // 512 elements of a message row per pass
-        for (int base = 0; base < g.Kg; base += kWave * kAhead) {
-            float v[kAhead];
-            double tw[kAhead], tb[kAhead];
-#pragma unroll
-            for (int k = 0; k < kAhead; ++k) {
-                const int j = base + lane + kWave * k;
-                v[k] = 0.0f;
-                tw[k] = tb[k] = 0.0;
-                if (live && j < g.Dmsg) {
-                    if (j < g.M)
-                        v[k] = self[j];
-                    else if (j < 2 * g.M)
-                        v[k] = other[j - g.M];
-                    else if (j < 2 * g.M + g.T) {
-                        tw[k] = w.time_w_rev[j - 2 * g.M];
-                        tb[k] = w.time_b_rev[j - 2 * g.M];
-                    } else
-                        v[k] = feat[j - 2 * g.M - g.T];
-                }
-            }
-            const double dt = row_t[r] - lu;  // since the node's last update
-#pragma unroll
-            for (int k = 0; k < kAhead; ++k) {
-                const int j = base + lane + kWave * k;
-                if (j < g.Kg) {
-                    float x = v[k];
-                    if (live && j >= 2 * g.M && j < 2 * g.M + g.T)
-                        x = time_enc(tw[k], tb[k], dt);
-                    P::store_a(X + (size_t)r * g.ldx, j, x);
-                }
-            }
-        }
-    }
-    __syncthreads();
-    TIG_MARK(2);
-
-    // 3. + 4. gates
+    const int n_ct = g.Ng / 16;
+    int cs = g.n_gru / tiles;
+    cs = cs < 1 ? 1 : (cs > n_ct ? n_ct : cs);
+    const int tpp = (n_ct + cs - 1) / cs;  // column tiles per item
+    cs = (n_ct + tpp - 1) / tpp;
+    const int items = tiles * cs;
     const int kblocks = g.Kg / P::KB;
     const int kblocks_hn = g.Khn / P::KB;
-    const int n_ct = g.Ng / 16 < ct_lo + g.tpp ? g.Ng / 16 : ct_lo + g.tpp;  // end of this block's tiles
-    constexpr int kPairs = kGruWaves / 2;  // column tiles per round
-    for (int base = ct_lo; base < n_ct; base += kPairs) {
-        const int ct = base + (wave % kPairs);
-        const int half = wave / kPairs;  // 0: r and z gates, 1: n gate
-        const bool on = ct < n_ct;
-        floatx4 acc1[MT], acc2[MT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            acc1[mt] = floatx4{0, 0, 0, 0};
-            acc2[mt] = floatx4{0, 0, 0, 0};
+
+    for (int item = (int)blockIdx.x; item < items; item += g.n_gru) {
+        // 1. this item's slice of the compacted winner list
+        const int r0 = (item / cs) * EC;
+        const int ct_lo = (item % cs) * tpp;
+        const int ct_hi = n_ct < ct_lo + tpp ? n_ct : ct_lo + tpp;
+        const int n_rows = n_win - r0 < EC ? n_win - r0 : EC;
+        if (threadIdx.x < EC) {
+            const int r = threadIdx.x;
+            int i = 0, u = 0, o = 0, b = 0;
+            double t = 0.0;
+            if (r < n_rows) {
+                const WinDesc d0 = a.win[r0 + r];
+                i = d0.entry;
+                u = d0.node;
+                o = d0.other;
+                b = d0.b;
+                t = d0.t;
+            }
+            row_i[r] = i;
+            row_u[r] = u;
+            row_o[r] = o;
+            row_e[r] = b;
+            row_t[r] = t;
         }
-        const int col = ct * 16 + (lane & 15);
-        if (on) {
-            if (half == 0) {
-                tile_gemm2<PREC, MT, 5>(acc1, acc2, X, g.ldx, w.gru_Wr, w.gru_Wz, kblocks, kblocks, kblocks, ct);
-                const float br = w.gru_br[col], bz = w.gru_bz[col];
+        __syncthreads();
+        TIG_MARK(1);
+
+        // 2. message rows from batch-start memory; rows beyond n_rows are zero.  One wavefront per
+        //    row, lanes along the row (no index arithmetic per element); all loads of a row are
+        //    requested before its first element is converted and stored.
+        for (int r = wave; r < EC; r += kGruWaves) {
+            const bool live = r < n_rows;
+            const int u = row_u[r], o = row_o[r];
+            const float *self = a.mem + (size_t)u * g.M;
+            const float *other = a.mem + (size_t)o * g.M;
+            const float *feat = a.edge_feat + (size_t)(a.msg_first_eid + row_e[r]) * g.F;
+            const double lu = live ? a.lu[u] : 0.0;
+            constexpr int kAhead = 8;  // 512 elements of a message row per pass
+            for (int base = 0; base < g.Kg; base += kWave * kAhead) {
+                float v[kAhead];
+                double tw[kAhead], tb[kAhead];
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int row = mt * 16 + 4 * (lane >> 4) + v;
-                        float *o2 = rz + ((size_t)row * g.Ng + col) * 2;
-                        o2[0] = 1.0f / (1.0f + __expf(-(acc1[mt][v] + br)));
-                        o2[1] = 1.0f / (1.0f + __expf(-(acc2[mt][v] + bz)));
+                for (int k = 0; k < kAhead; ++k) {
+                    const int j = base + lane + kWave * k;
+                    v[k] = 0.0f;
+                    tw[k] = tb[k] = 0.0;
+                    if (live && j < g.Dmsg) {
+                        if (j < g.M)
+                            v[k] = self[j];
+                        else if (j < 2 * g.M)
+                            v[k] = other[j - g.M];
+                        else if (j < 2 * g.M + g.T) {
+                            tw[k] = w.time_w_rev[j - 2 * g.M];
+                            tb[k] = w.time_b_rev[j - 2 * g.M];
+                        } else
+                            v[k] = feat[j - 2 * g.M - g.T];
                     }
-            } else {
-                // input part over the whole message, hidden part over s_self (the first Khn k's)
-                tile_gemm2<PREC, MT, 5>(acc1, acc2, X, g.ldx, w.gru_Win, w.gru_Whn, kblocks, kblocks_hn,
-                                        kblocks_hn, ct);
-                tile_gemm<PREC, MT, 6>(acc1, X, g.ldx, kblocks_hn, w.gru_Win, kblocks, kblocks_hn,
-                                       kblocks - kblocks_hn, ct);
+                }
+                const double dt = row_t[r] - lu;  // since the node's last update
+#pragma unroll
+                for (int k = 0; k < kAhead; ++k) {
+                    const int j = base + lane + kWave * k;
+                    if (j < g.Kg) {
+                        float x = v[k];
+                        if (live && j >= 2 * g.M && j < 2 * g.M + g.T)
+                            x = time_enc(tw[k], tb[k], dt);
+                        P::store_a(X + (size_t)r * g.ldx, j, x);
+                    }
+                }
             }
         }
         __syncthreads();
-        TIG_MARK(3);
-        if (on && half == 1 && col < g.M) {
-            const float bin = w.gru_bin[col], bhn = w.gru_bhn[col];
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+        TIG_MARK(2);
+
+        // 3. + 4. gates.  A round covers up to kPairs column tiles; with fewer, the pairs also split k.
+        for (int base = ct_lo; base < ct_hi; base += kPairs) {
+            const int cts = ct_hi - base < kPairs ? ct_hi - base : kPairs;  // column tiles of this round
+            const int ksplit = cts == 1 ? 8 : (cts == 2 ? 4 : (cts <= 4 ? 2 : 1));
+            const int pair = wave % kPairs;
+            const int half = wave / kPairs;  // 0: r and z gates, 1: n gate
+            const int ctl = pair / ksplit;   // column tile of the round
+            const int ks = pair % ksplit;    // k slice
+            const bool on = ctl < cts;
+            floatx4 acc1 = floatx4{0, 0, 0, 0}, acc2 = floatx4{0, 0, 0, 0};
+            if (on) {
+                const int ct = base + ctl;
+                const int per = (kblocks + ksplit - 1) / ksplit;
+                const int kb_lo = ks * per;
+                const int kb_hi = kblocks < kb_lo + per ? kblocks : kb_lo + per;
+                if (half == 0)
+                    tile_gemm2<PREC, 5>(acc1, acc2, X, g.ldx, w.gru_Wr, w.gru_Wz, kblocks, kblocks, kb_lo, kb_hi, ct);
+                else  // input part over the whole message, hidden part over s_self (the first Khn k's)
+                    tile_gemm2<PREC, 5>(acc1, acc2, X, g.ldx, w.gru_Win, w.gru_Whn, kblocks, kblocks_hn, kb_lo,
+                                        kb_hi, ct);
+            }
+            {
+                float *p1 = part + (size_t)((half * kPairs + pair) * 2) * 256;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int row = mt * 16 + 4 * (lane >> 4) + v;
-                    if (row < n_rows) {
-                        const float *i2 = rz + ((size_t)row * g.Ng + col) * 2;
-                        const float r = i2[0], z = i2[1];
-                        const float h = P::load_elem(X + (size_t)row * g.ldx, col);  // s_self
-                        const float x = acc1[mt][v] + bin + r * (acc2[mt][v] + bhn);
-                        const float e2 = __expf(2.0f * x);          // tanh(x) = 1 - 2 / (e^{2x} + 1)
-                        const float n = 1.0f - 2.0f / (e2 + 1.0f);
-                        a.staging[(size_t)row_i[row] * g.M + col] = (1.0f - z) * n + z * h;
-                    }
+                    const int e = (4 * (lane >> 4) + v) * 16 + (lane & 15);
+                    p1[e] = acc1[v];
+                    p1[256 + e] = acc2[v];
                 }
+            }
+            __syncthreads();
+            TIG_MARK(3);
+            for (int idx = threadIdx.x; idx < cts * 256; idx += kGruThreads) {
+                const int ctl2 = idx >> 8, e = idx & 255;
+                const int row = e >> 4, col = (base + ctl2) * 16 + (e & 15);
+                if (row < n_rows && col < g.M) {
+                    float sr = 0.0f, sz = 0.0f, sin_ = 0.0f, shn = 0.0f;
+                    for (int k2 = 0; k2 < ksplit; ++k2) {
+                        const float *q0 = part + (size_t)((ctl2 * ksplit + k2) * 2) * 256;
+                        const float *q1 = part + (size_t)((kPairs + ctl2 * ksplit + k2) * 2) * 256;
+                        sr += q0[e];
+                        sz += q0[256 + e];
+                        sin_ += q1[e];
+                        shn += q1[256 + e];
+                    }
+                    const float r = 1.0f / (1.0f + __expf(-(sr + w.gru_br[col])));
+                    const float z = 1.0f / (1.0f + __expf(-(sz + w.gru_bz[col])));
+                    const float h = P::load_elem(X + (size_t)row * g.ldx, col);  // s_self
+                    const float x = sin_ + w.gru_bin[col] + r * (shn + w.gru_bhn[col]);
+                    const float e2 = __expf(2.0f * x);          // tanh(x) = 1 - 2 / (e^{2x} + 1)
+                    const float n = 1.0f - 2.0f / (e2 + 1.0f);
+                    a.staging[(size_t)row_i[row] * g.M + col] = (1.0f - z) * n + z * h;
+                }
+            }
+            __syncthreads();  // the partial sums (and, after the last round, the tile) are reused
         }
-        __syncthreads();  // rz is reused by the next round
     }
     TIG_MARK(4);
 }
 
-GruParams gru_params(const Dims &d, int mt)
+GruParams gru_params(const Dims &d)
 {
     GruParams g;
     g.M = d.M;
@@ -256,40 +271,27 @@ GruParams gru_params(const Dims &d, int mt)
     g.Khn = d.Khn;
     g.Ng = d.Ng;
     g.ldx = lds_row_bytes(d.Kg);
-    g.off_rz = (16 * mt * 24 + 16 * mt * g.ldx + 15) / 16 * 16;
-    g.cs = 1;
-    g.tpp = d.Ng / 16;
+    g.off_part = (EC * 24 + EC * g.ldx + 15) / 16 * 16;
+    g.n_gru = 0;
+    g.n_finish = 0;
     return g;
 }
 
-template <int PREC>
-const void *pick_mt(int mt)
+const void *gru_kernel(const Dims &d)
 {
-    return mt == 1 ? (const void *)k_gru<PREC, 1> : (const void *)k_gru<PREC, 2>;
-}
-
-const void *gru_kernel(const Dims &d, int mt)
-{
-    return d.prec == TIG_BF16_MFMA ? pick_mt<TIG_BF16_MFMA>(mt) : pick_mt<TIG_FP32>(mt);
+    return d.prec == TIG_BF16_MFMA ? (const void *)k_gru<TIG_BF16_MFMA> : (const void *)k_gru<TIG_FP32>;
 }
 
 }  // namespace
 
-int gru_lds_bytes(const Dims &d, int mt)
+int gru_lds_bytes(const Dims &d)
 {
-    const GruParams g = gru_params(d, mt);
-    return g.off_rz + 16 * mt * d.Ng * 2 * 4;
+    return gru_params(d).off_part + 2 * kPairs * 2 * 256 * 4;
 }
 
 hipError_t prepare_gru(const Dims &d, const LaunchPlan &plan)
 {
-    for (int mt = 1; mt <= plan.gru_mt; ++mt) {
-        const hipError_t e = hipFuncSetAttribute(gru_kernel(d, mt), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                 gru_lds_bytes(d, mt));
-        if (e != hipSuccess)
-            return e;
-    }
-    return hipSuccess;
+    return hipFuncSetAttribute(gru_kernel(d), hipFuncAttributeMaxDynamicSharedMemorySize, gru_lds_bytes(d));
 }
 
 hipError_t launch_gru(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
@@ -297,26 +299,18 @@ hipError_t launch_gru(const Dims &d, const LaunchPlan &plan, const PackedWeights
 {
     StepArgs aa = a;
     PackedWeights ww = pw;
-    const int entries = 2 * a.msg_count;  // 0 in a deferred step with nothing to apply: lookup only
-    // Column split.  Every workgroup streams the gate weights of its columns from L2, which bounds
-    // its run time, so when the 16-row tiles do not fill the device the columns of a tile are
-    // split over as many workgroups as it takes at once.  Only the tiles below the winner count
-    // do any work.  (32-row tiles with halved columns measured slower at large batches.)
+    GruParams g = gru_params(d);
+    // GRU workgroups: one per compute unit, but no more than the work of the largest possible
+    // winner count (every entry a winner, every column tile its own item); none if nothing is applied
     const int cus = plan.num_cus > 0 ? plan.num_cus : 256;
-    const int mt = 1;
-    GruParams g = gru_params(d, mt);
-    const int tiles = (entries + 16 * mt - 1) / (16 * mt);
-    const int n_ct = d.Ng / 16;
-    int cs = tiles > 0 ? 2 * cus / tiles : 1;
-    cs = cs < 1 ? 1 : (cs > n_ct ? n_ct : cs);
-    g.tpp = (n_ct + cs - 1) / cs;
-    g.cs = (n_ct + g.tpp - 1) / g.tpp;
-    int n_gru_blocks = tiles * g.cs;
+    const int max_items = (2 * a.msg_count + EC - 1) / EC * (d.Ng / 16);
+    g.n_gru = max_items < cus ? max_items : cus;
+    g.n_finish = a.roles * a.count;
     int K = d.K;
-    const int n_lookup_blocks = (a.roles * a.count + kGruWaves - 1) / kGruWaves;
-    void *args[] = {&aa, &ww, &g, &n_gru_blocks, &K};
-    return hipLaunchKernel(gru_kernel(d, mt), dim3(n_gru_blocks + n_lookup_blocks), dim3(kGruThreads), args,
-                           (size_t)gru_lds_bytes(d, mt), s);
+    const int n_finish_blocks = (g.n_finish + kGruWaves - 1) / kGruWaves;
+    void *args[] = {&aa, &ww, &g, &K};
+    return hipLaunchKernel(gru_kernel(d), dim3(g.n_gru + n_finish_blocks), dim3(kGruThreads), args,
+                           (size_t)gru_lds_bytes(d), s);
 }
 
 }  // namespace tig

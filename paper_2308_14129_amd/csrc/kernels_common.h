@@ -370,6 +370,40 @@ __device__ inline void tile_gemm_two(floatx4 (&acc1)[MT], floatx4 (&acc2)[MT], c
     }
 }
 
+// The same for one output tile of each of two weight matrices with equal k depth (both over all
+// k-blocks of A from 0).
+template <int PREC, int MT, int DEPTH>
+__device__ inline void tile_gemm_pair(floatx4 (&acc1)[MT], floatx4 (&acc2)[MT], const char *A, int lda,
+                                      const void *W1, const void *W2, int kblocks, int nt1, int nt2)
+{
+    using P = Prec<PREC>;
+    using frag = typename P::frag;
+    const int lane = lane_id();
+    const size_t w1 = (size_t)nt1 * kblocks * kWave + lane;
+    const size_t w2 = (size_t)nt2 * kblocks * kWave + lane;
+    const char *ap = A + (size_t)(lane & 15) * lda;
+    const int g = lane >> 4;
+    for (int kb = 0; kb < kblocks; kb += DEPTH) {
+        frag b1[DEPTH], b2[DEPTH];
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u)
+            if (kb + u < kblocks) {
+                b1[u] = P::load_w(W1, w1 + (size_t)(kb + u) * kWave);
+                b2[u] = P::load_w(W2, w2 + (size_t)(kb + u) * kWave);
+            }
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u)
+            if (kb + u < kblocks) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const frag afrag = P::load_a(ap + (size_t)mt * 16 * lda, kb + u, g);
+                    P::mma(acc1[mt], afrag, b1[u]);
+                    P::mma(acc2[mt], afrag, b2[u]);
+                }
+            }
+    }
+}
+
 // Row stride in bytes >= 4*width whose 16-byte chunk count is odd: the 16 rows read by one
 // operand load then fall into distinct LDS bank groups.
 __host__ __device__ inline int lds_row_bytes(int width_elems)

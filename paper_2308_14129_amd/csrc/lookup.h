@@ -15,24 +15,25 @@
 
 namespace tig {
 
-__device__ inline void nbr_lookup_wave(const StepArgs &a, int K, int q)
+// One wavefront: the query (u, t) becomes row `row` of the query set (node, time, neighbour
+// slots, count; the row references are filled in later).  own_pos: adjacency position of the
+// query's own event in u's list (everything from there on has time >= t), or -1 if unknown.
+// my_nbr: the neighbour id this lane wrote (lanes below K), -1 for an unused slot.
+__device__ inline void nbr_lookup_wave(const StepArgs &a, int K, int32_t u, double t, int64_t own_pos,
+                                       const QuerySet &qs, int row, int32_t &my_nbr)
 {
+    my_nbr = -1;
     const int lane = lane_id();
-    const int role = q / a.count;
-    const int b = q - role * a.count;
-    const int64_t eid = a.first_eid + b;
-    const int32_t u = role == 0 ? a.src[eid] : (role == 1 ? a.dst[eid] : a.neg[b]);
-    const double t = a.ts[eid];
     int64_t lo = 0, hi = 0;
-    if (u >= 0 && (int64_t)u < a.num_nodes) {
+    const bool known = u >= 0 && (int64_t)u < a.num_nodes;
+    if (known) {
         lo = a.indptr[u];
         hi = a.indptr[u + 1];
     }
     const int64_t base = lo;
     // invariant: entries below lo have time < t; entries at or above hi have time >= t
-    if (role < 2) {
-        // the query's own event sits at pos; everything from there on has time >= t
-        hi = a.pos[2 * eid + role];
+    if (own_pos >= 0) {
+        hi = own_pos;
         if (hi - lo > kWave) {
             const int64_t idx = hi - 1 - lane;  // the 64 entries just below
             const bool less = a.csr[idx].ts < t;
@@ -73,20 +74,24 @@ __device__ inline void nbr_lookup_wave(const StepArgs &a, int K, int q)
     const int64_t avail = lo - base;
     if (lane < K) {
         const int64_t p = lo - 1 - lane;
-        const size_t o = (size_t)q * K + lane;
+        const size_t o = (size_t)row * K + lane;
         if (p >= base) {
             const CsrEntry e = a.csr[p];
-            a.nbr_node[o] = e.nbr;
-            a.nbr_eid[o] = e.eid;
-            a.nbr_ts[o] = e.ts;
+            my_nbr = e.nbr;
+            qs.nbr[o] = e.nbr;
+            qs.eid[o] = e.eid;
+            qs.ts[o] = e.ts;
         } else {
-            a.nbr_node[o] = -1;
-            a.nbr_eid[o] = -1;
-            a.nbr_ts[o] = 0.0;
+            qs.nbr[o] = -1;
+            qs.eid[o] = -1;
+            qs.ts[o] = 0.0;
         }
     }
-    if (lane == 0)
-        a.nbr_cnt[q] = (int32_t)(avail < K ? avail : K);
+    if (lane == 0) {
+        qs.cnt[row] = (int32_t)(avail < K ? avail : K);
+        qs.node[row] = known ? u : -1;
+        qs.t[row] = t;
+    }
 }
 
 }  // namespace tig

@@ -1,0 +1,183 @@
+// Query preparation of one batch (device side).  The embedding of a query depends on (node, t)
+// only (embedding module f of the paper's Sec. II-C: the node's state and its history before t),
+// and the sources and destinations of a batch repeat the same pairs many times over: hub nodes
+// take part in a large share of the events, and events that share a timestamp put the same hub
+// at the same time.  So every distinct (node, t) is embedded ONCE:
+//   dedup_block   merges equal pairs among the 2B source / destination entries of a batch through
+//                 a hash table of claims and looks up the K most recent neighbours of every
+//                 distinct pair.  It reads the event stream and the adjacency only, never the
+//                 model state, so it can run a step early, beside the previous embedding launch.
+//   finish_wave   what needs this step's inputs: the negatives' lookups (their ids arrive with the
+//                 call) and the row references (which rows this step's GRU replaces).
+// gfx950 only.
+#pragma once
+
+#include "kernels_common.h"
+#include "lookup.h"
+
+namespace tig {
+
+constexpr int kPrepThreads = 1024;
+constexpr int kPrepWaves = kPrepThreads / kWave;
+constexpr int kPrepLds = kPrepThreads * 4 + (kPrepWaves + 2) * 4;  // representative list + counters
+
+__device__ inline uint32_t query_hash(int32_t u, double t)
+{
+    const unsigned long long b = (unsigned long long)__double_as_longlong(t);
+    uint32_t h = (uint32_t)u * 0x9E3779B1u ^ (uint32_t)b * 0x85EBCA77u ^ (uint32_t)(b >> 32) * 0xC2B2AE3Du;
+    h ^= h >> 15;
+    h *= 0x2C1B3C6Du;
+    h ^= h >> 13;
+    return h;
+}
+
+__device__ inline void entry_query(const StepArgs &a, int64_t first_eid, int i, int32_t &u, double &t)
+{
+    const int64_t eid = first_eid + (i >> 1);
+    u = (i & 1) ? a.dst[eid] : a.src[eid];
+    t = a.ts[eid];
+}
+
+// The entry that represents query (u, t) of entry i: the first entry to claim the pair's slot in
+// the table (open addressing; a slot holds (epoch << 32 | entry), other epochs count as empty).
+// A slot changes once per job, from empty to claimed, and the compare-and-swap decides who
+// claimed it, so a stale read of "empty" only costs the failed swap.  The probe count is bounded
+// by the table size; if that bound were ever hit the entry simply represents itself.
+__device__ inline int claim_query(const StepArgs &a, const DedupJob &j, int i, int32_t u, double t)
+{
+    const int entries = 2 * j.count;
+    const unsigned long long mine = ((unsigned long long)j.epoch << 32) | (uint32_t)i;
+    uint32_t h = query_hash(u, t) & j.tab_mask;
+    for (uint32_t probes = 0; probes <= j.tab_mask; ++probes) {
+        unsigned long long cur = __hip_atomic_load(&j.tab[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((uint32_t)(cur >> 32) != j.epoch) {
+            const unsigned long long old = atomicCAS(&j.tab[h], cur, mine);
+            if (old == cur)
+                return i;
+            cur = old;
+            if ((uint32_t)(cur >> 32) != j.epoch)
+                continue;  // (not reachable: only this job's claims replace an empty slot)
+        }
+        const uint32_t other = (uint32_t)cur;
+        if ((int)other < entries) {
+            int32_t uo;
+            double to;
+            entry_query(a, j.first_eid, (int)other, uo, to);
+            if (uo == u && to == t)
+                return (int)other;
+        }
+        h = (h + 1) & j.tab_mask;
+    }
+    return i;
+}
+
+// Workgroup `wg` of j.n_wgs: its share of the entries is claimed one entry per thread; the
+// representatives among them are compacted, take consecutive rows of the query set (one atomic
+// per workgroup), and the wavefronts look up their neighbours.  smem: kPrepLds bytes.
+// ceil(2 * count / n_wgs) must not exceed kPrepThreads.
+__device__ inline void dedup_block(const StepArgs &a, const DedupJob &j, int K, int wg, char *smem)
+{
+    int *list = (int *)smem;            // [kPrepThreads] thread index of the n-th representative
+    int *s_cnt = list + kPrepThreads;   // [waves] representatives per wavefront, then their prefix
+    int *s_base = s_cnt + kPrepWaves;   // [1] first row of this workgroup, [1] its representatives
+    const int lane = lane_id();
+    const int wave = wave_id();
+    const int entries = 2 * j.count;
+    const int chunk = (entries + j.n_wgs - 1) / j.n_wgs;
+    const int i0 = wg * chunk;
+    const int i = i0 + (int)threadIdx.x;
+    const bool active = (int)threadIdx.x < chunk && i < entries;
+    bool is_rep = false;
+    if (active) {
+        int32_t u;
+        double t;
+        entry_query(a, j.first_eid, i, u, t);
+        const int rep = claim_query(a, j, i, u, t);
+        is_rep = rep == i;
+        if (!is_rep)
+            j.qs.slot[i] = -rep - 1;
+    }
+    const unsigned long long m = __ballot(is_rep);
+    const int rank = __popcll(m & ((1ull << lane) - 1ull));
+    if (lane == 0)
+        s_cnt[wave] = __popcll(m);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int w = 0; w < kPrepWaves; ++w) {
+            const int c = s_cnt[w];
+            s_cnt[w] = run;
+            run += c;
+        }
+        s_base[0] = run > 0 ? atomicAdd(j.qs.n_u, run) : 0;
+        s_base[1] = run;
+    }
+    __syncthreads();
+    if (is_rep)
+        list[s_cnt[wave] + rank] = (int)threadIdx.x;
+    __syncthreads();
+    const int base = s_base[0], n_rep = s_base[1];
+    for (int l = wave; l < n_rep; l += kPrepWaves) {
+        const int e = i0 + list[l];
+        int32_t u;
+        double t;
+        entry_query(a, j.first_eid, e, u, t);
+        const int64_t eid = j.first_eid + (e >> 1);
+        int32_t my_nbr;
+        nbr_lookup_wave(a, K, u, t, (int64_t)a.pos[2 * eid + (e & 1)], j.qs, base + l, my_nbr);
+        if (lane == 0)
+            j.qs.slot[e] = base + l;
+    }
+}
+
+// Where the current state row of node v lives during this step: the staged GRU output of the
+// entry that won v's message in the applied batch, or v's memory row.  msg_key[v] holds the key of
+// v's latest winning entry in the selections that used this key array; it belongs to the applied
+// batch iff its event id lies in that batch.
+__device__ inline int32_t resolve_ref(const StepArgs &a, int32_t v)
+{
+    if (v < 0 || (int64_t)v >= a.num_nodes)
+        return kRefNone;
+    if (a.msg_count > 0) {
+        const unsigned long long k = a.msg_key[v];
+        const uint32_t low = (uint32_t)k;
+        const int64_t e = (int64_t)(low >> 1);
+        if (k != 0ull && e >= a.msg_first_eid && e < a.msg_first_eid + a.msg_count)
+            return ~(int32_t)(2 * (e - a.msg_first_eid) + (low & 1u));
+    }
+    return v;
+}
+
+// Wavefront w of the finishing pass (3B of them with negatives, else 2B):
+//   w < 2B       row w of the source / destination queries, if there is one: row references
+//   w = 2B + b   the negative of event b: lookup into row n_u + b, then its row references
+__device__ inline void finish_wave(const StepArgs &a, int K, int w)
+{
+    const int lane = lane_id();
+    const int n_u = *a.qs.n_u;
+    int row;
+    int32_t my_nbr = -1;
+    if (w < 2 * a.count) {
+        row = w;
+        if (row >= n_u)
+            return;
+        if (lane < K)
+            my_nbr = a.qs.nbr[(size_t)row * K + lane];
+    } else {
+        const int b = w - 2 * a.count;
+        if (a.roles < 3 || b >= a.count)
+            return;
+        row = n_u + b;
+        nbr_lookup_wave(a, K, a.neg[b], a.ts[a.first_eid + b], -1, a.qs, row, my_nbr);
+    }
+    if (lane < K)
+        a.qs.ref[(size_t)row * K + lane] = resolve_ref(a, my_nbr);
+    if (lane == kWave - 1) {
+        // (for a negative the node id was validated by the lookup; re-derive it instead of reading
+        // back what another lane of this wavefront has just written)
+        const int32_t u = w < 2 * a.count ? a.qs.node[row] : a.neg[w - 2 * a.count];
+        a.qs.self_ref[row] = resolve_ref(a, u);
+    }
+}
+
+}  // namespace tig

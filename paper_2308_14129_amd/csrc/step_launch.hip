@@ -9,12 +9,8 @@ bool plan_launch(const Dims &d, int lds_limit, LaunchPlan *plan)
 {
     if (d.dkvp > 512)
         return false;
-    plan->gru_mt = 0;
-    for (int mt = 1; mt >= 1; --mt)
-        if (gru_lds_bytes(d, mt) <= lds_limit) {
-            plan->gru_mt = mt;
-            break;
-        }
+    if (gru_lds_bytes(d) > lds_limit)
+        return false;
     plan->emb_mt = 0;
     plan->num_cus = 0;
     for (int mt = 3; mt >= 1; --mt)
@@ -22,10 +18,9 @@ bool plan_launch(const Dims &d, int lds_limit, LaunchPlan *plan)
             plan->emb_mt = mt;
             break;
         }
-    if (!plan->gru_mt || !plan->emb_mt)
+    if (!plan->emb_mt)
         return false;
-    plan->gru_entries = 16 * plan->gru_mt;
-    plan->gru_lds = gru_lds_bytes(d, plan->gru_mt);
+    plan->gru_lds = gru_lds_bytes(d);
     plan->emb_lds = embed_lds_bytes(d, plan->emb_mt);
     return true;
 }
@@ -39,7 +34,7 @@ hipError_t prepare_kernels(const Dims &d, const LaunchPlan &plan)
 }
 
 hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw,
-                       const StepArgs &a, const StepArgs *sel, hipStream_t s, hipEvent_t *marks)
+                       const StepArgs &a, const StepPlan &sp, hipStream_t s, hipEvent_t *marks)
 {
     hipError_t e;
     int mark = 0;
@@ -47,20 +42,38 @@ hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeight
 
     if ((e = stamp()) != hipSuccess)
         return e;
-    bool needs_select = false;
-    if (sel && (e = launch_scatter(*sel, s, &needs_select)) != hipSuccess)
+    if (sp.big_sel && (e = launch_scatter(a, *sp.big_sel, s)) != hipSuccess)
         return e;
     if ((e = stamp()) != hipSuccess)
         return e;
-    if (needs_select && (e = launch_select(*sel, s)) != hipSuccess)
+    if (sp.big_sel && (e = launch_select(a, *sp.big_sel, s)) != hipSuccess)
         return e;
+    if ((e = stamp()) != hipSuccess)
+        return e;
+    if (sp.prep_sel || sp.prep_ded) {
+        if (sp.prep_ded) {
+            // a preparation of its own starts from an empty query set (and, if the table may hold
+            // claims of an unknown epoch, from an empty table)
+            if (sp.clear_tab)
+                e = launch_fill_zero(sp.prep_ded->tab, ((size_t)sp.prep_ded->tab_mask + 1) * 8, s);
+            if (e == hipSuccess)
+                e = launch_fill_zero(sp.prep_ded->qs.n_u, 4, s);
+            if (e != hipSuccess)
+                return e;
+        }
+        const SelectJob no_sel = {};
+        const DedupJob no_ded = {};
+        if ((e = launch_prepare(a, sp.prep_sel ? *sp.prep_sel : no_sel, sp.prep_ded ? *sp.prep_ded : no_ded, d.K,
+                                s)) != hipSuccess)
+            return e;
+    }
     if ((e = stamp()) != hipSuccess)
         return e;
     if ((e = launch_gru(d, plan, pw, a, s)) != hipSuccess || (e = stamp()) != hipSuccess)
         return e;
-    if ((e = launch_commit(a, d.M, s)) != hipSuccess || (e = stamp()) != hipSuccess)
-        return e;
     if ((e = launch_embed(d, plan, pw, a, s)) != hipSuccess || (e = stamp()) != hipSuccess)
+        return e;
+    if ((e = launch_decode(d, pw, a, s)) != hipSuccess || (e = stamp()) != hipSuccess)
         return e;
     return hipSuccess;
 }

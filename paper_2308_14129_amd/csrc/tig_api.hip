@@ -32,6 +32,18 @@ static hipError_t static_scratch_of(int dev, void **out)
     return hipSuccess;
 }
 
+// Per-step intermediates, carved from the scratch workspace (or from the static array).
+struct StepScratch {
+    QuerySet qs[2];        // distinct queries: the set a step uses, and the one prepared meanwhile
+    float *staging, *emb_u, *dec_a, *dec_b;
+    WinDesc *win[2];       // winner lists: the one a step applies, and the one selected meanwhile
+    int32_t *n_win[2];
+    uint8_t *flags[2];     // per-entry winner flags of each list's batch
+    unsigned long long *tab;  // claim table of the query preparation
+    uint32_t tab_slots;       // power of two
+    size_t bytes;
+};
+
 struct tig_ctx {
     Dims d;
     LaunchPlan plan;
@@ -44,28 +56,28 @@ struct tig_ctx {
     float *edge_feat;
     int64_t *indptr;
     CsrEntry *csr;
+    int32_t *pos;
     float *mem;
     double *lu;
-    unsigned long long *key;
+    unsigned long long *key[2];  // one key array per winner list
     void *packed;
-    // scratch (per step)
-    int32_t *nbr_node, *nbr_eid, *nbr_cnt;
-    double *nbr_ts;
-    float *staging;
-    WinDesc *win[2];   // winner lists: this step's, and the one selected ahead for the next
-    int32_t *n_win[2];
-    int cur;           // list used by the last step
-    bool ahead_valid;  // win[cur ^ 1] holds the winners of batch (ahead_first, ahead_count)
-    int64_t ahead_first;
-    int32_t ahead_count;
-    int num_cus;
-    int64_t cursor;    // end of the last batch stepped since the last reset / import
-    int last_launches; // kernels enqueued by the last tig_step
-    // deferred order: win[cur] holds the winners of batch (pend_first, pend_count), not yet applied
+    StepScratch S;     // in the scratch workspace
+    int wcur;          // update-first: winner list the last step applied; deferred: list with the pending winners
+    int qcur;          // query set the last step used
+    bool ahead_w_valid;  // update-first: list wcur ^ 1 holds the winners of batch (ahead_w_first, ahead_w_count)
+    int64_t ahead_w_first;
+    int32_t ahead_w_count;
+    bool ahead_q_valid;  // set qcur ^ 1 holds the queries of batch (ahead_q_first, ahead_q_count)
+    int64_t ahead_q_first;
+    int32_t ahead_q_count;
+    // deferred order: list wcur holds the winners of batch (pend_first, pend_count), not yet applied
     bool pend_valid;
     int64_t pend_first;
     int32_t pend_count;
-    int32_t *pos;
+    uint32_t epoch;    // of the last query preparation on S.tab
+    int num_cus;
+    int64_t cursor;    // end of the last batch stepped since the last reset / import
+    int last_launches; // kernels enqueued by the last tig_step
     void *static_scratch;  // this device's copy of g_static_scratch
     hipEvent_t marks[kNumStepKernels + 1];
     bool have_marks;
@@ -151,7 +163,7 @@ struct PersistentLayout {
     int32_t *pos;
     float *mem;
     double *lu;
-    unsigned long long *key;
+    unsigned long long *key[2];
     void *packed;
     size_t bytes;
 };
@@ -169,35 +181,45 @@ PersistentLayout persistent_layout(const Dims &d, int64_t N, int64_t E, void *ba
     L.pos = c.take<int32_t>((size_t)2 * E);
     L.mem = c.take<float>((size_t)N * d.M);
     L.lu = c.take<double>((size_t)N);
-    L.key = c.take<unsigned long long>((size_t)N);
+    L.key[0] = c.take<unsigned long long>((size_t)N);
+    L.key[1] = c.take<unsigned long long>((size_t)N);
     L.packed = c.take<char>(packed_weights_bytes(d));
     L.bytes = c.off;
     return L;
 }
 
-struct StepScratch {
-    int32_t *nbr_node, *nbr_eid, *nbr_cnt;
-    double *nbr_ts;
-    float *staging;
-    WinDesc *win[2];
-    int32_t *n_win[2];
-    size_t bytes;
-};
-
 StepScratch step_scratch(const Dims &d, void *base)
 {
     Carver c(base);
     StepScratch S;
-    const size_t Q = (size_t)3 * d.max_batch;
-    S.nbr_node = c.take<int32_t>(Q * d.K);
-    S.nbr_eid = c.take<int32_t>(Q * d.K);
-    S.nbr_ts = c.take<double>(Q * d.K);
-    S.nbr_cnt = c.take<int32_t>(Q);
-    S.staging = c.take<float>((size_t)2 * d.max_batch * d.M);
+    const size_t B = (size_t)d.max_batch, R = 3 * B;
     for (int i = 0; i < 2; ++i) {
-        S.win[i] = c.take<WinDesc>((size_t)2 * d.max_batch + 32);  // GRU tiles read whole 32-row slices
-        S.n_win[i] = c.take<int32_t>(1);
+        QuerySet &q = S.qs[i];
+        q.node = c.take<int32_t>(R);
+        q.t = c.take<double>(R);
+        q.cnt = c.take<int32_t>(R);
+        q.self_ref = c.take<int32_t>(R);
+        q.nbr = c.take<int32_t>(R * d.K);
+        q.ref = c.take<int32_t>(R * d.K);
+        q.eid = c.take<int32_t>(R * d.K);
+        q.ts = c.take<double>(R * d.K);
+        q.slot = c.take<int32_t>(2 * B);
+        q.n_u = c.take<int32_t>(1);
     }
+    S.staging = c.take<float>(2 * B * d.M);
+    S.emb_u = c.take<float>(R * d.E);
+    S.dec_a = c.take<float>(R * d.Ep);
+    S.dec_b = c.take<float>(R * d.Ep);
+    for (int i = 0; i < 2; ++i) {
+        S.win[i] = c.take<WinDesc>(2 * B + 32);  // the overwrite reads a few descriptors past the count
+        S.n_win[i] = c.take<int32_t>(1);
+        S.flags[i] = c.take<uint8_t>(2 * B);
+    }
+    uint32_t slots = 1024;
+    while (slots < 8 * B)  // four slots per (event, role) entry
+        slots *= 2;
+    S.tab_slots = slots;
+    S.tab = c.take<unsigned long long>(slots);
     S.bytes = c.off;
     return S;
 }
@@ -373,7 +395,8 @@ int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *w
     ctx->pos = L.pos;
     ctx->mem = L.mem;
     ctx->lu = L.lu;
-    ctx->key = L.key;
+    ctx->key[0] = L.key[0];
+    ctx->key[1] = L.key[1];
     ctx->packed = L.packed;
 
     // graph copy (host or device source)
@@ -413,39 +436,40 @@ int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *w
     // state after a reset
     INIT_TRY(launch_fill_zero(L.mem, sizeof(float) * (size_t)N * d.M, s), "zero memory");
     INIT_TRY(launch_fill_zero(L.lu, sizeof(double) * (size_t)N, s), "zero last_update");
-    INIT_TRY(launch_fill_zero(L.key, sizeof(unsigned long long) * (size_t)N, s), "zero keys");
+    INIT_TRY(launch_fill_zero(L.key[0], sizeof(unsigned long long) * (size_t)N, s), "zero keys");
+    INIT_TRY(launch_fill_zero(L.key[1], sizeof(unsigned long long) * (size_t)N, s), "zero keys");
+    INIT_TRY(hipStreamSynchronize(s), "sync");
+
+    // per-step intermediates: counters and the claim table start from zero
+    ctx->S = step_scratch(d, scratch);
+    for (int i = 0; i < 2; ++i) {
+        INIT_TRY(launch_fill_zero(ctx->S.n_win[i], 4, s), "clear counters");
+        INIT_TRY(launch_fill_zero(ctx->S.qs[i].n_u, 4, s), "clear counters");
+    }
+    INIT_TRY(launch_fill_zero(ctx->S.tab, sizeof(unsigned long long) * (size_t)ctx->S.tab_slots, s), "clear claim table");
     INIT_TRY(hipStreamSynchronize(s), "sync");
 #undef INIT_TRY
-
-    const StepScratch S = step_scratch(d, scratch);
-    ctx->nbr_node = S.nbr_node;
-    ctx->nbr_eid = S.nbr_eid;
-    ctx->nbr_ts = S.nbr_ts;
-    ctx->nbr_cnt = S.nbr_cnt;
-    ctx->staging = S.staging;
-    for (int i = 0; i < 2; ++i) {
-        ctx->win[i] = S.win[i];
-        ctx->n_win[i] = S.n_win[i];
-    }
-    ctx->cur = 0;
-    ctx->ahead_valid = false;
-    {
-        hipError_t e = launch_fill_zero(S.n_win[0], 256, s);
-        if (e == hipSuccess)
-            e = launch_fill_zero(S.n_win[1], 256, s);
-        const hipError_t e2 = e == hipSuccess ? hipStreamSynchronize(s) : e;
-        if (e2 != hipSuccess) {
-            snprintf(g_init_err, sizeof(g_init_err), "clear counters: %s", hipGetErrorString(e2));
-            delete ctx;
-            return TIG_EHIP;
-        }
-    }
     *out = ctx;
     return TIG_OK;
 }
 
+// A query preparation job for batch (first_eid, count) into query set `qs`.
+static DedupJob make_dedup(const StepScratch &S, const QuerySet &qs, int64_t first_eid, int32_t count,
+                           uint32_t epoch, bool shared)
+{
+    DedupJob j;
+    j.first_eid = first_eid;
+    j.count = count;
+    j.qs = qs;
+    j.tab = S.tab;
+    j.tab_mask = S.tab_slots - 1;
+    j.epoch = epoch;
+    j.n_wgs = prepare_workgroups(count, shared);
+    return j;
+}
+
 // `use_static`: every per-step intermediate lives in this device's static scratch array instead of
-// the context's scratch workspace, the winners are selected up front by the call itself, and
+// the context's scratch workspace, the call prepares everything itself (winners, queries), and
 // nothing is kept there for a later call.
 static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, hipEvent_t *marks,
                      bool use_static = false)
@@ -462,7 +486,7 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
         return fail(ctx, TIG_EINVAL, "tig_step: required output pointer is NULL");
     if (batch->first_eid < ctx->cursor)
         return fail(ctx, TIG_EORDER, "tig_step: batch starts before the end of the previous one");
-    StepScratch st;
+    StepScratch st = ctx->S;
     if (use_static) {
         if (ctx->d.deferred)
             return fail(ctx, TIG_EINVAL, "tig_step_static: the context runs the deferred message order");
@@ -471,133 +495,163 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
                                            "exceed TIG_STATIC_SCRATCH_BYTES");
         st = step_scratch(ctx->d, ctx->static_scratch);
     }
+    const Dims &d = ctx->d;
+    const int64_t first = batch->first_eid;
+    const int32_t count = batch->count;
 
     StepArgs a;
+    memset(&a, 0, sizeof(a));
     a.src = ctx->src;
     a.dst = ctx->dst;
     a.ts = ctx->ts;
     a.edge_feat = ctx->edge_feat;
     a.indptr = ctx->indptr;
     a.csr = ctx->csr;
+    a.pos = ctx->pos;
     a.num_nodes = ctx->num_nodes;
     a.mem = ctx->mem;
     a.lu = ctx->lu;
-    a.key = ctx->key;
-    a.first_eid = batch->first_eid;
-    a.count = batch->count;
+    a.first_eid = first;
+    a.count = count;
     a.roles = batch->neg_dst ? 3 : 2;
     a.neg = batch->neg_dst;
-    a.nbr_node = out->nbr_node ? out->nbr_node : (use_static ? st.nbr_node : ctx->nbr_node);
-    a.nbr_eid = out->nbr_eid ? out->nbr_eid : (use_static ? st.nbr_eid : ctx->nbr_eid);
-    a.nbr_ts = out->nbr_ts ? out->nbr_ts : (use_static ? st.nbr_ts : ctx->nbr_ts);
-    a.nbr_cnt = out->nbr_cnt ? out->nbr_cnt : (use_static ? st.nbr_cnt : ctx->nbr_cnt);
-    a.staging = use_static ? st.staging : ctx->staging;
-    a.pos = ctx->pos;
-    a.is_winner = out->is_winner;
+    a.staging = st.staging;
+    a.emb_u = st.emb_u;
+    a.dec_a = st.dec_a;
+    a.dec_b = st.dec_b;
     a.emb = out->emb;
     a.score_pos = out->score_pos;
     a.score_neg = out->score_neg;
+    a.out_nbr_node = out->nbr_node;
+    a.out_nbr_eid = out->nbr_eid;
+    a.out_nbr_ts = out->nbr_ts;
+    a.out_nbr_cnt = out->nbr_cnt;
+    a.out_is_winner = out->is_winner;
 
-    a.next_is_winner = nullptr;
-    const bool one_launch = 2 * batch->count <= 8192;  // selection in one workgroup
-    StepArgs sel;
-    const StepArgs *selp = nullptr;
-    int launches = 0;
-    int new_cur = ctx->cur;
-    if (use_static) {
-        // everything in the static array; this batch's winners are selected first, none ahead
-        a.win = st.win[0];
-        a.n_win = st.n_win[0];
-        a.msg_first_eid = batch->first_eid;
-        a.msg_count = batch->count;
-        a.next_first_eid = batch->first_eid + batch->count;
-        a.next_count = 0;
-        a.next_win = st.win[1];
-        a.next_n_win = st.n_win[1];
-        selp = &a;
-        launches += (one_launch ? 1 : 2) + 3;
-    } else if (ctx->d.deferred) {
-        // Deferred order: the GRU and the memory overwrite apply the winners kept by the previous
-        // step; this step's winners go to the other list, selected by one extra workgroup of the
-        // embedding launch when it can carry it, else by a selection of its own up front (it
-        // reads the event stream only).
-        a.win = ctx->win[ctx->cur];
-        a.n_win = ctx->n_win[ctx->cur];
+    // What the embedding launch can do on the side for a later step (never for a static call).
+    const bool one_wg = winners_in_one_launch(count);
+    const int spare = use_static ? 0 : embed_spare_workgroups(d, ctx->plan, a.roles, count);
+    uint32_t epoch = ctx->epoch;
+    bool clear_tab = use_static;  // the static array's table holds claims of unknown epochs
+    auto next_epoch = [&]() -> uint32_t {
+        if (use_static)
+            return 1u;
+        if (++epoch == 0u) {  // wrapped: claims of 2^32 jobs ago would read as current
+            clear_tab = true;
+            epoch = 1u;
+        }
+        return epoch;
+    };
+
+    StepPlan sp = {nullptr, nullptr, nullptr, false};
+    SelectJob sel_now = {};
+    DedupJob ded_now = {};
+    int launches = 3;
+
+    // ---- the distinct queries of this batch: prepared by the previous step's embedding launch if
+    // that step guessed this batch (it reads the event stream and the adjacency only), else now
+    const bool q_ready = !use_static && ctx->ahead_q_valid && ctx->ahead_q_first == first &&
+                         ctx->ahead_q_count == count;
+    const int qi = use_static ? 0 : (q_ready ? ctx->qcur ^ 1 : ctx->qcur);
+    a.qs = st.qs[qi];
+    if (!q_ready) {
+        ded_now = make_dedup(st, st.qs[qi], first, count, next_epoch(), one_wg);
+        sp.prep_ded = &ded_now;
+    }
+
+    // ---- the winners the GRU and the memory overwrite apply
+    int wi;  // list applied by this step
+    bool w_ready = false;
+    if (!d.deferred) {
+        // this batch's: selected ahead like the queries, else now
+        w_ready = !use_static && ctx->ahead_w_valid && ctx->ahead_w_first == first && ctx->ahead_w_count == count;
+        wi = use_static ? 0 : (w_ready ? ctx->wcur ^ 1 : ctx->wcur);
+        a.msg_first_eid = first;
+        a.msg_count = count;
+        a.win_flags = st.flags[wi];
+        if (!w_ready) {
+            sel_now = SelectJob{first, count, st.win[wi], st.n_win[wi], st.flags[wi], ctx->key[wi]};
+            (one_wg ? sp.prep_sel : sp.big_sel) = &sel_now;
+        }
+    } else {
+        // Deferred order: the winners kept by the previous step.  This batch's go to the other list,
+        // selected by one workgroup of the embedding launch when it can carry it, else up front
+        // (each list has a key array of its own, so the row references of this step, which need
+        // the applied batch's keys, are not disturbed).
+        wi = ctx->wcur;
         a.msg_first_eid = ctx->pend_first;
         a.msg_count = ctx->pend_valid ? ctx->pend_count : 0;
-        a.is_winner = nullptr;
-        a.next_first_eid = batch->first_eid;
-        a.next_count = 0;
-        a.next_win = ctx->win[ctx->cur ^ 1];
-        a.next_n_win = ctx->n_win[ctx->cur ^ 1];
-        a.next_is_winner = out->is_winner;
-        if (!marks && embed_can_select_ahead(ctx->d, ctx->plan, a.roles, batch->count, batch->count)) {
-            a.next_count = batch->count;
+        a.win_flags = st.flags[wi ^ 1];
+        const SelectJob mine = SelectJob{first, count, st.win[wi ^ 1], st.n_win[wi ^ 1], st.flags[wi ^ 1],
+                                         ctx->key[wi ^ 1]};
+        if (spare > 0 && one_wg) {
+            a.sel = mine;
         } else {
-            sel = a;
-            sel.win = a.next_win;
-            sel.n_win = a.next_n_win;
-            sel.is_winner = out->is_winner;
-            selp = &sel;
-            launches += one_launch ? 1 : 2;
+            sel_now = mine;
+            (one_wg ? sp.prep_sel : sp.big_sel) = &sel_now;
         }
-        launches += a.msg_count > 0 ? 3 : 2;
-    } else {
-        // Winner list of this batch: selected ahead by the previous step's embedding launch if that
-        // step guessed this batch (the selection depends on the event stream only, so state changes
-        // in between do not matter).  A caller that asks for the per-entry flags gets a fresh run.
-        const bool ready = ctx->ahead_valid && ctx->ahead_first == batch->first_eid &&
-                           ctx->ahead_count == batch->count && !out->is_winner && !marks;
-        new_cur = ready ? ctx->cur ^ 1 : ctx->cur;  // takes effect once the launches have succeeded
-        a.win = ctx->win[new_cur];
-        a.n_win = ctx->n_win[new_cur];
-        a.msg_first_eid = batch->first_eid;
-        a.msg_count = batch->count;
-        // Chronological training and evaluation pass consecutive batches of one size: guess that the
-        // next call continues where this one ends, and let the embedding launch select its winners.
-        // (The profiled step keeps every kernel to its own work.)
-        a.next_first_eid = batch->first_eid + batch->count;
-        a.next_count = 0;
-        a.next_win = ctx->win[new_cur ^ 1];
-        a.next_n_win = ctx->n_win[new_cur ^ 1];
-        if (!marks && a.next_first_eid < ctx->num_events) {
-            const int64_t left = ctx->num_events - a.next_first_eid;
-            const int32_t guess = left < batch->count ? (int32_t)left : batch->count;
-            if (embed_can_select_ahead(ctx->d, ctx->plan, a.roles, batch->count, guess))
-                a.next_count = guess;
-        }
-        if (!ready) {
-            selp = &a;
-            launches += one_launch ? 1 : 2;
-        }
-        launches += 3;
     }
-    const hipError_t e = launch_step(ctx->d, ctx->plan, ctx->pw, a, selp, ctx->stream, marks);
+    a.win = st.win[wi];
+    a.n_win = st.n_win[wi];
+    a.msg_key = ctx->key[wi];
+    if (sp.big_sel)
+        launches += 2;
+    if (sp.prep_sel || sp.prep_ded)
+        launches += 1;
+    sp.clear_tab = clear_tab && sp.prep_ded;
+
+    // ---- Chronological training and evaluation pass consecutive batches of one size: guess that
+    // the next call continues where this one ends, and let the embedding launch prepare that batch
+    // (its queries; in the update-first order also its winners) on compute units it leaves idle.
+    const int64_t next_first = first + count;
+    if (spare > 0 && next_first < ctx->num_events) {
+        const int64_t left = ctx->num_events - next_first;
+        const int32_t guess = left < count ? (int32_t)left : count;
+        if (winners_in_one_launch(guess)) {
+            a.ded = make_dedup(st, st.qs[qi ^ 1], next_first, guess, next_epoch(), true);
+            a.n_u_next = st.qs[qi ^ 1].n_u;
+            if (!d.deferred)
+                a.sel = SelectJob{next_first, guess, st.win[wi ^ 1], st.n_win[wi ^ 1], st.flags[wi ^ 1],
+                                  ctx->key[wi ^ 1]};
+        }
+    }
+    if (clear_tab && !sp.prep_ded && a.ded.count > 0) {
+        // the epoch wrapped and only the side job uses the table: clear it ahead of everything
+        const hipError_t e = launch_fill_zero(st.tab, sizeof(unsigned long long) * (size_t)st.tab_slots, ctx->stream);
+        if (e != hipSuccess)
+            return fail(ctx, TIG_EHIP, "tig_step: clearing the claim table", e);
+    }
+
+    const hipError_t e = launch_step(d, ctx->plan, ctx->pw, a, sp, ctx->stream, marks);
     if (e != hipSuccess) {
-        // kernels of this step may already be enqueued: the list bookkeeping stays as it was, the
-        // model state is undefined until tig_reset / tig_state_import
-        if (!use_static)
-            ctx->ahead_valid = false;
+        // kernels of this step may already be enqueued: nothing prepared ahead is trusted any more,
+        // and the model state is undefined until tig_reset / tig_state_import
+        if (!use_static) {
+            ctx->ahead_w_valid = false;
+            ctx->ahead_q_valid = false;
+            ctx->epoch = epoch;
+        }
         return fail(ctx, TIG_EHIP, "tig_step launch", e);
     }
-    if (!use_static) {
-        ctx->ahead_valid = false;
-        ctx->cur = new_cur;
-    }
-    ctx->cursor = batch->first_eid + batch->count;
-    if (!marks)
-        ctx->last_launches = launches;
-    if (use_static) {
-        // the context's own lists are untouched: a list selected ahead stays usable
-    } else if (ctx->d.deferred) {
-        ctx->cur ^= 1;  // the list just selected is the one the next step applies
+    ctx->cursor = next_first;
+    ctx->last_launches = launches;
+    if (use_static)
+        return TIG_OK;  // the context's own lists and sets are untouched: what was prepared ahead stays usable
+    ctx->epoch = epoch;
+    ctx->qcur = qi;
+    ctx->ahead_q_valid = a.ded.count > 0;
+    ctx->ahead_q_first = a.ded.first_eid;
+    ctx->ahead_q_count = a.ded.count;
+    if (d.deferred) {
+        ctx->wcur = wi ^ 1;  // the list just selected is the one the next step applies
         ctx->pend_valid = true;
-        ctx->pend_first = batch->first_eid;
-        ctx->pend_count = batch->count;
-    } else if (a.next_count > 0) {
-        ctx->ahead_valid = true;
-        ctx->ahead_first = a.next_first_eid;
-        ctx->ahead_count = a.next_count;
+        ctx->pend_first = first;
+        ctx->pend_count = count;
+    } else {
+        ctx->wcur = wi;
+        ctx->ahead_w_valid = a.sel.count > 0;
+        ctx->ahead_w_first = a.sel.first_eid;
+        ctx->ahead_w_count = a.sel.count;
     }
     return TIG_OK;
 }
@@ -640,14 +694,17 @@ int tig_step_profiled(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, 
     return TIG_OK;
 }
 
-// Deferred order: forgets the winners kept for the next step.  A selection of more than 4096 events
-// left its keys in the per-node array (the overwrite that would have cleared them never runs).
+// The cursor is rewound: forget the winners kept for the next step (deferred order) and the ones
+// selected ahead, and clear the key arrays (a selection of more than 4096 events merges its keys
+// into them with atomicMax and needs every older key to be smaller; the keys of a list selected
+// ahead go with them, so that list is dropped too).  Queries prepared ahead stay valid.
 static hipError_t drop_pending(tig_ctx *ctx)
 {
-    hipError_t e = hipSuccess;
-    if (ctx->pend_valid && 2 * ctx->pend_count > 8192)
-        e = launch_fill_zero(ctx->key, sizeof(unsigned long long) * (size_t)ctx->num_nodes, ctx->stream);
+    hipError_t e = launch_fill_zero(ctx->key[0], sizeof(unsigned long long) * (size_t)ctx->num_nodes, ctx->stream);
+    if (e == hipSuccess)
+        e = launch_fill_zero(ctx->key[1], sizeof(unsigned long long) * (size_t)ctx->num_nodes, ctx->stream);
     ctx->pend_valid = false;
+    ctx->ahead_w_valid = false;
     return e;
 }
 

@@ -68,6 +68,55 @@ struct __attribute__((aligned(8))) WinDesc {
     double t;       // event time
 };
 
+// A row reference names where the CURRENT state row of a node lives while a step runs: the
+// memory table (the node was not updated by this step), or the staged GRU output of the entry
+// that supplied the node's message (the memory overwrite happens after the embedding).
+//   ref >= 0: memory row `ref`;  ref < 0 (not kRefNone): staging row ~ref;  kRefNone: a zero row.
+constexpr int32_t kRefNone = INT32_MIN;
+
+// The distinct embedding queries (node, t) of one batch.  Source and destination queries of a
+// batch repeat heavily (hub nodes, events sharing a timestamp); each distinct pair gets ONE row
+// here, `slot` maps every (event, role) entry to its row.  Rows [0, *n_u) belong to source /
+// destination queries, rows *n_u + b to the negative of event b (negatives are not merged).
+struct QuerySet {
+    int32_t *node;      // [R] node id, -1: none
+    double *t;          // [R] query time
+    int32_t *cnt;       // [R] filled neighbour slots
+    int32_t *self_ref;  // [R] row reference of the node's own state
+    int32_t *nbr;       // [R x K] neighbour node ids, -1 = unused slot
+    int32_t *ref;       // [R x K] their row references
+    int32_t *eid;       // [R x K] their event ids, -1 = unused
+    double *ts;         // [R x K] their event times, 0.0 = unused
+    int32_t *slot;      // [2B] entry 2b+role -> row (>= 0), or -(entry of its representative) - 1
+    int32_t *n_u;       // [1]
+};
+
+// Last-message selection of one batch (count 0: nothing to do).  Besides the compacted winner
+// list it leaves key[node] = the winning entry's 64-bit (time, event id, role) key.  There are two
+// winner lists (the one a step applies and the one selected meanwhile), each with a key array of
+// its own; a key array is only ever written by selections of chronologically later batches, or
+// cleared (tig_reset / tig_state_import), so a stale key is never greater than a batch's own.
+struct SelectJob {
+    int64_t first_eid;
+    int32_t count;
+    WinDesc *win;       // out: winners
+    int32_t *n_win;     // out: their number
+    uint8_t *flags;     // out: [2 * count] 1 where the entry supplied its node's message
+    unsigned long long *key;  // in/out: [N] the key array that goes with this winner list
+};
+
+// Merging of equal (node, t) queries of one batch's sources and destinations + the neighbour
+// lookup of every distinct one (count 0: nothing to do).
+struct DedupJob {
+    int64_t first_eid;
+    int32_t count;
+    QuerySet qs;                // out (n_u must be 0 when the job starts)
+    unsigned long long *tab;    // hash table of claims, (epoch << 32 | entry); other epochs = empty
+    uint32_t tab_mask;          // slots - 1 (power of two, >= 4 * count)
+    uint32_t epoch;             // != 0, different from every earlier job on this table
+    int32_t n_wgs;              // workgroups that share the job
+};
+
 struct StepArgs {
     // graph (device)
     const int32_t *src, *dst;
@@ -80,7 +129,6 @@ struct StepArgs {
     // state (device)
     float *mem;
     double *lu;
-    unsigned long long *key;
     // batch
     int64_t first_eid;
     int32_t count;
@@ -90,27 +138,29 @@ struct StepArgs {
     // previous step's in the deferred order (msg_count 0: nothing to apply)
     int64_t msg_first_eid;
     int32_t msg_count;
+    WinDesc *win;
+    int32_t *n_win;
+    const unsigned long long *msg_key;  // [N] key array of that selection (see SelectJob)
+    const uint8_t *win_flags;  // flags of THIS batch's selection (copied out when asked for), may be NULL
     // intermediates (device)
-    int32_t *nbr_node, *nbr_eid, *nbr_cnt;
-    double *nbr_ts;
-    float *staging;  // [2*count x M] new memory rows of the winners, by entry 2b+role
-    WinDesc *win;       // [2*count] entries that supply their node's message (compacted)
-    int32_t *n_win;     // [1] their number
-    uint8_t *is_winner;  // may be NULL
-    // the batch expected to follow (next_count 0: none): its winners are selected by one extra
-    // workgroup of this step's embedding launch
-    int64_t next_first_eid;
-    int32_t next_count;
-    WinDesc *next_win;
-    int32_t *next_n_win;
-    uint8_t *next_is_winner;  // may be NULL
+    QuerySet qs;     // distinct queries of this batch
+    float *staging;  // [2*msg_count x M] new memory rows of the winners, by entry 2b+role
+    float *emb_u;    // [R x E] embedding of every distinct query
+    float *dec_a;    // [R x Ep] first decoder layer, source half, of every distinct query
+    float *dec_b;    // [R x Ep] the same, second-operand half
+    int32_t *n_u_next;  // counter of the query set the next preparation will fill (cleared here), may be NULL
+    // work done on compute units the embedding launch leaves idle: selection of a batch's winners
+    // and preparation of a batch's queries
+    SelectJob sel;
+    DedupJob ded;
     // outputs
     float *emb, *score_pos, *score_neg;
+    int32_t *out_nbr_node, *out_nbr_eid, *out_nbr_cnt;  // optional
+    double *out_nbr_ts;                                 // optional
+    uint8_t *out_is_winner;                             // optional
 };
 
 struct LaunchPlan {
-    int gru_entries;     // entries (event, role) per GRU workgroup: 16*gru_mt
-    int gru_mt;          // 16-row tiles per GRU workgroup
     int gru_lds;         // bytes
     int emb_mt;          // most 16-row tiles per embedding workgroup (what LDS holds)
     int num_cus;         // compute units of the device (0 until known)
@@ -133,30 +183,42 @@ hipError_t pack_weights(const Dims &d, const tig_weights &w_dev_f32, void *dst, 
                         PackedWeights *pw, hipStream_t s);
 
 bool plan_launch(const Dims &d, int lds_limit, LaunchPlan *plan);
-int gru_lds_bytes(const Dims &d, int mt);
+int gru_lds_bytes(const Dims &d);
 int embed_lds_bytes(const Dims &d, int mt);
 hipError_t prepare_gru(const Dims &d, const LaunchPlan &plan);
 hipError_t prepare_embed(const Dims &d, const LaunchPlan &plan);
 hipError_t prepare_small();
-// winners of the batch in one launch when it is small enough; otherwise scatter + *needs_select
-hipError_t launch_scatter(const StepArgs &a, hipStream_t s, bool *needs_select);
-hipError_t launch_select(const StepArgs &a, hipStream_t s);
-// GRU tiles and, in the same launch, the neighbour lookup of every query
+bool winners_in_one_launch(int count);
+// batches above the one-workgroup limit: keys to the per-node array, then winners + flags
+hipError_t launch_scatter(const StepArgs &a, const SelectJob &j, hipStream_t s);
+hipError_t launch_select(const StepArgs &a, const SelectJob &j, hipStream_t s);
+// selection (one workgroup, if sel.count > 0) and query preparation (if ded.count > 0) as a launch
+hipError_t launch_prepare(const StepArgs &a, const SelectJob &sel, const DedupJob &ded, int K, hipStream_t s);
+// GRU tiles and, in the same launch, what is left of the query preparation: negatives, row references
 hipError_t launch_gru(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
                       hipStream_t s);
-hipError_t launch_commit(const StepArgs &a, int M, hipStream_t s);
 hipError_t launch_embed(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
                         hipStream_t s);
-// whether the embedding launch of a batch of `count` events can carry one more workgroup that
-// selects the winners of a following batch of `next_count` events without delaying anything
-bool embed_can_select_ahead(const Dims &d, const LaunchPlan &plan, int roles, int count, int next_count);
+// scores and per-query embeddings from the distinct rows, memory overwrite, optional inspection outputs
+hipError_t launch_decode(const Dims &d, const PackedWeights &pw, const StepArgs &a, hipStream_t s);
+// workgroups the embedding launch can spare for a following batch's preparation (0: none)
+int embed_spare_workgroups(const Dims &d, const LaunchPlan &plan, int roles, int count);
+// workgroups of a batch's query preparation; `shared`: in a launch whose workgroups each occupy a
+// compute unit (beside the embedding tiles or the one-workgroup selection)
+int prepare_workgroups(int count, bool shared);
 hipError_t prepare_kernels(const Dims &d, const LaunchPlan &plan);
-constexpr int kNumStepKernels = 5;
-// `marks`: NULL, or kNumStepKernels + 1 events recorded before the first and after every kernel.
-// `sel`: NULL, or the arguments of a last-message selection to run first (its first_eid / count /
-// win / n_win / is_winner name the batch and where the winners go).
+constexpr int kNumStepKernels = TIG_NUM_STEP_KERNELS;
+// What one step launches, in order: [scatter, select] (up-front selection of a batch above the
+// one-workgroup limit), [prepare] (selection and / or query preparation not done ahead),
+// gru, embed, decode.  `marks`: NULL, or kNumStepKernels + 1 events.
+struct StepPlan {
+    const SelectJob *big_sel;   // scatter + select launches, or NULL
+    const SelectJob *prep_sel;  // selection inside the prepare launch, or NULL
+    const DedupJob *prep_ded;   // query preparation inside the prepare launch, or NULL
+    bool clear_tab;             // clear prep_ded's claim table first
+};
 hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw,
-                       const StepArgs &a, const StepArgs *sel, hipStream_t s, hipEvent_t *marks);
+                       const StepArgs &a, const StepPlan &sp, hipStream_t s, hipEvent_t *marks);
 hipError_t launch_fill_zero(void *ptr, size_t bytes, hipStream_t s);
 
 }  // namespace tig

@@ -1,8 +1,8 @@
 // Last-message selection of a whole batch inside ONE workgroup of 1024 threads (paper Sec. II-C:
 // the messages of a node within a batch are aggregated; this build keeps the last one).
 // The result depends on the event stream only, not on the model state, so the embedding kernel
-// of one step can run it for the FOLLOWING batch in one extra workgroup; the same code is also a
-// launch of its own.  gfx950 only.
+// of one step can run it for the FOLLOWING batch in one extra workgroup; the same code also runs
+// in the preparation launch of a step whose batch was not anticipated.  gfx950 only.
 #pragma once
 
 #include "kernels_common.h"
@@ -15,31 +15,6 @@ constexpr int kOneIters = 8;           // up to 8 entries per thread
 constexpr int kOneMaxEntries = kOneIters * kScatterThreads;
 constexpr int kOneSlots = 12288;       // 1.5 x the most distinct nodes, never fills up
 constexpr int kOneLds = kOneSlots * 12 + (kOneIters * kScatterWaves + 1) * 4;
-
-struct WinnersJob {
-    const int32_t *src, *dst;  // event endpoints
-    const double *ts;          // event times
-    int64_t first_eid;
-    int32_t count;             // 2 * count <= kOneMaxEntries
-    WinDesc *win;              // out: winners in entry order
-    int32_t *n_win;            // out: their number
-    uint8_t *is_winner;        // out, may be NULL: flag per entry
-};
-
-// the job of the step's own batch, or of the batch announced to follow it
-__host__ __device__ inline WinnersJob winners_job(const StepArgs &a, bool following)
-{
-    WinnersJob j;
-    j.src = a.src;
-    j.dst = a.dst;
-    j.ts = a.ts;
-    j.first_eid = following ? a.next_first_eid : a.first_eid;
-    j.count = following ? a.next_count : a.count;
-    j.win = following ? a.next_win : a.win;
-    j.n_win = following ? a.next_n_win : a.n_win;
-    j.is_winner = following ? a.next_is_winner : a.is_winner;
-    return j;
-}
 
 struct Entry {
     int32_t node, other;
@@ -109,7 +84,10 @@ __device__ inline void table_insert_max(int32_t *t_node, unsigned long long *t_k
 }
 
 // All 1024 threads of the workgroup call this; smem holds kOneLds bytes, 16-byte aligned.
-__device__ inline void winners_block(const WinnersJob &a, char *smem)
+// Besides the winner list and the per-entry flags, every winner leaves its key in key[node]: a
+// later lookup of "was this node updated by batch (first_eid, count), and by which entry" reads
+// key[node] and checks that the event id inside lies in the batch (keys of other batches do not).
+__device__ inline void winners_block(const StepArgs &g, const SelectJob &a, char *smem)
 {
     unsigned long long *t_key = (unsigned long long *)smem;   // [kOneSlots]
     int32_t *t_node = (int32_t *)(smem + kOneSlots * 8);      // [kOneSlots]
@@ -132,7 +110,7 @@ __device__ inline void winners_block(const WinnersJob &a, char *smem)
         ent[it].t = 0.0;
         ent[it].key = 0ull;
         if (i < n_entries)
-            ent[it] = load_entry(a.src, a.dst, a.ts, a.first_eid, i);
+            ent[it] = load_entry(g.src, g.dst, g.ts, a.first_eid, i);
     }
     __syncthreads();
 #pragma unroll
@@ -194,9 +172,10 @@ __device__ inline void winners_block(const WinnersJob &a, char *smem)
 #pragma unroll
     for (int it = 0; it < kOneIters; ++it) {
         const int i = it * kScatterThreads + threadIdx.x;
-        if (i < n_entries && a.is_winner)
-            a.is_winner[i] = win[it] ? 1 : 0;
+        if (i < n_entries && a.flags)
+            a.flags[i] = win[it] ? 1 : 0;
         if (win[it]) {
+            a.key[ent[it].node] = ent[it].key;
             WinDesc d;
             d.entry = i;
             d.node = ent[it].node;

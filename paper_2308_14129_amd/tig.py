@@ -207,15 +207,16 @@ class TigContext:
         fn = self.lib.tig_step_static if static else self.lib.tig_step
         self._check(fn(self.handle, ctypes.byref(b), ctypes.byref(o)))
 
-    KERNEL_NAMES = ("k_scatter", "k_select", "k_gru", "k_commit", "k_embed")
+    KERNEL_NAMES = ("k_scatter", "k_select", "k_prepare", "k_gru", "k_embed", "k_decode")
 
     def step_profiled(self, first_eid: int, count: int, neg_dst, out: StepOutputs):
-        """One step with HIP events around every kernel; returns the five durations in ms."""
+        """One step with HIP events around every kernel; returns the durations in ms, one per
+        entry of KERNEL_NAMES (0 for a kernel the step did not need)."""
         b = tig_batch(ctypes.sizeof(tig_batch), count, first_eid, _addr(neg_dst))
         o = tig_out(ctypes.sizeof(tig_out), 0, _addr(out.emb), _addr(out.score_pos), _addr(out.score_neg),
                     _addr(out.nbr_node), _addr(out.nbr_eid), _addr(out.nbr_ts), _addr(out.nbr_cnt),
                     _addr(out.is_winner))
-        ms = (c_float * 5)()
+        ms = (c_float * len(self.KERNEL_NAMES))()
         self._check(self.lib.tig_step_profiled(self.handle, ctypes.byref(b), ctypes.byref(o), ms))
         return [float(x) for x in ms]
 

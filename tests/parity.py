@@ -23,16 +23,16 @@ def gate(got: np.ndarray, ref: np.ndarray, tol: float, name: str) -> float:
     return worst
 
 
-def compare_step(ctx, out, ref, oracle_state, tol, check_state=True):
+def compare_step(ctx, out, ref, oracle_state, tol, check_state=True, before=None, touched=None):
     """Neighbour tables and winners bit-exact; embeddings, scores and state within `tol`.
-    Without the per-entry winner flags the winners are still pinned through last_update, which
-    must equal the oracle's bit for bit over all nodes."""
+    before = (mem, last_update) of the GPU side when the step started and touched = the node ids
+    whose messages the step applied: every other row must come out of the step bit-identical.
+    Returns the gate ratios and, under "state", the exported (mem, last_update)."""
     np.testing.assert_array_equal(out.nbr_cnt.cpu().numpy(), ref["nbr_cnt"], err_msg="nbr_cnt")
     np.testing.assert_array_equal(out.nbr_node.cpu().numpy(), ref["nbr_node"], err_msg="nbr_node")
     np.testing.assert_array_equal(out.nbr_eid.cpu().numpy(), ref["nbr_eid"], err_msg="nbr_eid")
     np.testing.assert_array_equal(out.nbr_ts.cpu().numpy(), ref["nbr_ts"], err_msg="nbr_ts")
-    if out.is_winner is not None:
-        np.testing.assert_array_equal(out.is_winner.cpu().numpy(), ref["is_winner"], err_msg="is_winner")
+    np.testing.assert_array_equal(out.is_winner.cpu().numpy(), ref["is_winner"], err_msg="is_winner")
     res = {"emb": gate(out.emb.cpu().numpy(), ref["emb"], tol, "emb"),
            "score_pos": gate(out.score_pos.cpu().numpy(), ref["score_pos"], tol, "score_pos")}
     if ref["score_neg"] is not None:
@@ -41,5 +41,10 @@ def compare_step(ctx, out, ref, oracle_state, tol, check_state=True):
         mem, lu = ctx.state_export()
         np.testing.assert_array_equal(lu, oracle_state.last_update, err_msg="last_update")
         res["mem"] = gate(mem, oracle_state.mem, tol, "mem")
-        # rows the oracle left untouched must be bit-identical on the GPU as well
+        if before is not None:
+            keep = np.ones(mem.shape[0], dtype=bool)
+            keep[np.asarray(touched, dtype=np.int64)] = False
+            assert np.array_equal(mem[keep], before[0][keep]), "a memory row outside the applied batch changed"
+            assert np.array_equal(lu[keep], before[1][keep]), "last_update outside the applied batch changed"
+        res["state"] = (mem, lu)
     return res

@@ -34,15 +34,16 @@ class Bundle:
         self.ix = O.NeighbourIndex(self.g.num_nodes, self.g.src, self.g.dst, self.g.ts)
 
 
-def run(bundle, precision, batches, locked, warm_at=None, with_neg=True, ctx=None, flags=True,
-        order="update_first"):
+def run(bundle, precision, batches, locked, warm_at=None, with_neg=True, ctx=None, order="update_first",
+        expect_launches=None):
     """Runs the batches on both sides.  locked=True loads the oracle's state into the GPU before
     every step (step-locked parity); otherwise both sides run freely from the same start, which
     is the state after a reset or, with warm_at, the seeded warm state of a mid-stream window.
-    flags=False leaves out the per-entry winner flags, as a training loop does: only then does a
-    step use the winners that the previous step's embedding launch selected ahead.
+    Every step asks for the neighbour tables and the per-entry winner flags (they do not change
+    what is launched) and checks that rows outside the applied batch stay bit-identical.
     order="deferred": both sides apply the previous step's winners before embedding (a state
-    import drops what is kept, on both sides)."""
+    import drops what is kept, on both sides).
+    expect_launches: kernels per step, checked from the second step on."""
     import torch
     w, g, W, ix = bundle.w, bundle.g, bundle.W, bundle.ix
     own = ctx is None
@@ -55,21 +56,30 @@ def run(bundle, precision, batches, locked, warm_at=None, with_neg=True, ctx=Non
     else:
         st = O.OracleState(*S.make_warm_state(w, g, warm_at))
         ctx.state_import(st.mem, st.last_update)
+    before = (st.mem.copy(), st.last_update.copy())
+    applied = None  # deferred order: the batch whose winners the next step applies
     worst = {}
-    for first, count in batches:
+    for n, (first, count) in enumerate(batches):
         print(f"[{w.name} {precision}] step first_eid={first} count={count}", flush=True)
         neg = S.make_negatives(w, g, first, count) if with_neg else None
         if locked:
             ctx.state_import(st.mem, st.last_update)
             st.drop_pending()
+            before = (st.mem.copy(), st.last_update.copy())
+            applied = None
         ref = O.step(st, g.src, g.dst, g.ts, g.edge_feat, W, first, count, neg, w.num_neighbors,
                      w.num_heads, index=ix, deferred=deferred)
         out = ctx.alloc_outputs(count, with_neg=with_neg, inspect=True)
-        if not flags:
-            out.is_winner = None
         ctx.step(first, count, torch.from_numpy(neg).to("cuda:0") if with_neg else None, out)
         torch.cuda.synchronize()
-        res = compare_step(ctx, out, ref, st, TOL[precision])
+        if expect_launches is not None and n > 0 and not locked:
+            assert ctx.launch_info()["kernels_per_step"] == expect_launches
+        msg = (first, count) if not deferred else applied
+        touched = (np.concatenate([g.src[msg[0]:msg[0] + msg[1]], g.dst[msg[0]:msg[0] + msg[1]]])
+                   if msg is not None else np.zeros(0, dtype=np.int64))
+        res = compare_step(ctx, out, ref, st, TOL[precision], before=before, touched=touched)
+        before = res.pop("state")
+        applied = (first, count)
         for k, v in res.items():
             worst[k] = max(worst.get(k, 0.0), v)
     print(f"[{w.name} {precision}] worst gate ratios: {worst}", flush=True)
@@ -114,27 +124,28 @@ def test_c1_single_event_batches(c1):
 
 
 @pytest.mark.parametrize("precision", ["fp32", "bf16"])
-def test_c1_consecutive_batches_with_winners_selected_ahead(c1, precision):
-    # whole stream incl. the short last batch (10,000 = 73 * 136 + 72), free running and step-locked
+def test_c1_consecutive_batches_prepared_ahead(c1, precision):
+    # whole stream incl. the short last batch (10,000 = 73 * 136 + 72), free running: from the second
+    # step on a step is three launches, its winners and queries prepared by the step before (the
+    # last, shorter batch was anticipated with its real size); and step-locked
     bs = list(S.batches(c1.w.num_events, 136))
     assert bs[-1][1] == 72
-    run(c1, precision, bs, locked=False, flags=False)
-    run(c1, "fp32", bs[:6], locked=True, flags=False)
+    run(c1, precision, bs, locked=False, expect_launches=3)
+    run(c1, "fp32", bs[:6], locked=True)
 
 
 def test_c1_wrong_guesses_of_the_next_batch(c1):
-    # batches that do not continue the previous one: revisits, gaps, changing sizes, and a
-    # request for the flags in between; every step must still equal the oracle's
+    # batches that do not continue the previous one: revisits, gaps, changing sizes; every step
+    # must still equal the oracle's
     import torch
     w, g, W = c1.w, c1.g, c1.W
     ctx = make_ctx(w, g, W, "fp32", 300)
     seq = [(0, 200), (200, 200), (200, 200), (400, 100), (500, 300), (1000, 300), (1300, 300),
            (1600, 7), (1607, 7), (1614, 300), (0, 200), (200, 200)]
-    run(c1, "fp32", seq[:5], locked=True, ctx=ctx, flags=False)
-    run(c1, "fp32", seq[5:10], locked=True, ctx=ctx, flags=False)
-    run(c1, "fp32", seq[10:], locked=False, ctx=ctx, flags=False)   # reset in between
-    run(c1, "fp32", [(0, 200), (200, 200)], locked=False, ctx=ctx, flags=True)
-    run(c1, "fp32", [(400, 200), (600, 200)], locked=True, ctx=ctx, flags=False)
+    run(c1, "fp32", seq[:5], locked=True, ctx=ctx)
+    run(c1, "fp32", seq[5:10], locked=True, ctx=ctx)
+    run(c1, "fp32", seq[10:], locked=False, ctx=ctx)   # reset in between
+    run(c1, "fp32", [(400, 200), (600, 200)], locked=True, ctx=ctx)
     ctx.close()
 
 
@@ -143,7 +154,7 @@ def test_c1_deferred_order_whole_stream(c1, precision):
     # the step applies the previous batch's winners, embeds, keeps its own; incl. the short last batch
     bs = list(S.batches(c1.w.num_events, 136))
     run(c1, precision, bs, locked=False, order="deferred")
-    run(c1, precision, bs[:8], locked=False, order="deferred", flags=False, with_neg=False)
+    run(c1, precision, bs[:8], locked=False, order="deferred", with_neg=False)
 
 
 def test_c1_deferred_order_gaps_sizes_and_imports(c1):
@@ -181,8 +192,7 @@ def test_c2_windows_and_last_short_batch_fp32(c2):
 
 def test_c2_window_bf16(c2):
     first, bs = window(c2.w, 0.5, 3)
-    run(c2, "bf16", bs, locked=False, warm_at=first)
-    run(c2, "bf16", bs, locked=False, warm_at=first, flags=False)
+    run(c2, "bf16", bs, locked=False, warm_at=first, expect_launches=3)
 
 
 # ------------------------------------------------------------------------------------- C3
@@ -209,8 +219,20 @@ def test_c3_batch_above_the_fused_selection_limit(c3):
     # ... and is never done ahead; 4096 -> 5000 -> 3000 crosses the limit in both directions
     first, bs = window(c3.w, 0.5, 1, 4096)
     seq = bs + [(first + 4096, 5000), (first + 9096, 3000), (first + 12096, 3000)]
-    run(c3, "fp32", seq, locked=False, warm_at=first, flags=False)
+    run(c3, "fp32", seq, locked=False, warm_at=first)
     run(c3, "fp32", seq, locked=False, warm_at=first, order="deferred")
+    # three large batches in a row (their keys stay in the per-node arrays from one to the next),
+    # then a state import and a restart from an earlier event
+    ctx = make_ctx(c3.w, c3.g, c3.W, "fp32", 5000, "deferred")
+    big = [(first + i * 5000, 5000) for i in range(3)]
+    run(c3, "fp32", big, locked=False, warm_at=first, ctx=ctx, order="deferred")
+    run(c3, "fp32", [(first - 3000, 3000), (first, 5000)], locked=False, warm_at=first - 3000, ctx=ctx,
+        order="deferred")
+    ctx.close()
+    ctx = make_ctx(c3.w, c3.g, c3.W, "fp32", 5000)
+    run(c3, "fp32", big, locked=False, warm_at=first, ctx=ctx)
+    run(c3, "fp32", [(first - 3000, 3000), (first, 5000)], locked=False, warm_at=first - 3000, ctx=ctx)
+    ctx.close()
 
 
 # ------------------------------------------------------------------------------------- C4
