@@ -118,16 +118,26 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
         // The workgroups beyond the tiles, on compute units this launch leaves idle (launched only
         // with 1024 threads): last-message selection and query preparation for a later step.
         if constexpr (kEmbedThreads == kScatterThreads) {
+            TIG_MARK(0);
             int x = (int)blockIdx.x - p.n_tiles;
+            if (x == 0 && threadIdx.x == 0 && a.rows_seen) {
+                // hints for the host (stores to its memory take a while: from a workgroup that ends
+                // long before the launch does)
+                a.rows_seen[0] = *a.qs.n_u + (a.roles == 3 ? a.count : 0);
+                if (a.msg_count > 0)
+                    a.rows_seen[1] = *a.n_win;
+            }
             if (a.sel.count > 0) {
                 if (x == 0) {
                     winners_block(a, a.sel, smem);
+                    TIG_MARK(7);
                     return;
                 }
                 --x;
             }
             if (a.ded.count > 0 && x < a.ded.n_wgs)
                 dedup_block(a, a.ded, p.K, x, smem);
+            TIG_MARK(7);
         }
         return;
     }
@@ -204,6 +214,34 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     }
     __syncthreads();
 
+    // Phase C hands its rows out through an LDS counter, heaviest first (sources / destinations come
+    // first in the set), so that wavefronts with short rows take more of them.  The neighbour table
+    // of a row (slot k lives in lane k) is fetched when the row before it is started; the first
+    // row's table is requested here, a phase early.
+    auto grab = [&]() -> int {
+        int r = 0;
+        if (lane == 0)
+            r = atomicAdd(next_row, 1);
+        return __builtin_amdgcn_readfirstlane(r);
+    };
+    auto load_nb = [&](int r, int32_t &v, int32_t &e, double &dt) {
+        v = 0;
+        e = 0;
+        dt = 0.0;
+        if (r < ROWS) {
+            const int q = row_q[r];
+            if (q >= 0 && lane < row_cnt[r]) {
+                v = a.qs.ref[(size_t)q * p.K + lane];  // row reference of the neighbour's state
+                e = a.qs.eid[(size_t)q * p.K + lane];
+                dt = row_t[r] - a.qs.ts[(size_t)q * p.K + lane];
+            }
+        }
+    };
+    int r = grab();
+    int32_t nb_v2, nb_e2;
+    double nb_dt2;
+    load_nb(r, nb_v2, nb_e2, nb_dt2);
+
     TIG_MARK(1);
     // ---- B. folded query: q~ = A1 s_u + a1  (fp32, [H x dkvp] per row) -----------------------
     {
@@ -256,28 +294,6 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
             offm[n] = jj < 0 ? 0xffffffffu : (uint32_t)jj * 4u;
         }
         const uint32_t m_bytes = (uint32_t)cM * 4u, f_bytes = (uint32_t)cF * 4u;
-        // Rows are handed out through an LDS counter, heaviest roles first (sources, destinations,
-        // negatives), so that wavefronts with short rows take more of them.  The neighbour table
-        // of a row (slot k lives in lane k) is fetched when the row before it is started.
-        auto grab = [&]() -> int {
-            int r = 0;
-            if (lane == 0)
-                r = atomicAdd(next_row, 1);
-            return __builtin_amdgcn_readfirstlane(r);
-        };
-        auto load_nb = [&](int r, int32_t &v, int32_t &e, double &dt) {
-            v = 0;
-            e = 0;
-            dt = 0.0;
-            if (r < ROWS) {
-                const int q = row_q[r];
-                if (q >= 0 && lane < row_cnt[r]) {
-                    v = a.qs.ref[(size_t)q * p.K + lane];  // row reference of the neighbour's state
-                    e = a.qs.eid[(size_t)q * p.K + lane];
-                    dt = row_t[r] - a.qs.ts[(size_t)q * p.K + lane];
-                }
-            }
-        };
         // time-encoding parameters of the lane's Phi dims, kept in registers for compiled-in shapes
         double tw_reg[NPHI], tb_reg[NPHI];
 #pragma unroll
@@ -290,10 +306,8 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                 tb_reg[n] = tw_tab[2 * j + 1];
             }
         }
-        int r = grab();
-        int32_t nb_v1, nb_e1, nb_v2, nb_e2;
-        double nb_dt1, nb_dt2;
-        load_nb(r, nb_v2, nb_e2, nb_dt2);
+        int32_t nb_v1, nb_e1;
+        double nb_dt1;
 #pragma unroll 1
         while (r < ROWS) {
             const int32_t nb_vc = nb_v2, nb_ec = nb_e2;
@@ -573,7 +587,7 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                 }
                 const int kb0 = my_ks * kb_half;
                 const int nkb = (kbT - kb0) < kb_half ? (kbT - kb0) : kb_half;
-                tile_gemm<PREC, MT, 4>(acc, rowbuf, p.row_bytes, kb0, w.emb_PR, kbT, kb0, nkb, my_nt);
+                tile_gemm<PREC, MT, (MT <= 2 ? 5 : 4)>(acc, rowbuf, p.row_bytes, kb0, w.emb_PR, kbT, kb0, nkb, my_nt);
             }
             if (ksplit == 2) {
                 if (on && my_ks == 1) {
@@ -794,13 +808,12 @@ int embed_lds_bytes(const Dims &d, int mt)
     return p.off_meta + 16 * mt * (3 * 4 + 8) + d.T * 16 + 16;
 }
 
-// 16-row tiles per workgroup for a batch of `count` events.  A workgroup's latency grows with its
-// rows, so the smallest tile count is taken whose tiles, one per workgroup, cover the most rows
-// the batch can have (no repeated query) on the compute units at hand.
-static int embed_tiles(const LaunchPlan &plan, int roles, int count, int units)
+// 16-row tiles per workgroup for `rows` query rows.  A workgroup's latency grows with its rows,
+// so the smallest tile count is taken whose tiles, one per workgroup, fit the compute units at hand.
+static int embed_tiles(const LaunchPlan &plan, int rows, int units)
 {
     for (int mt = 1; mt < plan.emb_mt; ++mt)
-        if ((roles * count + 16 * mt - 1) / (16 * mt) <= units)
+        if ((rows + 16 * mt - 1) / (16 * mt) <= units)
             return mt;
     return plan.emb_mt;
 }
@@ -825,8 +838,8 @@ int prepare_workgroups(int count, bool shared)
 {
     const int entries = 2 * count;
     int n = shared ? (entries + kPrepWaves - 1) / kPrepWaves : (entries + 4 * kPrepWaves - 1) / (4 * kPrepWaves);
-    if (shared && n > 63)
-        n = 63;
+    if (shared && n > 31)
+        n = 31;
     const int least = (entries + kPrepThreads - 1) / kPrepThreads;  // one entry per thread at most
     return n < least ? least : n;
 }
@@ -849,7 +862,11 @@ hipError_t launch_embed(const Dims &d, const LaunchPlan &plan, const PackedWeigh
     const int extra = (a.sel.count > 0 ? 1 : 0) + (a.ded.count > 0 ? a.ded.n_wgs : 0);
     const int cus = plan.num_cus > 0 ? plan.num_cus : 256;
     const int units = cus - extra > 16 ? cus - extra : 16;
-    const int mt = embed_tiles(plan, a.roles, a.count, units);
+    // The tile height follows the number of distinct rows recent steps had (any height is correct:
+    // the grid covers the most rows the batch can have, and tiles beyond the actual count return).
+    const int most = a.roles * a.count;
+    const int rows = a.rows_est > 0 && a.rows_est < most ? a.rows_est : most;
+    const int mt = embed_tiles(plan, rows, units);
     EmbedParams p = embed_params(d, mt);
     p.n_tiles = (a.roles * a.count + 16 * mt - 1) / (16 * mt);  // tiles in use if no query repeats
     void *args[] = {&aa, &ww, &p};

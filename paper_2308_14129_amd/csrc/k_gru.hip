@@ -8,11 +8,11 @@
 // 2B entries), so the GRU workgroups are a fixed grid that divides the work itself: 16-row tiles
 // of winners x slices of the gate columns, as many column slices per tile as keep the grid busy
 // (every workgroup streams only its slice of the gate weights; all slices of a tile gather the
-// same rows).  One work item (16 wavefronts):
+// same rows).  One work item (8 wavefronts):
 //   1  row descriptors: node, partner, event, event time (dt = t - last_update[node] in step 2)
 //   2  message rows [s_self | s_other | Phi(dt) | e] gathered from the batch-START memory into an
 //      LDS tile (every element of every row is an independent load: one round of latency)
-//   3  gate pre-activations on the matrix cores: the 16 wavefronts are 8 pairs, one wavefront of
+//   3  gate pre-activations on the matrix cores: the 8 wavefronts are 4 pairs, one wavefront of
 //      a pair for the r and z gates, the other for the two halves of the n gate (input part over
 //      the whole message, hidden part over s_self); the pairs split the item's column tiles and,
 //      when there are fewer column tiles than pairs, the k range of each; partial sums meet in LDS
@@ -35,7 +35,7 @@ extern "C" __attribute__((visibility("default"))) int tig_debug_phase_clocks_gru
 
 namespace {
 
-constexpr int kGruThreads = 1024;
+constexpr int kGruThreads = 512;  // two workgroups per compute unit: the finishing pass runs beside the GRU
 constexpr int kGruWaves = kGruThreads / kWave;
 constexpr int kPairs = kGruWaves / 2;  // wavefront pairs: (r, z) | n
 constexpr int EC = 16;                 // winners per tile
@@ -46,8 +46,13 @@ struct GruParams {
     int ldx;       // LDS row stride of the message tile, bytes
     int off_part;  // byte offset of the partial-sum buffer in LDS
     int n_gru;     // GRU workgroups (the first blocks of the grid)
-    int n_finish;  // wavefronts of the finishing pass
+    int cs;        // column slices per tile (any value from 1 to the number of column tiles is correct)
+    int n_neg_blocks;   // then: blocks of the negatives' lookups, kNegPerWave events per wavefront
+    int n_row_blocks;   // then: blocks that fix row references (grid-stride over the rows)
+                        // then: blocks that fix slots, one entry per thread
 };
+
+constexpr int kNegPerWave = 2;
 
 // acc1 += A x W1[nt]^T over W1's k-blocks [kb_lo, kb_hi) and acc2 += A x W2[nt]^T over W2's
 // k-blocks [kb_lo, min(kb_hi, w2_kblocks)): both weight streams are loaded DEPTH blocks ahead and
@@ -85,17 +90,28 @@ __device__ inline void tile_gemm2(floatx4 &acc1, floatx4 &acc2, const char *A, i
 }
 
 template <int PREC>
-__global__ void __launch_bounds__(kGruThreads)
+__global__ void __launch_bounds__(kGruThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))  // 128 registers: two workgroups per unit
 k_gru(StepArgs a, PackedWeights w, GruParams g, int K)
 {
     TIG_MARK(0);
+    if (blockIdx.x == 0 && threadIdx.x == 0 && a.n_u_next)
+        *a.n_u_next = 0;  // the query set the next preparation fills; nothing reads it meanwhile
     if ((int)blockIdx.x >= g.n_gru) {  // finishing pass of the query preparation
-        const int x = (int)blockIdx.x - g.n_gru;
-        if (x == 0 && threadIdx.x == 0 && a.n_u_next)
-            *a.n_u_next = 0;  // the query set the next preparation fills; nothing reads it meanwhile
-        const int fw = x * kGruWaves + wave_id();
-        if (fw < g.n_finish)
-            finish_wave(a, K, fw);
+        int x = (int)blockIdx.x - g.n_gru;
+        if (x < g.n_neg_blocks) {
+            const int n_u = *a.qs.n_u;
+            const int b0 = (x * kGruWaves + wave_id()) * kNegPerWave;
+            for (int b = b0; b < b0 + kNegPerWave && b < a.count; ++b)
+                finish_negative(a, K, b, n_u);
+        } else if ((x -= g.n_neg_blocks) < g.n_row_blocks) {
+            const int n_u = *a.qs.n_u;
+            for (int row = x * kGruWaves + wave_id(); row < n_u; row += g.n_row_blocks * kGruWaves)
+                finish_row(ref_ctx(a), a.qs, K, row);
+        } else if (a.finish_here) {
+            const int i = (x - g.n_row_blocks) * kGruThreads + (int)threadIdx.x;
+            if (i < 2 * a.count)
+                finish_slots(a.qs, i);
+        }
         TIG_MARK(1);
         return;
     }
@@ -108,23 +124,34 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int K)
     double *row_t = (double *)(row_e + EC);    // [EC] event time
     char *X = smem + EC * 24;                  // [EC rows x ldx bytes]
     float *part = (float *)(smem + g.off_part);  // [2 halves][kPairs][2 streams][16 x 16]
+    double *tw_tab = (double *)(part + 2 * kPairs * 2 * 256);  // [T][2] time-encoding (w_rev, b_rev)
 
     const int lane = lane_id();
     const int wave = wave_id();
 
-    // the work: tiles x column slices, as many slices as keep the GRU workgroups busy
+    // the work: tiles x column slices.  The slice count comes with the launch, so the first item's
+    // descriptors are requested together with the winner count (slots beyond the count hold stale
+    // descriptors of earlier batches or nothing: they are only used below the count).
+    const int n_ct = g.Ng / 16;
+    const int cs = g.cs;
+    const int tpp = (n_ct + cs - 1) / cs;  // column tiles per item
+    WinDesc d_first;
+    {
+        const int r = ((int)blockIdx.x / cs) * EC + (int)threadIdx.x;
+        if (threadIdx.x < EC && r < 2 * a.msg_count)
+            d_first = a.win[r];
+    }
     const int n_win = *a.n_win;
     const int tiles = (n_win + EC - 1) / EC;
     if (tiles == 0)
         return;
-    const int n_ct = g.Ng / 16;
-    int cs = g.n_gru / tiles;
-    cs = cs < 1 ? 1 : (cs > n_ct ? n_ct : cs);
-    const int tpp = (n_ct + cs - 1) / cs;  // column tiles per item
-    cs = (n_ct + tpp - 1) / tpp;
     const int items = tiles * cs;
     const int kblocks = g.Kg / P::KB;
     const int kblocks_hn = g.Khn / P::KB;
+    for (int j = threadIdx.x; j < g.T; j += kGruThreads) {  // (visible after the first barrier below)
+        tw_tab[2 * j] = w.time_w_rev[j];
+        tw_tab[2 * j + 1] = w.time_b_rev[j];
+    }
 
     for (int item = (int)blockIdx.x; item < items; item += g.n_gru) {
         // 1. this item's slice of the compacted winner list
@@ -137,7 +164,7 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int K)
             int i = 0, u = 0, o = 0, b = 0;
             double t = 0.0;
             if (r < n_rows) {
-                const WinDesc d0 = a.win[r0 + r];
+                const WinDesc d0 = item == (int)blockIdx.x ? d_first : a.win[r0 + r];
                 i = d0.entry;
                 u = d0.node;
                 o = d0.other;
@@ -154,45 +181,50 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int K)
         TIG_MARK(1);
 
         // 2. message rows from batch-start memory; rows beyond n_rows are zero.  One wavefront per
-        //    row, lanes along the row (no index arithmetic per element); all loads of a row are
-        //    requested before its first element is converted and stored.
-        for (int r = wave; r < EC; r += kGruWaves) {
-            const bool live = r < n_rows;
-            const int u = row_u[r], o = row_o[r];
-            const float *self = a.mem + (size_t)u * g.M;
-            const float *other = a.mem + (size_t)o * g.M;
-            const float *feat = a.edge_feat + (size_t)(a.msg_first_eid + row_e[r]) * g.F;
-            const double lu = live ? a.lu[u] : 0.0;
-            constexpr int kAhead = 8;  // 512 elements of a message row per pass
+        //    row, lanes along the row (no index arithmetic per element); the loads of both rows of a
+        //    wavefront are requested before the first element is converted and stored.
+        {
+            constexpr int kRowsPerWave = EC / kGruWaves;
+            constexpr int kAhead = 6;  // 384 elements of a message row per pass
             for (int base = 0; base < g.Kg; base += kWave * kAhead) {
-                float v[kAhead];
-                double tw[kAhead], tb[kAhead];
+                float v[kRowsPerWave][kAhead];
+                double dt[kRowsPerWave];
 #pragma unroll
-                for (int k = 0; k < kAhead; ++k) {
-                    const int j = base + lane + kWave * k;
-                    v[k] = 0.0f;
-                    tw[k] = tb[k] = 0.0;
-                    if (live && j < g.Dmsg) {
-                        if (j < g.M)
-                            v[k] = self[j];
-                        else if (j < 2 * g.M)
-                            v[k] = other[j - g.M];
-                        else if (j < 2 * g.M + g.T) {
-                            tw[k] = w.time_w_rev[j - 2 * g.M];
-                            tb[k] = w.time_b_rev[j - 2 * g.M];
-                        } else
-                            v[k] = feat[j - 2 * g.M - g.T];
+                for (int i = 0; i < kRowsPerWave; ++i) {
+                    const int r = wave + i * kGruWaves;
+                    const bool live = r < n_rows;
+                    const int u = row_u[r], o = row_o[r];
+                    const float *self = a.mem + (size_t)u * g.M;
+                    const float *other = a.mem + (size_t)o * g.M;
+                    const float *feat = a.edge_feat + (size_t)(a.msg_first_eid + row_e[r]) * g.F;
+                    dt[i] = live ? row_t[r] - a.lu[u] : 0.0;  // since the node's last update
+#pragma unroll
+                    for (int k = 0; k < kAhead; ++k) {
+                        const int j = base + lane + kWave * k;
+                        v[i][k] = 0.0f;
+                        if (live && j < g.Dmsg) {
+                            if (j < g.M)
+                                v[i][k] = self[j];
+                            else if (j < 2 * g.M)
+                                v[i][k] = other[j - g.M];
+                            else if (j >= 2 * g.M + g.T)
+                                v[i][k] = feat[j - 2 * g.M - g.T];
+                        }
                     }
                 }
-                const double dt = row_t[r] - lu;  // since the node's last update
 #pragma unroll
-                for (int k = 0; k < kAhead; ++k) {
-                    const int j = base + lane + kWave * k;
-                    if (j < g.Kg) {
-                        float x = v[k];
-                        if (live && j >= 2 * g.M && j < 2 * g.M + g.T)
-                            x = time_enc(tw[k], tb[k], dt);
-                        P::store_a(X + (size_t)r * g.ldx, j, x);
+                for (int i = 0; i < kRowsPerWave; ++i) {
+                    const int r = wave + i * kGruWaves;
+                    const bool live = r < n_rows;
+#pragma unroll
+                    for (int k = 0; k < kAhead; ++k) {
+                        const int j = base + lane + kWave * k;
+                        if (j < g.Kg) {
+                            float x = v[i][k];
+                            if (live && j >= 2 * g.M && j < 2 * g.M + g.T)
+                                x = time_enc(tw_tab[2 * (j - 2 * g.M)], tw_tab[2 * (j - 2 * g.M) + 1], dt[i]);
+                            P::store_a(X + (size_t)r * g.ldx, j, x);
+                        }
                     }
                 }
             }
@@ -203,12 +235,21 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int K)
         // 3. + 4. gates.  A round covers up to kPairs column tiles; with fewer, the pairs also split k.
         for (int base = ct_lo; base < ct_hi; base += kPairs) {
             const int cts = ct_hi - base < kPairs ? ct_hi - base : kPairs;  // column tiles of this round
-            const int ksplit = cts == 1 ? 8 : (cts == 2 ? 4 : (cts <= 4 ? 2 : 1));
+            const int ksplit = cts == 1 ? 4 : (cts == 2 ? 2 : 1);
             const int pair = wave % kPairs;
             const int half = wave / kPairs;  // 0: r and z gates, 1: n gate
             const int ctl = pair / ksplit;   // column tile of the round
             const int ks = pair % ksplit;    // k slice
             const bool on = ctl < cts;
+            // gate biases of the element this thread finishes below, requested with the weights
+            float pb[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            if ((int)threadIdx.x < cts * 256) {
+                const int col = (base + ((int)threadIdx.x >> 8)) * 16 + ((int)threadIdx.x & 15);
+                pb[0] = w.gru_br[col];
+                pb[1] = w.gru_bz[col];
+                pb[2] = w.gru_bin[col];
+                pb[3] = w.gru_bhn[col];
+            }
             floatx4 acc1 = floatx4{0, 0, 0, 0}, acc2 = floatx4{0, 0, 0, 0};
             if (on) {
                 const int ct = base + ctl;
@@ -216,9 +257,9 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int K)
                 const int kb_lo = ks * per;
                 const int kb_hi = kblocks < kb_lo + per ? kblocks : kb_lo + per;
                 if (half == 0)
-                    tile_gemm2<PREC, 5>(acc1, acc2, X, g.ldx, w.gru_Wr, w.gru_Wz, kblocks, kblocks, kb_lo, kb_hi, ct);
+                    tile_gemm2<PREC, 3>(acc1, acc2, X, g.ldx, w.gru_Wr, w.gru_Wz, kblocks, kblocks, kb_lo, kb_hi, ct);
                 else  // input part over the whole message, hidden part over s_self (the first Khn k's)
-                    tile_gemm2<PREC, 5>(acc1, acc2, X, g.ldx, w.gru_Win, w.gru_Whn, kblocks, kblocks_hn, kb_lo,
+                    tile_gemm2<PREC, 3>(acc1, acc2, X, g.ldx, w.gru_Win, w.gru_Whn, kblocks, kblocks_hn, kb_lo,
                                         kb_hi, ct);
             }
             {
@@ -245,10 +286,13 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int K)
                         sin_ += q1[e];
                         shn += q1[256 + e];
                     }
-                    const float r = 1.0f / (1.0f + __expf(-(sr + w.gru_br[col])));
-                    const float z = 1.0f / (1.0f + __expf(-(sz + w.gru_bz[col])));
+                    const bool pre = idx < kGruThreads;  // the preloaded biases are this element's
+                    const float br = pre ? pb[0] : w.gru_br[col], bz = pre ? pb[1] : w.gru_bz[col];
+                    const float bin = pre ? pb[2] : w.gru_bin[col], bhn = pre ? pb[3] : w.gru_bhn[col];
+                    const float r = 1.0f / (1.0f + __expf(-(sr + br)));
+                    const float z = 1.0f / (1.0f + __expf(-(sz + bz)));
                     const float h = P::load_elem(X + (size_t)row * g.ldx, col);  // s_self
-                    const float x = sin_ + w.gru_bin[col] + r * (shn + w.gru_bhn[col]);
+                    const float x = sin_ + bin + r * (shn + bhn);
                     const float e2 = __expf(2.0f * x);          // tanh(x) = 1 - 2 / (e^{2x} + 1)
                     const float n = 1.0f - 2.0f / (e2 + 1.0f);
                     a.staging[(size_t)row_i[row] * g.M + col] = (1.0f - z) * n + z * h;
@@ -273,7 +317,9 @@ GruParams gru_params(const Dims &d)
     g.ldx = lds_row_bytes(d.Kg);
     g.off_part = (EC * 24 + EC * g.ldx + 15) / 16 * 16;
     g.n_gru = 0;
-    g.n_finish = 0;
+    g.cs = 1;
+    g.n_neg_blocks = 0;
+    g.n_row_blocks = 0;
     return g;
 }
 
@@ -286,7 +332,7 @@ const void *gru_kernel(const Dims &d)
 
 int gru_lds_bytes(const Dims &d)
 {
-    return gru_params(d).off_part + 2 * kPairs * 2 * 256 * 4;
+    return gru_params(d).off_part + 2 * kPairs * 2 * 256 * 4 + d.T * 16;
 }
 
 hipError_t prepare_gru(const Dims &d, const LaunchPlan &plan)
@@ -305,12 +351,34 @@ hipError_t launch_gru(const Dims &d, const LaunchPlan &plan, const PackedWeights
     const int cus = plan.num_cus > 0 ? plan.num_cus : 256;
     const int max_items = (2 * a.msg_count + EC - 1) / EC * (d.Ng / 16);
     g.n_gru = max_items < cus ? max_items : cus;
-    g.n_finish = a.roles * a.count;
+    {
+        // as many column slices per tile as keep the GRU workgroups busy at the winner count recent
+        // steps had (hub nodes make it a small share of the 2 * msg_count entries)
+        const int most = 2 * a.msg_count;
+        const int wins = a.wins_est > 0 && a.wins_est < most ? a.wins_est : most;
+        const int tiles = (wins + EC - 1) / EC > 0 ? (wins + EC - 1) / EC : 1;
+        const int n_ct = d.Ng / 16;
+        int cs = g.n_gru / tiles;
+        cs = cs < 1 ? 1 : (cs > n_ct ? n_ct : cs);
+        const int tpp = (n_ct + cs - 1) / cs;
+        g.cs = (n_ct + tpp - 1) / tpp;
+    }
+    g.n_neg_blocks = a.roles == 3 ? (a.count + kNegPerWave * kGruWaves - 1) / (kNegPerWave * kGruWaves) : 0;
+    g.n_row_blocks = 0;
+    int n_slot_blocks = 0;
+    if (a.finish_here) {
+        const int rows = 2 * a.count;  // at most; a wavefront takes several rows if there are many
+        g.n_row_blocks = (rows + kGruWaves - 1) / kGruWaves;
+        if (g.n_row_blocks > 2 * cus)
+            g.n_row_blocks = 2 * cus;
+        n_slot_blocks = (2 * a.count + kGruThreads - 1) / kGruThreads;
+    }
+    if (g.n_gru + g.n_neg_blocks + g.n_row_blocks + n_slot_blocks == 0)
+        n_slot_blocks = 1;  // nothing to apply, nothing to finish: block 0 still clears the next set's counter
     int K = d.K;
-    const int n_finish_blocks = (g.n_finish + kGruWaves - 1) / kGruWaves;
     void *args[] = {&aa, &ww, &g, &K};
-    return hipLaunchKernel(gru_kernel(d), dim3(g.n_gru + n_finish_blocks), dim3(kGruThreads), args,
-                           (size_t)gru_lds_bytes(d), s);
+    return hipLaunchKernel(gru_kernel(d), dim3(g.n_gru + g.n_neg_blocks + g.n_row_blocks + n_slot_blocks),
+                           dim3(kGruThreads), args, (size_t)gru_lds_bytes(d), s);
 }
 
 }  // namespace tig

@@ -7,8 +7,8 @@
 //                 a hash table of claims and looks up the K most recent neighbours of every
 //                 distinct pair.  It reads the event stream and the adjacency only, never the
 //                 model state, so it can run a step early, beside the previous embedding launch.
-//   finish_wave   what needs this step's inputs: the negatives' lookups (their ids arrive with the
-//                 call) and the row references (which rows this step's GRU replaces).
+//   finish_*      the rest: slots pointed at rows, the row references (which rows the step's GRU
+//                 replaces), and the negatives' lookups (their ids arrive with the call).
 // gfx950 only.
 #pragma once
 
@@ -118,6 +118,8 @@ __device__ inline void dedup_block(const StepArgs &a, const DedupJob &j, int K, 
     __syncthreads();
     const int base = s_base[0], n_rep = s_base[1];
     for (int l = wave; l < n_rep; l += kPrepWaves) {
+        if (base + l >= entries)
+            break;  // (a set holds a row per entry at most: only a counter that did not start at 0 gets here)
         const int e = i0 + list[l];
         int32_t u;
         double t;
@@ -130,54 +132,77 @@ __device__ inline void dedup_block(const StepArgs &a, const DedupJob &j, int K, 
     }
 }
 
-// Where the current state row of node v lives during this step: the staged GRU output of the
-// entry that won v's message in the applied batch, or v's memory row.  msg_key[v] holds the key of
+// Where the current state row of node v lives during a step: the staged GRU output of the entry
+// that won v's message in the batch the step applies, or v's memory row.  key[v] holds the key of
 // v's latest winning entry in the selections that used this key array; it belongs to the applied
 // batch iff its event id lies in that batch.
-__device__ inline int32_t resolve_ref(const StepArgs &a, int32_t v)
+struct RefCtx {
+    int64_t num_nodes;
+    const unsigned long long *key;  // key array of the applied batch's selection
+    int64_t first_eid;              // the applied batch
+    int32_t count;                  // 0: the step applies nothing
+};
+
+__device__ inline RefCtx ref_ctx(const StepArgs &a)
 {
-    if (v < 0 || (int64_t)v >= a.num_nodes)
+    return RefCtx{a.num_nodes, a.msg_key, a.msg_first_eid, a.msg_count};
+}
+
+__device__ inline int32_t resolve_ref(const RefCtx &c, int32_t v)
+{
+    if (v < 0 || (int64_t)v >= c.num_nodes)
         return kRefNone;
-    if (a.msg_count > 0) {
-        const unsigned long long k = a.msg_key[v];
+    if (c.count > 0) {
+        const unsigned long long k = c.key[v];
         const uint32_t low = (uint32_t)k;
         const int64_t e = (int64_t)(low >> 1);
-        if (k != 0ull && e >= a.msg_first_eid && e < a.msg_first_eid + a.msg_count)
-            return ~(int32_t)(2 * (e - a.msg_first_eid) + (low & 1u));
+        if (k != 0ull && e >= c.first_eid && e < c.first_eid + c.count)
+            return ~(int32_t)(2 * (e - c.first_eid) + (low & 1u));
     }
     return v;
 }
 
-// Wavefront w of the finishing pass (3B of them with negatives, else 2B):
-//   w < 2B       row w of the source / destination queries, if there is one: row references
-//   w = 2B + b   the negative of event b: lookup into row n_u + b, then its row references
-__device__ inline void finish_wave(const StepArgs &a, int K, int w)
+// The finishing pass of a batch's preparation, in three parts that share nothing:
+//   finish_slots      entry i of the batch: its slot is pointed straight at its row (one thread
+//                     per entry; representatives' slots never change)
+//   finish_row        row `row` of the source / destination queries: row references
+//   finish_negative   the negative of event b: lookup into row n_u + b, then its row references
+// The first two need the batch's queries and the applied batch's keys only, so for a batch that
+// was prepared ahead they run a step early as well (beside the previous step's decode); the
+// negatives arrive with the call.
+__device__ inline void finish_slots(const QuerySet &qs, int i)
+{
+    const int sl = qs.slot[i];
+    if (sl < 0)
+        qs.slot[i] = qs.slot[-sl - 1];
+}
+
+__device__ inline void finish_refs(const RefCtx &c, const QuerySet &qs, int K, int row, int32_t my_nbr, int32_t u)
 {
     const int lane = lane_id();
-    const int n_u = *a.qs.n_u;
-    int row;
-    int32_t my_nbr = -1;
-    if (w < 2 * a.count) {
-        row = w;
-        if (row >= n_u)
-            return;
-        if (lane < K)
-            my_nbr = a.qs.nbr[(size_t)row * K + lane];
-    } else {
-        const int b = w - 2 * a.count;
-        if (a.roles < 3 || b >= a.count)
-            return;
-        row = n_u + b;
-        nbr_lookup_wave(a, K, a.neg[b], a.ts[a.first_eid + b], -1, a.qs, row, my_nbr);
-    }
     if (lane < K)
-        a.qs.ref[(size_t)row * K + lane] = resolve_ref(a, my_nbr);
-    if (lane == kWave - 1) {
-        // (for a negative the node id was validated by the lookup; re-derive it instead of reading
-        // back what another lane of this wavefront has just written)
-        const int32_t u = w < 2 * a.count ? a.qs.node[row] : a.neg[w - 2 * a.count];
-        a.qs.self_ref[row] = resolve_ref(a, u);
-    }
+        qs.ref[(size_t)row * K + lane] = resolve_ref(c, my_nbr);
+    if (lane == kWave - 1)
+        qs.self_ref[row] = resolve_ref(c, u);
+}
+
+__device__ inline void finish_row(const RefCtx &c, const QuerySet &qs, int K, int row)
+{
+    const int lane = lane_id();
+    int32_t my_nbr = -1;
+    if (lane < K)
+        my_nbr = qs.nbr[(size_t)row * K + lane];
+    finish_refs(c, qs, K, row, my_nbr, qs.node[row]);
+}
+
+__device__ inline void finish_negative(const StepArgs &a, int K, int b, int n_u)
+{
+    int32_t my_nbr;
+    const int32_t u = a.neg[b];
+    nbr_lookup_wave(a, K, u, a.ts[a.first_eid + b], -1, a.qs, n_u + b, my_nbr);
+    // (the node id is validated by resolve_ref as the lookup did; it is not read back from the row,
+    // which another lane of this wavefront has just written)
+    finish_refs(ref_ctx(a), a.qs, K, n_u + b, my_nbr, u);
 }
 
 }  // namespace tig

@@ -112,6 +112,8 @@ struct DecodeParams {
     int n_event_blocks;   // blocks of 4 wavefronts, one event each
     int n_commit_blocks;  // one winner each
     int n_expand_blocks;  // one query each (inspection outputs), 0 if none is wanted
+    int n_fin_row_blocks; // row references of the batch prepared ahead, grid-stride over its rows
+    int n_fin_slot_blocks; // its slots, one entry per thread
 };
 
 __device__ inline int row_of_entry(const QuerySet &qs, int i)
@@ -135,22 +137,39 @@ __global__ void __launch_bounds__(256) k_decode(StepArgs a, PackedWeights w, Dec
         int row[3];
         row[0] = row_of_entry(a.qs, 2 * b);
         row[1] = row_of_entry(a.qs, 2 * b + 1);
-        row[2] = n_u + b;
-        const float *da = a.dec_a + (size_t)row[0] * p.Ep;
-        float part[2] = {0.0f, 0.0f};
-        for (int j = lane; j < p.E; j += kWave) {
-            const float x = da[j] + w.dec_b1f[j], w2 = w.dec_w2[j];
-#pragma unroll
-            for (int r = 1; r < 3; ++r)
-                if (r < a.roles)
-                    part[r - 1] += w2 * fmaxf(x + a.dec_b[(size_t)row[r] * p.Ep + j], 0.0f);
-        }
-#pragma unroll
-        for (int r = 0; r < 3; ++r)
-            if (r < a.roles)
-                for (int j = lane; j < p.E; j += kWave)
-                    a.emb[((size_t)r * a.count + b) * p.E + j] = a.emb_u[(size_t)row[r] * p.E + j];
+        row[2] = a.roles == 3 ? n_u + b : row[1];
         const float b2 = w.dec_b2[0];
+        // every load of a 128-dim chunk is requested before the first is used
+        float part[2] = {0.0f, 0.0f};
+        for (int j0 = 0; j0 < p.E; j0 += 2 * kWave) {
+            float da[2], db[2][2], em[3][2], b1[2], w2[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int j = j0 + lane + kWave * u;
+                const bool in = j < p.E;
+                da[u] = in ? a.dec_a[(size_t)row[0] * p.Ep + j] : 0.0f;
+                db[0][u] = in ? a.dec_b[(size_t)row[1] * p.Ep + j] : 0.0f;
+                db[1][u] = in ? a.dec_b[(size_t)row[2] * p.Ep + j] : 0.0f;
+                b1[u] = in ? w.dec_b1f[j] : 0.0f;
+                w2[u] = in ? w.dec_w2[j] : 0.0f;
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+                    em[r][u] = in ? a.emb_u[(size_t)row[r] * p.E + j] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int j = j0 + lane + kWave * u;
+                if (j < p.E) {
+                    const float x = da[u] + b1[u];
+                    part[0] += w2[u] * fmaxf(x + db[0][u], 0.0f);
+                    part[1] += w2[u] * fmaxf(x + db[1][u], 0.0f);
+#pragma unroll
+                    for (int r = 0; r < 3; ++r)
+                        if (r < a.roles)
+                            a.emb[((size_t)r * a.count + b) * p.E + j] = em[r][u];
+                }
+            }
+        }
         const float s_pos = wave_sum_uniform(part[0]) + b2;
         const float s_neg = wave_sum_uniform(part[1]) + b2;
         if (lane == 0) {
@@ -163,18 +182,35 @@ __global__ void __launch_bounds__(256) k_decode(StepArgs a, PackedWeights w, Dec
     blk -= p.n_event_blocks;
     if (blk < p.n_commit_blocks) {
         // Memory overwrite M <- s_i(t) for the winners of the applied batch (every reader of this
-        // step took the staged rows instead), and last_update.  One wavefront per winner.
-        const int r = blk * 4 + wave_id();
-        const WinDesc d = a.win[r];  // r < 2*msg_count + 32: in range; read together with the count
-        if (r >= *a.n_win)
-            return;
-        for (int j = lane; j < p.M; j += kWave)
-            a.mem[(size_t)d.node * p.M + j] = a.staging[(size_t)d.entry * p.M + j];
-        if (lane == 0)
-            a.lu[d.node] = d.t;
+        // step took the staged rows instead), and last_update.  One wavefront per winner at a time.
+        const int n_win = *a.n_win;
+        for (int r = blk * 4 + wave_id(); r < n_win; r += p.n_commit_blocks * 4) {
+            const WinDesc d = a.win[r];
+            for (int j = lane; j < p.M; j += kWave)
+                a.mem[(size_t)d.node * p.M + j] = a.staging[(size_t)d.entry * p.M + j];
+            if (lane == 0)
+                a.lu[d.node] = d.t;
+        }
         return;
     }
     blk -= p.n_commit_blocks;
+    if (blk >= p.n_expand_blocks) {
+        // Finishing pass for the batch that the embedding launch has just prepared (prepare.h): its
+        // row references against the batch the NEXT step will apply, and its slots.
+        blk -= p.n_expand_blocks;
+        const QuerySet &nq = a.ded.qs;
+        if (blk < p.n_fin_row_blocks) {
+            const RefCtx c{a.num_nodes, a.fin_msg_key, a.fin_msg_first_eid, a.fin_msg_count};
+            const int n_u = *nq.n_u;
+            for (int row = blk * 4 + wave_id(); row < n_u; row += p.n_fin_row_blocks * 4)
+                finish_row(c, nq, p.K, row);
+        } else {
+            const int i = (blk - p.n_fin_row_blocks) * 256 + (int)threadIdx.x;
+            if (i < 2 * a.fin_count)
+                finish_slots(nq, i);
+        }
+        return;
+    }
     // inspection outputs, per query in the order [sources | destinations | negatives]
     const int q = blk * 4 + wave_id();
     if (q >= a.roles * a.count)
@@ -256,11 +292,23 @@ hipError_t launch_decode(const Dims &d, const PackedWeights &pw, const StepArgs 
     p.Ep = d.Ep;
     p.K = d.K;
     p.n_event_blocks = (a.count + 3) / 4;
+    // the winners are usually a small share of the 2 * msg_count entries: a modest number of
+    // wavefronts, each taking winner after winner
     p.n_commit_blocks = a.msg_count > 0 ? (2 * a.msg_count + 3) / 4 : 0;
+    if (p.n_commit_blocks > 128)
+        p.n_commit_blocks = 128;
     const bool expand = a.out_nbr_node || a.out_nbr_eid || a.out_nbr_ts || a.out_nbr_cnt || a.out_is_winner;
     p.n_expand_blocks = expand ? (a.roles * a.count + 3) / 4 : 0;
-    hipLaunchKernelGGL(k_decode, dim3(p.n_event_blocks + p.n_commit_blocks + p.n_expand_blocks), dim3(256), 0, s,
-                       a, pw, p);
+    p.n_fin_row_blocks = p.n_fin_slot_blocks = 0;
+    if (a.fin_count > 0) {
+        p.n_fin_row_blocks = (2 * a.fin_count + 3) / 4;
+        if (p.n_fin_row_blocks > 256)
+            p.n_fin_row_blocks = 256;
+        p.n_fin_slot_blocks = (2 * a.fin_count + 255) / 256;
+    }
+    hipLaunchKernelGGL(k_decode, dim3(p.n_event_blocks + p.n_commit_blocks + p.n_expand_blocks + p.n_fin_row_blocks +
+                                      p.n_fin_slot_blocks),
+                       dim3(256), 0, s, a, pw, p);
     return hipGetLastError();
 }
 

@@ -68,6 +68,7 @@ struct tig_ctx {
     int64_t ahead_w_first;
     int32_t ahead_w_count;
     bool ahead_q_valid;  // set qcur ^ 1 holds the queries of batch (ahead_q_first, ahead_q_count)
+    bool ahead_q_finished;  // ... with final slots and row references (else the step finishes them)
     int64_t ahead_q_first;
     int32_t ahead_q_count;
     // deferred order: list wcur holds the winners of batch (pend_first, pend_count), not yet applied
@@ -79,6 +80,11 @@ struct tig_ctx {
     int64_t cursor;    // end of the last batch stepped since the last reset / import
     int last_launches; // kernels enqueued by the last tig_step
     void *static_scratch;  // this device's copy of g_static_scratch
+    // Two pinned host words that the device can write: every step leaves its numbers of distinct
+    // query rows and of winners there, and later calls shape their launches by them (hints that
+    // may be a few steps old; results do not depend on them).  NULL if the allocation failed.
+    int32_t *rows_seen_host;
+    int32_t *rows_seen_dev;
     hipEvent_t marks[kNumStepKernels + 1];
     bool have_marks;
     char err[256];
@@ -449,6 +455,16 @@ int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *w
     INIT_TRY(launch_fill_zero(ctx->S.tab, sizeof(unsigned long long) * (size_t)ctx->S.tab_slots, s), "clear claim table");
     INIT_TRY(hipStreamSynchronize(s), "sync");
 #undef INIT_TRY
+    if (hipHostMalloc((void **)&ctx->rows_seen_host, 64, hipHostMallocMapped) == hipSuccess) {
+        ctx->rows_seen_host[0] = ctx->rows_seen_host[1] = 0;
+        if (hipHostGetDevicePointer((void **)&ctx->rows_seen_dev, ctx->rows_seen_host, 0) != hipSuccess) {
+            (void)hipHostFree(ctx->rows_seen_host);
+            ctx->rows_seen_host = ctx->rows_seen_dev = nullptr;
+        }
+    } else {
+        (void)hipGetLastError();
+        ctx->rows_seen_host = ctx->rows_seen_dev = nullptr;
+    }
     *out = ctx;
     return TIG_OK;
 }
@@ -527,6 +543,14 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     a.out_nbr_ts = out->nbr_ts;
     a.out_nbr_cnt = out->nbr_cnt;
     a.out_is_winner = out->is_winner;
+    a.rows_seen = ctx->rows_seen_dev;
+    if (ctx->rows_seen_host) {
+        // distinct rows of a recent step, with a margin of one eighth
+        const int32_t seen = ((volatile int32_t *)ctx->rows_seen_host)[0];
+        const int32_t wins = ((volatile int32_t *)ctx->rows_seen_host)[1];
+        a.rows_est = seen > 0 ? seen + seen / 8 : 0;
+        a.wins_est = wins > 0 ? wins + wins / 8 : 0;
+    }
 
     // What the embedding launch can do on the side for a later step (never for a static call).
     const bool one_wg = winners_in_one_launch(count);
@@ -554,6 +578,7 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
                          ctx->ahead_q_count == count;
     const int qi = use_static ? 0 : (q_ready ? ctx->qcur ^ 1 : ctx->qcur);
     a.qs = st.qs[qi];
+    a.finish_here = !(q_ready && ctx->ahead_q_finished);
     if (!q_ready) {
         ded_now = make_dedup(st, st.qs[qi], first, count, next_epoch(), one_wg);
         sp.prep_ded = &ded_now;
@@ -613,6 +638,13 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
             if (!d.deferred)
                 a.sel = SelectJob{next_first, guess, st.win[wi ^ 1], st.n_win[wi ^ 1], st.flags[wi ^ 1],
                                   ctx->key[wi ^ 1]};
+            // The decode launch finishes that preparation: row references against the batch the NEXT
+            // step applies -- the guessed batch itself, or in the deferred order this step's batch
+            // (selected into the other list by now, by the embedding launch or up front).
+            a.fin_count = guess;
+            a.fin_msg_first_eid = d.deferred ? first : next_first;
+            a.fin_msg_count = d.deferred ? count : guess;
+            a.fin_msg_key = ctx->key[wi ^ 1];
         }
     }
     if (clear_tab && !sp.prep_ded && a.ded.count > 0) {
@@ -640,6 +672,7 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     ctx->epoch = epoch;
     ctx->qcur = qi;
     ctx->ahead_q_valid = a.ded.count > 0;
+    ctx->ahead_q_finished = a.fin_count > 0;
     ctx->ahead_q_first = a.ded.first_eid;
     ctx->ahead_q_count = a.ded.count;
     if (d.deferred) {
@@ -703,6 +736,8 @@ static hipError_t drop_pending(tig_ctx *ctx)
     hipError_t e = launch_fill_zero(ctx->key[0], sizeof(unsigned long long) * (size_t)ctx->num_nodes, ctx->stream);
     if (e == hipSuccess)
         e = launch_fill_zero(ctx->key[1], sizeof(unsigned long long) * (size_t)ctx->num_nodes, ctx->stream);
+    if (ctx->d.deferred && ctx->pend_valid)
+        ctx->ahead_q_finished = false;  // its row references point at the pending batch's staged rows
     ctx->pend_valid = false;
     ctx->ahead_w_valid = false;
     return e;
@@ -769,6 +804,8 @@ void tig_destroy(tig_ctx *ctx)
     if (ctx->have_marks)
         for (int i = 0; i <= kNumStepKernels; ++i)
             (void)hipEventDestroy(ctx->marks[i]);
+    if (ctx->rows_seen_host)
+        (void)hipHostFree(ctx->rows_seen_host);
     delete ctx;
 }
 

@@ -148,7 +148,18 @@ struct StepArgs {
     float *emb_u;    // [R x E] embedding of every distinct query
     float *dec_a;    // [R x Ep] first decoder layer, source half, of every distinct query
     float *dec_b;    // [R x Ep] the same, second-operand half
+    // finishing pass of the preparation (prepare.h): in the GRU launch for this batch if its slots /
+    // row references are not final yet, and beside the decode for the batch prepared ahead (whose
+    // applied batch is (fin_first_eid, fin_count) with key array fin_key)
+    int32_t finish_here;        // 1: the GRU launch also fixes this batch's slots and row references
+    int32_t fin_count;          // 0: the decode launch finishes nothing
+    int64_t fin_msg_first_eid;
+    int32_t fin_msg_count;
+    const unsigned long long *fin_msg_key;
     int32_t *n_u_next;  // counter of the query set the next preparation will fill (cleared here), may be NULL
+    int32_t *rows_seen; // host memory mapped into the device: the step leaves its numbers of distinct rows [0] and of winners [1] here, may be NULL
+    int32_t rows_est;   // host side only: expected number of distinct rows (sizes the embedding tiles)
+    int32_t wins_est;   // host side only: expected number of winners (sizes the GRU column slices)
     // work done on compute units the embedding launch leaves idle: selection of a batch's winners
     // and preparation of a batch's queries
     SelectJob sel;
