@@ -190,8 +190,12 @@ TIG_API int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_we
  * clipped at the end of the stream): its step-2 winners and the neighbour lists of its distinct
  * source / destination queries.  That preparation reads the event stream and the adjacency only,
  * never the model state; the next call uses it if its batch is exactly that one, and otherwise
- * prepares its batch itself in one more launch.  Results do not depend on whether the guess was
- * right, and tig_reset / tig_state_import in between are fine.
+ * prepares its batch itself in one more launch.  The step's last launch (scores, embedding rows)
+ * also computes, into staging rows, the GRU output of the batch the next call would apply, from
+ * the memory as this step leaves it; the next call takes those rows if its batch is that one and
+ * the state has not been replaced since, else it runs the GRU itself.  A step of a chronological
+ * pass is therefore two launches.  Results do not depend on whether the guess was right, and
+ * tig_reset / tig_state_import in between are fine.
  */
 TIG_API int tig_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *out);
 
@@ -201,9 +205,11 @@ TIG_API int tig_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *out);
  * milliseconds to kernel_ms[0..TIG_NUM_STEP_KERNELS-1] (host), in launch order:
  *   0, 1  key scatter and winner selection of a batch above 4096 events (else ~0)
  *   2     preparation of a batch that the previous step did not prepare (else ~0)
- *   3     message + GRU, with the negatives' neighbour lookups and the row references
- *   4     attention embedding, merge MLP, first decoder layer (and the next batch's preparation)
- *   5     scores, per-query embedding rows, memory overwrite
+ *   3     message + GRU and what is left of the query preparation, for a step whose applied batch
+ *         the previous step's last launch did not cover (else ~0)
+ *   4     attention embedding (with the negatives' neighbour lookups), merge MLP, first decoder
+ *         layer, memory overwrite (and the next batch's preparation)
+ *   5     scores, per-query embedding rows (and message + GRU of the batch the next step applies)
  * For measurement: the event records add gaps between kernels, so time throughput with tig_step.
  */
 #define TIG_NUM_STEP_KERNELS 6
@@ -251,7 +257,7 @@ TIG_API void tig_destroy(tig_ctx *ctx);
 TIG_API const char *tig_strerror(int status);
 TIG_API const char *tig_last_error(const tig_ctx *ctx);
 
-/* For reports: the number of kernels the last step enqueued (3 when the previous step had
+/* For reports: the number of kernels the last step enqueued (2 when the previous step had
  * prepared this batch, 4 otherwise, 6 for batches above 4096 events; 0 before the first step) and
  * the dynamic LDS bytes of the two tile kernels at their largest tile count.
  * Any pointer may be NULL. */

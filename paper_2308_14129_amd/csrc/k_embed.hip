@@ -13,14 +13,19 @@
 //      W_d1[:, :E] emb and W_d1[:, E:] emb (merge layer 2 folded into the decoder weights)
 //      -> per-row arrays in global memory; the decode kernel pairs them up per event
 // State rows are read through row references: the memory table, or the staged GRU output for a
-// node this step updates (the memory overwrite runs after this kernel, beside the decode).
+// node this step updates -- so the memory overwrite M <- s_i(t) itself runs in a few extra
+// workgroups of this launch.
+// The negatives of the batch arrive with the call; the wavefront that takes a negative's row in
+// phase C looks up its neighbours first (a chain of dependent reads that hides behind the other
+// wavefronts' rows).
 // The projections W_Q, W_K, W_V, W_O and the first merge layer are folded into A1 and P at init
 // (pack.hip), which removes the per-neighbour key/value projections.
 // The number of rows is known on the device only: the grid has a tile for every 16*MT rows the
 // batch could have, and the tiles beyond the actual row count return at once.  Row r of tile p is
 // query row p + (number of tiles in use) * r, which spreads the heavy rows (sources /
-// destinations, first in the set) over all tiles.  Workgroups beyond the tiles prepare the batch expected next:
-// one selects its last-message winners, the others merge and look up its queries.
+// destinations, first in the set) over all tiles.  Workgroups beyond the tiles and the memory
+// overwrite prepare the batch expected next: one selects its last-message winners, the others
+// merge and look up its queries.
 #include <type_traits>
 #include <hip/hip_runtime.h>
 
@@ -54,7 +59,8 @@ struct EmbedParams {
     int row_bytes;  // LDS bytes per query row of the main buffer: [q~ / kvbar (N1) | s_u (Mq)]
     int ld1;        // row stride of the E-wide buffers, bytes
     int off_h1, off_meta;  // byte offsets in LDS
-    int n_tiles;    // workgroups that take row tiles; the ones beyond prepare the next batch
+    int n_tiles;    // workgroups that take row tiles
+    int n_commit;   // then: workgroups of the memory overwrite; the ones beyond prepare the next batch
     // bit n set: register n of a key/value row (dims 64 n .. 64 n + 63 of [Phi | s_v | e]) holds
     // at least one dim of the time encoding / of the neighbour's memory / of the edge feature
     int phi_regs, mem_regs, feat_regs;
@@ -115,15 +121,20 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     constexpr int NPHI = NPL;  // registers that may hold time-encoding dims (T <= 64 * NPL)
     extern __shared__ __attribute__((aligned(16))) char smem[];
     if ((int)blockIdx.x >= p.n_tiles) {
-        // The workgroups beyond the tiles, on compute units this launch leaves idle (launched only
-        // with 1024 threads): last-message selection and query preparation for a later step.
+        int x = (int)blockIdx.x - p.n_tiles;
+        if (x < p.n_commit) {
+            overwrite_memory(a, p.M, x * kEmbedWaves + wave_id(), p.n_commit * kEmbedWaves);
+            return;
+        }
+        x -= p.n_commit;
+        // The workgroups beyond, on compute units this launch leaves idle (launched only with
+        // 1024 threads): last-message selection and query preparation for a later step.
         if constexpr (kEmbedThreads == kScatterThreads) {
             TIG_MARK(0);
-            int x = (int)blockIdx.x - p.n_tiles;
             if (x == 0 && threadIdx.x == 0 && a.rows_seen) {
                 // hints for the host (stores to its memory take a while: from a workgroup that ends
                 // long before the launch does)
-                a.rows_seen[0] = *a.qs.n_u + (a.roles == 3 ? a.count : 0);
+                a.rows_seen[0] = *a.qs.n_u + (a.roles == 3 ? a.count : 0);  // (a hint: not clamped)
                 if (a.msg_count > 0)
                     a.rows_seen[1] = *a.n_win;
             }
@@ -153,8 +164,16 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     const int lane = lane_id();
     const int wave = wave_id();
     const int mem_off = 4 * p.N1;
-    const int n_rows = *a.qs.n_u + (a.roles == 3 ? a.count : 0);
+    int n_u = *a.qs.n_u;  // distinct source / destination queries; the negatives' rows follow at 2 * count
+    n_u = n_u < 2 * a.count ? n_u : 2 * a.count;
+    const int neg_row0 = 2 * a.count;
+    const int n_rows = n_u + (a.roles == 3 ? a.count : 0);
     const int n_passes = (n_rows + ROWS - 1) / ROWS;
+    // a row reference that is neither a memory row nor a staged row of the applied batch reads as none
+    auto checked_ref = [&](int32_t ref) -> int32_t {
+        const bool ok = ref >= 0 ? (int64_t)ref < a.num_nodes : (ref != kRefNone && ~ref < 2 * a.msg_count);
+        return ok ? ref : kRefNone;
+    };
 
     const int pass = (int)blockIdx.x;
     if (pass >= n_passes)
@@ -163,12 +182,26 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     // ---- A. query rows ------------------------------------------------------------------------
     if (threadIdx.x < ROWS) {
         const int r = threadIdx.x;
-        const int q = pass + n_passes * r;
-        const bool act = q < n_rows;
-        row_q[r] = act ? q : -1;
-        row_ref[r] = act ? a.qs.self_ref[q] : kRefNone;
-        row_cnt[r] = act ? a.qs.cnt[q] : 0;
-        row_t[r] = act ? a.qs.t[q] : 0.0;
+        const int x = pass + n_passes * r;
+        int q = -1, cnt = 0;
+        int32_t ref = kRefNone;
+        double t = 0.0;
+        if (x < n_u) {
+            q = x;
+            ref = a.qs.self_ref[q];
+            cnt = a.qs.cnt[q];
+            t = a.qs.t[q];
+        } else if (x < n_rows) {
+            // a negative: node and time from the call; its neighbours are looked up in phase C
+            const int b = x - n_u;
+            q = neg_row0 + b;
+            ref = resolve_ref(ref_ctx(a), a.neg[b]);
+            t = a.ts[a.first_eid + b];
+        }
+        row_q[r] = q;
+        row_ref[r] = checked_ref(ref);
+        row_cnt[r] = cnt < p.K ? cnt : p.K;
+        row_t[r] = t;
     }
     if (threadIdx.x == 0)
         *next_row = 0;
@@ -230,12 +263,18 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
         dt = 0.0;
         if (r < ROWS) {
             const int q = row_q[r];
-            if (q >= 0 && lane < row_cnt[r]) {
+            if (q >= 0 && q < neg_row0 && lane < row_cnt[r]) {
                 v = a.qs.ref[(size_t)q * p.K + lane];  // row reference of the neighbour's state
                 e = a.qs.eid[(size_t)q * p.K + lane];
                 dt = row_t[r] - a.qs.ts[(size_t)q * p.K + lane];
             }
         }
+    };
+    // what a gather can safely be pointed at: a valid row reference and event id (anything else, which
+    // only a corrupted table could hold, reads row 0)
+    auto safe_slot = [&](int32_t &v, int32_t &e) {
+        v = checked_ref(v) == kRefNone ? 0 : v;
+        e = e >= 0 ? e : 0;
     };
     int r = grab();
     int32_t nb_v2, nb_e2;
@@ -310,8 +349,8 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
         double nb_dt1;
 #pragma unroll 1
         while (r < ROWS) {
-            const int32_t nb_vc = nb_v2, nb_ec = nb_e2;
-            const double nb_dtc = nb_dt2;
+            int32_t nb_vc = nb_v2, nb_ec = nb_e2;
+            double nb_dtc = nb_dt2;
             const int r_next = grab();
             load_nb(r_next, nb_v1, nb_e1, nb_dt1);
             const int r_cur = r;
@@ -319,9 +358,22 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
             nb_v2 = nb_v1;
             nb_e2 = nb_e1;
             nb_dt2 = nb_dt1;
-            if (__builtin_amdgcn_readfirstlane(row_q[r_cur]) < 0)
+            const int q_cur = __builtin_amdgcn_readfirstlane(row_q[r_cur]);
+            if (q_cur < 0)
                 continue;
-            const int cnt = __builtin_amdgcn_readfirstlane(row_cnt[r_cur]);
+            int cnt;
+            if (q_cur >= neg_row0) {
+                // a negative: its neighbours are looked up now (slot k lands in lane k)
+                double ts_k;
+                cnt = finish_negative(a, p.K, q_cur - neg_row0, nb_vc, nb_ec, ts_k);
+                cnt = __builtin_amdgcn_readfirstlane(cnt);
+                nb_dtc = row_t[r_cur] - ts_k;
+                if (lane == 0)
+                    row_cnt[r_cur] = cnt;  // phase D picks the bias by it
+            } else {
+                cnt = __builtin_amdgcn_readfirstlane(row_cnt[r_cur]);
+            }
+            safe_slot(nb_vc, nb_ec);
             const float *qrow = (const float *)(rowbuf + (size_t)r_cur * p.row_bytes);
             char *arow = rowbuf + (size_t)r_cur * p.row_bytes;
             float qv[H][NPL], accv[H][NPL];
@@ -704,6 +756,7 @@ EmbedParams embed_params(const Dims &d, int mt)
     p.off_h1 = (rows * p.row_bytes + 15) / 16 * 16;
     p.off_meta = p.off_h1 + rows * p.ld1;
     p.n_tiles = 0;
+    p.n_commit = 0;
     p.phi_regs = p.mem_regs = p.feat_regs = 0;
     for (int n = 0; n * kWave < d.dkvp; ++n) {
         const int lo = n * kWave, hi = lo + kWave;
@@ -859,7 +912,17 @@ hipError_t launch_embed(const Dims &d, const LaunchPlan &plan, const PackedWeigh
 {
     StepArgs aa = a;
     PackedWeights ww = pw;
-    const int extra = (a.sel.count > 0 ? 1 : 0) + (a.ded.count > 0 ? a.ded.n_wgs : 0);
+    const int threads = embed_threads(d);
+    // memory overwrite: about four winners per wavefront at the winner count recent steps had
+    int n_commit = 0;
+    if (a.msg_count > 0) {
+        const int most = 2 * a.msg_count;
+        const int wins = a.wins_est > 0 && a.wins_est < most ? a.wins_est : most;
+        const int per_block = 4 * (threads / kWave);
+        n_commit = (wins + per_block - 1) / per_block;
+        n_commit = n_commit < 1 ? 1 : (n_commit > 16 ? 16 : n_commit);
+    }
+    const int extra = n_commit + (a.sel.count > 0 ? 1 : 0) + (a.ded.count > 0 ? a.ded.n_wgs : 0);
     const int cus = plan.num_cus > 0 ? plan.num_cus : 256;
     const int units = cus - extra > 16 ? cus - extra : 16;
     // The tile height follows the number of distinct rows recent steps had (any height is correct:
@@ -869,8 +932,8 @@ hipError_t launch_embed(const Dims &d, const LaunchPlan &plan, const PackedWeigh
     const int mt = embed_tiles(plan, rows, units);
     EmbedParams p = embed_params(d, mt);
     p.n_tiles = (a.roles * a.count + 16 * mt - 1) / (16 * mt);  // tiles in use if no query repeats
+    p.n_commit = n_commit;
     void *args[] = {&aa, &ww, &p};
-    const int threads = embed_threads(d);
     const int own = embed_lds_bytes(d, mt);
     const int lds = a.sel.count > 0 && own < kOneLds ? kOneLds : (own < kPrepLds ? kPrepLds : own);
     return hipLaunchKernel(embed_kernel(d, mt), dim3(p.n_tiles + extra), dim3(threads), args, (size_t)lds, s);

@@ -1,8 +1,13 @@
 // k_gru: message build and GRU state update (message module, state-update module and memory
 // fetch of the paper's Sec. II-C) for the compacted winners of one batch.  gfx950 only.
-// The same launch carries, in extra workgroups, what is left of the query preparation
-// (prepare.h): the lookups of the negatives and the row references.  They depend on nothing the
-// GRU produces, and both are chains of dependent memory round trips, so they hide each other.
+// The same grid carries, in extra workgroups, work that depends on nothing the GRU produces:
+//   - ahead of the embedding launch (a step whose batch was not prepared by the step before):
+//     what is left of the query preparation (prepare.h), slots and row references;
+//   - as the closing launch of a step (decode.h): the decoder scores and embedding rows of the
+//     step's events and the finishing pass of the batch prepared for the next step -- and then
+//     the GRU workgroups run for the batch the NEXT step applies (its winners were selected
+//     beside the embedding launch), so that step starts with its embedding launch.
+// All of these are chains of dependent memory round trips, so they hide each other.
 //
 // The number of winners is only known on the device (hub nodes make it a small fraction of the
 // 2B entries), so the GRU workgroups are a fixed grid that divides the work itself: 16-row tiles
@@ -16,10 +21,11 @@
 //      a pair for the r and z gates, the other for the two halves of the n gate (input part over
 //      the whole message, hidden part over s_self); the pairs split the item's column tiles and,
 //      when there are fewer column tiles than pairs, the k range of each; partial sums meet in LDS
-//   4  h' = (1 - z) n + z h  -> staging rows (memory is overwritten after the embedding)
+//   4  h' = (1 - z) n + z h  -> staging rows (memory is overwritten beside the embedding)
 // W_hr and W_hz are folded onto the s_self columns of W_ir / W_iz at init (pack.hip).
 #include <hip/hip_runtime.h>
 
+#include "decode.h"
 #include "kernels_common.h"
 #include "prepare.h"
 
@@ -47,12 +53,19 @@ struct GruParams {
     int off_part;  // byte offset of the partial-sum buffer in LDS
     int n_gru;     // GRU workgroups (the first blocks of the grid)
     int cs;        // column slices per tile (any value from 1 to the number of column tiles is correct)
-    int n_neg_blocks;   // then: blocks of the negatives' lookups, kNegPerWave events per wavefront
-    int n_row_blocks;   // then: blocks that fix row references (grid-stride over the rows)
-                        // then: blocks that fix slots, one entry per thread
+    int n_row_blocks;   // then: blocks that fix row references of this step's queries (grid-stride over the rows)
+    int n_slot_blocks;  // then: blocks that fix their slots, one entry per thread
+                        // then: the blocks of the closing work (decode.h)
+    int32_t *clear;     // a counter block 0 sets to 0, or NULL
 };
 
-constexpr int kNegPerWave = 2;
+// The batch whose winners the GRU workgroups apply.
+struct GruJob {
+    int64_t first_eid;
+    int32_t count;      // 0: nothing to apply
+    const WinDesc *win;
+    const int32_t *n_win;
+};
 
 // acc1 += A x W1[nt]^T over W1's k-blocks [kb_lo, kb_hi) and acc2 += A x W2[nt]^T over W2's
 // k-blocks [kb_lo, min(kb_hi, w2_kblocks)): both weight streams are loaded DEPTH blocks ahead and
@@ -91,26 +104,24 @@ __device__ inline void tile_gemm2(floatx4 &acc1, floatx4 &acc2, const char *A, i
 
 template <int PREC>
 __global__ void __launch_bounds__(kGruThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))  // 128 registers: two workgroups per unit
-k_gru(StepArgs a, PackedWeights w, GruParams g, int K)
+k_gru(StepArgs a, GruJob gj, PackedWeights w, GruParams g, DecodeParams dp)
 {
     TIG_MARK(0);
-    if (blockIdx.x == 0 && threadIdx.x == 0 && a.n_u_next)
-        *a.n_u_next = 0;  // the query set the next preparation fills; nothing reads it meanwhile
-    if ((int)blockIdx.x >= g.n_gru) {  // finishing pass of the query preparation
+    if (blockIdx.x == 0 && threadIdx.x == 0 && g.clear)
+        *g.clear = 0;
+    if ((int)blockIdx.x >= g.n_gru) {
         int x = (int)blockIdx.x - g.n_gru;
-        if (x < g.n_neg_blocks) {
-            const int n_u = *a.qs.n_u;
-            const int b0 = (x * kGruWaves + wave_id()) * kNegPerWave;
-            for (int b = b0; b < b0 + kNegPerWave && b < a.count; ++b)
-                finish_negative(a, K, b, n_u);
-        } else if ((x -= g.n_neg_blocks) < g.n_row_blocks) {
-            const int n_u = *a.qs.n_u;
+        if (x < g.n_row_blocks) {  // finishing pass of this step's query preparation
+            int n_u = *a.qs.n_u;
+            n_u = n_u < 2 * a.count ? n_u : 2 * a.count;
             for (int row = x * kGruWaves + wave_id(); row < n_u; row += g.n_row_blocks * kGruWaves)
-                finish_row(ref_ctx(a), a.qs, K, row);
-        } else if (a.finish_here) {
-            const int i = (x - g.n_row_blocks) * kGruThreads + (int)threadIdx.x;
+                finish_row(ref_ctx(a), a.qs, dp.K, row);
+        } else if ((x -= g.n_row_blocks) < g.n_slot_blocks) {
+            const int i = x * kGruThreads + (int)threadIdx.x;
             if (i < 2 * a.count)
-                finish_slots(a.qs, i);
+                finish_slots(a.qs, i, 2 * a.count);
+        } else {
+            closing_block(a, w, dp, x - g.n_slot_blocks, kGruWaves);
         }
         TIG_MARK(1);
         return;
@@ -138,10 +149,11 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int K)
     WinDesc d_first;
     {
         const int r = ((int)blockIdx.x / cs) * EC + (int)threadIdx.x;
-        if (threadIdx.x < EC && r < 2 * a.msg_count)
-            d_first = a.win[r];
+        if (threadIdx.x < EC && r < 2 * gj.count)
+            d_first = gj.win[r];
     }
-    const int n_win = *a.n_win;
+    int n_win = *gj.n_win;
+    n_win = n_win < 2 * gj.count ? n_win : 2 * gj.count;  // (a list never holds more than the batch's entries)
     const int tiles = (n_win + EC - 1) / EC;
     if (tiles == 0)
         return;
@@ -164,7 +176,7 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int K)
             int i = 0, u = 0, o = 0, b = 0;
             double t = 0.0;
             if (r < n_rows) {
-                const WinDesc d0 = item == (int)blockIdx.x ? d_first : a.win[r0 + r];
+                const WinDesc d0 = item == (int)blockIdx.x ? d_first : gj.win[r0 + r];
                 i = d0.entry;
                 u = d0.node;
                 o = d0.other;
@@ -196,7 +208,7 @@ k_gru(StepArgs a, PackedWeights w, GruParams g, int K)
                     const int u = row_u[r], o = row_o[r];
                     const float *self = a.mem + (size_t)u * g.M;
                     const float *other = a.mem + (size_t)o * g.M;
-                    const float *feat = a.edge_feat + (size_t)(a.msg_first_eid + row_e[r]) * g.F;
+                    const float *feat = a.edge_feat + (size_t)(gj.first_eid + row_e[r]) * g.F;
                     dt[i] = live ? row_t[r] - a.lu[u] : 0.0;  // since the node's last update
 #pragma unroll
                     for (int k = 0; k < kAhead; ++k) {
@@ -318,14 +330,46 @@ GruParams gru_params(const Dims &d)
     g.off_part = (EC * 24 + EC * g.ldx + 15) / 16 * 16;
     g.n_gru = 0;
     g.cs = 1;
-    g.n_neg_blocks = 0;
     g.n_row_blocks = 0;
+    g.n_slot_blocks = 0;
+    g.clear = nullptr;
     return g;
 }
 
 const void *gru_kernel(const Dims &d)
 {
     return d.prec == TIG_BF16_MFMA ? (const void *)k_gru<TIG_BF16_MFMA> : (const void *)k_gru<TIG_FP32>;
+}
+
+// GRU workgroups and column slices for a batch of `count` events with about `wins_est` winners.
+void size_gru(const Dims &d, const LaunchPlan &plan, int count, int wins_est, GruParams *g)
+{
+    // one workgroup per compute unit, but no more than the work of the largest possible winner
+    // count (every entry a winner, every column tile its own item); none if nothing is applied
+    const int cus = plan.num_cus > 0 ? plan.num_cus : 256;
+    const int max_items = (2 * count + EC - 1) / EC * (d.Ng / 16);
+    g->n_gru = max_items < cus ? max_items : cus;
+    // as many column slices per tile as keep the GRU workgroups busy at the winner count recent
+    // steps had (hub nodes make it a small share of the 2 * count entries)
+    const int most = 2 * count;
+    const int wins = wins_est > 0 && wins_est < most ? wins_est : most;
+    const int tiles = (wins + EC - 1) / EC > 0 ? (wins + EC - 1) / EC : 1;
+    const int n_ct = d.Ng / 16;
+    int cs = g->n_gru / tiles;
+    cs = cs < 1 ? 1 : (cs > n_ct ? n_ct : cs);
+    const int tpp = (n_ct + cs - 1) / cs;
+    g->cs = (n_ct + tpp - 1) / tpp;
+}
+
+DecodeParams no_closing(const Dims &d)
+{
+    DecodeParams p;
+    p.M = d.M;
+    p.E = d.E;
+    p.Ep = d.Ep;
+    p.K = d.K;
+    p.n_event_blocks = p.n_expand_blocks = p.n_fin_row_blocks = p.n_fin_slot_blocks = 0;
+    return p;
 }
 
 }  // namespace
@@ -340,45 +384,58 @@ hipError_t prepare_gru(const Dims &d, const LaunchPlan &plan)
     return hipFuncSetAttribute(gru_kernel(d), hipFuncAttributeMaxDynamicSharedMemorySize, gru_lds_bytes(d));
 }
 
+// Ahead of the embedding launch: the GRU of the batch this step applies and, if asked for, the
+// finishing pass of this step's queries.
 hipError_t launch_gru(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
                       hipStream_t s)
 {
     StepArgs aa = a;
     PackedWeights ww = pw;
     GruParams g = gru_params(d);
-    // GRU workgroups: one per compute unit, but no more than the work of the largest possible
-    // winner count (every entry a winner, every column tile its own item); none if nothing is applied
-    const int cus = plan.num_cus > 0 ? plan.num_cus : 256;
-    const int max_items = (2 * a.msg_count + EC - 1) / EC * (d.Ng / 16);
-    g.n_gru = max_items < cus ? max_items : cus;
-    {
-        // as many column slices per tile as keep the GRU workgroups busy at the winner count recent
-        // steps had (hub nodes make it a small share of the 2 * msg_count entries)
-        const int most = 2 * a.msg_count;
-        const int wins = a.wins_est > 0 && a.wins_est < most ? a.wins_est : most;
-        const int tiles = (wins + EC - 1) / EC > 0 ? (wins + EC - 1) / EC : 1;
-        const int n_ct = d.Ng / 16;
-        int cs = g.n_gru / tiles;
-        cs = cs < 1 ? 1 : (cs > n_ct ? n_ct : cs);
-        const int tpp = (n_ct + cs - 1) / cs;
-        g.cs = (n_ct + tpp - 1) / tpp;
-    }
-    g.n_neg_blocks = a.roles == 3 ? (a.count + kNegPerWave * kGruWaves - 1) / (kNegPerWave * kGruWaves) : 0;
-    g.n_row_blocks = 0;
-    int n_slot_blocks = 0;
+    GruJob gj = {a.msg_first_eid, a.msg_count, a.win, a.n_win};
+    DecodeParams dp = no_closing(d);
+    size_gru(d, plan, a.msg_count, a.wins_est, &g);
     if (a.finish_here) {
+        const int cus = plan.num_cus > 0 ? plan.num_cus : 256;
         const int rows = 2 * a.count;  // at most; a wavefront takes several rows if there are many
         g.n_row_blocks = (rows + kGruWaves - 1) / kGruWaves;
         if (g.n_row_blocks > 2 * cus)
             g.n_row_blocks = 2 * cus;
-        n_slot_blocks = (2 * a.count + kGruThreads - 1) / kGruThreads;
+        g.n_slot_blocks = (2 * a.count + kGruThreads - 1) / kGruThreads;
     }
-    if (g.n_gru + g.n_neg_blocks + g.n_row_blocks + n_slot_blocks == 0)
-        n_slot_blocks = 1;  // nothing to apply, nothing to finish: block 0 still clears the next set's counter
-    int K = d.K;
-    void *args[] = {&aa, &ww, &g, &K};
-    return hipLaunchKernel(gru_kernel(d), dim3(g.n_gru + g.n_neg_blocks + g.n_row_blocks + n_slot_blocks),
-                           dim3(kGruThreads), args, (size_t)gru_lds_bytes(d), s);
+    const int blocks = g.n_gru + g.n_row_blocks + g.n_slot_blocks;
+    if (blocks == 0)
+        return hipSuccess;  // nothing to apply, nothing to finish
+    void *args[] = {&aa, &gj, &ww, &g, &dp};
+    return hipLaunchKernel(gru_kernel(d), dim3(blocks), dim3(kGruThreads), args, (size_t)gru_lds_bytes(d), s);
+}
+
+// The closing launch of a step: scores and embedding rows of its events, inspection outputs, the
+// finishing pass of the batch prepared ahead; its own query set's counter is cleared for the
+// set's next preparation; and, if ahead.count > 0, the GRU of the batch the next step applies.
+hipError_t launch_closing(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
+                          const GruAhead &ahead, hipStream_t s)
+{
+    StepArgs aa = a;
+    PackedWeights ww = pw;
+    GruParams g = gru_params(d);
+    GruJob gj = {ahead.first_eid, ahead.count, ahead.win, ahead.n_win};
+    if (ahead.count > 0)
+        size_gru(d, plan, ahead.count, a.wins_est, &g);
+    g.clear = a.qs.n_u;
+    DecodeParams p = no_closing(d);
+    p.n_event_blocks = (a.count + kGruWaves - 1) / kGruWaves;
+    const bool expand = a.out_nbr_node || a.out_nbr_eid || a.out_nbr_ts || a.out_nbr_cnt || a.out_is_winner;
+    p.n_expand_blocks = expand ? (a.roles * a.count + kGruWaves - 1) / kGruWaves : 0;
+    if (a.fin_count > 0) {
+        p.n_fin_row_blocks = (2 * a.fin_count + kGruWaves - 1) / kGruWaves;
+        if (p.n_fin_row_blocks > 128)
+            p.n_fin_row_blocks = 128;
+        p.n_fin_slot_blocks = (2 * a.fin_count + kGruThreads - 1) / kGruThreads;
+    }
+    const int blocks = g.n_gru + p.n_event_blocks + p.n_expand_blocks + p.n_fin_row_blocks + p.n_fin_slot_blocks;
+    void *args[] = {&aa, &gj, &ww, &g, &p};
+    return hipLaunchKernel(gru_kernel(d), dim3(blocks), dim3(kGruThreads), args, (size_t)gru_lds_bytes(d), s);
 }
 
 }  // namespace tig

@@ -18,11 +18,14 @@ namespace tig {
 // One wavefront: the query (u, t) becomes row `row` of the query set (node, time, neighbour
 // slots, count; the row references are filled in later).  own_pos: adjacency position of the
 // query's own event in u's list (everything from there on has time >= t), or -1 if unknown.
-// my_nbr: the neighbour id this lane wrote (lanes below K), -1 for an unused slot.
-__device__ inline void nbr_lookup_wave(const StepArgs &a, int K, int32_t u, double t, int64_t own_pos,
-                                       const QuerySet &qs, int row, int32_t &my_nbr)
+// my_nbr / my_eid / my_ts: the slot this lane wrote (lanes below K; -1, -1, 0.0 for an unused
+// slot and for the other lanes).  Returns the number of filled slots.
+__device__ inline int nbr_lookup_wave(const StepArgs &a, int K, int32_t u, double t, int64_t own_pos,
+                                      const QuerySet &qs, int row, int32_t &my_nbr, int32_t &my_eid, double &my_ts)
 {
     my_nbr = -1;
+    my_eid = -1;
+    my_ts = 0.0;
     const int lane = lane_id();
     int64_t lo = 0, hi = 0;
     const bool known = u >= 0 && (int64_t)u < a.num_nodes;
@@ -78,6 +81,8 @@ __device__ inline void nbr_lookup_wave(const StepArgs &a, int K, int32_t u, doub
         if (p >= base) {
             const CsrEntry e = a.csr[p];
             my_nbr = e.nbr;
+            my_eid = e.eid;
+            my_ts = e.ts;
             qs.nbr[o] = e.nbr;
             qs.eid[o] = e.eid;
             qs.ts[o] = e.ts;
@@ -87,11 +92,13 @@ __device__ inline void nbr_lookup_wave(const StepArgs &a, int K, int32_t u, doub
             qs.ts[o] = 0.0;
         }
     }
+    const int cnt = (int)(avail < K ? avail : K);
     if (lane == 0) {
-        qs.cnt[row] = (int32_t)(avail < K ? avail : K);
+        qs.cnt[row] = cnt;
         qs.node[row] = known ? u : -1;
         qs.t[row] = t;
     }
+    return cnt;
 }
 
 }  // namespace tig

@@ -125,8 +125,9 @@ __device__ inline void dedup_block(const StepArgs &a, const DedupJob &j, int K, 
         double t;
         entry_query(a, j.first_eid, e, u, t);
         const int64_t eid = j.first_eid + (e >> 1);
-        int32_t my_nbr;
-        nbr_lookup_wave(a, K, u, t, (int64_t)a.pos[2 * eid + (e & 1)], j.qs, base + l, my_nbr);
+        int32_t my_nbr, my_eid;
+        double my_ts;
+        nbr_lookup_wave(a, K, u, t, (int64_t)a.pos[2 * eid + (e & 1)], j.qs, base + l, my_nbr, my_eid, my_ts);
         if (lane == 0)
             j.qs.slot[e] = base + l;
     }
@@ -166,14 +167,14 @@ __device__ inline int32_t resolve_ref(const RefCtx &c, int32_t v)
 //   finish_slots      entry i of the batch: its slot is pointed straight at its row (one thread
 //                     per entry; representatives' slots never change)
 //   finish_row        row `row` of the source / destination queries: row references
-//   finish_negative   the negative of event b: lookup into row n_u + b, then its row references
+//   finish_negative   the negative of event b: lookup into row 2 * count + b, then its row references
 // The first two need the batch's queries and the applied batch's keys only, so for a batch that
-// was prepared ahead they run a step early as well (beside the previous step's decode); the
-// negatives arrive with the call.
-__device__ inline void finish_slots(const QuerySet &qs, int i)
+// was prepared ahead they run a step early as well (in the previous step's closing launch); the
+// negatives arrive with the call and are looked up by the embedding kernel itself.
+__device__ inline void finish_slots(const QuerySet &qs, int i, int entries)
 {
     const int sl = qs.slot[i];
-    if (sl < 0)
+    if (sl < 0 && -sl - 1 < entries)
         qs.slot[i] = qs.slot[-sl - 1];
 }
 
@@ -195,14 +196,22 @@ __device__ inline void finish_row(const RefCtx &c, const QuerySet &qs, int K, in
     finish_refs(c, qs, K, row, my_nbr, qs.node[row]);
 }
 
-__device__ inline void finish_negative(const StepArgs &a, int K, int b, int n_u)
+// Returns the number of filled slots; my_ref / my_eid / my_ts: slot `lane` of the row (lanes
+// below K), as written to the query set.
+__device__ inline int finish_negative(const StepArgs &a, int K, int b, int32_t &my_ref, int32_t &my_eid,
+                                      double &my_ts)
 {
     int32_t my_nbr;
     const int32_t u = a.neg[b];
-    nbr_lookup_wave(a, K, u, a.ts[a.first_eid + b], -1, a.qs, n_u + b, my_nbr);
+    const int row = 2 * a.count + b;
+    const int cnt = nbr_lookup_wave(a, K, u, a.ts[a.first_eid + b], -1, a.qs, row, my_nbr, my_eid, my_ts);
     // (the node id is validated by resolve_ref as the lookup did; it is not read back from the row,
     // which another lane of this wavefront has just written)
-    finish_refs(ref_ctx(a), a.qs, K, n_u + b, my_nbr, u);
+    const RefCtx c = ref_ctx(a);
+    my_ref = resolve_ref(c, my_nbr);
+    if (lane_id() < K)
+        a.qs.ref[(size_t)row * K + lane_id()] = my_ref;
+    return cnt;
 }
 
 }  // namespace tig

@@ -40,6 +40,9 @@ hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeight
     int mark = 0;
     auto stamp = [&]() -> hipError_t { return marks ? hipEventRecord(marks[mark++], s) : hipSuccess; };
 
+    // the counter of a query set this step's embedding launch fills, if no closing launch cleared it
+    if (sp.clear_first && (e = launch_fill_zero(sp.clear_first, 4, s)) != hipSuccess)
+        return e;
     if ((e = stamp()) != hipSuccess)
         return e;
     if (sp.big_sel && (e = launch_scatter(a, *sp.big_sel, s)) != hipSuccess)
@@ -69,11 +72,13 @@ hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeight
     }
     if ((e = stamp()) != hipSuccess)
         return e;
-    if ((e = launch_gru(d, plan, pw, a, s)) != hipSuccess || (e = stamp()) != hipSuccess)
+    if (sp.gru_now && (e = launch_gru(d, plan, pw, a, s)) != hipSuccess)
+        return e;
+    if ((e = stamp()) != hipSuccess)
         return e;
     if ((e = launch_embed(d, plan, pw, a, s)) != hipSuccess || (e = stamp()) != hipSuccess)
         return e;
-    if ((e = launch_decode(d, pw, a, s)) != hipSuccess || (e = stamp()) != hipSuccess)
+    if ((e = launch_closing(d, plan, pw, a, sp.ahead, s)) != hipSuccess || (e = stamp()) != hipSuccess)
         return e;
     return hipSuccess;
 }

@@ -9,9 +9,6 @@
 //              equal queries and look up the neighbours of the distinct ones (prepare.h)
 //   k_scatter + k_select  larger batches: keys go to the per-node array in memory, pre-reduced per
 //              wavefront and per workgroup; a second launch selects and compacts the winners
-//   k_decode   per event, from the rows of the distinct queries: the two logits and the three
-//              embedding rows; in the same launch the memory overwrite M <- s_i(t), last_update,
-//              and the optional inspection outputs
 #include <hip/hip_runtime.h>
 
 #include "kernels_common.h"
@@ -107,131 +104,6 @@ __global__ void __launch_bounds__(256) k_select(StepArgs a, SelectJob j)
     }
 }
 
-struct DecodeParams {
-    int M, E, Ep, K;
-    int n_event_blocks;   // blocks of 4 wavefronts, one event each
-    int n_commit_blocks;  // one winner each
-    int n_expand_blocks;  // one query each (inspection outputs), 0 if none is wanted
-    int n_fin_row_blocks; // row references of the batch prepared ahead, grid-stride over its rows
-    int n_fin_slot_blocks; // its slots, one entry per thread
-};
-
-__device__ inline int row_of_entry(const QuerySet &qs, int i)
-{
-    const int s = qs.slot[i];
-    return s >= 0 ? s : qs.slot[-s - 1];
-}
-
-// score(a, b) = w_d2 . relu(W_d1 [emb_a | emb_b] + b_d1) + b_d2 (decoder g of Sec. II-C) from the
-// per-row halves of layer 1 that the embedding kernel left; the embedding rows of the event's
-// three queries are copies of their distinct rows.
-__global__ void __launch_bounds__(256) k_decode(StepArgs a, PackedWeights w, DecodeParams p)
-{
-    const int lane = lane_id();
-    int blk = (int)blockIdx.x;
-    if (blk < p.n_event_blocks) {
-        const int b = blk * 4 + wave_id();
-        if (b >= a.count)
-            return;
-        const int n_u = *a.qs.n_u;
-        int row[3];
-        row[0] = row_of_entry(a.qs, 2 * b);
-        row[1] = row_of_entry(a.qs, 2 * b + 1);
-        row[2] = a.roles == 3 ? n_u + b : row[1];
-        const float b2 = w.dec_b2[0];
-        // every load of a 128-dim chunk is requested before the first is used
-        float part[2] = {0.0f, 0.0f};
-        for (int j0 = 0; j0 < p.E; j0 += 2 * kWave) {
-            float da[2], db[2][2], em[3][2], b1[2], w2[2];
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int j = j0 + lane + kWave * u;
-                const bool in = j < p.E;
-                da[u] = in ? a.dec_a[(size_t)row[0] * p.Ep + j] : 0.0f;
-                db[0][u] = in ? a.dec_b[(size_t)row[1] * p.Ep + j] : 0.0f;
-                db[1][u] = in ? a.dec_b[(size_t)row[2] * p.Ep + j] : 0.0f;
-                b1[u] = in ? w.dec_b1f[j] : 0.0f;
-                w2[u] = in ? w.dec_w2[j] : 0.0f;
-#pragma unroll
-                for (int r = 0; r < 3; ++r)
-                    em[r][u] = in ? a.emb_u[(size_t)row[r] * p.E + j] : 0.0f;
-            }
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int j = j0 + lane + kWave * u;
-                if (j < p.E) {
-                    const float x = da[u] + b1[u];
-                    part[0] += w2[u] * fmaxf(x + db[0][u], 0.0f);
-                    part[1] += w2[u] * fmaxf(x + db[1][u], 0.0f);
-#pragma unroll
-                    for (int r = 0; r < 3; ++r)
-                        if (r < a.roles)
-                            a.emb[((size_t)r * a.count + b) * p.E + j] = em[r][u];
-                }
-            }
-        }
-        const float s_pos = wave_sum_uniform(part[0]) + b2;
-        const float s_neg = wave_sum_uniform(part[1]) + b2;
-        if (lane == 0) {
-            a.score_pos[b] = s_pos;
-            if (a.roles == 3)
-                a.score_neg[b] = s_neg;
-        }
-        return;
-    }
-    blk -= p.n_event_blocks;
-    if (blk < p.n_commit_blocks) {
-        // Memory overwrite M <- s_i(t) for the winners of the applied batch (every reader of this
-        // step took the staged rows instead), and last_update.  One wavefront per winner at a time.
-        const int n_win = *a.n_win;
-        for (int r = blk * 4 + wave_id(); r < n_win; r += p.n_commit_blocks * 4) {
-            const WinDesc d = a.win[r];
-            for (int j = lane; j < p.M; j += kWave)
-                a.mem[(size_t)d.node * p.M + j] = a.staging[(size_t)d.entry * p.M + j];
-            if (lane == 0)
-                a.lu[d.node] = d.t;
-        }
-        return;
-    }
-    blk -= p.n_commit_blocks;
-    if (blk >= p.n_expand_blocks) {
-        // Finishing pass for the batch that the embedding launch has just prepared (prepare.h): its
-        // row references against the batch the NEXT step will apply, and its slots.
-        blk -= p.n_expand_blocks;
-        const QuerySet &nq = a.ded.qs;
-        if (blk < p.n_fin_row_blocks) {
-            const RefCtx c{a.num_nodes, a.fin_msg_key, a.fin_msg_first_eid, a.fin_msg_count};
-            const int n_u = *nq.n_u;
-            for (int row = blk * 4 + wave_id(); row < n_u; row += p.n_fin_row_blocks * 4)
-                finish_row(c, nq, p.K, row);
-        } else {
-            const int i = (blk - p.n_fin_row_blocks) * 256 + (int)threadIdx.x;
-            if (i < 2 * a.fin_count)
-                finish_slots(nq, i);
-        }
-        return;
-    }
-    // inspection outputs, per query in the order [sources | destinations | negatives]
-    const int q = blk * 4 + wave_id();
-    if (q >= a.roles * a.count)
-        return;
-    const int role = q / a.count, b = q - role * a.count;
-    const int row = role < 2 ? row_of_entry(a.qs, 2 * b + role) : *a.qs.n_u + b;
-    if (lane < p.K) {
-        const size_t o = (size_t)q * p.K + lane, i = (size_t)row * p.K + lane;
-        if (a.out_nbr_node)
-            a.out_nbr_node[o] = a.qs.nbr[i];
-        if (a.out_nbr_eid)
-            a.out_nbr_eid[o] = a.qs.eid[i];
-        if (a.out_nbr_ts)
-            a.out_nbr_ts[o] = a.qs.ts[i];
-    }
-    if (lane == 0 && a.out_nbr_cnt)
-        a.out_nbr_cnt[q] = a.qs.cnt[row];
-    if (role < 2 && lane == 1 && a.out_is_winner && a.win_flags)
-        a.out_is_winner[2 * b + role] = a.win_flags[2 * b + role];
-}
-
 __global__ void k_fill_zero(uint32_t *p, size_t words)
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -281,34 +153,6 @@ hipError_t launch_prepare(const StepArgs &a, const SelectJob &sel, const DedupJo
         return hipSuccess;
     const int lds = sel.count > 0 ? kOneLds : kPrepLds;
     hipLaunchKernelGGL(k_prepare, dim3(blocks), dim3(kScatterThreads), lds, s, a, sel, ded, K);
-    return hipGetLastError();
-}
-
-hipError_t launch_decode(const Dims &d, const PackedWeights &pw, const StepArgs &a, hipStream_t s)
-{
-    DecodeParams p;
-    p.M = d.M;
-    p.E = d.E;
-    p.Ep = d.Ep;
-    p.K = d.K;
-    p.n_event_blocks = (a.count + 3) / 4;
-    // the winners are usually a small share of the 2 * msg_count entries: a modest number of
-    // wavefronts, each taking winner after winner
-    p.n_commit_blocks = a.msg_count > 0 ? (2 * a.msg_count + 3) / 4 : 0;
-    if (p.n_commit_blocks > 128)
-        p.n_commit_blocks = 128;
-    const bool expand = a.out_nbr_node || a.out_nbr_eid || a.out_nbr_ts || a.out_nbr_cnt || a.out_is_winner;
-    p.n_expand_blocks = expand ? (a.roles * a.count + 3) / 4 : 0;
-    p.n_fin_row_blocks = p.n_fin_slot_blocks = 0;
-    if (a.fin_count > 0) {
-        p.n_fin_row_blocks = (2 * a.fin_count + 3) / 4;
-        if (p.n_fin_row_blocks > 256)
-            p.n_fin_row_blocks = 256;
-        p.n_fin_slot_blocks = (2 * a.fin_count + 255) / 256;
-    }
-    hipLaunchKernelGGL(k_decode, dim3(p.n_event_blocks + p.n_commit_blocks + p.n_expand_blocks + p.n_fin_row_blocks +
-                                      p.n_fin_slot_blocks),
-                       dim3(256), 0, s, a, pw, p);
     return hipGetLastError();
 }
 

@@ -67,6 +67,11 @@ struct tig_ctx {
     bool ahead_w_valid;  // update-first: list wcur ^ 1 holds the winners of batch (ahead_w_first, ahead_w_count)
     int64_t ahead_w_first;
     int32_t ahead_w_count;
+    // the staging rows hold the GRU output for the winners of batch (ahead_g_first, ahead_g_count),
+    // computed by the last step's closing launch from the memory as that step left it
+    bool ahead_g_valid;
+    int64_t ahead_g_first;
+    int32_t ahead_g_count;
     bool ahead_q_valid;  // set qcur ^ 1 holds the queries of batch (ahead_q_first, ahead_q_count)
     bool ahead_q_finished;  // ... with final slots and row references (else the step finishes them)
     int64_t ahead_q_first;
@@ -567,10 +572,10 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
         return epoch;
     };
 
-    StepPlan sp = {nullptr, nullptr, nullptr, false};
+    StepPlan sp = {};
     SelectJob sel_now = {};
     DedupJob ded_now = {};
-    int launches = 3;
+    int launches = 2;  // embedding, closing
 
     // ---- the distinct queries of this batch: prepared by the previous step's embedding launch if
     // that step guessed this batch (it reads the event stream and the adjacency only), else now
@@ -619,9 +624,17 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     a.win = st.win[wi];
     a.n_win = st.n_win[wi];
     a.msg_key = ctx->key[wi];
+    // ---- the GRU of the applied batch: run by the previous step's closing launch if that step knew
+    // the batch (and the memory has not changed since), else now, together with what is left of
+    // this step's query preparation
+    const bool g_ready = !use_static && ctx->ahead_g_valid && a.msg_count > 0 && ctx->ahead_g_first == a.msg_first_eid &&
+                         ctx->ahead_g_count == a.msg_count && !a.finish_here && (d.deferred || w_ready);
+    sp.gru_now = !g_ready && (a.msg_count > 0 || a.finish_here);
     if (sp.big_sel)
         launches += 2;
     if (sp.prep_sel || sp.prep_ded)
+        launches += 1;
+    if (sp.gru_now)
         launches += 1;
     sp.clear_tab = clear_tab && sp.prep_ded;
 
@@ -634,7 +647,10 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
         const int32_t guess = left < count ? (int32_t)left : count;
         if (winners_in_one_launch(guess)) {
             a.ded = make_dedup(st, st.qs[qi ^ 1], next_first, guess, next_epoch(), true);
-            a.n_u_next = st.qs[qi ^ 1].n_u;
+            // that set's counter was cleared by the closing launch of the step that used the set,
+            // unless this step did not take the set prepared for it
+            if (!q_ready)
+                sp.clear_first = st.qs[qi ^ 1].n_u;
             if (!d.deferred)
                 a.sel = SelectJob{next_first, guess, st.win[wi ^ 1], st.n_win[wi ^ 1], st.flags[wi ^ 1],
                                   ctx->key[wi ^ 1]};
@@ -647,6 +663,15 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
             a.fin_msg_key = ctx->key[wi ^ 1];
         }
     }
+    // ---- The closing launch also runs the GRU of the batch the next step applies, once that batch's
+    // winners are known: in the update-first order the guessed batch (selected by this step's
+    // embedding launch), in the deferred order this step's own batch (whatever comes next).
+    if (!use_static) {
+        if (!d.deferred && a.sel.count > 0)
+            sp.ahead = GruAhead{a.sel.first_eid, a.sel.count, st.win[wi ^ 1], st.n_win[wi ^ 1]};
+        else if (d.deferred)
+            sp.ahead = GruAhead{first, count, st.win[wi ^ 1], st.n_win[wi ^ 1]};
+    }
     if (clear_tab && !sp.prep_ded && a.ded.count > 0) {
         // the epoch wrapped and only the side job uses the table: clear it ahead of everything
         const hipError_t e = launch_fill_zero(st.tab, sizeof(unsigned long long) * (size_t)st.tab_slots, ctx->stream);
@@ -658,6 +683,7 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     if (e != hipSuccess) {
         // kernels of this step may already be enqueued: nothing prepared ahead is trusted any more,
         // and the model state is undefined until tig_reset / tig_state_import
+        ctx->ahead_g_valid = false;
         if (!use_static) {
             ctx->ahead_w_valid = false;
             ctx->ahead_q_valid = false;
@@ -667,8 +693,11 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     }
     ctx->cursor = next_first;
     ctx->last_launches = launches;
+    ctx->ahead_g_valid = sp.ahead.count > 0;  // (never after a static call: the memory has changed)
+    ctx->ahead_g_first = sp.ahead.first_eid;
+    ctx->ahead_g_count = sp.ahead.count;
     if (use_static)
-        return TIG_OK;  // the context's own lists and sets are untouched: what was prepared ahead stays usable
+        return TIG_OK;  // the context's own lists and sets are untouched: winners and queries prepared ahead stay usable
     ctx->epoch = epoch;
     ctx->qcur = qi;
     ctx->ahead_q_valid = a.ded.count > 0;
@@ -740,6 +769,7 @@ static hipError_t drop_pending(tig_ctx *ctx)
         ctx->ahead_q_finished = false;  // its row references point at the pending batch's staged rows
     ctx->pend_valid = false;
     ctx->ahead_w_valid = false;
+    ctx->ahead_g_valid = false;  // computed from the memory that has just been replaced
     return e;
 }
 

@@ -77,7 +77,8 @@ constexpr int32_t kRefNone = INT32_MIN;
 // The distinct embedding queries (node, t) of one batch.  Source and destination queries of a
 // batch repeat heavily (hub nodes, events sharing a timestamp); each distinct pair gets ONE row
 // here, `slot` maps every (event, role) entry to its row.  Rows [0, *n_u) belong to source /
-// destination queries, rows *n_u + b to the negative of event b (negatives are not merged).
+// destination queries (*n_u <= 2 * count), row 2 * count + b to the negative of event b
+// (negatives are not merged; their place does not depend on the device-side count).
 struct QuerySet {
     int32_t *node;      // [R] node id, -1: none
     double *t;          // [R] query time
@@ -149,14 +150,14 @@ struct StepArgs {
     float *dec_a;    // [R x Ep] first decoder layer, source half, of every distinct query
     float *dec_b;    // [R x Ep] the same, second-operand half
     // finishing pass of the preparation (prepare.h): in the GRU launch for this batch if its slots /
-    // row references are not final yet, and beside the decode for the batch prepared ahead (whose
+    // row references are not final yet, and in the closing launch for the batch prepared ahead (whose
     // applied batch is (fin_first_eid, fin_count) with key array fin_key)
     int32_t finish_here;        // 1: the GRU launch also fixes this batch's slots and row references
     int32_t fin_count;          // 0: the decode launch finishes nothing
     int64_t fin_msg_first_eid;
     int32_t fin_msg_count;
     const unsigned long long *fin_msg_key;
-    int32_t *n_u_next;  // counter of the query set the next preparation will fill (cleared here), may be NULL
+    int32_t *n_u_clear; // counter of a query set that no kernel reads any more (cleared by the closing launch), may be NULL
     int32_t *rows_seen; // host memory mapped into the device: the step leaves its numbers of distinct rows [0] and of winners [1] here, may be NULL
     int32_t rows_est;   // host side only: expected number of distinct rows (sizes the embedding tiles)
     int32_t wins_est;   // host side only: expected number of winners (sizes the GRU column slices)
@@ -205,13 +206,26 @@ hipError_t launch_scatter(const StepArgs &a, const SelectJob &j, hipStream_t s);
 hipError_t launch_select(const StepArgs &a, const SelectJob &j, hipStream_t s);
 // selection (one workgroup, if sel.count > 0) and query preparation (if ded.count > 0) as a launch
 hipError_t launch_prepare(const StepArgs &a, const SelectJob &sel, const DedupJob &ded, int K, hipStream_t s);
-// GRU tiles and, in the same launch, what is left of the query preparation: negatives, row references
+// The batch whose winners the NEXT step applies, for the GRU workgroups of a step's closing launch
+// (count 0: none; that step runs the GRU itself).
+struct GruAhead {
+    int64_t first_eid;
+    int32_t count;
+    const WinDesc *win;
+    const int32_t *n_win;
+};
+// GRU of the batch a step applies and, in the same launch, what is left of its query preparation
+// (slots, row references), ahead of the embedding launch
 hipError_t launch_gru(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
                       hipStream_t s);
+// embedding of the distinct queries (the negatives' neighbours are looked up here); memory overwrite;
+// selection and query preparation for the batch expected next
 hipError_t launch_embed(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
                         hipStream_t s);
-// scores and per-query embeddings from the distinct rows, memory overwrite, optional inspection outputs
-hipError_t launch_decode(const Dims &d, const PackedWeights &pw, const StepArgs &a, hipStream_t s);
+// scores and per-query embeddings from the distinct rows, optional inspection outputs, finishing pass
+// of the batch prepared ahead, GRU of the batch the next step applies
+hipError_t launch_closing(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
+                          const GruAhead &ahead, hipStream_t s);
 // workgroups the embedding launch can spare for a following batch's preparation (0: none)
 int embed_spare_workgroups(const Dims &d, const LaunchPlan &plan, int roles, int count);
 // workgroups of a batch's query preparation; `shared`: in a launch whose workgroups each occupy a
@@ -221,12 +235,16 @@ hipError_t prepare_kernels(const Dims &d, const LaunchPlan &plan);
 constexpr int kNumStepKernels = TIG_NUM_STEP_KERNELS;
 // What one step launches, in order: [scatter, select] (up-front selection of a batch above the
 // one-workgroup limit), [prepare] (selection and / or query preparation not done ahead),
-// gru, embed, decode.  `marks`: NULL, or kNumStepKernels + 1 events.
+// [gru] (unless the previous step's closing launch ran it), embed, closing.
+// `marks`: NULL, or kNumStepKernels + 1 events.
 struct StepPlan {
     const SelectJob *big_sel;   // scatter + select launches, or NULL
     const SelectJob *prep_sel;  // selection inside the prepare launch, or NULL
     const DedupJob *prep_ded;   // query preparation inside the prepare launch, or NULL
     bool clear_tab;             // clear prep_ded's claim table first
+    bool gru_now;               // the GRU launch ahead of the embedding
+    int32_t *clear_first;       // a counter to clear ahead of everything, or NULL
+    GruAhead ahead;             // GRU workgroups of the closing launch
 };
 hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw,
                        const StepArgs &a, const StepPlan &sp, hipStream_t s, hipEvent_t *marks);

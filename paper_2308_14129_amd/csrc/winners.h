@@ -187,5 +187,24 @@ __device__ inline void winners_block(const StepArgs &g, const SelectJob &a, char
     }
 }
 
+// Memory overwrite M <- s_i(t) for the winners of the applied batch, and their last_update.
+// Wavefront `w` of `n_waves` takes winner after winner.  While a step runs, every reader of an
+// updated node's state takes the staged row through its row reference, never the memory row, so
+// this may run beside the embedding.
+__device__ inline void overwrite_memory(const StepArgs &a, int M, int w, int n_waves)
+{
+    const int lane = lane_id();
+    int n_win = *a.n_win;
+    n_win = n_win < 2 * a.msg_count ? n_win : 2 * a.msg_count;
+    for (int r = w; r < n_win; r += n_waves) {
+        const WinDesc d = a.win[r];
+        if (d.node < 0 || (int64_t)d.node >= a.num_nodes || d.entry < 0 || d.entry >= 2 * a.msg_count)
+            continue;  // (not a descriptor of this batch)
+        for (int j = lane; j < M; j += kWave)
+            a.mem[(size_t)d.node * M + j] = a.staging[(size_t)d.entry * M + j];
+        if (lane == 0)
+            a.lu[d.node] = d.t;
+    }
+}
 
 }  // namespace tig

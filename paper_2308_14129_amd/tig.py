@@ -207,7 +207,7 @@ class TigContext:
         fn = self.lib.tig_step_static if static else self.lib.tig_step
         self._check(fn(self.handle, ctypes.byref(b), ctypes.byref(o)))
 
-    KERNEL_NAMES = ("k_scatter", "k_select", "k_prepare", "k_gru", "k_embed", "k_decode")
+    KERNEL_NAMES = ("k_scatter", "k_select", "k_prepare", "k_gru", "k_embed", "k_closing")
 
     def step_profiled(self, first_eid: int, count: int, neg_dst, out: StepOutputs):
         """One step with HIP events around every kernel; returns the durations in ms, one per

@@ -167,9 +167,10 @@ def test_reset_export_import_roundtrip_and_determinism(c1):
 
 
 def test_launches_per_step(c1):
-    """A step whose batch continues the previous one runs three kernels (its winners and queries
-    were prepared inside the previous embedding launch); any other step prepares them in a launch
-    of its own.  Asking for the inspection outputs does not change what is launched."""
+    """A step whose batch continues the previous one runs two kernels (its winners and queries
+    were prepared inside the previous embedding launch, its GRU rows by the previous closing
+    launch); any other step prepares them in two launches of its own.  Asking for the inspection
+    outputs does not change what is launched."""
     import torch
     w, g, W = c1.w, c1.g, c1.W
     ctx = make_ctx(w, g, W, "fp32")
@@ -183,7 +184,7 @@ def test_launches_per_step(c1):
         seen.append(ctx.launch_info()["kernels_per_step"])
     torch.cuda.synchronize()
     # first step; two that continue; a gap; one that asks for the winner flags; one that continues
-    assert seen == [4, 3, 3, 4, 3, 3]
+    assert seen == [4, 2, 2, 4, 2, 2]
     ctx.close()
 
 

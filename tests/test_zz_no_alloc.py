@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 NAMES = ("emb", "score_pos", "score_neg", "nbr_node", "nbr_eid", "nbr_ts", "nbr_cnt", "is_winner")
 
 
-def _twin_steps(bundle, precision, seq, warm_at):
+def _twin_steps(bundle, precision, seq, warm_at, static_calls=None):
     import torch
     w, g, W = bundle.w, bundle.g, bundle.W
     ref_ctx = make_ctx(w, g, W, precision, max(c for _, c in seq))
@@ -29,7 +29,7 @@ def _twin_steps(bundle, precision, seq, warm_at):
         a = ref_ctx.alloc_outputs(count, inspect=True)
         b = new_ctx.alloc_outputs(count, inspect=True)
         ref_ctx.step(first, count, neg, a)
-        new_ctx.step(first, count, neg, b, static=True)
+        new_ctx.step(first, count, neg, b, static=static_calls is None or (first, count) in static_calls)
         torch.cuda.synchronize()
         for n in NAMES:
             assert torch.equal(getattr(a, n), getattr(b, n)), n
@@ -51,6 +51,14 @@ def test_static_scratch_step_equals_tig_step():
                             precision="bf16"))
     _twin_steps(odd, "bf16", [(1000, 100), (1100, 37)], warm_at=1000)
     _twin_steps(c1, "bf16", [(5000, 136), (5136, 50)], warm_at=5000)
+
+
+def test_static_and_ordinary_steps_mixed_on_one_context():
+    # consecutive batches, so every ordinary step prepares the next batch (winners, queries, GRU
+    # rows); a static call in between uses none of it and changes the memory under it
+    c1 = Bundle(S.WORKLOADS["c1_tiny"])
+    seq = [(4000 + 136 * i, 136) for i in range(7)]
+    _twin_steps(c1, "fp32", seq, warm_at=4000, static_calls={seq[2], seq[3], seq[5]})
 
 
 def test_static_scratch_step_rejects_what_it_cannot_hold():
