@@ -24,7 +24,6 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
 BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
 FP32_MFMA_PEAK_TFLOPS = 157.3
 
-CSRC = os.path.join(ROOT, "paper_2308_14129_amd", "csrc")
 PROFILES = os.path.join(ROOT, "profiles")
 
 
@@ -32,23 +31,12 @@ def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-def kernel_source_id():
-    """Hash of the kernel sources: counter figures under profiles/ name the sources they were
-    measured on and are reported only while the sources are still those."""
-    import hashlib
-    h = hashlib.sha256()
-    for name in sorted(os.listdir(CSRC)):
-        if name.endswith((".hip", ".h")):
-            h.update(name.encode())
-            h.update(open(os.path.join(CSRC, name), "rb").read())
-    return h.hexdigest()[:16]
-
-
-def counter_figures(workload, precision, batch):
-    """key: value lines of profiles/counters_<workload>_<precision>.md (written from the rocprofv3
-    --pmc runs described there); {} if there is none, it is for another batch size, or the kernel
-    sources have changed since."""
-    path = os.path.join(PROFILES, f"counters_{workload}_{precision}.md")
+def profile_figures(kind, workload, precision, batch):
+    """key: value lines of profiles/<kind>_<workload>_<precision>.md (written by
+    paper_2308_14129_amd.profiling from the rocprofv3 runs described there); {} if there is no such
+    file, it is for another batch size, or the kernel sources have changed since it was measured."""
+    from paper_2308_14129_amd.profiling import kernel_source_id
+    path = os.path.join(PROFILES, f"{kind}_{workload}_{precision}.md")
     if not os.path.exists(path):
         return {}
     vals = {}
@@ -60,6 +48,77 @@ def counter_figures(workload, precision, batch):
     if vals.get("kernel_source_id") != kernel_source_id() or vals.get("batch") != str(batch):
         return {}
     return vals
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def oracle_baseline(g, w, weights, batches, negs_np, mem0, lu0, order, n_steps, workers):
+    """The oracle as it stands on the host cores: (i) one thread, n_steps consecutive steps of the
+    timed window; (ii) `workers` replicas of it at once, each a single-threaded process stepping
+    its own n_steps consecutive batches of the window from the same warm state (the way the
+    paper's method itself scales: independent model replicas on disjoint parts of the stream).
+    Must run before anything touches the GPU (the replicas are forked)."""
+    import multiprocessing as mp
+    import numpy as np
+    from threadpoolctl import threadpool_limits
+    from oracle import tig_oracle as O
+    log("building the oracle's neighbour index ...")
+    ix = O.NeighbourIndex(g.num_nodes, g.src, g.dst, g.ts)
+
+    def replica(k):
+        st = O.OracleState(mem0, lu0)  # (forked: pages the steps touch are copied on write)
+        ev = 0
+        with threadpool_limits(limits=1):
+            for i in range(k * n_steps, (k + 1) * n_steps):
+                f, c = batches[i % len(batches)]
+                O.step(st, g.src, g.dst, g.ts, g.edge_feat, weights, f, c, negs_np[i % len(batches)],
+                       w.num_neighbors, w.num_heads, index=ix, deferred=order == "deferred")
+                ev += c
+        return ev
+
+    def child(k, q):
+        q.put(replica(k))
+
+    st1 = O.OracleState(mem0.copy(), lu0.copy())
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        ev1 = 0
+        for i in range(n_steps):
+            f, c = batches[i]
+            O.step(st1, g.src, g.dst, g.ts, g.edge_feat, weights, f, c, negs_np[i], w.num_neighbors,
+                   w.num_heads, index=ix, deferred=order == "deferred")
+            ev1 += c
+        one_s = time.perf_counter() - t0
+    del st1
+    all_rate, all_s = None, None
+    if workers > 1:
+        ctx = mp.get_context("fork")
+        q = ctx.Queue()
+        t0 = time.perf_counter()
+        procs = [ctx.Process(target=child, args=(k, q)) for k in range(workers)]
+        for p_ in procs:
+            p_.start()
+        ev_all = sum(q.get() for _ in procs)
+        for p_ in procs:
+            p_.join()
+        all_s = time.perf_counter() - t0
+        all_rate = ev_all / all_s
+    B = batches[0][1]
+    return {"value": round(ev1 / one_s, 1), "unit": "events/s", "cores": 1, "kind": "oracle",
+            "sample": f"{n_steps} steps of {B} events of the same window (float64 NumPy oracle, "
+                      f"indexed neighbour lookup, index build excluded), {one_s:.1f} s",
+            "all_cores": None if all_rate is None else {
+                "value": round(all_rate, 1), "cores": workers,
+                "sample": f"{workers} single-threaded replicas at once, {n_steps} steps each, {all_s:.1f} s"},
+            "cpu_model": cpu_model(), "nproc": os.cpu_count()}
 
 
 def distinct_queries(g, first, count, nbr_cnt):
@@ -160,11 +219,6 @@ def main():
     import tig_synth as S
     from paper_2308_14129_amd import tig
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    tig.load_library()  # fails loudly if libtig.so is missing
-
     w = S.WORKLOADS[args.workload]
     precision = args.precision or w.precision
     B = args.batch or w.batch_size
@@ -182,6 +236,23 @@ def main():
     batches = list(S.batches(w.num_events, B, first=first, stop=first + total_steps * B))
     assert len(batches) == total_steps, "workload too short for the requested steps"
 
+    mem0, lu0 = S.make_warm_state(w, g, first)
+    negs_np = np.stack([S.make_negatives(w, g, f, c) for f, c in batches])
+
+    # ---- CPU baseline first (its replicas are forked, which must happen before the GPU is touched):
+    # the oracle, as it stands, on a bounded sample of the timed window
+    cpu = None
+    if not args.no_cpu_baseline:
+        workers = max(1, min(16, os.cpu_count() or 1, len(batches[W_:]) // max(1, args.cpu_steps)))
+        cpu = oracle_baseline(g, w, weights, batches[W_:], negs_np[W_:], mem0, lu0, args.order,
+                              max(1, min(args.cpu_steps, K)), workers)
+        log(f"oracle: {cpu['value']} events/s on one core, "
+            f"{cpu['all_cores']['value'] if cpu['all_cores'] else '-'} on {workers}")
+
+    tig.load_library()  # fails loudly if libtig.so is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
     cfg = tig.make_config(w.mem_dim, w.time_dim, w.feat_dim, w.emb_dim, w.num_neighbors, w.num_heads, B,
                           precision, args.order)
     t0 = time.time()
@@ -190,8 +261,7 @@ def main():
     log(f"tig_init in {time.time() - t0:.1f} s (persistent {ctx.persistent_bytes / 1e9:.2f} GB, "
         f"scratch {ctx.scratch_bytes / 1e9:.2f} GB)")
 
-    mem0, lu0 = S.make_warm_state(w, g, first)
-    negs = torch.from_numpy(np.stack([S.make_negatives(w, g, f, c) for f, c in batches])).to("cuda:0")
+    negs = torch.from_numpy(negs_np).to("cuda:0")
     out = ctx.alloc_outputs(B, with_neg=True, inspect=False)
     torch.cuda.synchronize()
 
@@ -216,26 +286,34 @@ def main():
     value = events / wall_s
 
     # ---- per-kernel durations: HIP events on the context's stream around every kernel of the SAME
-    # launch sequence the timed region ran (same batches, prepared ahead in the same way) ----------
+    # launch sequence the timed region ran (same batches, prepared ahead in the same way, no
+    # inspection outputs).  The byte accounting needs the neighbour counts and winner flags of
+    # those batches: a pass of its own, before, asks for them. ---------------------------------
+    names = ctx.KERNEL_NAMES
+    n_prof = min(K, 50)
     ctx.state_import(mem0, lu0)
     run(0, W_)
-    torch.cuda.synchronize()
     insp = ctx.alloc_outputs(B, with_neg=True, inspect=True)
-    names = ctx.KERNEL_NAMES
-    sums = np.zeros(len(names))
     byte_sums = {n: 0.0 for n in names}
-    n_prof = min(K, 50)
     rows_sum = slots_sum = win_sum = 0
-    launches_prof = set()
     for i in range(W_, W_ + n_prof):
-        ms = ctx.step_profiled(batches[i][0], batches[i][1], negs[i], insp)
-        launches_prof.add(ctx.launch_info()["kernels_per_step"])
-        sums += np.array(ms)
+        ctx.step(batches[i][0], batches[i][1], negs[i], insp)
+        torch.cuda.synchronize()
         rows_u, slots_u = distinct_queries(g, batches[i][0], batches[i][1], insp.nbr_cnt.cpu().numpy())
         winners = int(insp.is_winner.sum().item())
         rows_sum, slots_sum, win_sum = rows_sum + rows_u, slots_sum + slots_u, win_sum + winners
         for n, v in algorithmic_bytes(w, batches[i][1], rows_u, slots_u, winners).items():
             byte_sums[n] += v
+    del insp
+    ctx.state_import(mem0, lu0)
+    run(0, W_)
+    torch.cuda.synchronize()
+    sums = np.zeros(len(names))
+    launches_prof = set()
+    for i in range(W_, W_ + n_prof):
+        ms = ctx.step_profiled(batches[i][0], batches[i][1], negs[i], out)
+        launches_prof.add(ctx.launch_info()["kernels_per_step"])
+        sums += np.array(ms)
     avg_ms = sums / n_prof
     dom = int(np.argmax(avg_ms))
     dom_name = names[dom]
@@ -245,7 +323,8 @@ def main():
                   "alg_bytes": int(byte_sums[n] / n_prof),
                   "GBps": round(byte_sums[n] / n_prof / max(float(avg_ms[i]), 1e-9) / 1e6, 1)}
               for i, n in enumerate(names) if avg_ms[i] > 1e-4 or byte_sums[n] > 0}
-    figs = counter_figures(w.name, precision, B)
+    figs = profile_figures("counters", w.name, precision, B)
+    trace = profile_figures("step_kernels", w.name, precision, B)
     traffic = float(figs["k_embed_hbm_bytes_per_launch"]) if dom_name == "k_embed" and \
         "k_embed_hbm_bytes_per_launch" in figs else None
     roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
@@ -254,6 +333,14 @@ def main():
                 "profiled_steps": n_prof, "kernels_per_profiled_step": sorted(launches_prof),
                 "distinct_query_rows": round(rows_sum / n_prof, 1), "queries": 3 * B,
                 "winners": round(win_sum / n_prof, 1)}
+    if dom_name + "_trace_avg_us" in trace:
+        # the same kernel's average duration in the committed rocprofv3 kernel trace (the event pair
+        # around a launch reads a few microseconds high on this machine)
+        t_us = float(trace[dom_name + "_trace_avg_us"])
+        roofline["trace_avg_kernel_us"] = t_us
+        roofline["trace_frac"] = round(dom_bytes / (t_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 5)
+    if traffic:
+        roofline["traffic_frac_of_peak"] = round(traffic / (float(avg_ms[dom]) * 1e-3) / 1e9 / HBM_PEAK_GBS, 5)
     issued, useful = mfma_flops(w, rows_sum / n_prof, win_sum / n_prof, precision)
     peak_tf = BF16_PEAK_TFLOPS if precision == "bf16" else FP32_MFMA_PEAK_TFLOPS
     mfma = {}
@@ -264,30 +351,10 @@ def main():
                    "issued_frac_of_peak": round(issued[n] / t_s / 1e12 / peak_tf, 5),
                    "useful_frac_of_peak": round(useful[n] / t_s / 1e12 / peak_tf, 5)}
     mfma["peak_TFLOPs"] = peak_tf
-    for k in ("k_embed_mfma_busy_frac", "k_gru_mfma_busy_frac"):
+    for k in ("k_embed_mfma_busy_frac", "k_gru_mfma_busy_frac", "k_embed_mfma_flop_per_launch",
+              "k_gru_mfma_flop_per_launch"):
         if k in figs:
-            mfma[k] = float(figs[k])
-
-    # ---- CPU baseline: the oracle, as it stands, single thread, on a bounded sample ---------------
-    cpu = None
-    if not args.no_cpu_baseline:
-        from threadpoolctl import threadpool_limits
-        from oracle import tig_oracle as O
-        log("building the oracle's neighbour index ...")
-        ix = O.NeighbourIndex(g.num_nodes, g.src, g.dst, g.ts)
-        st = O.OracleState(mem0.copy(), lu0.copy())
-        n_cpu = max(1, min(args.cpu_steps, K))
-        with threadpool_limits(limits=1):
-            t0 = time.perf_counter()
-            for i in range(W_, W_ + n_cpu):
-                f, c = batches[i]
-                O.step(st, g.src, g.dst, g.ts, g.edge_feat, weights, f, c, negs[i].cpu().numpy(),
-                       w.num_neighbors, w.num_heads, index=ix, deferred=args.order == "deferred")
-            cpu_s = time.perf_counter() - t0
-        cpu_events = sum(c for _, c in batches[W_:W_ + n_cpu])
-        cpu = {"value": round(cpu_events / cpu_s, 1), "unit": "events/s", "cores": 1, "kind": "oracle",
-               "sample": f"{n_cpu} steps of {B} events of the same window (float64 NumPy oracle, "
-                         f"indexed neighbour lookup, index build excluded), {cpu_s:.1f} s"}
+            mfma[k + "_counter"] = float(figs[k])
 
     if args.pmc_calibration:
         n = 256 << 20

@@ -160,6 +160,7 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     double *row_t = (double *)(row_ref + ROWS);   // [ROWS] query time
     double *tw_tab = row_t + ROWS;                // [T][2] time-encoding (w_rev, b_rev)
     int *next_row = (int *)(tw_tab + 2 * p.T);    // [1] row counter of phase C
+    int *row_todo = next_row + 4;                 // [ROWS] 1: a negative whose neighbours phase C looks up
 
     const int lane = lane_id();
     const int wave = wave_id();
@@ -192,16 +193,19 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
             cnt = a.qs.cnt[q];
             t = a.qs.t[q];
         } else if (x < n_rows) {
-            // a negative: node and time from the call; its neighbours are looked up in phase C
+            // a negative: node and time from the call.  For now the reference is the node's own
+            // memory row; the gather below checks whether this step updates the node.
             const int b = x - n_u;
             q = neg_row0 + b;
-            ref = resolve_ref(ref_ctx(a), a.neg[b]);
+            ref = a.neg[b];
+            ref = ref >= 0 ? ref : kRefNone;
             t = a.ts[a.first_eid + b];
         }
         row_q[r] = q;
         row_ref[r] = checked_ref(ref);
         row_cnt[r] = cnt < p.K ? cnt : p.K;
         row_t[r] = t;
+        row_todo[r] = 0;
     }
     if (threadIdx.x == 0)
         *next_row = 0;
@@ -212,17 +216,28 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     __syncthreads();
     {
         // one wavefront per row, lanes along the row (no index arithmetic per element); the loads
-        // of all of a wavefront's rows are requested before the first is stored
+        // of all of a wavefront's rows are requested before the first is stored.  For a negative
+        // the same round trip fetches the node's key (is its state row a staged one?) and the
+        // bounds of its adjacency list: a node without history, the usual case in a large graph,
+        // needs no lookup; the others are looked up by the wavefront that takes the row in phase C.
         constexpr int kRowsPerWave = (ROWS + kEmbedWaves - 1) / kEmbedWaves;
         constexpr int kAhead = 2;  // 128 floats of a row per lane pair of loads
         float v[kRowsPerWave][kAhead];
         const float *src_row[kRowsPerWave];
+        int32_t neg_u[kRowsPerWave], neg_ref[kRowsPerWave];  // node / checked row reference of a negative, else kRefNone
+        unsigned long long neg_key[kRowsPerWave];
+        int64_t deg_lo[kRowsPerWave], deg_hi[kRowsPerWave];
+        const RefCtx rc = ref_ctx(a);
+        auto row_ptr = [&](int32_t ref) -> const float * {
+            return ref == kRefNone ? nullptr
+                                   : (ref >= 0 ? a.mem + (size_t)ref * p.M : a.staging + (size_t)(~ref) * p.M);
+        };
 #pragma unroll
         for (int i = 0; i < kRowsPerWave; ++i) {
             const int r = wave + i * kEmbedWaves;
             const int ref = r < ROWS ? row_ref[r] : kRefNone;
-            src_row[i] = ref == kRefNone ? nullptr
-                                         : (ref >= 0 ? a.mem + (size_t)ref * p.M : a.staging + (size_t)(~ref) * p.M);
+            const bool is_neg = r < ROWS && row_q[r] >= neg_row0;
+            src_row[i] = row_ptr(ref);
 #pragma unroll
             for (int u = 0; u < kAhead; ++u) {
                 const int j = lane + kWave * u;
@@ -230,11 +245,35 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                 if (src_row[i] && j < p.M)
                     v[i][u] = src_row[i][j];
             }
+            neg_u[i] = is_neg ? ref : kRefNone;
+            neg_key[i] = 0ull;
+            deg_lo[i] = deg_hi[i] = 0;
+            if (neg_u[i] != kRefNone) {  // (a valid node id: checked above)
+                if (rc.count > 0)
+                    neg_key[i] = rc.key[neg_u[i]];
+                deg_lo[i] = a.indptr[neg_u[i]];
+                deg_hi[i] = a.indptr[neg_u[i] + 1];
+            }
         }
+#pragma unroll
+        for (int i = 0; i < kRowsPerWave; ++i)
+            neg_ref[i] = neg_u[i] != kRefNone ? checked_ref(ref_of_key(rc, neg_u[i], neg_key[i])) : kRefNone;
 #pragma unroll
         for (int i = 0; i < kRowsPerWave; ++i) {
             const int r = wave + i * kEmbedWaves;
             if (r < ROWS) {
+                if (neg_ref[i] != neg_u[i]) {  // a negative this step updates: the staged row instead
+                    src_row[i] = row_ptr(neg_ref[i]);
+#pragma unroll
+                    for (int u = 0; u < kAhead; ++u) {
+                        const int j = lane + kWave * u;
+                        v[i][u] = src_row[i] && j < p.M ? src_row[i][j] : 0.0f;
+                    }
+                    if (lane == 0)
+                        row_ref[r] = neg_ref[i];
+                }
+                if (deg_hi[i] > deg_lo[i] && lane == 0)
+                    row_todo[r] = 1;  // (a negative: only those have a degree here)
                 char *dst = rowbuf + (size_t)r * p.row_bytes + mem_off;
 #pragma unroll
                 for (int u = 0; u < kAhead; ++u)
@@ -251,11 +290,24 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     // first in the set), so that wavefronts with short rows take more of them.  The neighbour table
     // of a row (slot k lives in lane k) is fetched when the row before it is started; the first
     // row's table is requested here, a phase early.
+    // Order: the negatives that still need their lookup first (the longest chain of dependent
+    // reads), then the other rows by index.
+    static_assert(ROWS < 64, "one mask bit per row");
+    const unsigned long long todo_mask = __ballot(lane < ROWS && row_todo[lane < ROWS ? lane : 0] != 0);
+    const unsigned long long rest_mask = ~todo_mask & ((1ull << ROWS) - 1ull);
+    const int n_todo = __popcll(todo_mask);
     auto grab = [&]() -> int {
-        int r = 0;
+        int pos = 0;
         if (lane == 0)
-            r = atomicAdd(next_row, 1);
-        return __builtin_amdgcn_readfirstlane(r);
+            pos = atomicAdd(next_row, 1);
+        pos = __builtin_amdgcn_readfirstlane(pos);
+        if (pos >= ROWS)
+            return ROWS;
+        const unsigned long long m = pos < n_todo ? todo_mask : rest_mask;
+        const int k = pos < n_todo ? pos : pos - n_todo;
+        const bool hit = ((m >> lane) & 1ull) != 0ull && __popcll(m & ((1ull << lane) - 1ull)) == k;
+        const unsigned long long h = __ballot(hit);  // exactly one lane: the k-th set bit of m
+        return h != 0ull ? __ffsll((long long)h) - 1 : ROWS;
     };
     auto load_nb = [&](int r, int32_t &v, int32_t &e, double &dt) {
         v = 0;
@@ -362,7 +414,24 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
             if (q_cur < 0)
                 continue;
             int cnt;
-            if (q_cur >= neg_row0) {
+            if (q_cur >= neg_row0 && !__builtin_amdgcn_readfirstlane(row_todo[r_cur])) {
+                // a negative without history: its (empty) row of the query set is written here, where
+                // nothing waits for the stores
+                if (lane < p.K) {
+                    const size_t o = (size_t)q_cur * p.K + lane;
+                    a.qs.nbr[o] = -1;
+                    a.qs.eid[o] = -1;
+                    a.qs.ts[o] = 0.0;
+                    a.qs.ref[o] = kRefNone;
+                }
+                if (lane == 0) {
+                    const int32_t u = a.neg[q_cur - neg_row0];
+                    a.qs.cnt[q_cur] = 0;
+                    a.qs.node[q_cur] = u >= 0 && (int64_t)u < a.num_nodes ? u : -1;
+                    a.qs.t[q_cur] = row_t[r_cur];
+                }
+                cnt = 0;
+            } else if (q_cur >= neg_row0) {
                 // a negative: its neighbours are looked up now (slot k lands in lane k)
                 double ts_k;
                 cnt = finish_negative(a, p.K, q_cur - neg_row0, nb_vc, nb_ec, ts_k);
@@ -858,7 +927,7 @@ const void *embed_kernel(const Dims &d, int mt)
 int embed_lds_bytes(const Dims &d, int mt)
 {
     const EmbedParams p = embed_params(d, mt);
-    return p.off_meta + 16 * mt * (3 * 4 + 8) + d.T * 16 + 16;
+    return p.off_meta + 16 * mt * (4 * 4 + 8) + d.T * 16 + 16;
 }
 
 // 16-row tiles per workgroup for `rows` query rows.  A workgroup's latency grows with its rows,

@@ -149,18 +149,23 @@ __device__ inline RefCtx ref_ctx(const StepArgs &a)
     return RefCtx{a.num_nodes, a.msg_key, a.msg_first_eid, a.msg_count};
 }
 
-__device__ inline int32_t resolve_ref(const RefCtx &c, int32_t v)
+// ... given key k = c.key[v] of a valid node v (any value if the step applies nothing)
+__device__ inline int32_t ref_of_key(const RefCtx &c, int32_t v, unsigned long long k)
 {
-    if (v < 0 || (int64_t)v >= c.num_nodes)
-        return kRefNone;
     if (c.count > 0) {
-        const unsigned long long k = c.key[v];
         const uint32_t low = (uint32_t)k;
         const int64_t e = (int64_t)(low >> 1);
         if (k != 0ull && e >= c.first_eid && e < c.first_eid + c.count)
             return ~(int32_t)(2 * (e - c.first_eid) + (low & 1u));
     }
     return v;
+}
+
+__device__ inline int32_t resolve_ref(const RefCtx &c, int32_t v)
+{
+    if (v < 0 || (int64_t)v >= c.num_nodes)
+        return kRefNone;
+    return ref_of_key(c, v, c.count > 0 ? c.key[v] : 0ull);
 }
 
 // The finishing pass of a batch's preparation, in three parts that share nothing:
