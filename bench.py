@@ -188,6 +188,52 @@ def mfma_flops(w, rows_u, winners, precision):
     return issued, useful
 
 
+def bench_sep(g, w, torch, num_parts=8, top_k=0.01, beta=1e-6):
+    """The partitioner over the whole stream: centrality kernel (HBM-bound: 16 bytes per event in,
+    8 bytes per node out), hub selection, and the sequential edge loop on the host; beside them the
+    oracle's edge loop on a bounded prefix of the stream."""
+    import numpy as np
+    from oracle import sep_oracle as PO
+    from paper_2308_14129_amd import sep
+    E, N = g.num_events, g.num_nodes
+    src_d, dst_d, ts_d = (torch.from_numpy(a).to("cuda:0") for a in (g.src, g.dst, g.ts))
+    for _ in range(2):
+        cent_d = sep.centrality(src_d, dst_d, ts_d, N, beta)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 5
+    e0.record()
+    for _ in range(reps):
+        cent_d = sep.centrality(src_d, dst_d, ts_d, N, beta)
+    e1.record()
+    torch.cuda.synchronize()
+    cent_ms = e0.elapsed_time(e1) / reps
+    n_hubs = int(np.floor(top_k * N))
+    t0 = time.perf_counter()
+    hubs_d, is_hub_d = sep.top_k(cent_d, n_hubs)
+    torch.cuda.synchronize()
+    topk_ms = (time.perf_counter() - t0) * 1e3
+    cent, is_hub = cent_d.cpu().numpy(), is_hub_d.cpu().numpy()
+    cfg = sep.make_config(num_parts, beta, top_k, 1.0, 1e-3)
+    t0 = time.perf_counter()
+    part, node_parts, part_edges = sep.assign(cfg, g.src, g.dst, N, cent, is_hub)
+    assign_s = time.perf_counter() - t0
+    n_or = min(E, 200_000)
+    t0 = time.perf_counter()
+    PO.assign_stream(g.src[:n_or], g.dst[:n_or], N, cent, np.flatnonzero(is_hub), num_parts, 1.0, 1e-3)
+    oracle_s = time.perf_counter() - t0
+    cent_bytes = 16.0 * E + 16.0 * N  # events in; node array cleared and written
+    bits = np.unpackbits(node_parts.view(np.uint8).reshape(-1, 8), axis=1).sum(axis=1)
+    return {"num_parts": num_parts, "top_k": top_k, "beta": beta,
+            "centrality_ms": round(cent_ms, 3), "centrality_GBps": round(cent_bytes / cent_ms / 1e6, 1),
+            "centrality_frac_of_hbm_peak": round(cent_bytes / cent_ms / 1e6 / HBM_PEAK_GBS, 4),
+            "top_k_ms": round(topk_ms, 2),
+            "assign_edges_per_s": round(E / assign_s, 1), "assign_s": round(assign_s, 2),
+            "oracle_assign_edges_per_s": round(n_or / oracle_s, 1), "oracle_sample_edges": n_or,
+            "edge_cut": round(float(np.mean(part < 0)), 5), "shared_nodes": int((bits > 1).sum()),
+            "part_edges_min_max": [int(part_edges.min()), int(part_edges.max())]}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -208,6 +254,9 @@ def main():
     ap.add_argument("--ceilings", action="store_true",
                     help="also time a plain 1 GiB device copy (read + write) and report the measured "
                          "HBM bandwidth of this GPU beside the published peak")
+    ap.add_argument("--sep", action="store_true",
+                    help="also run the streaming edge partitioner (Sec. II-B) over the workload's whole event "
+                         "stream (8 partitions, 1 %% hubs) and report its stages in a \"sep\" object")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1",
@@ -383,6 +432,10 @@ def main():
         del src_buf, dst_buf
         roofline["measured_copy_GBps"] = measured_copy_gbs
 
+    sep_report = None
+    if args.sep:
+        sep_report = bench_sep(g, w, torch)
+
     info = ctx.launch_info()
     line = {
         "metric": "events/sec per TGN batch step (1 MI355X)",
@@ -410,6 +463,8 @@ def main():
         "stages": stages,
         "cpu_baseline": cpu,
     }
+    if sep_report is not None:
+        line["sep"] = sep_report
     ctx.close()
     print(json.dumps(line), flush=True)
 

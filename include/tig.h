@@ -264,6 +264,70 @@ TIG_API const char *tig_last_error(const tig_ctx *ctx);
 TIG_API int tig_launch_info(const tig_ctx *ctx, int32_t *kernels_per_step, int32_t *gru_lds_bytes,
                             int32_t *embed_lds_bytes);
 
+/* ------------------------------------------------------------------------------------------
+ * Streaming edge partitioner (Sec. II-B "Streaming Edge Partitioning Component", Alg. 1): the
+ * preprocessing step that cuts the event stream into the per-GPU sub-graphs.  Independent of any
+ * tig_ctx.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct tig_sep_config {
+    uint32_t struct_size;
+    int32_t num_parts;   /* |P|, 1..64 */
+    double beta;         /* time-decay rate of Eq. 1, >= 0 */
+    double top_k;        /* fraction k of the nodes that may be replicated (the hubs), 0..1 */
+    double lambda;       /* weight of the balance term, Eq. 6, > 0 */
+    double epsilon;      /* added to the denominator of Eq. 6, > 0 */
+} tig_sep_config;
+
+/*
+ * Node centrality with exponential time decay (Eq. 1): cent_out[i] = sum over the events incident
+ * to node i of exp(beta * (t - t_max)), t_max = ts[num_events - 1] (the stream is chronological).
+ * src, dst [E] int32, ts [E] fp64, cent_out [N] fp64: device pointers.  Enqueued on hip_stream
+ * (one small synchronous read of t_max aside).  The per-node sums are accumulated with fp64
+ * atomics, so their last bits depend on the order the device happened to add in.
+ * Events with an endpoint outside 0..N-1 are skipped.
+ */
+TIG_API int tig_sep_centrality(const int32_t *src, const int32_t *dst, const double *ts, int64_t num_events,
+                               int64_t num_nodes, double beta, double *cent_out, void *hip_stream);
+
+/*
+ * The hubs of Alg. 1 (first step): the n_hubs nodes of greatest centrality, equal centralities in
+ * order of node id.  cent [N] fp64, hubs_out [n_hubs] int32 (by rank), is_hub_out [N] bytes (1 for a
+ * hub), scratch (256-byte aligned, tig_sep_topk_scratch_bytes(N) bytes): device pointers.
+ * TIG_ENOSPACE if scratch is too small.  Enqueued on hip_stream.
+ */
+TIG_API size_t tig_sep_topk_scratch_bytes(int64_t num_nodes);
+TIG_API int tig_sep_top_k(const double *cent, int64_t num_nodes, int64_t n_hubs, int32_t *hubs_out,
+                          uint8_t *is_hub_out, void *scratch, size_t scratch_bytes, void *hip_stream);
+
+/*
+ * The edge loop of Alg. 1 (cases 1-5 with the score C = C_REP + C_BAL of Eq. 2-6).  Every
+ * decision depends on all earlier ones: sequential, on the host; ALL pointers are host pointers.
+ *   edge_part_out [E]   partition the edge went to, -1 for a discarded edge (Case 3)
+ *   node_parts_out [N]  bit p set: the node has a replica in partition p (the set A(i) of Alg. 1).
+ *                       A node with more than one bit is a shared node; the node loop of Alg. 1
+ *                       then lists it in every partition (the caller's part, from this mask).
+ *   part_edges_out [|P|] edges per partition (the |p| of Eq. 6)
+ * Readings: |p| counts edges; a resident non-hub is never replicated, so its partition is the
+ * only candidate whenever it is an endpoint; the arg max takes the lowest index among equal
+ * scores.  TIG_ERANGE if an endpoint is outside 0..N-1 (outputs are then partial).
+ */
+TIG_API int tig_sep_assign(const tig_sep_config *cfg, const int32_t *src, const int32_t *dst, int64_t num_events,
+                           int64_t num_nodes, const double *cent, const uint8_t *is_hub, int32_t *edge_part_out,
+                           uint64_t *node_parts_out, int64_t *part_edges_out);
+
+/*
+ * All of Alg. 1 up to the node masks: centrality and hubs (floor(top_k * N) of them) on the
+ * device, then the edge loop on the host.  src, dst, ts: device pointers; scratch: device,
+ * 256-byte aligned, tig_sep_scratch_bytes(N) bytes; every output is a HOST pointer (cent_out [N],
+ * is_hub_out [N], the rest as in tig_sep_assign).  Synchronous; allocates host staging for the
+ * endpoint arrays (TIG_ENOMEM if that fails).
+ */
+TIG_API size_t tig_sep_scratch_bytes(int64_t num_nodes);
+TIG_API int tig_sep_partition(const tig_sep_config *cfg, const int32_t *src, const int32_t *dst, const double *ts,
+                              int64_t num_events, int64_t num_nodes, void *scratch, size_t scratch_bytes,
+                              void *hip_stream, double *cent_out, uint8_t *is_hub_out, int32_t *edge_part_out,
+                              uint64_t *node_parts_out, int64_t *part_edges_out);
+
 #ifdef __cplusplus
 }
 #endif
