@@ -25,7 +25,7 @@ from collections import defaultdict
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-STEP_KERNELS = ("k_scatter", "k_select", "k_prepare", "k_gru", "k_embed")
+STEP_KERNELS = ("k_scatter", "k_select", "k_prepare", "k_gru", "k_embed", "k_centrality", "k_topk_keys", "k_topk_flags")
 COPY_KIB = 256 * 1024  # one calibration copy reads and writes this much
 XCDS = 8                # accelerator dies of one MI355X
 
