@@ -328,6 +328,74 @@ TIG_API int tig_sep_partition(const tig_sep_config *cfg, const int32_t *src, con
                               void *hip_stream, double *cent_out, uint8_t *is_hub_out, int32_t *edge_part_out,
                               uint64_t *node_parts_out, int64_t *part_edges_out);
 
+/* ------------------------------------------------------------------------------------------
+ * Epoch machinery of parallel training on partitions, as one GPU sees it when it holds several
+ * partitions at once (Sec. II-C "Distributed Parallel Training", Alg. 2).
+ * ------------------------------------------------------------------------------------------ */
+
+/*
+ * Shuffle-and-combine: the |P| small parts, in the caller's shuffled `order` (a permutation of
+ * 0..num_parts-1), are joined num_parts / num_groups at a time into num_groups groups;
+ * group_masks_out[g] has the bits of group g's parts.  Host pointers.  TIG_EINVAL if num_groups does
+ * not divide num_parts or `order` is not a permutation.
+ */
+TIG_API int tig_pac_combine(const int32_t *order, int32_t num_parts, int32_t num_groups, uint64_t *group_masks_out);
+
+/*
+ * Sub-graph of the (combined) partition `group`: E_k = {(i, j, t) in E | i, j in V_k}, where V_k
+ * holds the nodes with a replica in one of the group's parts and every shared node (a node with
+ * more than one bit in node_parts, tig_sep_assign's output).
+ *   src, dst [E], node_parts [N]: device;  eid_out [E] (capacity): the event ids of E_k in
+ *   chronological order;  local_out [N]: rank of the node among the members of V_k in id order, -1
+ *   for a non-member;  counts_out (HOST) [2]: |E_k|, |V_k|;  scratch: device, 256-byte aligned,
+ *   tig_pac_scratch_bytes(E, N) bytes (TIG_ENOSPACE if smaller).  Synchronous.
+ */
+TIG_API size_t tig_pac_scratch_bytes(int64_t num_events, int64_t num_nodes);
+TIG_API int tig_pac_subgraph(const int32_t *src, const int32_t *dst, int64_t num_events, const uint64_t *node_parts,
+                             int64_t num_nodes, uint64_t group, int32_t *eid_out, int32_t *local_out,
+                             int64_t *counts_out, void *scratch, size_t scratch_bytes, void *hip_stream);
+
+/*
+ * The sub-graph's event arrays from the whole graph's (all device pointers): for n event ids,
+ * endpoints relabelled through `local`, times, and feature rows [n x feat_dim].  Enqueued.
+ */
+TIG_API int tig_pac_gather(const int32_t *src, const int32_t *dst, const double *ts, const float *edge_feat,
+                           int32_t feat_dim, const int32_t *eid, int64_t n, const int32_t *local, int32_t *src_out,
+                           int32_t *dst_out, double *ts_out, float *feat_out, void *hip_stream);
+
+/* One resident partition of an epoch: a context over its sub-graph and what its steps need. */
+typedef struct tig_pac_part {
+    uint32_t struct_size;
+    int32_t batch;              /* events per step, 1..max_batch of the context */
+    tig_ctx *ctx;
+    int64_t num_events;         /* events of the sub-graph that take part (a prefix of the context's) */
+    const int32_t *neg_dst;     /* device [num_events]: one negative per event, or NULL */
+    float *backup_mem;          /* device [N_k x M]: the partition's memory backup */
+    double *backup_lu;          /* device [N_k] */
+    const tig_out *out;         /* outputs of the partition's steps (overwritten by every step) */
+} tig_pac_part;
+
+/*
+ * One epoch of Alg. 2 over the resident partitions, in lock step: every partition cycles over its
+ * own batches (memory reset at the start of a data cycle, backup at the end of one) until the
+ * partition with the most batches has finished a cycle (*steps_out, may be NULL, = that number of
+ * steps); then every partition's memory is restored from its latest backup.  Uses tig_reset,
+ * tig_step, tig_state_export and tig_state_import of the contexts; synchronous.
+ */
+TIG_API int tig_pac_epoch(tig_pac_part *parts, int32_t n_parts, int64_t *steps_out);
+
+/*
+ * Memory synchronisation of the shared nodes across resident partitions (end of Sec. II-C):
+ * local_ids (HOST array of n_parts DEVICE pointers) gives, for shared node s, its row
+ * local_ids[k][s] in partition k.  mode 0: every replica takes the row and the last-update time of
+ * the partition with the largest last-update time (the lowest partition among equal times);
+ * mode 1: the mean of the rows (summed in partition order, fp32) and the largest time.  The
+ * contexts must share memory width and stream and be distinct; ids of one partition must be
+ * distinct; at most 32 partitions.  A node with an id outside a partition is left alone.  Enqueued.
+ */
+TIG_API int tig_pac_sync_shared(tig_ctx *const *ctxs, int32_t n_parts, const int32_t *const *local_ids,
+                                int64_t n_shared, int32_t mode);
+
 #ifdef __cplusplus
 }
 #endif

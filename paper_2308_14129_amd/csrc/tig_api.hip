@@ -312,6 +312,14 @@ thread_local char g_init_err[256] = "";
 
 }  // namespace
 
+namespace tig {
+int fail_global(const char *what, hipError_t e)
+{
+    snprintf(g_init_err, sizeof(g_init_err), "%s: %s", what, hipGetErrorString(e));
+    return TIG_EHIP;
+}
+}  // namespace tig
+
 extern "C" {
 
 int tig_workspace_bytes(const tig_config *cfg, const tig_graph *graph, size_t *persistent_bytes,
@@ -824,6 +832,89 @@ int tig_state_import(tig_ctx *ctx, const float *mem_in, const double *last_updat
     if (e != hipSuccess)
         return fail(ctx, TIG_EHIP, "tig_state_import", e);
     ctx->cursor = 0;
+    return TIG_OK;
+}
+
+// ---- epoch machinery on one GPU (Sec. II-C "Distributed Parallel Training", Alg. 2) -------------
+
+int tig_pac_epoch(tig_pac_part *parts, int32_t n_parts, int64_t *steps_out)
+{
+    if (!parts || n_parts < 1)
+        return TIG_EINVAL;
+    int64_t most = 0;
+    for (int k = 0; k < n_parts; ++k) {
+        tig_pac_part &p = parts[k];
+        if (p.struct_size != sizeof(tig_pac_part) || !p.ctx || !p.out || !p.backup_mem || !p.backup_lu)
+            return TIG_EINVAL;
+        if (p.batch < 1 || p.batch > p.ctx->d.max_batch || p.num_events < 1 || p.num_events > p.ctx->num_events)
+            return fail(p.ctx, TIG_EINVAL, "tig_pac_epoch: batch or num_events outside the context's limits");
+        const int64_t nb = (p.num_events + p.batch - 1) / p.batch;
+        most = nb > most ? nb : most;
+    }
+    // Every partition cycles over its own batches until the one with the most batches has finished a
+    // data cycle: memory reset at the start of a cycle, backup at its end (Alg. 2).
+    for (int64_t step = 0; step < most; ++step) {
+        for (int k = 0; k < n_parts; ++k) {
+            tig_pac_part &p = parts[k];
+            const int64_t nb = (p.num_events + p.batch - 1) / p.batch;
+            const int64_t i = step % nb;
+            int rc = TIG_OK;
+            if (i == 0)
+                rc = tig_reset(p.ctx);
+            if (rc != TIG_OK)
+                return rc;
+            tig_batch b;
+            b.struct_size = sizeof(tig_batch);
+            b.first_eid = i * p.batch;
+            const int64_t left = p.num_events - b.first_eid;
+            b.count = (int32_t)(left < p.batch ? left : p.batch);
+            b.neg_dst = p.neg_dst ? p.neg_dst + b.first_eid : nullptr;
+            if ((rc = step_impl(p.ctx, &b, p.out, nullptr)) != TIG_OK)
+                return rc;
+            if (i == nb - 1 && (rc = tig_state_export(p.ctx, p.backup_mem, p.backup_lu)) != TIG_OK)
+                return rc;
+        }
+    }
+    // end of the epoch: every memory goes back to its latest backup, the end of a complete cycle
+    for (int k = 0; k < n_parts; ++k) {
+        const int rc = tig_state_import(parts[k].ctx, parts[k].backup_mem, parts[k].backup_lu);
+        if (rc != TIG_OK)
+            return rc;
+    }
+    if (steps_out)
+        *steps_out = most;
+    return TIG_OK;
+}
+
+int tig_pac_sync_shared(tig_ctx *const *ctxs, int32_t n_parts, const int32_t *const *local_ids, int64_t n_shared,
+                        int32_t mode)
+{
+    if (!ctxs || n_parts < 1 || n_parts > kMaxSyncParts || !local_ids || n_shared < 0 || (mode != 0 && mode != 1))
+        return TIG_EINVAL;
+    SyncArgs a;
+    memset(&a, 0, sizeof(a));
+    for (int k = 0; k < n_parts; ++k) {
+        if (!ctxs[k] || !local_ids[k])
+            return TIG_EINVAL;
+        if (ctxs[k]->d.M != ctxs[0]->d.M || ctxs[k]->stream != ctxs[0]->stream)
+            return fail(ctxs[k], TIG_EINVAL, "tig_pac_sync_shared: contexts differ in memory width or stream");
+        for (int j = 0; j < k; ++j)
+            if (ctxs[j] == ctxs[k])
+                return TIG_EINVAL;
+        a.mem[k] = ctxs[k]->mem;
+        a.lu[k] = ctxs[k]->lu;
+        a.ids[k] = local_ids[k];
+        a.num_nodes[k] = ctxs[k]->num_nodes;
+    }
+    a.n_parts = n_parts;
+    a.M = ctxs[0]->d.M;
+    a.mode = mode;
+    a.n_shared = n_shared;
+    const hipError_t e = launch_sync_shared(a, ctxs[0]->stream);
+    for (int k = 0; k < n_parts; ++k)
+        ctxs[k]->ahead_g_valid = false;  // staged GRU rows were computed from the memory before the exchange
+    if (e != hipSuccess)
+        return fail(ctxs[0], TIG_EHIP, "tig_pac_sync_shared", e);
     return TIG_OK;
 }
 

@@ -250,4 +250,18 @@ hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeight
                        const StepArgs &a, const StepPlan &sp, hipStream_t s, hipEvent_t *marks);
 hipError_t launch_fill_zero(void *ptr, size_t bytes, hipStream_t s);
 
+// Memory synchronisation of shared nodes across the partitions resident on one GPU.
+constexpr int kMaxSyncParts = 32;
+struct SyncArgs {
+    float *mem[kMaxSyncParts];
+    double *lu[kMaxSyncParts];
+    const int32_t *ids[kMaxSyncParts];  // [n_shared] row of shared node s in partition k
+    int64_t num_nodes[kMaxSyncParts];
+    int32_t n_parts, M, mode;           // mode 0: the row with the largest last-update time, 1: the mean
+    int64_t n_shared;
+};
+hipError_t launch_sync_shared(const SyncArgs &a, hipStream_t s);
+// records a failed HIP call of a context-free entry point (read back with tig_last_error(NULL)); returns TIG_EHIP
+int fail_global(const char *what, hipError_t e);
+
 }  // namespace tig

@@ -47,7 +47,8 @@ def _lib():
 
 def _check(rc):
     if rc != tig.TIG_OK:
-        raise tig.TigError(rc, tig.load_library().tig_strerror(rc).decode())
+        lib = tig.load_library()
+        raise tig.TigError(rc, lib.tig_strerror(rc).decode() + " / " + lib.tig_last_error(None).decode())
 
 
 def _ptr(a: np.ndarray):

@@ -76,6 +76,9 @@ def load_library() -> ctypes.CDLL:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2308_14129_amd.build`")
+    # PyTorch supplies the device memory, so its HIP runtime must be the one this process uses: it
+    # is loaded first, and the library's own dependency on the runtime then resolves to it.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     lib.tig_workspace_bytes.argtypes = [POINTER(tig_config), POINTER(tig_graph), POINTER(c_size_t),
                                         POINTER(c_size_t)]

@@ -18,21 +18,22 @@ def lib():
 
 
 def test_header_symbols_are_exported(lib):
-    from paper_2308_14129_amd import sep, tig
+    from paper_2308_14129_amd import pac, sep, tig
     header = open(os.path.join(ROOT, "include", "tig.h")).read()
     declared = set(re.findall(r"TIG_API\s+[\w\s\*]+?\b(tig_\w+)\s*\(", header))
-    assert declared == set(tig.EXPORTS) | set(sep.EXPORTS)
+    assert declared == set(tig.EXPORTS) | set(sep.EXPORTS) | set(pac.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
 
 
 def test_struct_sizes_match_header_layout():
-    from paper_2308_14129_amd import tig
+    from paper_2308_14129_amd import pac, sep, tig
     assert ctypes.sizeof(tig.tig_config) == 40
     assert ctypes.sizeof(tig.tig_graph) == 56
     assert ctypes.sizeof(tig.tig_weights) == 8 + 22 * 8
     assert ctypes.sizeof(tig.tig_batch) == 24
     assert ctypes.sizeof(tig.tig_out) == 8 + 8 * 8
+    assert ctypes.sizeof(sep.tig_sep_config) == 40 and ctypes.sizeof(pac.tig_pac_part) == 56
 
 
 def test_strerror_and_host_side_validation(lib):

@@ -71,3 +71,15 @@ def test_assign_rejects_bad_arguments(sep):
     with pytest.raises(tig.TigError) as ei:
         sep.assign(sep.make_config(2, 0.1, 0.0), [0, 5], [1, 2], 3, [1.0] * 3, [0] * 3)
     assert ei.value.status == tig.TIG_ERANGE
+
+
+def test_combine_host_call():
+    from paper_2308_14129_amd import pac, tig
+    from oracle import pac_oracle as E
+    order = np.random.default_rng(11).permutation(8)
+    assert pac.combine(order, 4) == E.combine(order, 4)
+    assert pac.combine(order, 8) == [1 << int(p) for p in order]
+    assert pac.combine(order, 1) == [0xFF]
+    for bad in (([0, 1, 2], 2), ([0, 0, 1, 2], 2), ([0, 1, 2, 7], 2)):
+        with pytest.raises(tig.TigError):
+            pac.combine(*bad)
