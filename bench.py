@@ -222,6 +222,16 @@ def bench_sep(g, w, torch, num_parts=8, top_k=0.01, beta=1e-6):
     t0 = time.perf_counter()
     PO.assign_stream(g.src[:n_or], g.dst[:n_or], N, cent, np.flatnonzero(is_hub), num_parts, 1.0, 1e-3)
     oracle_s = time.perf_counter() - t0
+    # sub-graph of one of two combined partitions (parts 0-3 of the 8): order-preserving compaction of
+    # the event stream; reads both endpoint arrays twice (count, write), writes the kept event ids
+    from paper_2308_14129_amd import pac
+    masks_d = torch.from_numpy(node_parts.view(np.int64)).to("cuda:0")
+    pac.subgraph(src_d, dst_d, masks_d, 0x0F)
+    t0 = time.perf_counter()
+    eid_k, _, n_k = pac.subgraph(src_d, dst_d, masks_d, 0x0F)
+    torch.cuda.synchronize()
+    sub_ms = (time.perf_counter() - t0) * 1e3
+    sub_bytes = 16.0 * E + 4.0 * eid_k.numel() + 12.0 * N
     cent_bytes = 16.0 * E + 16.0 * N  # events in; node array cleared and written
     bits = np.unpackbits(node_parts.view(np.uint8).reshape(-1, 8), axis=1).sum(axis=1)
     return {"num_parts": num_parts, "top_k": top_k, "beta": beta,
@@ -230,7 +240,9 @@ def bench_sep(g, w, torch, num_parts=8, top_k=0.01, beta=1e-6):
             "top_k_ms": round(topk_ms, 2),
             "assign_edges_per_s": round(E / assign_s, 1), "assign_s": round(assign_s, 2),
             "oracle_assign_edges_per_s": round(n_or / oracle_s, 1), "oracle_sample_edges": n_or,
-            "edge_cut": round(float(np.mean(part < 0)), 5), "shared_nodes": int((bits > 1).sum()),
+            "subgraph_ms": round(sub_ms, 3), "subgraph_GBps": round(sub_bytes / sub_ms / 1e6, 1),
+            "subgraph_events": int(eid_k.numel()), "subgraph_nodes": n_k,
+            "edge_cut": round(float(np.mean(part < 0)), 7), "shared_nodes": int((bits > 1).sum()),
             "part_edges_min_max": [int(part_edges.min()), int(part_edges.max())]}
 
 
