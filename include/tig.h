@@ -238,6 +238,40 @@ TIG_API int tig_step_profiled(tig_ctx *ctx, const tig_batch *batch, const tig_ou
 #define TIG_STATIC_SCRATCH_BYTES (32u << 20)
 TIG_API int tig_step_static(tig_ctx *ctx, const tig_batch *batch, const tig_out *out);
 
+/* ------------------------------------------------------------------------------------------
+ * Training step (Sec. II-C: the decoder's edge probabilities provide the self-supervised signal;
+ * Alg. 2: "Training and compute loss", "Backward and Optimize").  fp32 contexts only.
+ *   loss  = mean_b softplus(-score_pos[b]) + mean_b softplus(score_neg[b])   (binary cross-entropy
+ *           on the logits; the paper names neither loss nor optimiser: this build's reading)
+ *   the node memory is a constant of the step: gradients reach the GRU (and, through its message,
+ *   the time encoding) only through the memory rows that the step itself overwrites and its
+ *   embeddings then read; edge features take no gradient
+ *   update: W <- W - lr * dL/dW on fp32 master copies of the weights (plain SGD); the prepared
+ *   weights that tig_step reads are rebuilt from the masters afterwards
+ * ------------------------------------------------------------------------------------------ */
+
+/* Size of the training workspace of a configuration (device memory the caller allocates):
+ * master weights, gradients and the buffers of the backward pass, about
+ * 12 * max_batch * num_neighbors * (mem + feat + time + 4 * (mem + time)) bytes.
+ * TIG_EINVAL for a precision other than TIG_FP32 or a row shape the backward kernels cannot hold. */
+TIG_API int tig_train_workspace_bytes(const tig_config *cfg, size_t *bytes);
+
+/* Makes a context trainable: `weights` (host or device, as in tig_init; normally the same values)
+ * become the master weights in `workspace` (device, 256-byte aligned, owned by the caller until
+ * tig_destroy), and the context's prepared weights are rebuilt from them.  Synchronous. */
+TIG_API int tig_train_attach(tig_ctx *ctx, const tig_weights *weights, void *workspace, size_t workspace_bytes);
+
+/* One training step on a batch: the step of tig_step (same outputs, same state update, in the
+ * context's message order), the loss, the gradient of every weight, and the SGD update with
+ * learning rate lr >= 0 (0: gradients only, weights untouched).  batch->neg_dst is required.
+ * loss_out: device pointer to one float, or NULL.  Enqueued on the context's stream.  The call
+ * prepares its batch itself and leaves nothing prepared for a following call. */
+TIG_API int tig_train_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, float lr, float *loss_out);
+
+/* Copies the master weights (what = 0) or the gradients of the last training step (what = 1) to
+ * the non-NULL pointers of `dst` (host or device), laid out as in tig_weights.  Synchronous. */
+TIG_API int tig_train_get(tig_ctx *ctx, int32_t what, const tig_weights *dst);
+
 /* Memory reset at the start of a data cycle (Alg. 2): memory <- 0, last_update <- 0. Async. */
 TIG_API int tig_reset(tig_ctx *ctx);
 

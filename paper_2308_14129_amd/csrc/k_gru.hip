@@ -414,7 +414,7 @@ hipError_t launch_gru(const Dims &d, const LaunchPlan &plan, const PackedWeights
 // finishing pass of the batch prepared ahead; its own query set's counter is cleared for the
 // set's next preparation; and, if ahead.count > 0, the GRU of the batch the next step applies.
 hipError_t launch_closing(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
-                          const GruAhead &ahead, hipStream_t s)
+                          const GruAhead &ahead, hipStream_t s, bool events)
 {
     StepArgs aa = a;
     PackedWeights ww = pw;
@@ -424,7 +424,7 @@ hipError_t launch_closing(const Dims &d, const LaunchPlan &plan, const PackedWei
         size_gru(d, plan, ahead.count, a.wins_est, &g);
     g.clear = a.qs.n_u;
     DecodeParams p = no_closing(d);
-    p.n_event_blocks = (a.count + kGruWaves - 1) / kGruWaves;
+    p.n_event_blocks = events ? (a.count + kGruWaves - 1) / kGruWaves : 0;  // (a training step decodes itself)
     const bool expand = a.out_nbr_node || a.out_nbr_eid || a.out_nbr_ts || a.out_nbr_cnt || a.out_is_winner;
     p.n_expand_blocks = expand ? (a.roles * a.count + kGruWaves - 1) / kGruWaves : 0;
     if (a.fin_count > 0) {
@@ -433,7 +433,8 @@ hipError_t launch_closing(const Dims &d, const LaunchPlan &plan, const PackedWei
             p.n_fin_row_blocks = 128;
         p.n_fin_slot_blocks = (2 * a.fin_count + kGruThreads - 1) / kGruThreads;
     }
-    const int blocks = g.n_gru + p.n_event_blocks + p.n_expand_blocks + p.n_fin_row_blocks + p.n_fin_slot_blocks;
+    int blocks = g.n_gru + p.n_event_blocks + p.n_expand_blocks + p.n_fin_row_blocks + p.n_fin_slot_blocks;
+    blocks = blocks > 0 ? blocks : 1;  // (block 0 clears the counter whatever else there is to do)
     void *args[] = {&aa, &gj, &ww, &g, &p};
     return hipLaunchKernel(gru_kernel(d), dim3(blocks), dim3(kGruThreads), args, (size_t)gru_lds_bytes(d), s);
 }

@@ -76,6 +76,15 @@ hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeight
         return e;
     if ((e = stamp()) != hipSuccess)
         return e;
+    if (sp.train) {
+        if ((e = launch_train(d, a, sp.train_ws, sp.packed, sp.pw_out, sp.lr, sp.loss_out, s)) != hipSuccess ||
+            (e = stamp()) != hipSuccess)
+            return e;
+        // inspection outputs, and the query set's counter cleared for its next preparation
+        if ((e = launch_closing(d, plan, *sp.pw_out, a, GruAhead{}, s, false)) != hipSuccess || (e = stamp()) != hipSuccess)
+            return e;
+        return hipSuccess;
+    }
     if ((e = launch_embed(d, plan, pw, a, s)) != hipSuccess || (e = stamp()) != hipSuccess)
         return e;
     if ((e = launch_closing(d, plan, pw, a, sp.ahead, s)) != hipSuccess || (e = stamp()) != hipSuccess)

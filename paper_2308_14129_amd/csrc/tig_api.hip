@@ -85,6 +85,7 @@ struct tig_ctx {
     int64_t cursor;    // end of the last batch stepped since the last reset / import
     int last_launches; // kernels enqueued by the last tig_step
     void *static_scratch;  // this device's copy of g_static_scratch
+    void *train_ws;        // training workspace (master weights, gradients, the backward pass's buffers), or NULL
     // Two pinned host words that the device can write: every step leaves its numbers of distinct
     // query rows and of winners there, and later calls shape their launches by them (hints that
     // may be a few steps old; results do not depend on them).  NULL if the allocation failed.
@@ -500,8 +501,13 @@ static DedupJob make_dedup(const StepScratch &S, const QuerySet &qs, int64_t fir
 // `use_static`: every per-step intermediate lives in this device's static scratch array instead of
 // the context's scratch workspace, the call prepares everything itself (winners, queries), and
 // nothing is kept there for a later call.
+struct TrainCall {
+    float lr;
+    float *loss_out;
+};
+
 static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, hipEvent_t *marks,
-                     bool use_static = false)
+                     bool use_static = false, const TrainCall *train = nullptr)
 {
     if (!ctx)
         return TIG_EINVAL;
@@ -567,7 +573,8 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
 
     // What the embedding launch can do on the side for a later step (never for a static call).
     const bool one_wg = winners_in_one_launch(count);
-    const int spare = use_static ? 0 : embed_spare_workgroups(d, ctx->plan, a.roles, count);
+    // (a training step prepares nothing for a later step and takes nothing prepared for it)
+    const int spare = use_static || train ? 0 : embed_spare_workgroups(d, ctx->plan, a.roles, count);
     uint32_t epoch = ctx->epoch;
     bool clear_tab = use_static;  // the static array's table holds claims of unknown epochs
     auto next_epoch = [&]() -> uint32_t {
@@ -587,7 +594,7 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
 
     // ---- the distinct queries of this batch: prepared by the previous step's embedding launch if
     // that step guessed this batch (it reads the event stream and the adjacency only), else now
-    const bool q_ready = !use_static && ctx->ahead_q_valid && ctx->ahead_q_first == first &&
+    const bool q_ready = !use_static && !train && ctx->ahead_q_valid && ctx->ahead_q_first == first &&
                          ctx->ahead_q_count == count;
     const int qi = use_static ? 0 : (q_ready ? ctx->qcur ^ 1 : ctx->qcur);
     a.qs = st.qs[qi];
@@ -602,7 +609,8 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     bool w_ready = false;
     if (!d.deferred) {
         // this batch's: selected ahead like the queries, else now
-        w_ready = !use_static && ctx->ahead_w_valid && ctx->ahead_w_first == first && ctx->ahead_w_count == count;
+        w_ready = !use_static && !train && ctx->ahead_w_valid && ctx->ahead_w_first == first &&
+                  ctx->ahead_w_count == count;
         wi = use_static ? 0 : (w_ready ? ctx->wcur ^ 1 : ctx->wcur);
         a.msg_first_eid = first;
         a.msg_count = count;
@@ -674,7 +682,7 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     // ---- The closing launch also runs the GRU of the batch the next step applies, once that batch's
     // winners are known: in the update-first order the guessed batch (selected by this step's
     // embedding launch), in the deferred order this step's own batch (whatever comes next).
-    if (!use_static) {
+    if (!use_static && !train) {
         if (!d.deferred && a.sel.count > 0)
             sp.ahead = GruAhead{a.sel.first_eid, a.sel.count, st.win[wi ^ 1], st.n_win[wi ^ 1]};
         else if (d.deferred)
@@ -687,6 +695,14 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
             return fail(ctx, TIG_EHIP, "tig_step: clearing the claim table", e);
     }
 
+    if (train) {
+        sp.train = true;
+        sp.train_ws = ctx->train_ws;
+        sp.packed = ctx->packed;
+        sp.pw_out = &ctx->pw;
+        sp.lr = train->lr;
+        sp.loss_out = train->loss_out;
+    }
     const hipError_t e = launch_step(d, ctx->plan, ctx->pw, a, sp, ctx->stream, marks);
     if (e != hipSuccess) {
         // kernels of this step may already be enqueued: nothing prepared ahead is trusted any more,
@@ -734,6 +750,75 @@ int tig_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *out)
 int tig_step_static(tig_ctx *ctx, const tig_batch *batch, const tig_out *out)
 {
     return step_impl(ctx, batch, out, nullptr, true);
+}
+
+// ---- training (Sec. II-C self-supervised signal; Alg. 2 "Backward and Optimize") ---------------
+
+int tig_train_workspace_bytes(const tig_config *cfg, size_t *bytes)
+{
+    const int rc = check_config(cfg);
+    if (rc != TIG_OK)
+        return rc;
+    if (!bytes)
+        return TIG_EINVAL;
+    const Dims d = make_dims(*cfg);
+    if (!train_supported(d))
+        return TIG_EINVAL;
+    *bytes = train_workspace_bytes(d);
+    return TIG_OK;
+}
+
+int tig_train_attach(tig_ctx *ctx, const tig_weights *weights, void *workspace, size_t workspace_bytes)
+{
+    if (!ctx)
+        return TIG_EINVAL;
+    if (!weights || weights->struct_size != sizeof(tig_weights) || !workspace || ((uintptr_t)workspace & 255))
+        return fail(ctx, TIG_EINVAL, "tig_train_attach: NULL / misaligned argument or wrong struct_size");
+    WeightField wf[32];
+    const int nwf = weight_fields(ctx->d, wf);
+    for (int i = 0; i < nwf; ++i)
+        if (!(weights->*(wf[i].member)))
+            return fail(ctx, TIG_EINVAL, "tig_train_attach: a weight pointer is NULL");
+    if (!train_supported(ctx->d))
+        return fail(ctx, TIG_EINVAL, "tig_train_attach: training needs an fp32 context whose rows fit the backward kernels");
+    if (workspace_bytes < train_workspace_bytes(ctx->d))
+        return fail(ctx, TIG_ENOSPACE, "tig_train_attach: workspace too small");
+    hipError_t e = prepare_train(ctx->d);
+    if (e == hipSuccess)
+        e = train_attach(ctx->d, *weights, workspace, ctx->packed, &ctx->pw, ctx->stream);
+    if (e == hipSuccess)
+        e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess)
+        return fail(ctx, TIG_EHIP, "tig_train_attach", e);
+    ctx->train_ws = workspace;
+    ctx->ahead_g_valid = false;  // staged rows of another set of weights
+    return TIG_OK;
+}
+
+int tig_train_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, float lr, float *loss_out)
+{
+    if (!ctx)
+        return TIG_EINVAL;
+    if (!ctx->train_ws)
+        return fail(ctx, TIG_EINVAL, "tig_train_step: no training workspace attached (tig_train_attach)");
+    if (!batch || batch->struct_size != sizeof(tig_batch) || !batch->neg_dst)
+        return fail(ctx, TIG_EINVAL, "tig_train_step: the loss needs one negative per event");
+    if (!(lr >= 0.0f))
+        return fail(ctx, TIG_EINVAL, "tig_train_step: negative learning rate");
+    const TrainCall tc = {lr, loss_out};
+    return step_impl(ctx, batch, out, nullptr, false, &tc);
+}
+
+int tig_train_get(tig_ctx *ctx, int32_t what, const tig_weights *dst)
+{
+    if (!ctx)
+        return TIG_EINVAL;
+    if (!ctx->train_ws || !dst || dst->struct_size != sizeof(tig_weights) || (what != 0 && what != 1))
+        return fail(ctx, TIG_EINVAL, "tig_train_get: no workspace attached, NULL destination or unknown selector");
+    const hipError_t e = train_copy_out(ctx->d, ctx->train_ws, what == 1, *dst, ctx->stream);
+    if (e != hipSuccess)
+        return fail(ctx, TIG_EHIP, "tig_train_get", e);
+    return TIG_OK;
 }
 
 int tig_step_profiled(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, float *kernel_ms)

@@ -225,7 +225,7 @@ hipError_t launch_embed(const Dims &d, const LaunchPlan &plan, const PackedWeigh
 // scores and per-query embeddings from the distinct rows, optional inspection outputs, finishing pass
 // of the batch prepared ahead, GRU of the batch the next step applies
 hipError_t launch_closing(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
-                          const GruAhead &ahead, hipStream_t s);
+                          const GruAhead &ahead, hipStream_t s, bool events = true);
 // workgroups the embedding launch can spare for a following batch's preparation (0: none)
 int embed_spare_workgroups(const Dims &d, const LaunchPlan &plan, int roles, int count);
 // workgroups of a batch's query preparation; `shared`: in a launch whose workgroups each occupy a
@@ -243,6 +243,13 @@ struct StepPlan {
     const DedupJob *prep_ded;   // query preparation inside the prepare launch, or NULL
     bool clear_tab;             // clear prep_ded's claim table first
     bool gru_now;               // the GRU launch ahead of the embedding
+    // a training step: forward in direct form, loss, backward and SGD instead of the embedding launch
+    bool train;
+    void *train_ws;
+    void *packed;
+    PackedWeights *pw_out;
+    float lr;
+    float *loss_out;
     int32_t *clear_first;       // a counter to clear ahead of everything, or NULL
     GruAhead ahead;             // GRU workgroups of the closing launch
 };
@@ -261,6 +268,15 @@ struct SyncArgs {
     int64_t n_shared;
 };
 hipError_t launch_sync_shared(const SyncArgs &a, hipStream_t s);
+// ---- training step (train.hip) ----
+size_t train_workspace_bytes(const Dims &d);
+bool train_supported(const Dims &d);
+hipError_t prepare_train(const Dims &d);
+hipError_t train_attach(const Dims &d, const tig_weights &w, void *workspace, void *packed, PackedWeights *pw,
+                        hipStream_t s);
+hipError_t train_copy_out(const Dims &d, void *workspace, bool grads, const tig_weights &out, hipStream_t s);
+hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void *packed, PackedWeights *pw, float lr,
+                        float *loss_out, hipStream_t s);
 // records a failed HIP call of a context-free entry point (read back with tig_last_error(NULL)); returns TIG_EHIP
 int fail_global(const char *what, hipError_t e);
 

@@ -58,7 +58,8 @@ class tig_out(Structure):
 
 
 EXPORTS = ("tig_workspace_bytes", "tig_init", "tig_step", "tig_step_static", "tig_step_profiled", "tig_reset", "tig_state_export",
-           "tig_state_import", "tig_destroy", "tig_strerror", "tig_last_error", "tig_launch_info")
+           "tig_state_import", "tig_destroy", "tig_strerror", "tig_last_error", "tig_launch_info",
+           "tig_train_workspace_bytes", "tig_train_attach", "tig_train_step", "tig_train_get")
 
 _lib = None
 
@@ -97,8 +98,13 @@ def load_library() -> ctypes.CDLL:
     lib.tig_last_error.argtypes = [c_void_p]
     lib.tig_last_error.restype = ctypes.c_char_p
     lib.tig_launch_info.argtypes = [c_void_p, POINTER(c_int32), POINTER(c_int32), POINTER(c_int32)]
+    lib.tig_train_workspace_bytes.argtypes = [POINTER(tig_config), POINTER(c_size_t)]
+    lib.tig_train_attach.argtypes = [c_void_p, POINTER(tig_weights), c_void_p, c_size_t]
+    lib.tig_train_step.argtypes = [c_void_p, POINTER(tig_batch), POINTER(tig_out), c_float, c_void_p]
+    lib.tig_train_get.argtypes = [c_void_p, c_int32, POINTER(tig_weights)]
     for n in ("tig_workspace_bytes", "tig_init", "tig_step", "tig_step_static", "tig_step_profiled", "tig_reset", "tig_state_export",
-              "tig_state_import", "tig_launch_info"):
+              "tig_state_import", "tig_launch_info", "tig_train_workspace_bytes", "tig_train_attach", "tig_train_step",
+              "tig_train_get"):
         getattr(lib, n).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -222,6 +228,35 @@ class TigContext:
         ms = (c_float * len(self.KERNEL_NAMES))()
         self._check(self.lib.tig_step_profiled(self.handle, ctypes.byref(b), ctypes.byref(o), ms))
         return [float(x) for x in ms]
+
+    # -- training ----------------------------------------------------------------------------
+    def train_attach(self, weights: dict):
+        """Allocates the training workspace and makes `weights` the master weights."""
+        torch = self._torch
+        n = c_size_t(0)
+        self._check(self.lib.tig_train_workspace_bytes(ctypes.byref(self.cfg), ctypes.byref(n)))
+        self.train_ws = torch.empty(n.value, dtype=torch.uint8, device=self.device)
+        w = tig_weights(ctypes.sizeof(tig_weights), 0, *[_addr(weights[k]) for k in WEIGHT_NAMES])
+        self._check(self.lib.tig_train_attach(self.handle, ctypes.byref(w), self.train_ws.data_ptr(), n.value))
+        self._shapes = {k: np.asarray(weights[k]).shape for k in WEIGHT_NAMES}
+        self._loss = torch.zeros(1, dtype=torch.float32, device=self.device)
+
+    def train_step(self, first_eid: int, count: int, neg_dst, out: StepOutputs, lr: float):
+        """Enqueues one training step; returns the device tensor [1] that receives the loss."""
+        b = tig_batch(ctypes.sizeof(tig_batch), count, first_eid, _addr(neg_dst))
+        o = tig_out(ctypes.sizeof(tig_out), 0, _addr(out.emb), _addr(out.score_pos), _addr(out.score_neg),
+                    _addr(out.nbr_node), _addr(out.nbr_eid), _addr(out.nbr_ts), _addr(out.nbr_cnt),
+                    _addr(out.is_winner))
+        self._check(self.lib.tig_train_step(self.handle, ctypes.byref(b), ctypes.byref(o), c_float(lr),
+                                            self._loss.data_ptr()))
+        return self._loss
+
+    def train_get(self, what: str) -> dict:
+        """The master weights ("weights") or the last step's gradients ("grads") as host arrays."""
+        arrs = {k: np.empty(self._shapes[k], dtype=np.float32) for k in WEIGHT_NAMES}
+        w = tig_weights(ctypes.sizeof(tig_weights), 0, *[arrs[k].ctypes.data for k in WEIGHT_NAMES])
+        self._check(self.lib.tig_train_get(self.handle, {"weights": 0, "grads": 1}[what], ctypes.byref(w)))
+        return arrs
 
     def step_raw(self, batch: tig_batch, out: tig_out) -> int:
         return self.lib.tig_step(self.handle, ctypes.byref(batch), ctypes.byref(out))

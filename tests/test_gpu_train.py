@@ -1,0 +1,136 @@
+"""Training step on the GPU against the oracle (Sec. II-C self-supervised signal; Alg. 2 "Backward
+and Optimize"): outputs and state as for the batch step, loss, every weight's gradient within the
+fp32 tolerance, the SGD update, and the steps that follow it."""
+import numpy as np
+import pytest
+
+import tig_synth as S
+from oracle import tig_oracle as O
+from oracle import train_oracle as T
+from tests.parity import compare_step, gate
+from tests.test_gpu_parity import Bundle, make_ctx
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(600)]
+
+GRAD_TOL = 1e-4
+
+
+def check_grads(got, ref):
+    worst = {}
+    scale_all = max(np.abs(ref[k]).max() for k in T.PARAMS)
+    for k in T.PARAMS:
+        if k == "b_K":
+            # zero by the softmax's shift invariance: only rounding noise on either side
+            assert np.abs(got[k]).max() <= 1e-6 * scale_all
+            continue
+        worst[k] = gate(got[k].reshape(ref[k].shape), ref[k], GRAD_TOL, f"grad {k}")
+    return worst
+
+
+def run_training(bundle, batches, lr, order, warm_at, then_eval=0):
+    import torch
+    w, g, W0, ix = bundle.w, bundle.g, bundle.W, bundle.ix
+    deferred = order == "deferred"
+    W = {k: v.copy() for k, v in W0.items()}
+    ctx = make_ctx(w, g, W, "fp32", max(c for _, c in batches), order)
+    ctx.train_attach(W)
+    st = O.OracleState(*S.make_warm_state(w, g, warm_at))
+    ctx.state_import(st.mem, st.last_update)
+    for n, (first, count) in enumerate(batches):
+        print(f"[train {w.name} {order}] step first_eid={first} count={count} lr={lr}", flush=True)
+        neg = S.make_negatives(w, g, first, count)
+        ref, loss, grads = T.train_step(st, g.src, g.dst, g.ts, g.edge_feat, W, first, count, neg, w.num_neighbors,
+                                        w.num_heads, lr, index=ix, deferred=deferred)
+        out = ctx.alloc_outputs(count, inspect=True)
+        loss_dev = ctx.train_step(first, count, torch.from_numpy(neg).to("cuda:0"), out, lr)
+        torch.cuda.synchronize()
+        compare_step(ctx, out, ref, st, 1e-4)
+        assert float(loss_dev.item()) == pytest.approx(loss, rel=2e-5)
+        worst = check_grads(ctx.train_get("grads"), grads)
+        print(f"[train] loss {loss:.6f}; worst gradient gate ratios: "
+              f"{ {k: float(f'{v:.2e}') for k, v in sorted(worst.items(), key=lambda kv: -kv[1])[:4]} }", flush=True)
+        got_w = ctx.train_get("weights")
+        for k in T.PARAMS:
+            gate(got_w[k].reshape(W[k].shape), W[k], 1e-5, f"weight {k}")
+            # The next step starts from the SAME weights on both sides.  (The time encoding multiplies
+            # its frequencies by time differences of up to 1e5: a last-bit difference in a frequency,
+            # which an fp32 update against an fp64 one leaves, would move phases by ~1e-2 rad and
+            # swamp every tolerance; that sensitivity belongs to the model, not to a kernel.)
+            W[k] = got_w[k].reshape(W[k].shape).copy()
+    # ordinary steps after training read the updated weights
+    first = batches[-1][0] + batches[-1][1]
+    for _ in range(then_eval):
+        count = batches[-1][1]
+        neg = S.make_negatives(w, g, first, count)
+        ref = O.step(st, g.src, g.dst, g.ts, g.edge_feat, W, first, count, neg, w.num_neighbors, w.num_heads, index=ix,
+                     deferred=deferred)
+        out = ctx.alloc_outputs(count, inspect=True)
+        ctx.step(first, count, torch.from_numpy(neg).to("cuda:0"), out)
+        torch.cuda.synchronize()
+        compare_step(ctx, out, ref, st, 1e-4)
+        first += count
+    ctx.close()
+
+
+@pytest.fixture(scope="module")
+def c1():
+    return Bundle(S.WORKLOADS["c1_tiny"])
+
+
+@pytest.mark.parametrize("order", ["update_first", "deferred"])
+def test_c1_gradients(c1, order):
+    # lr = 0: every step's gradients are compared; ragged batch sizes, a one-event batch
+    run_training(c1, [(4000, 136), (4136, 200), (4336, 1), (4337, 64)], 0.0, order, warm_at=4000)
+
+
+@pytest.mark.parametrize("order", ["update_first", "deferred"])
+def test_c1_sgd_steps_then_evaluation(c1, order):
+    run_training(c1, [(6000, 200), (6200, 200), (6400, 200)], 0.01, order, warm_at=6000, then_eval=3)
+
+
+def test_c1_from_reset(c1):
+    import torch
+    # nothing in memory, no neighbours for the first events: empty neighbourhoods and zero rows
+    w, g, W = c1.w, c1.g, {k: v.copy() for k, v in c1.W.items()}
+    ctx = make_ctx(w, g, W, "fp32", 100)
+    ctx.train_attach(W)
+    st = O.OracleState.zeros(g.num_nodes, w.mem_dim)
+    for first in (0, 100):
+        neg = S.make_negatives(w, g, first, 100)
+        ref, loss, grads = T.train_step(st, g.src, g.dst, g.ts, g.edge_feat, W, first, 100, neg, w.num_neighbors,
+                                        w.num_heads, 0.0, index=c1.ix)
+        out = ctx.alloc_outputs(100, inspect=True)
+        loss_dev = ctx.train_step(first, 100, torch.from_numpy(neg).to("cuda:0"), out, 0.0)
+        torch.cuda.synchronize()
+        compare_step(ctx, out, ref, st, 1e-4)
+        assert float(loss_dev.item()) == pytest.approx(loss, rel=2e-5)
+        check_grads(ctx.train_get("grads"), grads)
+    ctx.close()
+
+
+def test_c2_shape_gradients():
+    # the wide rows of the bipartite workloads (172-dim memory and edge features)
+    b = Bundle(S.WORKLOADS["c2_bipartite_medium"].scaled(num_events=20000))
+    run_training(b, [(12000, 120), (12120, 120)], 0.0, "deferred", warm_at=12000)
+
+
+def test_training_needs_fp32_negatives_and_a_workspace(c1):
+    import torch
+    from paper_2308_14129_amd import tig
+    w, g, W = c1.w, c1.g, c1.W
+    neg = torch.from_numpy(S.make_negatives(w, g, 0, 100)).to("cuda:0")
+    ctx = make_ctx(w, g, W, "fp32", 100)
+    out = ctx.alloc_outputs(100)
+    b = tig.tig_batch(tig.ctypes.sizeof(tig.tig_batch), 100, 0, neg.data_ptr())
+    o = tig.tig_out(tig.ctypes.sizeof(tig.tig_out), 0, out.emb.data_ptr(), out.score_pos.data_ptr(),
+                    out.score_neg.data_ptr(), None, None, None, None, None)
+    assert ctx.lib.tig_train_step(ctx.handle, tig.ctypes.byref(b), tig.ctypes.byref(o), 0.1, None) == tig.TIG_EINVAL
+    ctx.train_attach(W)
+    b.neg_dst = None
+    assert ctx.lib.tig_train_step(ctx.handle, tig.ctypes.byref(b), tig.ctypes.byref(o), 0.1, None) == tig.TIG_EINVAL
+    ctx.close()
+    half = make_ctx(w, g, W, "bf16", 100)
+    with pytest.raises(tig.TigError) as ei:
+        half.train_attach(W)
+    assert ei.value.status == tig.TIG_EINVAL
+    half.close()
