@@ -188,6 +188,51 @@ def mfma_flops(w, rows_u, winners, precision):
     return issued, useful
 
 
+def bench_train(S, tig, torch, w, g, weights, B, batches, negs, negs_np, mem0, lu0, warm, steps=20, cpu_steps=1):
+    """Training steps (fp32 masters, deferred message order: a prediction never sees its own event
+    through the memory) over consecutive batches of the timed window, lr = 1e-4; beside them the
+    training oracle on `cpu_steps` steps of the same window."""
+    import numpy as np
+    cfg = tig.make_config(w.mem_dim, w.time_dim, w.feat_dim, w.emb_dim, w.num_neighbors, w.num_heads, B, "fp32",
+                          "deferred")
+    ctx = tig.TigContext(cfg, g.num_nodes, g.src, g.dst, g.ts, g.edge_feat, weights, device="cuda:0")
+    ctx.train_attach(weights)
+    ctx.state_import(mem0, lu0)
+    out = ctx.alloc_outputs(B)
+    n_warm = min(3, warm)
+    for i in range(n_warm):
+        ctx.train_step(batches[i][0], batches[i][1], negs[i], out, 1e-4)
+    torch.cuda.synchronize()
+    n = min(steps, len(batches) - n_warm)
+    t0 = time.perf_counter()
+    losses = []
+    for i in range(n_warm, n_warm + n):
+        losses.append(ctx.train_step(batches[i][0], batches[i][1], negs[i], out, 1e-4).clone())
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ws_bytes = ctx.train_ws.numel()
+    ctx.close()
+    rep_ = {"steps": n, "ms_per_step": round(dt * 1e3 / n, 3), "events_per_s": round(n * B / dt, 1),
+            "order": "deferred", "dtype": "f32", "lr": 1e-4, "workspace_GB": round(ws_bytes / 1e9, 2),
+            "loss_first_last": [round(float(losses[0].item()), 5), round(float(losses[-1].item()), 5)]}
+    if cpu_steps > 0:
+        from threadpoolctl import threadpool_limits
+        from oracle import tig_oracle as O
+        from oracle import train_oracle as TO
+        ix = O.NeighbourIndex(g.num_nodes, g.src, g.dst, g.ts)
+        st = O.OracleState(mem0.copy(), lu0.copy())
+        Wc = {k: v.copy() for k, v in weights.items()}
+        with threadpool_limits(limits=1):
+            t0 = time.perf_counter()
+            for i in range(cpu_steps):
+                TO.train_step(st, g.src, g.dst, g.ts, g.edge_feat, Wc, batches[i][0], batches[i][1], negs_np[i],
+                              w.num_neighbors, w.num_heads, 1e-4, index=ix, deferred=True)
+            cs = time.perf_counter() - t0
+        rep_["oracle_events_per_s"] = round(cpu_steps * B / cs, 1)
+        rep_["oracle_sample"] = f"{cpu_steps} training step(s) of {B} events, one core, {cs:.1f} s"
+    return rep_
+
+
 def bench_sep(g, w, torch, num_parts=8, top_k=0.01, beta=1e-6):
     """The partitioner over the whole stream: centrality kernel (HBM-bound: 16 bytes per event in,
     8 bytes per node out), hub selection, and the sequential edge loop on the host; beside them the
@@ -269,6 +314,9 @@ def main():
     ap.add_argument("--sep", action="store_true",
                     help="also run the streaming edge partitioner (Sec. II-B) over the workload's whole event "
                          "stream (8 partitions, 1 %% hubs) and report its stages in a \"sep\" object")
+    ap.add_argument("--train", action="store_true",
+                    help="also time training steps (forward, BCE loss, backward, SGD; fp32, deferred message "
+                         "order) on the same window and report them in a \"train\" object")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1",
@@ -444,11 +492,20 @@ def main():
         del src_buf, dst_buf
         roofline["measured_copy_GBps"] = measured_copy_gbs
 
+    train_report = None
+    if args.train:
+        ctx.close()
+        del ctx
+        torch.cuda.empty_cache()
+        train_report = bench_train(S, tig, torch, w, g, weights, B, batches, negs, negs_np, mem0, lu0, W_,
+                                   cpu_steps=0 if args.no_cpu_baseline else 1)
+        ctx = None
+
     sep_report = None
     if args.sep:
         sep_report = bench_sep(g, w, torch)
 
-    info = ctx.launch_info()
+    info = ctx.launch_info() if ctx is not None else {"kernels_per_step": 2}
     line = {
         "metric": "events/sec per TGN batch step (1 MI355X)",
         "value": round(value, 1),
@@ -477,7 +534,10 @@ def main():
     }
     if sep_report is not None:
         line["sep"] = sep_report
-    ctx.close()
+    if train_report is not None:
+        line["train"] = train_report
+    if ctx is not None:
+        ctx.close()
     print(json.dumps(line), flush=True)
 
 

@@ -25,9 +25,9 @@ def _hipcc() -> str:
     return "hipcc"
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(src: str, defines=(), tag: str = "") -> str:
+    obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + tag + ".o")
+    cmd = [_hipcc(), *HIPCC_FLAGS, *[f"-D{d}" for d in defines], "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
@@ -38,18 +38,24 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(verbose: bool = False) -> str:
+CLOCKS_LIB_PATH = os.path.join(HERE, "libtig_clocks.so")
+
+
+def build(verbose: bool = False, phase_clocks: bool = False) -> str:
+    """libtig.so; with phase_clocks=True instead libtig_clocks.so, the same library with per-workgroup
+    timestamps at the phase boundaries of the two tile kernels (read by phase_clocks.py)."""
     os.makedirs(OBJ_DIR, exist_ok=True)
+    defines, tag, out = (("TIG_PHASE_CLOCKS",), "_clocks", CLOCKS_LIB_PATH) if phase_clocks else ((), "", LIB_PATH)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]
+        objs = list(ex.map(lambda src: _compile(src, defines, tag), SOURCES))
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"link failed:\n{res.stderr}")
     if verbose:
-        print("built", LIB_PATH)
-    return LIB_PATH
+        print("built", out)
+    return out
 
 
 if __name__ == "__main__":
-    build(verbose=True)
+    build(verbose=True, phase_clocks="--phase-clocks" in sys.argv[1:])
