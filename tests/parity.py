@@ -1,7 +1,11 @@
 """Comparison helpers for the GPU-vs-oracle parity tests."""
 from __future__ import annotations
 
+import os
+
 import numpy as np
+
+REPORT = os.environ.get("TIG_PARITY_REPORT", "") not in ("", "0")   # also print max abs and pure-relative errors
 
 
 def gate(got: np.ndarray, ref: np.ndarray, tol: float, name: str) -> float:
@@ -18,6 +22,11 @@ def gate(got: np.ndarray, ref: np.ndarray, tol: float, name: str) -> float:
     denom[denom == 0.0] = 1.0
     ratio = np.abs(got - ref) / denom
     worst = float(ratio.max())
+    if REPORT:
+        big = np.abs(ref) > 1e-3 * max(s, 1e-30)   # pure relative error where the reference is not near zero
+        rel = float((np.abs(got - ref)[big] / np.abs(ref)[big]).max()) if big.any() else 0.0
+        print(f"[gate] {name}: ratio {worst:.2e} (tol {tol:g}), max abs {np.abs(got - ref).max():.2e}, "
+              f"max relative (|ref| > 1e-3 mean|ref|) {rel:.2e}", flush=True)
     assert worst <= tol, (f"{name}: max |got-ref|/(|ref|+mean|ref|) = {worst:.3e} > {tol:g} "
                           f"(max abs err {np.abs(got - ref).max():.3e}, mean|ref| {s:.3e})")
     return worst

@@ -35,7 +35,7 @@ class Bundle:
 
 
 def run(bundle, precision, batches, locked, warm_at=None, with_neg=True, ctx=None, order="update_first",
-        expect_launches=None):
+        expect_launches=None, quiet=False):
     """Runs the batches on both sides.  locked=True loads the oracle's state into the GPU before
     every step (step-locked parity); otherwise both sides run freely from the same start, which
     is the state after a reset or, with warm_at, the seeded warm state of a mid-stream window.
@@ -60,7 +60,8 @@ def run(bundle, precision, batches, locked, warm_at=None, with_neg=True, ctx=Non
     applied = None  # deferred order: the batch whose winners the next step applies
     worst = {}
     for n, (first, count) in enumerate(batches):
-        print(f"[{w.name} {precision}] step first_eid={first} count={count}", flush=True)
+        if not quiet or n % 50 == 0:
+            print(f"[{w.name} {precision}] step first_eid={first} count={count}", flush=True)
         neg = S.make_negatives(w, g, first, count) if with_neg else None
         if locked:
             ctx.state_import(st.mem, st.last_update)
@@ -188,6 +189,13 @@ def test_c2_windows_and_last_short_batch_fp32(c2):
     last = (w.num_events // 200) * 200            # 157,474 = 787 * 200 + 74
     assert w.num_events - last == 74
     run(c2, "fp32", [(last - 200, 200), (last, 74)], locked=True, warm_at=last - 200)
+
+
+@pytest.mark.timeout(900)
+def test_c2_whole_stream_free_running_fp32(c2):
+    # all 788 batches from reset (the last one has 74 events), both sides free running: every step's
+    # neighbour tables, winners, embeddings, scores and state; from the second step on two launches
+    run(c2, "fp32", list(S.batches(c2.w.num_events, 200)), locked=False, expect_launches=2, quiet=True)
 
 
 def test_c2_window_bf16(c2):
