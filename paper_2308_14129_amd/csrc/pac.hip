@@ -48,8 +48,11 @@ struct NodePred {
     __device__ bool operator()(int64_t v) const { return is_member(node_parts, num_nodes, v, group); }
 };
 
+// The count pass also leaves the verdicts of a thread's 8 consecutive items as one byte, so the
+// write pass neither re-reads the items nor repeats the test.
 template <class Pred>
-__global__ void __launch_bounds__(kCompThreads) k_comp_count(Pred pred, int64_t n, int32_t *block_counts)
+__global__ void __launch_bounds__(kCompThreads) k_comp_count(Pred pred, int64_t n, int32_t *block_counts,
+                                                             uint8_t *keep_bits)
 {
     __shared__ int total;
     if (threadIdx.x == 0)
@@ -57,10 +60,15 @@ __global__ void __launch_bounds__(kCompThreads) k_comp_count(Pred pred, int64_t 
     __syncthreads();
     const int64_t i0 = (int64_t)blockIdx.x * kCompBlock + (int64_t)threadIdx.x * kCompPer;
     int c = 0;
+    unsigned bits = 0;
 #pragma unroll
     for (int u = 0; u < kCompPer; ++u)
-        if (i0 + u < n && pred(i0 + u))
+        if (i0 + u < n && pred(i0 + u)) {
             ++c;
+            bits |= 1u << u;
+        }
+    if (i0 < n)
+        keep_bits[i0 / kCompPer] = (uint8_t)bits;
     if (c)
         atomicAdd(&total, c);
     __syncthreads();
@@ -99,20 +107,20 @@ __global__ void __launch_bounds__(kScanThreads) k_comp_scan(const int32_t *block
 }
 
 // kept items, in index order, to out[offset ..]; `rank_of` (may be NULL) gets every item's position or -1
-template <class Pred>
-__global__ void __launch_bounds__(kCompThreads) k_comp_write(Pred pred, int64_t n, const int64_t *block_offsets,
-                                                             int64_t capacity, int32_t *out, int32_t *rank_of)
+__global__ void __launch_bounds__(kCompThreads) k_comp_write(const uint8_t *keep_bits, int64_t n,
+                                                             const int64_t *block_offsets, int64_t capacity,
+                                                             int32_t *out, int32_t *rank_of)
 {
     __shared__ int wave_tot[kCompThreads / kWave];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int64_t i0 = (int64_t)blockIdx.x * kCompBlock + (int64_t)threadIdx.x * kCompPer;
+    static_assert(kCompPer == 8, "one byte of verdicts per thread");
+    const unsigned bits = i0 < n ? keep_bits[i0 / kCompPer] : 0u;
     bool keep[kCompPer];
-    int c = 0;
 #pragma unroll
-    for (int u = 0; u < kCompPer; ++u) {
-        keep[u] = i0 + u < n && pred(i0 + u);
-        c += keep[u] ? 1 : 0;
-    }
+    for (int u = 0; u < kCompPer; ++u)
+        keep[u] = (bits >> u) & 1u;
+    const int c = __popc(bits);
     int incl = c;  // inclusive scan over the wavefront
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) {
@@ -206,6 +214,7 @@ struct CompScratch {
     int32_t *block_counts;
     int64_t *block_offsets;
     int64_t *total;
+    uint8_t *keep_bits;
     size_t bytes;
 };
 
@@ -221,6 +230,8 @@ CompScratch comp_scratch(int64_t n_max, void *base)
     off += align_up(8 * (size_t)nb);
     c.total = base ? (int64_t *)(p + off) : nullptr;
     off += 256;
+    c.keep_bits = base ? (uint8_t *)(p + off) : nullptr;
+    off += align_up((size_t)nb * kCompThreads);  // one byte per thread of every workgroup
     c.bytes = off;
     return c;
 }
@@ -234,14 +245,15 @@ hipError_t compact(Pred pred, int64_t n, const CompScratch &c, int64_t capacity,
         *total_host = 0;
         return hipSuccess;
     }
-    hipLaunchKernelGGL(k_comp_count<Pred>, dim3((unsigned)nb), dim3(kCompThreads), 0, s, pred, n, c.block_counts);
+    hipLaunchKernelGGL(k_comp_count<Pred>, dim3((unsigned)nb), dim3(kCompThreads), 0, s, pred, n, c.block_counts,
+                       c.keep_bits);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return e;
     hipLaunchKernelGGL(k_comp_scan, dim3(1), dim3(kScanThreads), 0, s, c.block_counts, nb, c.block_offsets, c.total);
     if ((e = hipGetLastError()) != hipSuccess)
         return e;
-    hipLaunchKernelGGL((k_comp_write<Pred>), dim3((unsigned)nb), dim3(kCompThreads), 0, s, pred, n, c.block_offsets,
+    hipLaunchKernelGGL(k_comp_write, dim3((unsigned)nb), dim3(kCompThreads), 0, s, c.keep_bits, n, c.block_offsets,
                        capacity, out, rank_of);
     if ((e = hipGetLastError()) != hipSuccess)
         return e;

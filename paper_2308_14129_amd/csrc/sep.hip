@@ -25,7 +25,7 @@ namespace tig {
 namespace {
 
 constexpr int kCentThreads = 512;
-constexpr int kCentPerThread = 32;                         // events per thread
+constexpr int kCentPerThread = 128;                        // events per thread
 constexpr int kCentChunk = kCentThreads * kCentPerThread;  // events per workgroup
 constexpr int kCentSlots = 4096;                           // LDS table: node id + fp64 sum per slot
 constexpr int kCentProbes = 8;
