@@ -255,6 +255,46 @@ def make_weights(w: Workload) -> dict:
     return out
 
 
+def make_module_weights(w: Workload, updater: str = "gru", embedding: str = "attention") -> dict:
+    """Weights of another instance of the general architecture: as make_weights, with the plain
+    recurrent cell's shapes (W_i [M, D_msg], b_i [M], W_h [M, M], b_h [M]; Xavier / U(-0.1, 0.1) from
+    streams of their own) for updater "rnn", without the attention and merge weights and with a
+    decoder over M-wide embeddings for the embeddings that are not "attention", and with the
+    time-projection vector time_proj_w [M] ~ U(-1e-6, 1e-6) (time differences reach 2.6e6)."""
+    lib = _load()
+    M, T, F = w.mem_dim, w.time_dim, w.feat_dim
+    D = 2 * M + T + F
+    out = dict(make_weights(w))
+
+    def draw(name, shape, stream, lim):
+        a = np.empty(shape, dtype=np.float32)
+        _check(lib.tig_gen_uniform_f32(w.seed, stream, int(np.prod(shape)), -lim, lim, _ptr(a)), name)
+        out[name] = a
+
+    if updater == "rnn":
+        draw("W_i", (M, D), 200, math.sqrt(6.0 / (M + D)))
+        draw("b_i", (M,), 201, 0.1)
+        draw("W_h", (M, M), 202, math.sqrt(6.0 / (2 * M)))
+        draw("b_h", (M,), 203, 0.1)
+    if embedding != "attention":
+        for k in ("W_Q", "b_Q", "W_K", "b_K", "W_V", "b_V", "W_O", "b_O", "W_m1", "b_m1", "W_m2", "b_m2"):
+            out.pop(k)
+        draw("W_d1", (M, 2 * M), 204, math.sqrt(6.0 / (3 * M)))
+        draw("b_d1", (M,), 205, 0.1)
+        draw("w_d2", (M,), 206, math.sqrt(6.0 / (M + 1)))
+        draw("b_d2", (1,), 207, 0.1)
+    if embedding == "time_projection":
+        draw("time_proj_w", (M,), 208, 1e-6)
+    return out
+
+
+def make_node_feat(w: Workload, num_nodes: int) -> np.ndarray:
+    """Static node features [N, M] ~ U(-0.5, 0.5) (the paper's datasets mostly have none: zero vectors)."""
+    a = np.empty((num_nodes, w.mem_dim), dtype=np.float32)
+    _check(_load().tig_gen_uniform_f32(w.seed, 209, int(a.size), -0.5, 0.5, _ptr(a)), "node_feat")
+    return a
+
+
 def num_params(weights: dict) -> int:
     return int(sum(int(v.size) for v in weights.values()))
 
