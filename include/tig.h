@@ -160,6 +160,8 @@ TIG_API int tig_workspace_bytes(const tig_config *cfg, const tig_graph *graph,
  * listed under both endpoints), prepares the weights for the matrix cores, and zeroes the
  * state (memory and last_update), which is the state after a reset (Alg. 2).
  * `hip_stream` is a hipStream_t (NULL = the default stream); every later call enqueues on it.
+ * `weights` may be NULL: the context then has graph, adjacency and state but no model of its own,
+ * and tig_step fails with TIG_EINVAL until tig_modules_attach has given it one.
  * Synchronous: returns after the device has finished.  On failure *out is NULL.
  */
 TIG_API int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *weights,
@@ -271,6 +273,57 @@ TIG_API int tig_train_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *
 /* Copies the master weights (what = 0) or the gradients of the last training step (what = 1) to
  * the non-NULL pointers of `dst` (host or device), laid out as in tig_weights.  Synchronous. */
 TIG_API int tig_train_get(tig_ctx *ctx, int32_t what, const tig_weights *dst);
+
+/* ------------------------------------------------------------------------------------------
+ * Other instances of the general architecture (Sec. II-C "Training approach for TIGs": the messages
+ * of a node within a batch may be aggregated by their mean, the state update may be a GRU or a plain
+ * RNN, the embedding function f may be identity, time projection or attention; Sec. II-A: nodes may
+ * carry static features).  A module selection is attached to a context; tig_step, tig_reset,
+ * tig_state_export / _import and the epoch machinery then run that instance, in the context's
+ * message order, with the same arguments, outputs and errors.  fp32 contexts only.
+ *   aggregator  LAST: the node's message of greatest (time, event id).  MEAN: the element-wise mean of
+ *               all the node's messages of the batch, either role, each built from the memory at the
+ *               start of the step with its own event's time, partner and feature row; last_update
+ *               becomes the time of the node's last event of the batch either way
+ *   updater     GRU as in tig_step.  RNN: s = tanh(W_i m + b_i + W_h s' + b_h), with
+ *               W_i [M x D_msg], b_i [M], W_h [M x M], b_h [M] in tig_weights
+ *   embedding   ATTENTION as in tig_step.  IDENTITY: emb_i(t) = r_i(t).  TIME_PROJECTION:
+ *               emb_i(t) = (1 + (t - last_update_i) * time_proj_w) * r_i(t), element-wise, with the
+ *               last_update the step's memory overwrite left.  Both need emb_dim == mem_dim, read no
+ *               neighbours (the nbr_* outputs are not written) and ignore the attention and merge
+ *               weights (may be NULL); the decoder is W_d1 [M x 2M], b_d1 [M], w_d2 [M], b_d2 [1]
+ *   node_feat   [N x M] static node features (host or device) or NULL: wherever the embedding
+ *               reads a node's state, its own or a neighbour's, it reads r_i(t) = s_i(t) + v_i;
+ *               messages carry the raw memory rows
+ * (The paper names these options and gives no formulas: the formulas are this build's reading.)
+ * ------------------------------------------------------------------------------------------ */
+typedef enum tig_aggregator { TIG_AGG_LAST = 0, TIG_AGG_MEAN = 1 } tig_aggregator;
+typedef enum tig_updater { TIG_UPD_GRU = 0, TIG_UPD_RNN = 1 } tig_updater;
+typedef enum tig_embedding { TIG_EMB_ATTENTION = 0, TIG_EMB_IDENTITY = 1, TIG_EMB_TIME_PROJECTION = 2 } tig_embedding;
+
+typedef struct tig_modules {
+    uint32_t struct_size;
+    int32_t aggregator;       /* tig_aggregator */
+    int32_t updater;          /* tig_updater */
+    int32_t embedding;        /* tig_embedding */
+    const float *node_feat;   /* [N x M], host or device, or NULL */
+    const float *time_proj_w; /* [M], host or device; required for TIG_EMB_TIME_PROJECTION */
+} tig_modules;
+
+/* Size of the workspace of a module selection (device memory the caller allocates): transposed
+ * copies of the weights and, if node features are given, a copy of them.  TIG_EINVAL for a
+ * precision other than TIG_FP32, an unknown selector, emb_dim != mem_dim with an embedding that
+ * needs it, or rows the kernels cannot hold. */
+TIG_API int tig_modules_workspace_bytes(const tig_config *cfg, const tig_modules *modules, int64_t num_nodes,
+                                        size_t *bytes);
+
+/* Makes the context compute the selected instance with `weights` (host or device; shapes as above).
+ * `workspace`: device, 256-byte aligned, owned by the caller until tig_destroy.  Anything prepared
+ * ahead by earlier steps is dropped; the state (memory, last_update, cursor) is kept.  Afterwards
+ * tig_step_static and the tig_train_* calls refuse the context (TIG_EINVAL), and a context with a
+ * training workspace cannot take a module selection.  Synchronous. */
+TIG_API int tig_modules_attach(tig_ctx *ctx, const tig_modules *modules, const tig_weights *weights,
+                               void *workspace, size_t workspace_bytes);
 
 /* Memory reset at the start of a data cycle (Alg. 2): memory <- 0, last_update <- 0. Async. */
 TIG_API int tig_reset(tig_ctx *ctx);

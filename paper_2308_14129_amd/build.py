@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libtig.so")
-SOURCES = ["tig_api.hip", "csr_build.hip", "pack.hip", "step_launch.hip", "step_small.hip", "k_gru.hip", "k_embed.hip", "sep.hip", "pac.hip", "train.hip"]
+SOURCES = ["tig_api.hip", "csr_build.hip", "pack.hip", "step_launch.hip", "step_small.hip", "k_gru.hip", "k_embed.hip", "sep.hip", "pac.hip", "train.hip", "modules.hip"]
 
 # Packed-FP32 VALU instructions are switched off for every device translation unit.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

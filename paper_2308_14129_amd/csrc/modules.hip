@@ -1,0 +1,676 @@
+// Other instances of the general architecture (paper Sec. II-C "Training approach for TIGs": the
+// messages of a node within a batch "can be aggregated by ... mean message", the state update "can
+// be chosen from ... GRU, RNN", the embedding function f is "identity, time projection or
+// attention"; Sec. II-A: nodes may carry static features), device side.  gfx950 only, fp32.
+//
+// A context with an attached module selection runs its batch step here instead of in the fused
+// kernels of the headline instance (last message, GRU, attention), in plain per-row kernels:
+//   k_mod_update   one workgroup per node of the applied batch: aggregated message (the last one, or
+//                  the mean of all the node's messages of the batch, every one built from the memory
+//                  at the start of the step), then the GRU or the plain recurrent cell -> staged row
+//   k_mod_commit   memory overwrite M <- s_i(t) and last_update, after every message has been built
+//   k_mod_simple   identity / time-projection embedding of every query, straight to the output
+//   k_mod_rows     attention embedding in its direct form (separate query / key / value / output
+//                  projections, merge MLP), one workgroup per distinct query, node features added
+//                  wherever a state row is read; a negative's neighbours are looked up here
+//   k_mod_decode   eight events per workgroup: both logits (and, for the attention embedding, the
+//                  per-query embedding rows out of the distinct rows)
+// Weight matrices are read through transposed copies ([in x out]) so that a thread that owns an
+// output reads consecutive addresses.
+#include <hip/hip_runtime.h>
+
+#include "kernels_common.h"
+#include "prepare.h"
+#include "winners.h"
+
+namespace tig {
+
+namespace {
+
+constexpr int kModThreads = 256;
+constexpr int kModWaves = kModThreads / kWave;
+constexpr int kKC = 8;   // neighbour slots per register chunk
+constexpr int kEV = 8;   // events per decoder workgroup
+
+struct ModDims {
+    int M, T, F, E, K, H, da, dh, dkv, Dmsg;
+    int G;  // gate blocks of the state update: 3 (GRU: r, z, n) or 1 (plain recurrent cell)
+    int agg, upd, emb;
+};
+
+ModDims mod_dims(const Dims &d, const ModParams &p)
+{
+    return ModDims{d.M, d.T, d.F, d.E, d.K, d.H, d.da, d.dh, d.dkv, d.Dmsg, p.upd == TIG_UPD_GRU ? 3 : 1, p.agg, p.upd, p.emb};
+}
+
+// y[j] = bias[j] + sum_i WT[i * out + j] * x[i]   (x, y in LDS)
+__device__ inline void matvec_t(const float *WT, int in, int out, const float *x, const float *bias, float *y)
+{
+    for (int j = threadIdx.x; j < out; j += kModThreads) {
+        float acc = bias ? bias[j] : 0.0f;
+        for (int i = 0; i < in; ++i)
+            acc += WT[(size_t)i * out + j] * x[i];
+        y[j] = acc;
+    }
+}
+
+// Y[k][j] = bias[j] + sum_i WT[i * out + j] * X[k][i] for k < cnt   (X [cnt x ldx], Y [cnt x out] in LDS)
+__device__ inline void multivec_t(const float *WT, int in, int out, const float *X, int ldx, int cnt,
+                                  const float *bias, float *Y)
+{
+    for (int k0 = 0; k0 < cnt; k0 += kKC) {
+        for (int j = threadIdx.x; j < out; j += kModThreads) {
+            float acc[kKC];
+            const float b = bias ? bias[j] : 0.0f;
+#pragma unroll
+            for (int u = 0; u < kKC; ++u)
+                acc[u] = b;
+            for (int i = 0; i < in; ++i) {
+                const float w = WT[(size_t)i * out + j];
+#pragma unroll
+                for (int u = 0; u < kKC; ++u)
+                    acc[u] += w * X[(size_t)(k0 + u < cnt ? k0 + u : k0) * ldx + i];
+            }
+#pragma unroll
+            for (int u = 0; u < kKC; ++u)
+                if (k0 + u < cnt)
+                    Y[(size_t)(k0 + u) * out + j] = acc[u];
+        }
+    }
+}
+
+// r_i(t): the state row the embedding module reads for node v (memory row plus the static feature
+// row), element j; a node id outside the graph reads as a zero row
+__device__ inline float repr_elem(const StepArgs &a, const ModParams &p, int M, int32_t v, int j)
+{
+    if (v < 0 || (int64_t)v >= a.num_nodes)
+        return 0.0f;
+    float x = a.mem[(size_t)v * M + j];
+    if (p.node_feat)
+        x += p.node_feat[(size_t)v * M + j];
+    return x;
+}
+
+// ------------------------------------------------------------------------------------------
+// Aggregation + state update of one node of the applied batch (the batch's winner list names each
+// node once, with its last event).
+__global__ void __launch_bounds__(kModThreads) k_mod_update(StepArgs a, ModDims d, ModParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int M = d.M, T = d.T, F = d.F, D = d.Dmsg, GM = d.G * d.M;
+    const int rest = M + T + F;                 // message columns that differ between a node's messages
+    double *acc = (double *)smem;               // [rest]
+    float *msg = (float *)(acc + rest);         // [D]
+    float *h = msg + D;                         // [M]
+    float *gi = h + M;                          // [GM]
+    float *gh = gi + GM;                        // [GM]
+    int *list = (int *)(gh + GM);               // [kModThreads] entries of this node in a chunk
+    int *s_cnt = list + kModThreads;            // [waves + 2]
+
+    int n_win = *a.n_win;
+    n_win = n_win < 2 * a.msg_count ? n_win : 2 * a.msg_count;
+    const int r = (int)blockIdx.x;
+    if (r >= n_win)
+        return;
+    const WinDesc w = a.win[r];
+    if (w.node < 0 || (int64_t)w.node >= a.num_nodes || w.other < 0 || (int64_t)w.other >= a.num_nodes ||
+        w.entry < 0 || w.entry >= 2 * a.msg_count)
+        return;  // (not a descriptor of this batch)
+    const int lane = lane_id(), wave = wave_id();
+    const double lu0 = a.lu[w.node];
+    for (int j = threadIdx.x; j < M; j += kModThreads) {
+        const float v = a.mem[(size_t)w.node * M + j];
+        h[j] = v;
+        msg[j] = v;
+    }
+    if (d.agg == TIG_AGG_LAST) {
+        const int64_t eid = a.msg_first_eid + (w.entry >> 1);
+        for (int j = threadIdx.x; j < rest; j += kModThreads) {
+            float v;
+            if (j < M)
+                v = a.mem[(size_t)w.other * M + j];
+            else if (j < M + T)
+                v = time_enc(p.time_w_rev[j - M], p.time_b_rev[j - M], w.t - lu0);
+            else
+                v = a.edge_feat[(size_t)eid * F + (j - M - T)];
+            msg[M + j] = v;
+        }
+    } else {
+        // mean of all the node's messages of the batch: its entries are collected chunk by chunk in
+        // entry order (so the sum has one fixed order) and added column-parallel in double
+        for (int j = threadIdx.x; j < rest; j += kModThreads)
+            acc[j] = 0.0;
+        int total = 0;
+        const int entries = 2 * a.msg_count;
+        for (int base = 0; base < entries; base += kModThreads) {
+            const int i = base + (int)threadIdx.x;
+            bool mine = false;
+            if (i < entries) {
+                const int64_t e = a.msg_first_eid + (i >> 1);
+                mine = ((i & 1) ? a.dst[e] : a.src[e]) == w.node;
+            }
+            const unsigned long long m = __ballot(mine);
+            if (lane == 0)
+                s_cnt[wave] = __popcll(m);
+            __syncthreads();
+            int before = 0, n = 0;
+            for (int x = 0; x < kModWaves; ++x) {
+                if (x < wave)
+                    before += s_cnt[x];
+                n += s_cnt[x];
+            }
+            if (mine)
+                list[before + __popcll(m & ((1ull << lane) - 1ull))] = i;
+            __syncthreads();
+            for (int l = 0; l < n; ++l) {
+                const int i2 = list[l];
+                const int64_t e = a.msg_first_eid + (i2 >> 1);
+                int32_t o = (i2 & 1) ? a.src[e] : a.dst[e];
+                const double dt = a.ts[e] - lu0;
+                const bool ok = o >= 0 && (int64_t)o < a.num_nodes;
+                for (int j = threadIdx.x; j < rest; j += kModThreads) {
+                    float v;
+                    if (j < M)
+                        v = ok ? a.mem[(size_t)o * M + j] : 0.0f;
+                    else if (j < M + T)
+                        v = time_enc(p.time_w_rev[j - M], p.time_b_rev[j - M], dt);
+                    else
+                        v = a.edge_feat[(size_t)e * F + (j - M - T)];
+                    acc[j] += (double)v;
+                }
+            }
+            total += n;
+            __syncthreads();
+        }
+        const double inv = 1.0 / (double)(total > 0 ? total : 1);
+        for (int j = threadIdx.x; j < rest; j += kModThreads)
+            msg[M + j] = (float)(acc[j] * inv);
+    }
+    __syncthreads();
+    matvec_t(p.T_i, D, GM, msg, p.b_i, gi);
+    matvec_t(p.T_h, M, GM, h, p.b_h, gh);
+    __syncthreads();
+    for (int j = threadIdx.x; j < M; j += kModThreads) {
+        float out;
+        if (d.upd == TIG_UPD_GRU) {
+            const float rr = 1.0f / (1.0f + expf(-(gi[j] + gh[j])));
+            const float zz = 1.0f / (1.0f + expf(-(gi[M + j] + gh[M + j])));
+            const float nn = tanhf(gi[2 * M + j] + rr * gh[2 * M + j]);
+            out = (1.0f - zz) * nn + zz * h[j];
+        } else {
+            out = tanhf(gi[j] + gh[j]);
+        }
+        a.staging[(size_t)w.entry * M + j] = out;
+    }
+}
+
+__global__ void __launch_bounds__(kModThreads) k_mod_commit(StepArgs a, int M)
+{
+    overwrite_memory(a, M, (int)(blockIdx.x * kModWaves + threadIdx.x / kWave), (int)(gridDim.x * kModWaves));
+}
+
+// ------------------------------------------------------------------------------------------
+// Identity / time-projection embedding: emb[q] = r_u(t), or (1 + (t - last_update[u]) w_p) * r_u(t),
+// for the queries [sources | destinations | negatives]; also the winner flags out.
+__global__ void __launch_bounds__(kModThreads) k_mod_simple(StepArgs a, ModDims d, ModParams p)
+{
+    const int M = d.M;
+    const size_t n = (size_t)a.roles * a.count * M;
+    const size_t idx = (size_t)blockIdx.x * kModThreads + threadIdx.x;
+    if (idx < (size_t)2 * a.count && a.out_is_winner && a.win_flags)
+        a.out_is_winner[idx] = a.win_flags[idx];
+    if (idx >= n)
+        return;
+    const int q = (int)(idx / M), j = (int)(idx - (size_t)q * M);
+    const int role = q / a.count, b = q - role * a.count;
+    const int64_t e = a.first_eid + b;
+    const int32_t u = role == 0 ? a.src[e] : (role == 1 ? a.dst[e] : a.neg[b]);
+    float v = repr_elem(a, p, M, u, j);
+    if (d.emb == TIG_EMB_TIME_PROJECTION && u >= 0 && (int64_t)u < a.num_nodes)
+        v = (float)((1.0 + (a.ts[e] - a.lu[u]) * (double)p.time_proj_w[j]) * (double)v);
+    a.emb[idx] = v;
+}
+
+// ------------------------------------------------------------------------------------------
+// Attention embedding of one distinct query, direct form.
+__global__ void __launch_bounds__(kModThreads) k_mod_rows(StepArgs a, ModDims d, ModParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    int n_u = *a.qs.n_u;
+    n_u = n_u < 2 * a.count ? n_u : 2 * a.count;
+    const int n_rows = n_u + (a.roles == 3 ? a.count : 0);
+    const int x = (int)blockIdx.x;
+    if (x >= n_rows)
+        return;
+    const int M = d.M, F = d.F, E = d.E, K = d.K, H = d.H, da = d.da, dh = d.dh, dkv = d.dkv;
+    double *dts = (double *)smem;     // [K]
+    int *nbrs = (int *)(dts + K);     // [K]
+    int *eids = nbrs + K;             // [K]
+    int *meta = eids + K;             // [2] cnt, node (+ 2 of padding)
+    float *q_in = (float *)(meta + 4);  // [da]
+    float *Qv = q_in + da;            // [da]
+    float *kv = Qv + da;              // [K x dkv]
+    float *KPs = kv + K * dkv;        // [K x da]
+    float *VPs = KPs + K * da;        // [K x da]
+    float *sc = VPs + K * da;         // [H x K]
+    float *o = sc + H * K;            // [da]
+    float *xcat = o + da;             // [da + M]: attn | r_u
+    float *h1 = xcat + da + M;        // [E]
+
+    const int q = x < n_u ? x : 2 * a.count + (x - n_u);
+    if (x >= n_u && threadIdx.x < kWave) {  // a negative: the first wavefront looks up its neighbours
+        int32_t rf, ee;
+        double ts_k;
+        (void)finish_negative(a, K, x - n_u, rf, ee, ts_k);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int c = a.qs.cnt[q];
+        meta[0] = c < 0 ? 0 : (c > K ? K : c);
+        meta[1] = a.qs.node[q];
+    }
+    const double t_q = a.qs.t[q];
+    if ((int)threadIdx.x < K) {
+        nbrs[threadIdx.x] = a.qs.nbr[(size_t)q * K + threadIdx.x];
+        eids[threadIdx.x] = a.qs.eid[(size_t)q * K + threadIdx.x];
+        dts[threadIdx.x] = t_q - a.qs.ts[(size_t)q * K + threadIdx.x];
+    }
+    __syncthreads();
+    const int cnt = meta[0];
+    const int32_t u = meta[1];
+    for (int j = threadIdx.x; j < da; j += kModThreads) {
+        const float v = j < M ? repr_elem(a, p, M, u, j) : time_enc(p.time_w_rev[j - M], p.time_b_rev[j - M], 0.0);
+        q_in[j] = v;
+        if (j < M)
+            xcat[da + j] = v;
+    }
+    // key / value rows [r_v | e | Phi(t - t_k)]
+    for (int idx = threadIdx.x; idx < cnt * dkv; idx += kModThreads) {
+        const int k = idx / dkv, i = idx - k * dkv;
+        float v;
+        if (i < M)
+            v = repr_elem(a, p, M, nbrs[k], i);
+        else if (i < M + F)
+            v = eids[k] >= 0 ? a.edge_feat[(size_t)eids[k] * F + (i - M)] : 0.0f;
+        else
+            v = time_enc(p.time_w_rev[i - M - F], p.time_b_rev[i - M - F], dts[k]);
+        kv[idx] = v;
+    }
+    __syncthreads();
+    if (cnt > 0) {
+        matvec_t(p.T_Q, da, da, q_in, p.b_Q, Qv);
+        multivec_t(p.T_K, dkv, da, kv, dkv, cnt, p.b_K, KPs);
+        multivec_t(p.T_V, dkv, da, kv, dkv, cnt, p.b_V, VPs);
+        __syncthreads();
+        const float scale = 1.0f / sqrtf((float)dh);
+        for (int idx = threadIdx.x; idx < H * cnt; idx += kModThreads) {
+            const int hh = idx / cnt, k = idx - hh * cnt;
+            float s = 0.0f;
+            for (int e = 0; e < dh; ++e)
+                s += Qv[hh * dh + e] * KPs[(size_t)k * da + hh * dh + e];
+            sc[hh * K + k] = s * scale;
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < H) {
+            const int hh = threadIdx.x;
+            float mx = -INFINITY, sum = 0.0f;
+            for (int k = 0; k < cnt; ++k)
+                mx = fmaxf(mx, sc[hh * K + k]);
+            for (int k = 0; k < cnt; ++k) {
+                const float e = expf(sc[hh * K + k] - mx);
+                sc[hh * K + k] = e;
+                sum += e;
+            }
+            for (int k = 0; k < cnt; ++k)
+                sc[hh * K + k] /= sum;
+        }
+        __syncthreads();
+        for (int j = threadIdx.x; j < da; j += kModThreads) {
+            const int hh = j / dh;
+            float acc = 0.0f;
+            for (int k = 0; k < cnt; ++k)
+                acc += sc[hh * K + k] * VPs[(size_t)k * da + j];
+            o[j] = acc;
+        }
+        __syncthreads();
+        matvec_t(p.T_O, da, da, o, p.b_O, xcat);
+    } else {
+        for (int j = threadIdx.x; j < da; j += kModThreads)
+            xcat[j] = 0.0f;  // an empty neighbourhood gives the zero vector (no bias)
+    }
+    __syncthreads();
+    matvec_t(p.T_m1, da + M, E, xcat, p.b_m1, h1);
+    __syncthreads();
+    for (int j = threadIdx.x; j < E; j += kModThreads)
+        h1[j] = fmaxf(h1[j], 0.0f);
+    __syncthreads();
+    for (int j = threadIdx.x; j < E; j += kModThreads) {
+        float acc = p.b_m2[j];
+        for (int i = 0; i < E; ++i)
+            acc += p.T_m2[(size_t)i * E + j] * h1[i];
+        a.emb_u[(size_t)q * E + j] = acc;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+__device__ inline int mod_row_of_entry(const QuerySet &qs, int i, int entries)
+{
+    int s = qs.slot[i];
+    if (s < 0) {
+        const int rep = -s - 1;
+        s = rep < entries ? qs.slot[rep] : 0;
+    }
+    return s >= 0 && s < entries ? s : 0;
+}
+
+// Both logits of kEV events.  from_rows: the embeddings are the distinct rows of the query set (and
+// are copied out per query here); else they are already in the output, [sources | destinations |
+// negatives].
+__global__ void __launch_bounds__(kModThreads) k_mod_decode(StepArgs a, ModDims d, ModParams p, int from_rows)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int E = d.E, B = a.count, roles = a.roles;
+    float *em = (float *)smem;            // [kEV][3][E]
+    float *part = em + kEV * 3 * E;       // [kEV][2][waves]
+    const int b0 = (int)blockIdx.x * kEV;
+    const int nev = B - b0 < kEV ? B - b0 : kEV;
+    for (int idx = threadIdx.x; idx < nev * roles * E; idx += kModThreads) {
+        const int ev = idx / (roles * E), rem = idx - ev * roles * E;
+        const int r = rem / E, j = rem - r * E;
+        const int b = b0 + ev;
+        float v;
+        if (from_rows) {
+            const int row = r < 2 ? mod_row_of_entry(a.qs, 2 * b + r, 2 * B) : 2 * B + b;
+            v = a.emb_u[(size_t)row * E + j];
+            a.emb[((size_t)r * B + b) * E + j] = v;
+        } else {
+            v = a.emb[((size_t)r * B + b) * E + j];
+        }
+        em[(ev * 3 + r) * E + j] = v;
+    }
+    __syncthreads();
+    float sp[kEV], sn[kEV];
+#pragma unroll
+    for (int ev = 0; ev < kEV; ++ev)
+        sp[ev] = sn[ev] = 0.0f;
+    for (int j = threadIdx.x; j < E; j += kModThreads) {
+        float ya[kEV], yb[kEV], yn[kEV];
+#pragma unroll
+        for (int ev = 0; ev < kEV; ++ev)
+            ya[ev] = yb[ev] = yn[ev] = 0.0f;
+        for (int i = 0; i < E; ++i) {
+            const float wa = p.T_d1[(size_t)i * E + j], wb = p.T_d1[(size_t)(E + i) * E + j];
+#pragma unroll
+            for (int ev = 0; ev < kEV; ++ev) {
+                const float *row = em + (size_t)(ev < nev ? ev : 0) * 3 * E;
+                ya[ev] += wa * row[i];
+                yb[ev] += wb * row[E + i];
+                if (roles == 3)
+                    yn[ev] += wb * row[2 * E + i];
+            }
+        }
+        const float b1 = p.b_d1[j], w2 = p.w_d2[j];
+#pragma unroll
+        for (int ev = 0; ev < kEV; ++ev) {
+            sp[ev] += w2 * fmaxf(ya[ev] + yb[ev] + b1, 0.0f);
+            sn[ev] += w2 * fmaxf(ya[ev] + yn[ev] + b1, 0.0f);
+        }
+    }
+#pragma unroll
+    for (int ev = 0; ev < kEV; ++ev) {
+        const float s1 = wave_sum_uniform(sp[ev]), s2 = wave_sum_uniform(sn[ev]);
+        if (lane_id() == 0) {
+            part[(ev * 2 + 0) * kModWaves + wave_id()] = s1;
+            part[(ev * 2 + 1) * kModWaves + wave_id()] = s2;
+        }
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < nev * 2) {
+        const int ev = threadIdx.x >> 1, pr = threadIdx.x & 1;
+        float s = p.b_d2[0];
+        for (int w = 0; w < kModWaves; ++w)
+            s += part[(ev * 2 + pr) * kModWaves + w];
+        if (pr == 0)
+            a.score_pos[b0 + ev] = s;
+        else if (roles == 3)
+            a.score_neg[b0 + ev] = s;
+    }
+}
+
+__global__ void k_mod_transpose(float *dst, const float *src, int rows, int cols)  // dst[c][r] = src[r][c]
+{
+    const size_t n = (size_t)rows * cols, stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const size_t r = i / cols, c = i - r * cols;
+        dst[c * rows + r] = src[i];
+    }
+}
+
+__global__ void k_mod_revolutions(double *out, const float *in, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n)
+        out[i] = (double)in[i] / 6.283185307179586476925286766559;
+}
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+int update_lds(const ModDims &d)
+{
+    const int rest = d.M + d.T + d.F;
+    return rest * 8 + (d.Dmsg + d.M + 2 * d.G * d.M) * 4 + (kModThreads + kModWaves + 2) * 4;
+}
+
+int rows_lds(const ModDims &d)
+{
+    return d.K * 8 + (2 * d.K + 4) * 4 +
+           (2 * d.da + d.K * d.dkv + 2 * d.K * d.da + d.H * d.K + d.da + d.da + d.M + d.E) * 4;
+}
+
+int decode_lds(const ModDims &d) { return (kEV * 3 * d.E + kEV * 2 * kModWaves) * 4; }
+
+// One matrix of the workspace: raw copy (kept for nothing but the transpose) and its transpose.
+struct MatJob {
+    const float *src;     // caller's [rows x cols]
+    const float **dst_t;  // where the transposed copy's pointer goes
+    int rows, cols;
+};
+
+struct VecJob {
+    const float *src;
+    const float **dst;
+    size_t n;
+};
+
+}  // namespace
+
+// Layout of the attached workspace: [vectors | transposed matrices | raw staging of one matrix |
+// node features].  Fills `p` when base != NULL.
+static size_t mod_layout(const Dims &d, int agg, int upd, int emb, bool node_feat, int64_t num_nodes, char *base,
+                         ModParams *p, float **raw_stage, float **nf_dst)
+{
+    size_t off = 0;
+    auto take = [&](size_t count, size_t elem) -> void * {
+        void *q = base ? base + off : nullptr;
+        off += align_up(count * elem);
+        return q;
+    };
+    const size_t M = d.M, T = d.T, E = d.E, da = d.da, dkv = d.dkv, D = d.Dmsg, G = upd == TIG_UPD_GRU ? 3 : 1;
+    const bool attn = emb == TIG_EMB_ATTENTION;
+    ModParams q = {};
+    q.agg = agg;
+    q.upd = upd;
+    q.emb = emb;
+    q.time_w_rev = (const double *)take(T, 8);
+    q.time_b_rev = (const double *)take(T, 8);
+    q.b_i = (const float *)take(G * M, 4);
+    q.b_h = (const float *)take(G * M, 4);
+    q.T_i = (const float *)take(D * G * M, 4);
+    q.T_h = (const float *)take(M * G * M, 4);
+    size_t biggest = D * G * M;
+    if (attn) {
+        q.b_Q = (const float *)take(da, 4);
+        q.b_K = (const float *)take(da, 4);
+        q.b_V = (const float *)take(da, 4);
+        q.b_O = (const float *)take(da, 4);
+        q.b_m1 = (const float *)take(E, 4);
+        q.b_m2 = (const float *)take(E, 4);
+        q.T_Q = (const float *)take(da * da, 4);
+        q.T_K = (const float *)take(dkv * da, 4);
+        q.T_V = (const float *)take(dkv * da, 4);
+        q.T_O = (const float *)take(da * da, 4);
+        q.T_m1 = (const float *)take((da + M) * E, 4);
+        q.T_m2 = (const float *)take(E * E, 4);
+        const size_t c[] = {da * da, dkv * da, (da + M) * E, E * E};
+        for (size_t v : c)
+            biggest = v > biggest ? v : biggest;
+    }
+    q.b_d1 = (const float *)take(E, 4);
+    q.w_d2 = (const float *)take(E, 4);
+    q.b_d2 = (const float *)take(1, 4);
+    q.T_d1 = (const float *)take(2 * E * E, 4);
+    biggest = 2 * E * E > biggest ? 2 * E * E : biggest;
+    if (emb == TIG_EMB_TIME_PROJECTION)
+        q.time_proj_w = (const float *)take(M, 4);
+    float *stage = (float *)take(biggest > T ? biggest : T, 4);
+    float *nf = node_feat ? (float *)take((size_t)num_nodes * M, 4) : nullptr;
+    q.node_feat = nf;
+    if (p)
+        *p = q;
+    if (raw_stage)
+        *raw_stage = stage;
+    if (nf_dst)
+        *nf_dst = nf;
+    return off;
+}
+
+size_t modules_workspace_bytes(const Dims &d, const tig_modules &m, int64_t num_nodes)
+{
+    return mod_layout(d, m.aggregator, m.updater, m.embedding, m.node_feat != nullptr, num_nodes, nullptr, nullptr,
+                      nullptr, nullptr);
+}
+
+bool modules_supported(const Dims &d, const tig_modules &m)
+{
+    ModParams p = {};
+    p.agg = m.aggregator;
+    p.upd = m.updater;
+    p.emb = m.embedding;
+    const ModDims md = mod_dims(d, p);
+    if (m.embedding != TIG_EMB_ATTENTION && d.E != d.M)
+        return false;
+    return d.prec == TIG_FP32 && update_lds(md) <= 160 * 1024 && rows_lds(md) <= 160 * 1024 &&
+           decode_lds(md) <= 160 * 1024 && d.K <= kModThreads;
+}
+
+hipError_t modules_attach(const Dims &d, const tig_modules &m, const tig_weights &w, int64_t num_nodes, void *workspace,
+                          ModParams *out, hipStream_t s)
+{
+    ModParams p;
+    float *stage = nullptr, *nf = nullptr;
+    mod_layout(d, m.aggregator, m.updater, m.embedding, m.node_feat != nullptr, num_nodes, (char *)workspace, &p, &stage, &nf);
+    const ModDims md = mod_dims(d, p);
+    const int M = d.M, T = d.T, E = d.E, da = d.da, dkv = d.dkv, D = d.Dmsg, GM = md.G * d.M;
+    hipError_t e;
+    auto vec = [&](const float *dst, const float *src, size_t n) -> hipError_t {
+        return hipMemcpyAsync((void *)dst, src, 4 * n, hipMemcpyDefault, s);
+    };
+    // a matrix goes through the staging area (the source may be host memory) and is transposed from there
+    auto mat = [&](const float *dst_t, const float *src, int rows, int cols) -> hipError_t {
+        const size_t n = (size_t)rows * cols;
+        hipError_t e2 = hipMemcpyAsync(stage, src, 4 * n, hipMemcpyDefault, s);
+        if (e2 != hipSuccess)
+            return e2;
+        hipLaunchKernelGGL(k_mod_transpose, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (float *)dst_t, stage, rows, cols);
+        return hipGetLastError();
+    };
+    auto rev = [&](const double *dst, const float *src) -> hipError_t {
+        hipError_t e2 = hipMemcpyAsync(stage, src, 4 * (size_t)T, hipMemcpyDefault, s);
+        if (e2 != hipSuccess)
+            return e2;
+        hipLaunchKernelGGL(k_mod_revolutions, dim3((T + 255) / 256), dim3(256), 0, s, (double *)dst, stage, T);
+        return hipGetLastError();
+    };
+#define MOD_TRY(x)            \
+    if ((e = (x)) != hipSuccess) \
+        return e
+    MOD_TRY(rev(p.time_w_rev, w.time_w));
+    MOD_TRY(rev(p.time_b_rev, w.time_b));
+    MOD_TRY(vec(p.b_i, w.b_i, GM));
+    MOD_TRY(vec(p.b_h, w.b_h, GM));
+    MOD_TRY(mat(p.T_i, w.W_i, GM, D));
+    MOD_TRY(mat(p.T_h, w.W_h, GM, M));
+    if (m.embedding == TIG_EMB_ATTENTION) {
+        MOD_TRY(vec(p.b_Q, w.b_Q, da));
+        MOD_TRY(vec(p.b_K, w.b_K, da));
+        MOD_TRY(vec(p.b_V, w.b_V, da));
+        MOD_TRY(vec(p.b_O, w.b_O, da));
+        MOD_TRY(vec(p.b_m1, w.b_m1, E));
+        MOD_TRY(vec(p.b_m2, w.b_m2, E));
+        MOD_TRY(mat(p.T_Q, w.W_Q, da, da));
+        MOD_TRY(mat(p.T_K, w.W_K, da, dkv));
+        MOD_TRY(mat(p.T_V, w.W_V, da, dkv));
+        MOD_TRY(mat(p.T_O, w.W_O, da, da));
+        MOD_TRY(mat(p.T_m1, w.W_m1, E, da + M));
+        MOD_TRY(mat(p.T_m2, w.W_m2, E, E));
+    }
+    MOD_TRY(vec(p.b_d1, w.b_d1, E));
+    MOD_TRY(vec(p.w_d2, w.w_d2, E));
+    MOD_TRY(vec(p.b_d2, w.b_d2, 1));
+    MOD_TRY(mat(p.T_d1, w.W_d1, E, 2 * E));
+    if (m.embedding == TIG_EMB_TIME_PROJECTION)
+        MOD_TRY(vec(p.time_proj_w, m.time_proj_w, M));
+    if (nf)
+        MOD_TRY(hipMemcpyAsync(nf, m.node_feat, 4 * (size_t)num_nodes * M, hipMemcpyDefault, s));
+    MOD_TRY(hipFuncSetAttribute((const void *)k_mod_update, hipFuncAttributeMaxDynamicSharedMemorySize, update_lds(md)));
+    MOD_TRY(hipFuncSetAttribute((const void *)k_mod_rows, hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds(md)));
+    MOD_TRY(hipFuncSetAttribute((const void *)k_mod_decode, hipFuncAttributeMaxDynamicSharedMemorySize, decode_lds(md)));
+#undef MOD_TRY
+    *out = p;
+    return hipStreamSynchronize(s);
+}
+
+// Everything of a step after the selection (and, for the attention embedding, the query
+// preparation): state update, memory overwrite, embedding, decoder, inspection outputs.
+// `marks`: NULL, or two events recorded after the state update + overwrite and after the rest.
+hipError_t launch_modules(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
+                          const ModParams &p, hipStream_t s, hipEvent_t *marks)
+{
+    const ModDims md = mod_dims(d, p);
+    hipError_t e;
+    if (a.msg_count > 0) {
+        hipLaunchKernelGGL(k_mod_update, dim3(2 * a.msg_count), dim3(kModThreads), update_lds(md), s, a, md, p);
+        hipLaunchKernelGGL(k_mod_commit, dim3(64), dim3(kModThreads), 0, s, a, d.M);
+        if ((e = hipGetLastError()) != hipSuccess)
+            return e;
+    }
+    if (marks && (e = hipEventRecord(marks[0], s)) != hipSuccess)
+        return e;
+    // from here on every state row is read from the memory table: nothing is "applied" any more
+    StepArgs b = a;
+    b.msg_count = 0;
+    const int B = a.count;
+    if (p.emb == TIG_EMB_ATTENTION) {
+        b.finish_here = 1;  // slots of the query set (its row references all name memory rows)
+        if ((e = launch_gru(d, plan, pw, b, s)) != hipSuccess)
+            return e;
+        hipLaunchKernelGGL(k_mod_rows, dim3(3 * B), dim3(kModThreads), rows_lds(md), s, b, md, p);
+        hipLaunchKernelGGL(k_mod_decode, dim3((B + kEV - 1) / kEV), dim3(kModThreads), decode_lds(md), s, b, md, p, 1);
+        if ((e = hipGetLastError()) != hipSuccess)
+            return e;
+        // inspection outputs; the query set's counter is cleared for its next preparation
+        if ((e = launch_closing(d, plan, pw, b, GruAhead{}, s, false)) != hipSuccess)
+            return e;
+    } else {
+        const size_t n = (size_t)a.roles * B * d.M;
+        hipLaunchKernelGGL(k_mod_simple, dim3((unsigned)((n + kModThreads - 1) / kModThreads)), dim3(kModThreads), 0, s, b, md, p);
+        hipLaunchKernelGGL(k_mod_decode, dim3((B + kEV - 1) / kEV), dim3(kModThreads), decode_lds(md), s, b, md, p, 0);
+        if ((e = hipGetLastError()) != hipSuccess)
+            return e;
+    }
+    if (marks && (e = hipEventRecord(marks[1], s)) != hipSuccess)
+        return e;
+    return hipSuccess;
+}
+
+}  // namespace tig

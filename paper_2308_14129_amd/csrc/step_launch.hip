@@ -72,6 +72,12 @@ hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeight
     }
     if ((e = stamp()) != hipSuccess)
         return e;
+    if (sp.mods) {
+        if ((e = launch_modules(d, plan, pw, a, *sp.mods, s, marks ? marks + mark : nullptr)) != hipSuccess)
+            return e;
+        mark += marks ? 2 : 0;
+        return stamp();
+    }
     if (sp.gru_now && (e = launch_gru(d, plan, pw, a, s)) != hipSuccess)
         return e;
     if ((e = stamp()) != hipSuccess)

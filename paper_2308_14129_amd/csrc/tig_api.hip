@@ -86,6 +86,9 @@ struct tig_ctx {
     int last_launches; // kernels enqueued by the last tig_step
     void *static_scratch;  // this device's copy of g_static_scratch
     void *train_ws;        // training workspace (master weights, gradients, the backward pass's buffers), or NULL
+    bool has_model;        // tig_init was given weights (the headline instance's prepared weights exist)
+    void *mods_ws;         // workspace of an attached module selection, or NULL
+    ModParams mods;        // ... and its parameters
     // Two pinned host words that the device can write: every step leaves its numbers of distinct
     // query rows and of winners there, and later calls shape their launches by them (hints that
     // may be a few steps old; results do not depend on them).  NULL if the allocation failed.
@@ -356,7 +359,7 @@ int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *w
     int rc = tig_workspace_bytes(cfg, graph, &need_p, &need_s);
     if (rc != TIG_OK)
         return rc;
-    if (!weights || weights->struct_size != sizeof(tig_weights) || !persistent || !scratch)
+    if ((weights && weights->struct_size != sizeof(tig_weights)) || !persistent || !scratch)
         return TIG_EINVAL;
     const int64_t N = graph->num_nodes, E = graph->num_events;
     if (E > 0 && (!graph->src || !graph->dst || !graph->ts || !graph->edge_feat))
@@ -368,7 +371,7 @@ int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *w
     const Dims d = make_dims(*cfg);
     WeightField wf[32];
     const int nwf = weight_fields(d, wf);
-    for (int i = 0; i < nwf; ++i)
+    for (int i = 0; weights && i < nwf; ++i)
         if (!(weights->*(wf[i].member)))
             return TIG_EINVAL;
 
@@ -440,7 +443,8 @@ int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *w
     }
 
     // weights: stage raw fp32 copies, then fold / pad / reorder
-    {
+    ctx->has_model = weights != nullptr;
+    if (weights) {
         char *wbase = (char *)scratch + 256;
         RawWeights R = raw_weights_layout(d, wbase);
         for (int i = 0; i < nwf; ++i)
@@ -521,6 +525,15 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
         return fail(ctx, TIG_EINVAL, "tig_step: required output pointer is NULL");
     if (batch->first_eid < ctx->cursor)
         return fail(ctx, TIG_EORDER, "tig_step: batch starts before the end of the previous one");
+    const bool general = ctx->mods_ws != nullptr;
+    if (!general && !ctx->has_model)
+        return fail(ctx, TIG_EINVAL, "tig_step: the context was created without weights and no module selection is attached");
+    if (general && (use_static || train))
+        return fail(ctx, TIG_EINVAL, "tig_step_static / tig_train_step: the context runs an attached module selection");
+    // a training step or a step of a module selection prepares nothing for a later step and takes
+    // nothing prepared for it
+    const bool solo = train || general;
+    const bool wants_queries = !general || ctx->mods.emb == TIG_EMB_ATTENTION;
     StepScratch st = ctx->S;
     if (use_static) {
         if (ctx->d.deferred)
@@ -557,10 +570,12 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     a.emb = out->emb;
     a.score_pos = out->score_pos;
     a.score_neg = out->score_neg;
-    a.out_nbr_node = out->nbr_node;
-    a.out_nbr_eid = out->nbr_eid;
-    a.out_nbr_ts = out->nbr_ts;
-    a.out_nbr_cnt = out->nbr_cnt;
+    if (wants_queries) {
+        a.out_nbr_node = out->nbr_node;
+        a.out_nbr_eid = out->nbr_eid;
+        a.out_nbr_ts = out->nbr_ts;
+        a.out_nbr_cnt = out->nbr_cnt;
+    }
     a.out_is_winner = out->is_winner;
     a.rows_seen = ctx->rows_seen_dev;
     if (ctx->rows_seen_host) {
@@ -573,8 +588,7 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
 
     // What the embedding launch can do on the side for a later step (never for a static call).
     const bool one_wg = winners_in_one_launch(count);
-    // (a training step prepares nothing for a later step and takes nothing prepared for it)
-    const int spare = use_static || train ? 0 : embed_spare_workgroups(d, ctx->plan, a.roles, count);
+    const int spare = use_static || solo ? 0 : embed_spare_workgroups(d, ctx->plan, a.roles, count);
     uint32_t epoch = ctx->epoch;
     bool clear_tab = use_static;  // the static array's table holds claims of unknown epochs
     auto next_epoch = [&]() -> uint32_t {
@@ -594,12 +608,12 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
 
     // ---- the distinct queries of this batch: prepared by the previous step's embedding launch if
     // that step guessed this batch (it reads the event stream and the adjacency only), else now
-    const bool q_ready = !use_static && !train && ctx->ahead_q_valid && ctx->ahead_q_first == first &&
+    const bool q_ready = !use_static && !solo && ctx->ahead_q_valid && ctx->ahead_q_first == first &&
                          ctx->ahead_q_count == count;
     const int qi = use_static ? 0 : (q_ready ? ctx->qcur ^ 1 : ctx->qcur);
     a.qs = st.qs[qi];
     a.finish_here = !(q_ready && ctx->ahead_q_finished);
-    if (!q_ready) {
+    if (!q_ready && wants_queries) {
         ded_now = make_dedup(st, st.qs[qi], first, count, next_epoch(), one_wg);
         sp.prep_ded = &ded_now;
     }
@@ -609,7 +623,7 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     bool w_ready = false;
     if (!d.deferred) {
         // this batch's: selected ahead like the queries, else now
-        w_ready = !use_static && !train && ctx->ahead_w_valid && ctx->ahead_w_first == first &&
+        w_ready = !use_static && !solo && ctx->ahead_w_valid && ctx->ahead_w_first == first &&
                   ctx->ahead_w_count == count;
         wi = use_static ? 0 : (w_ready ? ctx->wcur ^ 1 : ctx->wcur);
         a.msg_first_eid = first;
@@ -643,9 +657,13 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     // ---- the GRU of the applied batch: run by the previous step's closing launch if that step knew
     // the batch (and the memory has not changed since), else now, together with what is left of
     // this step's query preparation
-    const bool g_ready = !use_static && ctx->ahead_g_valid && a.msg_count > 0 && ctx->ahead_g_first == a.msg_first_eid &&
+    const bool g_ready = !use_static && !general && ctx->ahead_g_valid && a.msg_count > 0 && ctx->ahead_g_first == a.msg_first_eid &&
                          ctx->ahead_g_count == a.msg_count && !a.finish_here && (d.deferred || w_ready);
-    sp.gru_now = !g_ready && (a.msg_count > 0 || a.finish_here);
+    sp.gru_now = !general && !g_ready && (a.msg_count > 0 || a.finish_here);
+    if (general) {
+        sp.mods = &ctx->mods;
+        launches += wants_queries ? 3 : 2;  // update, overwrite, [finishing pass,] embedding, decoder[, inspection]
+    }
     if (sp.big_sel)
         launches += 2;
     if (sp.prep_sel || sp.prep_ded)
@@ -682,7 +700,7 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     // ---- The closing launch also runs the GRU of the batch the next step applies, once that batch's
     // winners are known: in the update-first order the guessed batch (selected by this step's
     // embedding launch), in the deferred order this step's own batch (whatever comes next).
-    if (!use_static && !train) {
+    if (!use_static && !solo) {
         if (!d.deferred && a.sel.count > 0)
             sp.ahead = GruAhead{a.sel.first_eid, a.sel.count, st.win[wi ^ 1], st.n_win[wi ^ 1]};
         else if (d.deferred)
@@ -779,6 +797,8 @@ int tig_train_attach(tig_ctx *ctx, const tig_weights *weights, void *workspace, 
     for (int i = 0; i < nwf; ++i)
         if (!(weights->*(wf[i].member)))
             return fail(ctx, TIG_EINVAL, "tig_train_attach: a weight pointer is NULL");
+    if (ctx->mods_ws || !ctx->has_model)
+        return fail(ctx, TIG_EINVAL, "tig_train_attach: the context runs a module selection or has no model of its own");
     if (!train_supported(ctx->d))
         return fail(ctx, TIG_EINVAL, "tig_train_attach: training needs an fp32 context whose rows fit the backward kernels");
     if (workspace_bytes < train_workspace_bytes(ctx->d))
@@ -818,6 +838,75 @@ int tig_train_get(tig_ctx *ctx, int32_t what, const tig_weights *dst)
     const hipError_t e = train_copy_out(ctx->d, ctx->train_ws, what == 1, *dst, ctx->stream);
     if (e != hipSuccess)
         return fail(ctx, TIG_EHIP, "tig_train_get", e);
+    return TIG_OK;
+}
+
+// ---- other instances of the general architecture (Sec. II-C) -------------------------------------
+
+static int check_modules(const tig_modules *m)
+{
+    if (!m || m->struct_size != sizeof(tig_modules))
+        return TIG_EINVAL;
+    if (m->aggregator != TIG_AGG_LAST && m->aggregator != TIG_AGG_MEAN)
+        return TIG_EINVAL;
+    if (m->updater != TIG_UPD_GRU && m->updater != TIG_UPD_RNN)
+        return TIG_EINVAL;
+    if (m->embedding != TIG_EMB_ATTENTION && m->embedding != TIG_EMB_IDENTITY && m->embedding != TIG_EMB_TIME_PROJECTION)
+        return TIG_EINVAL;
+    if (m->embedding == TIG_EMB_TIME_PROJECTION && !m->time_proj_w)
+        return TIG_EINVAL;
+    return TIG_OK;
+}
+
+int tig_modules_workspace_bytes(const tig_config *cfg, const tig_modules *modules, int64_t num_nodes, size_t *bytes)
+{
+    int rc = check_config(cfg);
+    if (rc == TIG_OK)
+        rc = check_modules(modules);
+    if (rc != TIG_OK)
+        return rc;
+    if (!bytes || num_nodes < 1 || num_nodes > 0x7FFFFFFF)
+        return TIG_EINVAL;
+    const Dims d = make_dims(*cfg);
+    if (!modules_supported(d, *modules))
+        return TIG_EINVAL;
+    *bytes = modules_workspace_bytes(d, *modules, num_nodes);
+    return TIG_OK;
+}
+
+int tig_modules_attach(tig_ctx *ctx, const tig_modules *modules, const tig_weights *weights, void *workspace,
+                       size_t workspace_bytes)
+{
+    if (!ctx)
+        return TIG_EINVAL;
+    if (check_modules(modules) != TIG_OK || !weights || weights->struct_size != sizeof(tig_weights) || !workspace ||
+        ((uintptr_t)workspace & 255))
+        return fail(ctx, TIG_EINVAL, "tig_modules_attach: NULL / misaligned argument, wrong struct_size or unknown selector");
+    if (ctx->train_ws)
+        return fail(ctx, TIG_EINVAL, "tig_modules_attach: the context has a training workspace");
+    if (!modules_supported(ctx->d, *modules))
+        return fail(ctx, TIG_EINVAL, "tig_modules_attach: needs an fp32 context (emb_dim == mem_dim unless the embedding is "
+                                     "attention) whose rows fit the kernels");
+    const tig_weights &w = *weights;
+    const bool attn = modules->embedding == TIG_EMB_ATTENTION;
+    if (!w.time_w || !w.time_b || !w.W_i || !w.b_i || !w.W_h || !w.b_h || !w.W_d1 || !w.b_d1 || !w.w_d2 || !w.b_d2 ||
+        (attn && (!w.W_Q || !w.b_Q || !w.W_K || !w.b_K || !w.W_V || !w.b_V || !w.W_O || !w.b_O || !w.W_m1 || !w.b_m1 ||
+                  !w.W_m2 || !w.b_m2)))
+        return fail(ctx, TIG_EINVAL, "tig_modules_attach: a weight pointer the selection needs is NULL");
+    if (workspace_bytes < modules_workspace_bytes(ctx->d, *modules, ctx->num_nodes))
+        return fail(ctx, TIG_ENOSPACE, "tig_modules_attach: workspace too small");
+    hipError_t e = hipStreamSynchronize(ctx->stream);
+    ModParams mp;
+    if (e == hipSuccess)
+        e = modules_attach(ctx->d, *modules, w, ctx->num_nodes, workspace, &mp, ctx->stream);
+    if (e != hipSuccess)
+        return fail(ctx, TIG_EHIP, "tig_modules_attach", e);
+    ctx->mods = mp;
+    ctx->mods_ws = workspace;
+    // nothing prepared by earlier steps of another model is trusted
+    ctx->ahead_g_valid = false;
+    ctx->ahead_w_valid = false;
+    ctx->ahead_q_valid = false;
     return TIG_OK;
 }
 

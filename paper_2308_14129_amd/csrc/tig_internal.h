@@ -252,6 +252,7 @@ struct StepPlan {
     float *loss_out;
     int32_t *clear_first;       // a counter to clear ahead of everything, or NULL
     GruAhead ahead;             // GRU workgroups of the closing launch
+    const struct ModParams *mods;  // a context with a module selection: its kernels instead of GRU, embedding and closing launches
 };
 hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw,
                        const StepArgs &a, const StepPlan &sp, hipStream_t s, hipEvent_t *marks);
@@ -277,6 +278,26 @@ hipError_t train_attach(const Dims &d, const tig_weights &w, void *workspace, vo
 hipError_t train_copy_out(const Dims &d, void *workspace, bool grads, const tig_weights &out, hipStream_t s);
 hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void *packed, PackedWeights *pw, float lr,
                         float *loss_out, hipStream_t s);
+// ---- other instances of the general architecture (modules.hip) ----
+// Module selection of a context and its weights: transposed copies ([in x out]) in the attached workspace.
+struct ModParams {
+    int agg, upd, emb;                         // tig_aggregator, tig_updater, tig_embedding
+    const double *time_w_rev, *time_b_rev;     // [T] time-encoding frequency / phase in revolutions
+    const float *T_i, *T_h, *b_i, *b_h;        // state update: [D_msg x GM], [M x GM], [GM], [GM] (G = 3 GRU, 1 RNN)
+    const float *T_Q, *T_K, *T_V, *T_O, *b_Q, *b_K, *b_V, *b_O;  // attention
+    const float *T_m1, *T_m2, *b_m1, *b_m2;    // merge MLP
+    const float *T_d1, *b_d1, *w_d2, *b_d2;    // decoder: [2E x E], [E], [E], [1]
+    const float *node_feat;                    // [N x M] or NULL
+    const float *time_proj_w;                  // [M] or NULL
+};
+size_t modules_workspace_bytes(const Dims &d, const tig_modules &m, int64_t num_nodes);
+bool modules_supported(const Dims &d, const tig_modules &m);
+hipError_t modules_attach(const Dims &d, const tig_modules &m, const tig_weights &w, int64_t num_nodes, void *workspace,
+                          ModParams *out, hipStream_t s);
+// state update, memory overwrite, embedding, decoder and inspection outputs of a step of a context
+// with a module selection; marks: NULL, or two events (after the overwrite, after the rest)
+hipError_t launch_modules(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
+                          const ModParams &p, hipStream_t s, hipEvent_t *marks);
 // records a failed HIP call of a context-free entry point (read back with tig_last_error(NULL)); returns TIG_EHIP
 int fail_global(const char *what, hipError_t e);
 

@@ -24,6 +24,10 @@ PRECISIONS = {"fp32": TIG_FP32, "bf16": TIG_BF16_MFMA}
 TIG_UPDATE_FIRST, TIG_DEFERRED = 0, 1
 MESSAGE_ORDERS = {"update_first": TIG_UPDATE_FIRST, "deferred": TIG_DEFERRED}
 
+AGGREGATORS = {"last": 0, "mean": 1}
+UPDATERS = {"gru": 0, "rnn": 1}
+EMBEDDINGS = {"attention": 0, "identity": 1, "time_projection": 2}
+
 WEIGHT_NAMES = ("time_w", "time_b", "W_i", "b_i", "W_h", "b_h", "W_Q", "b_Q", "W_K", "b_K", "W_V",
                 "b_V", "W_O", "b_O", "W_m1", "b_m1", "W_m2", "b_m2", "W_d1", "b_d1", "w_d2", "b_d2")
 
@@ -45,6 +49,11 @@ class tig_weights(Structure):
     _fields_ = [("struct_size", c_uint32), ("reserved", c_uint32)] + [(n, c_void_p) for n in WEIGHT_NAMES]
 
 
+class tig_modules(Structure):
+    _fields_ = [("struct_size", c_uint32), ("aggregator", c_int32), ("updater", c_int32), ("embedding", c_int32),
+                ("node_feat", c_void_p), ("time_proj_w", c_void_p)]
+
+
 class tig_batch(Structure):
     _fields_ = [("struct_size", c_uint32), ("count", c_int32), ("first_eid", c_int64),
                 ("neg_dst", c_void_p)]
@@ -59,7 +68,8 @@ class tig_out(Structure):
 
 EXPORTS = ("tig_workspace_bytes", "tig_init", "tig_step", "tig_step_static", "tig_step_profiled", "tig_reset", "tig_state_export",
            "tig_state_import", "tig_destroy", "tig_strerror", "tig_last_error", "tig_launch_info",
-           "tig_train_workspace_bytes", "tig_train_attach", "tig_train_step", "tig_train_get")
+           "tig_train_workspace_bytes", "tig_train_attach", "tig_train_step", "tig_train_get",
+           "tig_modules_workspace_bytes", "tig_modules_attach")
 
 _lib = None
 
@@ -102,6 +112,10 @@ def load_library() -> ctypes.CDLL:
     lib.tig_train_attach.argtypes = [c_void_p, POINTER(tig_weights), c_void_p, c_size_t]
     lib.tig_train_step.argtypes = [c_void_p, POINTER(tig_batch), POINTER(tig_out), c_float, c_void_p]
     lib.tig_train_get.argtypes = [c_void_p, c_int32, POINTER(tig_weights)]
+    lib.tig_modules_workspace_bytes.argtypes = [POINTER(tig_config), POINTER(tig_modules), c_int64, POINTER(c_size_t)]
+    lib.tig_modules_attach.argtypes = [c_void_p, POINTER(tig_modules), POINTER(tig_weights), c_void_p, c_size_t]
+    lib.tig_modules_workspace_bytes.restype = ctypes.c_int
+    lib.tig_modules_attach.restype = ctypes.c_int
     for n in ("tig_workspace_bytes", "tig_init", "tig_step", "tig_step_static", "tig_step_profiled", "tig_reset", "tig_state_export",
               "tig_state_import", "tig_launch_info", "tig_train_workspace_bytes", "tig_train_attach", "tig_train_step",
               "tig_train_get"):
@@ -171,10 +185,11 @@ class TigContext:
             self.stream = stream if stream is not None else torch.cuda.current_stream()
         g = tig_graph(ctypes.sizeof(tig_graph), 0, self.num_nodes, self.num_events, _addr(src),
                       _addr(dst), _addr(ts), _addr(edge_feat))
-        w = tig_weights(ctypes.sizeof(tig_weights), 0, *[_addr(weights[n]) for n in WEIGHT_NAMES])
+        w = (tig_weights(ctypes.sizeof(tig_weights), 0, *[_addr(weights[n]) for n in WEIGHT_NAMES])
+             if weights is not None else None)
         h = c_void_p(None)
         with torch.cuda.device(self.device):
-            rc = self.lib.tig_init(ctypes.byref(cfg), ctypes.byref(g), ctypes.byref(w),
+            rc = self.lib.tig_init(ctypes.byref(cfg), ctypes.byref(g), ctypes.byref(w) if w is not None else None,
                                    self.persistent.data_ptr(), pbytes, self.scratch.data_ptr(), sbytes,
                                    c_void_p(self.stream.cuda_stream), ctypes.byref(h))
         if rc != TIG_OK:
@@ -228,6 +243,22 @@ class TigContext:
         ms = (c_float * len(self.KERNEL_NAMES))()
         self._check(self.lib.tig_step_profiled(self.handle, ctypes.byref(b), ctypes.byref(o), ms))
         return [float(x) for x in ms]
+
+    # -- other instances of the general architecture -------------------------------------------
+    def modules_attach(self, weights: dict, aggregator="last", updater="gru", embedding="attention", node_feat=None):
+        """Allocates the workspace of a module selection and attaches it with `weights` (a dict that may
+        lack the attention / merge weights unless the embedding is attention; "time_proj_w" for the
+        time projection)."""
+        torch = self._torch
+        m = tig_modules(ctypes.sizeof(tig_modules), AGGREGATORS[aggregator], UPDATERS[updater], EMBEDDINGS[embedding],
+                        _addr(node_feat), _addr(weights.get("time_proj_w")))
+        n = c_size_t(0)
+        self._check(self.lib.tig_modules_workspace_bytes(ctypes.byref(self.cfg), ctypes.byref(m), self.num_nodes,
+                                                         ctypes.byref(n)))
+        self.mods_ws = torch.empty(n.value, dtype=torch.uint8, device=self.device)
+        w = tig_weights(ctypes.sizeof(tig_weights), 0, *[_addr(weights.get(k)) for k in WEIGHT_NAMES])
+        self._check(self.lib.tig_modules_attach(self.handle, ctypes.byref(m), ctypes.byref(w), self.mods_ws.data_ptr(),
+                                                n.value))
 
     # -- training ----------------------------------------------------------------------------
     def train_attach(self, weights: dict):

@@ -1,0 +1,208 @@
+"""Other instances of the general architecture (Sec. II-C: mean aggregator, RNN update, identity /
+time-projection embedding; Sec. II-A node features) on the GPU against their oracle, through the C
+ABI: tig_init without weights + tig_modules_attach, then ordinary tig_step calls.
+
+Bar: winners and (attention embedding) neighbour tables bit-exact; embeddings, scores and memory
+within 1e-4 under the per-tensor gate; last_update bit-exact; rows outside the applied batch
+bit-identical."""
+import numpy as np
+import pytest
+
+import tig_synth as S
+from oracle import modules_oracle as G
+from oracle import tig_oracle as O
+from tests.parity import gate
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+INSTANCES = {
+    "jodie_like": dict(aggregator="last", updater="rnn", embedding="time_projection"),
+    "dyrep_like": dict(aggregator="last", updater="rnn", embedding="identity"),
+    "mean_gru_identity": dict(aggregator="mean", updater="gru", embedding="identity"),
+    "mean_rnn_projection": dict(aggregator="mean", updater="rnn", embedding="time_projection"),
+    "mean_gru_attention": dict(aggregator="mean", updater="gru", embedding="attention"),
+    "last_rnn_attention": dict(aggregator="last", updater="rnn", embedding="attention"),
+    "headline": dict(aggregator="last", updater="gru", embedding="attention"),
+}
+
+
+class Case:
+    def __init__(self, w, inst, node_feat, order="update_first", max_batch=None):
+        import torch
+        from paper_2308_14129_amd import tig
+        self.w, self.inst = w, inst
+        self.g = S.make_graph(w)
+        self.W = S.make_module_weights(w, inst["updater"], inst["embedding"])
+        self.ix = O.NeighbourIndex(self.g.num_nodes, self.g.src, self.g.dst, self.g.ts)
+        self.nf = S.make_node_feat(w, self.g.num_nodes) if node_feat else None
+        self.mods = G.Modules(inst["aggregator"], inst["updater"], inst["embedding"], self.nf)
+        self.deferred = order == "deferred"
+        E = w.emb_dim if inst["embedding"] == "attention" else w.mem_dim
+        cfg = tig.make_config(w.mem_dim, w.time_dim, w.feat_dim, E, w.num_neighbors, w.num_heads,
+                              max_batch or w.batch_size, "fp32", order)
+        self.ctx = tig.TigContext(cfg, self.g.num_nodes, self.g.src, self.g.dst, self.g.ts, self.g.edge_feat, None)
+        self.ctx.modules_attach(self.W, node_feat=self.nf, **inst)
+        self.torch = torch
+
+    def run(self, batches, warm_at=None, with_neg=True, locked=False):
+        torch, w, g, ctx = self.torch, self.w, self.g, self.ctx
+        attn = self.inst["embedding"] == "attention"
+        if warm_at is None:
+            st = O.OracleState.zeros(g.num_nodes, w.mem_dim)
+            ctx.reset()
+        else:
+            st = O.OracleState(*S.make_warm_state(w, g, warm_at))
+            ctx.state_import(st.mem, st.last_update)
+        before = (st.mem.copy(), st.last_update.copy())
+        applied = None
+        worst = {}
+        for first, count in batches:
+            print(f"[{w.name} {self.inst}] step first_eid={first} count={count}", flush=True)
+            neg = S.make_negatives(w, g, first, count) if with_neg else None
+            if locked:
+                ctx.state_import(st.mem, st.last_update)
+                st.drop_pending()
+                before = (st.mem.copy(), st.last_update.copy())
+                applied = None
+            ref = G.step(st, g.src, g.dst, g.ts, g.edge_feat, self.W, first, count, neg, w.num_neighbors, w.num_heads,
+                         self.mods, index=self.ix, deferred=self.deferred)
+            out = ctx.alloc_outputs(count, with_neg=with_neg, inspect=True)
+            if not attn:
+                out.nbr_cnt.fill_(-7)      # must stay untouched
+            ctx.step(first, count, torch.from_numpy(neg).to("cuda:0") if with_neg else None, out)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(out.is_winner.cpu().numpy(), ref["is_winner"], err_msg="is_winner")
+            if attn:
+                for k in ("nbr_cnt", "nbr_node", "nbr_eid", "nbr_ts"):
+                    np.testing.assert_array_equal(getattr(out, k).cpu().numpy(), ref[k], err_msg=k)
+            else:
+                assert int((out.nbr_cnt != -7).sum()) == 0
+            res = {"emb": gate(out.emb.cpu().numpy(), ref["emb"], TOL, "emb"),
+                   "score_pos": gate(out.score_pos.cpu().numpy(), ref["score_pos"], TOL, "score_pos")}
+            if with_neg:
+                res["score_neg"] = gate(out.score_neg.cpu().numpy(), ref["score_neg"], TOL, "score_neg")
+            mem, lu = ctx.state_export()
+            np.testing.assert_array_equal(lu, st.last_update, err_msg="last_update")
+            res["mem"] = gate(mem, st.mem, TOL, "mem")
+            msg = (first, count) if not self.deferred else applied
+            keep = np.ones(g.num_nodes, dtype=bool)
+            if msg is not None:
+                keep[np.concatenate([g.src[msg[0]:msg[0] + msg[1]], g.dst[msg[0]:msg[0] + msg[1]]])] = False
+            assert np.array_equal(mem[keep], before[0][keep]) and np.array_equal(lu[keep], before[1][keep])
+            before = (mem, lu)
+            applied = (first, count)
+            for k, v in res.items():
+                worst[k] = max(worst.get(k, 0.0), v)
+        print(f"[{w.name} {self.inst}] worst gate ratios: {worst}", flush=True)
+        return worst
+
+    def close(self):
+        self.ctx.close()
+
+
+def window(w, frac, steps, batch=None):
+    B = batch or w.batch_size
+    first = int(w.num_events * frac) // B * B
+    return first, list(S.batches(w.num_events, B, first=first, stop=first + steps * B))
+
+
+@pytest.mark.parametrize("name", list(INSTANCES))
+@pytest.mark.parametrize("node_feat", [False, True])
+def test_c1_from_reset_and_ragged(name, node_feat):
+    """From reset, free running, ragged batch of 136 (tails in every kernel), then a one-event batch
+    and a batch without negatives."""
+    c = Case(S.WORKLOADS["c1_tiny"], INSTANCES[name], node_feat)
+    c.run(list(S.batches(c.w.num_events, 136))[:10])
+    c.run([(3000, 1), (3001, 136)], warm_at=3000)
+    c.run([(5000, 200), (5200, 200)], warm_at=5000, with_neg=False)
+    c.close()
+
+
+@pytest.mark.parametrize("name", ["jodie_like", "mean_gru_attention", "mean_rnn_projection"])
+def test_c1_deferred_order(name):
+    c = Case(S.WORKLOADS["c1_tiny"], INSTANCES[name], True, order="deferred")
+    c.run(list(S.batches(c.w.num_events, 136))[:10])
+    c.run([(3000, 100), (3100, 100), (3300, 50)], warm_at=3000)      # a gap; import drops what is kept
+    c.close()
+
+
+@pytest.mark.parametrize("name", ["mean_gru_attention", "jodie_like"])
+def test_c1_step_locked_whole_stream_tail(name):
+    c = Case(S.WORKLOADS["c1_tiny"], INSTANCES[name], False)
+    c.run(list(S.batches(c.w.num_events, 200))[-3:] + [(9990, 10)], warm_at=9400, locked=True)
+    c.close()
+
+
+@pytest.mark.parametrize("name", ["mean_gru_attention", "dyrep_like", "mean_rnn_projection"])
+def test_c2_wide_rows_window(name):
+    w = S.WORKLOADS["c2_bipartite_medium"]
+    c = Case(w, INSTANCES[name], name != "dyrep_like")
+    first, bs = window(w, 0.5, 3)
+    c.run(bs, warm_at=first)
+    c.close()
+
+
+@pytest.mark.parametrize("name", ["mean_gru_attention", "jodie_like"])
+def test_c3_batch_2000_and_above_the_selection_limit(name):
+    """K = 20, 2000 events per batch (a hub node collects hundreds of messages for the mean), then a
+    5000-event batch (selection in its own launches)."""
+    w = S.WORKLOADS["c3_bipartite_dense"]
+    c = Case(w, INSTANCES[name], False, max_batch=5000)
+    first, bs = window(w, 0.5, 2, 2000)
+    c.run(bs, warm_at=first)
+    c.run([(first, 5000)], warm_at=first)
+    c.close()
+
+
+def test_headline_selection_matches_the_fused_step():
+    """The module path with (last, GRU, attention, no node features) and the fused kernels of the
+    headline instance compute the same step: both within the gate of the same oracle."""
+    import torch
+    from paper_2308_14129_amd import tig
+    w = S.WORKLOADS["c1_tiny"]
+    c = Case(w, INSTANCES["headline"], False)
+    cfg = tig.make_config(w.mem_dim, w.time_dim, w.feat_dim, w.emb_dim, w.num_neighbors, w.num_heads, w.batch_size)
+    fused = tig.TigContext(cfg, c.g.num_nodes, c.g.src, c.g.dst, c.g.ts, c.g.edge_feat, c.W)
+    warm = S.make_warm_state(w, c.g, 4000)
+    neg = torch.from_numpy(S.make_negatives(w, c.g, 4000, 200)).to("cuda:0")
+    outs = []
+    for ctx in (c.ctx, fused):
+        ctx.state_import(*warm)
+        o = ctx.alloc_outputs(200)
+        ctx.step(4000, 200, neg, o)
+        torch.cuda.synchronize()
+        outs.append(o)
+    gate(outs[0].emb.cpu().numpy(), outs[1].emb.cpu().numpy(), 2e-4, "emb (module path vs fused path)")
+    gate(outs[0].score_pos.cpu().numpy(), outs[1].score_pos.cpu().numpy(), 2e-4, "score_pos")
+    fused.close()
+    c.close()
+
+
+def test_context_without_weights_refuses_steps_and_static_and_training():
+    import ctypes
+    import torch
+    from paper_2308_14129_amd import tig
+    w = S.WORKLOADS["c1_tiny"]
+    g = S.make_graph(w)
+    cfg = tig.make_config(w.mem_dim, w.time_dim, w.feat_dim, w.mem_dim, w.num_neighbors, w.num_heads, 200)
+    ctx = tig.TigContext(cfg, g.num_nodes, g.src, g.dst, g.ts, g.edge_feat, None)
+    out = ctx.alloc_outputs(200)
+    neg = torch.from_numpy(S.make_negatives(w, g, 0, 200)).to("cuda:0")
+    with pytest.raises(tig.TigError) as ei:
+        ctx.step(0, 200, neg, out)
+    assert ei.value.status == tig.TIG_EINVAL
+    W = S.make_module_weights(w, "rnn", "identity")
+    ctx.modules_attach(W, updater="rnn", embedding="identity")
+    ctx.step(0, 200, neg, out)
+    with pytest.raises(tig.TigError) as ei:
+        ctx.step(200, 200, neg, out, static=True)
+    assert ei.value.status == tig.TIG_EINVAL
+    torch.cuda.synchronize()
+    # emb_dim != mem_dim with a non-attention embedding is refused
+    cfg2 = tig.make_config(w.mem_dim, w.time_dim, w.feat_dim, w.mem_dim + 4, w.num_neighbors, w.num_heads, 200)
+    m = tig.tig_modules(ctypes.sizeof(tig.tig_modules), 0, 1, 1, None, None)
+    n = ctypes.c_size_t(0)
+    assert ctx.lib.tig_modules_workspace_bytes(ctypes.byref(cfg2), ctypes.byref(m), g.num_nodes, ctypes.byref(n)) == tig.TIG_EINVAL
+    ctx.close()
