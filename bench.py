@@ -233,6 +233,93 @@ def bench_train(S, tig, torch, w, g, weights, B, batches, negs, negs_np, mem0, l
     return rep_
 
 
+MODULE_INSTANCES = {
+    "jodie_like": dict(aggregator="last", updater="rnn", embedding="time_projection"),
+    "dyrep_like": dict(aggregator="last", updater="rnn", embedding="identity"),
+    "mean_gru_identity": dict(aggregator="mean", updater="gru", embedding="identity"),
+    "mean_gru_attention": dict(aggregator="mean", updater="gru", embedding="attention"),
+}
+
+
+def bench_modules(S, tig, torch, w, g, B, batches, negs, negs_np, mem0, lu0, warm, names, steps=50, cpu_steps=1):
+    """Other instances of the general architecture (Sec. II-C: mean aggregator, RNN update, identity /
+    time-projection embedding) on the timed window, update-first order, fp32: events/s of plain
+    tig_step calls, the stage durations from tig_step_profiled, the step's algorithmic bytes against
+    the HBM peak, and the instance's oracle on `cpu_steps` steps."""
+    import numpy as np
+    M, T, F, K_ = w.mem_dim, w.time_dim, w.feat_dim, w.num_neighbors
+    report = {}
+    for name in names:
+        inst = MODULE_INSTANCES[name]
+        attn = inst["embedding"] == "attention"
+        E = w.emb_dim if attn else M
+        Wm = S.make_module_weights(w, inst["updater"], inst["embedding"])
+        cfg = tig.make_config(M, T, F, E, K_, w.num_heads, B, "fp32", "update_first")
+        ctx = tig.TigContext(cfg, g.num_nodes, g.src, g.dst, g.ts, g.edge_feat, None, device="cuda:0")
+        ctx.modules_attach(Wm, **inst)
+        ctx.state_import(mem0, lu0)
+        out = ctx.alloc_outputs(B)
+        n_warm = min(5, warm)
+        n = min(steps, len(batches) - n_warm)
+        for i in range(n_warm):
+            ctx.step(batches[i][0], batches[i][1], negs[i], out)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n_warm, n_warm + n):
+            ctx.step(batches[i][0], batches[i][1], negs[i], out)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        # stage durations and the byte accounting's counts on a few of the same steps
+        ctx.state_import(mem0, lu0)
+        insp = ctx.alloc_outputs(B, with_neg=True, inspect=True)
+        sums = np.zeros(len(ctx.KERNEL_NAMES))
+        n_prof = min(10, n)
+        alg = 0.0
+        for i in range(n_prof):
+            ms = ctx.step_profiled(batches[i][0], batches[i][1], negs[i], insp)
+            sums += np.array(ms)
+            f, c = batches[i]
+            nodes = np.concatenate([g.src[f:f + c], g.dst[f:f + c]])
+            n_nodes = int(np.unique(nodes).size)
+            msgs = 2 * c if inst["aggregator"] == "mean" else n_nodes
+            # applied nodes: own row + last_update in, new row + last_update out; per message partner row + feature row
+            by = n_nodes * (8 * M + 16) + msgs * (4 * (M + F) + 16)
+            if attn:
+                rows_u, slots_u = distinct_queries(g, f, c, insp.nbr_cnt.cpu().numpy())
+                by += rows_u * (4 * M + 24) + slots_u * (4 * (M + F) + 16) + 3 * c * 4 * E
+            else:
+                by += 3 * c * (4 * M + 8) + 3 * c * 4 * E      # state rows in, embeddings out
+            by += 8 * c
+            alg += by
+        avg_ms = sums / n_prof
+        ctx.close()
+        del ctx, out, insp
+        torch.cuda.empty_cache()
+        r = {"modules": inst, "steps": n, "ms_per_step": round(dt * 1e3 / n, 4), "events_per_s": round(n * B / dt, 1),
+             "dtype": "f32", "stage_us": {"selection_and_queries": round(float(avg_ms[:3].sum()) * 1e3, 1),
+                                           "update_and_overwrite": round(float(avg_ms[3]) * 1e3, 1),
+                                           "embedding_and_decoder": round(float(avg_ms[4]) * 1e3, 1)},
+             "alg_bytes_per_step": int(alg / n_prof),
+             "hbm_frac": round(alg / n_prof / (dt / n) / 1e9 / HBM_PEAK_GBS, 5)}
+        if cpu_steps > 0:
+            from threadpoolctl import threadpool_limits
+            from oracle import modules_oracle as G
+            from oracle import tig_oracle as O
+            ix = O.NeighbourIndex(g.num_nodes, g.src, g.dst, g.ts)
+            st = O.OracleState(mem0.copy(), lu0.copy())
+            mods = G.Modules(inst["aggregator"], inst["updater"], inst["embedding"], None)
+            with threadpool_limits(limits=1):
+                t0 = time.perf_counter()
+                for i in range(cpu_steps):
+                    G.step(st, g.src, g.dst, g.ts, g.edge_feat, Wm, batches[i][0], batches[i][1], negs_np[i], K_,
+                           w.num_heads, mods, index=ix)
+                cs = time.perf_counter() - t0
+            r["oracle_events_per_s"] = round(cpu_steps * B / cs, 1)
+            r["oracle_sample"] = f"{cpu_steps} step(s) of {B} events, one core, {cs:.1f} s"
+        report[name] = r
+    return report
+
+
 def bench_sep(g, w, torch, num_parts=8, top_k=0.01, beta=1e-6):
     """The partitioner over the whole stream: centrality kernel (HBM-bound: 16 bytes per event in,
     8 bytes per node out), hub selection, and the sequential edge loop on the host; beside them the
@@ -317,6 +404,9 @@ def main():
     ap.add_argument("--train", action="store_true",
                     help="also time training steps (forward, BCE loss, backward, SGD; fp32, deferred message "
                          "order) on the same window and report them in a \"train\" object")
+    ap.add_argument("--modules", default=None,
+                    help="also time other instances of the general architecture (comma-separated names of "
+                         "MODULE_INSTANCES, or 'all') on the same window and report them in a \"modules\" object")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1",
@@ -501,11 +591,24 @@ def main():
                                    cpu_steps=0 if args.no_cpu_baseline else 1)
         ctx = None
 
+    modules_report = None
+    if args.modules:
+        names_m = list(MODULE_INSTANCES) if args.modules == "all" else args.modules.split(",")
+        if ctx is not None:
+            info_kept = ctx.launch_info()
+            ctx.close()
+            ctx = None
+            torch.cuda.empty_cache()
+        modules_report = bench_modules(S, tig, torch, w, g, B, batches, negs, negs_np, mem0, lu0, W_, names_m,
+                                       cpu_steps=0 if args.no_cpu_baseline else 1)
+
     sep_report = None
     if args.sep:
         sep_report = bench_sep(g, w, torch)
 
     info = ctx.launch_info() if ctx is not None else {"kernels_per_step": 2}
+    if ctx is None and args.modules and not args.train:
+        info = info_kept
     line = {
         "metric": "events/sec per TGN batch step (1 MI355X)",
         "value": round(value, 1),
@@ -536,6 +639,8 @@ def main():
         line["sep"] = sep_report
     if train_report is not None:
         line["train"] = train_report
+    if modules_report is not None:
+        line["modules"] = modules_report
     if ctx is not None:
         ctx.close()
     print(json.dumps(line), flush=True)

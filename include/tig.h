@@ -319,7 +319,8 @@ TIG_API int tig_modules_workspace_bytes(const tig_config *cfg, const tig_modules
 
 /* Makes the context compute the selected instance with `weights` (host or device; shapes as above).
  * `workspace`: device, 256-byte aligned, owned by the caller until tig_destroy.  Anything prepared
- * ahead by earlier steps is dropped; the state (memory, last_update, cursor) is kept.  Afterwards
+ * ahead by earlier steps, and the winners a deferred step kept for the next one, are dropped; the
+ * state (memory, last_update, cursor) is kept.  Afterwards
  * tig_step_static and the tig_train_* calls refuse the context (TIG_EINVAL), and a context with a
  * training workspace cannot take a module selection.  Synchronous. */
 TIG_API int tig_modules_attach(tig_ctx *ctx, const tig_modules *modules, const tig_weights *weights,

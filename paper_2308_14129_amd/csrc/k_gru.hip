@@ -387,14 +387,14 @@ hipError_t prepare_gru(const Dims &d, const LaunchPlan &plan)
 // Ahead of the embedding launch: the GRU of the batch this step applies and, if asked for, the
 // finishing pass of this step's queries.
 hipError_t launch_gru(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
-                      hipStream_t s)
+                      hipStream_t s, bool gru_work)
 {
     StepArgs aa = a;
     PackedWeights ww = pw;
     GruParams g = gru_params(d);
-    GruJob gj = {a.msg_first_eid, a.msg_count, a.win, a.n_win};
+    GruJob gj = {a.msg_first_eid, gru_work ? a.msg_count : 0, a.win, a.n_win};
     DecodeParams dp = no_closing(d);
-    size_gru(d, plan, a.msg_count, a.wins_est, &g);
+    size_gru(d, plan, gj.count, a.wins_est, &g);
     if (a.finish_here) {
         const int cus = plan.num_cus > 0 ? plan.num_cus : 256;
         const int rows = 2 * a.count;  // at most; a wavefront takes several rows if there are many

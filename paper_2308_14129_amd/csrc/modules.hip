@@ -48,7 +48,8 @@ __device__ inline void matvec_t(const float *WT, int in, int out, const float *x
 {
     for (int j = threadIdx.x; j < out; j += kModThreads) {
         float acc = bias ? bias[j] : 0.0f;
-        for (int i = 0; i < in; ++i)
+#pragma unroll 8
+        for (int i = 0; i < in; ++i)  // (unrolled: eight independent loads in flight, not one per step)
             acc += WT[(size_t)i * out + j] * x[i];
         y[j] = acc;
     }
@@ -65,6 +66,7 @@ __device__ inline void multivec_t(const float *WT, int in, int out, const float 
 #pragma unroll
             for (int u = 0; u < kKC; ++u)
                 acc[u] = b;
+#pragma unroll 4
             for (int i = 0; i < in; ++i) {
                 const float w = WT[(size_t)i * out + j];
 #pragma unroll
@@ -92,20 +94,56 @@ __device__ inline float repr_elem(const StepArgs &a, const ModParams &p, int M, 
 }
 
 // ------------------------------------------------------------------------------------------
-// Aggregation + state update of one node of the applied batch (the batch's winner list names each
-// node once, with its last event).
+// Mean aggregator, first half: one wavefront per (event, role) entry of the applied batch adds the
+// columns of its message that differ between a node's messages -- [s'_other | Phi(dt) | e] -- to the
+// accumulation row of the entry that won the node's last message (named by the node's key), in
+// double with device atomics (a hub node collects thousands of messages per batch; the rows of its
+// partners arrive from all over the device).  The rows are all zero between steps: k_mod_update
+// clears what it has read.
+__global__ void __launch_bounds__(kModThreads) k_mod_msgsum(StepArgs a, ModDims d, ModParams p)
+{
+    const int M = d.M, T = d.T, F = d.F, rest = M + T + F;
+    const int i = (int)blockIdx.x * kModWaves + wave_id();
+    if (i >= 2 * a.msg_count)
+        return;
+    const int lane = lane_id();
+    const int64_t e = a.msg_first_eid + (i >> 1);
+    const int32_t u = (i & 1) ? a.dst[e] : a.src[e];
+    const int32_t o = (i & 1) ? a.src[e] : a.dst[e];
+    if (u < 0 || (int64_t)u >= a.num_nodes)
+        return;
+    const int32_t ref = ref_of_key(ref_ctx(a), u, a.msg_key[u]);
+    if (ref >= 0 || ref == kRefNone)
+        return;  // (not reachable: every node of the applied batch has a winning entry in it)
+    const int row = ~ref;
+    const bool ok = o >= 0 && (int64_t)o < a.num_nodes;
+    const double dt = a.ts[e] - a.lu[u];
+    double *acc = p.acc + ((size_t)row * kAccCopies + ((i >> 1) & (kAccCopies - 1))) * rest;
+    for (int j = lane; j < rest; j += kWave) {
+        float v;
+        if (j < M)
+            v = ok ? a.mem[(size_t)o * M + j] : 0.0f;
+        else if (j < M + T)
+            v = time_enc(p.time_w_rev[j - M], p.time_b_rev[j - M], dt);
+        else
+            v = a.edge_feat[(size_t)e * F + (j - M - T)];
+        unsafeAtomicAdd(&acc[j], (double)v);
+    }
+    if (lane == 0)
+        atomicAdd(&p.acc_cnt[row], 1);
+}
+
+// Aggregated message + state update of one node of the applied batch (the batch's winner list names
+// each node once, with its last event).
 __global__ void __launch_bounds__(kModThreads) k_mod_update(StepArgs a, ModDims d, ModParams p)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int M = d.M, T = d.T, F = d.F, D = d.Dmsg, GM = d.G * d.M;
     const int rest = M + T + F;                 // message columns that differ between a node's messages
-    double *acc = (double *)smem;               // [rest]
-    float *msg = (float *)(acc + rest);         // [D]
+    float *msg = (float *)smem;                 // [D]
     float *h = msg + D;                         // [M]
     float *gi = h + M;                          // [GM]
     float *gh = gi + GM;                        // [GM]
-    int *list = (int *)(gh + GM);               // [kModThreads] entries of this node in a chunk
-    int *s_cnt = list + kModThreads;            // [waves + 2]
 
     int n_win = *a.n_win;
     n_win = n_win < 2 * a.msg_count ? n_win : 2 * a.msg_count;
@@ -116,14 +154,13 @@ __global__ void __launch_bounds__(kModThreads) k_mod_update(StepArgs a, ModDims 
     if (w.node < 0 || (int64_t)w.node >= a.num_nodes || w.other < 0 || (int64_t)w.other >= a.num_nodes ||
         w.entry < 0 || w.entry >= 2 * a.msg_count)
         return;  // (not a descriptor of this batch)
-    const int lane = lane_id(), wave = wave_id();
-    const double lu0 = a.lu[w.node];
     for (int j = threadIdx.x; j < M; j += kModThreads) {
         const float v = a.mem[(size_t)w.node * M + j];
         h[j] = v;
         msg[j] = v;
     }
     if (d.agg == TIG_AGG_LAST) {
+        const double lu0 = a.lu[w.node];
         const int64_t eid = a.msg_first_eid + (w.entry >> 1);
         for (int j = threadIdx.x; j < rest; j += kModThreads) {
             float v;
@@ -136,55 +173,21 @@ __global__ void __launch_bounds__(kModThreads) k_mod_update(StepArgs a, ModDims 
             msg[M + j] = v;
         }
     } else {
-        // mean of all the node's messages of the batch: its entries are collected chunk by chunk in
-        // entry order (so the sum has one fixed order) and added column-parallel in double
-        for (int j = threadIdx.x; j < rest; j += kModThreads)
-            acc[j] = 0.0;
-        int total = 0;
-        const int entries = 2 * a.msg_count;
-        for (int base = 0; base < entries; base += kModThreads) {
-            const int i = base + (int)threadIdx.x;
-            bool mine = false;
-            if (i < entries) {
-                const int64_t e = a.msg_first_eid + (i >> 1);
-                mine = ((i & 1) ? a.dst[e] : a.src[e]) == w.node;
+        double *acc = p.acc + (size_t)w.entry * kAccCopies * rest;
+        const int n = p.acc_cnt[w.entry];
+        const double inv = 1.0 / (double)(n > 0 ? n : 1);
+        for (int j = threadIdx.x; j < rest; j += kModThreads) {
+            double sum = 0.0;
+#pragma unroll
+            for (int c = 0; c < kAccCopies; ++c) {  // (fixed order: the result does not depend on the adds' order beyond fp64 rounding)
+                sum += acc[(size_t)c * rest + j];
+                acc[(size_t)c * rest + j] = 0.0;
             }
-            const unsigned long long m = __ballot(mine);
-            if (lane == 0)
-                s_cnt[wave] = __popcll(m);
-            __syncthreads();
-            int before = 0, n = 0;
-            for (int x = 0; x < kModWaves; ++x) {
-                if (x < wave)
-                    before += s_cnt[x];
-                n += s_cnt[x];
-            }
-            if (mine)
-                list[before + __popcll(m & ((1ull << lane) - 1ull))] = i;
-            __syncthreads();
-            for (int l = 0; l < n; ++l) {
-                const int i2 = list[l];
-                const int64_t e = a.msg_first_eid + (i2 >> 1);
-                int32_t o = (i2 & 1) ? a.src[e] : a.dst[e];
-                const double dt = a.ts[e] - lu0;
-                const bool ok = o >= 0 && (int64_t)o < a.num_nodes;
-                for (int j = threadIdx.x; j < rest; j += kModThreads) {
-                    float v;
-                    if (j < M)
-                        v = ok ? a.mem[(size_t)o * M + j] : 0.0f;
-                    else if (j < M + T)
-                        v = time_enc(p.time_w_rev[j - M], p.time_b_rev[j - M], dt);
-                    else
-                        v = a.edge_feat[(size_t)e * F + (j - M - T)];
-                    acc[j] += (double)v;
-                }
-            }
-            total += n;
-            __syncthreads();
+            msg[M + j] = (float)(sum * inv);
         }
-        const double inv = 1.0 / (double)(total > 0 ? total : 1);
-        for (int j = threadIdx.x; j < rest; j += kModThreads)
-            msg[M + j] = (float)(acc[j] * inv);
+        __syncthreads();  // (every thread has read the count)
+        if (threadIdx.x == 0)
+            p.acc_cnt[w.entry] = 0;
     }
     __syncthreads();
     matvec_t(p.T_i, D, GM, msg, p.b_i, gi);
@@ -393,20 +396,23 @@ __global__ void __launch_bounds__(kModThreads) k_mod_decode(StepArgs a, ModDims 
 #pragma unroll
     for (int ev = 0; ev < kEV; ++ev)
         sp[ev] = sn[ev] = 0.0f;
+    // (no condition inside the loops: events beyond the batch repeat event 0, a step without negatives
+    // reads the destination row twice; both results are dropped below)
+    const int noff = roles == 3 ? 2 * E : E;
     for (int j = threadIdx.x; j < E; j += kModThreads) {
         float ya[kEV], yb[kEV], yn[kEV];
 #pragma unroll
         for (int ev = 0; ev < kEV; ++ev)
             ya[ev] = yb[ev] = yn[ev] = 0.0f;
-        for (int i = 0; i < E; ++i) {
+#pragma unroll 4
+        for (int i = 0; i < E; ++i) {  // (unrolled: the weight loads of four steps are in flight together)
             const float wa = p.T_d1[(size_t)i * E + j], wb = p.T_d1[(size_t)(E + i) * E + j];
 #pragma unroll
             for (int ev = 0; ev < kEV; ++ev) {
-                const float *row = em + (size_t)(ev < nev ? ev : 0) * 3 * E;
-                ya[ev] += wa * row[i];
-                yb[ev] += wb * row[E + i];
-                if (roles == 3)
-                    yn[ev] += wb * row[2 * E + i];
+                const float *row = em + (ev < nev ? ev : 0) * 3 * E;
+                ya[ev] = fmaf(wa, row[i], ya[ev]);
+                yb[ev] = fmaf(wb, row[E + i], yb[ev]);
+                yn[ev] = fmaf(wb, row[noff + i], yn[ev]);
             }
         }
         const float b1 = p.b_d1[j], w2 = p.w_d2[j];
@@ -455,11 +461,7 @@ __global__ void k_mod_revolutions(double *out, const float *in, int n)
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
-int update_lds(const ModDims &d)
-{
-    const int rest = d.M + d.T + d.F;
-    return rest * 8 + (d.Dmsg + d.M + 2 * d.G * d.M) * 4 + (kModThreads + kModWaves + 2) * 4;
-}
+int update_lds(const ModDims &d) { return (d.Dmsg + d.M + 2 * d.G * d.M) * 4; }
 
 int rows_lds(const ModDims &d)
 {
@@ -532,9 +534,14 @@ static size_t mod_layout(const Dims &d, int agg, int upd, int emb, bool node_fea
     biggest = 2 * E * E > biggest ? 2 * E * E : biggest;
     if (emb == TIG_EMB_TIME_PROJECTION)
         q.time_proj_w = (const float *)take(M, 4);
+    if (agg == TIG_AGG_MEAN) {
+        q.acc = (double *)take((size_t)2 * d.max_batch * kAccCopies * (M + T + d.F), 8);
+        q.acc_cnt = (int32_t *)take((size_t)2 * d.max_batch, 4);
+    }
     float *stage = (float *)take(biggest > T ? biggest : T, 4);
     float *nf = node_feat ? (float *)take((size_t)num_nodes * M, 4) : nullptr;
     q.node_feat = nf;
+    q.fused_embed = attn && !node_feat;
     if (p)
         *p = q;
     if (raw_stage)
@@ -622,6 +629,10 @@ hipError_t modules_attach(const Dims &d, const tig_modules &m, const tig_weights
         MOD_TRY(vec(p.time_proj_w, m.time_proj_w, M));
     if (nf)
         MOD_TRY(hipMemcpyAsync(nf, m.node_feat, 4 * (size_t)num_nodes * M, hipMemcpyDefault, s));
+    if (p.acc) {
+        MOD_TRY(launch_fill_zero(p.acc, (size_t)2 * d.max_batch * kAccCopies * (M + T + d.F) * 8, s));
+        MOD_TRY(launch_fill_zero(p.acc_cnt, (size_t)2 * d.max_batch * 4, s));
+    }
     MOD_TRY(hipFuncSetAttribute((const void *)k_mod_update, hipFuncAttributeMaxDynamicSharedMemorySize, update_lds(md)));
     MOD_TRY(hipFuncSetAttribute((const void *)k_mod_rows, hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds(md)));
     MOD_TRY(hipFuncSetAttribute((const void *)k_mod_decode, hipFuncAttributeMaxDynamicSharedMemorySize, decode_lds(md)));
@@ -639,7 +650,25 @@ hipError_t launch_modules(const Dims &d, const LaunchPlan &plan, const PackedWei
     const ModDims md = mod_dims(d, p);
     hipError_t e;
     if (a.msg_count > 0) {
+        if (p.agg == TIG_AGG_MEAN)
+            hipLaunchKernelGGL(k_mod_msgsum, dim3((2 * a.msg_count + kModWaves - 1) / kModWaves), dim3(kModThreads), 0, s, a, md, p);
         hipLaunchKernelGGL(k_mod_update, dim3(2 * a.msg_count), dim3(kModThreads), update_lds(md), s, a, md, p);
+        if ((e = hipGetLastError()) != hipSuccess)
+            return e;
+    }
+    if (p.fused_embed) {
+        // attention without node features: the fused kernels of the headline instance embed and decode,
+        // reading updated nodes' rows from the staged rows (the memory overwrite runs beside them)
+        if (marks && (e = hipEventRecord(marks[0], s)) != hipSuccess)
+            return e;
+        StepArgs f = a;
+        f.finish_here = 1;
+        if ((e = launch_gru(d, plan, pw, f, s, false)) != hipSuccess || (e = launch_embed(d, plan, pw, f, s)) != hipSuccess ||
+            (e = launch_closing(d, plan, pw, f, GruAhead{}, s)) != hipSuccess)
+            return e;
+        return marks ? hipEventRecord(marks[1], s) : hipSuccess;
+    }
+    if (a.msg_count > 0) {
         hipLaunchKernelGGL(k_mod_commit, dim3(64), dim3(kModThreads), 0, s, a, d.M);
         if ((e = hipGetLastError()) != hipSuccess)
             return e;

@@ -260,7 +260,7 @@ size_t pack_scratch_bytes(const Dims &d) { return scratch_layout(d, nullptr).byt
 size_t packed_weights_bytes(const Dims &d) { return layout(d, nullptr).bytes; }
 
 hipError_t pack_weights(const Dims &d, const tig_weights &w, void *dst, void *scratch,
-                        PackedWeights *pw, hipStream_t s)
+                        PackedWeights *pw, hipStream_t s, bool with_gru)
 {
     const PackedLayout L = layout(d, dst);
     const ScratchLayout S = scratch_layout(d, scratch);
@@ -277,6 +277,7 @@ hipError_t pack_weights(const Dims &d, const tig_weights &w, void *dst, void *sc
     hipLaunchKernelGGL(k_to_revolutions, grid(T), blk, 0, s, L.time_b_rev, w.time_b, T);
 
     // ---- GRU: gates r, z with the hidden weights folded onto the s_self columns ------------
+    if (with_gru) {
     const float *W_ir = w.W_i, *W_iz = w.W_i + (size_t)M * Dmsg, *W_in = w.W_i + (size_t)2 * M * Dmsg;
     const float *W_hr = w.W_h, *W_hz = w.W_h + (size_t)M * M, *W_hn = w.W_h + (size_t)2 * M * M;
     hipLaunchKernelGGL(k_add_cols, grid((size_t)M * Dmsg), blk, 0, s, S.Wr, Dmsg, W_ir, Dmsg, W_hr, M, M,
@@ -297,6 +298,7 @@ hipError_t pack_weights(const Dims &d, const tig_weights &w, void *dst, void *sc
     hipLaunchKernelGGL(k_vec_f32, grid(d.Ng), blk, 0, s, L.gru_bhn, d.Ng, M, (const double *)nullptr,
                        w.b_h + 2 * M, (const float *)nullptr);
     TIG_TRY(hipGetLastError());
+    }
 
     // ---- attention query fold ---------------------------------------------------------------
     // cQ = W_Q[:, M:] Phi(0) + b_Q

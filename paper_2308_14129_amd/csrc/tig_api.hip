@@ -62,6 +62,7 @@ struct tig_ctx {
     unsigned long long *key[2];  // one key array per winner list
     void *packed;
     StepScratch S;     // in the scratch workspace
+    void *scratch;     // the scratch workspace itself
     int wcur;          // update-first: winner list the last step applied; deferred: list with the pending winners
     int qcur;          // query set the last step used
     bool ahead_w_valid;  // update-first: list wcur ^ 1 holds the winners of batch (ahead_w_first, ahead_w_count)
@@ -466,6 +467,7 @@ int tig_init(const tig_config *cfg, const tig_graph *graph, const tig_weights *w
 
     // per-step intermediates: counters and the claim table start from zero
     ctx->S = step_scratch(d, scratch);
+    ctx->scratch = scratch;
     for (int i = 0; i < 2; ++i) {
         INIT_TRY(launch_fill_zero(ctx->S.n_win[i], 4, s), "clear counters");
         INIT_TRY(launch_fill_zero(ctx->S.qs[i].n_u, 4, s), "clear counters");
@@ -662,7 +664,7 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     sp.gru_now = !general && !g_ready && (a.msg_count > 0 || a.finish_here);
     if (general) {
         sp.mods = &ctx->mods;
-        launches += wants_queries ? 3 : 2;  // update, overwrite, [finishing pass,] embedding, decoder[, inspection]
+        launches += ctx->mods.fused_embed ? 2 : (wants_queries ? 4 : 2);  // update[, overwrite][, finishing pass], embedding, decoder / closing
     }
     if (sp.big_sel)
         launches += 2;
@@ -899,6 +901,34 @@ int tig_modules_attach(tig_ctx *ctx, const tig_modules *modules, const tig_weigh
     ModParams mp;
     if (e == hipSuccess)
         e = modules_attach(ctx->d, *modules, w, ctx->num_nodes, workspace, &mp, ctx->stream);
+    if (e == hipSuccess && mp.fused_embed) {
+        // the fused embedding / closing kernels run this selection's attention: their prepared weights
+        // are folded from `weights` as in tig_init (staged through the scratch workspace, whose
+        // per-step counters and claim table are then put back to their resting state)
+        hipStream_t s = ctx->stream;
+        char *wbase = (char *)ctx->scratch + 256;
+        RawWeights R = raw_weights_layout(ctx->d, wbase);
+        WeightField wf[32];
+        const int nwf = weight_fields(ctx->d, wf);
+        for (int i = 0; i < nwf && e == hipSuccess; ++i) {
+            if (wf[i].member == &tig_weights::W_i || wf[i].member == &tig_weights::b_i ||
+                wf[i].member == &tig_weights::W_h || wf[i].member == &tig_weights::b_h)
+                continue;  // the state update has kernels of its own
+            e = hipMemcpyAsync((void *)(R.w.*(wf[i].member)), w.*(wf[i].member), sizeof(float) * wf[i].count,
+                               hipMemcpyDefault, s);
+        }
+        if (e == hipSuccess)
+            e = pack_weights(ctx->d, R.w, ctx->packed, wbase + R.bytes, &ctx->pw, s, false);
+        for (int i = 0; i < 2 && e == hipSuccess; ++i) {
+            e = launch_fill_zero(ctx->S.n_win[i], 4, s);
+            if (e == hipSuccess)
+                e = launch_fill_zero(ctx->S.qs[i].n_u, 4, s);
+        }
+        if (e == hipSuccess)
+            e = launch_fill_zero(ctx->S.tab, sizeof(unsigned long long) * (size_t)ctx->S.tab_slots, s);
+        if (e == hipSuccess)
+            e = hipStreamSynchronize(s);
+    }
     if (e != hipSuccess)
         return fail(ctx, TIG_EHIP, "tig_modules_attach", e);
     ctx->mods = mp;
@@ -907,6 +937,7 @@ int tig_modules_attach(tig_ctx *ctx, const tig_modules *modules, const tig_weigh
     ctx->ahead_g_valid = false;
     ctx->ahead_w_valid = false;
     ctx->ahead_q_valid = false;
+    ctx->pend_valid = false;  // (a deferred step's kept winners lived in the scratch workspace)
     return TIG_OK;
 }
 

@@ -191,8 +191,10 @@ hipError_t csr_build(const int32_t *src, const int32_t *dst, const double *ts, i
 size_t pack_scratch_bytes(const Dims &d);
 size_t packed_weights_bytes(const Dims &d);
 // Folds / pads / reorders the weights into `dst` (device, packed_weights_bytes) and fills `pw`.
+// with_gru = false: W_i / W_h are not read and the GRU part stays zero (a context whose state update
+// runs elsewhere).
 hipError_t pack_weights(const Dims &d, const tig_weights &w_dev_f32, void *dst, void *scratch,
-                        PackedWeights *pw, hipStream_t s);
+                        PackedWeights *pw, hipStream_t s, bool with_gru = true);
 
 bool plan_launch(const Dims &d, int lds_limit, LaunchPlan *plan);
 int gru_lds_bytes(const Dims &d);
@@ -216,8 +218,9 @@ struct GruAhead {
 };
 // GRU of the batch a step applies and, in the same launch, what is left of its query preparation
 // (slots, row references), ahead of the embedding launch
+// (gru_work = false: only the finishing pass -- the staged rows come from elsewhere)
 hipError_t launch_gru(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
-                      hipStream_t s);
+                      hipStream_t s, bool gru_work = true);
 // embedding of the distinct queries (the negatives' neighbours are looked up here); memory overwrite;
 // selection and query preparation for the batch expected next
 hipError_t launch_embed(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw, const StepArgs &a,
@@ -280,6 +283,7 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
                         float *loss_out, hipStream_t s);
 // ---- other instances of the general architecture (modules.hip) ----
 // Module selection of a context and its weights: transposed copies ([in x out]) in the attached workspace.
+constexpr int kAccCopies = 8;  // accumulation rows per node of the mean aggregator (entries are dealt out to them: less same-address traffic)
 struct ModParams {
     int agg, upd, emb;                         // tig_aggregator, tig_updater, tig_embedding
     const double *time_w_rev, *time_b_rev;     // [T] time-encoding frequency / phase in revolutions
@@ -289,6 +293,9 @@ struct ModParams {
     const float *T_d1, *b_d1, *w_d2, *b_d2;    // decoder: [2E x E], [E], [E], [1]
     const float *node_feat;                    // [N x M] or NULL
     const float *time_proj_w;                  // [M] or NULL
+    bool fused_embed;                          // attention without node features: the fused embedding / closing launches run it
+    double *acc;                               // mean aggregator: [2 * max_batch x kAccCopies x (M + T + F)] message sums by winning entry, zero between steps
+    int32_t *acc_cnt;                          // ... and the number of messages in each
 };
 size_t modules_workspace_bytes(const Dims &d, const tig_modules &m, int64_t num_nodes);
 bool modules_supported(const Dims &d, const tig_modules &m);
