@@ -21,6 +21,15 @@ float32 only where the method stores a value:
                           last_update the step's memory overwrite left     (E = M)
   node features v [N, M]: wherever the embedding module reads a node's state -- its own or a
        neighbour's -- it reads r_i(t) = s_i(t) + v_i; messages carry the raw memory rows.
+  layers  the embedding sums over the k-hop temporal neighbourhood neighbor_i^k([0, t]) (Sec. II-C,
+       embedding module).  With the attention function, k = 2 is two stacked layers:
+         h0_i(t) = r_i(t)
+         hl_i(t) = merge_l(attention_l([h(l-1)_i(t) | Phi(0)], {[h(l-1)_j(t) | e_ij | Phi(t - t_ij)]}), h(l-1)_i(t))
+       over the K most recent neighbours j of i before t.  Every row of layer l-1 is taken AT THE
+       QUERY TIME t: a neighbour's layer-1 row attends over that neighbour's own K most recent
+       events before t (which include its event with i).  Layer 1 has the weights of the one-layer
+       model; layer 2 has a set of its own, with the layer-1 width E where layer 1 has the state
+       width M: W_Q, W_O [E+T, E+T], W_K, W_V [E+T, E+F+T], W_m1 [E, 2E+T], W_m2 [E, E].
 
 These details are this build's readings (the paper names the options and gives no formulas):
 parity unpinned for the CHOICES.  The implementation of each is pinned in
@@ -28,7 +37,10 @@ tests/test_modules_oracle.py: reduction to tig_oracle.step bit for bit when the 
 headline one; mean == last when no node repeats in a batch; a hand-worked three-message mean seen
 through selector weights; order independence of the mean; the RNN cell against closed forms and the
 float64 library cell; identity / time-projection values written out by hand; zero node features ==
-no node features.
+no node features; two layers: a pass-through second layer returns the first layer's rows, a
+second layer that averages its neighbour rows returns the mean of the one-layer embeddings that
+the pinned one-layer step gives for those neighbours as negatives at the query's time, a chain
+graph whose far end is visible only through the second hop, no future event within either hop.
 """
 from __future__ import annotations
 
@@ -48,6 +60,8 @@ class Modules:
     updater: str = "gru"             # "gru" | "rnn"
     embedding: str = "attention"     # "attention" | "identity" | "time_projection"
     node_feat: np.ndarray = None     # float32 [N, M] or None
+    layers: int = 1                  # attention embedding: 1 or 2 stacked layers
+    layer2: dict = None              # weights of the second layer (W_Q b_Q W_K b_K W_V b_V W_O b_O W_m1 b_m1 W_m2 b_m2)
 
 
 def rnn_cell(m, h, W_i, b_i, W_h, b_h):
@@ -111,6 +125,29 @@ def node_repr(state, mods, u):
     return r.astype(f32)
 
 
+def embed_layer(state, mods, W, edge_feat, H, lookup, l, u, t, table=None):
+    """h^l_u(t) of the attention embedding (float32 [M] for l = 0, [E] above): layer l over the K most
+    recent neighbours of u before t, every input row being the layer l-1 row of its node at the SAME
+    time t.  lookup(nodes, times) -> (nbr_node, nbr_eid, nbr_ts, nbr_cnt); table: the row of that
+    answer for (u, t) if the caller has it already."""
+    if l == 0:
+        return node_repr(state, mods, u)
+    Wl = W if l == 1 else mods.layer2
+    if table is None:
+        nn, ne, nt, nc = lookup(np.array([u], dtype=np.int32), np.array([t], dtype=f64))
+        table = (nn[0], ne[0], nt[0], int(nc[0]))
+    nb_node, nb_eid, nb_ts, c = table
+    h_self = embed_layer(state, mods, W, edge_feat, H, lookup, l - 1, u, t)
+    q_in = np.concatenate([h_self, O.time_encode(0.0, W["time_w"], W["time_b"])])
+    if c > 0:
+        h_nb = np.stack([embed_layer(state, mods, W, edge_feat, H, lookup, l - 1, int(v), t) for v in nb_node[:c]])
+        phi_k = O.time_encode(t - nb_ts[:c], W["time_w"], W["time_b"])
+        kv = np.concatenate([h_nb, edge_feat[nb_eid[:c]], phi_k], axis=1).astype(f32)
+    else:
+        kv = np.zeros((0, h_self.shape[0] + edge_feat.shape[1] + W["time_w"].shape[0]), dtype=f32)
+    return O.merge(O.attention(q_in, kv, Wl, H), h_self, Wl).astype(f32)
+
+
 def step(state, src, dst, ts, edge_feat, W, first_eid, count, neg_dst, K, H, mods, index=None, deferred=False):
     """One chronological batch step of the chosen instance; updates `state` in place.  Same outputs
     and conventions as tig_oracle.step (neighbour tables only for the attention embedding).
@@ -143,25 +180,16 @@ def step(state, src, dst, ts, edge_feat, W, first_eid, count, neg_dst, K, H, mod
 
     if mods.embedding == "attention":
         if index is None:
-            nb_node, nb_eid, nb_ts, nb_cnt = O.neighbours_bruteforce_batch(src, dst, ts, q_node, q_time, K)
+            lookup = lambda nodes, times: O.neighbours_bruteforce_batch(src, dst, ts, nodes, times, K)
         else:
-            nb_node, nb_eid, nb_ts, nb_cnt = index.query(q_node, q_time, K)
+            lookup = lambda nodes, times: index.query(nodes, times, K)
+        nb_node, nb_eid, nb_ts, nb_cnt = lookup(q_node, q_time)
         res.update(nbr_node=nb_node, nbr_eid=nb_eid, nbr_ts=nb_ts, nbr_cnt=nb_cnt)
         E = W["W_m2"].shape[0]
         emb = np.empty((Q, E), dtype=f32)
-        phi0 = O.time_encode(0.0, W["time_w"], W["time_b"])
         for q in range(Q):
-            u = int(q_node[q])
-            c = int(nb_cnt[q])
-            r_u = node_repr(state, mods, u)
-            q_in = np.concatenate([r_u, phi0])
-            if c > 0:
-                r_v = np.stack([node_repr(state, mods, int(v)) for v in nb_node[q, :c]])
-                phi_k = O.time_encode(q_time[q] - nb_ts[q, :c], W["time_w"], W["time_b"])
-                kv = np.concatenate([r_v, edge_feat[nb_eid[q, :c]], phi_k], axis=1).astype(f32)
-            else:
-                kv = np.zeros((0, M + edge_feat.shape[1] + W["time_w"].shape[0]), dtype=f32)
-            emb[q] = O.merge(O.attention(q_in, kv, W, H), r_u, W).astype(f32)
+            table = (nb_node[q], nb_eid[q], nb_ts[q], int(nb_cnt[q]))
+            emb[q] = embed_layer(state, mods, W, edge_feat, H, lookup, mods.layers, int(q_node[q]), float(q_time[q]), table)
     else:
         emb = np.empty((Q, M), dtype=f32)
         for q in range(Q):

@@ -288,6 +288,24 @@ def make_module_weights(w: Workload, updater: str = "gru", embedding: str = "att
     return out
 
 
+def make_layer2_weights(w: Workload) -> dict:
+    """Weights of a second attention layer (inputs of the first layer's width E where the first layer
+    has the state width M): W_Q, W_O [E+T, E+T], W_K, W_V [E+T, E+F+T], W_m1 [E, 2E+T], W_m2 [E, E],
+    biases; Xavier-uniform / U(-0.1, 0.1) from streams of their own."""
+    lib = _load()
+    E, T, F = w.emb_dim, w.time_dim, w.feat_dim
+    da, dkv = E + T, E + F + T
+    shapes = {"W_Q": (da, da), "b_Q": (da,), "W_K": (da, dkv), "b_K": (da,), "W_V": (da, dkv), "b_V": (da,),
+              "W_O": (da, da), "b_O": (da,), "W_m1": (E, da + E), "b_m1": (E,), "W_m2": (E, E), "b_m2": (E,)}
+    out = {}
+    for k, (name, shape) in enumerate(shapes.items()):
+        a = np.empty(shape, dtype=np.float32)
+        lim = math.sqrt(6.0 / (shape[0] + shape[1])) if name.startswith("W_") else 0.1
+        _check(lib.tig_gen_uniform_f32(w.seed, 220 + k, int(np.prod(shape)), -lim, lim, _ptr(a)), name)
+        out[name] = a
+    return out
+
+
 def make_node_feat(w: Workload, num_nodes: int) -> np.ndarray:
     """Static node features [N, M] ~ U(-0.5, 0.5) (the paper's datasets mostly have none: zero vectors)."""
     a = np.empty((num_nodes, w.mem_dim), dtype=np.float32)
