@@ -238,6 +238,7 @@ MODULE_INSTANCES = {
     "dyrep_like": dict(aggregator="last", updater="rnn", embedding="identity"),
     "mean_gru_identity": dict(aggregator="mean", updater="gru", embedding="identity"),
     "mean_gru_attention": dict(aggregator="mean", updater="gru", embedding="attention"),
+    "two_layer_attention": dict(aggregator="last", updater="gru", embedding="attention", layers=2),
 }
 
 
@@ -254,9 +255,10 @@ def bench_modules(S, tig, torch, w, g, B, batches, negs, negs_np, mem0, lu0, war
         attn = inst["embedding"] == "attention"
         E = w.emb_dim if attn else M
         Wm = S.make_module_weights(w, inst["updater"], inst["embedding"])
+        L2 = S.make_layer2_weights(w) if inst.get("layers", 1) == 2 else None
         cfg = tig.make_config(M, T, F, E, K_, w.num_heads, B, "fp32", "update_first")
         ctx = tig.TigContext(cfg, g.num_nodes, g.src, g.dst, g.ts, g.edge_feat, None, device="cuda:0")
-        ctx.modules_attach(Wm, **inst)
+        ctx.modules_attach(Wm, layer2=L2, **inst)
         ctx.state_import(mem0, lu0)
         out = ctx.alloc_outputs(B)
         n_warm = min(5, warm)
@@ -287,6 +289,10 @@ def bench_modules(S, tig, torch, w, g, B, batches, negs, negs_np, mem0, lu0, war
             if attn:
                 rows_u, slots_u = distinct_queries(g, f, c, insp.nbr_cnt.cpu().numpy())
                 by += rows_u * (4 * M + 24) + slots_u * (4 * (M + F) + 16) + 3 * c * 4 * E
+                if L2 is not None:
+                    # second hop, a lower bound (every neighbour with a full table of its own is not assumed):
+                    # per filled slot one more table entry list and the first layer's row written and read back
+                    by += slots_u * (16 * K_ + 8 * E)
             else:
                 by += 3 * c * (4 * M + 8) + 3 * c * 4 * E      # state rows in, embeddings out
             by += 8 * c
@@ -307,7 +313,7 @@ def bench_modules(S, tig, torch, w, g, B, batches, negs, negs_np, mem0, lu0, war
             from oracle import tig_oracle as O
             ix = O.NeighbourIndex(g.num_nodes, g.src, g.dst, g.ts)
             st = O.OracleState(mem0.copy(), lu0.copy())
-            mods = G.Modules(inst["aggregator"], inst["updater"], inst["embedding"], None)
+            mods = G.Modules(inst["aggregator"], inst["updater"], inst["embedding"], None, inst.get("layers", 1), L2)
             with threadpool_limits(limits=1):
                 t0 = time.perf_counter()
                 for i in range(cpu_steps):

@@ -301,6 +301,18 @@ typedef enum tig_aggregator { TIG_AGG_LAST = 0, TIG_AGG_MEAN = 1 } tig_aggregato
 typedef enum tig_updater { TIG_UPD_GRU = 0, TIG_UPD_RNN = 1 } tig_updater;
 typedef enum tig_embedding { TIG_EMB_ATTENTION = 0, TIG_EMB_IDENTITY = 1, TIG_EMB_TIME_PROJECTION = 2 } tig_embedding;
 
+/* Weights of a second attention layer (fp32, row-major [out x in], host or device).  Its input rows
+ * are first-layer embeddings, so it has the width E where the first layer has the state width M:
+ * d_a2 = E + T, d_kv2 = E + F + T (d_a2 divisible by num_heads);
+ *   W_Q, W_O [d_a2 x d_a2], W_K, W_V [d_a2 x d_kv2], biases [d_a2],
+ *   W_m1 [E x (d_a2 + E)], b_m1 [E], W_m2 [E x E], b_m2 [E]. */
+typedef struct tig_layer_weights {
+    uint32_t struct_size;
+    uint32_t reserved;
+    const float *W_Q, *b_Q, *W_K, *b_K, *W_V, *b_V, *W_O, *b_O;
+    const float *W_m1, *b_m1, *W_m2, *b_m2;
+} tig_layer_weights;
+
 typedef struct tig_modules {
     uint32_t struct_size;
     int32_t aggregator;       /* tig_aggregator */
@@ -308,12 +320,24 @@ typedef struct tig_modules {
     int32_t embedding;        /* tig_embedding */
     const float *node_feat;   /* [N x M], host or device, or NULL */
     const float *time_proj_w; /* [M], host or device; required for TIG_EMB_TIME_PROJECTION */
+    /* Attention embedding over the 2-hop temporal neighbourhood (the embedding module of Sec. II-C
+     * sums over neighbor_i^k([0, t])): num_layers = 2 stacks a second layer on the first,
+     *   h1_i(t)  = merge_1(attention_1([r_i(t) | Phi(0)], {[r_j(t) | e_ij | Phi(t - t_ij)]}), r_i(t))
+     *   emb_i(t) = merge_2(attention_2([h1_i(t) | Phi(0)], {[h1_j(t) | e_ij | Phi(t - t_ij)]}), h1_i(t))
+     * over the K most recent neighbours j of i before t; a neighbour's first-layer row is taken at the
+     * QUERY's time t, over that neighbour's own K most recent events before t.  The first layer uses
+     * the attention / merge weights of tig_weights, the second `layer2`.  0 or 1: one layer. */
+    int32_t num_layers;
+    int32_t reserved;
+    const tig_layer_weights *layer2; /* required iff num_layers == 2 (TIG_EMB_ATTENTION only) */
 } tig_modules;
 
 /* Size of the workspace of a module selection (device memory the caller allocates): transposed
  * copies of the weights and, if node features are given, a copy of them.  TIG_EINVAL for a
  * precision other than TIG_FP32, an unknown selector, emb_dim != mem_dim with an embedding that
- * needs it, or rows the kernels cannot hold. */
+ * needs it, two layers without the attention embedding or without `layer2`, or rows the kernels
+ * cannot hold.  Two layers add the second hop's neighbour tables and the first layer's rows:
+ * 3 * max_batch * (K * K * 16 + (K + 1) * 4 * E) bytes. */
 TIG_API int tig_modules_workspace_bytes(const tig_config *cfg, const tig_modules *modules, int64_t num_nodes,
                                         size_t *bytes);
 

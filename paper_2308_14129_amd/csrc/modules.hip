@@ -13,6 +13,10 @@
 //   k_mod_rows     attention embedding in its direct form (separate query / key / value / output
 //                  projections, merge MLP), one workgroup per distinct query, node features added
 //                  wherever a state row is read; a negative's neighbours are looked up here
+//   k_mod_hop2     two stacked attention layers (the embedding module's sum over the 2-hop temporal
+//                  neighbourhood): the K most recent events, before the QUERY's time, of every
+//                  neighbour of every distinct query; k_mod_rows then runs twice: the first layer for
+//                  each (query, neighbour) pair and each query itself, the second layer over those rows
 //   k_mod_decode   eight events per workgroup: both logits (and, for the attention embedding, the
 //                  per-query embedding rows out of the distinct rows)
 // Weight matrices are read through transposed copies ([in x out]) so that a thread that owns an
@@ -37,6 +41,23 @@ struct ModDims {
     int G;  // gate blocks of the state update: 3 (GRU: r, z, n) or 1 (plain recurrent cell)
     int agg, upd, emb;
 };
+
+// What one launch of k_mod_rows computes.
+enum RowsMode {
+    kRowsSingle = 0,  // the one-layer embedding of every distinct query
+    kRowsFirst = 1,   // first of two layers: item (q, j): neighbour j < cnt of query row q at the query's time, j == K: q itself
+    kRowsSecond = 2,  // second of two layers, over the first layer's rows
+};
+
+// The dimensions the second layer sees: its input rows are E wide.
+ModDims second_layer_dims(ModDims d)
+{
+    d.M = d.E;
+    d.da = d.E + d.T;
+    d.dkv = d.E + d.F + d.T;
+    d.dh = d.da / d.H;
+    return d;
+}
 
 ModDims mod_dims(const Dims &d, const ModParams &p)
 {
@@ -235,17 +256,55 @@ __global__ void __launch_bounds__(kModThreads) k_mod_simple(StepArgs a, ModDims 
 }
 
 // ------------------------------------------------------------------------------------------
-// Attention embedding of one distinct query, direct form.
-__global__ void __launch_bounds__(kModThreads) k_mod_rows(StepArgs a, ModDims d, ModParams p)
+// Two layers: the neighbour tables of the second hop.  One workgroup per query row (distinct source /
+// destination queries, then the negatives, whose own table is looked up first): wavefront w takes the
+// neighbours k = w, w + waves, ... and looks up the K most recent events of neighbour k before the
+// QUERY's time into row q * K + k of the second-hop tables.
+__global__ void __launch_bounds__(kModThreads) k_mod_hop2(StepArgs a, ModDims d, ModParams p)
 {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    __shared__ int s_cnt;
     int n_u = *a.qs.n_u;
     n_u = n_u < 2 * a.count ? n_u : 2 * a.count;
     const int n_rows = n_u + (a.roles == 3 ? a.count : 0);
     const int x = (int)blockIdx.x;
     if (x >= n_rows)
         return;
+    const int K = d.K;
+    const int q = x < n_u ? x : 2 * a.count + (x - n_u);
+    if (x >= n_u && threadIdx.x < kWave) {
+        int32_t rf, ee;
+        double ts_k;
+        (void)finish_negative(a, K, x - n_u, rf, ee, ts_k);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int c = a.qs.cnt[q];
+        s_cnt = c < 0 ? 0 : (c > K ? K : c);
+    }
+    __syncthreads();
+    const int cnt = s_cnt;
+    const double t_q = a.qs.t[q];
+    for (int k = wave_id(); k < cnt; k += kModWaves) {
+        int32_t nb, ee;
+        double tt;
+        (void)nbr_lookup_wave(a, K, a.qs.nbr[(size_t)q * K + k], t_q, -1, p.hop2, q * K + k, nb, ee, tt);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// One attention layer + merge MLP of one item, direct form.  d and L are the layer's own dimensions
+// and weights (the second layer's input rows are E wide).
+__global__ void __launch_bounds__(kModThreads) k_mod_rows(StepArgs a, ModDims d, ModParams p, AttnLayer L, int mode)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    int n_u = *a.qs.n_u;
+    n_u = n_u < 2 * a.count ? n_u : 2 * a.count;
+    const int n_rows = n_u + (a.roles == 3 ? a.count : 0);
     const int M = d.M, F = d.F, E = d.E, K = d.K, H = d.H, da = d.da, dh = d.dh, dkv = d.dkv;
+    const int x = mode == kRowsFirst ? (int)blockIdx.x / (K + 1) : (int)blockIdx.x;
+    const int item = mode == kRowsFirst ? (int)blockIdx.x - x * (K + 1) : K;
+    if (x >= n_rows)
+        return;
     double *dts = (double *)smem;     // [K]
     int *nbrs = (int *)(dts + K);     // [K]
     int *eids = nbrs + K;             // [K]
@@ -257,42 +316,59 @@ __global__ void __launch_bounds__(kModThreads) k_mod_rows(StepArgs a, ModDims d,
     float *VPs = KPs + K * da;        // [K x da]
     float *sc = VPs + K * da;         // [H x K]
     float *o = sc + H * K;            // [da]
-    float *xcat = o + da;             // [da + M]: attn | r_u
+    float *xcat = o + da;             // [da + M]: attn | own row
     float *h1 = xcat + da + M;        // [E]
 
     const int q = x < n_u ? x : 2 * a.count + (x - n_u);
-    if (x >= n_u && threadIdx.x < kWave) {  // a negative: the first wavefront looks up its neighbours
+    if (mode == kRowsSingle && x >= n_u && threadIdx.x < kWave) {  // a negative: the first wavefront looks up its neighbours
         int32_t rf, ee;
         double ts_k;
         (void)finish_negative(a, K, x - n_u, rf, ee, ts_k);
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
+    // the item's neighbour table: the query's own, or (first of two layers, item < K) the one of its
+    // neighbour `item` at the query's time
+    const bool hop = mode == kRowsFirst && item < K;
+    if (hop) {
         const int c = a.qs.cnt[q];
+        if (item >= (c < 0 ? 0 : (c > K ? K : c)))
+            return;  // (uniform over the workgroup) an unused slot
+    }
+    const QuerySet &tab = hop ? p.hop2 : a.qs;
+    const int trow = hop ? q * K + item : q;
+    if (threadIdx.x == 0) {
+        const int c = tab.cnt[trow];
         meta[0] = c < 0 ? 0 : (c > K ? K : c);
-        meta[1] = a.qs.node[q];
+        meta[1] = hop ? a.qs.nbr[(size_t)q * K + item] : a.qs.node[q];
     }
     const double t_q = a.qs.t[q];
     if ((int)threadIdx.x < K) {
-        nbrs[threadIdx.x] = a.qs.nbr[(size_t)q * K + threadIdx.x];
-        eids[threadIdx.x] = a.qs.eid[(size_t)q * K + threadIdx.x];
-        dts[threadIdx.x] = t_q - a.qs.ts[(size_t)q * K + threadIdx.x];
+        nbrs[threadIdx.x] = tab.nbr[(size_t)trow * K + threadIdx.x];
+        eids[threadIdx.x] = tab.eid[(size_t)trow * K + threadIdx.x];
+        dts[threadIdx.x] = t_q - tab.ts[(size_t)trow * K + threadIdx.x];
     }
     __syncthreads();
     const int cnt = meta[0];
     const int32_t u = meta[1];
+    const float *rows1 = p.h1 + (size_t)q * (K + 1) * E;  // second layer: the first layer's rows of this query
     for (int j = threadIdx.x; j < da; j += kModThreads) {
-        const float v = j < M ? repr_elem(a, p, M, u, j) : time_enc(p.time_w_rev[j - M], p.time_b_rev[j - M], 0.0);
+        float v;
+        if (j >= M)
+            v = time_enc(p.time_w_rev[j - M], p.time_b_rev[j - M], 0.0);
+        else if (mode == kRowsSecond)
+            v = rows1[(size_t)K * E + j];
+        else
+            v = repr_elem(a, p, M, u, j);
         q_in[j] = v;
         if (j < M)
             xcat[da + j] = v;
     }
-    // key / value rows [r_v | e | Phi(t - t_k)]
+    // key / value rows [row of the neighbour | e | Phi(t - t_k)]
     for (int idx = threadIdx.x; idx < cnt * dkv; idx += kModThreads) {
         const int k = idx / dkv, i = idx - k * dkv;
         float v;
         if (i < M)
-            v = repr_elem(a, p, M, nbrs[k], i);
+            v = mode == kRowsSecond ? rows1[(size_t)k * E + i] : repr_elem(a, p, M, nbrs[k], i);
         else if (i < M + F)
             v = eids[k] >= 0 ? a.edge_feat[(size_t)eids[k] * F + (i - M)] : 0.0f;
         else
@@ -301,9 +377,9 @@ __global__ void __launch_bounds__(kModThreads) k_mod_rows(StepArgs a, ModDims d,
     }
     __syncthreads();
     if (cnt > 0) {
-        matvec_t(p.T_Q, da, da, q_in, p.b_Q, Qv);
-        multivec_t(p.T_K, dkv, da, kv, dkv, cnt, p.b_K, KPs);
-        multivec_t(p.T_V, dkv, da, kv, dkv, cnt, p.b_V, VPs);
+        matvec_t(L.T_Q, da, da, q_in, L.b_Q, Qv);
+        multivec_t(L.T_K, dkv, da, kv, dkv, cnt, L.b_K, KPs);
+        multivec_t(L.T_V, dkv, da, kv, dkv, cnt, L.b_V, VPs);
         __syncthreads();
         const float scale = 1.0f / sqrtf((float)dh);
         for (int idx = threadIdx.x; idx < H * cnt; idx += kModThreads) {
@@ -336,22 +412,23 @@ __global__ void __launch_bounds__(kModThreads) k_mod_rows(StepArgs a, ModDims d,
             o[j] = acc;
         }
         __syncthreads();
-        matvec_t(p.T_O, da, da, o, p.b_O, xcat);
+        matvec_t(L.T_O, da, da, o, L.b_O, xcat);
     } else {
         for (int j = threadIdx.x; j < da; j += kModThreads)
             xcat[j] = 0.0f;  // an empty neighbourhood gives the zero vector (no bias)
     }
     __syncthreads();
-    matvec_t(p.T_m1, da + M, E, xcat, p.b_m1, h1);
+    matvec_t(L.T_m1, da + M, E, xcat, L.b_m1, h1);
     __syncthreads();
     for (int j = threadIdx.x; j < E; j += kModThreads)
         h1[j] = fmaxf(h1[j], 0.0f);
     __syncthreads();
+    float *out = mode == kRowsFirst ? p.h1 + ((size_t)q * (K + 1) + item) * E : a.emb_u + (size_t)q * E;
     for (int j = threadIdx.x; j < E; j += kModThreads) {
-        float acc = p.b_m2[j];
+        float acc = L.b_m2[j];
         for (int i = 0; i < E; ++i)
-            acc += p.T_m2[(size_t)i * E + j] * h1[i];
-        a.emb_u[(size_t)q * E + j] = acc;
+            acc += L.T_m2[(size_t)i * E + j] * h1[i];
+        out[j] = acc;
     }
 }
 
@@ -469,6 +546,13 @@ int rows_lds(const ModDims &d)
            (2 * d.da + d.K * d.dkv + 2 * d.K * d.da + d.H * d.K + d.da + d.da + d.M + d.E) * 4;
 }
 
+// the larger of the two layers' needs (the second layer's rows are E wide)
+int rows_lds_all(const ModDims &d, int layers)
+{
+    const int a = rows_lds(d), b = layers == 2 ? rows_lds(second_layer_dims(d)) : 0;
+    return a > b ? a : b;
+}
+
 int decode_lds(const ModDims &d) { return (kEV * 3 * d.E + kEV * 2 * kModWaves) * 4; }
 
 // One matrix of the workspace: raw copy (kept for nothing but the transpose) and its transpose.
@@ -488,7 +572,7 @@ struct VecJob {
 
 // Layout of the attached workspace: [vectors | transposed matrices | raw staging of one matrix |
 // node features].  Fills `p` when base != NULL.
-static size_t mod_layout(const Dims &d, int agg, int upd, int emb, bool node_feat, int64_t num_nodes, char *base,
+static size_t mod_layout(const Dims &d, int agg, int upd, int emb, int layers, bool node_feat, int64_t num_nodes, char *base,
                          ModParams *p, float **raw_stage, float **nf_dst)
 {
     size_t off = 0;
@@ -497,12 +581,13 @@ static size_t mod_layout(const Dims &d, int agg, int upd, int emb, bool node_fea
         off += align_up(count * elem);
         return q;
     };
-    const size_t M = d.M, T = d.T, E = d.E, da = d.da, dkv = d.dkv, D = d.Dmsg, G = upd == TIG_UPD_GRU ? 3 : 1;
+    const size_t M = d.M, T = d.T, E = d.E, D = d.Dmsg, G = upd == TIG_UPD_GRU ? 3 : 1;
     const bool attn = emb == TIG_EMB_ATTENTION;
     ModParams q = {};
     q.agg = agg;
     q.upd = upd;
     q.emb = emb;
+    q.layers = layers == 2 ? 2 : 1;
     q.time_w_rev = (const double *)take(T, 8);
     q.time_b_rev = (const double *)take(T, 8);
     q.b_i = (const float *)take(G * M, 4);
@@ -511,21 +596,36 @@ static size_t mod_layout(const Dims &d, int agg, int upd, int emb, bool node_fea
     q.T_h = (const float *)take(M * G * M, 4);
     size_t biggest = D * G * M;
     if (attn) {
-        q.b_Q = (const float *)take(da, 4);
-        q.b_K = (const float *)take(da, 4);
-        q.b_V = (const float *)take(da, 4);
-        q.b_O = (const float *)take(da, 4);
-        q.b_m1 = (const float *)take(E, 4);
-        q.b_m2 = (const float *)take(E, 4);
-        q.T_Q = (const float *)take(da * da, 4);
-        q.T_K = (const float *)take(dkv * da, 4);
-        q.T_V = (const float *)take(dkv * da, 4);
-        q.T_O = (const float *)take(da * da, 4);
-        q.T_m1 = (const float *)take((da + M) * E, 4);
-        q.T_m2 = (const float *)take(E * E, 4);
-        const size_t c[] = {da * da, dkv * da, (da + M) * E, E * E};
-        for (size_t v : c)
-            biggest = v > biggest ? v : biggest;
+        for (int l = 0; l < q.layers; ++l) {
+            // layer l reads rows of width in_w: the state width, then the first layer's width
+            const size_t in_w = l == 0 ? M : E, a_w = in_w + T, kv_w = in_w + d.F + T;
+            AttnLayer &A = q.L[l];
+            A.b_Q = (const float *)take(a_w, 4);
+            A.b_K = (const float *)take(a_w, 4);
+            A.b_V = (const float *)take(a_w, 4);
+            A.b_O = (const float *)take(a_w, 4);
+            A.b_m1 = (const float *)take(E, 4);
+            A.b_m2 = (const float *)take(E, 4);
+            A.T_Q = (const float *)take(a_w * a_w, 4);
+            A.T_K = (const float *)take(kv_w * a_w, 4);
+            A.T_V = (const float *)take(kv_w * a_w, 4);
+            A.T_O = (const float *)take(a_w * a_w, 4);
+            A.T_m1 = (const float *)take((a_w + in_w) * E, 4);
+            A.T_m2 = (const float *)take(E * E, 4);
+            const size_t c[] = {a_w * a_w, kv_w * a_w, (a_w + in_w) * E, E * E};
+            for (size_t v : c)
+                biggest = v > biggest ? v : biggest;
+        }
+        if (q.layers == 2) {
+            const size_t R2 = (size_t)3 * d.max_batch * d.K;  // rows of the second-hop tables
+            q.hop2.node = (int32_t *)take(R2, 4);
+            q.hop2.t = (double *)take(R2, 8);
+            q.hop2.cnt = (int32_t *)take(R2, 4);
+            q.hop2.nbr = (int32_t *)take(R2 * d.K, 4);
+            q.hop2.eid = (int32_t *)take(R2 * d.K, 4);
+            q.hop2.ts = (double *)take(R2 * d.K, 8);
+            q.h1 = (float *)take((size_t)3 * d.max_batch * (d.K + 1) * E, 4);
+        }
     }
     q.b_d1 = (const float *)take(E, 4);
     q.w_d2 = (const float *)take(E, 4);
@@ -541,7 +641,7 @@ static size_t mod_layout(const Dims &d, int agg, int upd, int emb, bool node_fea
     float *stage = (float *)take(biggest > T ? biggest : T, 4);
     float *nf = node_feat ? (float *)take((size_t)num_nodes * M, 4) : nullptr;
     q.node_feat = nf;
-    q.fused_embed = attn && !node_feat;
+    q.fused_embed = attn && !node_feat && q.layers == 1;
     if (p)
         *p = q;
     if (raw_stage)
@@ -553,8 +653,8 @@ static size_t mod_layout(const Dims &d, int agg, int upd, int emb, bool node_fea
 
 size_t modules_workspace_bytes(const Dims &d, const tig_modules &m, int64_t num_nodes)
 {
-    return mod_layout(d, m.aggregator, m.updater, m.embedding, m.node_feat != nullptr, num_nodes, nullptr, nullptr,
-                      nullptr, nullptr);
+    return mod_layout(d, m.aggregator, m.updater, m.embedding, m.num_layers, m.node_feat != nullptr, num_nodes, nullptr,
+                      nullptr, nullptr, nullptr);
 }
 
 bool modules_supported(const Dims &d, const tig_modules &m)
@@ -566,7 +666,9 @@ bool modules_supported(const Dims &d, const tig_modules &m)
     const ModDims md = mod_dims(d, p);
     if (m.embedding != TIG_EMB_ATTENTION && d.E != d.M)
         return false;
-    return d.prec == TIG_FP32 && update_lds(md) <= 160 * 1024 && rows_lds(md) <= 160 * 1024 &&
+    if (m.num_layers == 2 && (m.embedding != TIG_EMB_ATTENTION || (d.E + d.T) % d.H != 0))
+        return false;
+    return d.prec == TIG_FP32 && update_lds(md) <= 160 * 1024 && rows_lds_all(md, m.num_layers) <= 160 * 1024 &&
            decode_lds(md) <= 160 * 1024 && d.K <= kModThreads;
 }
 
@@ -575,9 +677,10 @@ hipError_t modules_attach(const Dims &d, const tig_modules &m, const tig_weights
 {
     ModParams p;
     float *stage = nullptr, *nf = nullptr;
-    mod_layout(d, m.aggregator, m.updater, m.embedding, m.node_feat != nullptr, num_nodes, (char *)workspace, &p, &stage, &nf);
+    mod_layout(d, m.aggregator, m.updater, m.embedding, m.num_layers, m.node_feat != nullptr, num_nodes, (char *)workspace, &p,
+               &stage, &nf);
     const ModDims md = mod_dims(d, p);
-    const int M = d.M, T = d.T, E = d.E, da = d.da, dkv = d.dkv, D = d.Dmsg, GM = md.G * d.M;
+    const int M = d.M, T = d.T, E = d.E, D = d.Dmsg, GM = md.G * d.M;
     hipError_t e;
     auto vec = [&](const float *dst, const float *src, size_t n) -> hipError_t {
         return hipMemcpyAsync((void *)dst, src, 4 * n, hipMemcpyDefault, s);
@@ -608,18 +711,27 @@ hipError_t modules_attach(const Dims &d, const tig_modules &m, const tig_weights
     MOD_TRY(mat(p.T_i, w.W_i, GM, D));
     MOD_TRY(mat(p.T_h, w.W_h, GM, M));
     if (m.embedding == TIG_EMB_ATTENTION) {
-        MOD_TRY(vec(p.b_Q, w.b_Q, da));
-        MOD_TRY(vec(p.b_K, w.b_K, da));
-        MOD_TRY(vec(p.b_V, w.b_V, da));
-        MOD_TRY(vec(p.b_O, w.b_O, da));
-        MOD_TRY(vec(p.b_m1, w.b_m1, E));
-        MOD_TRY(vec(p.b_m2, w.b_m2, E));
-        MOD_TRY(mat(p.T_Q, w.W_Q, da, da));
-        MOD_TRY(mat(p.T_K, w.W_K, da, dkv));
-        MOD_TRY(mat(p.T_V, w.W_V, da, dkv));
-        MOD_TRY(mat(p.T_O, w.W_O, da, da));
-        MOD_TRY(mat(p.T_m1, w.W_m1, E, da + M));
-        MOD_TRY(mat(p.T_m2, w.W_m2, E, E));
+        // the second layer's matrices have the first layer's roles with E-wide input rows
+        tig_layer_weights first = {};
+        first.W_Q = w.W_Q, first.b_Q = w.b_Q, first.W_K = w.W_K, first.b_K = w.b_K, first.W_V = w.W_V, first.b_V = w.b_V;
+        first.W_O = w.W_O, first.b_O = w.b_O, first.W_m1 = w.W_m1, first.b_m1 = w.b_m1, first.W_m2 = w.W_m2, first.b_m2 = w.b_m2;
+        for (int l = 0; l < p.layers; ++l) {
+            const tig_layer_weights &src = l == 0 ? first : *m.layer2;
+            const AttnLayer &A = p.L[l];
+            const int in_w = l == 0 ? M : E, a_w = in_w + T, kv_w = in_w + d.F + T;
+            MOD_TRY(vec(A.b_Q, src.b_Q, a_w));
+            MOD_TRY(vec(A.b_K, src.b_K, a_w));
+            MOD_TRY(vec(A.b_V, src.b_V, a_w));
+            MOD_TRY(vec(A.b_O, src.b_O, a_w));
+            MOD_TRY(vec(A.b_m1, src.b_m1, E));
+            MOD_TRY(vec(A.b_m2, src.b_m2, E));
+            MOD_TRY(mat(A.T_Q, src.W_Q, a_w, a_w));
+            MOD_TRY(mat(A.T_K, src.W_K, a_w, kv_w));
+            MOD_TRY(mat(A.T_V, src.W_V, a_w, kv_w));
+            MOD_TRY(mat(A.T_O, src.W_O, a_w, a_w));
+            MOD_TRY(mat(A.T_m1, src.W_m1, E, a_w + in_w));
+            MOD_TRY(mat(A.T_m2, src.W_m2, E, E));
+        }
     }
     MOD_TRY(vec(p.b_d1, w.b_d1, E));
     MOD_TRY(vec(p.w_d2, w.w_d2, E));
@@ -634,7 +746,7 @@ hipError_t modules_attach(const Dims &d, const tig_modules &m, const tig_weights
         MOD_TRY(launch_fill_zero(p.acc_cnt, (size_t)2 * d.max_batch * 4, s));
     }
     MOD_TRY(hipFuncSetAttribute((const void *)k_mod_update, hipFuncAttributeMaxDynamicSharedMemorySize, update_lds(md)));
-    MOD_TRY(hipFuncSetAttribute((const void *)k_mod_rows, hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds(md)));
+    MOD_TRY(hipFuncSetAttribute((const void *)k_mod_rows, hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds_all(md, p.layers)));
     MOD_TRY(hipFuncSetAttribute((const void *)k_mod_decode, hipFuncAttributeMaxDynamicSharedMemorySize, decode_lds(md)));
 #undef MOD_TRY
     *out = p;
@@ -683,7 +795,14 @@ hipError_t launch_modules(const Dims &d, const LaunchPlan &plan, const PackedWei
         b.finish_here = 1;  // slots of the query set (its row references all name memory rows)
         if ((e = launch_gru(d, plan, pw, b, s)) != hipSuccess)
             return e;
-        hipLaunchKernelGGL(k_mod_rows, dim3(3 * B), dim3(kModThreads), rows_lds(md), s, b, md, p);
+        if (p.layers == 2) {
+            const ModDims md2 = second_layer_dims(md);
+            hipLaunchKernelGGL(k_mod_hop2, dim3(3 * B), dim3(kModThreads), 0, s, b, md, p);
+            hipLaunchKernelGGL(k_mod_rows, dim3(3 * B * (d.K + 1)), dim3(kModThreads), rows_lds(md), s, b, md, p, p.L[0], (int)kRowsFirst);
+            hipLaunchKernelGGL(k_mod_rows, dim3(3 * B), dim3(kModThreads), rows_lds(md2), s, b, md2, p, p.L[1], (int)kRowsSecond);
+        } else {
+            hipLaunchKernelGGL(k_mod_rows, dim3(3 * B), dim3(kModThreads), rows_lds(md), s, b, md, p, p.L[0], (int)kRowsSingle);
+        }
         hipLaunchKernelGGL(k_mod_decode, dim3((B + kEV - 1) / kEV), dim3(kModThreads), decode_lds(md), s, b, md, p, 1);
         if ((e = hipGetLastError()) != hipSuccess)
             return e;

@@ -857,6 +857,14 @@ static int check_modules(const tig_modules *m)
         return TIG_EINVAL;
     if (m->embedding == TIG_EMB_TIME_PROJECTION && !m->time_proj_w)
         return TIG_EINVAL;
+    if (m->num_layers < 0 || m->num_layers > 2)
+        return TIG_EINVAL;
+    if (m->num_layers == 2) {
+        const tig_layer_weights *l = m->layer2;
+        if (m->embedding != TIG_EMB_ATTENTION || !l || l->struct_size != sizeof(tig_layer_weights) || !l->W_Q || !l->b_Q ||
+            !l->W_K || !l->b_K || !l->W_V || !l->b_V || !l->W_O || !l->b_O || !l->W_m1 || !l->b_m1 || !l->W_m2 || !l->b_m2)
+            return TIG_EINVAL;
+    }
     return TIG_OK;
 }
 
@@ -888,7 +896,7 @@ int tig_modules_attach(tig_ctx *ctx, const tig_modules *modules, const tig_weigh
         return fail(ctx, TIG_EINVAL, "tig_modules_attach: the context has a training workspace");
     if (!modules_supported(ctx->d, *modules))
         return fail(ctx, TIG_EINVAL, "tig_modules_attach: needs an fp32 context (emb_dim == mem_dim unless the embedding is "
-                                     "attention) whose rows fit the kernels");
+                                     "attention; two layers: emb_dim + time_dim divisible by num_heads) whose rows fit the kernels");
     const tig_weights &w = *weights;
     const bool attn = modules->embedding == TIG_EMB_ATTENTION;
     if (!w.time_w || !w.time_b || !w.W_i || !w.b_i || !w.W_h || !w.b_h || !w.W_d1 || !w.b_d1 || !w.w_d2 || !w.b_d2 ||

@@ -284,12 +284,18 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
 // ---- other instances of the general architecture (modules.hip) ----
 // Module selection of a context and its weights: transposed copies ([in x out]) in the attached workspace.
 constexpr int kAccCopies = 8;  // accumulation rows per node of the mean aggregator (entries are dealt out to them: less same-address traffic)
-struct ModParams {
-    int agg, upd, emb;                         // tig_aggregator, tig_updater, tig_embedding
-    const double *time_w_rev, *time_b_rev;     // [T] time-encoding frequency / phase in revolutions
-    const float *T_i, *T_h, *b_i, *b_h;        // state update: [D_msg x GM], [M x GM], [GM], [GM] (G = 3 GRU, 1 RNN)
+struct AttnLayer {
     const float *T_Q, *T_K, *T_V, *T_O, *b_Q, *b_K, *b_V, *b_O;  // attention
     const float *T_m1, *T_m2, *b_m1, *b_m2;    // merge MLP
+};
+struct ModParams {
+    int agg, upd, emb;                         // tig_aggregator, tig_updater, tig_embedding
+    int layers;                                // attention embedding: 1 or 2 stacked layers
+    const double *time_w_rev, *time_b_rev;     // [T] time-encoding frequency / phase in revolutions
+    const float *T_i, *T_h, *b_i, *b_h;        // state update: [D_msg x GM], [M x GM], [GM], [GM] (G = 3 GRU, 1 RNN)
+    AttnLayer L[2];                            // first layer (input width M) and second (input width E)
+    QuerySet hop2;                             // two layers: neighbour tables of (neighbour k of query row q, t_q) at row q * K + k
+    float *h1;                                 // two layers: first-layer rows [3 * max_batch x (K + 1) x E]: neighbour k of row q, then q itself
     const float *T_d1, *b_d1, *w_d2, *b_d2;    // decoder: [2E x E], [E], [E], [1]
     const float *node_feat;                    // [N x M] or NULL
     const float *time_proj_w;                  // [M] or NULL

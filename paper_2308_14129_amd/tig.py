@@ -49,9 +49,17 @@ class tig_weights(Structure):
     _fields_ = [("struct_size", c_uint32), ("reserved", c_uint32)] + [(n, c_void_p) for n in WEIGHT_NAMES]
 
 
+LAYER_WEIGHT_NAMES = ("W_Q", "b_Q", "W_K", "b_K", "W_V", "b_V", "W_O", "b_O", "W_m1", "b_m1", "W_m2", "b_m2")
+
+
+class tig_layer_weights(Structure):
+    _fields_ = [("struct_size", c_uint32), ("reserved", c_uint32)] + [(n, c_void_p) for n in LAYER_WEIGHT_NAMES]
+
+
 class tig_modules(Structure):
     _fields_ = [("struct_size", c_uint32), ("aggregator", c_int32), ("updater", c_int32), ("embedding", c_int32),
-                ("node_feat", c_void_p), ("time_proj_w", c_void_p)]
+                ("node_feat", c_void_p), ("time_proj_w", c_void_p), ("num_layers", c_int32), ("reserved", c_int32),
+                ("layer2", POINTER(tig_layer_weights))]
 
 
 class tig_batch(Structure):
@@ -245,13 +253,18 @@ class TigContext:
         return [float(x) for x in ms]
 
     # -- other instances of the general architecture -------------------------------------------
-    def modules_attach(self, weights: dict, aggregator="last", updater="gru", embedding="attention", node_feat=None):
+    def modules_attach(self, weights: dict, aggregator="last", updater="gru", embedding="attention", node_feat=None,
+                       layers=1, layer2=None):
         """Allocates the workspace of a module selection and attaches it with `weights` (a dict that may
         lack the attention / merge weights unless the embedding is attention; "time_proj_w" for the
-        time projection)."""
+        time projection; `layer2`: the dict of a second attention layer's weights for layers = 2)."""
         torch = self._torch
+        l2 = None
+        if layer2 is not None:
+            l2 = tig_layer_weights(ctypes.sizeof(tig_layer_weights), 0, *[_addr(layer2[k]) for k in LAYER_WEIGHT_NAMES])
         m = tig_modules(ctypes.sizeof(tig_modules), AGGREGATORS[aggregator], UPDATERS[updater], EMBEDDINGS[embedding],
-                        _addr(node_feat), _addr(weights.get("time_proj_w")))
+                        _addr(node_feat), _addr(weights.get("time_proj_w")), layers, 0,
+                        ctypes.pointer(l2) if l2 is not None else None)
         n = c_size_t(0)
         self._check(self.lib.tig_modules_workspace_bytes(ctypes.byref(self.cfg), ctypes.byref(m), self.num_nodes,
                                                          ctypes.byref(n)))

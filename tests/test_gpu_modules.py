@@ -29,7 +29,7 @@ INSTANCES = {
 
 
 class Case:
-    def __init__(self, w, inst, node_feat, order="update_first", max_batch=None):
+    def __init__(self, w, inst, node_feat, order="update_first", max_batch=None, layers=1):
         import torch
         from paper_2308_14129_amd import tig
         self.w, self.inst = w, inst
@@ -37,13 +37,14 @@ class Case:
         self.W = S.make_module_weights(w, inst["updater"], inst["embedding"])
         self.ix = O.NeighbourIndex(self.g.num_nodes, self.g.src, self.g.dst, self.g.ts)
         self.nf = S.make_node_feat(w, self.g.num_nodes) if node_feat else None
-        self.mods = G.Modules(inst["aggregator"], inst["updater"], inst["embedding"], self.nf)
+        self.L2 = S.make_layer2_weights(w) if layers == 2 else None
+        self.mods = G.Modules(inst["aggregator"], inst["updater"], inst["embedding"], self.nf, layers, self.L2)
         self.deferred = order == "deferred"
         E = w.emb_dim if inst["embedding"] == "attention" else w.mem_dim
         cfg = tig.make_config(w.mem_dim, w.time_dim, w.feat_dim, E, w.num_neighbors, w.num_heads,
                               max_batch or w.batch_size, "fp32", order)
         self.ctx = tig.TigContext(cfg, self.g.num_nodes, self.g.src, self.g.dst, self.g.ts, self.g.edge_feat, None)
-        self.ctx.modules_attach(self.W, node_feat=self.nf, **inst)
+        self.ctx.modules_attach(self.W, node_feat=self.nf, layers=layers, layer2=self.L2, **inst)
         self.torch = torch
 
     def run(self, batches, warm_at=None, with_neg=True, locked=False):
@@ -156,6 +157,54 @@ def test_c3_batch_2000_and_above_the_selection_limit(name):
     c.close()
 
 
+@pytest.mark.parametrize("name,node_feat", [("headline", False), ("mean_gru_attention", True), ("last_rnn_attention", False)])
+def test_c1_two_layers_from_reset_and_ragged(name, node_feat):
+    """Two stacked attention layers (the embedding over the 2-hop neighbourhood): from reset (empty
+    and short neighbour tables in both hops), ragged batches, a one-event batch, no negatives."""
+    c = Case(S.WORKLOADS["c1_tiny"], INSTANCES[name], node_feat, layers=2)
+    c.run(list(S.batches(c.w.num_events, 136))[:6])
+    c.run([(3000, 1), (3001, 136)], warm_at=3000)
+    c.run([(5000, 200)], warm_at=5000, with_neg=False)
+    c.close()
+
+
+def test_c1_two_layers_deferred_order():
+    c = Case(S.WORKLOADS["c1_tiny"], INSTANCES["headline"], True, order="deferred", layers=2)
+    c.run([(3000, 100), (3100, 100), (3300, 50)], warm_at=3000)
+    c.close()
+
+
+def test_c2_two_layers_wide_rows_emb_narrower_than_memory():
+    """E = 100 != M = 172: the second layer's rows have a width of their own."""
+    w = S.WORKLOADS["c2_bipartite_medium"]
+    c = Case(w, INSTANCES["headline"], True, layers=2)
+    first, bs = window(w, 0.5, 2)
+    c.run(bs, warm_at=first)
+    c.close()
+
+
+def test_c3_two_layers_twenty_neighbours():
+    w = S.WORKLOADS["c3_bipartite_dense"]
+    c = Case(w, INSTANCES["mean_gru_attention"], False, layers=2)
+    first, bs = window(w, 0.5, 1)
+    c.run(bs, warm_at=first)
+    c.close()
+
+
+def test_two_layers_need_the_attention_embedding_and_their_weights():
+    import ctypes
+    from paper_2308_14129_amd import tig
+    w = S.WORKLOADS["c1_tiny"]
+    cfg = tig.make_config(w.mem_dim, w.time_dim, w.feat_dim, w.mem_dim, w.num_neighbors, w.num_heads, 200)
+    lib = tig.load_library()
+    n = ctypes.c_size_t(0)
+    for emb, l2 in ((1, True), (0, False)):
+        L2 = S.make_layer2_weights(w)
+        lw = tig.tig_layer_weights(ctypes.sizeof(tig.tig_layer_weights), 0, *[L2[k].ctypes.data for k in tig.LAYER_WEIGHT_NAMES])
+        m = tig.tig_modules(ctypes.sizeof(tig.tig_modules), 0, 0, emb, None, None, 2, 0, ctypes.pointer(lw) if l2 else None)
+        assert lib.tig_modules_workspace_bytes(ctypes.byref(cfg), ctypes.byref(m), 1000, ctypes.byref(n)) == tig.TIG_EINVAL
+
+
 def test_headline_selection_matches_the_fused_step():
     """The module path with (last, GRU, attention, no node features) and the fused kernels of the
     headline instance compute the same step: both within the gate of the same oracle."""
@@ -202,7 +251,7 @@ def test_context_without_weights_refuses_steps_and_static_and_training():
     torch.cuda.synchronize()
     # emb_dim != mem_dim with a non-attention embedding is refused
     cfg2 = tig.make_config(w.mem_dim, w.time_dim, w.feat_dim, w.mem_dim + 4, w.num_neighbors, w.num_heads, 200)
-    m = tig.tig_modules(ctypes.sizeof(tig.tig_modules), 0, 1, 1, None, None)
+    m = tig.tig_modules(ctypes.sizeof(tig.tig_modules), 0, 1, 1, None, None, 1, 0, None)
     n = ctypes.c_size_t(0)
     assert ctx.lib.tig_modules_workspace_bytes(ctypes.byref(cfg2), ctypes.byref(m), g.num_nodes, ctypes.byref(n)) == tig.TIG_EINVAL
     ctx.close()
