@@ -45,11 +45,18 @@ __global__ void k_gemm64(double *C, int ldc, const TA *A, int ars, int acs, cons
     if (idx >= m * n)
         return;
     const int i = idx / n, j = idx % n;
-    double acc = 0.0;
-    for (int k = 0; k < kdim; ++k)
-        acc += (double)A[(size_t)i * ars + (size_t)k * acs] * (double)B[(size_t)k * brs + (size_t)j * bcs];
+    // four partial sums: the loads of four steps are in flight together and the adds do not wait for each other
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    int k = 0;
+    for (; k + 4 <= kdim; k += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            acc[u] += (double)A[(size_t)i * ars + (size_t)(k + u) * acs] * (double)B[(size_t)(k + u) * brs + (size_t)j * bcs];
+    }
+    for (; k < kdim; ++k)
+        acc[0] += (double)A[(size_t)i * ars + (size_t)k * acs] * (double)B[(size_t)k * brs + (size_t)j * bcs];
     double *c = C + (size_t)i * ldc + j;
-    *c = (beta != 0.0 ? beta * *c : 0.0) + alpha * acc;
+    *c = (beta != 0.0 ? beta * *c : 0.0) + alpha * ((acc[0] + acc[1]) + (acc[2] + acc[3]));
 }
 
 template <typename TA, typename TB>
@@ -260,8 +267,9 @@ size_t pack_scratch_bytes(const Dims &d) { return scratch_layout(d, nullptr).byt
 size_t packed_weights_bytes(const Dims &d) { return layout(d, nullptr).bytes; }
 
 hipError_t pack_weights(const Dims &d, const tig_weights &w, void *dst, void *scratch,
-                        PackedWeights *pw, hipStream_t s, bool with_gru)
+                        PackedWeights *pw, hipStream_t s, int parts)
 {
+    const bool with_gru = (parts & kPackGru) != 0, with_embed = (parts & kPackEmbed) != 0;
     const PackedLayout L = layout(d, dst);
     const ScratchLayout S = scratch_layout(d, scratch);
     const int M = d.M, T = d.T, E = d.E, H = d.H, da = d.da, dh = d.dh, dkv = d.dkv;
@@ -269,8 +277,12 @@ hipError_t pack_weights(const Dims &d, const tig_weights &w, void *dst, void *sc
     const dim3 blk(kThreads);
     auto grid = [](size_t n) { return dim3((unsigned)((n + kThreads - 1) / kThreads)); };
 
-    TIG_TRY(launch_fill_zero(dst, L.bytes, s));
-    TIG_TRY(launch_fill_zero(scratch, S.bytes, s));
+    // every prepared matrix and vector is written whole, padding included; the clears are for the gaps
+    // between them and for the padded rows of the folding scratch
+    if (parts == kPackAll)
+        TIG_TRY(launch_fill_zero(dst, L.bytes, s));
+    if (with_embed)
+        TIG_TRY(launch_fill_zero(scratch, S.bytes, s));
 
     // time encoding parameters in revolutions: the kernels take cos(2 pi (w_rev x + b_rev))
     hipLaunchKernelGGL(k_to_revolutions, grid(T), blk, 0, s, L.time_w_rev, w.time_w, T);
@@ -300,6 +312,7 @@ hipError_t pack_weights(const Dims &d, const tig_weights &w, void *dst, void *sc
     TIG_TRY(hipGetLastError());
     }
 
+    if (with_embed) {
     // ---- attention query fold ---------------------------------------------------------------
     // cQ = W_Q[:, M:] Phi(0) + b_Q
     hipLaunchKernelGGL(k_phi0, grid(T), blk, 0, s, S.phi0, w.time_b, T);
@@ -382,6 +395,7 @@ hipError_t pack_weights(const Dims &d, const tig_weights &w, void *dst, void *sc
     hipLaunchKernelGGL(k_vec_f32, grid(1), blk, 0, s, L.dec_b2, 1, 1, (const double *)nullptr, w.b_d2,
                        (const float *)nullptr);
     TIG_TRY(hipGetLastError());
+    }
 
     pw->time_w_rev = L.time_w_rev;
     pw->time_b_rev = L.time_b_rev;

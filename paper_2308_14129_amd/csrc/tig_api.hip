@@ -86,6 +86,7 @@ struct tig_ctx {
     int64_t cursor;    // end of the last batch stepped since the last reset / import
     int last_launches; // kernels enqueued by the last tig_step
     void *static_scratch;  // this device's copy of g_static_scratch
+    bool embed_stale;      // training steps have moved the master weights since the attention / merge / decoder weights were last folded
     void *train_ws;        // training workspace (master weights, gradients, the backward pass's buffers), or NULL
     bool has_model;        // tig_init was given weights (the headline instance's prepared weights exist)
     void *mods_ws;         // workspace of an attached module selection, or NULL
@@ -715,6 +716,12 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
             return fail(ctx, TIG_EHIP, "tig_step: clearing the claim table", e);
     }
 
+    if (!train && ctx->train_ws && ctx->embed_stale) {
+        const hipError_t e = train_refold_embed(d, ctx->train_ws, ctx->packed, &ctx->pw, ctx->stream);
+        if (e != hipSuccess)
+            return fail(ctx, TIG_EHIP, "tig_step: re-folding the weights after training steps", e);
+        ctx->embed_stale = false;
+    }
     if (train) {
         sp.train = true;
         sp.train_ws = ctx->train_ws;
@@ -735,6 +742,8 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
         }
         return fail(ctx, TIG_EHIP, "tig_step launch", e);
     }
+    if (train && train->lr != 0.0f)
+        ctx->embed_stale = true;
     ctx->cursor = next_first;
     ctx->last_launches = launches;
     ctx->ahead_g_valid = sp.ahead.count > 0;  // (never after a static call: the memory has changed)
@@ -926,7 +935,7 @@ int tig_modules_attach(tig_ctx *ctx, const tig_modules *modules, const tig_weigh
                                hipMemcpyDefault, s);
         }
         if (e == hipSuccess)
-            e = pack_weights(ctx->d, R.w, ctx->packed, wbase + R.bytes, &ctx->pw, s, false);
+            e = pack_weights(ctx->d, R.w, ctx->packed, wbase + R.bytes, &ctx->pw, s, kPackEmbed);
         for (int i = 0; i < 2 && e == hipSuccess; ++i) {
             e = launch_fill_zero(ctx->S.n_win[i], 4, s);
             if (e == hipSuccess)

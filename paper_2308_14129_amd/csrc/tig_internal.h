@@ -191,10 +191,12 @@ hipError_t csr_build(const int32_t *src, const int32_t *dst, const double *ts, i
 size_t pack_scratch_bytes(const Dims &d);
 size_t packed_weights_bytes(const Dims &d);
 // Folds / pads / reorders the weights into `dst` (device, packed_weights_bytes) and fills `pw`.
-// with_gru = false: W_i / W_h are not read and the GRU part stays zero (a context whose state update
-// runs elsewhere).
+// parts: kPackGru = the state update's matrices (W_i / W_h are read), kPackEmbed = attention, merge
+// MLP and decoder; the time-encoding parameters go with either.  A part that is left out keeps what
+// `dst` holds (zeros after tig_init's clear for a context whose state update runs elsewhere).
+enum PackParts { kPackGru = 1, kPackEmbed = 2, kPackAll = 3 };
 hipError_t pack_weights(const Dims &d, const tig_weights &w_dev_f32, void *dst, void *scratch,
-                        PackedWeights *pw, hipStream_t s, bool with_gru = true);
+                        PackedWeights *pw, hipStream_t s, int parts = kPackAll);
 
 bool plan_launch(const Dims &d, int lds_limit, LaunchPlan *plan);
 int gru_lds_bytes(const Dims &d);
@@ -281,6 +283,9 @@ hipError_t train_attach(const Dims &d, const tig_weights &w, void *workspace, vo
 hipError_t train_copy_out(const Dims &d, void *workspace, bool grads, const tig_weights &out, hipStream_t s);
 hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void *packed, PackedWeights *pw, float lr,
                         float *loss_out, hipStream_t s);
+// after training steps with lr != 0 only the state update's prepared weights follow the masters: this
+// re-folds the rest (attention, merge MLP, decoder) for the fused inference kernels
+hipError_t train_refold_embed(const Dims &d, void *workspace, void *packed, PackedWeights *pw, hipStream_t s);
 // ---- other instances of the general architecture (modules.hip) ----
 // Module selection of a context and its weights: transposed copies ([in x out]) in the attached workspace.
 constexpr int kAccCopies = 8;  // accumulation rows per node of the mean aggregator (entries are dealt out to them: less same-address traffic)

@@ -58,7 +58,8 @@ __device__ inline void matvec_t(const float *WT, int in, int out, const float *x
 {
     for (int j = threadIdx.x; j < out; j += kTrThreads) {
         float acc = bias ? bias[j] : 0.0f;
-        for (int i = 0; i < in; ++i)
+#pragma unroll 8
+        for (int i = 0; i < in; ++i)  // (unrolled: eight independent weight loads in flight, not one per step)
             acc += WT[(size_t)i * out + j] * x[i];
         y[j] = acc;
     }
@@ -69,6 +70,7 @@ __device__ inline void matvec_n(const float *W, int out, int in, const float *dy
 {
     for (int i = threadIdx.x; i < in; i += kTrThreads) {
         float acc = 0.0f;
+#pragma unroll 8
         for (int o = 0; o < out; ++o)
             acc += W[(size_t)o * in + i] * dy[o];
         dx[i] = acc;
@@ -86,6 +88,7 @@ __device__ inline void multivec_t(const float *WT, int in, int out, const float 
 #pragma unroll
             for (int u = 0; u < kKC; ++u)
                 acc[u] = b;
+#pragma unroll 4
             for (int i = 0; i < in; ++i) {
                 const float w = WT[(size_t)i * out + j];
 #pragma unroll
@@ -118,6 +121,8 @@ struct TrainBufs {
     // per applied winner r, and per entry of the applied batch
     float *MSG, *DGI, *DGH, *TGG, *D_STAG;
     int32_t *n_rows;  // [1] distinct queries of the step (written by the forward kernel's block 0)
+    int32_t *live;    // [3B x K] the filled neighbour slots (row x * K + k) of the step, in no particular order
+    int32_t *n_live;  // [1] their number (cleared with the gradients)
 };
 
 // compact row of query-set row q
@@ -174,6 +179,16 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_rows_fwd(StepArgs a, PackedWe
     __syncthreads();
     const int cnt = meta[0];
     const float *self = state_row(a, M, meta[1]);
+    if (threadIdx.x < kWave && cnt > 0) {
+        // the filled slots go on the list that the key / value weight gradients run over (most rows of
+        // a step are negatives without history: their K slots are zero rows)
+        int base = 0;
+        if (threadIdx.x == 0)
+            base = atomicAdd(t.n_live, cnt);
+        base = __shfl(base, 0);
+        if ((int)threadIdx.x < cnt && base >= 0 && base + (int)threadIdx.x < 3 * a.count * K)
+            t.live[base + threadIdx.x] = x * K + (int)threadIdx.x;
+    }
     for (int j = threadIdx.x; j < da; j += kTrThreads) {
         const float v = j < M ? (self ? self[j] : 0.0f) : time_enc(pw.time_w_rev[j - M], pw.time_b_rev[j - M], 0.0);
         q_in[j] = v;
@@ -621,9 +636,13 @@ __device__ inline int row_count(const RowCount &rc)
     return r < 0 ? 0 : (r < rc.rows_max ? (int)r : rc.rows_max);
 }
 
-// C[Mo x No] += A[rows x Mo]^T B[rows x No]; one wavefront per 32 x 32 block of C and slice of the rows
+// C[Mo x No] += A[rows x Mo]^T B[rows x No]; one wavefront per 32 x 32 block of C and slice of the rows.
+// csum != NULL: also csum[Mo] += the column sums of A (the bias gradient that goes with the weight
+// gradient: A^T times a column of ones), by the wavefronts of the first block column.
+// ridx != NULL: the contraction runs over the rows ridx[0 .. rows) of A and B (each below ridx_max).
 __global__ void __launch_bounds__(256) k_gemm_tn(float *C, int ldc, const float *A, int lda, const float *B, int ldb,
-                                                 int Mo, int No, RowCount rc, int n_slices)
+                                                 int Mo, int No, RowCount rc, int n_slices, float *csum, const int32_t *ridx,
+                                                 int ridx_max)
 {
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
     const int lane = threadIdx.x & (kWave - 1);
@@ -638,28 +657,46 @@ __global__ void __launch_bounds__(256) k_gemm_tn(float *C, int ldc, const float 
     const int k_lo = slice * per, k_hi = k_lo + per < rows ? k_lo + per : rows;
     if (k_lo >= k_hi)
         return;
-    floatx4 acc[2][2];
+    const bool with_sum = csum != nullptr && n0 == 0;  // (uniform over the wavefront)
+    floatx4 acc[2][2], accs[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 2; ++i) {
+        accs[i] = floatx4{0, 0, 0, 0};
 #pragma unroll
         for (int j = 0; j < 2; ++j)
             acc[i][j] = floatx4{0, 0, 0, 0};
+    }
     const int c = lane & 15, g = lane >> 4;
-    for (int k = k_lo; k < k_hi; k += 4) {
-        const int kk = k + g;
-        const bool kin = kk < k_hi;
-        float av[2], bv[2];
+    constexpr int kU = 4;  // k-steps whose loads are issued together
+    for (int k = k_lo; k < k_hi; k += 4 * kU) {
+        float av[kU][2], bv[kU][2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int mm = m0 + 16 * i + c, nn = n0 + 16 * i + c;
-            av[i] = kin && mm < Mo ? A[(size_t)kk * lda + mm] : 0.0f;
-            bv[i] = kin && nn < No ? B[(size_t)kk * ldb + nn] : 0.0f;
+        for (int u = 0; u < kU; ++u) {
+            const int kk = k + 4 * u + g;
+            bool kin = kk < k_hi;
+            int row = kk;
+            if (ridx) {
+                row = kin ? ridx[kk] : 0;
+                kin = kin && row >= 0 && row < ridx_max;
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int mm = m0 + 16 * i + c, nn = n0 + 16 * i + c;
+                av[u][i] = kin && mm < Mo ? A[(size_t)row * lda + mm] : 0.0f;
+                bv[u][i] = kin && nn < No ? B[(size_t)row * ldb + nn] : 0.0f;
+            }
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int u = 0; u < kU; ++u) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+            for (int i = 0; i < 2; ++i) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][i], bv[u][j], acc[i][j], 0, 0, 0);
+                if (with_sum)
+                    accs[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][i], 1.0f, accs[i], 0, 0, 0);
+            }
+        }
     }
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -671,6 +708,16 @@ __global__ void __launch_bounds__(256) k_gemm_tn(float *C, int ldc, const float 
                 if (mm < Mo && nn < No)
                     atomicAdd(&C[(size_t)mm * ldc + nn], acc[i][j][v]);
             }
+    if (with_sum && c == 0) {  // every column of the sum block holds the same value: column 0 adds it
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int mm = m0 + 16 * i + 4 * g + v;
+                if (mm < Mo)
+                    atomicAdd(&csum[mm], accs[i][v]);
+            }
+    }
 }
 
 // out[j] += sum over the rows of A[row][j]
@@ -684,6 +731,7 @@ __global__ void __launch_bounds__(256) k_colsum(float *out, const float *A, int 
     const int per = (rows + n_slices - 1) / n_slices;
     const int lo = slice * per, hi = lo + per < rows ? lo + per : rows;
     float acc = 0.0f;
+#pragma unroll 8
     for (int r = lo; r < hi; ++r)
         acc += A[(size_t)r * lda + j];
     if (lo < hi)
@@ -714,8 +762,18 @@ __global__ void k_sgd(float *P, const float *G, size_t n, float lr)
         P[i] -= lr * G[i];
 }
 
-__global__ void k_transpose(float *dst, const float *src, int rows, int cols)  // dst[c][r] = src[r][c]
+// The transposed copies of all weight matrices in one launch: blockIdx.y names the matrix.
+struct TransposeJobs {
+    float *dst[9];
+    const float *src[9];
+    int rows[9], cols[9];
+};
+__global__ void k_transpose(TransposeJobs J)  // dst[c][r] = src[r][c]
 {
+    const int m = blockIdx.y;
+    const int rows = J.rows[m], cols = J.cols[m];
+    const float *src = J.src[m];
+    float *dst = J.dst[m];
     const size_t n = (size_t)rows * cols, stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
         const size_t r = i / cols, c = i - r * cols;
@@ -776,6 +834,7 @@ static TrainLayout train_layout(const Dims &d, void *base)
     L.G = take(n);
     L.b.D_EMB = take(R * E);
     L.b.D_STAG = take(U * M);
+    L.b.n_live = (int32_t *)take(64);
     L.zero_hi = off;
     const float **wf[22] = {&L.w.time_w, &L.w.time_b, &L.w.W_i, &L.w.b_i, &L.w.W_h, &L.w.b_h, &L.w.W_Q, &L.w.b_Q,
                             &L.w.W_K, &L.w.b_K, &L.w.W_V, &L.w.b_V, &L.w.W_O, &L.w.b_O, &L.w.W_m1, &L.w.b_m1,
@@ -825,6 +884,7 @@ static TrainLayout train_layout(const Dims &d, void *base)
     b.DGH = take(U * 3 * M);
     b.TGG = take(U * 2 * T);
     b.n_rows = (int32_t *)take(64);
+    b.live = (int32_t *)take(S);
     L.pack_scratch = base ? p + off : nullptr;
     off += align_up(pack_scratch_bytes(d));
     L.bytes = off;
@@ -882,10 +942,17 @@ static hipError_t transpose_all(const Dims &d, const TrainLayout &L, hipStream_t
     const Job jobs[] = {{L.T_i, L.w.W_i, 3 * d.M, d.Dmsg}, {L.T_h, L.w.W_h, 3 * d.M, d.M}, {L.T_Q, L.w.W_Q, d.da, d.da},
                         {L.T_K, L.w.W_K, d.da, d.dkv},     {L.T_V, L.w.W_V, d.da, d.dkv},  {L.T_O, L.w.W_O, d.da, d.da},
                         {L.T_m1, L.w.W_m1, d.E, d.da + d.M}, {L.T_m2, L.w.W_m2, d.E, d.E},  {L.T_d1, L.w.W_d1, d.E, 2 * d.E}};
-    for (const Job &j : jobs) {
-        const size_t n = (size_t)j.rows * j.cols;
-        hipLaunchKernelGGL(k_transpose, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, j.dst, j.src, j.rows, j.cols);
+    TransposeJobs J;
+    size_t most = 0;
+    for (int i = 0; i < 9; ++i) {
+        J.dst[i] = jobs[i].dst;
+        J.src[i] = jobs[i].src;
+        J.rows[i] = jobs[i].rows;
+        J.cols[i] = jobs[i].cols;
+        const size_t n = (size_t)jobs[i].rows * jobs[i].cols;
+        most = n > most ? n : most;
     }
+    hipLaunchKernelGGL(k_transpose, dim3((unsigned)((most + 1023) / 1024), 9), dim3(256), 0, s, J);
     return hipGetLastError();
 }
 
@@ -954,15 +1021,21 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
     if ((e = hipGetLastError()) != hipSuccess)
         return e;
 
-    const RowCount rows{b.n_rows, 0, 1, R}, slots{b.n_rows, 0, K, R * K}, pairs{nullptr, 0, 1, 2 * B},
+    const RowCount rows{b.n_rows, 0, 1, R}, live{b.n_live, 0, 1, R * K}, pairs{nullptr, 0, 1, 2 * B},
         wins{a.n_win, 0, 1, 2 * a.msg_count};
-    auto gemm = [&](const float *C, int Mo, int No, const float *A, const float *Bm, const RowCount &rc, int ldb = 0) {
+    // weight gradient C += A^T B together with the bias gradient csum += column sums of A
+    auto gemm = [&](const float *C, const float *csum, int Mo, int No, const float *A, const float *Bm, const RowCount &rc,
+                    int ldb = 0, const int32_t *ridx = nullptr, int ridx_max = 0) {
         const int tiles = ((Mo + 31) / 32) * ((No + 31) / 32);
-        int n_slices = rc.rows_max / 256;  // about 256 rows per wavefront
-        n_slices = n_slices < 1 ? 1 : (n_slices > 512 ? 512 : n_slices);
+        // about 3072 wavefronts per contraction: every slice ends in one atomic add per element of its
+        // block, so few slices; a slice keeps at least 64 rows
+        int n_slices = 3072 / tiles;
+        const int most = rc.rows_max / 64;
+        n_slices = n_slices > most ? most : n_slices;
+        n_slices = n_slices < 1 ? 1 : n_slices;
         const int waves = tiles * n_slices;
         hipLaunchKernelGGL(k_gemm_tn, dim3((waves + 3) / 4), dim3(256), 0, s, (float *)C, No, A, Mo, Bm, ldb ? ldb : No, Mo, No,
-                           rc, n_slices);
+                           rc, n_slices, (float *)csum, ridx, ridx_max);
     };
     auto colsum = [&](const float *out, const float *A, int lda, int cols, const RowCount &rc) {
         int n_slices = rc.rows_max / 512;
@@ -972,34 +1045,22 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
     };
     const int M = d.M, T = d.T, E = d.E, da = d.da, dkv = d.dkv, D = d.Dmsg;
     // decoder
-    gemm(L.g.W_d1, E, 2 * E, b.DY, b.CAT, pairs);
-    colsum(L.g.b_d1, b.DY, E, E, pairs);
-    gemm(L.g.w_d2, 1, E, b.DLOGIT, b.G_, pairs);
-    colsum(L.g.b_d2, b.DLOGIT, 1, 1, pairs);
+    gemm(L.g.W_d1, L.g.b_d1, E, 2 * E, b.DY, b.CAT, pairs);
+    gemm(L.g.w_d2, L.g.b_d2, 1, E, b.DLOGIT, b.G_, pairs);
     // merge MLP
-    gemm(L.g.W_m2, E, E, b.D_EMB, b.H1, rows);
-    colsum(L.g.b_m2, b.D_EMB, E, E, rows);
-    gemm(L.g.W_m1, E, da + M, b.DZ1, b.X1, rows);
-    colsum(L.g.b_m1, b.DZ1, E, E, rows);
+    gemm(L.g.W_m2, L.g.b_m2, E, E, b.D_EMB, b.H1, rows);
+    gemm(L.g.W_m1, L.g.b_m1, E, da + M, b.DZ1, b.X1, rows);
     // attention
-    gemm(L.g.W_O, da, da, b.D_ATTN, b.O_, rows);
-    colsum(L.g.b_O, b.D_ATTN, da, da, rows);
-    gemm(L.g.W_Q, da, da, b.DQV, b.QIN, rows);
-    colsum(L.g.b_Q, b.DQV, da, da, rows);
-    gemm(L.g.W_K, da, dkv, b.DKP, b.KV, slots);
-    colsum(L.g.b_K, b.DKP, da, da, slots);
-    gemm(L.g.W_V, da, dkv, b.DVP, b.KV, slots);
-    colsum(L.g.b_V, b.DVP, da, da, slots);
-    // time encoding: per-row partial sums [gw | gb]
-    colsum(L.g.time_w, b.TG, 2 * T, T, rows);
-    colsum(L.g.time_b, b.TG + T, 2 * T, T, rows);
+    gemm(L.g.W_O, L.g.b_O, da, da, b.D_ATTN, b.O_, rows);
+    gemm(L.g.W_Q, L.g.b_Q, da, da, b.DQV, b.QIN, rows);
+    gemm(L.g.W_K, L.g.b_K, da, dkv, b.DKP, b.KV, live, 0, b.live, R * K);
+    gemm(L.g.W_V, L.g.b_V, da, dkv, b.DVP, b.KV, live, 0, b.live, R * K);
+    // time encoding: per-row partial sums [gw | gb]; the two gradients are neighbours in the gradient buffer
+    colsum(L.g.time_w, b.TG, 2 * T, 2 * T, rows);
     if (a.msg_count > 0) {
-        gemm(L.g.W_i, 3 * M, D, b.DGI, b.MSG, wins);
-        colsum(L.g.b_i, b.DGI, 3 * M, 3 * M, wins);
-        gemm(L.g.W_h, 3 * M, M, b.DGH, b.MSG, wins, D);  // h = the first M columns of the message rows
-        colsum(L.g.b_h, b.DGH, 3 * M, 3 * M, wins);
-        colsum(L.g.time_w, b.TGG, 2 * T, T, wins);
-        colsum(L.g.time_b, b.TGG + T, 2 * T, T, wins);
+        gemm(L.g.W_i, L.g.b_i, 3 * M, D, b.DGI, b.MSG, wins);
+        gemm(L.g.W_h, L.g.b_h, 3 * M, M, b.DGH, b.MSG, wins, D);  // h = the first M columns of the message rows
+        colsum(L.g.time_w, b.TGG, 2 * T, 2 * T, wins);
     }
     if (loss_out)
         hipLaunchKernelGGL(k_loss_sum, dim3(1), dim3(256), 0, s, b.LOSS, 2 * B, loss_out);
@@ -1014,9 +1075,18 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
             return e;
         if ((e = transpose_all(d, L, s)) != hipSuccess)
             return e;
-        e = pack_weights(d, L.w, packed, L.pack_scratch, pw, s);
+        // the step's own forward pass reads the masters and their transposes; of the prepared weights
+        // only the state update's (and the time encoding's) are read by a training step, so only they
+        // follow every update; the rest is re-folded when an inference step next needs it
+        e = pack_weights(d, L.w, packed, L.pack_scratch, pw, s, kPackGru);
     }
     return e;
+}
+
+hipError_t train_refold_embed(const Dims &d, void *workspace, void *packed, PackedWeights *pw, hipStream_t s)
+{
+    const TrainLayout L = train_layout(d, workspace);
+    return pack_weights(d, L.w, packed, L.pack_scratch, pw, s, kPackEmbed);
 }
 
 }  // namespace tig
