@@ -7,12 +7,16 @@
 // (binary cross-entropy on the logits of each event against one negative), the hand-written
 // backward pass and a plain SGD update of the fp32 master weights; the folded, lane-ordered
 // weights that the inference kernels read are rebuilt from the masters afterwards (pack.hip).
-//   k_tr_rows_fwd   one workgroup per distinct query: attention and merge MLP from the step's
-//                   state rows (a negative's neighbours are looked up here)
+//   k_tr_gather     the distinct queries as matrices: query rows, key / value rows of the filled
+//                   neighbour slots, the list of those slots (a negative's neighbours are looked up here)
+//   k_rowgemm       every layer product of the forward AND the backward pass over all rows at once on
+//                   the matrix cores (fp32 16x16x4): Q / K / V / O projections, merge MLP, and their
+//                   transposed products dX = dY W; the per-slot products run over the filled slots only
+//   k_tr_attn_fwd / k_tr_attn_bwd   scores, softmax, weighted value sum of one query per wavefront
 //   k_tr_decoder    one workgroup per event: both logits, loss terms, embedding rows out, and the
 //                   decoder's backward down to the embeddings (added into the rows' gradients)
-//   k_tr_rows_bwd   one workgroup per distinct query: merge MLP and attention backward; the
-//                   gradient w.r.t. state rows that this step's GRU wrote goes to those rows
+//   k_tr_scatter    the gradient w.r.t. state rows that this step's GRU wrote goes to those rows;
+//                   time-encoding partial sums per query
 //   k_tr_gru_bwd    one workgroup per applied winner: message and GRU gates recomputed from the
 //                   memory as the step found it, backward to the gate pre-activations
 //   k_gemm_tn       every weight gradient is dW = D^T X over the rows' stored (delta, input) pairs:
@@ -114,8 +118,10 @@ struct TrainBufs {
     const float *T_i, *T_h, *T_Q, *T_K, *T_V, *T_O, *T_m1, *T_m2, *T_d1;
     // per distinct query (compact row x: sources / destinations first, then the negatives)
     float *QIN, *QV, *O_, *PROB, *X1, *H1, *D_EMB, *DZ1, *D_ATTN, *DQV, *TG;
+    float *DOUT, *DSU, *DQIN;  // gradients of the heads' outputs [da], of the own state through the merge layer [M], of the query row [da]
+    int32_t *HAS;              // 1 for a query with at least one filled neighbour slot
     // per neighbour slot (row x * K + k)
-    float *KV, *KP, *VP, *DKP, *DVP;
+    float *KV, *KP, *VP, *DKP, *DVP, *DKV;
     // per (pair, event): pair 0 = (source, destination), pair 1 = (source, negative); row p * count + b
     float *CAT, *DY, *G_, *DLOGIT, *LOSS;
     // per applied winner r, and per entry of the applied batch
@@ -129,167 +135,147 @@ struct TrainBufs {
 __device__ inline int compact_row(int q, int n_u, int count) { return q < 2 * count ? q : n_u + (q - 2 * count); }
 
 // ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(kTrThreads) k_tr_rows_fwd(StepArgs a, PackedWeights pw, TrainDims d, TrainBufs t)
+constexpr int kRowWaves = kTrThreads / kWave;  // rows per workgroup of the per-row kernels (one wavefront each)
+
+__device__ inline double shfl_f64(double v, int src)
 {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __shfl(lo, src);
+    hi = __shfl(hi, src);
+    return __hiloint2double(hi, lo);
+}
+
+// The step's distinct queries laid out as matrices (one wavefront per query): the query row
+// [s_u | Phi(0)], the own state as the tail of the merge layer's input, the key / value rows
+// [s_v | e | Phi(t - t_k)] of the filled neighbour slots, and the list of those slots.  A negative's
+// neighbours are looked up here.
+__global__ void __launch_bounds__(kTrThreads) k_tr_gather(StepArgs a, PackedWeights pw, TrainDims d, TrainBufs t)
+{
     int n_u = *a.qs.n_u;
     n_u = n_u < 2 * a.count ? n_u : 2 * a.count;
     const int n_rows = n_u + a.count;
     if (blockIdx.x == 0 && threadIdx.x == 0)
         *t.n_rows = n_rows;
-    const int x = (int)blockIdx.x;
+    const int x = (int)blockIdx.x * kRowWaves + wave_id();
     if (x >= n_rows)
-        return;
-    const int M = d.M, F = d.F, E = d.E, K = d.K, H = d.H, da = d.da, dh = d.dh, dkv = d.dkv;
-    double *dts = (double *)smem;     // [K]
-    int *refs = (int *)(dts + K);     // [K]
-    int *eids = refs + K;             // [K]
-    int *meta = eids + K;             // [2] cnt, self_ref (+ 2 of padding)
-    float *s_u = (float *)(meta + 4); // [M]
-    float *q_in = s_u + M;            // [da]
-    float *Qv = q_in + da;            // [da]
-    float *kv = Qv + da;              // [K x dkv]
-    float *KPs = kv + K * dkv;        // [K x da]
-    float *VPs = KPs + K * da;        // [K x da]
-    float *sc = VPs + K * da;         // [H x K]
-    float *o = sc + H * K;            // [da]
-    float *xcat = o + da;             // [da + M]: attn | s_u
-    float *h1 = xcat + da + M;        // [E]
-
+        return;  // (uniform over the wavefront)
+    const int lane = lane_id();
+    const int M = d.M, F = d.F, K = d.K, da = d.da, dkv = d.dkv;
     const int q = x < n_u ? x : 2 * a.count + (x - n_u);
-    if (x >= n_u && threadIdx.x < kWave) {  // a negative: the first wavefront looks up its neighbours
-        int32_t rf, ee;
-        double ts_k;
-        (void)finish_negative(a, K, x - n_u, rf, ee, ts_k);
-        if (threadIdx.x == 0)
-            a.qs.self_ref[q] = resolve_ref(ref_ctx(a), a.neg[x - n_u]);
+    int cnt;
+    int32_t sref, my_ref = kRefNone, my_eid = -1;
+    double my_ts = 0.0, t_q;
+    if (x >= n_u) {
+        const int b = x - n_u;
+        t_q = a.ts[a.first_eid + b];
+        cnt = finish_negative(a, K, b, my_ref, my_eid, my_ts);
+        sref = resolve_ref(ref_ctx(a), a.neg[b]);
+        if (lane == 0)
+            a.qs.self_ref[q] = sref;
+    } else {
+        t_q = a.qs.t[q];
+        cnt = a.qs.cnt[q];
+        sref = a.qs.self_ref[q];
+        if (lane < K) {
+            my_ref = a.qs.ref[(size_t)q * K + lane];
+            my_eid = a.qs.eid[(size_t)q * K + lane];
+            my_ts = a.qs.ts[(size_t)q * K + lane];
+        }
     }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int c = a.qs.cnt[q];
-        meta[0] = c < 0 ? 0 : (c > K ? K : c);
-        meta[1] = a.qs.self_ref[q];
-    }
-    const double t_q = a.qs.t[q];
-    if ((int)threadIdx.x < K) {
-        refs[threadIdx.x] = a.qs.ref[(size_t)q * K + threadIdx.x];
-        eids[threadIdx.x] = a.qs.eid[(size_t)q * K + threadIdx.x];
-        dts[threadIdx.x] = t_q - a.qs.ts[(size_t)q * K + threadIdx.x];
-    }
-    __syncthreads();
-    const int cnt = meta[0];
-    const float *self = state_row(a, M, meta[1]);
-    if (threadIdx.x < kWave && cnt > 0) {
-        // the filled slots go on the list that the key / value weight gradients run over (most rows of
-        // a step are negatives without history: their K slots are zero rows)
+    cnt = cnt < 0 ? 0 : (cnt > K ? K : cnt);
+    if (lane == 0)
+        t.HAS[x] = cnt > 0 ? 1 : 0;
+    if (cnt > 0) {
+        // the filled slots go on the list that every per-slot matrix product runs over (most rows of a
+        // step are negatives without history)
         int base = 0;
-        if (threadIdx.x == 0)
+        if (lane == 0)
             base = atomicAdd(t.n_live, cnt);
         base = __shfl(base, 0);
-        if ((int)threadIdx.x < cnt && base >= 0 && base + (int)threadIdx.x < 3 * a.count * K)
-            t.live[base + threadIdx.x] = x * K + (int)threadIdx.x;
+        if (lane < cnt && base >= 0 && base + lane < 3 * a.count * K)
+            t.live[base + lane] = x * K + lane;
     }
-    for (int j = threadIdx.x; j < da; j += kTrThreads) {
+    const float *self = state_row(a, M, sref);
+    for (int j = lane; j < da; j += kWave) {
         const float v = j < M ? (self ? self[j] : 0.0f) : time_enc(pw.time_w_rev[j - M], pw.time_b_rev[j - M], 0.0);
-        q_in[j] = v;
-        if (j < M)
-            s_u[j] = v;
         t.QIN[(size_t)x * da + j] = v;
+        if (j < M)
+            t.X1[(size_t)x * (da + M) + da + j] = v;
     }
-    // key / value rows [s_v | e | Phi(t - t_k)]; unused slots are zero rows
-    for (int idx = threadIdx.x; idx < K * dkv; idx += kTrThreads) {
-        const int k = idx / dkv, i = idx - k * dkv;
-        float v = 0.0f;
-        if (k < cnt) {
-            if (i < M) {
-                const float *row = state_row(a, M, refs[k]);
+    for (int k = 0; k < cnt; ++k) {
+        const int32_t rf = __shfl(my_ref, k), eid = __shfl(my_eid, k);
+        const double dt = t_q - shfl_f64(my_ts, k);
+        const float *row = state_row(a, M, rf);
+        float *dst = t.KV + ((size_t)x * K + k) * dkv;
+        for (int i = lane; i < dkv; i += kWave) {
+            float v;
+            if (i < M)
                 v = row ? row[i] : 0.0f;
-            } else if (i < M + F) {
-                v = eids[k] >= 0 ? a.edge_feat[(size_t)eids[k] * F + (i - M)] : 0.0f;
-            } else {
-                v = time_enc(pw.time_w_rev[i - M - F], pw.time_b_rev[i - M - F], dts[k]);
-            }
+            else if (i < M + F)
+                v = eid >= 0 ? a.edge_feat[(size_t)eid * F + (i - M)] : 0.0f;
+            else
+                v = time_enc(pw.time_w_rev[i - M - F], pw.time_b_rev[i - M - F], dt);
+            dst[i] = v;
         }
-        kv[idx] = v;
-        t.KV[((size_t)x * K) * dkv + idx] = v;
     }
-    __syncthreads();
-    if (cnt > 0) {
-        matvec_t(t.T_Q, da, da, q_in, t.b_Q, Qv);
-        multivec_t(t.T_K, dkv, da, kv, dkv, cnt, t.b_K, KPs);
-        multivec_t(t.T_V, dkv, da, kv, dkv, cnt, t.b_V, VPs);
-        __syncthreads();
-        const float scale = 1.0f / sqrtf((float)dh);
-        for (int idx = threadIdx.x; idx < H * cnt; idx += kTrThreads) {
-            const int h = idx / cnt, k = idx - h * cnt;
-            float s = 0.0f;
-            for (int e = 0; e < dh; ++e)
-                s += Qv[h * dh + e] * KPs[(size_t)k * da + h * dh + e];
-            sc[h * K + k] = s * scale;
-        }
-        __syncthreads();
-        if ((int)threadIdx.x < H) {
-            const int h = threadIdx.x;
-            float mx = -INFINITY, sum = 0.0f;
-            for (int k = 0; k < cnt; ++k)
-                mx = fmaxf(mx, sc[h * K + k]);
-            for (int k = 0; k < cnt; ++k) {
-                const float e = expf(sc[h * K + k] - mx);
-                sc[h * K + k] = e;
-                sum += e;
-            }
-            for (int k = 0; k < cnt; ++k)
-                sc[h * K + k] /= sum;
-            for (int k = cnt; k < K; ++k)
-                sc[h * K + k] = 0.0f;
-        }
-        __syncthreads();
-        for (int j = threadIdx.x; j < da; j += kTrThreads) {
-            const int h = j / dh;
-            float acc = 0.0f;
-            for (int k = 0; k < cnt; ++k)
-                acc += sc[h * K + k] * VPs[(size_t)k * da + j];
-            o[j] = acc;
-        }
-        __syncthreads();
-        matvec_t(t.T_O, da, da, o, t.b_O, xcat);
-    } else {
-        for (int j = threadIdx.x; j < da; j += kTrThreads) {
-            Qv[j] = 0.0f;
-            o[j] = 0.0f;
-            xcat[j] = 0.0f;
-        }
-        for (int idx = threadIdx.x; idx < H * K; idx += kTrThreads)
-            sc[idx] = 0.0f;
+}
+
+// Scores, softmax and weighted value sum of one query per wavefront, from the projected rows
+// (QV, and KP / VP of its filled slots): lane h * K + k holds slot k of head h.
+__global__ void __launch_bounds__(kTrThreads) k_tr_attn_fwd(StepArgs a, TrainDims d, TrainBufs t)
+{
+    int n_u = *a.qs.n_u;
+    n_u = n_u < 2 * a.count ? n_u : 2 * a.count;
+    const int n_rows = n_u + a.count;
+    const int x = (int)blockIdx.x * kRowWaves + wave_id();
+    if (x >= n_rows)
+        return;
+    const int lane = lane_id();
+    const int K = d.K, H = d.H, da = d.da, dh = d.dh;
+    const int q = x < n_u ? x : 2 * a.count + (x - n_u);
+    int cnt = a.qs.cnt[q];
+    cnt = cnt < 0 ? 0 : (cnt > K ? K : cnt);
+    if (cnt == 0) {
+        for (int j = lane; j < da; j += kWave)
+            t.O_[(size_t)x * da + j] = 0.0f;
+        if (lane < H * K)
+            t.PROB[(size_t)x * H * K + lane] = 0.0f;
+        return;
     }
-    for (int j = threadIdx.x; j < M; j += kTrThreads)
-        xcat[da + j] = s_u[j];
-    __syncthreads();
-    matvec_t(t.T_m1, da + M, E, xcat, t.b_m1, h1);
-    __syncthreads();
-    for (int j = threadIdx.x; j < E; j += kTrThreads)
-        h1[j] = fmaxf(h1[j], 0.0f);
-    __syncthreads();
-    // emb = W_m2 h1 + b_m2 straight to the row of the query set
-    for (int j = threadIdx.x; j < E; j += kTrThreads) {
-        float acc = t.b_m2[j];
-        for (int i = 0; i < E; ++i)
-            acc += t.T_m2[(size_t)i * E + j] * h1[i];
-        a.emb_u[(size_t)q * E + j] = acc;
-        t.H1[(size_t)x * E + j] = h1[j];
-    }
-    for (int j = threadIdx.x; j < da; j += kTrThreads) {
-        t.QV[(size_t)x * da + j] = Qv[j];
-        t.O_[(size_t)x * da + j] = o[j];
-    }
-    for (int j = threadIdx.x; j < da + M; j += kTrThreads)
-        t.X1[(size_t)x * (da + M) + j] = xcat[j];
-    for (int idx = threadIdx.x; idx < H * K; idx += kTrThreads)
-        t.PROB[(size_t)x * H * K + idx] = sc[idx];
-    for (int idx = threadIdx.x; idx < K * da; idx += kTrThreads) {
-        const bool live = idx / da < cnt;
-        t.KP[((size_t)x * K) * da + idx] = live ? KPs[idx] : 0.0f;
-        t.VP[((size_t)x * K) * da + idx] = live ? VPs[idx] : 0.0f;
+    const float *Qv = t.QV + (size_t)x * da;
+    const float scale = 1.0f / sqrtf((float)dh);
+    float sc = -INFINITY;
+    for (int h = 0; h < H; ++h)
+        for (int k = 0; k < cnt; ++k) {
+            const float *kp = t.KP + ((size_t)x * K + k) * da + h * dh;
+            float part = 0.0f;
+            for (int e = lane; e < dh; e += kWave)
+                part += Qv[h * dh + e] * kp[e];
+            const float s2 = wave_sum_uniform(part) * scale;
+            if (lane == h * K + k)
+                sc = s2;
+        }
+    // softmax over the filled slots of the lane's head (every lane walks the head of lane % (H * K))
+    const int hl = (lane % (H * K)) / K;
+    float mx = -INFINITY;
+    for (int k = 0; k < cnt; ++k)
+        mx = fmaxf(mx, __shfl(sc, hl * K + k));
+    const bool mine = lane < H * K && lane - hl * K < cnt;
+    const float ex = mine ? expf(sc - mx) : 0.0f;
+    float sum = 0.0f;
+    for (int k = 0; k < cnt; ++k)
+        sum += __shfl(ex, hl * K + k);
+    const float pr = mine ? ex / sum : 0.0f;
+    if (lane < H * K)
+        t.PROB[(size_t)x * H * K + lane] = pr;
+    for (int j0 = 0; j0 < da; j0 += kWave) {  // (every lane stays in the loop: the shuffles read lanes below H * K)
+        const int j = j0 + lane < da ? j0 + lane : da - 1;
+        const int h = j / dh;
+        float acc = 0.0f;
+        for (int k = 0; k < cnt; ++k)
+            acc += __shfl(pr, h * K + k) * t.VP[((size_t)x * K + k) * da + j];
+        if (j0 + lane < da)
+            t.O_[(size_t)x * da + j] = acc;
     }
 }
 
@@ -383,173 +369,154 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_decoder(StepArgs a, TrainDims
 }
 
 // ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(kTrThreads) k_tr_rows_bwd(StepArgs a, PackedWeights pw, TrainDims d, TrainBufs t)
+// Backward of scores / softmax / weighted sum of one query per wavefront: from the gradient of the
+// heads' outputs (DOUT) to the gradients of the projected query (DQV) and of the projected key /
+// value rows of its filled slots (DKP, DVP).
+__global__ void __launch_bounds__(kTrThreads) k_tr_attn_bwd(StepArgs a, TrainDims d, TrainBufs t)
 {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
     int n_u = *a.qs.n_u;
     n_u = n_u < 2 * a.count ? n_u : 2 * a.count;
     const int n_rows = n_u + a.count;
-    const int x = (int)blockIdx.x;
+    const int x = (int)blockIdx.x * kRowWaves + wave_id();
     if (x >= n_rows)
         return;
-    const int M = d.M, T = d.T, F = d.F, E = d.E, K = d.K, H = d.H, da = d.da, dh = d.dh, dkv = d.dkv;
-    double *dts = (double *)smem;     // [K]
-    int *refs = (int *)(dts + K);     // [K]
-    int *meta = refs + K;             // [2] (+ K + 2 of padding)
-    float *de = (float *)(meta + K + 4);  // [E]
-    float *dz1 = de + E;              // [E]
-    float *dx = dz1 + E;              // [da + M]
-    float *dout = dx + da + M;        // [da]  gradient of the heads' outputs
-    float *Qv = dout + da;            // [da]
-    float *KPs = Qv + da;             // [K x da]
-    float *VPs = KPs + K * da;        // [K x da]
-    float *dKP = VPs + K * da;        // [K x da]
-    float *dVP = dKP + K * da;        // [K x da]
-    float *pr = dVP + K * da;         // [H x K]
-    float *dav = pr + H * K;          // [H x K]
-    float *dsv = dav + H * K;         // [H x K]
-    float *dQv = dsv + H * K;         // [da]
-    float *dqin = dQv + da;           // [da]
-    float *tg = dqin + da;            // [2T]
-
+    const int lane = lane_id();
+    const int K = d.K, H = d.H, da = d.da, dh = d.dh;
     const int q = x < n_u ? x : 2 * a.count + (x - n_u);
-    if (threadIdx.x == 0) {
-        int c = a.qs.cnt[q];
-        meta[0] = c < 0 ? 0 : (c > K ? K : c);
-        meta[1] = a.qs.self_ref[q];
-    }
-    const double t_q = a.qs.t[q];
-    if ((int)threadIdx.x < K) {
-        refs[threadIdx.x] = a.qs.ref[(size_t)q * K + threadIdx.x];
-        dts[threadIdx.x] = t_q - a.qs.ts[(size_t)q * K + threadIdx.x];
-    }
-    for (int j = threadIdx.x; j < E; j += kTrThreads)
-        de[j] = t.D_EMB[(size_t)x * E + j];
-    for (int j = threadIdx.x; j < 2 * T; j += kTrThreads)
-        tg[j] = 0.0f;
-    __syncthreads();
-    const int cnt = meta[0];
-    // merge MLP: dz1 = (W_m2^T d_emb) where z1 > 0;  dx = W_m1^T dz1 = [d_attn | d s_u]
-    for (int i = threadIdx.x; i < E; i += kTrThreads) {
-        float acc = 0.0f;
-        for (int o2 = 0; o2 < E; ++o2)
-            acc += t.W_m2[(size_t)o2 * E + i] * de[o2];
-        const float v = t.H1[(size_t)x * E + i] > 0.0f ? acc : 0.0f;
-        dz1[i] = v;
-        t.DZ1[(size_t)x * E + i] = v;
-    }
-    __syncthreads();
-    matvec_n(t.W_m1, E, da + M, dz1, dx);
-    __syncthreads();
-    for (int j = threadIdx.x; j < da; j += kTrThreads)
-        t.D_ATTN[(size_t)x * da + j] = cnt > 0 ? dx[j] : 0.0f;  // no neighbours: attn is the constant 0
-    if (cnt > 0) {
-        matvec_n(t.W_O, da, da, dx, dout);
-        for (int j = threadIdx.x; j < da; j += kTrThreads)
-            Qv[j] = t.QV[(size_t)x * da + j];
-        for (int idx = threadIdx.x; idx < cnt * da; idx += kTrThreads) {
-            KPs[idx] = t.KP[((size_t)x * K) * da + idx];
-            VPs[idx] = t.VP[((size_t)x * K) * da + idx];
-        }
-        for (int idx = threadIdx.x; idx < H * K; idx += kTrThreads)
-            pr[idx] = t.PROB[(size_t)x * H * K + idx];
-        __syncthreads();
-        for (int idx = threadIdx.x; idx < H * cnt; idx += kTrThreads) {
-            const int h = idx / cnt, k = idx - h * cnt;
-            float s = 0.0f;
-            for (int e = 0; e < dh; ++e)
-                s += VPs[(size_t)k * da + h * dh + e] * dout[h * dh + e];
-            dav[h * K + k] = s;
-        }
-        __syncthreads();
-        for (int idx = threadIdx.x; idx < H * cnt; idx += kTrThreads) {
-            const int h = idx / cnt, k = idx - h * cnt;
-            float dot = 0.0f;
-            for (int k2 = 0; k2 < cnt; ++k2)
-                dot += pr[h * K + k2] * dav[h * K + k2];
-            dsv[h * K + k] = pr[h * K + k] * (dav[h * K + k] - dot);
-        }
-        __syncthreads();
-        const float scale = 1.0f / sqrtf((float)dh);
-        for (int j = threadIdx.x; j < da; j += kTrThreads) {
-            const int h = j / dh;
-            float acc = 0.0f;
-            for (int k = 0; k < cnt; ++k) {
-                acc += dsv[h * K + k] * KPs[(size_t)k * da + j];
-                dKP[(size_t)k * da + j] = dsv[h * K + k] * Qv[j] * scale;
-                dVP[(size_t)k * da + j] = pr[h * K + k] * dout[j];
-            }
-            dQv[j] = acc * scale;
-        }
-        __syncthreads();
-        matvec_n(t.W_Q, da, da, dQv, dqin);
-        __syncthreads();
-        // Phi(0)_j = cos(b_j): only the phase takes a gradient from the query row
-        for (int j = threadIdx.x; j < T; j += kTrThreads)
-            tg[T + j] += -time_enc_sin(pw.time_w_rev[j], pw.time_b_rev[j], 0.0) * dqin[M + j];
-        __syncthreads();
-        // d kv[k][i] = sum_o W_K[o][i] dKP[k][o] + W_V[o][i] dVP[k][o]; the thread that owns column i
-        // sends the state part to the staged rows and keeps the time-encoding part
-        for (int i = threadIdx.x; i < dkv; i += kTrThreads) {
-            if (i >= M && i < M + F)
-                continue;  // edge features are constants
-            float gw = 0.0f, gb = 0.0f;
-            for (int k0 = 0; k0 < cnt; k0 += kKC) {
-                float acc[kKC];
-#pragma unroll
-                for (int u = 0; u < kKC; ++u)
-                    acc[u] = 0.0f;
-                for (int o2 = 0; o2 < da; ++o2) {
-                    const float wk = t.W_K[(size_t)o2 * dkv + i], wv = t.W_V[(size_t)o2 * dkv + i];
-#pragma unroll
-                    for (int u = 0; u < kKC; ++u) {
-                        const int k = k0 + u < cnt ? k0 + u : k0;
-                        acc[u] += wk * dKP[(size_t)k * da + o2] + wv * dVP[(size_t)k * da + o2];
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < kKC; ++u) {
-                    const int k = k0 + u;
-                    if (k >= cnt)
-                        continue;
-                    if (i < M) {
-                        const int32_t rf = refs[k];
-                        if (rf < 0 && rf != kRefNone && ~rf < 2 * a.msg_count)
-                            atomicAdd(&t.D_STAG[(size_t)(~rf) * M + i], acc[u]);
-                    } else {
-                        const int j = i - M - F;
-                        const float sn = time_enc_sin(pw.time_w_rev[j], pw.time_b_rev[j], dts[k]);
-                        gw += -sn * (float)dts[k] * acc[u];
-                        gb += -sn * acc[u];
-                    }
-                }
-            }
-            if (i >= M + F) {
-                tg[i - M - F] += gw;
-                tg[T + i - M - F] += gb;
-            }
-        }
-        for (int j = threadIdx.x; j < da; j += kTrThreads)
-            t.DQV[(size_t)x * da + j] = dQv[j];
-    } else {
-        for (int j = threadIdx.x; j < da; j += kTrThreads) {
+    int cnt = a.qs.cnt[q];
+    cnt = cnt < 0 ? 0 : (cnt > K ? K : cnt);
+    if (cnt == 0) {
+        for (int j = lane; j < da; j += kWave)
             t.DQV[(size_t)x * da + j] = 0.0f;
-            dqin[j] = 0.0f;
+        return;
+    }
+    const float *dout = t.DOUT + (size_t)x * da;
+    const float *Qv = t.QV + (size_t)x * da;
+    const float scale = 1.0f / sqrtf((float)dh);
+    float dav = 0.0f;  // lane h * K + k: <VP[k] of head h, dout of head h>
+    for (int h = 0; h < H; ++h)
+        for (int k = 0; k < cnt; ++k) {
+            const float *vp = t.VP + ((size_t)x * K + k) * da + h * dh;
+            float part = 0.0f;
+            for (int e = lane; e < dh; e += kWave)
+                part += vp[e] * dout[h * dh + e];
+            const float s2 = wave_sum_uniform(part);
+            if (lane == h * K + k)
+                dav = s2;
+        }
+    const float pr = lane < H * K ? t.PROB[(size_t)x * H * K + lane] : 0.0f;  // (zero beyond the filled slots)
+    const int hl = (lane % (H * K)) / K;
+    float dot = 0.0f;
+    for (int k = 0; k < cnt; ++k)
+        dot += __shfl(pr, hl * K + k) * __shfl(dav, hl * K + k);
+    const float dsv = pr * (dav - dot);
+    for (int j0 = 0; j0 < da; j0 += kWave) {  // (every lane stays in the loop: the shuffles read lanes below H * K)
+        const bool in = j0 + lane < da;
+        const int j = in ? j0 + lane : da - 1;
+        const int h = j / dh;
+        const float qv = Qv[j], dj = dout[j];
+        float acc = 0.0f;
+        for (int k = 0; k < cnt; ++k) {
+            const float ds = __shfl(dsv, h * K + k), pk = __shfl(pr, h * K + k);
+            const size_t o = ((size_t)x * K + k) * da + j;
+            acc += ds * t.KP[o];
+            if (in) {
+                t.DKP[o] = ds * qv * scale;
+                t.DVP[o] = pk * dj;
+            }
+        }
+        if (in)
+            t.DQV[(size_t)x * da + j] = acc * scale;
+    }
+}
+
+// What is left of a query's backward pass after the matrix products, one wavefront per query: the
+// gradients w.r.t. state rows that this step's GRU wrote (own row: from the merge layer and the
+// query projection; neighbour rows: from the key / value rows) are added to those staged rows'
+// gradients; the time-encoding partial sums [gw | gb] of the row are written out.
+// A hub node's staged row is a neighbour of most queries of a batch: its thousands of row additions
+// would queue up on the same addresses.  A workgroup therefore collects the additions of its
+// kScatterRows queries in an LDS table of kScatterSlots rows (direct-mapped by staged row; a row
+// whose place is taken goes to memory directly) and adds every table row to memory once.
+constexpr int kScatterRows = 64, kScatterSlots = 64, kTrScatterThreads = 1024;
+
+__global__ void __launch_bounds__(kTrScatterThreads) k_tr_scatter(StepArgs a, PackedWeights pw, TrainDims d, TrainBufs t)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int M = d.M, T = d.T, F = d.F, K = d.K, da = d.da, dkv = d.dkv;
+    int *tag = (int *)smem;                        // [slots] staged row held by the slot, -1: none
+    float *acc = (float *)(tag + kScatterSlots);   // [slots x M]
+    for (int i = threadIdx.x; i < kScatterSlots; i += kTrScatterThreads)
+        tag[i] = -1;
+    for (int i = threadIdx.x; i < kScatterSlots * M; i += kTrScatterThreads)
+        acc[i] = 0.0f;
+    __syncthreads();
+    int n_u = *a.qs.n_u;
+    n_u = n_u < 2 * a.count ? n_u : 2 * a.count;
+    const int n_rows = n_u + a.count;
+    const int lane = lane_id();
+    const int x_end = ((int)blockIdx.x + 1) * kScatterRows < n_rows ? ((int)blockIdx.x + 1) * kScatterRows : n_rows;
+    for (int x = (int)blockIdx.x * kScatterRows + wave_id(); x < x_end; x += kTrScatterThreads / kWave) {
+        const int q = x < n_u ? x : 2 * a.count + (x - n_u);
+        int cnt = a.qs.cnt[q];
+        cnt = cnt < 0 ? 0 : (cnt > K ? K : cnt);
+        const double t_q = a.qs.t[q];
+        // lane k < cnt: neighbour slot k, lane cnt: the query's own row.  Each claims the table row of
+        // its staged row (or finds it claimed by another staged row: then the additions go to memory).
+        int my_srow = -1, my_lds = 0;
+        double my_dt = 0.0;
+        if (lane <= cnt) {
+            const int32_t rf = lane < cnt ? a.qs.ref[(size_t)q * K + lane] : a.qs.self_ref[q];
+            if (lane < cnt)
+                my_dt = t_q - a.qs.ts[(size_t)q * K + lane];
+            if (rf < 0 && rf != kRefNone && ~rf < 2 * a.msg_count) {
+                my_srow = ~rf;
+                const int old = atomicCAS(&tag[my_srow & (kScatterSlots - 1)], -1, my_srow);
+                my_lds = old == -1 || old == my_srow;
+            }
+        }
+        const int n_el = (cnt + 1) * M;
+#pragma unroll 4
+        for (int e0 = 0; e0 < n_el; e0 += kWave) {  // (every lane stays in the loop: the shuffles read lanes up to cnt)
+            const bool in = e0 + lane < n_el;
+            const int e = in ? e0 + lane : 0;
+            const int k = e / M, i = e - k * M;
+            const int srow = __shfl(my_srow, k), lds = __shfl(my_lds, k);
+            if (in && srow >= 0) {
+                float v;
+                if (k < cnt)
+                    v = t.DKV[((size_t)x * K + k) * dkv + i];
+                else
+                    v = t.DSU[(size_t)x * M + i] + (cnt > 0 ? t.DQIN[(size_t)x * da + i] : 0.0f);
+                atomicAdd(lds ? &acc[(size_t)(srow & (kScatterSlots - 1)) * M + i] : &t.D_STAG[(size_t)srow * M + i], v);
+            }
+        }
+        for (int j0 = 0; j0 < T; j0 += kWave) {
+            const bool in = j0 + lane < T;
+            const int j = in ? j0 + lane : 0;
+            float gw = 0.0f, gb = 0.0f;
+            if (cnt > 0)  // Phi(0)_j = cos(b_j): only the phase takes a gradient from the query row
+                gb += -time_enc_sin(pw.time_w_rev[j], pw.time_b_rev[j], 0.0) * t.DQIN[(size_t)x * da + M + j];
+#pragma unroll 4
+            for (int k = 0; k < cnt; ++k) {
+                const double dt = shfl_f64(my_dt, k);
+                const float g = t.DKV[((size_t)x * K + k) * dkv + M + F + j];
+                const float sn = time_enc_sin(pw.time_w_rev[j], pw.time_b_rev[j], dt);
+                gw += -sn * (float)dt * g;
+                gb += -sn * g;
+            }
+            if (in) {
+                t.TG[(size_t)x * 2 * T + j] = gw;
+                t.TG[(size_t)x * 2 * T + T + j] = gb;
+            }
         }
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < K * da; idx += kTrThreads) {
-        const bool live = idx / da < cnt;
-        t.DKP[((size_t)x * K) * da + idx] = live ? dKP[idx] : 0.0f;
-        t.DVP[((size_t)x * K) * da + idx] = live ? dVP[idx] : 0.0f;
+    for (int i = threadIdx.x; i < kScatterSlots * M; i += kTrScatterThreads) {
+        const int srow = tag[i / M];
+        if (srow >= 0 && srow < 2 * a.msg_count)
+            atomicAdd(&t.D_STAG[(size_t)srow * M + (i % M)], acc[i]);
     }
-    // own state row: from the merge layer and (with neighbours) from the query projection
-    const int32_t sr = meta[1];
-    if (sr < 0 && sr != kRefNone && ~sr < 2 * a.msg_count)
-        for (int i = threadIdx.x; i < M; i += kTrThreads)
-            atomicAdd(&t.D_STAG[(size_t)(~sr) * M + i], dx[da + i] + dqin[i]);
-    for (int j = threadIdx.x; j < 2 * T; j += kTrThreads)
-        t.TG[(size_t)x * 2 * T + j] = tg[j];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -636,28 +603,36 @@ __device__ inline int row_count(const RowCount &rc)
     return r < 0 ? 0 : (r < rc.rows_max ? (int)r : rc.rows_max);
 }
 
-// C[Mo x No] += A[rows x Mo]^T B[rows x No]; one wavefront per 32 x 32 block of C and slice of the rows.
+// C[Mo x No] += A[rows x Mo]^T B[rows x No].  A workgroup of eight wavefronts takes one 32 x 32 block
+// of C and one slice of the rows; the wavefronts split the slice, add their blocks up in LDS, and
+// the workgroup adds the result to C with one atomic per element (the atomics, not the products, bound
+// these contractions: few of them).
 // csum != NULL: also csum[Mo] += the column sums of A (the bias gradient that goes with the weight
-// gradient: A^T times a column of ones), by the wavefronts of the first block column.
+// gradient: A^T times a column of ones), by the workgroups of the first block column.
 // ridx != NULL: the contraction runs over the rows ridx[0 .. rows) of A and B (each below ridx_max).
-__global__ void __launch_bounds__(256) k_gemm_tn(float *C, int ldc, const float *A, int lda, const float *B, int ldb,
-                                                 int Mo, int No, RowCount rc, int n_slices, float *csum, const int32_t *ridx,
-                                                 int ridx_max)
+constexpr int kTnWaves = 8;
+__global__ void __launch_bounds__(kTnWaves *kWave) k_gemm_tn(float *C, int ldc, const float *A, int lda, const float *B, int ldb,
+                                                              int Mo, int No, RowCount rc, int n_slices, float *csum,
+                                                              const int32_t *ridx, int ridx_max)
 {
-    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+    __shared__ float red[kTnWaves][1024];
+    __shared__ float reds[kTnWaves][32];
+    const int w = threadIdx.x / kWave;
     const int lane = threadIdx.x & (kWave - 1);
     const int tiles_n = (No + 31) / 32, tiles_m = (Mo + 31) / 32;
-    const int slice = wave % n_slices;
-    const int tile = wave / n_slices;
+    const int slice = (int)blockIdx.x % n_slices;
+    const int tile = (int)blockIdx.x / n_slices;
     if (tile >= tiles_m * tiles_n)
         return;
     const int m0 = (tile / tiles_n) * 32, n0 = (tile % tiles_n) * 32;
     const int rows = row_count(rc);
-    const int per = ((rows + n_slices - 1) / n_slices + 3) / 4 * 4;
-    const int k_lo = slice * per, k_hi = k_lo + per < rows ? k_lo + per : rows;
-    if (k_lo >= k_hi)
-        return;
-    const bool with_sum = csum != nullptr && n0 == 0;  // (uniform over the wavefront)
+    const int per = (rows + n_slices - 1) / n_slices;
+    const int s_lo = slice * per, s_hi = s_lo + per < rows ? s_lo + per : rows;
+    if (s_lo >= s_hi)
+        return;  // (uniform over the workgroup)
+    const int sub = ((s_hi - s_lo + kTnWaves - 1) / kTnWaves + 3) / 4 * 4;
+    const int k_lo = s_lo + w * sub, k_hi = k_lo + sub < s_hi ? k_lo + sub : s_hi;
+    const bool with_sum = csum != nullptr && n0 == 0;  // (uniform over the workgroup)
     floatx4 acc[2][2], accs[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -698,24 +673,185 @@ __global__ void __launch_bounds__(256) k_gemm_tn(float *C, int ldc, const float 
             }
         }
     }
+    // element ((i * 2 + j) * 4 + v) * 64 + lane of a wavefront's block is C[m0 + 16 i + 4 g + v][n0 + 16 j + c]
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int mm = m0 + 16 * i + 4 * g + v, nn = n0 + 16 * j + c;
-                if (mm < Mo && nn < No)
-                    atomicAdd(&C[(size_t)mm * ldc + nn], acc[i][j][v]);
+            for (int v = 0; v < 4; ++v)
+                red[w][((i * 2 + j) * 4 + v) * kWave + lane] = acc[i][j][v];
+    if (c == 0) {  // every column of the sum block holds the same value: column 0 keeps it
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                reds[w][16 * i + 4 * g + v] = accs[i][v];
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < 1024; e += kTnWaves * kWave) {
+        float sum = 0.0f;
+#pragma unroll
+        for (int ww = 0; ww < kTnWaves; ++ww)
+            sum += red[ww][e];
+        const int l = e & (kWave - 1), v = (e / kWave) & 3, j = (e / (4 * kWave)) & 1, i = e / (8 * kWave);
+        const int mm = m0 + 16 * i + 4 * (l >> 4) + v, nn = n0 + 16 * j + (l & 15);
+        if (mm < Mo && nn < No)
+            atomicAdd(&C[(size_t)mm * ldc + nn], sum);
+    }
+    if (with_sum && threadIdx.x < 32) {
+        float sum = 0.0f;
+#pragma unroll
+        for (int ww = 0; ww < kTnWaves; ++ww)
+            sum += reds[ww][threadIdx.x];
+        if (m0 + (int)threadIdx.x < Mo)
+            atomicAdd(&csum[m0 + threadIdx.x], sum);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// A layer product over all rows at once: C[r][n] = f(sum_k A[r][k] W[n][k] (+ sum_k A2[r][k] W2[n][k]) + bias[n])
+// on the matrix cores (fp32 16x16x4).  A and W are both k-contiguous: a forward product takes the
+// weight matrix as stored ([out x in]), a backward product dX = dY W its transposed copy
+// ([in x out]).  A workgroup takes 32 rows; each of its four wavefronts one block of 32 columns
+// (blockIdx.y counts groups of four column blocks).  A lane loads four consecutive k of its row per step (k = k0 + 4 g + v
+// for lane group g: the four groups cover 16 k, and the v-th products of a step pair the same k in
+// both operands).
+struct RowGemm {
+    const float *A, *W, *A2, *W2, *bias;
+    float *C;
+    int lda, ldw, lda2, ldw2, ldc;
+    int N, Kd, Kd2;
+    RowCount rc;
+    const int32_t *ridx;     // NULL, or: logical row r is row ridx[r] (< ridx_max) of A, A2 and C
+    int ridx_max;
+    int relu;                // f = max(., 0)
+    const float *gate;       // NULL, or: the result is kept where gate[row][n] > 0, else 0
+    int ldg;
+    const int32_t *rowmask;  // NULL, or: rows with rowmask[row] == 0 give 0 (no bias)
+    const int32_t *remap_nu; // NULL, or: output row of r is r below min(*remap_nu, remap_2b), else remap_2b + (r - that)
+    int remap_2b;
+    int vecA, vecW, vecA2, vecW2;  // operand rows are 16-byte aligned: four k in one load
+};
+
+__device__ inline floatx4 load_k4(const float *row, int k, int Kd, bool ok, int vec)
+{
+    floatx4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (!ok)
+        return v;
+    if (vec && k + 3 < Kd)
+        return *(const floatx4 *)(row + k);
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        if (k + u < Kd)
+            v[u] = row[k + u];
+    return v;
+}
+
+__global__ void __launch_bounds__(256) k_rowgemm(RowGemm p)
+{
+    const int rows = row_count(p.rc);
+    const int r0 = (int)blockIdx.x * 32;
+    if (r0 >= rows)
+        return;
+    const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+    const int c = lane & 15, g = lane >> 4;
+    // the two rows whose operand this lane loads (rows r0 + c and r0 + 16 + c)
+    size_t arow[2];
+    bool aok[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int r = r0 + 16 * i + c;
+        bool ok = r < rows;
+        int pr = r;
+        if (p.ridx) {
+            pr = ok ? p.ridx[r] : 0;
+            ok = ok && pr >= 0 && pr < p.ridx_max;
+        }
+        arow[i] = (size_t)(ok ? pr : 0);
+        aok[i] = ok;
+    }
+    const int tiles_n = (p.N + 31) / 32;
+    const int tn = (int)blockIdx.y * 4 + w;  // this wavefront's block of 32 columns
+    if (tn >= tiles_n)
+        return;
+    {
+        const int n0 = tn * 32;
+        floatx4 acc[2][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[i][j] = floatx4{0, 0, 0, 0};
+        for (int pass = 0; pass < (p.A2 ? 2 : 1); ++pass) {
+            const float *A = pass ? p.A2 : p.A, *W = pass ? p.W2 : p.W;
+            const int lda = pass ? p.lda2 : p.lda, ldw = pass ? p.ldw2 : p.ldw, Kd = pass ? p.Kd2 : p.Kd;
+            const int vA = pass ? p.vecA2 : p.vecA, vW = pass ? p.vecW2 : p.vecW;
+            const float *ar[2] = {A + arow[0] * lda, A + arow[1] * lda};
+            const int nn0 = n0 + c, nn1 = n0 + 16 + c;
+            const bool wok[2] = {nn0 < p.N, nn1 < p.N};
+            const float *wr[2] = {W + (size_t)(wok[0] ? nn0 : 0) * ldw, W + (size_t)(wok[1] ? nn1 : 0) * ldw};
+            constexpr int kU = 4;  // steps of 16 k whose loads are issued together
+            for (int k0 = 0; k0 < Kd; k0 += 16 * kU) {
+                floatx4 av[kU][2], wv[kU][2];
+#pragma unroll
+                for (int u = 0; u < kU; ++u) {
+                    const int kk = k0 + 16 * u + 4 * g;
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        av[u][i] = load_k4(ar[i], kk, Kd, aok[i], vA);
+                        wv[u][i] = load_k4(wr[i], kk, Kd, wok[i], vW);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < kU; ++u) {
+                    if (k0 + 16 * u >= Kd)
+                        break;  // (uniform: nothing but zeros was loaded for this step)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+#pragma unroll
+                        for (int i = 0; i < 2; ++i)
+#pragma unroll
+                            for (int j = 0; j < 2; ++j)
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][i][v], wv[u][j][v], acc[i][j], 0, 0, 0);
+                }
             }
-    if (with_sum && c == 0) {  // every column of the sum block holds the same value: column 0 adds it
+        }
+        int nu = 0;
+        if (p.remap_nu) {
+            nu = *p.remap_nu;
+            nu = nu < 0 ? 0 : (nu < p.remap_2b ? nu : p.remap_2b);
+        }
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int mm = m0 + 16 * i + 4 * g + v;
-                if (mm < Mo)
-                    atomicAdd(&csum[mm], accs[i][v]);
+                const int r = r0 + 16 * i + 4 * g + v;
+                if (r >= rows)
+                    continue;
+                int orow = r;
+                if (p.ridx) {
+                    orow = p.ridx[r];
+                    if (orow < 0 || orow >= p.ridx_max)
+                        continue;
+                }
+                const bool dead = p.rowmask && p.rowmask[orow] == 0;
+                if (p.remap_nu)
+                    orow = r < nu ? r : p.remap_2b + (r - nu);
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int n = n0 + 16 * j + c;
+                    if (n >= p.N)
+                        continue;
+                    float val = acc[i][j][v] + (p.bias ? p.bias[n] : 0.0f);
+                    if (p.relu)
+                        val = fmaxf(val, 0.0f);
+                    if (p.gate && !(p.gate[(size_t)orow * p.ldg + n] > 0.0f))
+                        val = 0.0f;
+                    if (dead)
+                        val = 0.0f;
+                    p.C[(size_t)orow * p.ldc + n] = val;
+                }
             }
     }
 }
@@ -869,11 +1005,16 @@ static TrainLayout train_layout(const Dims &d, void *base)
     b.D_ATTN = take(R * da);
     b.DQV = take(R * da);
     b.TG = take(R * 2 * T);
+    b.DOUT = take(R * da);
+    b.DSU = take(R * M);
+    b.DQIN = take(R * da);
+    b.HAS = (int32_t *)take(R);
     b.KV = take(S * dkv);
     b.KP = take(S * da);
     b.VP = take(S * da);
     b.DKP = take(S * da);
     b.DVP = take(S * da);
+    b.DKV = take(S * dkv);
     b.CAT = take(U * 2 * E);
     b.DY = take(U * E);
     b.G_ = take(U * E);
@@ -897,28 +1038,15 @@ static TrainLayout train_layout(const Dims &d, void *base)
     return L;
 }
 
-static int fwd_lds(const Dims &d)
-{
-    // doubles [K], ints [2K + 4], floats: s_u, q_in, Qv, kv, KP, VP, sc, o, xcat, h1
-    return 8 * d.K + 4 * (2 * d.K + 4) +
-           4 * (d.M + 2 * d.da + d.K * d.dkv + 2 * d.K * d.da + d.H * d.K + d.da + d.da + d.M + d.E) + 64;
-}
-static int bwd_lds(const Dims &d)
-{
-    // doubles [K], ints [2K + 4], floats: de, dz1, dx, dout, Qv, KP, VP, dKP, dVP, pr, dav, dsv, dQv, dqin, tg
-    return 8 * d.K + 4 * (2 * d.K + 4) +
-           4 * (2 * d.E + d.da + d.M + 2 * d.da + 4 * d.K * d.da + 3 * d.H * d.K + 2 * d.da + 2 * d.T) + 64;
-}
 static int gru_bwd_lds(const Dims &d) { return 4 * (d.Dmsg + 12 * d.M); }
+static int scatter_lds(const Dims &d) { return 4 * kScatterSlots * (d.M + 1); }
 static int dec_lds(const Dims &d) { return 4 * (5 * d.E + 8); }
 
 size_t train_workspace_bytes(const Dims &d) { return train_layout(d, nullptr).bytes; }
 
 hipError_t prepare_train(const Dims &d)
 {
-    hipError_t e = hipFuncSetAttribute((const void *)k_tr_rows_fwd, hipFuncAttributeMaxDynamicSharedMemorySize, fwd_lds(d));
-    if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void *)k_tr_rows_bwd, hipFuncAttributeMaxDynamicSharedMemorySize, bwd_lds(d));
+    hipError_t e = hipFuncSetAttribute((const void *)k_tr_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, scatter_lds(d));
     if (e == hipSuccess)
         e = hipFuncSetAttribute((const void *)k_tr_gru_bwd, hipFuncAttributeMaxDynamicSharedMemorySize, gru_bwd_lds(d));
     if (e == hipSuccess)
@@ -928,8 +1056,8 @@ hipError_t prepare_train(const Dims &d)
 
 bool train_supported(const Dims &d)
 {
-    return d.prec == TIG_FP32 && fwd_lds(d) <= 160 * 1024 && bwd_lds(d) <= 160 * 1024 && gru_bwd_lds(d) <= 160 * 1024 &&
-           d.K <= kTrThreads;
+    // (the attention kernels keep slot k of head h in lane h * K + k of a query's wavefront)
+    return d.prec == TIG_FP32 && gru_bwd_lds(d) <= 160 * 1024 && scatter_lds(d) <= 64 * 1024 && d.H * d.K <= kWave;
 }
 
 static hipError_t transpose_all(const Dims &d, const TrainLayout &L, hipStream_t s)
@@ -1013,29 +1141,86 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
     if (e != hipSuccess)
         return e;
     const int B = a.count, R = 3 * B, K = d.K;
-    hipLaunchKernelGGL(k_tr_rows_fwd, dim3(R), dim3(kTrThreads), fwd_lds(d), s, a, pwv, td, b);
+    const int M = d.M, T = d.T, E = d.E, da = d.da, dkv = d.dkv, D = d.Dmsg;
+    const RowCount rows{b.n_rows, 0, 1, R}, live{b.n_live, 0, 1, R * K}, pairs{nullptr, 0, 1, 2 * B},
+        wins{a.n_win, 0, 1, 2 * a.msg_count};
+    // one layer product over all rows (or over the filled slots: `slots`)
+    auto vec_ok = [](const float *p, int ld) { return (((uintptr_t)p & 15) == 0 && ld % 4 == 0) ? 1 : 0; };
+    auto layer = [&](float *C, int ldc, const float *A, int lda, const float *W, int ldw, const float *bias, int N, int Kd,
+                     bool slots = false) {
+        RowGemm g = {};
+        g.A = A, g.lda = lda, g.W = W, g.ldw = ldw, g.bias = bias, g.C = C, g.ldc = ldc, g.N = N, g.Kd = Kd;
+        g.rc = slots ? live : rows;
+        if (slots)
+            g.ridx = b.live, g.ridx_max = R * K;
+        g.vecA = vec_ok(A, lda), g.vecW = vec_ok(W, ldw);
+        return g;
+    };
+    auto run = [&](const RowGemm &g) {
+        hipLaunchKernelGGL(k_rowgemm, dim3((g.rc.rows_max + 31) / 32, ((g.N + 31) / 32 + 3) / 4), dim3(256), 0, s, g);
+    };
+    const dim3 per_row((R + kRowWaves - 1) / kRowWaves);
+    // ---- forward, direct form
+    hipLaunchKernelGGL(k_tr_gather, per_row, dim3(kTrThreads), 0, s, a, pwv, td, b);
+    run(layer(b.QV, da, b.QIN, da, b.W_Q, da, b.b_Q, da, da));
+    run(layer(b.KP, da, b.KV, dkv, b.W_K, dkv, b.b_K, da, dkv, true));
+    run(layer(b.VP, da, b.KV, dkv, b.W_V, dkv, b.b_V, da, dkv, true));
+    hipLaunchKernelGGL(k_tr_attn_fwd, per_row, dim3(kTrThreads), 0, s, a, td, b);
+    {   // attn = W_O o + b_O into the head of the merge layer's input; the zero vector without neighbours
+        RowGemm g = layer(b.X1, da + M, b.O_, da, b.W_O, da, b.b_O, da, da);
+        g.rowmask = b.HAS;
+        run(g);
+    }
+    {
+        RowGemm g = layer(b.H1, E, b.X1, da + M, b.W_m1, da + M, b.b_m1, E, da + M);
+        g.relu = 1;
+        run(g);
+    }
+    {   // emb = W_m2 h1 + b_m2 straight to the rows of the query set
+        RowGemm g = layer(a.emb_u, E, b.H1, E, b.W_m2, E, b.b_m2, E, E);
+        g.remap_nu = a.qs.n_u, g.remap_2b = 2 * B;
+        run(g);
+    }
     hipLaunchKernelGGL(k_tr_decoder, dim3(B), dim3(kTrThreads), dec_lds(d), s, a, td, b);
-    hipLaunchKernelGGL(k_tr_rows_bwd, dim3(R), dim3(kTrThreads), bwd_lds(d), s, a, pwv, td, b);
+    // ---- backward: dX = dY W through the transposed copies
+    {   // dz1 = (W_m2^T d_emb) where z1 > 0
+        RowGemm g = layer(b.DZ1, E, b.D_EMB, E, b.T_m2, E, nullptr, E, E);
+        g.gate = b.H1, g.ldg = E;
+        run(g);
+    }
+    {   // [d_attn | d s_u] = W_m1^T dz1; without neighbours attn is the constant 0
+        RowGemm g = layer(b.D_ATTN, da, b.DZ1, E, b.T_m1, E, nullptr, da, E);
+        g.rowmask = b.HAS;
+        run(g);
+        run(layer(b.DSU, M, b.DZ1, E, b.T_m1 + (size_t)da * E, E, nullptr, M, E));
+    }
+    run(layer(b.DOUT, da, b.D_ATTN, da, b.T_O, da, nullptr, da, da));
+    hipLaunchKernelGGL(k_tr_attn_bwd, per_row, dim3(kTrThreads), 0, s, a, td, b);
+    run(layer(b.DQIN, da, b.DQV, da, b.T_Q, da, nullptr, da, da));
+    {   // d kv = W_K^T dKP + W_V^T dVP over the filled slots
+        RowGemm g = layer(b.DKV, dkv, b.DKP, da, b.T_K, da, nullptr, dkv, da, true);
+        g.A2 = b.DVP, g.lda2 = da, g.W2 = b.T_V, g.ldw2 = da, g.Kd2 = da;
+        g.vecA2 = vec_ok(b.DVP, da), g.vecW2 = vec_ok(b.T_V, da);
+        run(g);
+    }
+    hipLaunchKernelGGL(k_tr_scatter, dim3((R + kScatterRows - 1) / kScatterRows), dim3(kTrScatterThreads), scatter_lds(d), s, a,
+                       pwv, td, b);
     if (a.msg_count > 0)
         hipLaunchKernelGGL(k_tr_gru_bwd, dim3(2 * a.msg_count), dim3(kTrThreads), gru_bwd_lds(d), s, a, pwv, td, b);
     if ((e = hipGetLastError()) != hipSuccess)
         return e;
 
-    const RowCount rows{b.n_rows, 0, 1, R}, live{b.n_live, 0, 1, R * K}, pairs{nullptr, 0, 1, 2 * B},
-        wins{a.n_win, 0, 1, 2 * a.msg_count};
     // weight gradient C += A^T B together with the bias gradient csum += column sums of A
     auto gemm = [&](const float *C, const float *csum, int Mo, int No, const float *A, const float *Bm, const RowCount &rc,
                     int ldb = 0, const int32_t *ridx = nullptr, int ridx_max = 0) {
         const int tiles = ((Mo + 31) / 32) * ((No + 31) / 32);
-        // about 3072 wavefronts per contraction: every slice ends in one atomic add per element of its
-        // block, so few slices; a slice keeps at least 64 rows
-        int n_slices = 3072 / tiles;
-        const int most = rc.rows_max / 64;
+        // about 512 workgroups of eight wavefronts per contraction; a wavefront keeps at least 32 rows
+        int n_slices = 512 / tiles;
+        const int most = rc.rows_max / (32 * kTnWaves);
         n_slices = n_slices > most ? most : n_slices;
         n_slices = n_slices < 1 ? 1 : n_slices;
-        const int waves = tiles * n_slices;
-        hipLaunchKernelGGL(k_gemm_tn, dim3((waves + 3) / 4), dim3(256), 0, s, (float *)C, No, A, Mo, Bm, ldb ? ldb : No, Mo, No,
-                           rc, n_slices, (float *)csum, ridx, ridx_max);
+        hipLaunchKernelGGL(k_gemm_tn, dim3(tiles * n_slices), dim3(kTnWaves * kWave), 0, s, (float *)C, No, A, Mo, Bm,
+                           ldb ? ldb : No, Mo, No, rc, n_slices, (float *)csum, ridx, ridx_max);
     };
     auto colsum = [&](const float *out, const float *A, int lda, int cols, const RowCount &rc) {
         int n_slices = rc.rows_max / 512;
@@ -1043,7 +1228,6 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
         hipLaunchKernelGGL(k_colsum, dim3((cols + 255) / 256, n_slices), dim3(256), 0, s, (float *)out, A, lda, cols, rc,
                            n_slices);
     };
-    const int M = d.M, T = d.T, E = d.E, da = d.da, dkv = d.dkv, D = d.Dmsg;
     // decoder
     gemm(L.g.W_d1, L.g.b_d1, E, 2 * E, b.DY, b.CAT, pairs);
     gemm(L.g.w_d2, L.g.b_d2, 1, E, b.DLOGIT, b.G_, pairs);
