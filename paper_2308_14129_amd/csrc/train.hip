@@ -120,15 +120,15 @@ struct TrainBufs {
     float *QIN, *QV, *O_, *PROB, *X1, *H1, *D_EMB, *DZ1, *D_ATTN, *DQV, *TG;
     float *DOUT, *DSU, *DQIN;  // gradients of the heads' outputs [da], of the own state through the merge layer [M], of the query row [da]
     int32_t *HAS;              // 1 for a query with at least one filled neighbour slot
-    // per neighbour slot (row x * K + k)
+    // per filled neighbour slot: slot k of query x is row slot0[x] + k (the filled slots of a step are packed)
     float *KV, *KP, *VP, *DKP, *DVP, *DKV;
     // per (pair, event): pair 0 = (source, destination), pair 1 = (source, negative); row p * count + b
     float *CAT, *DY, *G_, *DLOGIT, *LOSS;
     // per applied winner r, and per entry of the applied batch
     float *MSG, *DGI, *DGH, *TGG, *D_STAG;
     int32_t *n_rows;  // [1] distinct queries of the step (written by the forward kernel's block 0)
-    int32_t *live;    // [3B x K] the filled neighbour slots (row x * K + k) of the step, in no particular order
-    int32_t *n_live;  // [1] their number (cleared with the gradients)
+    int32_t *slot0;   // [3B] first row of a query's filled slots in the per-slot matrices
+    int32_t *n_live;  // [1] filled slots of the step (cleared with the gradients)
 };
 
 // compact row of query-set row q
@@ -143,6 +143,15 @@ __device__ inline double shfl_f64(double v, int src)
     lo = __shfl(lo, src);
     hi = __shfl(hi, src);
     return __hiloint2double(hi, lo);
+}
+
+// First per-slot row of query x; cnt drops to 0 if the rows would leave the per-slot matrices.
+__device__ inline size_t slot_rows(const StepArgs &a, const TrainBufs &t, int x, int K, int &cnt)
+{
+    const int sb = cnt > 0 ? t.slot0[x] : 0;
+    if (sb < 0 || sb + cnt > 3 * a.count * K)
+        cnt = 0;
+    return (size_t)(cnt > 0 ? sb : 0);
 }
 
 // The step's distinct queries laid out as matrices (one wavefront per query): the query row
@@ -183,17 +192,19 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_gather(StepArgs a, PackedWeig
         }
     }
     cnt = cnt < 0 ? 0 : (cnt > K ? K : cnt);
-    if (lane == 0)
-        t.HAS[x] = cnt > 0 ? 1 : 0;
+    int sb = 0;
     if (cnt > 0) {
-        // the filled slots go on the list that every per-slot matrix product runs over (most rows of a
-        // step are negatives without history)
-        int base = 0;
+        // the filled slots of the step are packed into the per-slot matrices (most rows of a step are
+        // negatives without history), in the order the wavefronts happen to arrive
         if (lane == 0)
-            base = atomicAdd(t.n_live, cnt);
-        base = __shfl(base, 0);
-        if (lane < cnt && base >= 0 && base + lane < 3 * a.count * K)
-            t.live[base + lane] = x * K + lane;
+            sb = atomicAdd(t.n_live, cnt);
+        sb = __shfl(sb, 0);
+        if (sb < 0 || sb + cnt > 3 * a.count * K)
+            cnt = 0;  // (not reachable while the counter is cleared every step)
+    }
+    if (lane == 0) {
+        t.HAS[x] = cnt > 0 ? 1 : 0;
+        t.slot0[x] = cnt > 0 ? sb : -1;
     }
     const float *self = state_row(a, M, sref);
     for (int j = lane; j < da; j += kWave) {
@@ -206,7 +217,7 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_gather(StepArgs a, PackedWeig
         const int32_t rf = __shfl(my_ref, k), eid = __shfl(my_eid, k);
         const double dt = t_q - shfl_f64(my_ts, k);
         const float *row = state_row(a, M, rf);
-        float *dst = t.KV + ((size_t)x * K + k) * dkv;
+        float *dst = t.KV + ((size_t)sb + k) * dkv;
         for (int i = lane; i < dkv; i += kWave) {
             float v;
             if (i < M)
@@ -235,6 +246,7 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_fwd(StepArgs a, TrainDim
     const int q = x < n_u ? x : 2 * a.count + (x - n_u);
     int cnt = a.qs.cnt[q];
     cnt = cnt < 0 ? 0 : (cnt > K ? K : cnt);
+    const size_t sb = slot_rows(a, t, x, K, cnt);
     if (cnt == 0) {
         for (int j = lane; j < da; j += kWave)
             t.O_[(size_t)x * da + j] = 0.0f;
@@ -247,7 +259,7 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_fwd(StepArgs a, TrainDim
     float sc = -INFINITY;
     for (int h = 0; h < H; ++h)
         for (int k = 0; k < cnt; ++k) {
-            const float *kp = t.KP + ((size_t)x * K + k) * da + h * dh;
+            const float *kp = t.KP + (sb + k) * da + h * dh;
             float part = 0.0f;
             for (int e = lane; e < dh; e += kWave)
                 part += Qv[h * dh + e] * kp[e];
@@ -273,7 +285,7 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_fwd(StepArgs a, TrainDim
         const int h = j / dh;
         float acc = 0.0f;
         for (int k = 0; k < cnt; ++k)
-            acc += __shfl(pr, h * K + k) * t.VP[((size_t)x * K + k) * da + j];
+            acc += __shfl(pr, h * K + k) * t.VP[(sb + k) * da + j];
         if (j0 + lane < da)
             t.O_[(size_t)x * da + j] = acc;
     }
@@ -385,6 +397,7 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_bwd(StepArgs a, TrainDim
     const int q = x < n_u ? x : 2 * a.count + (x - n_u);
     int cnt = a.qs.cnt[q];
     cnt = cnt < 0 ? 0 : (cnt > K ? K : cnt);
+    const size_t sb = slot_rows(a, t, x, K, cnt);
     if (cnt == 0) {
         for (int j = lane; j < da; j += kWave)
             t.DQV[(size_t)x * da + j] = 0.0f;
@@ -396,7 +409,7 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_bwd(StepArgs a, TrainDim
     float dav = 0.0f;  // lane h * K + k: <VP[k] of head h, dout of head h>
     for (int h = 0; h < H; ++h)
         for (int k = 0; k < cnt; ++k) {
-            const float *vp = t.VP + ((size_t)x * K + k) * da + h * dh;
+            const float *vp = t.VP + (sb + k) * da + h * dh;
             float part = 0.0f;
             for (int e = lane; e < dh; e += kWave)
                 part += vp[e] * dout[h * dh + e];
@@ -418,7 +431,7 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_bwd(StepArgs a, TrainDim
         float acc = 0.0f;
         for (int k = 0; k < cnt; ++k) {
             const float ds = __shfl(dsv, h * K + k), pk = __shfl(pr, h * K + k);
-            const size_t o = ((size_t)x * K + k) * da + j;
+            const size_t o = (sb + k) * da + j;
             acc += ds * t.KP[o];
             if (in) {
                 t.DKP[o] = ds * qv * scale;
@@ -436,9 +449,9 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_bwd(StepArgs a, TrainDim
 // gradients; the time-encoding partial sums [gw | gb] of the row are written out.
 // A hub node's staged row is a neighbour of most queries of a batch: its thousands of row additions
 // would queue up on the same addresses.  A workgroup therefore collects the additions of its
-// kScatterRows queries in an LDS table of kScatterSlots rows (direct-mapped by staged row; a row
+// kScatterRows queries (one per wavefront) in an LDS table of kScatterSlots rows (direct-mapped by staged row; a row
 // whose place is taken goes to memory directly) and adds every table row to memory once.
-constexpr int kScatterRows = 64, kScatterSlots = 64, kTrScatterThreads = 1024;
+constexpr int kScatterRows = 16, kScatterSlots = 64, kTrScatterThreads = 1024;
 
 __global__ void __launch_bounds__(kTrScatterThreads) k_tr_scatter(StepArgs a, PackedWeights pw, TrainDims d, TrainBufs t)
 {
@@ -460,6 +473,7 @@ __global__ void __launch_bounds__(kTrScatterThreads) k_tr_scatter(StepArgs a, Pa
         const int q = x < n_u ? x : 2 * a.count + (x - n_u);
         int cnt = a.qs.cnt[q];
         cnt = cnt < 0 ? 0 : (cnt > K ? K : cnt);
+        const size_t sb = slot_rows(a, t, x, K, cnt);
         const double t_q = a.qs.t[q];
         // lane k < cnt: neighbour slot k, lane cnt: the query's own row.  Each claims the table row of
         // its staged row (or finds it claimed by another staged row: then the additions go to memory).
@@ -476,7 +490,6 @@ __global__ void __launch_bounds__(kTrScatterThreads) k_tr_scatter(StepArgs a, Pa
             }
         }
         const int n_el = (cnt + 1) * M;
-#pragma unroll 4
         for (int e0 = 0; e0 < n_el; e0 += kWave) {  // (every lane stays in the loop: the shuffles read lanes up to cnt)
             const bool in = e0 + lane < n_el;
             const int e = in ? e0 + lane : 0;
@@ -485,7 +498,7 @@ __global__ void __launch_bounds__(kTrScatterThreads) k_tr_scatter(StepArgs a, Pa
             if (in && srow >= 0) {
                 float v;
                 if (k < cnt)
-                    v = t.DKV[((size_t)x * K + k) * dkv + i];
+                    v = t.DKV[(sb + k) * dkv + i];
                 else
                     v = t.DSU[(size_t)x * M + i] + (cnt > 0 ? t.DQIN[(size_t)x * da + i] : 0.0f);
                 atomicAdd(lds ? &acc[(size_t)(srow & (kScatterSlots - 1)) * M + i] : &t.D_STAG[(size_t)srow * M + i], v);
@@ -497,10 +510,9 @@ __global__ void __launch_bounds__(kTrScatterThreads) k_tr_scatter(StepArgs a, Pa
             float gw = 0.0f, gb = 0.0f;
             if (cnt > 0)  // Phi(0)_j = cos(b_j): only the phase takes a gradient from the query row
                 gb += -time_enc_sin(pw.time_w_rev[j], pw.time_b_rev[j], 0.0) * t.DQIN[(size_t)x * da + M + j];
-#pragma unroll 4
             for (int k = 0; k < cnt; ++k) {
                 const double dt = shfl_f64(my_dt, k);
-                const float g = t.DKV[((size_t)x * K + k) * dkv + M + F + j];
+                const float g = t.DKV[(sb + k) * dkv + M + F + j];
                 const float sn = time_enc_sin(pw.time_w_rev[j], pw.time_b_rev[j], dt);
                 gw += -sn * (float)dt * g;
                 gb += -sn * g;
@@ -609,11 +621,9 @@ __device__ inline int row_count(const RowCount &rc)
 // these contractions: few of them).
 // csum != NULL: also csum[Mo] += the column sums of A (the bias gradient that goes with the weight
 // gradient: A^T times a column of ones), by the workgroups of the first block column.
-// ridx != NULL: the contraction runs over the rows ridx[0 .. rows) of A and B (each below ridx_max).
 constexpr int kTnWaves = 8;
 __global__ void __launch_bounds__(kTnWaves *kWave) k_gemm_tn(float *C, int ldc, const float *A, int lda, const float *B, int ldb,
-                                                              int Mo, int No, RowCount rc, int n_slices, float *csum,
-                                                              const int32_t *ridx, int ridx_max)
+                                                              int Mo, int No, RowCount rc, int n_slices, float *csum)
 {
     __shared__ float red[kTnWaves][1024];
     __shared__ float reds[kTnWaves][32];
@@ -648,12 +658,8 @@ __global__ void __launch_bounds__(kTnWaves *kWave) k_gemm_tn(float *C, int ldc, 
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
             const int kk = k + 4 * u + g;
-            bool kin = kk < k_hi;
-            int row = kk;
-            if (ridx) {
-                row = kin ? ridx[kk] : 0;
-                kin = kin && row >= 0 && row < ridx_max;
-            }
+            const bool kin = kk < k_hi;
+            const int row = kk;
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const int mm = m0 + 16 * i + c, nn = n0 + 16 * i + c;
@@ -723,8 +729,6 @@ struct RowGemm {
     int lda, ldw, lda2, ldw2, ldc;
     int N, Kd, Kd2;
     RowCount rc;
-    const int32_t *ridx;     // NULL, or: logical row r is row ridx[r] (< ridx_max) of A, A2 and C
-    int ridx_max;
     int relu;                // f = max(., 0)
     const float *gate;       // NULL, or: the result is kept where gate[row][n] > 0, else 0
     int ldg;
@@ -734,9 +738,17 @@ struct RowGemm {
     int vecA, vecW, vecA2, vecW2;  // operand rows are 16-byte aligned: four k in one load
 };
 
+// Four consecutive k of one operand row.  VEC (rows 16-byte aligned, Kd a multiple of 4): one load,
+// no branch -- a row or k outside the operand reads a valid address and is zeroed afterwards.
+template <bool VEC>
 __device__ inline floatx4 load_k4(const float *row, int k, int Kd, bool ok, int vec)
 {
     floatx4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (VEC) {
+        const bool in = ok && k < Kd;
+        const floatx4 r = *(const floatx4 *)(row + (k < Kd ? k : 0));
+        return in ? r : v;
+    }
     if (!ok)
         return v;
     if (vec && k + 3 < Kd)
@@ -748,6 +760,7 @@ __device__ inline floatx4 load_k4(const float *row, int k, int Kd, bool ok, int 
     return v;
 }
 
+template <bool VEC>
 __global__ void __launch_bounds__(256) k_rowgemm(RowGemm p)
 {
     const int rows = row_count(p.rc);
@@ -762,13 +775,8 @@ __global__ void __launch_bounds__(256) k_rowgemm(RowGemm p)
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int r = r0 + 16 * i + c;
-        bool ok = r < rows;
-        int pr = r;
-        if (p.ridx) {
-            pr = ok ? p.ridx[r] : 0;
-            ok = ok && pr >= 0 && pr < p.ridx_max;
-        }
-        arow[i] = (size_t)(ok ? pr : 0);
+        const bool ok = r < rows;
+        arow[i] = (size_t)(ok ? r : 0);
         aok[i] = ok;
     }
     const int tiles_n = (p.N + 31) / 32;
@@ -799,8 +807,8 @@ __global__ void __launch_bounds__(256) k_rowgemm(RowGemm p)
                     const int kk = k0 + 16 * u + 4 * g;
 #pragma unroll
                     for (int i = 0; i < 2; ++i) {
-                        av[u][i] = load_k4(ar[i], kk, Kd, aok[i], vA);
-                        wv[u][i] = load_k4(wr[i], kk, Kd, wok[i], vW);
+                        av[u][i] = load_k4<VEC>(ar[i], kk, Kd, aok[i], vA);
+                        wv[u][i] = load_k4<VEC>(wr[i], kk, Kd, wok[i], vW);
                     }
                 }
 #pragma unroll
@@ -830,11 +838,6 @@ __global__ void __launch_bounds__(256) k_rowgemm(RowGemm p)
                 if (r >= rows)
                     continue;
                 int orow = r;
-                if (p.ridx) {
-                    orow = p.ridx[r];
-                    if (orow < 0 || orow >= p.ridx_max)
-                        continue;
-                }
                 const bool dead = p.rowmask && p.rowmask[orow] == 0;
                 if (p.remap_nu)
                     orow = r < nu ? r : p.remap_2b + (r - nu);
@@ -1025,7 +1028,7 @@ static TrainLayout train_layout(const Dims &d, void *base)
     b.DGH = take(U * 3 * M);
     b.TGG = take(U * 2 * T);
     b.n_rows = (int32_t *)take(64);
-    b.live = (int32_t *)take(S);
+    b.slot0 = (int32_t *)take(R);
     L.pack_scratch = base ? p + off : nullptr;
     off += align_up(pack_scratch_bytes(d));
     L.bytes = off;
@@ -1151,13 +1154,16 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
         RowGemm g = {};
         g.A = A, g.lda = lda, g.W = W, g.ldw = ldw, g.bias = bias, g.C = C, g.ldc = ldc, g.N = N, g.Kd = Kd;
         g.rc = slots ? live : rows;
-        if (slots)
-            g.ridx = b.live, g.ridx_max = R * K;
         g.vecA = vec_ok(A, lda), g.vecW = vec_ok(W, ldw);
         return g;
     };
     auto run = [&](const RowGemm &g) {
-        hipLaunchKernelGGL(k_rowgemm, dim3((g.rc.rows_max + 31) / 32, ((g.N + 31) / 32 + 3) / 4), dim3(256), 0, s, g);
+        const dim3 grid((g.rc.rows_max + 31) / 32, ((g.N + 31) / 32 + 3) / 4);
+        const bool all_vec = g.vecA && g.vecW && g.Kd % 4 == 0 && (!g.A2 || (g.vecA2 && g.vecW2 && g.Kd2 % 4 == 0));
+        if (all_vec)
+            hipLaunchKernelGGL(k_rowgemm<true>, grid, dim3(256), 0, s, g);
+        else
+            hipLaunchKernelGGL(k_rowgemm<false>, grid, dim3(256), 0, s, g);
     };
     const dim3 per_row((R + kRowWaves - 1) / kRowWaves);
     // ---- forward, direct form
@@ -1212,7 +1218,7 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
 
     // weight gradient C += A^T B together with the bias gradient csum += column sums of A
     auto gemm = [&](const float *C, const float *csum, int Mo, int No, const float *A, const float *Bm, const RowCount &rc,
-                    int ldb = 0, const int32_t *ridx = nullptr, int ridx_max = 0) {
+                    int ldb = 0) {
         const int tiles = ((Mo + 31) / 32) * ((No + 31) / 32);
         // about 512 workgroups of eight wavefronts per contraction; a wavefront keeps at least 32 rows
         int n_slices = 512 / tiles;
@@ -1220,7 +1226,7 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
         n_slices = n_slices > most ? most : n_slices;
         n_slices = n_slices < 1 ? 1 : n_slices;
         hipLaunchKernelGGL(k_gemm_tn, dim3(tiles * n_slices), dim3(kTnWaves * kWave), 0, s, (float *)C, No, A, Mo, Bm,
-                           ldb ? ldb : No, Mo, No, rc, n_slices, (float *)csum, ridx, ridx_max);
+                           ldb ? ldb : No, Mo, No, rc, n_slices, (float *)csum);
     };
     auto colsum = [&](const float *out, const float *A, int lda, int cols, const RowCount &rc) {
         int n_slices = rc.rows_max / 512;
@@ -1237,8 +1243,8 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
     // attention
     gemm(L.g.W_O, L.g.b_O, da, da, b.D_ATTN, b.O_, rows);
     gemm(L.g.W_Q, L.g.b_Q, da, da, b.DQV, b.QIN, rows);
-    gemm(L.g.W_K, L.g.b_K, da, dkv, b.DKP, b.KV, live, 0, b.live, R * K);
-    gemm(L.g.W_V, L.g.b_V, da, dkv, b.DVP, b.KV, live, 0, b.live, R * K);
+    gemm(L.g.W_K, L.g.b_K, da, dkv, b.DKP, b.KV, live);
+    gemm(L.g.W_V, L.g.b_V, da, dkv, b.DVP, b.KV, live);
     // time encoding: per-row partial sums [gw | gb]; the two gradients are neighbours in the gradient buffer
     colsum(L.g.time_w, b.TG, 2 * T, 2 * T, rows);
     if (a.msg_count > 0) {
