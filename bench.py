@@ -384,6 +384,67 @@ def bench_sep(g, w, torch, num_parts=8, top_k=0.01, beta=1e-6):
             "part_edges_min_max": [int(part_edges.min()), int(part_edges.max())]}
 
 
+def derive_partition(S, torch, w, scale, n_hubs, num_parts=None, beta=1e-6):
+    """One GPU's partition DERIVED instead of postulated: a parent stream of `scale` times the
+    workload's events over `scale` times its owned ids is cut by the streaming edge partitioner
+    (Sec. II-B, Alg. 1) into `num_parts` partitions (default: `scale`) with the `n_hubs` most central
+    nodes replicated; partition 0's sub-graph (Sec. II-C: the events between its members, shared hubs
+    included, local ids) becomes the workload the step is timed on.  Returns (workload, graph, report).
+    With rank-frequency Zipf endpoints most events run between two hubs, and the shared hubs are
+    members of every partition: a partition's sub-graph then holds nearly the whole parent stream."""
+    num_parts = num_parts or scale
+    import dataclasses
+    import numpy as np
+    from paper_2308_14129_amd import pac, sep
+    owned = w.n_src - n_hubs
+    parent = dataclasses.replace(w, name=w.name + "_parent", n_src=scale * owned + n_hubs, num_events=scale * w.num_events)
+    t0 = time.time()
+    gp = S.make_graph(parent, with_features=False)
+    N, E = gp.num_nodes, gp.num_events
+    log(f"parent stream: {N} ids, {E} events, generated in {time.time() - t0:.1f} s")
+    src_d, dst_d, ts_d = (torch.from_numpy(a).to("cuda:0") for a in (gp.src, gp.dst, gp.ts))
+    top_k = n_hubs / N
+    cent_d = sep.centrality(src_d, dst_d, ts_d, N, beta)
+    hubs_d, is_hub_d = sep.top_k(cent_d, n_hubs)
+    torch.cuda.synchronize()
+    cent, is_hub = cent_d.cpu().numpy(), is_hub_d.cpu().numpy()
+    cfg = sep.make_config(num_parts, beta, top_k, 1.0, 1e-3)
+    t0 = time.perf_counter()
+    part, node_parts, part_edges = sep.assign(cfg, gp.src, gp.dst, N, cent, is_hub)
+    assign_s = time.perf_counter() - t0
+    log(f"edge loop: {assign_s:.1f} s ({E / assign_s / 1e6:.1f} M edges/s)")
+    copies = np.unpackbits(node_parts.view(np.uint8).reshape(-1, 8), axis=1).sum(axis=1)
+    placed = copies > 0
+    n_shared = int((copies > 1).sum())
+    rf = (n_shared * num_parts + (int(placed.sum()) - n_shared)) / max(1, int(placed.sum()))  # a shared node is listed in every partition
+    masks_d = torch.from_numpy(node_parts.view(np.int64)).to("cuda:0")
+    t0 = time.perf_counter()
+    eid_k, local_d, n_k = pac.subgraph(src_d, dst_d, masks_d, 1)
+    dummy = torch.empty((E, 1), dtype=torch.float32, device="cuda:0")  # the parent has no feature rows: the sub-graph draws its own
+    s_k, d_k, t_k, _ = pac.gather(src_d, dst_d, ts_d, dummy, eid_k, local_d)
+    torch.cuda.synchronize()
+    sub_s = time.perf_counter() - t0
+    n_e = int(eid_k.numel())
+    src_k, dst_k, ts_k = s_k.cpu().numpy(), d_k.cpu().numpy(), t_k.cpu().numpy()
+    hubs_in = int(is_hub_d[(local_d >= 0)].sum().item())
+    del src_d, dst_d, ts_d, dummy, eid_k, local_d, s_k, d_k, t_k, masks_d, cent_d, hubs_d, is_hub_d
+    torch.cuda.empty_cache()
+    name = w.name.replace("gpu_partition", "derived_partition") if "gpu_partition" in w.name else w.name + "_derived_partition"
+    ws = dataclasses.replace(w, name=name, n_src=n_k, num_events=n_e)
+    g = S.Graph(n_k, src_k, dst_k, ts_k, S.make_edge_feat(ws, n_e))
+    report = {"parent_nodes": N, "parent_events": E, "num_parts": num_parts, "hubs": n_hubs, "top_k": round(top_k, 6),
+              "beta": beta, "assign_s": round(assign_s, 1), "assign_edges_per_s": round(E / assign_s, 1),
+              "edge_cut": round(float(np.mean(part < 0)), 8), "nodes_placed": int(placed.sum()),
+              "shared_nodes": n_shared, "replication_factor": round(rf, 5),
+              # Theorem 1 over the nodes that occur: the hubs are the fraction k' of them, RF <= k'|P| + (1 - k')
+              "theorem_1_bound": round((n_hubs * num_parts + int(placed.sum()) - n_hubs) / max(1, int(placed.sum())), 5),
+              "part_edges_min_max": [int(part_edges.min()), int(part_edges.max())],
+              "subgraph_and_gather_s": round(sub_s, 3), "partition_nodes": n_k, "partition_hubs": hubs_in,
+              "partition_events": n_e}
+    log(f"partition 0: {n_k} nodes ({hubs_in} hubs), {n_e} events; RF {rf:.4f} <= {report['theorem_1_bound']}")
+    return ws, g, report
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -413,6 +474,13 @@ def main():
     ap.add_argument("--modules", default=None,
                     help="also time other instances of the general architecture (comma-separated names of "
                          "MODULE_INSTANCES, or 'all') on the same window and report them in a \"modules\" object")
+    ap.add_argument("--derive", action="store_true",
+                    help="time the step on a partition DERIVED by the streaming edge partitioner from a parent "
+                         "stream of --derive-scale times the workload's events (partition 0 of --derive-parts), "
+                         "instead of on the workload as postulated; reported in a \"derived\" object (no CPU baseline)")
+    ap.add_argument("--derive-scale", type=int, default=1)
+    ap.add_argument("--derive-parts", type=int, default=4)
+    ap.add_argument("--derive-hubs", type=int, default=100_000)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1",
@@ -430,7 +498,15 @@ def main():
     K, W_ = args.steps, args.warmup
     t0 = time.time()
     log(f"generating {w.name}: {w.num_nodes} nodes, {w.num_events} events ...")
-    g = S.make_graph(w)
+    derived = None
+    if args.derive:
+        if w.bipartite or not torch.cuda.is_available():
+            print("bench.py: --derive needs a GPU and a workload with one id space", file=sys.stderr)
+            sys.exit(1)
+        args.no_cpu_baseline = True  # (the oracle's replicas are forked, which must happen before the GPU is touched)
+        w, g, derived = derive_partition(S, torch, w, args.derive_scale, args.derive_hubs, args.derive_parts)
+    else:
+        g = S.make_graph(w)
     weights = S.make_weights(w)
     log(f"generated in {time.time() - t0:.1f} s")
 
@@ -647,6 +723,8 @@ def main():
         line["train"] = train_report
     if modules_report is not None:
         line["modules"] = modules_report
+    if derived is not None:
+        line["derived"] = derived
     if ctx is not None:
         ctx.close()
     print(json.dumps(line), flush=True)

@@ -156,19 +156,20 @@ __global__ void k_pac_gather(const int32_t *__restrict__ src, const int32_t *__r
                              const int32_t *__restrict__ eid, int64_t n, const int32_t *__restrict__ local,
                              int32_t *src_out, int32_t *dst_out, double *ts_out, float *feat_out)
 {
-    // one wavefront per event: the feature row is copied by its lanes
-    const int64_t w = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+    // one wavefront per event and turn: the feature row is copied by its lanes (a grid of one wavefront
+    // per event would pass 2^32 threads beyond 67 M events, which a dispatch cannot express)
+    const int64_t n_waves = (int64_t)gridDim.x * (blockDim.x / kWave);
     const int lane = threadIdx.x & (kWave - 1);
-    if (w >= n)
-        return;
-    const int64_t e = eid[w];
-    if (lane == 0) {
-        src_out[w] = local[src[e]];
-        dst_out[w] = local[dst[e]];
-        ts_out[w] = ts[e];
+    for (int64_t w = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave; w < n; w += n_waves) {
+        const int64_t e = eid[w];
+        if (lane == 0) {
+            src_out[w] = local[src[e]];
+            dst_out[w] = local[dst[e]];
+            ts_out[w] = ts[e];
+        }
+        for (int j = lane; j < F; j += kWave)
+            feat_out[w * F + j] = feat[e * F + j];
     }
-    for (int j = lane; j < F; j += kWave)
-        feat_out[w * F + j] = feat[e * F + j];
 }
 
 __global__ void __launch_bounds__(256) k_sync_shared(SyncArgs a)
@@ -316,7 +317,8 @@ int tig_pac_gather(const int32_t *src, const int32_t *dst, const double *ts, con
         return TIG_EINVAL;
     if (n == 0)
         return TIG_OK;
-    const int64_t blocks = (n * kWave + 255) / 256;
+    int64_t blocks = (n * kWave + 255) / 256;
+    blocks = blocks > (1 << 20) ? (1 << 20) : blocks;  // (the kernel strides over the events)
     hipLaunchKernelGGL(k_pac_gather, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)hip_stream, src, dst, ts,
                        edge_feat, (int)feat_dim, eid, n, local, src_out, dst_out, ts_out, feat_out);
     return hipGetLastError() == hipSuccess ? TIG_OK : TIG_EHIP;

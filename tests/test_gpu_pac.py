@@ -140,3 +140,55 @@ def test_shared_node_synchronisation(cut, mode):
         torch.cuda.synchronize()
         gate(o.emb.cpu().numpy(), want["emb"], 1e-4, "emb after the exchange")
         p["ctx"].close()
+
+
+def test_partition_derived_from_a_parent_stream_is_a_valid_workload():
+    """bench.py --derive: a parent stream cut by the partitioner into four parts, part 0 extracted on the
+    device with local ids.  The result must be a well-formed chronological stream over its own ids, every
+    event an event of the parent between two members, within Theorem 1's replication bound."""
+    import torch
+    import bench
+    w = S.WORKLOADS["c1_tiny"]
+    ws, g, rep = bench.derive_partition(S, torch, w, 4, 50)
+    assert g.num_nodes == rep["partition_nodes"] == ws.num_nodes and g.num_events == rep["partition_events"] == ws.num_events
+    assert rep["parent_events"] == 4 * w.num_events and rep["parent_nodes"] == 4 * (w.num_nodes - 50) + 50
+    assert 0 < g.num_events < rep["parent_events"]
+    assert np.all(np.diff(g.ts) >= 0) and np.all(g.src != g.dst)
+    assert g.src.min() >= 0 and g.dst.min() >= 0 and max(g.src.max(), g.dst.max()) < g.num_nodes
+    assert rep["replication_factor"] <= rep["theorem_1_bound"] + 1e-12
+    assert rep["partition_hubs"] <= 50 and g.edge_feat.shape == (g.num_events, w.feat_dim)
+    # the same cut by the oracle's own stream loop keeps the same events (when no decision was near a tie)
+    import dataclasses
+    parent = dataclasses.replace(w, n_src=rep["parent_nodes"], num_events=rep["parent_events"])
+    gp = S.make_graph(parent, with_features=False)
+    cent = P.centrality(gp.src, gp.dst, gp.ts, gp.num_nodes, rep["beta"])
+    order = sorted(range(len(cent)), key=lambda i: (-cent[i], i))
+    gap = cent[order[49]] - cent[order[50]]
+    _, A, _, margin = P.assign_stream(gp.src, gp.dst, gp.num_nodes, cent, sorted(order[:50]), 4, 1.0, 1e-3)
+    if margin > 1e-9 and gap > 1e-9:
+        members = np.array([len(a) > 1 or a == {0} for a in A], dtype=bool)
+        keep = members[gp.src] & members[gp.dst]
+        assert int(keep.sum()) == g.num_events and int(members.sum()) == g.num_nodes
+        np.testing.assert_array_equal(g.ts, gp.ts[keep])
+        np.testing.assert_array_equal(g.src, (np.cumsum(members) - 1)[gp.src[keep]])
+
+
+def test_gather_beyond_the_thread_limit_of_one_dispatch():
+    """One wavefront per event would need more than 2^32 threads above 67 M events: the gather strides."""
+    import torch
+    from paper_2308_14129_amd import pac
+    n, N = 70_000_000, 1000
+    dev = "cuda:0"
+    src = (torch.arange(n, device=dev, dtype=torch.int64) % N).to(torch.int32)
+    dst = ((torch.arange(n, device=dev, dtype=torch.int64) * 7 + 1) % N).to(torch.int32)
+    ts = torch.arange(n, device=dev, dtype=torch.float64)
+    feat = torch.arange(n, device=dev, dtype=torch.float32).reshape(n, 1)
+    eid = torch.arange(n - 1, -1, -1, device=dev, dtype=torch.int32)      # reversed: every row moves
+    local = torch.arange(N, device=dev, dtype=torch.int32) + 5
+    s, d, t, f = pac.gather(src, dst, ts, feat, eid, local)
+    torch.cuda.synchronize()
+    for w in (0, 1, 67_108_863, 67_108_864, n - 2, n - 1):
+        e = n - 1 - w
+        assert int(s[w]) == e % N + 5 and int(d[w]) == (e * 7 + 1) % N + 5
+        assert float(t[w]) == float(e) and float(f[w, 0]) == float(np.float32(e))
+    assert bool((t == torch.arange(n - 1, -1, -1, device=dev, dtype=torch.float64)).all())

@@ -190,6 +190,14 @@ def make_graph(w: Workload, with_features: bool = True) -> Graph:
     return Graph(w.num_nodes, src, dst, ts, feat)
 
 
+def make_edge_feat(w: Workload, num_events: int) -> np.ndarray:
+    """i.i.d. N(0, 1) fp32 edge features [num_events, F] from the workload's seed (for an event list that
+    was not drawn by make_graph, e.g. a partition's sub-graph)."""
+    feat = np.empty((num_events, w.feat_dim), dtype=np.float32)
+    _check(_load().tig_gen_edge_feat(w.seed, num_events, w.feat_dim, _ptr(feat)), "tig_gen_edge_feat")
+    return feat
+
+
 def make_negatives(w: Workload, g: Graph, first_eid: int, count: int) -> np.ndarray:
     """One negative destination per event of the batch (never equal to the source)."""
     neg = np.empty(count, dtype=np.int32)
