@@ -118,40 +118,79 @@ __device__ inline float repr_elem(const StepArgs &a, const ModParams &p, int M, 
 // Mean aggregator, first half: one wavefront per (event, role) entry of the applied batch adds the
 // columns of its message that differ between a node's messages -- [s'_other | Phi(dt) | e] -- to the
 // accumulation row of the entry that won the node's last message (named by the node's key), in
-// double with device atomics (a hub node collects thousands of messages per batch; the rows of its
-// partners arrive from all over the device).  The rows are all zero between steps: k_mod_update
-// clears what it has read.
-__global__ void __launch_bounds__(kModThreads) k_mod_msgsum(StepArgs a, ModDims d, ModParams p)
+// double.  A hub node collects thousands of messages per batch, and additions to one address queue
+// up: a workgroup first collects its kMsgEntries entries' rows in an LDS table of kMsgSlots rows
+// (direct-mapped by accumulation row; a row whose place is taken goes to memory directly) and adds
+// every table row to memory once, dealt out over the node's kAccCopies copies.  The rows in memory
+// are all zero between steps: k_mod_update clears what it has read.
+constexpr int kMsgThreads = 1024, kMsgEntries = 64, kMsgSlots = 16;
+
+__global__ void __launch_bounds__(kMsgThreads) k_mod_msgsum(StepArgs a, ModDims d, ModParams p)
 {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
     const int M = d.M, T = d.T, F = d.F, rest = M + T + F;
-    const int i = (int)blockIdx.x * kModWaves + wave_id();
-    if (i >= 2 * a.msg_count)
-        return;
-    const int lane = lane_id();
-    const int64_t e = a.msg_first_eid + (i >> 1);
-    const int32_t u = (i & 1) ? a.dst[e] : a.src[e];
-    const int32_t o = (i & 1) ? a.src[e] : a.dst[e];
-    if (u < 0 || (int64_t)u >= a.num_nodes)
-        return;
-    const int32_t ref = ref_of_key(ref_ctx(a), u, a.msg_key[u]);
-    if (ref >= 0 || ref == kRefNone)
-        return;  // (not reachable: every node of the applied batch has a winning entry in it)
-    const int row = ~ref;
-    const bool ok = o >= 0 && (int64_t)o < a.num_nodes;
-    const double dt = a.ts[e] - a.lu[u];
-    double *acc = p.acc + ((size_t)row * kAccCopies + ((i >> 1) & (kAccCopies - 1))) * rest;
-    for (int j = lane; j < rest; j += kWave) {
-        float v;
-        if (j < M)
-            v = ok ? a.mem[(size_t)o * M + j] : 0.0f;
-        else if (j < M + T)
-            v = time_enc(p.time_w_rev[j - M], p.time_b_rev[j - M], dt);
-        else
-            v = a.edge_feat[(size_t)e * F + (j - M - T)];
-        unsafeAtomicAdd(&acc[j], (double)v);
+    double *acc = (double *)smem;                    // [slots x rest]
+    int *tag = (int *)(acc + kMsgSlots * rest);      // [slots] accumulation row held by the slot, -1: none
+    int *cnt = tag + kMsgSlots;                      // [slots] messages collected in it
+    for (int i = threadIdx.x; i < kMsgSlots * rest; i += kMsgThreads)
+        acc[i] = 0.0;
+    if (threadIdx.x < kMsgSlots) {
+        tag[threadIdx.x] = -1;
+        cnt[threadIdx.x] = 0;
     }
-    if (lane == 0)
-        atomicAdd(&p.acc_cnt[row], 1);
+    __syncthreads();
+    const int lane = lane_id();
+    const int i_end = ((int)blockIdx.x + 1) * kMsgEntries < 2 * a.msg_count ? ((int)blockIdx.x + 1) * kMsgEntries : 2 * a.msg_count;
+    for (int i = (int)blockIdx.x * kMsgEntries + wave_id(); i < i_end; i += kMsgThreads / kWave) {
+        const int64_t e = a.msg_first_eid + (i >> 1);
+        const int32_t u = (i & 1) ? a.dst[e] : a.src[e];
+        const int32_t o = (i & 1) ? a.src[e] : a.dst[e];
+        if (u < 0 || (int64_t)u >= a.num_nodes)
+            continue;
+        const int32_t ref = ref_of_key(ref_ctx(a), u, a.msg_key[u]);
+        if (ref >= 0 || ref == kRefNone)
+            continue;  // (not reachable: every node of the applied batch has a winning entry in it)
+        const int row = ~ref;
+        const bool ok = o >= 0 && (int64_t)o < a.num_nodes;
+        const double dt = a.ts[e] - a.lu[u];
+        const int slot = row & (kMsgSlots - 1);
+        int old = 0;
+        if (lane == 0)
+            old = atomicCAS(&tag[slot], -1, row);
+        old = __shfl(old, 0);
+        const bool in_lds = old == -1 || old == row;
+        double *dst = in_lds ? acc + (size_t)slot * rest
+                             : p.acc + ((size_t)row * kAccCopies + ((i >> 1) & (kAccCopies - 1))) * rest;
+        for (int j = lane; j < rest; j += kWave) {
+            float v;
+            if (j < M)
+                v = ok ? a.mem[(size_t)o * M + j] : 0.0f;
+            else if (j < M + T)
+                v = time_enc(p.time_w_rev[j - M], p.time_b_rev[j - M], dt);
+            else
+                v = a.edge_feat[(size_t)e * F + (j - M - T)];
+            if (in_lds)
+                atomicAdd(&dst[j], (double)v);
+            else
+                unsafeAtomicAdd(&dst[j], (double)v);
+        }
+        if (lane == 0) {
+            if (in_lds)
+                atomicAdd(&cnt[slot], 1);
+            else
+                atomicAdd(&p.acc_cnt[row], 1);
+        }
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < kMsgSlots * rest; idx += kMsgThreads) {
+        const int slot = idx / rest, j = idx - slot * rest;
+        const int row = tag[slot];
+        if (row < 0 || row >= 2 * a.msg_count)
+            continue;
+        unsafeAtomicAdd(&p.acc[((size_t)row * kAccCopies + ((int)blockIdx.x & (kAccCopies - 1))) * rest + j], acc[idx]);
+        if (j == 0)
+            atomicAdd(&p.acc_cnt[row], cnt[slot]);
+    }
 }
 
 // Aggregated message + state update of one node of the applied batch (the batch's winner list names
@@ -540,6 +579,8 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 int update_lds(const ModDims &d) { return (d.Dmsg + d.M + 2 * d.G * d.M) * 4; }
 
+int msgsum_lds(const ModDims &d) { return kMsgSlots * (d.M + d.T + d.F) * 8 + 2 * kMsgSlots * 4; }
+
 int rows_lds(const ModDims &d)
 {
     return d.K * 8 + (2 * d.K + 4) * 4 +
@@ -668,7 +709,7 @@ bool modules_supported(const Dims &d, const tig_modules &m)
         return false;
     if (m.num_layers == 2 && (m.embedding != TIG_EMB_ATTENTION || (d.E + d.T) % d.H != 0))
         return false;
-    return d.prec == TIG_FP32 && update_lds(md) <= 160 * 1024 && rows_lds_all(md, m.num_layers) <= 160 * 1024 &&
+    return d.prec == TIG_FP32 && update_lds(md) <= 160 * 1024 && msgsum_lds(md) <= 64 * 1024 && rows_lds_all(md, m.num_layers) <= 160 * 1024 &&
            decode_lds(md) <= 160 * 1024 && d.K <= kModThreads;
 }
 
@@ -746,6 +787,7 @@ hipError_t modules_attach(const Dims &d, const tig_modules &m, const tig_weights
         MOD_TRY(launch_fill_zero(p.acc_cnt, (size_t)2 * d.max_batch * 4, s));
     }
     MOD_TRY(hipFuncSetAttribute((const void *)k_mod_update, hipFuncAttributeMaxDynamicSharedMemorySize, update_lds(md)));
+    MOD_TRY(hipFuncSetAttribute((const void *)k_mod_msgsum, hipFuncAttributeMaxDynamicSharedMemorySize, msgsum_lds(md)));
     MOD_TRY(hipFuncSetAttribute((const void *)k_mod_rows, hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds_all(md, p.layers)));
     MOD_TRY(hipFuncSetAttribute((const void *)k_mod_decode, hipFuncAttributeMaxDynamicSharedMemorySize, decode_lds(md)));
 #undef MOD_TRY
@@ -763,7 +805,8 @@ hipError_t launch_modules(const Dims &d, const LaunchPlan &plan, const PackedWei
     hipError_t e;
     if (a.msg_count > 0) {
         if (p.agg == TIG_AGG_MEAN)
-            hipLaunchKernelGGL(k_mod_msgsum, dim3((2 * a.msg_count + kModWaves - 1) / kModWaves), dim3(kModThreads), 0, s, a, md, p);
+            hipLaunchKernelGGL(k_mod_msgsum, dim3((2 * a.msg_count + kMsgEntries - 1) / kMsgEntries), dim3(kMsgThreads),
+                               msgsum_lds(md), s, a, md, p);
         hipLaunchKernelGGL(k_mod_update, dim3(2 * a.msg_count), dim3(kModThreads), update_lds(md), s, a, md, p);
         if ((e = hipGetLastError()) != hipSuccess)
             return e;
