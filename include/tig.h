@@ -205,10 +205,10 @@ TIG_API int tig_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *out);
  * The same step, same launches, with a HIP event recorded on the context's stream before the first
  * and after every kernel; waits for the step to finish and writes the kernel durations in
  * milliseconds to kernel_ms[0..TIG_NUM_STEP_KERNELS-1] (host), in launch order:
- *   0, 1  key scatter and winner selection of a batch above 4096 events (else ~0)
- *   2     preparation of a batch that the previous step did not prepare (else ~0)
+ *   0, 1  key scatter and winner selection of a batch above 4096 events (else 0)
+ *   2     preparation of a batch that the previous step did not prepare (else 0)
  *   3     message + GRU and what is left of the query preparation, for a step whose applied batch
- *         the previous step's last launch did not cover (else ~0)
+ *         the previous step's last launch did not cover (else 0)
  *   4     attention embedding (with the negatives' neighbour lookups), merge MLP, first decoder
  *         layer, memory overwrite (and the next batch's preparation)
  *   5     scores, per-query embedding rows (and message + GRU of the batch the next step applies)

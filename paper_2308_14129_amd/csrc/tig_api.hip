@@ -97,6 +97,7 @@ struct tig_ctx {
     int32_t *rows_seen_host;
     int32_t *rows_seen_dev;
     hipEvent_t marks[kNumStepKernels + 1];
+    unsigned last_ran;  // which intervals between the marks held a kernel in the last step
     bool have_marks;
     char err[256];
 };
@@ -731,6 +732,10 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
         sp.loss_out = train->loss_out;
     }
     const hipError_t e = launch_step(d, ctx->plan, ctx->pw, a, sp, ctx->stream, marks);
+    // bit i: the interval between marks i and i + 1 held a kernel (a module selection's kernels fill
+    // intervals 3 and 4)
+    ctx->last_ran = (sp.big_sel ? 3u : 0u) | ((sp.prep_sel || sp.prep_ded) ? 4u : 0u) |
+                    ((sp.mods || sp.gru_now) ? 8u : 0u) | 16u | (sp.mods ? 0u : 32u);
     if (e != hipSuccess) {
         // kernels of this step may already be enqueued: nothing prepared ahead is trusted any more,
         // and the model state is undefined until tig_reset / tig_state_import
@@ -981,6 +986,9 @@ int tig_step_profiled(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, 
     hipError_t e = hipEventSynchronize(ctx->marks[kNumStepKernels]);
     for (int i = 0; i < kNumStepKernels && e == hipSuccess; ++i)
         e = hipEventElapsedTime(&kernel_ms[i], ctx->marks[i], ctx->marks[i + 1]);
+    for (int i = 0; i < kNumStepKernels; ++i)
+        if (!((ctx->last_ran >> i) & 1u))
+            kernel_ms[i] = 0.0f;  // (an empty interval still reads a few microseconds)
     if (e != hipSuccess)
         return fail(ctx, TIG_EHIP, "tig_step_profiled timing", e);
     return TIG_OK;
