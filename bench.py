@@ -603,7 +603,7 @@ def main():
     stages = {n: {"avg_us": round(float(avg_ms[i]) * 1e3, 2),
                   "alg_bytes": int(byte_sums[n] / n_prof),
                   "GBps": round(byte_sums[n] / n_prof / max(float(avg_ms[i]), 1e-9) / 1e6, 1)}
-              for i, n in enumerate(names) if avg_ms[i] > 1e-4 or byte_sums[n] > 0}
+              for i, n in enumerate(names) if avg_ms[i] > 1e-4}   # (a launch the steps did not need reads 0)
     figs = profile_figures("counters", w.name, precision, B)
     trace = profile_figures("step_kernels", w.name, precision, B)
     traffic = float(figs["k_embed_hbm_bytes_per_launch"]) if dom_name == "k_embed" and \

@@ -13,8 +13,9 @@
 //                   the matrix cores (fp32 16x16x4): Q / K / V / O projections, merge MLP, and their
 //                   transposed products dX = dY W; the per-slot products run over the filled slots only
 //   k_tr_attn_fwd / k_tr_attn_bwd   scores, softmax, weighted value sum of one query per wavefront
-//   k_tr_decoder    one workgroup per event: both logits, loss terms, embedding rows out, and the
-//                   decoder's backward down to the embeddings (added into the rows' gradients)
+//   k_tr_pairs / k_tr_logit / k_tr_pair_scatter   around the decoder's two contractions: the decoder's
+//                   input rows per (pair, event), logits and loss terms, and the gradients of those
+//                   rows added into the distinct embedding rows' gradients
 //   k_tr_scatter    the gradient w.r.t. state rows that this step's GRU wrote goes to those rows;
 //                   time-encoding partial sums per query
 //   k_tr_gru_bwd    one workgroup per applied winner: message and GRU gates recomputed from the
@@ -123,7 +124,7 @@ struct TrainBufs {
     // per filled neighbour slot: slot k of query x is row slot0[x] + k (the filled slots of a step are packed)
     float *KV, *KP, *VP, *DKP, *DVP, *DKV;
     // per (pair, event): pair 0 = (source, destination), pair 1 = (source, negative); row p * count + b
-    float *CAT, *DY, *G_, *DLOGIT, *LOSS;
+    float *CAT, *DY, *G_, *DCAT, *DLOGIT, *LOSS;
     // per applied winner r, and per entry of the applied batch
     float *MSG, *DGI, *DGH, *TGG, *D_STAG;
     int32_t *n_rows;  // [1] distinct queries of the step (written by the forward kernel's block 0)
@@ -315,68 +316,77 @@ __device__ inline int row_of_entry_tr(const QuerySet &qs, int i, int entries)
     return s >= 0 && s < entries ? s : 0;
 }
 
-__global__ void __launch_bounds__(kTrThreads) k_tr_decoder(StepArgs a, TrainDims d, TrainBufs t)
+// The decoder runs as contractions over all (pair, event) rows (pair 0 = (source, destination), pair
+// 1 = (source, negative); row p * count + b) with three small kernels around them.
+// k_tr_pairs, one wavefront per event: the three embedding rows of the event go out, and the two
+// input rows [emb_source | emb_destination], [emb_source | emb_negative] of the decoder are laid out.
+__global__ void __launch_bounds__(kTrThreads) k_tr_pairs(StepArgs a, TrainDims d, TrainBufs t)
 {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    const int E = d.E, b = (int)blockIdx.x, B = a.count;
-    float *em = (float *)smem;  // [3 x E]: source, destination, negative
-    float *y = em + 3 * E;      // [E]
-    float *dy = y + E;          // [E]
-    float *red = dy + E;        // [waves]
+    const int E = d.E, B = a.count;
+    const int b = (int)blockIdx.x * kRowWaves + wave_id();
+    if (b >= B)
+        return;
+    const int lane = lane_id();
+    const int r0 = row_of_entry_tr(a.qs, 2 * b, 2 * B), r1 = row_of_entry_tr(a.qs, 2 * b + 1, 2 * B), r2 = 2 * B + b;
+    for (int j = lane; j < E; j += kWave) {
+        const float es = a.emb_u[(size_t)r0 * E + j], ed = a.emb_u[(size_t)r1 * E + j], en = a.emb_u[(size_t)r2 * E + j];
+        a.emb[(size_t)b * E + j] = es;
+        a.emb[((size_t)B + b) * E + j] = ed;
+        a.emb[((size_t)2 * B + b) * E + j] = en;
+        t.CAT[(size_t)b * 2 * E + j] = es;
+        t.CAT[(size_t)b * 2 * E + E + j] = ed;
+        t.CAT[((size_t)B + b) * 2 * E + j] = es;
+        t.CAT[((size_t)B + b) * 2 * E + E + j] = en;
+    }
+}
+
+// k_tr_logit, one wavefront per (pair, event) row, after G_ = relu(W_d1 cat + b_d1): the logit, its
+// loss term and the gradient of the hidden layer's pre-activation.
+__global__ void __launch_bounds__(kTrThreads) k_tr_logit(StepArgs a, TrainDims d, TrainBufs t)
+{
+    const int E = d.E, B = a.count;
+    const int pr = (int)blockIdx.x * kRowWaves + wave_id();
+    if (pr >= 2 * B)
+        return;
+    const int lane = lane_id();
+    const int p = pr >= B ? 1 : 0, b = pr - p * B;
+    float part = 0.0f;
+    for (int j = lane; j < E; j += kWave)
+        part += t.w_d2[j] * t.G_[(size_t)pr * E + j];
+    const float logit = wave_sum_uniform(part) + t.b_d2[0];
+    // d softplus(sign * logit) / d logit = sign * sigmoid(sign * logit), averaged over the batch
+    const float sign = p == 0 ? -1.0f : 1.0f;
+    const float z = sign * logit;
+    const float dlogit = sign / (1.0f + expf(-z)) / (float)B;
+    if (lane == 0) {
+        (p == 0 ? a.score_pos : a.score_neg)[b] = logit;
+        t.DLOGIT[pr] = dlogit;
+        t.LOSS[pr] = (z > 0.0f ? z + log1pf(expf(-z)) : log1pf(expf(z))) / (float)B;
+    }
+    for (int j = lane; j < E; j += kWave)
+        t.DY[(size_t)pr * E + j] = t.G_[(size_t)pr * E + j] > 0.0f ? dlogit * t.w_d2[j] : 0.0f;
+}
+
+// k_tr_pair_scatter, one wavefront per event, after DCAT = DY W_d1: the gradients of the event's two
+// decoder input rows are added to the gradients of the three distinct embedding rows they were
+// copied from (rows of sources and destinations are shared by many events: atomics).
+__global__ void __launch_bounds__(kTrThreads) k_tr_pair_scatter(StepArgs a, TrainDims d, TrainBufs t)
+{
+    const int E = d.E, B = a.count;
+    const int b = (int)blockIdx.x * kRowWaves + wave_id();
+    if (b >= B)
+        return;
+    const int lane = lane_id();
     int n_u = *a.qs.n_u;
     n_u = n_u < 2 * B ? n_u : 2 * B;
-    int row[3];
-    row[0] = row_of_entry_tr(a.qs, 2 * b, 2 * B);
-    row[1] = row_of_entry_tr(a.qs, 2 * b + 1, 2 * B);
-    row[2] = 2 * B + b;
-    for (int idx = threadIdx.x; idx < 3 * E; idx += kTrThreads) {
-        const int r = idx / E, j = idx - r * E;
-        const float v = a.emb_u[(size_t)row[r] * E + j];
-        em[idx] = v;
-        a.emb[((size_t)r * B + b) * E + j] = v;
-    }
-    __syncthreads();
-    for (int p = 0; p < 2; ++p) {
-        const float *ea = em, *eb = em + (1 + p) * E;
-        const size_t pr = (size_t)p * B + b;
-        for (int j = threadIdx.x; j < E; j += kTrThreads) {
-            float acc = t.b_d1[j];
-            for (int i = 0; i < E; ++i)
-                acc += t.T_d1[(size_t)i * E + j] * ea[i] + t.T_d1[(size_t)(E + i) * E + j] * eb[i];
-            y[j] = acc;
-        }
-        __syncthreads();
-        float part = 0.0f;
-        for (int j = threadIdx.x; j < E; j += kTrThreads)
-            part += t.w_d2[j] * fmaxf(y[j], 0.0f);
-        const float logit = block_sum(part, red) + t.b_d2[0];
-        // d softplus(sign * logit) / d logit = sign * sigmoid(sign * logit), averaged over the batch
-        const float sign = p == 0 ? -1.0f : 1.0f;
-        const float z = sign * logit;
-        const float dlogit = sign / (1.0f + expf(-z)) / (float)B;
-        if (threadIdx.x == 0) {
-            (p == 0 ? a.score_pos : a.score_neg)[b] = logit;
-            t.DLOGIT[pr] = dlogit;
-            t.LOSS[pr] = (z > 0.0f ? z + log1pf(expf(-z)) : log1pf(expf(z))) / (float)B;
-        }
-        for (int j = threadIdx.x; j < E; j += kTrThreads) {
-            const float g = fmaxf(y[j], 0.0f);
-            const float v = y[j] > 0.0f ? dlogit * t.w_d2[j] : 0.0f;
-            dy[j] = v;
-            t.DY[pr * E + j] = v;
-            t.G_[pr * E + j] = g;
-            t.CAT[pr * 2 * E + j] = ea[j];
-            t.CAT[pr * 2 * E + E + j] = eb[j];
-        }
-        __syncthreads();
-        const int xa = compact_row(row[0], n_u, B), xb = compact_row(row[1 + p], n_u, B);
-        for (int i = threadIdx.x; i < 2 * E; i += kTrThreads) {
-            float acc = 0.0f;
-            for (int o2 = 0; o2 < E; ++o2)
-                acc += t.W_d1[(size_t)o2 * 2 * E + i] * dy[o2];
-            atomicAdd(&t.D_EMB[(size_t)(i < E ? xa : xb) * E + (i < E ? i : i - E)], acc);
-        }
-        __syncthreads();
+    const int xs = compact_row(row_of_entry_tr(a.qs, 2 * b, 2 * B), n_u, B);
+    const int xd = compact_row(row_of_entry_tr(a.qs, 2 * b + 1, 2 * B), n_u, B);
+    const int xn = compact_row(2 * B + b, n_u, B);
+    const float *g0 = t.DCAT + (size_t)b * 2 * E, *g1 = t.DCAT + ((size_t)B + b) * 2 * E;
+    for (int j = lane; j < E; j += kWave) {
+        atomicAdd(&t.D_EMB[(size_t)xs * E + j], g0[j] + g1[j]);
+        atomicAdd(&t.D_EMB[(size_t)xd * E + j], g0[E + j]);
+        atomicAdd(&t.D_EMB[(size_t)xn * E + j], g1[E + j]);
     }
 }
 
@@ -1021,6 +1031,7 @@ static TrainLayout train_layout(const Dims &d, void *base)
     b.CAT = take(U * 2 * E);
     b.DY = take(U * E);
     b.G_ = take(U * E);
+    b.DCAT = take(U * 2 * E);
     b.DLOGIT = take(U);
     b.LOSS = take(U);
     b.MSG = take(U * D);
@@ -1043,7 +1054,6 @@ static TrainLayout train_layout(const Dims &d, void *base)
 
 static int gru_bwd_lds(const Dims &d) { return 4 * (d.Dmsg + 12 * d.M); }
 static int scatter_lds(const Dims &d) { return 4 * kScatterSlots * (d.M + 1); }
-static int dec_lds(const Dims &d) { return 4 * (5 * d.E + 8); }
 
 size_t train_workspace_bytes(const Dims &d) { return train_layout(d, nullptr).bytes; }
 
@@ -1052,8 +1062,6 @@ hipError_t prepare_train(const Dims &d)
     hipError_t e = hipFuncSetAttribute((const void *)k_tr_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, scatter_lds(d));
     if (e == hipSuccess)
         e = hipFuncSetAttribute((const void *)k_tr_gru_bwd, hipFuncAttributeMaxDynamicSharedMemorySize, gru_bwd_lds(d));
-    if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void *)k_tr_decoder, hipFuncAttributeMaxDynamicSharedMemorySize, dec_lds(d));
     return e;
 }
 
@@ -1187,7 +1195,18 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
         g.remap_nu = a.qs.n_u, g.remap_2b = 2 * B;
         run(g);
     }
-    hipLaunchKernelGGL(k_tr_decoder, dim3(B), dim3(kTrThreads), dec_lds(d), s, a, td, b);
+    {   // decoder: input rows, hidden layer, logits and loss terms; then back to the embedding rows
+        const dim3 per_event((B + kRowWaves - 1) / kRowWaves), per_pair((2 * B + kRowWaves - 1) / kRowWaves);
+        hipLaunchKernelGGL(k_tr_pairs, per_event, dim3(kTrThreads), 0, s, a, td, b);
+        RowGemm g = layer(b.G_, E, b.CAT, 2 * E, b.W_d1, 2 * E, b.b_d1, E, 2 * E);
+        g.rc = pairs, g.relu = 1;
+        run(g);
+        hipLaunchKernelGGL(k_tr_logit, per_pair, dim3(kTrThreads), 0, s, a, td, b);
+        g = layer(b.DCAT, 2 * E, b.DY, E, b.T_d1, E, nullptr, 2 * E, E);
+        g.rc = pairs;
+        run(g);
+        hipLaunchKernelGGL(k_tr_pair_scatter, per_event, dim3(kTrThreads), 0, s, a, td, b);
+    }
     // ---- backward: dX = dY W through the transposed copies
     {   // dz1 = (W_m2^T d_emb) where z1 > 0
         RowGemm g = layer(b.DZ1, E, b.D_EMB, E, b.T_m2, E, nullptr, E, E);
