@@ -18,8 +18,9 @@
 //                   rows added into the distinct embedding rows' gradients
 //   k_tr_scatter    the gradient w.r.t. state rows that this step's GRU wrote goes to those rows;
 //                   time-encoding partial sums per query
-//   k_tr_gru_bwd    one workgroup per applied winner: message and GRU gates recomputed from the
-//                   memory as the step found it, backward to the gate pre-activations
+//   k_tr_gru_msg / k_tr_gru_gates / k_tr_gru_time   around the contractions of the GRU's backward
+//                   pass over the applied winners: message rows from the memory as the step found it,
+//                   gates and the gradients of their pre-activations, time-encoding gradient
 //   k_gemm_tn       every weight gradient is dW = D^T X over the rows' stored (delta, input) pairs:
 //                   a [out x in] contraction over thousands of rows on the matrix cores (fp32
 //                   16x16x4), split over the row range, partial results added with atomics
@@ -40,7 +41,6 @@ namespace tig {
 namespace {
 
 constexpr int kTrThreads = 256;
-constexpr int kKC = 8;  // neighbour slots per register chunk
 
 __device__ inline const float *state_row(const StepArgs &a, int M, int32_t ref)
 {
@@ -56,56 +56,6 @@ __device__ inline float time_enc_sin(double w_rev, double b_rev, double x)
 {
     const double phase = fma(w_rev, x, b_rev);
     return __builtin_amdgcn_sinf((float)__builtin_amdgcn_fract(phase));
-}
-
-// y[j] = bias[j] + sum_i WT[i * out + j] * x[i]   (x, y in LDS)
-__device__ inline void matvec_t(const float *WT, int in, int out, const float *x, const float *bias, float *y)
-{
-    for (int j = threadIdx.x; j < out; j += kTrThreads) {
-        float acc = bias ? bias[j] : 0.0f;
-#pragma unroll 8
-        for (int i = 0; i < in; ++i)  // (unrolled: eight independent weight loads in flight, not one per step)
-            acc += WT[(size_t)i * out + j] * x[i];
-        y[j] = acc;
-    }
-}
-
-// dx[i] = sum_o W[o * in + i] * dy[o]  for i in [0, in)   (dy, dx in LDS)
-__device__ inline void matvec_n(const float *W, int out, int in, const float *dy, float *dx)
-{
-    for (int i = threadIdx.x; i < in; i += kTrThreads) {
-        float acc = 0.0f;
-#pragma unroll 8
-        for (int o = 0; o < out; ++o)
-            acc += W[(size_t)o * in + i] * dy[o];
-        dx[i] = acc;
-    }
-}
-
-// Y[k][j] = bias[j] + sum_i WT[i * out + j] * X[k][i] for k < cnt   (X [cnt x ldx], Y [cnt x out] in LDS)
-__device__ inline void multivec_t(const float *WT, int in, int out, const float *X, int ldx, int cnt,
-                                  const float *bias, float *Y)
-{
-    for (int k0 = 0; k0 < cnt; k0 += kKC) {
-        for (int j = threadIdx.x; j < out; j += kTrThreads) {
-            float acc[kKC];
-            const float b = bias ? bias[j] : 0.0f;
-#pragma unroll
-            for (int u = 0; u < kKC; ++u)
-                acc[u] = b;
-#pragma unroll 4
-            for (int i = 0; i < in; ++i) {
-                const float w = WT[(size_t)i * out + j];
-#pragma unroll
-                for (int u = 0; u < kKC; ++u)
-                    acc[u] += w * X[(size_t)(k0 + u < cnt ? k0 + u : k0) * ldx + i];
-            }
-#pragma unroll
-            for (int u = 0; u < kKC; ++u)
-                if (k0 + u < cnt)
-                    Y[(size_t)(k0 + u) * out + j] = acc[u];
-        }
-    }
 }
 
 struct TrainDims {
@@ -126,7 +76,7 @@ struct TrainBufs {
     // per (pair, event): pair 0 = (source, destination), pair 1 = (source, negative); row p * count + b
     float *CAT, *DY, *G_, *DCAT, *DLOGIT, *LOSS;
     // per applied winner r, and per entry of the applied batch
-    float *MSG, *DGI, *DGH, *TGG, *D_STAG;
+    float *MSG, *GI, *GH, *DGI, *DGH, *DPHI, *D_STAG;
     int32_t *n_rows;  // [1] distinct queries of the step (written by the forward kernel's block 0)
     int32_t *slot0;   // [3B] first row of a query's filled slots in the per-slot matrices
     int32_t *n_live;  // [1] filled slots of the step (cleared with the gradients)
@@ -159,23 +109,26 @@ __device__ inline size_t slot_rows(const StepArgs &a, const TrainBufs &t, int x,
 // [s_u | Phi(0)], the own state as the tail of the merge layer's input, the key / value rows
 // [s_v | e | Phi(t - t_k)] of the filled neighbour slots, and the list of those slots.  A negative's
 // neighbours are looked up here.
-__global__ void __launch_bounds__(kTrThreads) k_tr_gather(StepArgs a, PackedWeights pw, TrainDims d, TrainBufs t)
+constexpr int kGatherWaves = 16;  // queries per workgroup of k_tr_gather
+
+__global__ void __launch_bounds__(kGatherWaves *kWave) k_tr_gather(StepArgs a, PackedWeights pw, TrainDims d, TrainBufs t)
 {
+    __shared__ int wg_cnt[kGatherWaves], wg_base;
     int n_u = *a.qs.n_u;
     n_u = n_u < 2 * a.count ? n_u : 2 * a.count;
     const int n_rows = n_u + a.count;
     if (blockIdx.x == 0 && threadIdx.x == 0)
         *t.n_rows = n_rows;
-    const int x = (int)blockIdx.x * kRowWaves + wave_id();
-    if (x >= n_rows)
-        return;  // (uniform over the wavefront)
+    const int x = (int)blockIdx.x * kGatherWaves + wave_id();
+    const bool live_row = x < n_rows;  // (uniform over the wavefront; every wavefront reaches the barriers)
     const int lane = lane_id();
     const int M = d.M, F = d.F, K = d.K, da = d.da, dkv = d.dkv;
     const int q = x < n_u ? x : 2 * a.count + (x - n_u);
-    int cnt;
-    int32_t sref, my_ref = kRefNone, my_eid = -1;
-    double my_ts = 0.0, t_q;
-    if (x >= n_u) {
+    int cnt = 0;
+    int32_t sref = kRefNone, my_ref = kRefNone, my_eid = -1;
+    double my_ts = 0.0, t_q = 0.0;
+    if (!live_row) {
+    } else if (x >= n_u) {
         const int b = x - n_u;
         t_q = a.ts[a.first_eid + b];
         cnt = finish_negative(a, K, b, my_ref, my_eid, my_ts);
@@ -193,16 +146,26 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_gather(StepArgs a, PackedWeig
         }
     }
     cnt = cnt < 0 ? 0 : (cnt > K ? K : cnt);
-    int sb = 0;
-    if (cnt > 0) {
-        // the filled slots of the step are packed into the per-slot matrices (most rows of a step are
-        // negatives without history), in the order the wavefronts happen to arrive
-        if (lane == 0)
-            sb = atomicAdd(t.n_live, cnt);
-        sb = __shfl(sb, 0);
-        if (sb < 0 || sb + cnt > 3 * a.count * K)
-            cnt = 0;  // (not reachable while the counter is cleared every step)
+    // the filled slots of the step are packed into the per-slot matrices (most rows of a step are
+    // negatives without history), in the order the workgroups happen to arrive: one addition to the
+    // step's counter per workgroup (one per query queued thousands of them on the one address)
+    if (lane == 0)
+        wg_cnt[wave_id()] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int total = 0;
+        for (int i = 0; i < kGatherWaves; ++i)
+            total += wg_cnt[i];
+        wg_base = total > 0 ? atomicAdd(t.n_live, total) : 0;
     }
+    __syncthreads();
+    if (!live_row)
+        return;
+    int sb = wg_base;
+    for (int i = 0; i < wave_id(); ++i)
+        sb += wg_cnt[i];
+    if (cnt > 0 && (sb < 0 || sb + cnt > 3 * a.count * K))
+        cnt = 0;  // (not reachable while the counter is cleared every step)
     if (lane == 0) {
         t.HAS[x] = cnt > 0 ? 1 : 0;
         t.slot0[x] = cnt > 0 ? sb : -1;
@@ -293,19 +256,6 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_fwd(StepArgs a, TrainDim
 }
 
 // ------------------------------------------------------------------------------------------
-__device__ inline float block_sum(float v, float *red)
-{
-    v = wave_sum_uniform(v);
-    if ((threadIdx.x & (kWave - 1)) == 0)
-        red[threadIdx.x / kWave] = v;
-    __syncthreads();
-    float s = 0.0f;
-    for (int w = 0; w < kTrThreads / kWave; ++w)
-        s += red[w];
-    __syncthreads();
-    return s;
-}
-
 __device__ inline int row_of_entry_tr(const QuerySet &qs, int i, int entries)
 {
     int s = qs.slot[i];
@@ -542,74 +492,100 @@ __global__ void __launch_bounds__(kTrScatterThreads) k_tr_scatter(StepArgs a, Pa
 }
 
 // ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(kTrThreads) k_tr_gru_bwd(StepArgs a, PackedWeights pw, TrainDims d, TrainBufs t)
+// The GRU's backward pass runs as contractions over the applied winners' rows with three small
+// kernels around them (one wavefront per winner): the message rows as the step found the memory
+// (k_tr_gru_msg); after GI = MSG W_i^T + b_i and GH = MSG[:, :M] W_h^T + b_h the gates and the
+// gradients of their pre-activations (k_tr_gru_gates); after DPHI = DGI W_i[:, 2M : 2M + T] the
+// time encoding's gradient (k_tr_gru_time).
+__device__ inline bool win_ok(const StepArgs &a, const WinDesc &w)
 {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    return w.node >= 0 && (int64_t)w.node < a.num_nodes && w.other >= 0 && (int64_t)w.other < a.num_nodes &&
+           w.entry >= 0 && w.entry < 2 * a.msg_count && w.b >= 0 && w.b < a.msg_count;
+}
+
+__global__ void __launch_bounds__(kTrThreads) k_tr_gru_msg(StepArgs a, PackedWeights pw, TrainDims d, TrainBufs t)
+{
     int n_win = *a.n_win;
     n_win = n_win < 2 * a.msg_count ? n_win : 2 * a.msg_count;
-    const int r = (int)blockIdx.x;
-    if (r >= n_win)
-        return;
     const int M = d.M, T = d.T, F = d.F, D = d.Dmsg;
-    float *m = (float *)smem;     // [Dmsg]
-    float *gi = m + D;            // [3M]
-    float *gh = gi + 3 * M;       // [3M]
-    float *dgi = gh + 3 * M;      // [3M]
-    float *dgh = dgi + 3 * M;     // [3M]
-    const WinDesc w = a.win[r];
-    const bool ok = w.node >= 0 && (int64_t)w.node < a.num_nodes && w.other >= 0 && (int64_t)w.other < a.num_nodes &&
-                    w.entry >= 0 && w.entry < 2 * a.msg_count && w.b >= 0 && w.b < a.msg_count;
-    const double dt = ok ? w.t - a.lu[w.node] : 0.0;
-    for (int j = threadIdx.x; j < D; j += kTrThreads) {
-        float v = 0.0f;
-        if (ok) {
-            if (j < M)
-                v = a.mem[(size_t)w.node * M + j];
-            else if (j < 2 * M)
-                v = a.mem[(size_t)w.other * M + (j - M)];
-            else if (j < 2 * M + T)
-                v = time_enc(pw.time_w_rev[j - 2 * M], pw.time_b_rev[j - 2 * M], dt);
-            else
-                v = a.edge_feat[(size_t)(a.msg_first_eid + w.b) * F + (j - 2 * M - T)];
+    const int lane = lane_id();
+    for (int r = (int)blockIdx.x * kRowWaves + wave_id(); r < n_win; r += (int)gridDim.x * kRowWaves) {
+        const WinDesc w = a.win[r];
+        const bool ok = win_ok(a, w);
+        const double dt = ok ? w.t - a.lu[w.node] : 0.0;
+        for (int j = lane; j < D; j += kWave) {
+            float v = 0.0f;
+            if (ok) {
+                if (j < M)
+                    v = a.mem[(size_t)w.node * M + j];
+                else if (j < 2 * M)
+                    v = a.mem[(size_t)w.other * M + (j - M)];
+                else if (j < 2 * M + T)
+                    v = time_enc(pw.time_w_rev[j - 2 * M], pw.time_b_rev[j - 2 * M], dt);
+                else
+                    v = a.edge_feat[(size_t)(a.msg_first_eid + w.b) * F + (j - 2 * M - T)];
+            }
+            t.MSG[(size_t)r * D + j] = v;
         }
-        m[j] = v;
-        t.MSG[(size_t)r * D + j] = v;
     }
-    __syncthreads();
-    matvec_t(t.T_i, D, 3 * M, m, t.b_i, gi);
-    matvec_t(t.T_h, M, 3 * M, m, t.b_h, gh);  // h = s_self = the first M entries of the message
-    __syncthreads();
-    for (int j = threadIdx.x; j < M; j += kTrThreads) {
-        const float rg = 1.0f / (1.0f + expf(-(gi[j] + gh[j])));
-        const float zg = 1.0f / (1.0f + expf(-(gi[M + j] + gh[M + j])));
-        const float ng = tanhf(gi[2 * M + j] + rg * gh[2 * M + j]);
-        const float dh = ok ? t.D_STAG[(size_t)w.entry * M + j] : 0.0f;
-        const float dn = dh * (1.0f - zg);
-        const float dz = dh * (m[j] - ng);
-        const float dpre_n = dn * (1.0f - ng * ng);
-        const float dpre_r = dpre_n * gh[2 * M + j] * rg * (1.0f - rg);
-        const float dpre_z = dz * zg * (1.0f - zg);
-        dgi[j] = dpre_r;
-        dgi[M + j] = dpre_z;
-        dgi[2 * M + j] = dpre_n;
-        dgh[j] = dpre_r;
-        dgh[M + j] = dpre_z;
-        dgh[2 * M + j] = dpre_n * rg;
+}
+
+__global__ void __launch_bounds__(kTrThreads) k_tr_gru_gates(StepArgs a, TrainDims d, TrainBufs t)
+{
+    int n_win = *a.n_win;
+    n_win = n_win < 2 * a.msg_count ? n_win : 2 * a.msg_count;
+    const int M = d.M, D = d.Dmsg;
+    const int lane = lane_id();
+    for (int r = (int)blockIdx.x * kRowWaves + wave_id(); r < n_win; r += (int)gridDim.x * kRowWaves) {
+        const WinDesc w = a.win[r];
+        const bool ok = win_ok(a, w);
+        const float *gi = t.GI + (size_t)r * 3 * M, *gh = t.GH + (size_t)r * 3 * M;
+        float *dgi = t.DGI + (size_t)r * 3 * M, *dgh = t.DGH + (size_t)r * 3 * M;
+        for (int j = lane; j < M; j += kWave) {
+            const float rg = 1.0f / (1.0f + expf(-(gi[j] + gh[j])));
+            const float zg = 1.0f / (1.0f + expf(-(gi[M + j] + gh[M + j])));
+            const float ng = tanhf(gi[2 * M + j] + rg * gh[2 * M + j]);
+            const float dh = ok ? t.D_STAG[(size_t)w.entry * M + j] : 0.0f;
+            const float dn = dh * (1.0f - zg);
+            const float dz = dh * (t.MSG[(size_t)r * D + j] - ng);  // h = s_self = the first M entries of the message
+            const float dpre_n = dn * (1.0f - ng * ng);
+            const float dpre_r = dpre_n * gh[2 * M + j] * rg * (1.0f - rg);
+            const float dpre_z = dz * zg * (1.0f - zg);
+            dgi[j] = dpre_r;
+            dgi[M + j] = dpre_z;
+            dgi[2 * M + j] = dpre_n;
+            dgh[j] = dpre_r;
+            dgh[M + j] = dpre_z;
+            dgh[2 * M + j] = dpre_n * rg;
+        }
     }
-    __syncthreads();
-    for (int j = threadIdx.x; j < 3 * M; j += kTrThreads) {
-        t.DGI[(size_t)r * 3 * M + j] = dgi[j];
-        t.DGH[(size_t)r * 3 * M + j] = dgh[j];
+}
+
+// gw[j] += sum_r -sin(phase_rj) dt_r DPHI[r][j], gb[j] += sum_r -sin(phase_rj) DPHI[r][j] over the applied
+// winners: a thread per column and slice of the winners.  g_time: [gw | gb], 2T floats.
+__global__ void __launch_bounds__(kTrThreads) k_tr_gru_time(StepArgs a, PackedWeights pw, TrainDims d, TrainBufs t, float *g_time)
+{
+    int n_win = *a.n_win;
+    n_win = n_win < 2 * a.msg_count ? n_win : 2 * a.msg_count;
+    const int T = d.T;
+    const int j = (int)blockIdx.x * kTrThreads + (int)threadIdx.x;
+    if (j >= T)
+        return;
+    const int per = (n_win + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int lo = (int)blockIdx.y * per, hi = lo + per < n_win ? lo + per : n_win;
+    if (lo >= hi)
+        return;
+    const double w_rev = pw.time_w_rev[j], b_rev = pw.time_b_rev[j];
+    float gw = 0.0f, gb = 0.0f;
+    for (int r = lo; r < hi; ++r) {
+        const WinDesc w = a.win[r];
+        const double dt = win_ok(a, w) ? w.t - a.lu[w.node] : 0.0;
+        const float v = -time_enc_sin(w_rev, b_rev, dt) * t.DPHI[(size_t)r * T + j];
+        gw += (float)dt * v;
+        gb += v;
     }
-    // the message's time encoding: d m[2M + j] = sum_o W_i[o][2M + j] dgi[o]
-    for (int j = threadIdx.x; j < T; j += kTrThreads) {
-        float acc = 0.0f;
-        for (int o2 = 0; o2 < 3 * M; ++o2)
-            acc += t.W_i[(size_t)o2 * D + 2 * M + j] * dgi[o2];
-        const float sn = time_enc_sin(pw.time_w_rev[j], pw.time_b_rev[j], dt);
-        t.TGG[(size_t)r * 2 * T + j] = -sn * (float)dt * acc;
-        t.TGG[(size_t)r * 2 * T + T + j] = -sn * acc;
-    }
+    atomicAdd(&g_time[j], gw);
+    atomicAdd(&g_time[T + j], gb);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -730,9 +706,9 @@ __global__ void __launch_bounds__(kTnWaves *kWave) k_gemm_tn(float *C, int ldc, 
 // on the matrix cores (fp32 16x16x4).  A and W are both k-contiguous: a forward product takes the
 // weight matrix as stored ([out x in]), a backward product dX = dY W its transposed copy
 // ([in x out]).  A workgroup takes 32 rows; each of its four wavefronts one block of 32 columns
-// (blockIdx.y counts groups of four column blocks).  A lane loads four consecutive k of its row per step (k = k0 + 4 g + v
-// for lane group g: the four groups cover 16 k, and the v-th products of a step pair the same k in
-// both operands).
+// (blockIdx.y counts groups of four column blocks; the workgroups stride over the row blocks).  A lane
+// loads four consecutive k of its row per step (k = k0 + 4 g + v for lane group g: the four groups
+// cover 16 k, and the v-th products of a step pair the same k in both operands).
 struct RowGemm {
     const float *A, *W, *A2, *W2, *bias;
     float *C;
@@ -746,6 +722,14 @@ struct RowGemm {
     const int32_t *remap_nu; // NULL, or: output row of r is r below min(*remap_nu, remap_2b), else remap_2b + (r - that)
     int remap_2b;
     int vecA, vecW, vecA2, vecW2;  // operand rows are 16-byte aligned: four k in one load
+    // two products that share A in one launch: columns n >= n_split (n_split > 0) take the weight rows
+    // W_hi[n - n_split] and bias_hi[n - n_split] and go to C_hi[row][n - n_split]; rowmask then covers
+    // the columns below n_split only
+    int n_split;
+    const float *W_hi, *bias_hi;
+    float *C_hi;
+    int ldc_hi;
+    int ldw_hi, Kd_hi;  // 0: as W; else the rows of W_hi are Kd_hi <= Kd long (A's columns beyond count as 0 for them)
 };
 
 // Four consecutive k of one operand row.  VEC (rows 16-byte aligned, Kd a multiple of 4): one load,
@@ -774,27 +758,25 @@ template <bool VEC>
 __global__ void __launch_bounds__(256) k_rowgemm(RowGemm p)
 {
     const int rows = row_count(p.rc);
-    const int r0 = (int)blockIdx.x * 32;
-    if (r0 >= rows)
-        return;
     const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
     const int c = lane & 15, g = lane >> 4;
-    // the two rows whose operand this lane loads (rows r0 + c and r0 + 16 + c)
-    size_t arow[2];
-    bool aok[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int r = r0 + 16 * i + c;
-        const bool ok = r < rows;
-        arow[i] = (size_t)(ok ? r : 0);
-        aok[i] = ok;
-    }
     const int tiles_n = (p.N + 31) / 32;
     const int tn = (int)blockIdx.y * 4 + w;  // this wavefront's block of 32 columns
     if (tn >= tiles_n)
         return;
-    {
-        const int n0 = tn * 32;
+    const int n0 = tn * 32;
+    const int split = p.n_split > 0 ? p.n_split : p.N;
+    for (int r0 = (int)blockIdx.x * 32; r0 < rows; r0 += (int)gridDim.x * 32) {
+        // the two rows whose operand this lane loads (rows r0 + c and r0 + 16 + c)
+        size_t arow[2];
+        bool aok[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int r = r0 + 16 * i + c;
+            const bool ok = r < rows;
+            arow[i] = (size_t)(ok ? r : 0);
+            aok[i] = ok;
+        }
         floatx4 acc[2][2];
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -808,7 +790,15 @@ __global__ void __launch_bounds__(256) k_rowgemm(RowGemm p)
             const float *ar[2] = {A + arow[0] * lda, A + arow[1] * lda};
             const int nn0 = n0 + c, nn1 = n0 + 16 + c;
             const bool wok[2] = {nn0 < p.N, nn1 < p.N};
-            const float *wr[2] = {W + (size_t)(wok[0] ? nn0 : 0) * ldw, W + (size_t)(wok[1] ? nn1 : 0) * ldw};
+            const float *wr[2];
+            int wkd[2];  // length of the lane's weight rows
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int nn = wok[i] ? (i ? nn1 : nn0) : 0;
+                const bool hi = nn >= split;  // (no second pass with a split)
+                wr[i] = hi ? p.W_hi + (size_t)(nn - split) * (p.ldw_hi ? p.ldw_hi : ldw) : W + (size_t)nn * ldw;
+                wkd[i] = hi && p.Kd_hi ? p.Kd_hi : Kd;
+            }
             constexpr int kU = 4;  // steps of 16 k whose loads are issued together
             for (int k0 = 0; k0 < Kd; k0 += 16 * kU) {
                 floatx4 av[kU][2], wv[kU][2];
@@ -818,7 +808,7 @@ __global__ void __launch_bounds__(256) k_rowgemm(RowGemm p)
 #pragma unroll
                     for (int i = 0; i < 2; ++i) {
                         av[u][i] = load_k4<VEC>(ar[i], kk, Kd, aok[i], vA);
-                        wv[u][i] = load_k4<VEC>(wr[i], kk, Kd, wok[i], vW);
+                        wv[u][i] = load_k4<VEC>(wr[i], kk, wkd[i], wok[i], vW);
                     }
                 }
 #pragma unroll
@@ -856,14 +846,19 @@ __global__ void __launch_bounds__(256) k_rowgemm(RowGemm p)
                     const int n = n0 + 16 * j + c;
                     if (n >= p.N)
                         continue;
-                    float val = acc[i][j][v] + (p.bias ? p.bias[n] : 0.0f);
+                    const bool hi = n >= split;
+                    const float *bias = hi ? p.bias_hi : p.bias;
+                    float val = acc[i][j][v] + (bias ? bias[hi ? n - split : n] : 0.0f);
                     if (p.relu)
                         val = fmaxf(val, 0.0f);
                     if (p.gate && !(p.gate[(size_t)orow * p.ldg + n] > 0.0f))
                         val = 0.0f;
-                    if (dead)
+                    if (dead && !hi)
                         val = 0.0f;
-                    p.C[(size_t)orow * p.ldc + n] = val;
+                    if (hi)
+                        p.C_hi[(size_t)orow * p.ldc_hi + (n - split)] = val;
+                    else
+                        p.C[(size_t)orow * p.ldc + n] = val;
                 }
             }
     }
@@ -885,23 +880,6 @@ __global__ void __launch_bounds__(256) k_colsum(float *out, const float *A, int 
         acc += A[(size_t)r * lda + j];
     if (lo < hi)
         atomicAdd(&out[j], acc);
-}
-
-__global__ void k_loss_sum(const float *terms, int n, float *loss_out)
-{
-    __shared__ float red[256];
-    float acc = 0.0f;
-    for (int i = threadIdx.x; i < n; i += 256)
-        acc += terms[i];
-    red[threadIdx.x] = acc;
-    __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-        if ((int)threadIdx.x < s)
-            red[threadIdx.x] += red[threadIdx.x + s];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0)
-        *loss_out = red[0];
 }
 
 __global__ void k_sgd(float *P, const float *G, size_t n, float lr)
@@ -930,10 +908,31 @@ __global__ void k_transpose(TransposeJobs J)  // dst[c][r] = src[r][c]
     }
 }
 
-__global__ void __launch_bounds__(256) k_tr_commit(StepArgs a, int M)
+// The step's last kernel: the memory overwrite (the GRU's backward read the memory as the step found
+// it); one more workgroup adds up the loss terms (terms != NULL).
+__global__ void __launch_bounds__(256) k_tr_commit(StepArgs a, int M, int commit_blocks, const float *terms, int n_terms,
+                                                   float *loss_out)
 {
-    overwrite_memory(a, M, (int)(blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave),
-                     (int)(gridDim.x * (blockDim.x / kWave)));
+    if ((int)blockIdx.x < commit_blocks) {
+        overwrite_memory(a, M, (int)(blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave),
+                         (int)(commit_blocks * (blockDim.x / kWave)));
+        return;
+    }
+    __shared__ float red[256];
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int i = threadIdx.x; i < n_terms; i += 4 * 256)
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            acc[u] += i + u * 256 < n_terms ? terms[i + u * 256] : 0.0f;
+    red[threadIdx.x] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    __syncthreads();
+    for (int st = 128; st > 0; st >>= 1) {
+        if ((int)threadIdx.x < st)
+            red[threadIdx.x] += red[threadIdx.x + st];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0)
+        *loss_out = red[0];
 }
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
@@ -1037,7 +1036,9 @@ static TrainLayout train_layout(const Dims &d, void *base)
     b.MSG = take(U * D);
     b.DGI = take(U * 3 * M);
     b.DGH = take(U * 3 * M);
-    b.TGG = take(U * 2 * T);
+    b.GI = take(U * 3 * M);
+    b.GH = take(U * 3 * M);
+    b.DPHI = take(U * T);
     b.n_rows = (int32_t *)take(64);
     b.slot0 = (int32_t *)take(R);
     L.pack_scratch = base ? p + off : nullptr;
@@ -1052,23 +1053,19 @@ static TrainLayout train_layout(const Dims &d, void *base)
     return L;
 }
 
-static int gru_bwd_lds(const Dims &d) { return 4 * (d.Dmsg + 12 * d.M); }
 static int scatter_lds(const Dims &d) { return 4 * kScatterSlots * (d.M + 1); }
 
 size_t train_workspace_bytes(const Dims &d) { return train_layout(d, nullptr).bytes; }
 
 hipError_t prepare_train(const Dims &d)
 {
-    hipError_t e = hipFuncSetAttribute((const void *)k_tr_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, scatter_lds(d));
-    if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void *)k_tr_gru_bwd, hipFuncAttributeMaxDynamicSharedMemorySize, gru_bwd_lds(d));
-    return e;
+    return hipFuncSetAttribute((const void *)k_tr_scatter, hipFuncAttributeMaxDynamicSharedMemorySize, scatter_lds(d));
 }
 
 bool train_supported(const Dims &d)
 {
     // (the attention kernels keep slot k of head h in lane h * K + k of a query's wavefront)
-    return d.prec == TIG_FP32 && gru_bwd_lds(d) <= 160 * 1024 && scatter_lds(d) <= 64 * 1024 && d.H * d.K <= kWave;
+    return d.prec == TIG_FP32 && scatter_lds(d) <= 64 * 1024 && d.H * d.K <= kWave;
 }
 
 static hipError_t transpose_all(const Dims &d, const TrainLayout &L, hipStream_t s)
@@ -1166,8 +1163,10 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
         return g;
     };
     auto run = [&](const RowGemm &g) {
-        const dim3 grid((g.rc.rows_max + 31) / 32, ((g.N + 31) / 32 + 3) / 4);
-        const bool all_vec = g.vecA && g.vecW && g.Kd % 4 == 0 && (!g.A2 || (g.vecA2 && g.vecW2 && g.Kd2 % 4 == 0));
+        // (the row count is known on the device only: at most 1024 row blocks are launched and stride)
+        const int row_blocks = (g.rc.rows_max + 31) / 32;
+        const dim3 grid(row_blocks < 1024 ? row_blocks : 1024, ((g.N + 31) / 32 + 3) / 4);
+        const bool all_vec = g.vecA && g.vecW && g.Kd % 4 == 0 && g.Kd_hi % 4 == 0 && g.ldw_hi % 4 == 0 && (!g.A2 || (g.vecA2 && g.vecW2 && g.Kd2 % 4 == 0));
         if (all_vec)
             hipLaunchKernelGGL(k_rowgemm<true>, grid, dim3(256), 0, s, g);
         else
@@ -1175,10 +1174,14 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
     };
     const dim3 per_row((R + kRowWaves - 1) / kRowWaves);
     // ---- forward, direct form
-    hipLaunchKernelGGL(k_tr_gather, per_row, dim3(kTrThreads), 0, s, a, pwv, td, b);
+    hipLaunchKernelGGL(k_tr_gather, dim3((R + kGatherWaves - 1) / kGatherWaves), dim3(kGatherWaves * kWave), 0, s, a, pwv, td, b);
     run(layer(b.QV, da, b.QIN, da, b.W_Q, da, b.b_Q, da, da));
-    run(layer(b.KP, da, b.KV, dkv, b.W_K, dkv, b.b_K, da, dkv, true));
-    run(layer(b.VP, da, b.KV, dkv, b.W_V, dkv, b.b_V, da, dkv, true));
+    {   // key and value projections of the filled slots in one launch (they share the rows)
+        RowGemm g = layer(b.KP, da, b.KV, dkv, b.W_K, dkv, b.b_K, 2 * da, dkv, true);
+        g.n_split = da, g.W_hi = b.W_V, g.bias_hi = b.b_V, g.C_hi = b.VP, g.ldc_hi = da;
+        g.vecW = g.vecW && vec_ok(b.W_V, dkv);
+        run(g);
+    }
     hipLaunchKernelGGL(k_tr_attn_fwd, per_row, dim3(kTrThreads), 0, s, a, td, b);
     {   // attn = W_O o + b_O into the head of the merge layer's input; the zero vector without neighbours
         RowGemm g = layer(b.X1, da + M, b.O_, da, b.W_O, da, b.b_O, da, da);
@@ -1214,10 +1217,11 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
         run(g);
     }
     {   // [d_attn | d s_u] = W_m1^T dz1; without neighbours attn is the constant 0
-        RowGemm g = layer(b.D_ATTN, da, b.DZ1, E, b.T_m1, E, nullptr, da, E);
+        RowGemm g = layer(b.D_ATTN, da, b.DZ1, E, b.T_m1, E, nullptr, da + M, E);
         g.rowmask = b.HAS;
+        g.n_split = da, g.W_hi = b.T_m1 + (size_t)da * E, g.bias_hi = nullptr, g.C_hi = b.DSU, g.ldc_hi = M;
+        g.vecW = g.vecW && vec_ok(g.W_hi, E);
         run(g);
-        run(layer(b.DSU, M, b.DZ1, E, b.T_m1 + (size_t)da * E, E, nullptr, M, E));
     }
     run(layer(b.DOUT, da, b.D_ATTN, da, b.T_O, da, nullptr, da, da));
     hipLaunchKernelGGL(k_tr_attn_bwd, per_row, dim3(kTrThreads), 0, s, a, td, b);
@@ -1230,8 +1234,23 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
     }
     hipLaunchKernelGGL(k_tr_scatter, dim3((R + kScatterRows - 1) / kScatterRows), dim3(kTrScatterThreads), scatter_lds(d), s, a,
                        pwv, td, b);
-    if (a.msg_count > 0)
-        hipLaunchKernelGGL(k_tr_gru_bwd, dim3(2 * a.msg_count), dim3(kTrThreads), gru_bwd_lds(d), s, a, pwv, td, b);
+    if (a.msg_count > 0) {
+        // GRU backward over the applied winners (their number is known on the device only)
+        const int wg = (2 * a.msg_count + kRowWaves - 1) / kRowWaves;
+        const dim3 per_win(wg < 256 ? wg : 256);
+        hipLaunchKernelGGL(k_tr_gru_msg, per_win, dim3(kTrThreads), 0, s, a, pwv, td, b);
+        RowGemm g = layer(b.GI, 3 * M, b.MSG, D, b.W_i, D, b.b_i, 6 * M, D);
+        g.rc = wins;
+        g.n_split = 3 * M, g.W_hi = b.W_h, g.ldw_hi = M, g.Kd_hi = M, g.bias_hi = b.b_h, g.C_hi = b.GH, g.ldc_hi = 3 * M;
+        g.vecW = g.vecW && vec_ok(b.W_h, M);
+        run(g);
+        hipLaunchKernelGGL(k_tr_gru_gates, per_win, dim3(kTrThreads), 0, s, a, td, b);
+        g = layer(b.DPHI, T, b.DGI, 3 * M, b.T_i + (size_t)2 * M * 3 * M, 3 * M, nullptr, T, 3 * M);
+        g.rc = wins;
+        run(g);
+        hipLaunchKernelGGL(k_tr_gru_time, dim3((T + kTrThreads - 1) / kTrThreads, 128), dim3(kTrThreads), 0, s, a, pwv, td, b,
+                           (float *)L.g.time_w);
+    }
     if ((e = hipGetLastError()) != hipSuccess)
         return e;
 
@@ -1248,7 +1267,7 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
                            ldb ? ldb : No, Mo, No, rc, n_slices, (float *)csum);
     };
     auto colsum = [&](const float *out, const float *A, int lda, int cols, const RowCount &rc) {
-        int n_slices = rc.rows_max / 512;
+        int n_slices = rc.rows_max / 64;
         n_slices = n_slices < 1 ? 1 : (n_slices > 256 ? 256 : n_slices);
         hipLaunchKernelGGL(k_colsum, dim3((cols + 255) / 256, n_slices), dim3(256), 0, s, (float *)out, A, lda, cols, rc,
                            n_slices);
@@ -1269,13 +1288,14 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
     if (a.msg_count > 0) {
         gemm(L.g.W_i, L.g.b_i, 3 * M, D, b.DGI, b.MSG, wins);
         gemm(L.g.W_h, L.g.b_h, 3 * M, M, b.DGH, b.MSG, wins, D);  // h = the first M columns of the message rows
-        colsum(L.g.time_w, b.TGG, 2 * T, 2 * T, wins);
     }
-    if (loss_out)
-        hipLaunchKernelGGL(k_loss_sum, dim3(1), dim3(256), 0, s, b.LOSS, 2 * B, loss_out);
     // the memory overwrite comes last: the GRU's backward read the memory as the step found it
-    if (a.msg_count > 0)
-        hipLaunchKernelGGL(k_tr_commit, dim3(32), dim3(256), 0, s, a, M);
+    {
+        const int commit_blocks = a.msg_count > 0 ? 32 : 0;
+        if (commit_blocks + (loss_out ? 1 : 0) > 0)
+            hipLaunchKernelGGL(k_tr_commit, dim3(commit_blocks + (loss_out ? 1 : 0)), dim3(256), 0, s, a, M, commit_blocks,
+                               b.LOSS, 2 * B, loss_out);
+    }
     if ((e = hipGetLastError()) != hipSuccess)
         return e;
     if (lr != 0.0f) {

@@ -97,3 +97,12 @@ def test_c5_sampled_queries_against_bruteforce_definition(c5, c5_ctx):
                                                  w.num_neighbors)
         assert bc == nb_cnt[q]
         assert np.array_equal(bn, nb_node[q]) and np.array_equal(be, nb_eid[q]) and np.array_equal(bt, nb_ts[q])
+
+
+def test_c5_training_steps(c5, c5_ctx):
+    # the training step at the benchmark's size: loss, every gradient, state and outputs of two
+    # consecutive 4000-event batches (deferred order, as bench.py --train runs it)
+    from tests.test_gpu_train import run_training
+    c5_ctx("close")
+    first, bs = window(c5.w, 0.5, 2)
+    run_training(c5, bs, 0.0, "deferred", warm_at=first)

@@ -114,6 +114,16 @@ def test_c2_shape_gradients():
     run_training(b, [(12000, 120), (12120, 120)], 0.0, "deferred", warm_at=12000)
 
 
+def test_c5_shape_gradients():
+    # the row shapes of the one-GPU partition workload (100-dim memory, 8-dim edge features) on a
+    # short stream with its endpoint skew and time density; batches of more than a thousand events,
+    # so that hub rows are shared by hundreds of events
+    w5 = S.WORKLOADS["c5_gpu_partition"]
+    b = Bundle(w5.scaled(num_events=40000, n_src=20000, span=float(int(w5.span * 40000 / w5.num_events))))
+    run_training(b, [(30000, 1500), (31500, 1200)], 0.0, "deferred", warm_at=30000)
+    run_training(b, [(30000, 1000), (31000, 1000), (32000, 1000)], 1e-3, "update_first", warm_at=30000)
+
+
 def test_training_needs_fp32_negatives_and_a_workspace(c1):
     import torch
     from paper_2308_14129_amd import tig
