@@ -101,20 +101,6 @@ __global__ void k_phi0(double *out, const float *time_b, int T)
         out[i] = cos((double)time_b[i]);
 }
 
-// D[i*ld + j] = (double)A[i*lda + j] + (j < cols_b ? B[i*ldb + j] : 0)
-__global__ void k_add_cols(double *D, int ld, const float *A, int lda, const float *B, int ldb,
-                           int rows, int cols, int cols_b)
-{
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= rows * cols)
-        return;
-    const int i = idx / cols, j = idx % cols;
-    double v = (double)A[(size_t)i * lda + j];
-    if (j < cols_b)
-        v += (double)B[(size_t)i * ldb + j];
-    D[(size_t)i * ld + j] = v;
-}
-
 __global__ void k_copy_block(double *D, int ld, const float *A, int lda, int rows, int cols)
 {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
@@ -136,15 +122,12 @@ __device__ inline uint16_t f32_to_bf16_rne(float f)
 // fp32: 4 floats per lane.  bf16: 8 values per lane, split as x = hi + lo with hi = bf16(x),
 // lo = bf16(x - hi): 8 hi values (16 bytes) followed by the 8 lo values (16 bytes).
 // Either way an element takes 4 bytes and one wavefront operand load is contiguous.
-template <typename TS, bool BF16>
-__global__ void k_pack(void *out, const TS *W, int ld, int rows, int cols, int rows_p, int cols_p)
+// Element idx of a prepared [rows_p x cols_p] matrix: value(r, c) of the source (0 in the padding).
+template <bool BF16, typename F>
+__device__ inline void pack_element(void *out, size_t idx, int rows, int cols, int cols_p, F value)
 {
     constexpr int KB = BF16 ? 32 : 16;
     constexpr int VL = KB / 4;
-    const size_t total = (size_t)rows_p * cols_p;
-    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= total)
-        return;
     const int s = (int)(idx % VL);
     const int lane = (int)((idx / VL) % 64);
     const size_t blk = idx / (VL * 64);
@@ -155,7 +138,7 @@ __global__ void k_pack(void *out, const TS *W, int ld, int rows, int cols, int r
     const int c = kb * KB + VL * (lane / 16) + s;
     float v = 0.0f;
     if (r < rows && c < cols)
-        v = (float)W[(size_t)r * ld + c];
+        v = value(r, c);
     if (BF16) {
         uint16_t *o = (uint16_t *)out + (blk * 64 + lane) * 16 + s;
         const uint16_t hi = f32_to_bf16_rne(v);
@@ -163,6 +146,67 @@ __global__ void k_pack(void *out, const TS *W, int ld, int rows, int cols, int r
         o[8] = f32_to_bf16_rne(v - __uint_as_float((uint32_t)hi << 16));
     } else {
         ((float *)out)[idx] = v;
+    }
+}
+
+template <typename TS, bool BF16>
+__global__ void k_pack(void *out, const TS *W, int ld, int rows, int cols, int rows_p, int cols_p)
+{
+    const size_t total = (size_t)rows_p * cols_p;
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total)
+        return;
+    pack_element<BF16>(out, idx, rows, cols, cols_p, [&](int r, int c) { return (float)W[(size_t)r * ld + c]; });
+}
+
+// Everything the state update's kernels read, prepared in one launch (a training step rebuilds it
+// after every update of the masters): blockIdx.y names the piece -- 0, 1 the time encoding's
+// parameters in revolutions; 2, 3 the r and z gates' matrices with the hidden weights folded onto the
+// s_self columns (added in double precision); 4, 5 the n gate's input and hidden matrices; 6..9 the
+// bias vectors (b_ir + b_hr, b_iz + b_hz, b_in, b_hn).
+struct GruPackJob {
+    double *time_w_rev, *time_b_rev;
+    const float *time_w, *time_b, *W_i, *W_h, *b_i, *b_h;
+    void *Wr, *Wz, *Win, *Whn;
+    float *br, *bz, *bin, *bhn;
+    int M, T, Dmsg, Ng, Kg, Khn;
+};
+
+template <bool BF16>
+__global__ void k_pack_gru(GruPackJob j)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int piece = blockIdx.y, M = j.M, D = j.Dmsg;
+    if (piece < 2) {
+        if (idx < (size_t)j.T)
+            (piece ? j.time_b_rev : j.time_w_rev)[idx] = (double)(piece ? j.time_b : j.time_w)[idx] / 6.283185307179586476925286766559;
+    } else if (piece < 4) {
+        const float *Wi = j.W_i + (size_t)(piece - 2) * M * D, *Wh = j.W_h + (size_t)(piece - 2) * M * M;
+        if (idx < (size_t)j.Ng * j.Kg)
+            pack_element<BF16>(piece == 2 ? j.Wr : j.Wz, idx, M, D, j.Kg, [&](int r, int c) {
+                double v = (double)Wi[(size_t)r * D + c];
+                if (c < M)
+                    v += (double)Wh[(size_t)r * M + c];
+                return (float)v;
+            });
+    } else if (piece == 4) {
+        const float *W = j.W_i + (size_t)2 * M * D;
+        if (idx < (size_t)j.Ng * j.Kg)
+            pack_element<BF16>(j.Win, idx, M, D, j.Kg, [&](int r, int c) { return W[(size_t)r * D + c]; });
+    } else if (piece == 5) {
+        const float *W = j.W_h + (size_t)2 * M * M;
+        if (idx < (size_t)j.Ng * j.Khn)
+            pack_element<BF16>(j.Whn, idx, M, M, j.Khn, [&](int r, int c) { return W[(size_t)r * M + c]; });
+    } else if (idx < (size_t)j.Ng) {
+        const int i = (int)idx, g = piece - 6;  // 0: r, 1: z, 2: n (input side), 3: n (hidden side)
+        double v = 0.0;
+        if (i < M) {
+            if (g < 2)
+                v = (double)j.b_i[g * M + i] + (double)j.b_h[g * M + i];
+            else
+                v = (double)(g == 2 ? j.b_i : j.b_h)[2 * M + i];
+        }
+        (g == 0 ? j.br : g == 1 ? j.bz : g == 2 ? j.bin : j.bhn)[i] = (float)v;
     }
 }
 
@@ -229,7 +273,7 @@ PackedLayout layout(const Dims &d, void *base)
 }
 
 struct ScratchLayout {
-    double *phi0, *cQ, *A1, *a1, *G, *PR, *cvec, *gv, *Wr, *Wz, *dec, *decF, *bvec;
+    double *phi0, *cQ, *A1, *a1, *G, *PR, *cvec, *gv, *dec, *decF, *bvec;
     size_t bytes;
 };
 
@@ -245,8 +289,6 @@ ScratchLayout scratch_layout(const Dims &d, void *base)
     S.PR = c.take<double>((size_t)d.E * (d.H * d.dkvp + d.M));
     S.cvec = c.take<double>(d.E);
     S.gv = c.take<double>(d.da);
-    S.Wr = c.take<double>((size_t)d.M * d.Dmsg);
-    S.Wz = c.take<double>((size_t)d.M * d.Dmsg);
     S.dec = c.take<double>((size_t)2 * d.Ep * d.E);
     S.decF = c.take<double>((size_t)2 * d.Ep * d.E);
     S.bvec = c.take<double>(d.E);
@@ -285,31 +327,27 @@ hipError_t pack_weights(const Dims &d, const tig_weights &w, void *dst, void *sc
         TIG_TRY(launch_fill_zero(scratch, S.bytes, s));
 
     // time encoding parameters in revolutions: the kernels take cos(2 pi (w_rev x + b_rev))
-    hipLaunchKernelGGL(k_to_revolutions, grid(T), blk, 0, s, L.time_w_rev, w.time_w, T);
-    hipLaunchKernelGGL(k_to_revolutions, grid(T), blk, 0, s, L.time_b_rev, w.time_b, T);
+    if (!with_gru) {
+        hipLaunchKernelGGL(k_to_revolutions, grid(T), blk, 0, s, L.time_w_rev, w.time_w, T);
+        hipLaunchKernelGGL(k_to_revolutions, grid(T), blk, 0, s, L.time_b_rev, w.time_b, T);
+    }
 
-    // ---- GRU: gates r, z with the hidden weights folded onto the s_self columns ------------
+    // ---- GRU: gates r, z with the hidden weights folded onto the s_self columns; one launch --
     if (with_gru) {
-    const float *W_ir = w.W_i, *W_iz = w.W_i + (size_t)M * Dmsg, *W_in = w.W_i + (size_t)2 * M * Dmsg;
-    const float *W_hr = w.W_h, *W_hz = w.W_h + (size_t)M * M, *W_hn = w.W_h + (size_t)2 * M * M;
-    hipLaunchKernelGGL(k_add_cols, grid((size_t)M * Dmsg), blk, 0, s, S.Wr, Dmsg, W_ir, Dmsg, W_hr, M, M,
-                       Dmsg, M);
-    hipLaunchKernelGGL(k_add_cols, grid((size_t)M * Dmsg), blk, 0, s, S.Wz, Dmsg, W_iz, Dmsg, W_hz, M, M,
-                       Dmsg, M);
-    TIG_TRY(hipGetLastError());
-    TIG_TRY(pack<double>(s, d.prec, L.gru_Wr, S.Wr, Dmsg, M, Dmsg, d.Ng, d.Kg));
-    TIG_TRY(pack<double>(s, d.prec, L.gru_Wz, S.Wz, Dmsg, M, Dmsg, d.Ng, d.Kg));
-    TIG_TRY(pack<float>(s, d.prec, L.gru_Win, W_in, Dmsg, M, Dmsg, d.Ng, d.Kg));
-    TIG_TRY(pack<float>(s, d.prec, L.gru_Whn, W_hn, M, M, M, d.Ng, d.Khn));
-    hipLaunchKernelGGL(k_vec_f32, grid(d.Ng), blk, 0, s, L.gru_br, d.Ng, M, (const double *)nullptr,
-                       w.b_i, w.b_h);
-    hipLaunchKernelGGL(k_vec_f32, grid(d.Ng), blk, 0, s, L.gru_bz, d.Ng, M, (const double *)nullptr,
-                       w.b_i + M, w.b_h + M);
-    hipLaunchKernelGGL(k_vec_f32, grid(d.Ng), blk, 0, s, L.gru_bin, d.Ng, M, (const double *)nullptr,
-                       w.b_i + 2 * M, (const float *)nullptr);
-    hipLaunchKernelGGL(k_vec_f32, grid(d.Ng), blk, 0, s, L.gru_bhn, d.Ng, M, (const double *)nullptr,
-                       w.b_h + 2 * M, (const float *)nullptr);
-    TIG_TRY(hipGetLastError());
+        GruPackJob j;
+        j.time_w_rev = L.time_w_rev, j.time_b_rev = L.time_b_rev, j.time_w = w.time_w, j.time_b = w.time_b;
+        j.W_i = w.W_i, j.W_h = w.W_h, j.b_i = w.b_i, j.b_h = w.b_h;
+        j.Wr = L.gru_Wr, j.Wz = L.gru_Wz, j.Win = L.gru_Win, j.Whn = L.gru_Whn;
+        j.br = L.gru_br, j.bz = L.gru_bz, j.bin = L.gru_bin, j.bhn = L.gru_bhn;
+        j.M = M, j.T = T, j.Dmsg = Dmsg, j.Ng = d.Ng, j.Kg = d.Kg, j.Khn = d.Khn;
+        size_t most = (size_t)d.Ng * (d.Kg > d.Khn ? d.Kg : d.Khn);
+        most = most > (size_t)T ? most : (size_t)T;
+        const dim3 g2((unsigned)((most + kThreads - 1) / kThreads), 10);
+        if (d.prec == TIG_BF16_MFMA)
+            hipLaunchKernelGGL(k_pack_gru<true>, g2, blk, 0, s, j);
+        else
+            hipLaunchKernelGGL(k_pack_gru<false>, g2, blk, 0, s, j);
+        TIG_TRY(hipGetLastError());
     }
 
     if (with_embed) {

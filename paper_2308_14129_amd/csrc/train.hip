@@ -195,6 +195,28 @@ __global__ void __launch_bounds__(kGatherWaves *kWave) k_tr_gather(StepArgs a, P
     }
 }
 
+// <a, b> over n floats, by one lane (the lanes of a wavefront walk different rows: every load of the
+// walk is independent of the others, so a row costs one memory round trip, not one per element).
+// vec: both rows are 16-byte aligned and n is a multiple of 4.
+__device__ inline float lane_dot(const float *a, const float *b, int n, bool vec)
+{
+    float acc = 0.0f;
+    if (vec) {
+        floatx4 s4 = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll 8
+        for (int e = 0; e < n; e += 4) {
+            const floatx4 x = *(const floatx4 *)(a + e), y = *(const floatx4 *)(b + e);
+            s4 += x * y;
+        }
+        acc = (s4[0] + s4[1]) + (s4[2] + s4[3]);
+    } else {
+#pragma unroll 8
+        for (int e = 0; e < n; ++e)
+            acc += a[e] * b[e];
+    }
+    return acc;
+}
+
 // Scores, softmax and weighted value sum of one query per wavefront, from the projected rows
 // (QV, and KP / VP of its filled slots): lane h * K + k holds slot k of head h.
 __global__ void __launch_bounds__(kTrThreads) k_tr_attn_fwd(StepArgs a, TrainDims d, TrainBufs t)
@@ -220,17 +242,13 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_fwd(StepArgs a, TrainDim
     }
     const float *Qv = t.QV + (size_t)x * da;
     const float scale = 1.0f / sqrtf((float)dh);
+    const bool vec = dh % 4 == 0 && da % 4 == 0 && (((uintptr_t)t.QV | (uintptr_t)t.KP | (uintptr_t)t.VP) & 15) == 0;
     float sc = -INFINITY;
-    for (int h = 0; h < H; ++h)
-        for (int k = 0; k < cnt; ++k) {
-            const float *kp = t.KP + (sb + k) * da + h * dh;
-            float part = 0.0f;
-            for (int e = lane; e < dh; e += kWave)
-                part += Qv[h * dh + e] * kp[e];
-            const float s2 = wave_sum_uniform(part) * scale;
-            if (lane == h * K + k)
-                sc = s2;
-        }
+    {   // lane h * K + k forms the score of slot k under head h by itself
+        const int h = lane / K, k = lane - h * K;
+        if (lane < H * K && k < cnt)
+            sc = lane_dot(Qv + h * dh, t.KP + (sb + k) * da + h * dh, dh, vec) * scale;
+    }
     // softmax over the filled slots of the lane's head (every lane walks the head of lane % (H * K))
     const int hl = (lane % (H * K)) / K;
     float mx = -INFINITY;
@@ -366,17 +384,13 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_bwd(StepArgs a, TrainDim
     const float *dout = t.DOUT + (size_t)x * da;
     const float *Qv = t.QV + (size_t)x * da;
     const float scale = 1.0f / sqrtf((float)dh);
-    float dav = 0.0f;  // lane h * K + k: <VP[k] of head h, dout of head h>
-    for (int h = 0; h < H; ++h)
-        for (int k = 0; k < cnt; ++k) {
-            const float *vp = t.VP + (sb + k) * da + h * dh;
-            float part = 0.0f;
-            for (int e = lane; e < dh; e += kWave)
-                part += vp[e] * dout[h * dh + e];
-            const float s2 = wave_sum_uniform(part);
-            if (lane == h * K + k)
-                dav = s2;
-        }
+    const bool vec = dh % 4 == 0 && da % 4 == 0 && (((uintptr_t)t.DOUT | (uintptr_t)t.VP) & 15) == 0;
+    float dav = 0.0f;  // lane h * K + k: <VP[k] of head h, dout of head h>, formed by the lane itself
+    {
+        const int h = lane / K, k = lane - h * K;
+        if (lane < H * K && k < cnt)
+            dav = lane_dot(t.VP + (sb + k) * da + h * dh, dout + h * dh, dh, vec);
+    }
     const float pr = lane < H * K ? t.PROB[(size_t)x * H * K + lane] : 0.0f;  // (zero beyond the filled slots)
     const int hl = (lane % (H * K)) / K;
     float dot = 0.0f;
@@ -389,10 +403,11 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_bwd(StepArgs a, TrainDim
         const int h = j / dh;
         const float qv = Qv[j], dj = dout[j];
         float acc = 0.0f;
+        for (int k = 0; k < cnt; ++k)  // (loads only: the slots' round trips overlap)
+            acc += __shfl(dsv, h * K + k) * t.KP[(sb + k) * da + j];
         for (int k = 0; k < cnt; ++k) {
             const float ds = __shfl(dsv, h * K + k), pk = __shfl(pr, h * K + k);
             const size_t o = (sb + k) * da + j;
-            acc += ds * t.KP[o];
             if (in) {
                 t.DKP[o] = ds * qv * scale;
                 t.DVP[o] = pk * dj;
