@@ -177,20 +177,35 @@ __global__ void __launch_bounds__(kGatherWaves *kWave) k_tr_gather(StepArgs a, P
         if (j < M)
             t.X1[(size_t)x * (da + M) + da + j] = v;
     }
-    for (int k = 0; k < cnt; ++k) {
-        const int32_t rf = __shfl(my_ref, k), eid = __shfl(my_eid, k);
-        const double dt = t_q - shfl_f64(my_ts, k);
-        const float *row = state_row(a, M, rf);
-        float *dst = t.KV + ((size_t)sb + k) * dkv;
+    // kGC slots at a time: all their loads are issued before the first store (a store between two
+    // slots' loads would make every slot wait for its own round trip)
+    constexpr int kGC = 5;
+    for (int k0 = 0; k0 < cnt; k0 += kGC) {
+        const float *row[kGC];
+        int32_t eid[kGC];
+        double dt[kGC];
+#pragma unroll
+        for (int u = 0; u < kGC; ++u) {
+            const int k = k0 + u < cnt ? k0 + u : cnt - 1;  // (uniform; the shuffles are executed by every lane)
+            row[u] = state_row(a, M, __shfl(my_ref, k));
+            eid[u] = __shfl(my_eid, k);
+            dt[u] = t_q - shfl_f64(my_ts, k);
+        }
         for (int i = lane; i < dkv; i += kWave) {
-            float v;
-            if (i < M)
-                v = row ? row[i] : 0.0f;
-            else if (i < M + F)
-                v = eid >= 0 ? a.edge_feat[(size_t)eid * F + (i - M)] : 0.0f;
-            else
-                v = time_enc(pw.time_w_rev[i - M - F], pw.time_b_rev[i - M - F], dt);
-            dst[i] = v;
+            float v[kGC];
+#pragma unroll
+            for (int u = 0; u < kGC; ++u) {
+                if (i < M)
+                    v[u] = row[u] ? row[u][i] : 0.0f;
+                else if (i < M + F)
+                    v[u] = eid[u] >= 0 ? a.edge_feat[(size_t)eid[u] * F + (i - M)] : 0.0f;
+                else
+                    v[u] = time_enc(pw.time_w_rev[i - M - F], pw.time_b_rev[i - M - F], dt[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < kGC; ++u)
+                if (k0 + u < cnt)
+                    t.KV[((size_t)sb + k0 + u) * dkv + i] = v[u];
         }
     }
 }
@@ -465,19 +480,33 @@ __global__ void __launch_bounds__(kTrScatterThreads) k_tr_scatter(StepArgs a, Pa
             }
         }
         const int n_el = (cnt + 1) * M;
-        for (int e0 = 0; e0 < n_el; e0 += kWave) {  // (every lane stays in the loop: the shuffles read lanes up to cnt)
-            const bool in = e0 + lane < n_el;
-            const int e = in ? e0 + lane : 0;
-            const int k = e / M, i = e - k * M;
-            const int srow = __shfl(my_srow, k), lds = __shfl(my_lds, k);
-            if (in && srow >= 0) {
-                float v;
-                if (k < cnt)
-                    v = t.DKV[(sb + k) * dkv + i];
-                else
-                    v = t.DSU[(size_t)x * M + i] + (cnt > 0 ? t.DQIN[(size_t)x * da + i] : 0.0f);
-                atomicAdd(lds ? &acc[(size_t)(srow & (kScatterSlots - 1)) * M + i] : &t.D_STAG[(size_t)srow * M + i], v);
+        constexpr int kSC = 6;  // values a lane loads before it adds the first (their round trips overlap)
+        for (int e0 = 0; e0 < n_el; e0 += kSC * kWave) {  // (every lane stays in the loop: the shuffles read lanes up to cnt)
+            float v[kSC];
+            int srow[kSC], lds[kSC], col[kSC];
+#pragma unroll
+            for (int u = 0; u < kSC; ++u) {
+                const bool in = e0 + u * kWave + lane < n_el;
+                const int e = in ? e0 + u * kWave + lane : 0;
+                const int k = e / M, i = e - k * M;
+                srow[u] = __shfl(my_srow, k);
+                lds[u] = __shfl(my_lds, k);
+                col[u] = i;
+                if (!in)
+                    srow[u] = -1;
+                v[u] = 0.0f;
+                if (srow[u] >= 0) {
+                    if (k < cnt)
+                        v[u] = t.DKV[(sb + k) * dkv + i];
+                    else
+                        v[u] = t.DSU[(size_t)x * M + i] + (cnt > 0 ? t.DQIN[(size_t)x * da + i] : 0.0f);
+                }
             }
+#pragma unroll
+            for (int u = 0; u < kSC; ++u)
+                if (srow[u] >= 0)
+                    atomicAdd(lds[u] ? &acc[(size_t)(srow[u] & (kScatterSlots - 1)) * M + col[u]]
+                                     : &t.D_STAG[(size_t)srow[u] * M + col[u]], v[u]);
         }
         for (int j0 = 0; j0 < T; j0 += kWave) {
             const bool in = j0 + lane < T;
