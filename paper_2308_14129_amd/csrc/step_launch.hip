@@ -83,7 +83,7 @@ hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeight
     if ((e = stamp()) != hipSuccess)
         return e;
     if (sp.train) {
-        if ((e = launch_train(d, a, sp.train_ws, sp.packed, sp.pw_out, sp.lr, sp.loss_out, s)) != hipSuccess ||
+        if ((e = launch_train(d, a, sp.train_ws, sp.packed, sp.pw_out, sp.lr, sp.loss_out, s, sp.train_side)) != hipSuccess ||
             (e = stamp()) != hipSuccess)
             return e;
         // inspection outputs, and the query set's counter cleared for its next preparation

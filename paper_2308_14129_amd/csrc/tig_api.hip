@@ -88,6 +88,8 @@ struct tig_ctx {
     void *static_scratch;  // this device's copy of g_static_scratch
     bool embed_stale;      // training steps have moved the master weights since the attention / merge / decoder weights were last folded
     void *train_ws;        // training workspace (master weights, gradients, the backward pass's buffers), or NULL
+    TrainSide train_side;  // side stream and events of the training step's weight-gradient contractions
+    bool have_train_side;
     bool has_model;        // tig_init was given weights (the headline instance's prepared weights exist)
     void *mods_ws;         // workspace of an attached module selection, or NULL
     ModParams mods;        // ... and its parameters
@@ -730,6 +732,7 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
         sp.pw_out = &ctx->pw;
         sp.lr = train->lr;
         sp.loss_out = train->loss_out;
+        sp.train_side = ctx->have_train_side ? &ctx->train_side : nullptr;
     }
     const hipError_t e = launch_step(d, ctx->plan, ctx->pw, a, sp, ctx->stream, marks);
     // bit i: the interval between marks i and i + 1 held a kernel (a module selection's kernels fill
@@ -820,6 +823,22 @@ int tig_train_attach(tig_ctx *ctx, const tig_weights *weights, void *workspace, 
     if (workspace_bytes < train_workspace_bytes(ctx->d))
         return fail(ctx, TIG_ENOSPACE, "tig_train_attach: workspace too small");
     hipError_t e = prepare_train(ctx->d);
+    if (e == hipSuccess && !ctx->have_train_side) {
+        // (default priority; non-blocking: no implicit ordering against the legacy default stream)
+        TrainSide ts = {};
+        int made = 0;
+        e = hipStreamCreateWithFlags(&ts.stream, hipStreamNonBlocking);
+        for (; e == hipSuccess && made <= kTrainForks; ++made)
+            e = hipEventCreateWithFlags(made < kTrainForks ? &ts.fork[made] : &ts.join, hipEventDisableTiming);
+        if (e == hipSuccess) {
+            ctx->train_side = ts;
+            ctx->have_train_side = true;
+        } else if (ts.stream) {
+            for (int i = 0; i < made - 1; ++i)
+                (void)hipEventDestroy(i < kTrainForks ? ts.fork[i] : ts.join);
+            (void)hipStreamDestroy(ts.stream);
+        }
+    }
     if (e == hipSuccess)
         e = train_attach(ctx->d, *weights, workspace, ctx->packed, &ctx->pw, ctx->stream);
     if (e == hipSuccess)
@@ -1157,6 +1176,13 @@ void tig_destroy(tig_ctx *ctx)
             (void)hipEventDestroy(ctx->marks[i]);
     if (ctx->rows_seen_host)
         (void)hipHostFree(ctx->rows_seen_host);
+    if (ctx->have_train_side) {
+        (void)hipStreamSynchronize(ctx->train_side.stream);
+        for (int i = 0; i < kTrainForks; ++i)
+            (void)hipEventDestroy(ctx->train_side.fork[i]);
+        (void)hipEventDestroy(ctx->train_side.join);
+        (void)hipStreamDestroy(ctx->train_side.stream);
+    }
     delete ctx;
 }
 

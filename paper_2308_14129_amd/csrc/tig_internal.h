@@ -255,6 +255,7 @@ struct StepPlan {
     PackedWeights *pw_out;
     float lr;
     float *loss_out;
+    const struct TrainSide *train_side;  // NULL, or the side stream of the weight-gradient contractions
     int32_t *clear_first;       // a counter to clear ahead of everything, or NULL
     GruAhead ahead;             // GRU workgroups of the closing launch
     const struct ModParams *mods;  // a context with a module selection: its kernels instead of GRU, embedding and closing launches
@@ -281,8 +282,18 @@ hipError_t prepare_train(const Dims &d);
 hipError_t train_attach(const Dims &d, const tig_weights &w, void *workspace, void *packed, PackedWeights *pw,
                         hipStream_t s);
 hipError_t train_copy_out(const Dims &d, void *workspace, bool grads, const tig_weights &out, hipStream_t s);
+// A second stream for the weight-gradient contractions of a training step: they depend on nothing
+// but their own (delta, input) rows, so they run beside the rest of the backward pass; `fork[i]` is
+// recorded on the step's stream when the rows of group i are complete, `join` on the side stream
+// after the last contraction (the step's stream waits for it ahead of the update).
+constexpr int kTrainForks = 5;
+struct TrainSide {
+    hipStream_t stream;
+    hipEvent_t fork[kTrainForks], join;
+};
+// side: NULL = everything on s
 hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void *packed, PackedWeights *pw, float lr,
-                        float *loss_out, hipStream_t s);
+                        float *loss_out, hipStream_t s, const TrainSide *side);
 // after training steps with lr != 0 only the state update's prepared weights follow the masters: this
 // re-folds the rest (attention, merge MLP, decoder) for the fused inference kernels
 hipError_t train_refold_embed(const Dims &d, void *workspace, void *packed, PackedWeights *pw, hipStream_t s);

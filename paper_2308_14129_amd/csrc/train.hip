@@ -23,7 +23,9 @@
 //                   gates and the gradients of their pre-activations, time-encoding gradient
 //   k_gemm_tn       every weight gradient is dW = D^T X over the rows' stored (delta, input) pairs:
 //                   a [out x in] contraction over thousands of rows on the matrix cores (fp32
-//                   16x16x4), split over the row range, partial results added with atomics
+//                   16x16x4), split over the row range, partial results added with atomics; they run
+//                   on a second stream beside the rest of the backward pass (forked when their rows
+//                   are complete, joined ahead of the update)
 //   k_colsum        bias and time-encoding gradients: column sums of stored per-row values
 // Weight matrices are kept twice, [out x in] and transposed: a thread that owns an output reads
 // the transposed copy, a thread that owns an input the native one, so both directions are
@@ -1183,7 +1185,7 @@ hipError_t train_copy_out(const Dims &d, void *workspace, bool grads, const tig_
 // Everything of a training step after the GRU launch: forward in direct form, loss, backward, SGD,
 // re-folding of the packed weights, memory overwrite.
 hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void *packed, PackedWeights *pw, float lr,
-                        float *loss_out, hipStream_t s)
+                        float *loss_out, hipStream_t s, const TrainSide *side)
 {
     const TrainLayout L = train_layout(d, workspace);
     const TrainDims td = train_dims(d);
@@ -1217,6 +1219,35 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
             hipLaunchKernelGGL(k_rowgemm<false>, grid, dim3(256), 0, s, g);
     };
     const dim3 per_row((R + kRowWaves - 1) / kRowWaves);
+    // The weight gradients, C += A^T B together with the bias gradient csum += column sums of A, run on
+    // the side stream as soon as their rows are complete (fork(i): the rows of group i are), beside the
+    // rest of the backward pass, which leaves most compute units idle.
+    const hipStream_t ws = side ? side->stream : s;
+    hipError_t fe = hipSuccess;
+    auto fork = [&](int i) {
+        if (!side || fe != hipSuccess)
+            return;
+        fe = hipEventRecord(side->fork[i], s);
+        if (fe == hipSuccess)
+            fe = hipStreamWaitEvent(side->stream, side->fork[i], 0);
+    };
+    auto gemm = [&](const float *C, const float *csum, int Mo, int No, const float *A, const float *Bm, const RowCount &rc,
+                    int ldb = 0) {
+        const int tiles = ((Mo + 31) / 32) * ((No + 31) / 32);
+        // about 512 workgroups of eight wavefronts per contraction; a wavefront keeps at least 32 rows
+        int n_slices = 512 / tiles;
+        const int most = rc.rows_max / (32 * kTnWaves);
+        n_slices = n_slices > most ? most : n_slices;
+        n_slices = n_slices < 1 ? 1 : n_slices;
+        hipLaunchKernelGGL(k_gemm_tn, dim3(tiles * n_slices), dim3(kTnWaves * kWave), 0, ws, (float *)C, No, A, Mo, Bm,
+                           ldb ? ldb : No, Mo, No, rc, n_slices, (float *)csum);
+    };
+    auto colsum = [&](const float *out, const float *A, int lda, int cols, const RowCount &rc) {
+        int n_slices = rc.rows_max / 64;
+        n_slices = n_slices < 1 ? 1 : (n_slices > 256 ? 256 : n_slices);
+        hipLaunchKernelGGL(k_colsum, dim3((cols + 255) / 256, n_slices), dim3(256), 0, ws, (float *)out, A, lda, cols, rc,
+                           n_slices);
+    };
     // ---- forward, direct form
     hipLaunchKernelGGL(k_tr_gather, dim3((R + kGatherWaves - 1) / kGatherWaves), dim3(kGatherWaves * kWave), 0, s, a, pwv, td, b);
     run(layer(b.QV, da, b.QIN, da, b.W_Q, da, b.b_Q, da, da));
@@ -1249,6 +1280,9 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
         g.rc = pairs, g.relu = 1;
         run(g);
         hipLaunchKernelGGL(k_tr_logit, per_pair, dim3(kTrThreads), 0, s, a, td, b);
+        fork(0);
+        gemm(L.g.W_d1, L.g.b_d1, E, 2 * E, b.DY, b.CAT, pairs);
+        gemm(L.g.w_d2, L.g.b_d2, 1, E, b.DLOGIT, b.G_, pairs);
         g = layer(b.DCAT, 2 * E, b.DY, E, b.T_d1, E, nullptr, 2 * E, E);
         g.rc = pairs;
         run(g);
@@ -1259,6 +1293,9 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
         RowGemm g = layer(b.DZ1, E, b.D_EMB, E, b.T_m2, E, nullptr, E, E);
         g.gate = b.H1, g.ldg = E;
         run(g);
+        fork(1);  // merge MLP
+        gemm(L.g.W_m2, L.g.b_m2, E, E, b.D_EMB, b.H1, rows);
+        gemm(L.g.W_m1, L.g.b_m1, E, da + M, b.DZ1, b.X1, rows);
     }
     {   // [d_attn | d s_u] = W_m1^T dz1; without neighbours attn is the constant 0
         RowGemm g = layer(b.D_ATTN, da, b.DZ1, E, b.T_m1, E, nullptr, da + M, E);
@@ -1269,6 +1306,11 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
     }
     run(layer(b.DOUT, da, b.D_ATTN, da, b.T_O, da, nullptr, da, da));
     hipLaunchKernelGGL(k_tr_attn_bwd, per_row, dim3(kTrThreads), 0, s, a, td, b);
+    fork(2);  // attention
+    gemm(L.g.W_O, L.g.b_O, da, da, b.D_ATTN, b.O_, rows);
+    gemm(L.g.W_Q, L.g.b_Q, da, da, b.DQV, b.QIN, rows);
+    gemm(L.g.W_K, L.g.b_K, da, dkv, b.DKP, b.KV, live);
+    gemm(L.g.W_V, L.g.b_V, da, dkv, b.DVP, b.KV, live);
     run(layer(b.DQIN, da, b.DQV, da, b.T_Q, da, nullptr, da, da));
     {   // d kv = W_K^T dKP + W_V^T dVP over the filled slots
         RowGemm g = layer(b.DKV, dkv, b.DKP, da, b.T_K, da, nullptr, dkv, da, true);
@@ -1278,6 +1320,8 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
     }
     hipLaunchKernelGGL(k_tr_scatter, dim3((R + kScatterRows - 1) / kScatterRows), dim3(kTrScatterThreads), scatter_lds(d), s, a,
                        pwv, td, b);
+    fork(3);  // time encoding: per-row partial sums [gw | gb]; the two gradients are neighbours in the gradient buffer
+    colsum(L.g.time_w, b.TG, 2 * T, 2 * T, rows);
     if (a.msg_count > 0) {
         // GRU backward over the applied winners (their number is known on the device only)
         const int wg = (2 * a.msg_count + kRowWaves - 1) / kRowWaves;
@@ -1289,49 +1333,20 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
         g.vecW = g.vecW && vec_ok(b.W_h, M);
         run(g);
         hipLaunchKernelGGL(k_tr_gru_gates, per_win, dim3(kTrThreads), 0, s, a, td, b);
+        fork(4);  // state update
+        gemm(L.g.W_i, L.g.b_i, 3 * M, D, b.DGI, b.MSG, wins);
+        gemm(L.g.W_h, L.g.b_h, 3 * M, M, b.DGH, b.MSG, wins, D);  // h = the first M columns of the message rows
         g = layer(b.DPHI, T, b.DGI, 3 * M, b.T_i + (size_t)2 * M * 3 * M, 3 * M, nullptr, T, 3 * M);
         g.rc = wins;
         run(g);
         hipLaunchKernelGGL(k_tr_gru_time, dim3((T + kTrThreads - 1) / kTrThreads, 128), dim3(kTrThreads), 0, s, a, pwv, td, b,
                            (float *)L.g.time_w);
     }
-    if ((e = hipGetLastError()) != hipSuccess)
+    if ((e = hipGetLastError()) != hipSuccess || (e = fe) != hipSuccess)
         return e;
-
-    // weight gradient C += A^T B together with the bias gradient csum += column sums of A
-    auto gemm = [&](const float *C, const float *csum, int Mo, int No, const float *A, const float *Bm, const RowCount &rc,
-                    int ldb = 0) {
-        const int tiles = ((Mo + 31) / 32) * ((No + 31) / 32);
-        // about 512 workgroups of eight wavefronts per contraction; a wavefront keeps at least 32 rows
-        int n_slices = 512 / tiles;
-        const int most = rc.rows_max / (32 * kTnWaves);
-        n_slices = n_slices > most ? most : n_slices;
-        n_slices = n_slices < 1 ? 1 : n_slices;
-        hipLaunchKernelGGL(k_gemm_tn, dim3(tiles * n_slices), dim3(kTnWaves * kWave), 0, s, (float *)C, No, A, Mo, Bm,
-                           ldb ? ldb : No, Mo, No, rc, n_slices, (float *)csum);
-    };
-    auto colsum = [&](const float *out, const float *A, int lda, int cols, const RowCount &rc) {
-        int n_slices = rc.rows_max / 64;
-        n_slices = n_slices < 1 ? 1 : (n_slices > 256 ? 256 : n_slices);
-        hipLaunchKernelGGL(k_colsum, dim3((cols + 255) / 256, n_slices), dim3(256), 0, s, (float *)out, A, lda, cols, rc,
-                           n_slices);
-    };
-    // decoder
-    gemm(L.g.W_d1, L.g.b_d1, E, 2 * E, b.DY, b.CAT, pairs);
-    gemm(L.g.w_d2, L.g.b_d2, 1, E, b.DLOGIT, b.G_, pairs);
-    // merge MLP
-    gemm(L.g.W_m2, L.g.b_m2, E, E, b.D_EMB, b.H1, rows);
-    gemm(L.g.W_m1, L.g.b_m1, E, da + M, b.DZ1, b.X1, rows);
-    // attention
-    gemm(L.g.W_O, L.g.b_O, da, da, b.D_ATTN, b.O_, rows);
-    gemm(L.g.W_Q, L.g.b_Q, da, da, b.DQV, b.QIN, rows);
-    gemm(L.g.W_K, L.g.b_K, da, dkv, b.DKP, b.KV, live);
-    gemm(L.g.W_V, L.g.b_V, da, dkv, b.DVP, b.KV, live);
-    // time encoding: per-row partial sums [gw | gb]; the two gradients are neighbours in the gradient buffer
-    colsum(L.g.time_w, b.TG, 2 * T, 2 * T, rows);
-    if (a.msg_count > 0) {
-        gemm(L.g.W_i, L.g.b_i, 3 * M, D, b.DGI, b.MSG, wins);
-        gemm(L.g.W_h, L.g.b_h, 3 * M, M, b.DGH, b.MSG, wins, D);  // h = the first M columns of the message rows
+    if (side) {  // the step's stream goes on when the last weight gradient is complete
+        if ((e = hipEventRecord(side->join, side->stream)) != hipSuccess || (e = hipStreamWaitEvent(s, side->join, 0)) != hipSuccess)
+            return e;
     }
     // the memory overwrite comes last: the GRU's backward read the memory as the step found it
     {
