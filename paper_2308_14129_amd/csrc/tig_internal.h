@@ -286,7 +286,7 @@ hipError_t train_copy_out(const Dims &d, void *workspace, bool grads, const tig_
 // but their own (delta, input) rows, so they run beside the rest of the backward pass; `fork[i]` is
 // recorded on the step's stream when the rows of group i are complete, `join` on the side stream
 // after the last contraction (the step's stream waits for it ahead of the update).
-constexpr int kTrainForks = 5;
+constexpr int kTrainForks = 6;
 struct TrainSide {
     hipStream_t stream;
     hipEvent_t fork[kTrainForks], join;

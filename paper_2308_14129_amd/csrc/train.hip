@@ -71,10 +71,11 @@ struct TrainBufs {
     const float *T_i, *T_h, *T_Q, *T_K, *T_V, *T_O, *T_m1, *T_m2, *T_d1;
     // per distinct query (compact row x: sources / destinations first, then the negatives)
     float *QIN, *QV, *O_, *PROB, *X1, *H1, *D_EMB, *DZ1, *D_ATTN, *DQV, *TG;
+    float *QT, *KVB, *DKVB, *DQT;  // per head q~, the weighted sums of the key / value rows, and their gradients [H x dkv]
     float *DOUT, *DSU, *DQIN;  // gradients of the heads' outputs [da], of the own state through the merge layer [M], of the query row [da]
     int32_t *HAS;              // 1 for a query with at least one filled neighbour slot
     // per filled neighbour slot: slot k of query x is row slot0[x] + k (the filled slots of a step are packed)
-    float *KV, *KP, *VP, *DKP, *DVP, *DKV;
+    float *KV, *DKV;
     // per (pair, event): pair 0 = (source, destination), pair 1 = (source, negative); row p * count + b
     float *CAT, *DY, *G_, *DCAT, *DLOGIT, *LOSS;
     // per applied winner r, and per entry of the applied batch
@@ -234,8 +235,17 @@ __device__ inline float lane_dot(const float *a, const float *b, int n, bool vec
     return acc;
 }
 
-// Scores, softmax and weighted value sum of one query per wavefront, from the projected rows
-// (QV, and KP / VP of its filled slots): lane h * K + k holds slot k of head h.
+// The attention core runs in a re-associated form that is the same function in exact arithmetic: with
+// q~_h = W_K,h^T Qv_h the score of slot k under head h is <q~_h, kv_k> / sqrt(d_h) plus a constant
+// over the slots (the key bias), which the softmax cancels; and the head's output is
+// W_V,h (sum_k p_hk kv_k) + b_V,h because the p_hk sum to one.  Every matrix product of the attention
+// is then a product over QUERIES (q~, the output, and in the backward pass their transposes) instead
+// of over the three times as many filled neighbour slots; what is left per slot are dot products
+// and weighted sums of the raw key / value rows, done here by one wavefront per query.
+constexpr int kMaxTrainHeads = 4;
+
+// Scores, softmax, and the weighted sums KVB[x][h] = sum_k p_hk kv_k of one query per wavefront, from
+// QT = q~ and the raw rows KV of its filled slots: lane h * K + k holds slot k of head h.
 __global__ void __launch_bounds__(kTrThreads) k_tr_attn_fwd(StepArgs a, TrainDims d, TrainBufs t)
 {
     int n_u = *a.qs.n_u;
@@ -245,26 +255,27 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_fwd(StepArgs a, TrainDim
     if (x >= n_rows)
         return;
     const int lane = lane_id();
-    const int K = d.K, H = d.H, da = d.da, dh = d.dh;
+    const int K = d.K, H = d.H, dh = d.dh, dkv = d.dkv;
     const int q = x < n_u ? x : 2 * a.count + (x - n_u);
     int cnt = a.qs.cnt[q];
     cnt = cnt < 0 ? 0 : (cnt > K ? K : cnt);
     const size_t sb = slot_rows(a, t, x, K, cnt);
+    float *kvb = t.KVB + (size_t)x * H * dkv;
     if (cnt == 0) {
-        for (int j = lane; j < da; j += kWave)
-            t.O_[(size_t)x * da + j] = 0.0f;
+        for (int j = lane; j < H * dkv; j += kWave)
+            kvb[j] = 0.0f;
         if (lane < H * K)
             t.PROB[(size_t)x * H * K + lane] = 0.0f;
         return;
     }
-    const float *Qv = t.QV + (size_t)x * da;
+    const float *qt = t.QT + (size_t)x * H * dkv;
     const float scale = 1.0f / sqrtf((float)dh);
-    const bool vec = dh % 4 == 0 && da % 4 == 0 && (((uintptr_t)t.QV | (uintptr_t)t.KP | (uintptr_t)t.VP) & 15) == 0;
+    const bool vec = dkv % 4 == 0 && (((uintptr_t)t.QT | (uintptr_t)t.KV) & 15) == 0;
     float sc = -INFINITY;
     {   // lane h * K + k forms the score of slot k under head h by itself
         const int h = lane / K, k = lane - h * K;
         if (lane < H * K && k < cnt)
-            sc = lane_dot(Qv + h * dh, t.KP + (sb + k) * da + h * dh, dh, vec) * scale;
+            sc = lane_dot(qt + (size_t)h * dkv, t.KV + (sb + k) * dkv, dkv, vec) * scale;
     }
     // softmax over the filled slots of the lane's head (every lane walks the head of lane % (H * K))
     const int hl = (lane % (H * K)) / K;
@@ -279,14 +290,21 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_fwd(StepArgs a, TrainDim
     const float pr = mine ? ex / sum : 0.0f;
     if (lane < H * K)
         t.PROB[(size_t)x * H * K + lane] = pr;
-    for (int j0 = 0; j0 < da; j0 += kWave) {  // (every lane stays in the loop: the shuffles read lanes below H * K)
-        const int j = j0 + lane < da ? j0 + lane : da - 1;
-        const int h = j / dh;
-        float acc = 0.0f;
-        for (int k = 0; k < cnt; ++k)
-            acc += __shfl(pr, h * K + k) * t.VP[(sb + k) * da + j];
-        if (j0 + lane < da)
-            t.O_[(size_t)x * da + j] = acc;
+    for (int i0 = 0; i0 < dkv; i0 += kWave) {  // (every lane stays in the loop: the shuffles read lanes below H * K)
+        const bool in = i0 + lane < dkv;
+        const int i = in ? i0 + lane : dkv - 1;
+        float acc[kMaxTrainHeads] = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int k = 0; k < cnt; ++k) {
+            const float v = t.KV[(sb + k) * dkv + i];
+#pragma unroll
+            for (int h = 0; h < kMaxTrainHeads; ++h)
+                if (h < H)
+                    acc[h] += __shfl(pr, h * K + k) * v;
+        }
+#pragma unroll
+        for (int h = 0; h < kMaxTrainHeads; ++h)
+            if (h < H && in)
+                kvb[(size_t)h * dkv + i] = acc[h];
     }
 }
 
@@ -376,9 +394,9 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_pair_scatter(StepArgs a, Trai
 }
 
 // ------------------------------------------------------------------------------------------
-// Backward of scores / softmax / weighted sum of one query per wavefront: from the gradient of the
-// heads' outputs (DOUT) to the gradients of the projected query (DQV) and of the projected key /
-// value rows of its filled slots (DKP, DVP).
+// Backward of scores / softmax / weighted sums of one query per wavefront: from the gradient of the
+// weighted sums (DKVB) to the gradient of q~ (DQT) and to the gradients of the raw key / value rows of
+// its filled slots (DKV), which are complete with it.
 __global__ void __launch_bounds__(kTrThreads) k_tr_attn_bwd(StepArgs a, TrainDims d, TrainBufs t)
 {
     int n_u = *a.qs.n_u;
@@ -388,50 +406,60 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_bwd(StepArgs a, TrainDim
     if (x >= n_rows)
         return;
     const int lane = lane_id();
-    const int K = d.K, H = d.H, da = d.da, dh = d.dh;
+    const int K = d.K, H = d.H, dh = d.dh, dkv = d.dkv;
     const int q = x < n_u ? x : 2 * a.count + (x - n_u);
     int cnt = a.qs.cnt[q];
     cnt = cnt < 0 ? 0 : (cnt > K ? K : cnt);
     const size_t sb = slot_rows(a, t, x, K, cnt);
+    float *dqt = t.DQT + (size_t)x * H * dkv;
     if (cnt == 0) {
-        for (int j = lane; j < da; j += kWave)
-            t.DQV[(size_t)x * da + j] = 0.0f;
+        for (int j = lane; j < H * dkv; j += kWave)
+            dqt[j] = 0.0f;
         return;
     }
-    const float *dout = t.DOUT + (size_t)x * da;
-    const float *Qv = t.QV + (size_t)x * da;
+    const float *dkvb = t.DKVB + (size_t)x * H * dkv;
+    const float *qt = t.QT + (size_t)x * H * dkv;
     const float scale = 1.0f / sqrtf((float)dh);
-    const bool vec = dh % 4 == 0 && da % 4 == 0 && (((uintptr_t)t.DOUT | (uintptr_t)t.VP) & 15) == 0;
-    float dav = 0.0f;  // lane h * K + k: <VP[k] of head h, dout of head h>, formed by the lane itself
+    const bool vec = dkv % 4 == 0 && (((uintptr_t)t.DKVB | (uintptr_t)t.KV) & 15) == 0;
+    float dp = 0.0f;  // lane h * K + k: d p_hk = <kv_k, d KVB_h>, formed by the lane itself
     {
         const int h = lane / K, k = lane - h * K;
         if (lane < H * K && k < cnt)
-            dav = lane_dot(t.VP + (sb + k) * da + h * dh, dout + h * dh, dh, vec);
+            dp = lane_dot(t.KV + (sb + k) * dkv, dkvb + (size_t)h * dkv, dkv, vec);
     }
     const float pr = lane < H * K ? t.PROB[(size_t)x * H * K + lane] : 0.0f;  // (zero beyond the filled slots)
     const int hl = (lane % (H * K)) / K;
     float dot = 0.0f;
     for (int k = 0; k < cnt; ++k)
-        dot += __shfl(pr, hl * K + k) * __shfl(dav, hl * K + k);
-    const float dsv = pr * (dav - dot);
-    for (int j0 = 0; j0 < da; j0 += kWave) {  // (every lane stays in the loop: the shuffles read lanes below H * K)
-        const bool in = j0 + lane < da;
-        const int j = in ? j0 + lane : da - 1;
-        const int h = j / dh;
-        const float qv = Qv[j], dj = dout[j];
-        float acc = 0.0f;
-        for (int k = 0; k < cnt; ++k)  // (loads only: the slots' round trips overlap)
-            acc += __shfl(dsv, h * K + k) * t.KP[(sb + k) * da + j];
-        for (int k = 0; k < cnt; ++k) {
-            const float ds = __shfl(dsv, h * K + k), pk = __shfl(pr, h * K + k);
-            const size_t o = (sb + k) * da + j;
-            if (in) {
-                t.DKP[o] = ds * qv * scale;
-                t.DVP[o] = pk * dj;
-            }
+        dot += __shfl(pr, hl * K + k) * __shfl(dp, hl * K + k);
+    const float dsv = pr * (dp - dot) * scale;  // gradient of <q~_h, kv_k>
+    for (int i0 = 0; i0 < dkv; i0 += kWave) {  // (every lane stays in the loop: the shuffles read lanes below H * K)
+        const bool in = i0 + lane < dkv;
+        const int i = in ? i0 + lane : dkv - 1;
+        float g_kvb[kMaxTrainHeads], g_qt[kMaxTrainHeads], acc[kMaxTrainHeads];
+#pragma unroll
+        for (int h = 0; h < kMaxTrainHeads; ++h) {
+            g_kvb[h] = h < H ? dkvb[(size_t)h * dkv + i] : 0.0f;
+            g_qt[h] = h < H ? qt[(size_t)h * dkv + i] : 0.0f;
+            acc[h] = 0.0f;
         }
-        if (in)
-            t.DQV[(size_t)x * da + j] = acc * scale;
+        for (int k = 0; k < cnt; ++k) {
+            const float v = t.KV[(sb + k) * dkv + i];
+            float dk = 0.0f;  // d kv_k[i] = sum_h p_hk d KVB_h[i] + d s_hk q~_h[i]
+#pragma unroll
+            for (int h = 0; h < kMaxTrainHeads; ++h)
+                if (h < H) {
+                    const float ds = __shfl(dsv, h * K + k);
+                    acc[h] += ds * v;
+                    dk += __shfl(pr, h * K + k) * g_kvb[h] + ds * g_qt[h];
+                }
+            if (in)
+                t.DKV[(sb + k) * dkv + i] = dk;
+        }
+#pragma unroll
+        for (int h = 0; h < kMaxTrainHeads; ++h)
+            if (h < H && in)
+                dqt[(size_t)h * dkv + i] = acc[h];
     }
 }
 
@@ -654,9 +682,19 @@ __device__ inline int row_count(const RowCount &rc)
 // csum != NULL: also csum[Mo] += the column sums of A (the bias gradient that goes with the weight
 // gradient: A^T times a column of ones), by the workgroups of the first block column.
 constexpr int kTnWaves = 8;
+// blockIdx.y = z names one product of a batch (one per attention head): C + z * zC, A + z * zA,
+// B + z * zB, csum + z * zS (element offsets).
+struct TnBatch {
+    int zC, zA, zB, zS;
+};
 __global__ void __launch_bounds__(kTnWaves *kWave) k_gemm_tn(float *C, int ldc, const float *A, int lda, const float *B, int ldb,
-                                                              int Mo, int No, RowCount rc, int n_slices, float *csum)
+                                                              int Mo, int No, RowCount rc, int n_slices, float *csum, TnBatch zb)
 {
+    C += (size_t)blockIdx.y * zb.zC;
+    A += (size_t)blockIdx.y * zb.zA;
+    B += (size_t)blockIdx.y * zb.zB;
+    if (csum)
+        csum += (size_t)blockIdx.y * zb.zS;
     __shared__ float red[kTnWaves][1024];
     __shared__ float reds[kTnWaves][32];
     const int w = threadIdx.x / kWave;
@@ -776,6 +814,9 @@ struct RowGemm {
     float *C_hi;
     int ldc_hi;
     int ldw_hi, Kd_hi;  // 0: as W; else the rows of W_hi are Kd_hi <= Kd long (A's columns beyond count as 0 for them)
+    // a batch of products in one launch (one per attention head): product z = blockIdx.z reads A + z * zA,
+    // W + z * zW, bias + z * zBias and writes C + z * zC (element offsets)
+    int zA, zW, zC, zBias;
 };
 
 // Four consecutive k of one operand row.  VEC (rows 16-byte aligned, Kd a multiple of 4): one load,
@@ -830,7 +871,7 @@ __global__ void __launch_bounds__(256) k_rowgemm(RowGemm p)
             for (int j = 0; j < 2; ++j)
                 acc[i][j] = floatx4{0, 0, 0, 0};
         for (int pass = 0; pass < (p.A2 ? 2 : 1); ++pass) {
-            const float *A = pass ? p.A2 : p.A, *W = pass ? p.W2 : p.W;
+            const float *A = pass ? p.A2 : p.A + (size_t)blockIdx.z * p.zA, *W = pass ? p.W2 : p.W + (size_t)blockIdx.z * p.zW;
             const int lda = pass ? p.lda2 : p.lda, ldw = pass ? p.ldw2 : p.ldw, Kd = pass ? p.Kd2 : p.Kd;
             const int vA = pass ? p.vecA2 : p.vecA, vW = pass ? p.vecW2 : p.vecW;
             const float *ar[2] = {A + arow[0] * lda, A + arow[1] * lda};
@@ -893,7 +934,7 @@ __global__ void __launch_bounds__(256) k_rowgemm(RowGemm p)
                     if (n >= p.N)
                         continue;
                     const bool hi = n >= split;
-                    const float *bias = hi ? p.bias_hi : p.bias;
+                    const float *bias = hi ? p.bias_hi : (p.bias ? p.bias + (size_t)blockIdx.z * p.zBias : nullptr);
                     float val = acc[i][j][v] + (bias ? bias[hi ? n - split : n] : 0.0f);
                     if (p.relu)
                         val = fmaxf(val, 0.0f);
@@ -904,7 +945,7 @@ __global__ void __launch_bounds__(256) k_rowgemm(RowGemm p)
                     if (hi)
                         p.C_hi[(size_t)orow * p.ldc_hi + (n - split)] = val;
                     else
-                        p.C[(size_t)orow * p.ldc + n] = val;
+                        p.C[(size_t)blockIdx.z * p.zC + (size_t)orow * p.ldc + n] = val;
                 }
             }
     }
@@ -1068,10 +1109,10 @@ static TrainLayout train_layout(const Dims &d, void *base)
     b.DQIN = take(R * da);
     b.HAS = (int32_t *)take(R);
     b.KV = take(S * dkv);
-    b.KP = take(S * da);
-    b.VP = take(S * da);
-    b.DKP = take(S * da);
-    b.DVP = take(S * da);
+    b.QT = take(R * H * dkv);
+    b.KVB = take(R * H * dkv);
+    b.DKVB = take(R * H * dkv);
+    b.DQT = take(R * H * dkv);
     b.DKV = take(S * dkv);
     b.CAT = take(U * 2 * E);
     b.DY = take(U * E);
@@ -1111,7 +1152,7 @@ hipError_t prepare_train(const Dims &d)
 bool train_supported(const Dims &d)
 {
     // (the attention kernels keep slot k of head h in lane h * K + k of a query's wavefront)
-    return d.prec == TIG_FP32 && scatter_lds(d) <= 64 * 1024 && d.H * d.K <= kWave;
+    return d.prec == TIG_FP32 && scatter_lds(d) <= 64 * 1024 && d.H * d.K <= kWave && d.H <= kMaxTrainHeads;
 }
 
 static hipError_t transpose_all(const Dims &d, const TrainLayout &L, hipStream_t s)
@@ -1195,7 +1236,7 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
     if (e != hipSuccess)
         return e;
     const int B = a.count, R = 3 * B, K = d.K;
-    const int M = d.M, T = d.T, E = d.E, da = d.da, dkv = d.dkv, D = d.Dmsg;
+    const int M = d.M, T = d.T, E = d.E, H = d.H, da = d.da, dh = d.dh, dkv = d.dkv, D = d.Dmsg;
     const RowCount rows{b.n_rows, 0, 1, R}, live{b.n_live, 0, 1, R * K}, pairs{nullptr, 0, 1, 2 * B},
         wins{a.n_win, 0, 1, 2 * a.msg_count};
     // one layer product over all rows (or over the filled slots: `slots`)
@@ -1208,10 +1249,10 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
         g.vecA = vec_ok(A, lda), g.vecW = vec_ok(W, ldw);
         return g;
     };
-    auto run = [&](const RowGemm &g) {
+    auto run = [&](const RowGemm &g, int nz = 1) {
         // (the row count is known on the device only: at most 1024 row blocks are launched and stride)
         const int row_blocks = (g.rc.rows_max + 31) / 32;
-        const dim3 grid(row_blocks < 1024 ? row_blocks : 1024, ((g.N + 31) / 32 + 3) / 4);
+        const dim3 grid(row_blocks < 1024 ? row_blocks : 1024, ((g.N + 31) / 32 + 3) / 4, nz);
         const bool all_vec = g.vecA && g.vecW && g.Kd % 4 == 0 && g.Kd_hi % 4 == 0 && g.ldw_hi % 4 == 0 && (!g.A2 || (g.vecA2 && g.vecW2 && g.Kd2 % 4 == 0));
         if (all_vec)
             hipLaunchKernelGGL(k_rowgemm<true>, grid, dim3(256), 0, s, g);
@@ -1232,15 +1273,15 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
             fe = hipStreamWaitEvent(side->stream, side->fork[i], 0);
     };
     auto gemm = [&](const float *C, const float *csum, int Mo, int No, const float *A, const float *Bm, const RowCount &rc,
-                    int ldb = 0) {
+                    int ldb = 0, int lda = 0, int nz = 1, TnBatch zb = TnBatch{0, 0, 0, 0}) {
         const int tiles = ((Mo + 31) / 32) * ((No + 31) / 32);
         // about 512 workgroups of eight wavefronts per contraction; a wavefront keeps at least 32 rows
-        int n_slices = 512 / tiles;
+        int n_slices = 512 / (tiles * nz);
         const int most = rc.rows_max / (32 * kTnWaves);
         n_slices = n_slices > most ? most : n_slices;
         n_slices = n_slices < 1 ? 1 : n_slices;
-        hipLaunchKernelGGL(k_gemm_tn, dim3(tiles * n_slices), dim3(kTnWaves * kWave), 0, ws, (float *)C, No, A, Mo, Bm,
-                           ldb ? ldb : No, Mo, No, rc, n_slices, (float *)csum);
+        hipLaunchKernelGGL(k_gemm_tn, dim3(tiles * n_slices, nz), dim3(kTnWaves * kWave), 0, ws, (float *)C, No, A,
+                           lda ? lda : Mo, Bm, ldb ? ldb : No, Mo, No, rc, n_slices, (float *)csum, zb);
     };
     auto colsum = [&](const float *out, const float *A, int lda, int cols, const RowCount &rc) {
         int n_slices = rc.rows_max / 64;
@@ -1251,13 +1292,19 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
     // ---- forward, direct form
     hipLaunchKernelGGL(k_tr_gather, dim3((R + kGatherWaves - 1) / kGatherWaves), dim3(kGatherWaves * kWave), 0, s, a, pwv, td, b);
     run(layer(b.QV, da, b.QIN, da, b.W_Q, da, b.b_Q, da, da));
-    {   // key and value projections of the filled slots in one launch (they share the rows)
-        RowGemm g = layer(b.KP, da, b.KV, dkv, b.W_K, dkv, b.b_K, 2 * da, dkv, true);
-        g.n_split = da, g.W_hi = b.W_V, g.bias_hi = b.b_V, g.C_hi = b.VP, g.ldc_hi = da;
-        g.vecW = g.vecW && vec_ok(b.W_V, dkv);
-        run(g);
+    {   // q~_h = W_K,h^T Qv_h, every head in one launch
+        RowGemm g = layer(b.QT, H * dkv, b.QV, da, b.T_K, da, nullptr, dkv, dh);
+        g.zA = dh, g.zW = dh, g.zC = dkv;
+        g.vecA = g.vecA && dh % 4 == 0, g.vecW = g.vecW && dh % 4 == 0;
+        run(g, H);
     }
     hipLaunchKernelGGL(k_tr_attn_fwd, per_row, dim3(kTrThreads), 0, s, a, td, b);
+    {   // o_h = W_V,h KVB_h + b_V,h
+        RowGemm g = layer(b.O_, da, b.KVB, H * dkv, b.W_V, dkv, b.b_V, dh, dkv);
+        g.zA = dkv, g.zW = dh * dkv, g.zC = dh, g.zBias = dh;
+        g.vecA = g.vecA && dkv % 4 == 0, g.vecW = g.vecW && (dh * dkv) % 4 == 0;
+        run(g, H);
+    }
     {   // attn = W_O o + b_O into the head of the merge layer's input; the zero vector without neighbours
         RowGemm g = layer(b.X1, da + M, b.O_, da, b.W_O, da, b.b_O, da, da);
         g.rowmask = b.HAS;
@@ -1305,19 +1352,26 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
         run(g);
     }
     run(layer(b.DOUT, da, b.D_ATTN, da, b.T_O, da, nullptr, da, da));
-    hipLaunchKernelGGL(k_tr_attn_bwd, per_row, dim3(kTrThreads), 0, s, a, td, b);
-    fork(2);  // attention
-    gemm(L.g.W_O, L.g.b_O, da, da, b.D_ATTN, b.O_, rows);
-    gemm(L.g.W_Q, L.g.b_Q, da, da, b.DQV, b.QIN, rows);
-    gemm(L.g.W_K, L.g.b_K, da, dkv, b.DKP, b.KV, live);
-    gemm(L.g.W_V, L.g.b_V, da, dkv, b.DVP, b.KV, live);
-    run(layer(b.DQIN, da, b.DQV, da, b.T_Q, da, nullptr, da, da));
-    {   // d kv = W_K^T dKP + W_V^T dVP over the filled slots
-        RowGemm g = layer(b.DKV, dkv, b.DKP, da, b.T_K, da, nullptr, dkv, da, true);
-        g.A2 = b.DVP, g.lda2 = da, g.W2 = b.T_V, g.ldw2 = da, g.Kd2 = da;
-        g.vecA2 = vec_ok(b.DVP, da), g.vecW2 = vec_ok(b.T_V, da);
-        run(g);
+    {   // d KVB_h = W_V,h^T d o_h
+        RowGemm g = layer(b.DKVB, H * dkv, b.DOUT, da, b.T_V, da, nullptr, dkv, dh);
+        g.zA = dh, g.zW = dh, g.zC = dkv;
+        g.vecA = g.vecA && dh % 4 == 0, g.vecW = g.vecW && dh % 4 == 0;
+        run(g, H);
     }
+    hipLaunchKernelGGL(k_tr_attn_bwd, per_row, dim3(kTrThreads), 0, s, a, td, b);
+    fork(2);  // attention: dW_V,h = d o_h^T KVB_h, dW_K,h = Qv_h^T d q~_h over the queries (the key bias takes no gradient)
+    gemm(L.g.W_O, L.g.b_O, da, da, b.D_ATTN, b.O_, rows);
+    gemm(L.g.W_V, L.g.b_V, dh, dkv, b.DOUT, b.KVB, rows, H * dkv, da, H, TnBatch{dh * dkv, dh, dkv, dh});
+    gemm(L.g.W_K, nullptr, dh, dkv, b.QV, b.DQT, rows, H * dkv, da, H, TnBatch{dh * dkv, dh, dkv, 0});
+    {   // d Qv_h = W_K,h d q~_h
+        RowGemm g = layer(b.DQV, da, b.DQT, H * dkv, b.W_K, dkv, nullptr, dh, dkv);
+        g.zA = dkv, g.zW = dh * dkv, g.zC = dh;
+        g.vecA = g.vecA && dkv % 4 == 0, g.vecW = g.vecW && (dh * dkv) % 4 == 0;
+        run(g, H);
+    }
+    fork(5);
+    gemm(L.g.W_Q, L.g.b_Q, da, da, b.DQV, b.QIN, rows);
+    run(layer(b.DQIN, da, b.DQV, da, b.T_Q, da, nullptr, da, da));
     hipLaunchKernelGGL(k_tr_scatter, dim3((R + kScatterRows - 1) / kScatterRows), dim3(kTrScatterThreads), scatter_lds(d), s, a,
                        pwv, td, b);
     fork(3);  // time encoding: per-row partial sums [gw | gb]; the two gradients are neighbours in the gradient buffer
