@@ -308,6 +308,13 @@ k_gru(StepArgs a, GruJob gj, PackedWeights w, GruParams g, DecodeParams dp)
                     const float e2 = __expf(2.0f * x);          // tanh(x) = 1 - 2 / (e^{2x} + 1)
                     const float n = 1.0f - 2.0f / (e2 + 1.0f);
                     a.staging[(size_t)row_i[row] * g.M + col] = (1.0f - z) * n + z * h;
+                    if (a.gru_gates) {  // (uniform) a training step keeps the gates for its backward pass
+                        float *go = a.gru_gates + (size_t)(r0 + row) * 4 * g.M + col;
+                        go[0] = r;
+                        go[g.M] = z;
+                        go[2 * g.M] = n;
+                        go[3 * g.M] = shn + bhn;
+                    }
                 }
             }
             __syncthreads();  // the partial sums (and, after the last round, the tile) are reused

@@ -663,7 +663,8 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     // ---- the GRU of the applied batch: run by the previous step's closing launch if that step knew
     // the batch (and the memory has not changed since), else now, together with what is left of
     // this step's query preparation
-    const bool g_ready = !use_static && !general && ctx->ahead_g_valid && a.msg_count > 0 && ctx->ahead_g_first == a.msg_first_eid &&
+    // (a training step runs it itself: its backward pass reads the gates that this launch leaves)
+    const bool g_ready = !use_static && !general && !train && ctx->ahead_g_valid && a.msg_count > 0 && ctx->ahead_g_first == a.msg_first_eid &&
                          ctx->ahead_g_count == a.msg_count && !a.finish_here && (d.deferred || w_ready);
     sp.gru_now = !general && !g_ready && (a.msg_count > 0 || a.finish_here);
     if (general) {
@@ -733,6 +734,7 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
         sp.lr = train->lr;
         sp.loss_out = train->loss_out;
         sp.train_side = ctx->have_train_side ? &ctx->train_side : nullptr;
+        a.gru_gates = train_gates_buffer(d, ctx->train_ws);
     }
     const hipError_t e = launch_step(d, ctx->plan, ctx->pw, a, sp, ctx->stream, marks);
     // bit i: the interval between marks i and i + 1 held a kernel (a module selection's kernels fill

@@ -146,6 +146,7 @@ struct StepArgs {
     // intermediates (device)
     QuerySet qs;     // distinct queries of this batch
     float *staging;  // [2*msg_count x M] new memory rows of the winners, by entry 2b+role
+    float *gru_gates;  // NULL, or [2*msg_count x 4 x M]: r, z, n and the hidden half of n's pre-activation of winner r of the list (a training step's backward pass reads them)
     float *emb_u;    // [R x E] embedding of every distinct query
     float *dec_a;    // [R x Ep] first decoder layer, source half, of every distinct query
     float *dec_b;    // [R x Ep] the same, second-operand half
@@ -297,6 +298,8 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
 // after training steps with lr != 0 only the state update's prepared weights follow the masters: this
 // re-folds the rest (attention, merge MLP, decoder) for the fused inference kernels
 hipError_t train_refold_embed(const Dims &d, void *workspace, void *packed, PackedWeights *pw, hipStream_t s);
+// where the step's GRU launch leaves the gates of the applied winners for the backward pass
+float *train_gates_buffer(const Dims &d, void *workspace);
 // ---- other instances of the general architecture (modules.hip) ----
 // Module selection of a context and its weights: transposed copies ([in x out]) in the attached workspace.
 constexpr int kAccCopies = 8;  // accumulation rows per node of the mean aggregator (entries are dealt out to them: less same-address traffic)

@@ -79,7 +79,7 @@ struct TrainBufs {
     // per (pair, event): pair 0 = (source, destination), pair 1 = (source, negative); row p * count + b
     float *CAT, *DY, *G_, *DCAT, *DLOGIT, *LOSS;
     // per applied winner r, and per entry of the applied batch
-    float *MSG, *GI, *GH, *DGI, *DGH, *DPHI, *D_STAG;
+    float *MSG, *GATES, *DGI, *DGH, *DPHI, *D_STAG;
     int32_t *n_rows;  // [1] distinct queries of the step (written by the forward kernel's block 0)
     int32_t *slot0;   // [3B] first row of a query's filled slots in the per-slot matrices
     int32_t *n_live;  // [1] filled slots of the step (cleared with the gradients)
@@ -613,17 +613,15 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_gru_gates(StepArgs a, TrainDi
     for (int r = (int)blockIdx.x * kRowWaves + wave_id(); r < n_win; r += (int)gridDim.x * kRowWaves) {
         const WinDesc w = a.win[r];
         const bool ok = win_ok(a, w);
-        const float *gi = t.GI + (size_t)r * 3 * M, *gh = t.GH + (size_t)r * 3 * M;
+        const float *gt = t.GATES + (size_t)r * 4 * M;  // r, z, n, W_hn h + b_hn as the step's GRU launch left them
         float *dgi = t.DGI + (size_t)r * 3 * M, *dgh = t.DGH + (size_t)r * 3 * M;
         for (int j = lane; j < M; j += kWave) {
-            const float rg = 1.0f / (1.0f + expf(-(gi[j] + gh[j])));
-            const float zg = 1.0f / (1.0f + expf(-(gi[M + j] + gh[M + j])));
-            const float ng = tanhf(gi[2 * M + j] + rg * gh[2 * M + j]);
+            const float rg = gt[j], zg = gt[M + j], ng = gt[2 * M + j], ghn = gt[3 * M + j];
             const float dh = ok ? t.D_STAG[(size_t)w.entry * M + j] : 0.0f;
             const float dn = dh * (1.0f - zg);
             const float dz = dh * (t.MSG[(size_t)r * D + j] - ng);  // h = s_self = the first M entries of the message
             const float dpre_n = dn * (1.0f - ng * ng);
-            const float dpre_r = dpre_n * gh[2 * M + j] * rg * (1.0f - rg);
+            const float dpre_r = dpre_n * ghn * rg * (1.0f - rg);
             const float dpre_z = dz * zg * (1.0f - zg);
             dgi[j] = dpre_r;
             dgi[M + j] = dpre_z;
@@ -1123,8 +1121,7 @@ static TrainLayout train_layout(const Dims &d, void *base)
     b.MSG = take(U * D);
     b.DGI = take(U * 3 * M);
     b.DGH = take(U * 3 * M);
-    b.GI = take(U * 3 * M);
-    b.GH = take(U * 3 * M);
+    b.GATES = take(U * 4 * M);
     b.DPHI = take(U * T);
     b.n_rows = (int32_t *)take(64);
     b.slot0 = (int32_t *)take(R);
@@ -1381,16 +1378,11 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
         const int wg = (2 * a.msg_count + kRowWaves - 1) / kRowWaves;
         const dim3 per_win(wg < 256 ? wg : 256);
         hipLaunchKernelGGL(k_tr_gru_msg, per_win, dim3(kTrThreads), 0, s, a, pwv, td, b);
-        RowGemm g = layer(b.GI, 3 * M, b.MSG, D, b.W_i, D, b.b_i, 6 * M, D);
-        g.rc = wins;
-        g.n_split = 3 * M, g.W_hi = b.W_h, g.ldw_hi = M, g.Kd_hi = M, g.bias_hi = b.b_h, g.C_hi = b.GH, g.ldc_hi = 3 * M;
-        g.vecW = g.vecW && vec_ok(b.W_h, M);
-        run(g);
         hipLaunchKernelGGL(k_tr_gru_gates, per_win, dim3(kTrThreads), 0, s, a, td, b);
         fork(4);  // state update
         gemm(L.g.W_i, L.g.b_i, 3 * M, D, b.DGI, b.MSG, wins);
         gemm(L.g.W_h, L.g.b_h, 3 * M, M, b.DGH, b.MSG, wins, D);  // h = the first M columns of the message rows
-        g = layer(b.DPHI, T, b.DGI, 3 * M, b.T_i + (size_t)2 * M * 3 * M, 3 * M, nullptr, T, 3 * M);
+        RowGemm g = layer(b.DPHI, T, b.DGI, 3 * M, b.T_i + (size_t)2 * M * 3 * M, 3 * M, nullptr, T, 3 * M);
         g.rc = wins;
         run(g);
         hipLaunchKernelGGL(k_tr_gru_time, dim3((T + kTrThreads - 1) / kTrThreads, 128), dim3(kTrThreads), 0, s, a, pwv, td, b,
@@ -1424,6 +1416,8 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
     }
     return e;
 }
+
+float *train_gates_buffer(const Dims &d, void *workspace) { return train_layout(d, workspace).b.GATES; }
 
 hipError_t train_refold_embed(const Dims &d, void *workspace, void *packed, PackedWeights *pw, hipStream_t s)
 {
