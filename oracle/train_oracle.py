@@ -15,7 +15,9 @@ Readings where the paper is silent (it names neither the loss nor the optimiser)
     start of the step) are constants as well;
   * values the method stores in float32 (messages, memory rows, key/value rows, embeddings,
     scores) are differentiated as if the rounding were the identity;
-  * relu'(0) = 0;
+  * relu'(0) = 0 (a float32 implementation can land on the other side of zero where a pre-activation
+    is within its rounding error of zero: `tie_eps` reports such units, `relu_flip` evaluates the
+    gradients with the gate of listed units inverted, so that a comparison can accept either side);
   * optimiser: W <- W - lr * dL/dW in float32 (SGD without momentum).
 
 Pins (tests/test_oracle_train.py): the forward equals tig_oracle.step bit for bit; every gradient
@@ -43,9 +45,13 @@ def bce_loss(score_pos, score_neg):
 
 
 def train_step(state, src, dst, ts, edge_feat, W, first_eid, count, neg_dst, K, H, lr, index=None,
-               deferred=False):
+               deferred=False, tie_eps=0.0, relu_flip=frozenset()):
     """One training step.  Runs tig_oracle.step (state updated in place), then loss, gradients and
-    the SGD update of W (in place).  Returns (the step's outputs, loss, grads: dict name -> float64)."""
+    the SGD update of W (in place).  Returns (the step's outputs, loss, grads: dict name -> float64).
+    tie_eps > 0: the outputs carry "relu_ties", the ReLU units whose pre-activation is closer to zero
+    than tie_eps, as (|pre-activation|, layer, row, unit) with layer "dec" (row = pair index: event b
+    against its destination, count + b against its negative) or "merge" (row = query index).
+    relu_flip: units (layer, row, unit) whose gate is taken as the opposite of (pre-activation > 0)."""
     M = state.mem.shape[1]
     T = W["time_w"].shape[0]
     F = edge_feat.shape[1]
@@ -75,7 +81,21 @@ def train_step(state, src, dst, ts, edge_feat, W, first_eid, count, neg_dst, K, 
     d_emb = np.zeros_like(emb)
     pairs = [(b, B + b, out["score_pos"][b], -1.0) for b in range(B)] + \
             [(b, 2 * B + b, out["score_neg"][b], +1.0) for b in range(B)]
-    for qa, qb, logit, sign in pairs:
+    ties = []
+    flips = {}
+    for layer, row, unit in relu_flip:
+        flips.setdefault((layer, int(row)), []).append(int(unit))
+
+    def relu_gate(pre, layer, row):
+        gate = pre > 0.0
+        if tie_eps > 0.0:
+            for j in np.nonzero(np.abs(pre) < tie_eps)[0]:
+                ties.append((float(abs(pre[j])), layer, row, int(j)))
+        for j in flips.get((layer, row), ()):
+            gate[j] = not gate[j]
+        return gate
+
+    for p_idx, (qa, qb, logit, sign) in enumerate(pairs):
         # d softplus(sign * logit) / d logit = sign * sigmoid(sign * logit), averaged over the batch
         dlogit = sign * O.sigmoid(sign * float(logit)) / B
         x = np.concatenate([emb[qa], emb[qb]])
@@ -83,7 +103,7 @@ def train_step(state, src, dst, ts, edge_feat, W, first_eid, count, neg_dst, K, 
         hid = np.maximum(y, 0.0)
         g["w_d2"] += dlogit * hid
         g["b_d2"] += dlogit
-        dy = dlogit * Wd["w_d2"] * (y > 0.0)
+        dy = dlogit * Wd["w_d2"] * relu_gate(y, "dec", p_idx)
         g["W_d1"] += np.outer(dy, x)
         g["b_d1"] += dy
         dx = Wd["W_d1"].T @ dy
@@ -130,7 +150,7 @@ def train_step(state, src, dst, ts, edge_feat, W, first_eid, count, neg_dst, K, 
         de = d_emb[q]
         g["W_m2"] += np.outer(de, h1)
         g["b_m2"] += de
-        dz1 = (Wd["W_m2"].T @ de) * (z1 > 0.0)
+        dz1 = (Wd["W_m2"].T @ de) * relu_gate(z1, "merge", q)
         g["W_m1"] += np.outer(dz1, x)
         g["b_m1"] += dz1
         dx = Wd["W_m1"].T @ dz1
@@ -207,4 +227,6 @@ def train_step(state, src, dst, ts, edge_feat, W, first_eid, count, neg_dst, K, 
     if lr != 0.0:
         for k in PARAMS:
             W[k] = (W[k].astype(f64) - lr * g[k]).astype(f32)
+    if tie_eps > 0.0:
+        out["relu_ties"] = ties
     return out, loss, g

@@ -213,39 +213,75 @@ __global__ void __launch_bounds__(kGatherWaves *kWave) k_tr_gather(StepArgs a, P
     }
 }
 
-// <a, b> over n floats, by one lane (the lanes of a wavefront walk different rows: every load of the
-// walk is independent of the others, so a row costs one memory round trip, not one per element).
-// vec: both rows are 16-byte aligned and n is a multiple of 4.
-__device__ inline float lane_dot(const float *a, const float *b, int n, bool vec)
-{
-    float acc = 0.0f;
-    if (vec) {
-        floatx4 s4 = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll 8
-        for (int e = 0; e < n; e += 4) {
-            const floatx4 x = *(const floatx4 *)(a + e), y = *(const floatx4 *)(b + e);
-            s4 += x * y;
-        }
-        acc = (s4[0] + s4[1]) + (s4[2] + s4[3]);
-    } else {
-#pragma unroll 8
-        for (int e = 0; e < n; ++e)
-            acc += a[e] * b[e];
-    }
-    return acc;
-}
-
 // The attention core runs in a re-associated form that is the same function in exact arithmetic: with
 // q~_h = W_K,h^T Qv_h the score of slot k under head h is <q~_h, kv_k> / sqrt(d_h) plus a constant
 // over the slots (the key bias), which the softmax cancels; and the head's output is
 // W_V,h (sum_k p_hk kv_k) + b_V,h because the p_hk sum to one.  Every matrix product of the attention
 // is then a product over QUERIES (q~, the output, and in the backward pass their transposes) instead
 // of over the three times as many filled neighbour slots; what is left per slot are dot products
-// and weighted sums of the raw key / value rows, done here by one wavefront per query.
+// and weighted sums of the raw key / value rows, done here by one wavefront per query: the lanes lie
+// along the row (coalesced loads), kAttnCH slots' rows are requested together, and a dot product is
+// one wave reduction.
 constexpr int kMaxTrainHeads = 4;
+constexpr int kAttnCH = 4;  // slots per register chunk
+constexpr int kAttnCC = 8;  // 64-column pieces of a row a lane can hold: rows of up to 512 columns
+
+// kvr[u][c] = column c * 64 + lane of the raw row of slot k0 + u (the last filled slot again beyond cnt)
+__device__ inline void load_kv_chunk(float (&kvr)[kAttnCH][kAttnCC], const float *KV, size_t sb, int k0, int cnt, int dkv, int lane)
+{
+#pragma unroll
+    for (int u = 0; u < kAttnCH; ++u) {
+        const int k = k0 + u < cnt ? k0 + u : cnt - 1;
+#pragma unroll
+        for (int c = 0; c < kAttnCC; ++c) {
+            const int i = c * kWave + lane;
+            kvr[u][c] = c * kWave < dkv && i < dkv ? KV[(sb + k) * dkv + i] : 0.0f;  // (the first test is uniform)
+        }
+    }
+}
+
+// v[h][c] = column c * 64 + lane of head h's row of a per-query [H x dkv] array
+template <int HT>
+__device__ inline void load_head_rows(float (&v)[HT][kAttnCC], const float *rows, int H, int dkv, int lane)
+{
+#pragma unroll
+    for (int h = 0; h < HT; ++h)
+#pragma unroll
+        for (int c = 0; c < kAttnCC; ++c) {
+            const int i = c * kWave + lane;
+            v[h][c] = h < H && c * kWave < dkv && i < dkv ? rows[(size_t)h * dkv + i] : 0.0f;
+        }
+}
+
+// lane h * K + k: <head h's row of v, raw row of slot k> for k < cnt (other lanes: `other`)
+template <int HT>
+__device__ inline float slot_dots(const float (&v)[HT][kAttnCC], const float *KV, size_t sb, int cnt, int H, int K, int dkv,
+                                  int lane, float other)
+{
+    float res = other;
+    for (int k0 = 0; k0 < cnt; k0 += kAttnCH) {
+        float kvr[kAttnCH][kAttnCC];
+        load_kv_chunk(kvr, KV, sb, k0, cnt, dkv, lane);
+#pragma unroll
+        for (int u = 0; u < kAttnCH; ++u)
+#pragma unroll
+            for (int h = 0; h < HT; ++h)
+                if (h < H && k0 + u < cnt) {  // (uniform)
+                    float part = 0.0f;
+#pragma unroll
+                    for (int c = 0; c < kAttnCC; ++c)
+                        part += v[h][c] * kvr[u][c];
+                    const float sum = wave_sum_uniform(part);
+                    if (lane == h * K + k0 + u)
+                        res = sum;
+                }
+    }
+    return res;
+}
 
 // Scores, softmax, and the weighted sums KVB[x][h] = sum_k p_hk kv_k of one query per wavefront, from
 // QT = q~ and the raw rows KV of its filled slots: lane h * K + k holds slot k of head h.
+template <int HT>
 __global__ void __launch_bounds__(kTrThreads) k_tr_attn_fwd(StepArgs a, TrainDims d, TrainBufs t)
 {
     int n_u = *a.qs.n_u;
@@ -268,14 +304,12 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_fwd(StepArgs a, TrainDim
             t.PROB[(size_t)x * H * K + lane] = 0.0f;
         return;
     }
-    const float *qt = t.QT + (size_t)x * H * dkv;
     const float scale = 1.0f / sqrtf((float)dh);
-    const bool vec = dkv % 4 == 0 && (((uintptr_t)t.QT | (uintptr_t)t.KV) & 15) == 0;
-    float sc = -INFINITY;
-    {   // lane h * K + k forms the score of slot k under head h by itself
-        const int h = lane / K, k = lane - h * K;
-        if (lane < H * K && k < cnt)
-            sc = lane_dot(qt + (size_t)h * dkv, t.KV + (sb + k) * dkv, dkv, vec) * scale;
+    float sc;
+    {
+        float qtr[HT][kAttnCC];
+        load_head_rows<HT>(qtr, t.QT + (size_t)x * H * dkv, H, dkv, lane);
+        sc = slot_dots<HT>(qtr, t.KV, sb, cnt, H, K, dkv, lane, -INFINITY) * scale;
     }
     // softmax over the filled slots of the lane's head (every lane walks the head of lane % (H * K))
     const int hl = (lane % (H * K)) / K;
@@ -290,22 +324,32 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_fwd(StepArgs a, TrainDim
     const float pr = mine ? ex / sum : 0.0f;
     if (lane < H * K)
         t.PROB[(size_t)x * H * K + lane] = pr;
-    for (int i0 = 0; i0 < dkv; i0 += kWave) {  // (every lane stays in the loop: the shuffles read lanes below H * K)
-        const bool in = i0 + lane < dkv;
-        const int i = in ? i0 + lane : dkv - 1;
-        float acc[kMaxTrainHeads] = {0.0f, 0.0f, 0.0f, 0.0f};
-        for (int k = 0; k < cnt; ++k) {
-            const float v = t.KV[(sb + k) * dkv + i];
+    float acc[HT][kAttnCC];
 #pragma unroll
-            for (int h = 0; h < kMaxTrainHeads; ++h)
-                if (h < H)
-                    acc[h] += __shfl(pr, h * K + k) * v;
-        }
+    for (int h = 0; h < HT; ++h)
 #pragma unroll
-        for (int h = 0; h < kMaxTrainHeads; ++h)
-            if (h < H && in)
-                kvb[(size_t)h * dkv + i] = acc[h];
+        for (int c = 0; c < kAttnCC; ++c)
+            acc[h][c] = 0.0f;
+    for (int k0 = 0; k0 < cnt; k0 += kAttnCH) {
+        float kvr[kAttnCH][kAttnCC];
+        load_kv_chunk(kvr, t.KV, sb, k0, cnt, dkv, lane);
+#pragma unroll
+        for (int u = 0; u < kAttnCH; ++u)
+#pragma unroll
+            for (int h = 0; h < HT; ++h)
+                if (h < H && k0 + u < cnt) {  // (uniform: the shuffles are executed by every lane)
+                    const float p = __shfl(pr, h * K + k0 + u);
+#pragma unroll
+                    for (int c = 0; c < kAttnCC; ++c)
+                        acc[h][c] += p * kvr[u][c];
+                }
     }
+#pragma unroll
+    for (int h = 0; h < HT; ++h)
+#pragma unroll
+        for (int c = 0; c < kAttnCC; ++c)
+            if (h < H && c * kWave + lane < dkv)
+                kvb[(size_t)h * dkv + c * kWave + lane] = acc[h][c];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -397,6 +441,7 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_pair_scatter(StepArgs a, Trai
 // Backward of scores / softmax / weighted sums of one query per wavefront: from the gradient of the
 // weighted sums (DKVB) to the gradient of q~ (DQT) and to the gradients of the raw key / value rows of
 // its filled slots (DKV), which are complete with it.
+template <int HT>
 __global__ void __launch_bounds__(kTrThreads) k_tr_attn_bwd(StepArgs a, TrainDims d, TrainBufs t)
 {
     int n_u = *a.qs.n_u;
@@ -417,50 +462,56 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_bwd(StepArgs a, TrainDim
             dqt[j] = 0.0f;
         return;
     }
-    const float *dkvb = t.DKVB + (size_t)x * H * dkv;
-    const float *qt = t.QT + (size_t)x * H * dkv;
     const float scale = 1.0f / sqrtf((float)dh);
-    const bool vec = dkv % 4 == 0 && (((uintptr_t)t.DKVB | (uintptr_t)t.KV) & 15) == 0;
-    float dp = 0.0f;  // lane h * K + k: d p_hk = <kv_k, d KVB_h>, formed by the lane itself
-    {
-        const int h = lane / K, k = lane - h * K;
-        if (lane < H * K && k < cnt)
-            dp = lane_dot(t.KV + (sb + k) * dkv, dkvb + (size_t)h * dkv, dkv, vec);
-    }
+    float g_kvb[HT][kAttnCC];
+    load_head_rows<HT>(g_kvb, t.DKVB + (size_t)x * H * dkv, H, dkv, lane);
+    // lane h * K + k: d p_hk = <kv_k, d KVB_h>
+    const float dp = slot_dots<HT>(g_kvb, t.KV, sb, cnt, H, K, dkv, lane, 0.0f);
     const float pr = lane < H * K ? t.PROB[(size_t)x * H * K + lane] : 0.0f;  // (zero beyond the filled slots)
     const int hl = (lane % (H * K)) / K;
     float dot = 0.0f;
     for (int k = 0; k < cnt; ++k)
         dot += __shfl(pr, hl * K + k) * __shfl(dp, hl * K + k);
     const float dsv = pr * (dp - dot) * scale;  // gradient of <q~_h, kv_k>
-    for (int i0 = 0; i0 < dkv; i0 += kWave) {  // (every lane stays in the loop: the shuffles read lanes below H * K)
-        const bool in = i0 + lane < dkv;
-        const int i = in ? i0 + lane : dkv - 1;
-        float g_kvb[kMaxTrainHeads], g_qt[kMaxTrainHeads], acc[kMaxTrainHeads];
+    float g_qt[HT][kAttnCC], acc[HT][kAttnCC];
+    load_head_rows<HT>(g_qt, t.QT + (size_t)x * H * dkv, H, dkv, lane);
 #pragma unroll
-        for (int h = 0; h < kMaxTrainHeads; ++h) {
-            g_kvb[h] = h < H ? dkvb[(size_t)h * dkv + i] : 0.0f;
-            g_qt[h] = h < H ? qt[(size_t)h * dkv + i] : 0.0f;
-            acc[h] = 0.0f;
-        }
-        for (int k = 0; k < cnt; ++k) {
-            const float v = t.KV[(sb + k) * dkv + i];
-            float dk = 0.0f;  // d kv_k[i] = sum_h p_hk d KVB_h[i] + d s_hk q~_h[i]
+    for (int h = 0; h < HT; ++h)
 #pragma unroll
-            for (int h = 0; h < kMaxTrainHeads; ++h)
-                if (h < H) {
-                    const float ds = __shfl(dsv, h * K + k);
-                    acc[h] += ds * v;
-                    dk += __shfl(pr, h * K + k) * g_kvb[h] + ds * g_qt[h];
-                }
-            if (in)
-                t.DKV[(sb + k) * dkv + i] = dk;
-        }
+        for (int c = 0; c < kAttnCC; ++c)
+            acc[h][c] = 0.0f;
+    for (int k0 = 0; k0 < cnt; k0 += kAttnCH) {
+        float kvr[kAttnCH][kAttnCC];
+        load_kv_chunk(kvr, t.KV, sb, k0, cnt, dkv, lane);
 #pragma unroll
-        for (int h = 0; h < kMaxTrainHeads; ++h)
-            if (h < H && in)
-                dqt[(size_t)h * dkv + i] = acc[h];
+        for (int u = 0; u < kAttnCH; ++u)
+            if (k0 + u < cnt) {  // (uniform: the shuffles are executed by every lane)
+                float dk[kAttnCC];  // d kv_k = sum_h p_hk d KVB_h + d s_hk q~_h
+#pragma unroll
+                for (int c = 0; c < kAttnCC; ++c)
+                    dk[c] = 0.0f;
+#pragma unroll
+                for (int h = 0; h < HT; ++h)
+                    if (h < H) {
+                        const float ds = __shfl(dsv, h * K + k0 + u), p = __shfl(pr, h * K + k0 + u);
+#pragma unroll
+                        for (int c = 0; c < kAttnCC; ++c) {
+                            acc[h][c] += ds * kvr[u][c];
+                            dk[c] += p * g_kvb[h][c] + ds * g_qt[h][c];
+                        }
+                    }
+#pragma unroll
+                for (int c = 0; c < kAttnCC; ++c)
+                    if (c * kWave + lane < dkv)
+                        t.DKV[(sb + k0 + u) * dkv + c * kWave + lane] = dk[c];
+            }
     }
+#pragma unroll
+    for (int h = 0; h < HT; ++h)
+#pragma unroll
+        for (int c = 0; c < kAttnCC; ++c)
+            if (h < H && c * kWave + lane < dkv)
+                dqt[(size_t)h * dkv + c * kWave + lane] = acc[h][c];
 }
 
 // What is left of a query's backward pass after the matrix products, one wavefront per query: the
@@ -1149,7 +1200,7 @@ hipError_t prepare_train(const Dims &d)
 bool train_supported(const Dims &d)
 {
     // (the attention kernels keep slot k of head h in lane h * K + k of a query's wavefront)
-    return d.prec == TIG_FP32 && scatter_lds(d) <= 64 * 1024 && d.H * d.K <= kWave && d.H <= kMaxTrainHeads;
+    return d.prec == TIG_FP32 && scatter_lds(d) <= 64 * 1024 && d.H * d.K <= kWave && d.H <= kMaxTrainHeads && d.dkv <= kAttnCC * kWave;
 }
 
 static hipError_t transpose_all(const Dims &d, const TrainLayout &L, hipStream_t s)
@@ -1295,7 +1346,10 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
         g.vecA = g.vecA && dh % 4 == 0, g.vecW = g.vecW && dh % 4 == 0;
         run(g, H);
     }
-    hipLaunchKernelGGL(k_tr_attn_fwd, per_row, dim3(kTrThreads), 0, s, a, td, b);
+    if (H <= 2)
+        hipLaunchKernelGGL(k_tr_attn_fwd<2>, per_row, dim3(kTrThreads), 0, s, a, td, b);
+    else
+        hipLaunchKernelGGL(k_tr_attn_fwd<kMaxTrainHeads>, per_row, dim3(kTrThreads), 0, s, a, td, b);
     {   // o_h = W_V,h KVB_h + b_V,h
         RowGemm g = layer(b.O_, da, b.KVB, H * dkv, b.W_V, dkv, b.b_V, dh, dkv);
         g.zA = dkv, g.zW = dh * dkv, g.zC = dh, g.zBias = dh;
@@ -1355,7 +1409,10 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
         g.vecA = g.vecA && dh % 4 == 0, g.vecW = g.vecW && dh % 4 == 0;
         run(g, H);
     }
-    hipLaunchKernelGGL(k_tr_attn_bwd, per_row, dim3(kTrThreads), 0, s, a, td, b);
+    if (H <= 2)
+        hipLaunchKernelGGL(k_tr_attn_bwd<2>, per_row, dim3(kTrThreads), 0, s, a, td, b);
+    else
+        hipLaunchKernelGGL(k_tr_attn_bwd<kMaxTrainHeads>, per_row, dim3(kTrThreads), 0, s, a, td, b);
     fork(2);  // attention: dW_V,h = d o_h^T KVB_h, dW_K,h = Qv_h^T d q~_h over the queries (the key bias takes no gradient)
     gemm(L.g.W_O, L.g.b_O, da, da, b.D_ATTN, b.O_, rows);
     gemm(L.g.W_V, L.g.b_V, dh, dkv, b.DOUT, b.KVB, rows, H * dkv, da, H, TnBatch{dh * dkv, dh, dkv, dh});

@@ -13,6 +13,12 @@ from tests.test_gpu_parity import Bundle, make_ctx
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(600)]
 
 GRAD_TOL = 1e-4
+# A float32 forward pass can land on the other side of zero where a ReLU pre-activation of the float64
+# oracle is closer to zero than this (the two sides agree to about 1e-6 of the terms' size, and every
+# step has a million such units): the oracle reports these units, and where the gradients disagree the
+# comparison looks for the gates among them that the GPU took the other way (relu'(0) has two sides).
+TIE_EPS = 4e-6
+MAX_TIES = 16
 
 
 def check_grads(got, ref):
@@ -27,6 +33,32 @@ def check_grads(got, ref):
     return worst
 
 
+def flat(grads):
+    scale = {k: max(float(np.mean(np.abs(grads[k]))), 1e-30) for k in T.PARAMS}
+    return scale, lambda g: np.concatenate([(np.asarray(g[k], dtype=np.float64).reshape(-1)) / scale[k]
+                                            for k in T.PARAMS if k != "b_K"])
+
+
+def resolve_relu_ties(got, grads, ties, rerun):
+    """The oracle's gradients with the gates of those tied units inverted that explain got - grads
+    (rerun(flips) -> gradients of the same step with the listed gates inverted); raises if none do."""
+    scale, vec = flat(grads)
+    shaped = {k: got[k].reshape(grads[k].shape) for k in T.PARAMS}
+    resid = vec(shaped) - vec(grads)
+    chosen = []
+    deltas = []
+    for tie in ties:
+        g_i = rerun(frozenset([tie[1:]]))
+        deltas.append((tie, vec(g_i) - vec(grads)))
+    for tie, dlt in sorted(deltas, key=lambda td: -float(np.linalg.norm(td[1]))):
+        if np.linalg.norm(resid - dlt) < np.linalg.norm(resid):
+            resid = resid - dlt
+            chosen.append(tie[1:])
+    assert chosen, "no tied ReLU unit explains the difference"
+    print(f"[train] ReLU ties taken the other way by the GPU: {chosen} of {len(ties)} within {TIE_EPS:g}", flush=True)
+    return rerun(frozenset(chosen))
+
+
 def run_training(bundle, batches, lr, order, warm_at, then_eval=0):
     import torch
     w, g, W0, ix = bundle.w, bundle.g, bundle.W, bundle.ix
@@ -39,14 +71,28 @@ def run_training(bundle, batches, lr, order, warm_at, then_eval=0):
     for n, (first, count) in enumerate(batches):
         print(f"[train {w.name} {order}] step first_eid={first} count={count} lr={lr}", flush=True)
         neg = S.make_negatives(w, g, first, count)
+        st_before, W_before = st.copy(), {k: v.copy() for k, v in W.items()}
         ref, loss, grads = T.train_step(st, g.src, g.dst, g.ts, g.edge_feat, W, first, count, neg, w.num_neighbors,
-                                        w.num_heads, lr, index=ix, deferred=deferred)
+                                        w.num_heads, lr, index=ix, deferred=deferred, tie_eps=TIE_EPS)
         out = ctx.alloc_outputs(count, inspect=True)
         loss_dev = ctx.train_step(first, count, torch.from_numpy(neg).to("cuda:0"), out, lr)
         torch.cuda.synchronize()
         compare_step(ctx, out, ref, st, 1e-4)
         assert float(loss_dev.item()) == pytest.approx(loss, rel=2e-5)
-        worst = check_grads(ctx.train_get("grads"), grads)
+        got = ctx.train_get("grads")
+        try:
+            worst = check_grads(got, grads)
+        except AssertionError:
+            ties = ref.get("relu_ties", [])
+            if not ties or len(ties) > MAX_TIES:
+                raise
+
+            def rerun(flips):
+                return T.train_step(st_before.copy(), g.src, g.dst, g.ts, g.edge_feat,
+                                    {k: v.copy() for k, v in W_before.items()}, first, count, neg, w.num_neighbors,
+                                    w.num_heads, lr, index=ix, deferred=deferred, relu_flip=flips)[2]
+            worst = check_grads(got, resolve_relu_ties(got, grads, ties, rerun))
+        del st_before, W_before
         print(f"[train] loss {loss:.6f}; worst gradient gate ratios: "
               f"{ {k: float(f'{v:.2e}') for k, v in sorted(worst.items(), key=lambda kv: -kv[1])[:4]} }", flush=True)
         got_w = ctx.train_get("weights")

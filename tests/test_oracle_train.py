@@ -174,3 +174,40 @@ def test_sgd_update(c1):
     _, loss2, _ = T.train_step(warm(w, g, 5000), g.src, g.dst, g.ts, g.edge_feat, W1, 5000, 50, neg, w.num_neighbors,
                                w.num_heads, 0.0, index=ix)
     assert loss2 < loss0
+
+
+def test_relu_ties_and_inverted_gates(c1):
+    # the options a float32 comparison uses where a pre-activation is within rounding of zero
+    w, g, W = c1
+    ix = O.NeighbourIndex(g.num_nodes, g.src, g.dst, g.ts)
+    B = 40
+    neg = S.make_negatives(w, g, 5000, B)
+
+    def step(**kw):
+        return T.train_step(warm(w, g, 5000), g.src, g.dst, g.ts, g.edge_feat, {k: v.copy() for k, v in W.items()}, 5000,
+                            B, neg, w.num_neighbors, w.num_heads, 0.0, index=ix, **kw)
+    out0, _, g0 = step()
+    assert "relu_ties" not in out0
+    # a huge threshold lists every unit the backward pass went through, and changes nothing else
+    out1, _, g1 = step(tie_eps=1e9)
+    E = w.emb_dim
+    dec = [t for t in out1["relu_ties"] if t[1] == "dec"]
+    merge = [t for t in out1["relu_ties"] if t[1] == "merge"]
+    assert len(dec) == 2 * B * E and len(merge) % E == 0 and 0 < len(merge) <= 3 * B * E
+    assert all(np.array_equal(g0[k], g1[k]) for k in T.PARAMS)
+    # inverting the gate of an ACTIVE decoder unit removes exactly its term d logit * w_d2[j] from b_d1[j]
+    # (pair p < B is event p against its destination: d logit = -sigmoid(-logit) / B)
+    p, j = next((t[2], t[3]) for t in dec if t[2] < B and t[0] > 1e-3 and
+                (W["W_d1"][t[3]].astype(np.float64) @ np.concatenate([out0["emb"][t[2]], out0["emb"][B + t[2]]]).astype(np.float64)
+                 + W["b_d1"][t[3]]) > 0)
+    _, _, g2 = step(relu_flip=frozenset([("dec", p, j)]))
+    dlogit = -O.sigmoid(-float(out0["score_pos"][p])) / B
+    assert g2["b_d1"][j] - g0["b_d1"][j] == pytest.approx(-dlogit * float(W["w_d2"][j]), rel=1e-9)
+    others = np.delete(np.arange(E), j)
+    assert np.array_equal(g2["b_d1"][others], g0["b_d1"][others])
+    assert np.array_equal(g2["w_d2"], g0["w_d2"]) and np.array_equal(g2["b_d2"], g0["b_d2"])   # the forward is untouched
+    assert not np.array_equal(g2["W_m2"], g0["W_m2"])                                          # ... what lies upstream is not
+    # inverting it twice is the identity
+    _, _, g3 = step(relu_flip=frozenset([("dec", p, j), ("merge", 0, 0)]))
+    _, _, g4 = step(relu_flip=frozenset([("merge", 0, 0)]))
+    assert g3["b_d1"][j] - g4["b_d1"][j] == pytest.approx(-dlogit * float(W["w_d2"][j]), rel=1e-9)
