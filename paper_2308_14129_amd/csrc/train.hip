@@ -2,25 +2,29 @@
 // signals for training"; Alg. 2: "Training and compute loss", "Backward and Optimize"), device side.
 // gfx950 only, fp32.
 //
-// The step's forward pass is recomputed here in its DIRECT form (separate query / key / value /
-// output projections, the intermediates a backward pass needs kept in memory), then the loss
-// (binary cross-entropy on the logits of each event against one negative), the hand-written
-// backward pass and a plain SGD update of the fp32 master weights; the folded, lane-ordered
-// weights that the inference kernels read are rebuilt from the masters afterwards (pack.hip).
+// The step's forward pass is recomputed here with the intermediates a backward pass needs kept in
+// memory (separate query / output projections and merge layers; the attention core in the
+// re-associated form stated above k_tr_attn_fwd), then the loss (binary cross-entropy on the logits
+// of each event against one negative), the hand-written backward pass and a plain SGD update of the
+// fp32 master weights; the folded, lane-ordered weights that the inference kernels read are rebuilt
+// from the masters afterwards (pack.hip).
 //   k_tr_gather     the distinct queries as matrices: query rows, key / value rows of the filled
 //                   neighbour slots, the list of those slots (a negative's neighbours are looked up here)
 //   k_rowgemm       every layer product of the forward AND the backward pass over all rows at once on
-//                   the matrix cores (fp32 16x16x4): Q / K / V / O projections, merge MLP, and their
-//                   transposed products dX = dY W; the per-slot products run over the filled slots only
-//   k_tr_attn_fwd / k_tr_attn_bwd   scores, softmax, weighted value sum of one query per wavefront
+//                   the matrix cores (fp32 16x16x4): query projection, q~ and the heads' outputs (one
+//                   product per head in one launch), output projection, merge MLP, decoder, and
+//                   their transposed products dX = dY W -- all over queries or events, none over slots
+//   k_tr_attn_fwd / k_tr_attn_bwd   scores, softmax, weighted sums of the raw key / value rows of
+//                   one query per wavefront, and their backward down to the raw rows' gradients
 //   k_tr_pairs / k_tr_logit / k_tr_pair_scatter   around the decoder's two contractions: the decoder's
 //                   input rows per (pair, event), logits and loss terms, and the gradients of those
 //                   rows added into the distinct embedding rows' gradients
 //   k_tr_scatter    the gradient w.r.t. state rows that this step's GRU wrote goes to those rows;
 //                   time-encoding partial sums per query
-//   k_tr_gru_msg / k_tr_gru_gates / k_tr_gru_time   around the contractions of the GRU's backward
-//                   pass over the applied winners: message rows from the memory as the step found it,
-//                   gates and the gradients of their pre-activations, time-encoding gradient
+//   k_tr_gru_msg / k_tr_gru_gates / k_tr_gru_time   the GRU's backward pass over the applied
+//                   winners: message rows from the memory as the step found it, gradients of the
+//                   gate pre-activations (the gates themselves are left by the step's GRU launch),
+//                   time-encoding gradient
 //   k_gemm_tn       every weight gradient is dW = D^T X over the rows' stored (delta, input) pairs:
 //                   a [out x in] contraction over thousands of rows on the matrix cores (fp32
 //                   16x16x4), split over the row range, partial results added with atomics; they run
