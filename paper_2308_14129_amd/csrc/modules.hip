@@ -10,13 +10,14 @@
 //                  at the start of the step), then the GRU or the plain recurrent cell -> staged row
 //   k_mod_commit   memory overwrite M <- s_i(t) and last_update, after every message has been built
 //   k_mod_simple   identity / time-projection embedding of every query, straight to the output
-//   k_mod_rows     attention embedding in its direct form (separate query / key / value / output
-//                  projections, merge MLP), one workgroup per distinct query, node features added
-//                  wherever a state row is read; a negative's neighbours are looked up here
+//   k_mr_items / k_mr_attn + k_rowgemm   attention embedding with node features and / or two stacked
+//                  layers: every layer product as one contraction over all items of the layer, the
+//                  attention core per item in its re-associated form (stated above k_mr_items); a
+//                  negative's neighbours are looked up by k_mr_items
 //   k_mod_hop2     two stacked attention layers (the embedding module's sum over the 2-hop temporal
 //                  neighbourhood): the K most recent events, before the QUERY's time, of every
-//                  neighbour of every distinct query; k_mod_rows then runs twice: the first layer for
-//                  each (query, neighbour) pair and each query itself, the second layer over those rows
+//                  neighbour of every distinct query; the first layer then runs over each used
+//                  (query, neighbour) pair and each query itself, the second layer over those rows
 //   k_mod_decode   eight events per workgroup: both logits (and, for the attention embedding, the
 //                  per-query embedding rows out of the distinct rows)
 // Weight matrices are read through transposed copies ([in x out]) so that a thread that owns an
@@ -25,6 +26,7 @@
 
 #include "kernels_common.h"
 #include "prepare.h"
+#include "rowgemm.h"
 #include "winners.h"
 
 namespace tig {
@@ -33,20 +35,12 @@ namespace {
 
 constexpr int kModThreads = 256;
 constexpr int kModWaves = kModThreads / kWave;
-constexpr int kKC = 8;   // neighbour slots per register chunk
 constexpr int kEV = 8;   // events per decoder workgroup
 
 struct ModDims {
     int M, T, F, E, K, H, da, dh, dkv, Dmsg;
     int G;  // gate blocks of the state update: 3 (GRU: r, z, n) or 1 (plain recurrent cell)
     int agg, upd, emb;
-};
-
-// What one launch of k_mod_rows computes.
-enum RowsMode {
-    kRowsSingle = 0,  // the one-layer embedding of every distinct query
-    kRowsFirst = 1,   // first of two layers: item (q, j): neighbour j < cnt of query row q at the query's time, j == K: q itself
-    kRowsSecond = 2,  // second of two layers, over the first layer's rows
 };
 
 // The dimensions the second layer sees: its input rows are E wide.
@@ -73,32 +67,6 @@ __device__ inline void matvec_t(const float *WT, int in, int out, const float *x
         for (int i = 0; i < in; ++i)  // (unrolled: eight independent loads in flight, not one per step)
             acc += WT[(size_t)i * out + j] * x[i];
         y[j] = acc;
-    }
-}
-
-// Y[k][j] = bias[j] + sum_i WT[i * out + j] * X[k][i] for k < cnt   (X [cnt x ldx], Y [cnt x out] in LDS)
-__device__ inline void multivec_t(const float *WT, int in, int out, const float *X, int ldx, int cnt,
-                                  const float *bias, float *Y)
-{
-    for (int k0 = 0; k0 < cnt; k0 += kKC) {
-        for (int j = threadIdx.x; j < out; j += kModThreads) {
-            float acc[kKC];
-            const float b = bias ? bias[j] : 0.0f;
-#pragma unroll
-            for (int u = 0; u < kKC; ++u)
-                acc[u] = b;
-#pragma unroll 4
-            for (int i = 0; i < in; ++i) {
-                const float w = WT[(size_t)i * out + j];
-#pragma unroll
-                for (int u = 0; u < kKC; ++u)
-                    acc[u] += w * X[(size_t)(k0 + u < cnt ? k0 + u : k0) * ldx + i];
-            }
-#pragma unroll
-            for (int u = 0; u < kKC; ++u)
-                if (k0 + u < cnt)
-                    Y[(size_t)(k0 + u) * out + j] = acc[u];
-        }
     }
 }
 
@@ -331,144 +299,236 @@ __global__ void __launch_bounds__(kModThreads) k_mod_hop2(StepArgs a, ModDims d,
 }
 
 // ------------------------------------------------------------------------------------------
-// One attention layer + merge MLP of one item, direct form.  d and L are the layer's own dimensions
-// and weights (the second layer's input rows are E wide).
-__global__ void __launch_bounds__(kModThreads) k_mod_rows(StepArgs a, ModDims d, ModParams p, AttnLayer L, int mode)
+// The attention embedding as contractions over all ITEMS of a layer at once (an item is a distinct
+// query or, in the first of two layers, neighbour j of a distinct query at the query's time): every
+// layer product is one k_rowgemm launch over the items instead of one pass over the weight matrices
+// per item (forty thousand workgroups streaming 0.7 MB each from L2 bounded the per-item kernel),
+// and the attention core runs in the re-associated form that is the same function in exact
+// arithmetic -- q~_h = W_K,h^T Qv_h, score <q~_h, kv_k> / sqrt(d_h) (the key bias adds a constant
+// over the slots that the softmax cancels), head output W_V,h (sum_k p_hk kv_k) + b_V,h -- so that no
+// product runs over neighbour slots and the raw key / value rows [row of the neighbour | e |
+// Phi(t - t_k)] are never stored: the attention kernel forms them in registers.
+//   k_mr_items   one wavefront per distinct query: the item list (first of two layers: the used
+//                (query, slot) pairs and the queries themselves, packed in the order the workgroups
+//                arrive), query rows [own row | Phi(0)] and the own row as the tail of the merge
+//                layer's input
+//   k_mr_attn    one wavefront per item: scores, softmax, weighted sums of the raw rows
+enum MrMode { kMrSingle = 0, kMrFirst = 1, kMrSecond = 2 };
+constexpr int kMrWaves = 16;
+constexpr int kMrCH = 4;   // slots per register chunk
+constexpr int kMrCC = 8;   // 64-column pieces of a raw row a lane can hold at most: rows of up to 512 columns
+constexpr int kMrMaxHeads = 4;
+
+// One wavefront per distinct query row x; its items are the used slots j < cnt of its neighbour table
+// and -- slot K -- the query itself (one layer, and the second of two: that one only).
+template <int MODE>
+__global__ void __launch_bounds__(kMrWaves *kWave) k_mr_items(StepArgs a, ModDims d, ModParams p)
 {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    __shared__ int wg_items[kMrWaves], wg_base;
     int n_u = *a.qs.n_u;
     n_u = n_u < 2 * a.count ? n_u : 2 * a.count;
     const int n_rows = n_u + (a.roles == 3 ? a.count : 0);
-    const int M = d.M, F = d.F, E = d.E, K = d.K, H = d.H, da = d.da, dh = d.dh, dkv = d.dkv;
-    const int x = mode == kRowsFirst ? (int)blockIdx.x / (K + 1) : (int)blockIdx.x;
-    const int item = mode == kRowsFirst ? (int)blockIdx.x - x * (K + 1) : K;
-    if (x >= n_rows)
-        return;
-    double *dts = (double *)smem;     // [K]
-    int *nbrs = (int *)(dts + K);     // [K]
-    int *eids = nbrs + K;             // [K]
-    int *meta = eids + K;             // [2] cnt, node (+ 2 of padding)
-    float *q_in = (float *)(meta + 4);  // [da]
-    float *Qv = q_in + da;            // [da]
-    float *kv = Qv + da;              // [K x dkv]
-    float *KPs = kv + K * dkv;        // [K x da]
-    float *VPs = KPs + K * da;        // [K x da]
-    float *sc = VPs + K * da;         // [H x K]
-    float *o = sc + H * K;            // [da]
-    float *xcat = o + da;             // [da + M]: attn | own row
-    float *h1 = xcat + da + M;        // [E]
-
+    const int M = d.M, E = d.E, K = d.K, da = d.da;
+    const int lane = lane_id();
+    const int x = (int)blockIdx.x * kMrWaves + wave_id();
+    const bool valid = x < n_rows;  // (uniform over the wavefront; every wavefront reaches the barriers)
     const int q = x < n_u ? x : 2 * a.count + (x - n_u);
-    if (mode == kRowsSingle && x >= n_u && threadIdx.x < kWave) {  // a negative: the first wavefront looks up its neighbours
-        int32_t rf, ee;
-        double ts_k;
-        (void)finish_negative(a, K, x - n_u, rf, ee, ts_k);
+    int cnt_x = 0;
+    if (valid) {
+        if (MODE == kMrSingle && x >= n_u) {  // a negative: its neighbours are looked up here
+            int32_t rf, ee;
+            double ts_k;
+            cnt_x = finish_negative(a, K, x - n_u, rf, ee, ts_k);
+        } else {
+            cnt_x = a.qs.cnt[q];
+        }
+        cnt_x = cnt_x < 0 ? 0 : (cnt_x > K ? K : cnt_x);
     }
-    __syncthreads();
-    // the item's neighbour table: the query's own, or (first of two layers, item < K) the one of its
-    // neighbour `item` at the query's time
-    const bool hop = mode == kRowsFirst && item < K;
-    if (hop) {
-        const int c = a.qs.cnt[q];
-        if (item >= (c < 0 ? 0 : (c > K ? K : c)))
-            return;  // (uniform over the workgroup) an unused slot
+    const int n_it = !valid ? 0 : (MODE == kMrFirst ? cnt_x + 1 : 1);
+    int ci0 = x;
+    if (MODE == kMrFirst) {  // the items are packed in the order the workgroups arrive: one addition per workgroup
+        if (lane == 0)
+            wg_items[wave_id()] = n_it;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int total = 0;
+            for (int i = 0; i < kMrWaves; ++i)
+                total += wg_items[i];
+            wg_base = total > 0 ? atomicAdd(p.mr_n, total) : 0;
+        }
+        __syncthreads();
+        ci0 = wg_base;
+        for (int i = 0; i < wave_id(); ++i)
+            ci0 += wg_items[i];
+        if (ci0 < 0 || ci0 + n_it > 3 * a.count * (K + 1))
+            return;  // (not reachable while the counter is cleared every step)
     }
+    const int32_t u_self = !valid ? -1 : (MODE == kMrSingle && x >= n_u ? a.neg[x - n_u] : a.qs.node[q]);
+    for (int it = 0; it < n_it; ++it) {
+        const int j = MODE == kMrFirst && it < cnt_x ? it : K;
+        const int ci = ci0 + it;
+        const bool hop = j < K;
+        int cnt_item = cnt_x;
+        int32_t u = u_self;
+        if (hop) {
+            const int c = p.hop2.cnt[(size_t)q * K + j];
+            cnt_item = c < 0 ? 0 : (c > K ? K : c);
+            u = a.qs.nbr[(size_t)q * K + j];
+        }
+        if (lane == 0) {
+            p.mr_itq[ci] = q;
+            p.mr_itj[ci] = j;
+            p.mr_has[ci] = cnt_item > 0 ? 1 : 0;
+            if (MODE == kMrFirst)
+                p.mr_ci[(size_t)x * (K + 1) + j] = ci;
+        }
+        // the item's own row: the node's state row (+ features), or -- second layer -- its first-layer row
+        const float *own1 = MODE == kMrSecond ? p.h1 + (size_t)p.mr_ci[(size_t)x * (K + 1) + K] * E : nullptr;
+        for (int jj = lane; jj < da; jj += kWave) {
+            float v;
+            if (jj >= M)
+                v = time_enc(p.time_w_rev[jj - M], p.time_b_rev[jj - M], 0.0);
+            else
+                v = MODE == kMrSecond ? own1[jj] : repr_elem(a, p, M, u, jj);
+            p.mr_qin[(size_t)ci * da + jj] = v;
+            if (jj < M)
+                p.mr_x1[(size_t)ci * (da + M) + da + jj] = v;
+        }
+    }
+}
+
+// CC: 64-column pieces of a raw row (dkv <= 64 CC)
+template <int MODE, int HT, int CC>
+__global__ void __launch_bounds__(kModThreads) k_mr_attn(StepArgs a, ModDims d, ModParams p)
+{
+    int n_u = *a.qs.n_u;
+    n_u = n_u < 2 * a.count ? n_u : 2 * a.count;
+    const int n_rows = n_u + (a.roles == 3 ? a.count : 0);
+    int n_items = n_rows;
+    if (MODE == kMrFirst) {
+        n_items = *p.mr_n;
+        const int most = 3 * a.count * (d.K + 1);
+        n_items = n_items < 0 ? 0 : (n_items < most ? n_items : most);
+    }
+    const int ci = (int)blockIdx.x * kModWaves + wave_id();
+    if (ci >= n_items)
+        return;
+    const int lane = lane_id();
+    const int M = d.M, F = d.F, E = d.E, K = d.K, H = d.H, dh = d.dh, dkv = d.dkv;
+    const int q = p.mr_itq[ci], j = p.mr_itj[ci];
+    const bool hop = MODE == kMrFirst && j < K;
     const QuerySet &tab = hop ? p.hop2 : a.qs;
-    const int trow = hop ? q * K + item : q;
-    if (threadIdx.x == 0) {
-        const int c = tab.cnt[trow];
-        meta[0] = c < 0 ? 0 : (c > K ? K : c);
-        meta[1] = hop ? a.qs.nbr[(size_t)q * K + item] : a.qs.node[q];
+    const size_t trow = hop ? (size_t)q * K + j : (size_t)q;
+    int cnt = tab.cnt[trow];
+    cnt = cnt < 0 ? 0 : (cnt > K ? K : cnt);
+    float *kvb = p.mr_kvb + (size_t)ci * H * dkv;
+    if (cnt == 0) {
+        for (int i = lane; i < H * dkv; i += kWave)
+            kvb[i] = 0.0f;
+        return;
     }
     const double t_q = a.qs.t[q];
-    if ((int)threadIdx.x < K) {
-        nbrs[threadIdx.x] = tab.nbr[(size_t)trow * K + threadIdx.x];
-        eids[threadIdx.x] = tab.eid[(size_t)trow * K + threadIdx.x];
-        dts[threadIdx.x] = t_q - tab.ts[(size_t)trow * K + threadIdx.x];
+    // lane k < cnt: slot k of the item's table
+    int32_t my_nbr = -1, my_eid = -1, my_src = 0;
+    double my_dt = 0.0;
+    if (lane < cnt) {
+        my_nbr = tab.nbr[trow * K + lane];
+        my_eid = tab.eid[trow * K + lane];
+        my_dt = t_q - tab.ts[trow * K + lane];
+        if (MODE == kMrSecond)  // (second layer: item ci is query row x = ci; its slot's first-layer row)
+            my_src = p.mr_ci[(size_t)ci * (K + 1) + lane];
     }
-    __syncthreads();
-    const int cnt = meta[0];
-    const int32_t u = meta[1];
-    const float *rows1 = p.h1 + (size_t)q * (K + 1) * E;  // second layer: the first layer's rows of this query
-    for (int j = threadIdx.x; j < da; j += kModThreads) {
-        float v;
-        if (j >= M)
-            v = time_enc(p.time_w_rev[j - M], p.time_b_rev[j - M], 0.0);
-        else if (mode == kRowsSecond)
-            v = rows1[(size_t)K * E + j];
-        else
-            v = repr_elem(a, p, M, u, j);
-        q_in[j] = v;
-        if (j < M)
-            xcat[da + j] = v;
-    }
-    // key / value rows [row of the neighbour | e | Phi(t - t_k)]
-    for (int idx = threadIdx.x; idx < cnt * dkv; idx += kModThreads) {
-        const int k = idx / dkv, i = idx - k * dkv;
-        float v;
-        if (i < M)
-            v = mode == kRowsSecond ? rows1[(size_t)k * E + i] : repr_elem(a, p, M, nbrs[k], i);
-        else if (i < M + F)
-            v = eids[k] >= 0 ? a.edge_feat[(size_t)eids[k] * F + (i - M)] : 0.0f;
-        else
-            v = time_enc(p.time_w_rev[i - M - F], p.time_b_rev[i - M - F], dts[k]);
-        kv[idx] = v;
-    }
-    __syncthreads();
-    if (cnt > 0) {
-        matvec_t(L.T_Q, da, da, q_in, L.b_Q, Qv);
-        multivec_t(L.T_K, dkv, da, kv, dkv, cnt, L.b_K, KPs);
-        multivec_t(L.T_V, dkv, da, kv, dkv, cnt, L.b_V, VPs);
-        __syncthreads();
-        const float scale = 1.0f / sqrtf((float)dh);
-        for (int idx = threadIdx.x; idx < H * cnt; idx += kModThreads) {
-            const int hh = idx / cnt, k = idx - hh * cnt;
-            float s = 0.0f;
-            for (int e = 0; e < dh; ++e)
-                s += Qv[hh * dh + e] * KPs[(size_t)k * da + hh * dh + e];
-            sc[hh * K + k] = s * scale;
-        }
-        __syncthreads();
-        if ((int)threadIdx.x < H) {
-            const int hh = threadIdx.x;
-            float mx = -INFINITY, sum = 0.0f;
-            for (int k = 0; k < cnt; ++k)
-                mx = fmaxf(mx, sc[hh * K + k]);
-            for (int k = 0; k < cnt; ++k) {
-                const float e = expf(sc[hh * K + k] - mx);
-                sc[hh * K + k] = e;
-                sum += e;
+    // kvr[u][c] = column c * 64 + lane of the raw row [row of the neighbour | e | Phi(t - t_k)] of slot k0 + u
+    auto load_chunk = [&](float (&kvr)[kMrCH][CC], int k0) {
+#pragma unroll
+        for (int u = 0; u < kMrCH; ++u) {
+            const int k = k0 + u < cnt ? k0 + u : cnt - 1;  // (uniform; the shuffles are executed by every lane)
+            const int32_t nb = __shfl(my_nbr, k), ee = __shfl(my_eid, k), sr = __shfl(my_src, k);
+            const int dlo = __shfl(__double2loint(my_dt), k), dhi = __shfl(__double2hiint(my_dt), k);
+            const double dt = __hiloint2double(dhi, dlo);
+#pragma unroll
+            for (int c = 0; c < CC; ++c) {
+                const int i = c * kWave + lane;
+                float v = 0.0f;
+                if (c * kWave < dkv && i < dkv) {  // (the first test is uniform)
+                    if (i < M)
+                        v = MODE == kMrSecond ? p.h1[(size_t)sr * E + i] : repr_elem(a, p, M, nb, i);
+                    else if (i < M + F)
+                        v = ee >= 0 ? a.edge_feat[(size_t)ee * F + (i - M)] : 0.0f;
+                    else
+                        v = time_enc(p.time_w_rev[i - M - F], p.time_b_rev[i - M - F], dt);
+                }
+                kvr[u][c] = v;
             }
-            for (int k = 0; k < cnt; ++k)
-                sc[hh * K + k] /= sum;
         }
-        __syncthreads();
-        for (int j = threadIdx.x; j < da; j += kModThreads) {
-            const int hh = j / dh;
-            float acc = 0.0f;
-            for (int k = 0; k < cnt; ++k)
-                acc += sc[hh * K + k] * VPs[(size_t)k * da + j];
-            o[j] = acc;
+    };
+    const float scale = 1.0f / sqrtf((float)dh);
+    float sc = -INFINITY;  // lane h * K + k: score of slot k under head h
+    {
+        float qtr[HT][CC];
+        const float *qt = p.mr_qt + (size_t)ci * H * dkv;
+#pragma unroll
+        for (int h = 0; h < HT; ++h)
+#pragma unroll
+            for (int c = 0; c < CC; ++c) {
+                const int i = c * kWave + lane;
+                qtr[h][c] = h < H && c * kWave < dkv && i < dkv ? qt[(size_t)h * dkv + i] : 0.0f;
+            }
+        for (int k0 = 0; k0 < cnt; k0 += kMrCH) {
+            float kvr[kMrCH][CC];
+            load_chunk(kvr, k0);
+#pragma unroll
+            for (int u = 0; u < kMrCH; ++u)
+#pragma unroll
+                for (int h = 0; h < HT; ++h)
+                    if (h < H && k0 + u < cnt) {  // (uniform)
+                        float part = 0.0f;
+#pragma unroll
+                        for (int c = 0; c < CC; ++c)
+                            part += qtr[h][c] * kvr[u][c];
+                        const float sum = wave_sum_uniform(part) * scale;
+                        if (lane == h * K + k0 + u)
+                            sc = sum;
+                    }
         }
-        __syncthreads();
-        matvec_t(L.T_O, da, da, o, L.b_O, xcat);
-    } else {
-        for (int j = threadIdx.x; j < da; j += kModThreads)
-            xcat[j] = 0.0f;  // an empty neighbourhood gives the zero vector (no bias)
     }
-    __syncthreads();
-    matvec_t(L.T_m1, da + M, E, xcat, L.b_m1, h1);
-    __syncthreads();
-    for (int j = threadIdx.x; j < E; j += kModThreads)
-        h1[j] = fmaxf(h1[j], 0.0f);
-    __syncthreads();
-    float *out = mode == kRowsFirst ? p.h1 + ((size_t)q * (K + 1) + item) * E : a.emb_u + (size_t)q * E;
-    for (int j = threadIdx.x; j < E; j += kModThreads) {
-        float acc = L.b_m2[j];
-        for (int i = 0; i < E; ++i)
-            acc += L.T_m2[(size_t)i * E + j] * h1[i];
-        out[j] = acc;
+    // softmax over the filled slots of the lane's head (every lane walks the head of lane % (H * K))
+    const int hl = (lane % (H * K)) / K;
+    float mx = -INFINITY;
+    for (int k = 0; k < cnt; ++k)
+        mx = fmaxf(mx, __shfl(sc, hl * K + k));
+    const bool mine = lane < H * K && lane - hl * K < cnt;
+    const float ex = mine ? expf(sc - mx) : 0.0f;
+    float sum = 0.0f;
+    for (int k = 0; k < cnt; ++k)
+        sum += __shfl(ex, hl * K + k);
+    const float pr = mine ? ex / sum : 0.0f;
+    float acc[HT][CC];
+#pragma unroll
+    for (int h = 0; h < HT; ++h)
+#pragma unroll
+        for (int c = 0; c < CC; ++c)
+            acc[h][c] = 0.0f;
+    for (int k0 = 0; k0 < cnt; k0 += kMrCH) {
+        float kvr[kMrCH][CC];
+        load_chunk(kvr, k0);
+#pragma unroll
+        for (int u = 0; u < kMrCH; ++u)
+#pragma unroll
+            for (int h = 0; h < HT; ++h)
+                if (h < H && k0 + u < cnt) {  // (uniform: the shuffles are executed by every lane)
+                    const float pk = __shfl(pr, h * K + k0 + u);
+#pragma unroll
+                    for (int c = 0; c < CC; ++c)
+                        acc[h][c] += pk * kvr[u][c];
+                }
     }
+#pragma unroll
+    for (int h = 0; h < HT; ++h)
+#pragma unroll
+        for (int c = 0; c < CC; ++c)
+            if (h < H && c * kWave + lane < dkv)
+                kvb[(size_t)h * dkv + c * kWave + lane] = acc[h][c];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -581,19 +641,6 @@ int update_lds(const ModDims &d) { return (d.Dmsg + d.M + 2 * d.G * d.M) * 4; }
 
 int msgsum_lds(const ModDims &d) { return kMsgSlots * (d.M + d.T + d.F) * 8 + 2 * kMsgSlots * 4; }
 
-int rows_lds(const ModDims &d)
-{
-    return d.K * 8 + (2 * d.K + 4) * 4 +
-           (2 * d.da + d.K * d.dkv + 2 * d.K * d.da + d.H * d.K + d.da + d.da + d.M + d.E) * 4;
-}
-
-// the larger of the two layers' needs (the second layer's rows are E wide)
-int rows_lds_all(const ModDims &d, int layers)
-{
-    const int a = rows_lds(d), b = layers == 2 ? rows_lds(second_layer_dims(d)) : 0;
-    return a > b ? a : b;
-}
-
 int decode_lds(const ModDims &d) { return (kEV * 3 * d.E + kEV * 2 * kModWaves) * 4; }
 
 // One matrix of the workspace: raw copy (kept for nothing but the transpose) and its transpose.
@@ -653,6 +700,11 @@ static size_t mod_layout(const Dims &d, int agg, int upd, int emb, int layers, b
             A.T_O = (const float *)take(a_w * a_w, 4);
             A.T_m1 = (const float *)take((a_w + in_w) * E, 4);
             A.T_m2 = (const float *)take(E * E, 4);
+            A.N_Q = (const float *)take(a_w * a_w, 4);
+            A.N_V = (const float *)take(a_w * kv_w, 4);
+            A.N_O = (const float *)take(a_w * a_w, 4);
+            A.N_m1 = (const float *)take(E * (a_w + in_w), 4);
+            A.N_m2 = (const float *)take(E * E, 4);
             const size_t c[] = {a_w * a_w, kv_w * a_w, (a_w + in_w) * E, E * E};
             for (size_t v : c)
                 biggest = v > biggest ? v : biggest;
@@ -666,6 +718,22 @@ static size_t mod_layout(const Dims &d, int agg, int upd, int emb, int layers, b
             q.hop2.eid = (int32_t *)take(R2 * d.K, 4);
             q.hop2.ts = (double *)take(R2 * d.K, 8);
             q.h1 = (float *)take((size_t)3 * d.max_batch * (d.K + 1) * E, 4);
+            q.mr_ci = (int32_t *)take((size_t)3 * d.max_batch * (d.K + 1), 4);
+        }
+        {   // the items' matrices: widths of the wider layer
+            const size_t items = (size_t)3 * d.max_batch * (q.layers == 2 ? d.K + 1 : 1);
+            const size_t in_w = q.layers == 2 && E > M ? E : M, a_w = in_w + T, kv_w = in_w + d.F + T;
+            q.mr_qin = (float *)take(items * a_w, 4);
+            q.mr_qv = (float *)take(items * a_w, 4);
+            q.mr_qt = (float *)take(items * d.H * kv_w, 4);
+            q.mr_kvb = (float *)take(items * d.H * kv_w, 4);
+            q.mr_o = (float *)take(items * a_w, 4);
+            q.mr_x1 = (float *)take(items * (a_w + in_w), 4);
+            q.mr_h1 = (float *)take(items * E, 4);
+            q.mr_has = (int32_t *)take(items, 4);
+            q.mr_itq = (int32_t *)take(items, 4);
+            q.mr_itj = (int32_t *)take(items, 4);
+            q.mr_n = (int32_t *)take(64, 4);
         }
     }
     q.b_d1 = (const float *)take(E, 4);
@@ -709,8 +777,9 @@ bool modules_supported(const Dims &d, const tig_modules &m)
         return false;
     if (m.num_layers == 2 && (m.embedding != TIG_EMB_ATTENTION || (d.E + d.T) % d.H != 0))
         return false;
-    return d.prec == TIG_FP32 && update_lds(md) <= 160 * 1024 && msgsum_lds(md) <= 64 * 1024 && rows_lds_all(md, m.num_layers) <= 160 * 1024 &&
-           decode_lds(md) <= 160 * 1024 && d.K <= kModThreads;
+    return d.prec == TIG_FP32 && update_lds(md) <= 160 * 1024 && msgsum_lds(md) <= 64 * 1024 && decode_lds(md) <= 160 * 1024 && d.K <= kModThreads &&
+           (m.embedding != TIG_EMB_ATTENTION || (d.H <= kMrMaxHeads && d.H * d.K <= kWave && d.dkv <= kMrCC * kWave &&
+                                                  d.E + d.F + d.T <= kMrCC * kWave));
 }
 
 hipError_t modules_attach(const Dims &d, const tig_modules &m, const tig_weights &w, int64_t num_nodes, void *workspace,
@@ -772,6 +841,11 @@ hipError_t modules_attach(const Dims &d, const tig_modules &m, const tig_weights
             MOD_TRY(mat(A.T_O, src.W_O, a_w, a_w));
             MOD_TRY(mat(A.T_m1, src.W_m1, E, a_w + in_w));
             MOD_TRY(mat(A.T_m2, src.W_m2, E, E));
+            MOD_TRY(vec(A.N_Q, src.W_Q, (size_t)a_w * a_w));
+            MOD_TRY(vec(A.N_V, src.W_V, (size_t)a_w * kv_w));
+            MOD_TRY(vec(A.N_O, src.W_O, (size_t)a_w * a_w));
+            MOD_TRY(vec(A.N_m1, src.W_m1, (size_t)E * (a_w + in_w)));
+            MOD_TRY(vec(A.N_m2, src.W_m2, (size_t)E * E));
         }
     }
     MOD_TRY(vec(p.b_d1, w.b_d1, E));
@@ -788,7 +862,6 @@ hipError_t modules_attach(const Dims &d, const tig_modules &m, const tig_weights
     }
     MOD_TRY(hipFuncSetAttribute((const void *)k_mod_update, hipFuncAttributeMaxDynamicSharedMemorySize, update_lds(md)));
     MOD_TRY(hipFuncSetAttribute((const void *)k_mod_msgsum, hipFuncAttributeMaxDynamicSharedMemorySize, msgsum_lds(md)));
-    MOD_TRY(hipFuncSetAttribute((const void *)k_mod_rows, hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds_all(md, p.layers)));
     MOD_TRY(hipFuncSetAttribute((const void *)k_mod_decode, hipFuncAttributeMaxDynamicSharedMemorySize, decode_lds(md)));
 #undef MOD_TRY
     *out = p;
@@ -838,13 +911,82 @@ hipError_t launch_modules(const Dims &d, const LaunchPlan &plan, const PackedWei
         b.finish_here = 1;  // slots of the query set (its row references all name memory rows)
         if ((e = launch_gru(d, plan, pw, b, s)) != hipSuccess)
             return e;
+        // one attention layer + merge MLP over all items of `mode`: item list and query rows, the layer's
+        // products as contractions over the items, the attention core per item in between
+        auto layer_pass = [&](const ModDims &ld, const AttnLayer &A, int mode) {
+            const int items_max = 3 * B * (mode == kMrFirst ? d.K + 1 : 1);
+            const RowCount rc = mode == kMrFirst ? RowCount{p.mr_n, 0, 1, items_max}
+                                                 : RowCount{b.qs.n_u, b.roles == 3 ? B : 0, 1, items_max};
+            const int da = ld.da, dh = ld.dh, dkv = ld.dkv, M_ = ld.M, E_ = ld.E, H = ld.H;
+            const dim3 g_items((3 * B + kMrWaves - 1) / kMrWaves), g_attn((items_max + kModWaves - 1) / kModWaves);
+            auto prod = [&](float *C, int ldc, const float *X, int lda, const float *W, int ldw, const float *bias, int N, int Kd) {
+                RowGemm g = {};
+                g.A = X, g.lda = lda, g.W = W, g.ldw = ldw, g.bias = bias, g.C = C, g.ldc = ldc, g.N = N, g.Kd = Kd, g.rc = rc;
+                g.vecA = rowgemm_vec_ok(X, lda), g.vecW = rowgemm_vec_ok(W, ldw);
+                return g;
+            };
+            if (mode == kMrSingle)
+                hipLaunchKernelGGL(k_mr_items<kMrSingle>, g_items, dim3(kMrWaves * kWave), 0, s, b, ld, p);
+            else if (mode == kMrFirst)
+                hipLaunchKernelGGL(k_mr_items<kMrFirst>, g_items, dim3(kMrWaves * kWave), 0, s, b, ld, p);
+            else
+                hipLaunchKernelGGL(k_mr_items<kMrSecond>, g_items, dim3(kMrWaves * kWave), 0, s, b, ld, p);
+            launch_rowgemm(prod(p.mr_qv, da, p.mr_qin, da, A.N_Q, da, A.b_Q, da, da), 1, s);
+            {   // q~_h = W_K,h^T Qv_h, every head in one launch
+                RowGemm g = prod(p.mr_qt, H * dkv, p.mr_qv, da, A.T_K, da, nullptr, dkv, dh);
+                g.zA = dh, g.zW = dh, g.zC = dkv;
+                g.vecA = g.vecA && dh % 4 == 0, g.vecW = g.vecW && dh % 4 == 0;
+                launch_rowgemm(g, H, s);
+            }
+#define MR_ATTN(MODE)                                                                                             \
+    do {                                                                                                          \
+        if (H <= 2 && dkv <= 256)                                                                                 \
+            hipLaunchKernelGGL((k_mr_attn<MODE, 2, 4>), g_attn, dim3(kModThreads), 0, s, b, ld, p);               \
+        else if (H <= 2)                                                                                          \
+            hipLaunchKernelGGL((k_mr_attn<MODE, 2, kMrCC>), g_attn, dim3(kModThreads), 0, s, b, ld, p);           \
+        else                                                                                                      \
+            hipLaunchKernelGGL((k_mr_attn<MODE, kMrMaxHeads, kMrCC>), g_attn, dim3(kModThreads), 0, s, b, ld, p); \
+    } while (0)
+            if (mode == kMrSingle)
+                MR_ATTN(kMrSingle);
+            else if (mode == kMrFirst)
+                MR_ATTN(kMrFirst);
+            else
+                MR_ATTN(kMrSecond);
+#undef MR_ATTN
+            {   // o_h = W_V,h KVB_h + b_V,h
+                RowGemm g = prod(p.mr_o, da, p.mr_kvb, H * dkv, A.N_V, dkv, A.b_V, dh, dkv);
+                g.zA = dkv, g.zW = dh * dkv, g.zC = dh, g.zBias = dh;
+                g.vecA = g.vecA && dkv % 4 == 0, g.vecW = g.vecW && (dh * dkv) % 4 == 0;
+                launch_rowgemm(g, H, s);
+            }
+            {   // attn = W_O o + b_O into the head of the merge layer's input; the zero vector without neighbours
+                RowGemm g = prod(p.mr_x1, da + M_, p.mr_o, da, A.N_O, da, A.b_O, da, da);
+                g.rowmask = p.mr_has;
+                launch_rowgemm(g, 1, s);
+            }
+            {
+                RowGemm g = prod(p.mr_h1, E_, p.mr_x1, da + M_, A.N_m1, da + M_, A.b_m1, E_, da + M_);
+                g.relu = 1;
+                launch_rowgemm(g, 1, s);
+            }
+            if (mode == kMrFirst) {  // the first layer's rows, one per item
+                launch_rowgemm(prod(p.h1, E_, p.mr_h1, E_, A.N_m2, E_, A.b_m2, E_, E_), 1, s);
+            } else {                 // the embedding rows of the query set
+                RowGemm g = prod(b.emb_u, E_, p.mr_h1, E_, A.N_m2, E_, A.b_m2, E_, E_);
+                g.remap_nu = b.qs.n_u, g.remap_2b = 2 * B;
+                launch_rowgemm(g, 1, s);
+            }
+        };
         if (p.layers == 2) {
             const ModDims md2 = second_layer_dims(md);
+            if ((e = launch_fill_zero(p.mr_n, 4, s)) != hipSuccess)
+                return e;
             hipLaunchKernelGGL(k_mod_hop2, dim3(3 * B), dim3(kModThreads), 0, s, b, md, p);
-            hipLaunchKernelGGL(k_mod_rows, dim3(3 * B * (d.K + 1)), dim3(kModThreads), rows_lds(md), s, b, md, p, p.L[0], (int)kRowsFirst);
-            hipLaunchKernelGGL(k_mod_rows, dim3(3 * B), dim3(kModThreads), rows_lds(md2), s, b, md2, p, p.L[1], (int)kRowsSecond);
+            layer_pass(md, p.L[0], kMrFirst);
+            layer_pass(md2, p.L[1], kMrSecond);
         } else {
-            hipLaunchKernelGGL(k_mod_rows, dim3(3 * B), dim3(kModThreads), rows_lds(md), s, b, md, p, p.L[0], (int)kRowsSingle);
+            layer_pass(md, p.L[0], kMrSingle);
         }
         hipLaunchKernelGGL(k_mod_decode, dim3((B + kEV - 1) / kEV), dim3(kModThreads), decode_lds(md), s, b, md, p, 1);
         if ((e = hipGetLastError()) != hipSuccess)

@@ -306,6 +306,7 @@ constexpr int kAccCopies = 8;  // accumulation rows per node of the mean aggrega
 struct AttnLayer {
     const float *T_Q, *T_K, *T_V, *T_O, *b_Q, *b_K, *b_V, *b_O;  // attention
     const float *T_m1, *T_m2, *b_m1, *b_m2;    // merge MLP
+    const float *N_Q, *N_V, *N_O, *N_m1, *N_m2;  // the matrices as given ([out x in]) for the contractions over all rows
 };
 struct ModParams {
     int agg, upd, emb;                         // tig_aggregator, tig_updater, tig_embedding
@@ -314,7 +315,15 @@ struct ModParams {
     const float *T_i, *T_h, *b_i, *b_h;        // state update: [D_msg x GM], [M x GM], [GM], [GM] (G = 3 GRU, 1 RNN)
     AttnLayer L[2];                            // first layer (input width M) and second (input width E)
     QuerySet hop2;                             // two layers: neighbour tables of (neighbour k of query row q, t_q) at row q * K + k
-    float *h1;                                 // two layers: first-layer rows [3 * max_batch x (K + 1) x E]: neighbour k of row q, then q itself
+    float *h1;                                 // two layers: first-layer rows [3 * max_batch x (K + 1) x E], one per item in the items' order
+    // the attention embedding as contractions over all items of a layer (an item: a distinct query, or --
+    // first of two layers -- neighbour j of a distinct query at the query's time); widths are the larger of
+    // the two layers'
+    float *mr_qin, *mr_qv, *mr_qt, *mr_kvb, *mr_o, *mr_x1, *mr_h1;
+    int32_t *mr_has;                           // [items] 1 for an item with at least one filled neighbour slot
+    int32_t *mr_itq, *mr_itj;                  // [items] the item's query row and slot (K: the query itself)
+    int32_t *mr_ci;                            // [3 * max_batch x (K + 1)] item of (query row x, slot j), first layer
+    int32_t *mr_n;                             // [1] items of the first layer (cleared every step)
     const float *T_d1, *b_d1, *w_d2, *b_d2;    // decoder: [2E x E], [E], [E], [1]
     const float *node_feat;                    // [N x M] or NULL
     const float *time_proj_w;                  // [M] or NULL
