@@ -319,6 +319,44 @@ constexpr int kMrCH = 4;   // slots per register chunk
 constexpr int kMrCC = 8;   // 64-column pieces of a raw row a lane can hold at most: rows of up to 512 columns
 constexpr int kMrMaxHeads = 4;
 
+// The item of (query row x, slot j) once the item list is complete: an index, or the pair's
+// representative's.
+__device__ inline int mr_item_of(const ModParams &p, size_t dense)
+{
+    int c = p.mr_ci[dense];
+    if (c < 0)
+        c = p.mr_ci[(size_t)(-c - 1)];
+    return c < 0 ? 0 : c;
+}
+
+// First of two layers: equal (node, t) pairs -- a hub is a neighbour of most queries of a second, and
+// is a query itself -- are one item.  Pair (u, t) of (x, j) index `dense` claims a slot of the table
+// (open addressing; a slot changes once per step, from empty to claimed); returns the index that
+// represents the pair: its own, or the first claimant's.
+__device__ inline int mr_claim(const StepArgs &a, const ModParams &p, int K, int n_u, int dense, int32_t u, double t)
+{
+    uint32_t h = query_hash(u, t) & p.mr_tab_mask;
+    for (uint32_t probes = 0; probes <= p.mr_tab_mask; ++probes) {
+        uint32_t cur = __hip_atomic_load(&p.mr_tab[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (cur == 0u) {
+            const uint32_t old = atomicCAS(&p.mr_tab[h], 0u, (uint32_t)dense + 1u);
+            if (old == 0u)
+                return dense;
+            cur = old;
+        }
+        const int other = (int)(cur - 1u);
+        const int xo = other / (K + 1), jo = other - xo * (K + 1);
+        if (xo < n_u + a.count) {
+            const int qo = xo < n_u ? xo : 2 * a.count + (xo - n_u);
+            const int32_t uo = jo < K ? a.qs.nbr[(size_t)qo * K + jo] : a.qs.node[qo];
+            if (uo == u && a.qs.t[qo] == t)
+                return other;
+        }
+        h = (h + 1) & p.mr_tab_mask;
+    }
+    return dense;
+}
+
 // One wavefront per distinct query row x; its items are the used slots j < cnt of its neighbour table
 // and -- slot K -- the query itself (one layer, and the second of two: that one only).
 template <int MODE>
@@ -344,7 +382,23 @@ __global__ void __launch_bounds__(kMrWaves *kWave) k_mr_items(StepArgs a, ModDim
         }
         cnt_x = cnt_x < 0 ? 0 : (cnt_x > K ? K : cnt_x);
     }
-    const int n_it = !valid ? 0 : (MODE == kMrFirst ? cnt_x + 1 : 1);
+    const int32_t u_self = !valid ? -1 : (MODE == kMrSingle && x >= n_u ? a.neg[x - n_u] : a.qs.node[q]);
+    // lane `it` of the wavefront: candidate item `it` of the row (slots first, the query itself last)
+    const int n_cand = !valid ? 0 : (MODE == kMrFirst ? cnt_x + 1 : 1);
+    const int my_j = MODE == kMrFirst && lane < cnt_x ? lane : K;
+    int32_t my_u = u_self;
+    bool is_item = lane < n_cand;
+    if (MODE == kMrFirst && lane < n_cand) {
+        if (my_j < K)
+            my_u = a.qs.nbr[(size_t)q * K + my_j];
+        const int dense = x * (K + 1) + my_j;
+        const int rep = mr_claim(a, p, K, n_u, dense, my_u, a.qs.t[q]);
+        is_item = rep == dense;
+        if (!is_item)
+            p.mr_ci[dense] = -rep - 1;
+    }
+    const unsigned long long items = __ballot(is_item);
+    const int n_it = __popcll(items);
     int ci0 = x;
     if (MODE == kMrFirst) {  // the items are packed in the order the workgroups arrive: one addition per workgroup
         if (lane == 0)
@@ -363,17 +417,17 @@ __global__ void __launch_bounds__(kMrWaves *kWave) k_mr_items(StepArgs a, ModDim
         if (ci0 < 0 || ci0 + n_it > 3 * a.count * (K + 1))
             return;  // (not reachable while the counter is cleared every step)
     }
-    const int32_t u_self = !valid ? -1 : (MODE == kMrSingle && x >= n_u ? a.neg[x - n_u] : a.qs.node[q]);
-    for (int it = 0; it < n_it; ++it) {
-        const int j = MODE == kMrFirst && it < cnt_x ? it : K;
-        const int ci = ci0 + it;
+    int rank = 0;
+    for (unsigned long long left = items; left != 0ull; left &= left - 1ull, ++rank) {
+        const int it = __ffsll((long long)left) - 1;  // (uniform)
+        const int j = __shfl(my_j, it);
+        const int32_t u = __shfl(my_u, it);
+        const int ci = ci0 + rank;
         const bool hop = j < K;
         int cnt_item = cnt_x;
-        int32_t u = u_self;
         if (hop) {
             const int c = p.hop2.cnt[(size_t)q * K + j];
             cnt_item = c < 0 ? 0 : (c > K ? K : c);
-            u = a.qs.nbr[(size_t)q * K + j];
         }
         if (lane == 0) {
             p.mr_itq[ci] = q;
@@ -383,7 +437,7 @@ __global__ void __launch_bounds__(kMrWaves *kWave) k_mr_items(StepArgs a, ModDim
                 p.mr_ci[(size_t)x * (K + 1) + j] = ci;
         }
         // the item's own row: the node's state row (+ features), or -- second layer -- its first-layer row
-        const float *own1 = MODE == kMrSecond ? p.h1 + (size_t)p.mr_ci[(size_t)x * (K + 1) + K] * E : nullptr;
+        const float *own1 = MODE == kMrSecond ? p.h1 + (size_t)mr_item_of(p, (size_t)x * (K + 1) + K) * E : nullptr;
         for (int jj = lane; jj < da; jj += kWave) {
             float v;
             if (jj >= M)
@@ -436,7 +490,7 @@ __global__ void __launch_bounds__(kModThreads) k_mr_attn(StepArgs a, ModDims d, 
         my_eid = tab.eid[trow * K + lane];
         my_dt = t_q - tab.ts[trow * K + lane];
         if (MODE == kMrSecond)  // (second layer: item ci is query row x = ci; its slot's first-layer row)
-            my_src = p.mr_ci[(size_t)ci * (K + 1) + lane];
+            my_src = mr_item_of(p, (size_t)ci * (K + 1) + lane);
     }
     // kvr[u][c] = column c * 64 + lane of the raw row [row of the neighbour | e | Phi(t - t_k)] of slot k0 + u
     auto load_chunk = [&](float (&kvr)[kMrCH][CC], int k0) {
@@ -719,6 +773,11 @@ static size_t mod_layout(const Dims &d, int agg, int upd, int emb, int layers, b
             q.hop2.ts = (double *)take(R2 * d.K, 8);
             q.h1 = (float *)take((size_t)3 * d.max_batch * (d.K + 1) * E, 4);
             q.mr_ci = (int32_t *)take((size_t)3 * d.max_batch * (d.K + 1), 4);
+            size_t slots = 1024;
+            while (slots < (size_t)2 * 3 * d.max_batch * (d.K + 1))
+                slots *= 2;
+            q.mr_tab = (uint32_t *)take(slots, 4);
+            q.mr_tab_mask = (uint32_t)(slots - 1);
         }
         {   // the items' matrices: widths of the wider layer
             const size_t items = (size_t)3 * d.max_batch * (q.layers == 2 ? d.K + 1 : 1);
@@ -775,7 +834,7 @@ bool modules_supported(const Dims &d, const tig_modules &m)
     const ModDims md = mod_dims(d, p);
     if (m.embedding != TIG_EMB_ATTENTION && d.E != d.M)
         return false;
-    if (m.num_layers == 2 && (m.embedding != TIG_EMB_ATTENTION || (d.E + d.T) % d.H != 0))
+    if (m.num_layers == 2 && (m.embedding != TIG_EMB_ATTENTION || (d.E + d.T) % d.H != 0 || d.K + 1 > kWave))
         return false;
     return d.prec == TIG_FP32 && update_lds(md) <= 160 * 1024 && msgsum_lds(md) <= 64 * 1024 && decode_lds(md) <= 160 * 1024 && d.K <= kModThreads &&
            (m.embedding != TIG_EMB_ATTENTION || (d.H <= kMrMaxHeads && d.H * d.K <= kWave && d.dkv <= kMrCC * kWave &&
@@ -980,7 +1039,8 @@ hipError_t launch_modules(const Dims &d, const LaunchPlan &plan, const PackedWei
         };
         if (p.layers == 2) {
             const ModDims md2 = second_layer_dims(md);
-            if ((e = launch_fill_zero(p.mr_n, 4, s)) != hipSuccess)
+            if ((e = launch_fill_zero(p.mr_n, 4, s)) != hipSuccess ||
+                (e = launch_fill_zero(p.mr_tab, ((size_t)p.mr_tab_mask + 1) * 4, s)) != hipSuccess)
                 return e;
             hipLaunchKernelGGL(k_mod_hop2, dim3(3 * B), dim3(kModThreads), 0, s, b, md, p);
             layer_pass(md, p.L[0], kMrFirst);

@@ -322,8 +322,10 @@ struct ModParams {
     float *mr_qin, *mr_qv, *mr_qt, *mr_kvb, *mr_o, *mr_x1, *mr_h1;
     int32_t *mr_has;                           // [items] 1 for an item with at least one filled neighbour slot
     int32_t *mr_itq, *mr_itj;                  // [items] the item's query row and slot (K: the query itself)
-    int32_t *mr_ci;                            // [3 * max_batch x (K + 1)] item of (query row x, slot j), first layer
+    int32_t *mr_ci;                            // [3 * max_batch x (K + 1)] first layer: item of (query row x, slot j), or -(1 + the (x, j) index that represents its (node, t) pair)
     int32_t *mr_n;                             // [1] items of the first layer (cleared every step)
+    uint32_t *mr_tab;                          // first layer: claims of equal (node, t) pairs, 1 + the claimant's (x, j) index, 0 = empty (cleared every step)
+    uint32_t mr_tab_mask;                      // its size - 1 (a power of two)
     const float *T_d1, *b_d1, *w_d2, *b_d2;    // decoder: [2E x E], [E], [E], [1]
     const float *node_feat;                    // [N x M] or NULL
     const float *time_proj_w;                  // [M] or NULL
