@@ -63,8 +63,8 @@ __device__ inline void matvec_t(const float *WT, int in, int out, const float *x
 {
     for (int j = threadIdx.x; j < out; j += kModThreads) {
         float acc = bias ? bias[j] : 0.0f;
-#pragma unroll 8
-        for (int i = 0; i < in; ++i)  // (unrolled: eight independent loads in flight, not one per step)
+#pragma unroll 16
+        for (int i = 0; i < in; ++i)  // (unrolled: sixteen independent loads in flight, not one per step)
             acc += WT[(size_t)i * out + j] * x[i];
         y[j] = acc;
     }
@@ -634,8 +634,8 @@ __global__ void __launch_bounds__(kModThreads) k_mod_decode(StepArgs a, ModDims 
 #pragma unroll
         for (int ev = 0; ev < kEV; ++ev)
             ya[ev] = yb[ev] = yn[ev] = 0.0f;
-#pragma unroll 4
-        for (int i = 0; i < E; ++i) {  // (unrolled: the weight loads of four steps are in flight together)
+#pragma unroll 10
+        for (int i = 0; i < E; ++i) {  // (unrolled: the weight loads of ten steps are in flight together)
             const float wa = p.T_d1[(size_t)i * E + j], wb = p.T_d1[(size_t)(E + i) * E + j];
 #pragma unroll
             for (int ev = 0; ev < kEV; ++ev) {
