@@ -468,9 +468,10 @@ def main():
     ap.add_argument("--sep", action="store_true",
                     help="also run the streaming edge partitioner (Sec. II-B) over the workload's whole event "
                          "stream (8 partitions, 1 %% hubs) and report its stages in a \"sep\" object")
-    ap.add_argument("--train", action="store_true",
-                    help="also time training steps (forward, BCE loss, backward, SGD; fp32, deferred message "
-                         "order) on the same window and report them in a \"train\" object")
+    ap.add_argument("--train", action="store_true", help="(the default; kept for older command lines)")
+    ap.add_argument("--no-train", action="store_true",
+                    help="skip the training steps (forward, BCE loss, backward, SGD; fp32, deferred message order) "
+                         "that are otherwise timed on the same window and reported in a \"train\" object")
     ap.add_argument("--modules", default=None,
                     help="also time other instances of the general architecture (comma-separated names of "
                          "MODULE_INSTANCES, or 'all') on the same window and report them in a \"modules\" object")
@@ -664,8 +665,9 @@ def main():
         del src_buf, dst_buf
         roofline["measured_copy_GBps"] = measured_copy_gbs
 
+    info = ctx.launch_info()
     train_report = None
-    if args.train:
+    if not args.no_train:
         ctx.close()
         del ctx
         torch.cuda.empty_cache()
@@ -677,7 +679,6 @@ def main():
     if args.modules:
         names_m = list(MODULE_INSTANCES) if args.modules == "all" else args.modules.split(",")
         if ctx is not None:
-            info_kept = ctx.launch_info()
             ctx.close()
             ctx = None
             torch.cuda.empty_cache()
@@ -688,9 +689,6 @@ def main():
     if args.sep:
         sep_report = bench_sep(g, w, torch)
 
-    info = ctx.launch_info() if ctx is not None else {"kernels_per_step": 2}
-    if ctx is None and args.modules and not args.train:
-        info = info_kept
     line = {
         "metric": "events/sec per TGN batch step (1 MI355X)",
         "value": round(value, 1),
