@@ -76,124 +76,206 @@ __device__ inline floatx4 load_k4(const float *row, int k, int Kd, bool ok, int 
     return v;
 }
 
+// acc += the part over k in [k_lo, k_hi) (k_lo a multiple of 16) of one block of 32 rows x 32 columns
+// of product z of p, by one wavefront: rows r0 .., columns 32 tn ..
 template <bool VEC>
-__global__ void __launch_bounds__(256) k_rowgemm(RowGemm p)
+__device__ inline void rowgemm_accumulate(const RowGemm &p, int rows, int r0, int tn, int z, int pass, int k_lo, int k_hi,
+                                          floatx4 (&acc)[2][2])
 {
-    const int rows = row_count(p.rc);
-    const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+    const int lane = threadIdx.x & (kWave - 1);
     const int c = lane & 15, g = lane >> 4;
-    const int tiles_n = (p.N + 31) / 32;
-    const int tn = (int)blockIdx.y * 4 + w;  // this wavefront's block of 32 columns
-    if (tn >= tiles_n)
-        return;
     const int n0 = tn * 32;
     const int split = p.n_split > 0 ? p.n_split : p.N;
-    for (int r0 = (int)blockIdx.x * 32; r0 < rows; r0 += (int)gridDim.x * 32) {
-        // the two rows whose operand this lane loads (rows r0 + c and r0 + 16 + c)
-        size_t arow[2];
-        bool aok[2];
+    // the two rows whose operand this lane loads (rows r0 + c and r0 + 16 + c)
+    size_t arow[2];
+    bool aok[2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int r = r0 + 16 * i + c;
-            const bool ok = r < rows;
-            arow[i] = (size_t)(ok ? r : 0);
-            aok[i] = ok;
+    for (int i = 0; i < 2; ++i) {
+        const int r = r0 + 16 * i + c;
+        const bool ok = r < rows;
+        arow[i] = (size_t)(ok ? r : 0);
+        aok[i] = ok;
+    }
+    const float *A = pass ? p.A2 : p.A + (size_t)z * p.zA, *W = pass ? p.W2 : p.W + (size_t)z * p.zW;
+    const int lda = pass ? p.lda2 : p.lda, ldw = pass ? p.ldw2 : p.ldw, Kd = pass ? p.Kd2 : p.Kd;
+    const int vA = pass ? p.vecA2 : p.vecA, vW = pass ? p.vecW2 : p.vecW;
+    const float *ar[2] = {A + arow[0] * lda, A + arow[1] * lda};
+    const int nn0 = n0 + c, nn1 = n0 + 16 + c;
+    const bool wok[2] = {nn0 < p.N, nn1 < p.N};
+    const float *wr[2];
+    int wkd[2];  // length of the lane's weight rows
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int nn = wok[i] ? (i ? nn1 : nn0) : 0;
+        const bool hi = nn >= split;  // (no second pass with a split)
+        wr[i] = hi ? p.W_hi + (size_t)(nn - split) * (p.ldw_hi ? p.ldw_hi : ldw) : W + (size_t)nn * ldw;
+        wkd[i] = hi && p.Kd_hi ? p.Kd_hi : Kd;
+    }
+    const int k_end = k_hi < Kd ? k_hi : Kd;
+    constexpr int kU = 4;  // steps of 16 k whose loads are issued together
+    for (int k0 = k_lo; k0 < k_end; k0 += 16 * kU) {
+        floatx4 av[kU][2], wv[kU][2];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int kk = k0 + 16 * u + 4 * g;
+            const bool on = k0 + 16 * u < k_end;  // (uniform)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                av[u][i] = load_k4<VEC>(ar[i], kk, Kd, aok[i] && on, vA);
+                wv[u][i] = load_k4<VEC>(wr[i], kk, wkd[i], wok[i] && on, vW);
+            }
         }
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            if (k0 + 16 * u >= k_end)
+                break;  // (uniform: nothing but zeros was loaded for this step)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][i][v], wv[u][j][v], acc[i][j], 0, 0, 0);
+        }
+    }
+}
+
+// Epilogue and store of the 16 x 16 sub-blocks (i, j) with i in [i_lo, i_hi), j in [j_lo, j_hi) of the block.
+__device__ inline void rowgemm_store(const RowGemm &p, int rows, int r0, int tn, int z, const floatx4 (&acc)[2][2], int i_lo,
+                                     int i_hi, int j_lo, int j_hi)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int c = lane & 15, g = lane >> 4;
+    const int n0 = tn * 32;
+    const int split = p.n_split > 0 ? p.n_split : p.N;
+    int nu = 0;
+    if (p.remap_nu) {
+        nu = *p.remap_nu;
+        nu = nu < 0 ? 0 : (nu < p.remap_2b ? nu : p.remap_2b);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int r = r0 + 16 * i + 4 * g + v;
+            if (r >= rows || i < i_lo || i >= i_hi)
+                continue;
+            int orow = r;
+            const bool dead = p.rowmask && p.rowmask[orow] == 0;
+            if (p.remap_nu)
+                orow = r < nu ? r : p.remap_2b + (r - nu);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int n = n0 + 16 * j + c;
+                if (n >= p.N || j < j_lo || j >= j_hi)
+                    continue;
+                const bool hi = n >= split;
+                const float *bias = hi ? p.bias_hi : (p.bias ? p.bias + (size_t)z * p.zBias : nullptr);
+                float val = acc[i][j][v] + (bias ? bias[hi ? n - split : n] : 0.0f);
+                if (p.relu)
+                    val = fmaxf(val, 0.0f);
+                if (p.gate && !(p.gate[(size_t)orow * p.ldg + n] > 0.0f))
+                    val = 0.0f;
+                if (dead && !hi)
+                    val = 0.0f;
+                if (hi)
+                    p.C_hi[(size_t)orow * p.ldc_hi + (n - split)] = val;
+                else
+                    p.C[(size_t)z * p.zC + (size_t)orow * p.ldc + n] = val;
+            }
+        }
+}
+
+template <bool VEC>
+__device__ inline void rowgemm_tile(const RowGemm &p, int rows, int r0, int tn, int z)
+{
+    floatx4 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            acc[i][j] = floatx4{0, 0, 0, 0};
+    for (int pass = 0; pass < (p.A2 ? 2 : 1); ++pass)
+        rowgemm_accumulate<VEC>(p, rows, r0, tn, z, pass, 0, pass ? p.Kd2 : p.Kd, acc);
+    rowgemm_store(p, rows, r0, tn, z, acc, 0, 2, 0, 2);
+}
+
+// The same product with the k range of a block split over the four wavefronts of a workgroup
+// (partial blocks added up in LDS; wavefront w then finishes sub-block (w / 2, w % 2)): for products
+// over few rows, where one wavefront per block leaves one wavefront per SIMD walking its whole k
+// range as a chain of load -> multiply rounds with nothing to overlap them.
+template <bool VEC>
+__global__ void __launch_bounds__(256) k_rowgemm_ks(RowGemm p)
+{
+    __shared__ float red[4][16][kWave];
+    const int rows = row_count(p.rc);
+    const int lane = threadIdx.x & (kWave - 1), w = (int)threadIdx.x / kWave;
+    const int tn = (int)blockIdx.y, z = (int)blockIdx.z;
+    const int kq = ((p.Kd + 3) / 4 + 15) / 16 * 16;  // k per wavefront, a multiple of 16
+    for (int r0 = (int)blockIdx.x * 32; r0 < rows; r0 += (int)gridDim.x * 32) {
         floatx4 acc[2][2];
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
                 acc[i][j] = floatx4{0, 0, 0, 0};
-        for (int pass = 0; pass < (p.A2 ? 2 : 1); ++pass) {
-            const float *A = pass ? p.A2 : p.A + (size_t)blockIdx.z * p.zA, *W = pass ? p.W2 : p.W + (size_t)blockIdx.z * p.zW;
-            const int lda = pass ? p.lda2 : p.lda, ldw = pass ? p.ldw2 : p.ldw, Kd = pass ? p.Kd2 : p.Kd;
-            const int vA = pass ? p.vecA2 : p.vecA, vW = pass ? p.vecW2 : p.vecW;
-            const float *ar[2] = {A + arow[0] * lda, A + arow[1] * lda};
-            const int nn0 = n0 + c, nn1 = n0 + 16 + c;
-            const bool wok[2] = {nn0 < p.N, nn1 < p.N};
-            const float *wr[2];
-            int wkd[2];  // length of the lane's weight rows
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int nn = wok[i] ? (i ? nn1 : nn0) : 0;
-                const bool hi = nn >= split;  // (no second pass with a split)
-                wr[i] = hi ? p.W_hi + (size_t)(nn - split) * (p.ldw_hi ? p.ldw_hi : ldw) : W + (size_t)nn * ldw;
-                wkd[i] = hi && p.Kd_hi ? p.Kd_hi : Kd;
-            }
-            constexpr int kU = 4;  // steps of 16 k whose loads are issued together
-            for (int k0 = 0; k0 < Kd; k0 += 16 * kU) {
-                floatx4 av[kU][2], wv[kU][2];
-#pragma unroll
-                for (int u = 0; u < kU; ++u) {
-                    const int kk = k0 + 16 * u + 4 * g;
-#pragma unroll
-                    for (int i = 0; i < 2; ++i) {
-                        av[u][i] = load_k4<VEC>(ar[i], kk, Kd, aok[i], vA);
-                        wv[u][i] = load_k4<VEC>(wr[i], kk, wkd[i], wok[i], vW);
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < kU; ++u) {
-                    if (k0 + 16 * u >= Kd)
-                        break;  // (uniform: nothing but zeros was loaded for this step)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v)
-#pragma unroll
-                        for (int i = 0; i < 2; ++i)
-#pragma unroll
-                            for (int j = 0; j < 2; ++j)
-                                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][i][v], wv[u][j][v], acc[i][j], 0, 0, 0);
-                }
-            }
-        }
-        int nu = 0;
-        if (p.remap_nu) {
-            nu = *p.remap_nu;
-            nu = nu < 0 ? 0 : (nu < p.remap_2b ? nu : p.remap_2b);
-        }
+        rowgemm_accumulate<VEC>(p, rows, r0, tn, z, 0, w * kq, (w + 1) * kq, acc);
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int r = r0 + 16 * i + 4 * g + v;
-                if (r >= rows)
-                    continue;
-                int orow = r;
-                const bool dead = p.rowmask && p.rowmask[orow] == 0;
-                if (p.remap_nu)
-                    orow = r < nu ? r : p.remap_2b + (r - nu);
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const int n = n0 + 16 * j + c;
-                    if (n >= p.N)
-                        continue;
-                    const bool hi = n >= split;
-                    const float *bias = hi ? p.bias_hi : (p.bias ? p.bias + (size_t)blockIdx.z * p.zBias : nullptr);
-                    float val = acc[i][j][v] + (bias ? bias[hi ? n - split : n] : 0.0f);
-                    if (p.relu)
-                        val = fmaxf(val, 0.0f);
-                    if (p.gate && !(p.gate[(size_t)orow * p.ldg + n] > 0.0f))
-                        val = 0.0f;
-                    if (dead && !hi)
-                        val = 0.0f;
-                    if (hi)
-                        p.C_hi[(size_t)orow * p.ldc_hi + (n - split)] = val;
-                    else
-                        p.C[(size_t)blockIdx.z * p.zC + (size_t)orow * p.ldc + n] = val;
-                }
-            }
+                for (int v = 0; v < 4; ++v)
+                    red[w][(i * 2 + j) * 4 + v][lane] = acc[i][j][v];
+        __syncthreads();
+        const int si = w >> 1, sj = w & 1;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (i == si && j == sj)
+                        acc[i][j][v] = (red[0][(i * 2 + j) * 4 + v][lane] + red[1][(i * 2 + j) * 4 + v][lane]) +
+                                       (red[2][(i * 2 + j) * 4 + v][lane] + red[3][(i * 2 + j) * 4 + v][lane]);
+        rowgemm_store(p, rows, r0, tn, z, acc, si, si + 1, sj, sj + 1);
+        __syncthreads();  // (the partial blocks are reused by the next row block)
     }
+}
+
+template <bool VEC>
+__global__ void __launch_bounds__(256) k_rowgemm(RowGemm p)
+{
+    const int rows = row_count(p.rc);
+    const int tiles_n = (p.N + 31) / 32;
+    const int tn = (int)blockIdx.y * 4 + (int)threadIdx.x / kWave;  // this wavefront's block of 32 columns
+    if (tn >= tiles_n)
+        return;
+    for (int r0 = (int)blockIdx.x * 32; r0 < rows; r0 += (int)gridDim.x * 32)
+        rowgemm_tile<VEC>(p, rows, r0, tn, (int)blockIdx.z);
+}
+
+inline bool rowgemm_all_vec(const RowGemm &g)
+{
+    return g.vecA && g.vecW && g.Kd % 4 == 0 && g.Kd_hi % 4 == 0 && g.ldw_hi % 4 == 0 &&
+           (!g.A2 || (g.vecA2 && g.vecW2 && g.Kd2 % 4 == 0));
 }
 
 // (the row count is known on the device only: at most 1024 row blocks are launched and stride)
 inline void launch_rowgemm(const RowGemm &g, int nz, hipStream_t s)
 {
-    const int row_blocks = (g.rc.rows_max + 31) / 32;
-    const dim3 grid(row_blocks < 1024 ? (row_blocks > 0 ? row_blocks : 1) : 1024, ((g.N + 31) / 32 + 3) / 4, nz);
-    const bool all_vec = g.vecA && g.vecW && g.Kd % 4 == 0 && g.Kd_hi % 4 == 0 && g.ldw_hi % 4 == 0 &&
-                         (!g.A2 || (g.vecA2 && g.vecW2 && g.Kd2 % 4 == 0));
-    if (all_vec)
+    const int row_blocks = (g.rc.rows_max + 31) / 32, tiles_n = (g.N + 31) / 32;
+    const int gx = row_blocks < 1024 ? (row_blocks > 0 ? row_blocks : 1) : 1024;
+    if (!g.A2 && g.Kd >= 64 && row_blocks <= 512) {  // few rows: four wavefronts per block, each a quarter of k
+        const dim3 grid(gx, tiles_n, nz);
+        if (rowgemm_all_vec(g))
+            hipLaunchKernelGGL(k_rowgemm_ks<true>, grid, dim3(256), 0, s, g);
+        else
+            hipLaunchKernelGGL(k_rowgemm_ks<false>, grid, dim3(256), 0, s, g);
+        return;
+    }
+    const dim3 grid(gx, (tiles_n + 3) / 4, nz);
+    if (rowgemm_all_vec(g))
         hipLaunchKernelGGL(k_rowgemm<true>, grid, dim3(256), 0, s, g);
     else
         hipLaunchKernelGGL(k_rowgemm<false>, grid, dim3(256), 0, s, g);
