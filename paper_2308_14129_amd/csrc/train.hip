@@ -590,9 +590,12 @@ __global__ void __launch_bounds__(kTrScatterThreads) k_tr_scatter(StepArgs a, Pa
             }
 #pragma unroll
             for (int u = 0; u < kSC; ++u)
-                if (srow[u] >= 0)
-                    atomicAdd(lds[u] ? &acc[(size_t)(srow[u] & (kScatterSlots - 1)) * M + col[u]]
-                                     : &t.D_STAG[(size_t)srow[u] * M + col[u]], v[u]);
+                if (srow[u] >= 0) {  // (two statements: one LDS and one global instruction, not a flat one)
+                    if (lds[u])
+                        atomicAdd(&acc[(size_t)(srow[u] & (kScatterSlots - 1)) * M + col[u]], v[u]);
+                    else
+                        atomicAdd(&t.D_STAG[(size_t)srow[u] * M + col[u]], v[u]);
+                }
         }
         for (int j0 = 0; j0 < T; j0 += kWave) {
             const bool in = j0 + lane < T;

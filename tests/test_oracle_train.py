@@ -211,3 +211,61 @@ def test_relu_ties_and_inverted_gates(c1):
     _, _, g3 = step(relu_flip=frozenset([("dec", p, j), ("merge", 0, 0)]))
     _, _, g4 = step(relu_flip=frozenset([("merge", 0, 0)]))
     assert g3["b_d1"][j] - g4["b_d1"][j] == pytest.approx(-dlogit * float(W["w_d2"][j]), rel=1e-9)
+
+
+@pytest.mark.parametrize("H", [1, 2, 4])
+def test_reassociated_attention_backward_is_the_direct_form(H):
+    # The training kernels run the attention core with q~_h = W_K,h^T Qv_h (scores <q~_h, kv_k> / sqrt(d_h): the
+    # key bias adds a constant over the slots, which the softmax cancels) and head output W_V,h (sum_k p_hk kv_k)
+    # + b_V,h, forward and backward.  In exact arithmetic that is the direct form the oracle differentiates:
+    # every gradient below is formed both ways in float64.
+    rng = np.random.default_rng(7 + H)
+    c, d_a, d_kv = 7, 8 * H, 11
+    d_h = d_a // H
+    Qv, kv = rng.normal(size=d_a), rng.normal(size=(c, d_kv))
+    W_K, W_V = rng.normal(size=(d_a, d_kv)), rng.normal(size=(d_a, d_kv))
+    b_K, b_V = rng.normal(size=d_a), rng.normal(size=d_a)
+    do = rng.normal(size=d_a)                      # gradient of the heads' outputs
+    # ---- direct form (the oracle's statements)
+    Kp, Vp = kv @ W_K.T + b_K, kv @ W_V.T + b_V
+    o = np.zeros(d_a)
+    dQv, dKp, dVp = np.zeros(d_a), np.zeros_like(Kp), np.zeros_like(Vp)
+    probs = []
+    for h in range(H):
+        sl = slice(h * d_h, (h + 1) * d_h)
+        s = Kp[:, sl] @ Qv[sl] / np.sqrt(d_h)
+        a = np.exp(s - s.max())
+        a /= a.sum()
+        probs.append(a)
+        o[sl] = a @ Vp[:, sl]
+        dVp[:, sl] = np.outer(a, do[sl])
+        da = Vp[:, sl] @ do[sl]
+        ds = a * (da - a @ da)
+        dQv[sl] = ds @ Kp[:, sl] / np.sqrt(d_h)
+        dKp[:, sl] = np.outer(ds, Qv[sl]) / np.sqrt(d_h)
+    dW_K, db_K, dW_V, db_V = dKp.T @ kv, dKp.sum(axis=0), dVp.T @ kv, dVp.sum(axis=0)
+    dkv = dKp @ W_K + dVp @ W_V
+    # ---- re-associated form (what the kernels compute: products over the query, vectors over the slots)
+    o2, dQv2, dkv2 = np.zeros(d_a), np.zeros(d_a), np.zeros_like(kv)
+    dW_K2, dW_V2, db_V2 = np.zeros_like(W_K), np.zeros_like(W_V), np.zeros(d_a)
+    for h in range(H):
+        sl = slice(h * d_h, (h + 1) * d_h)
+        qt = W_K[sl].T @ Qv[sl]                              # q~_h
+        s = kv @ qt / np.sqrt(d_h)                           # scores up to the constant <b_K,h, Qv_h> / sqrt(d_h)
+        a = np.exp(s - s.max())
+        a /= a.sum()
+        assert np.allclose(a, probs[h], rtol=1e-12, atol=1e-15)
+        kvb = a @ kv                                         # sum_k p_hk kv_k
+        o2[sl] = W_V[sl] @ kvb + b_V[sl]
+        dkvb = W_V[sl].T @ do[sl]                            # d(sum_k p_hk kv_k)
+        dW_V2[sl] = np.outer(do[sl], kvb)
+        db_V2[sl] = do[sl]
+        dp = kv @ dkvb
+        ds = a * (dp - a @ dp) / np.sqrt(d_h)                # gradient of <q~_h, kv_k>
+        dqt = ds @ kv
+        dkv2 += np.outer(a, dkvb) + np.outer(ds, qt)
+        dQv2[sl] = W_K[sl] @ dqt
+        dW_K2[sl] = np.outer(Qv[sl], dqt)
+    for got, want in ((o2, o), (dQv2, dQv), (dkv2, dkv), (dW_K2, dW_K), (dW_V2, dW_V), (db_V2, db_V)):
+        assert np.allclose(got, want, rtol=1e-10, atol=1e-12)
+    assert np.abs(db_K).max() < 1e-12                        # softmax shift invariance: the key bias takes no gradient
