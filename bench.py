@@ -188,7 +188,25 @@ def mfma_flops(w, rows_u, winners, precision):
     return issued, useful
 
 
-def bench_train(S, tig, torch, w, g, weights, B, batches, negs, negs_np, mem0, lu0, warm, steps=20, cpu_steps=1):
+def train_flops(w, rows, pairs, winners):
+    """Multiply-adds x 2 of the contractions of one training step as the kernels run them (attention
+    core re-associated: every product over queries, events or winners): forward, backward, weight gradients."""
+    M, T, E, F, H = w.mem_dim, w.time_dim, w.emb_dim, w.feat_dim, w.num_heads
+    da, dkv, D = M + T, M + F + T, 2 * M + T + F
+
+    def mm(r, n, k):
+        return 2.0 * r * n * k
+    fwd = mm(rows, da, da) + mm(rows, dkv, da) + mm(rows, da, dkv) + mm(rows, da, da) + mm(rows, E, da + M) + \
+        mm(rows, E, E) + mm(pairs, E, 2 * E) + mm(winners, 3 * M, D) + mm(winners, 3 * M, M)
+    bwd = mm(pairs, 2 * E, E) + mm(rows, E, E) + mm(rows, da + M, E) + mm(rows, da, da) + mm(rows, dkv, da) + \
+        mm(rows, da, dkv) + mm(rows, da, da) + mm(winners, T, 3 * M)
+    wgr = mm(pairs, E, 2 * E) + mm(pairs, 1, E) + mm(rows, E, E) + mm(rows, E, da + M) + 2 * mm(rows, da, da) + \
+        2 * mm(rows, da, dkv) + mm(winners, 3 * M, D) + mm(winners, 3 * M, M)
+    return fwd + bwd + wgr
+
+
+def bench_train(S, tig, torch, w, g, weights, B, batches, negs, negs_np, mem0, lu0, warm, steps=20, cpu_steps=1,
+                rows_per_step=None, winners_per_step=None):
     """Training steps (fp32 masters, deferred message order: a prediction never sees its own event
     through the memory) over consecutive batches of the timed window, lr = 1e-4; beside them the
     training oracle on `cpu_steps` steps of the same window."""
@@ -215,6 +233,10 @@ def bench_train(S, tig, torch, w, g, weights, B, batches, negs, negs_np, mem0, l
     rep_ = {"steps": n, "ms_per_step": round(dt * 1e3 / n, 3), "events_per_s": round(n * B / dt, 1),
             "order": "deferred", "dtype": "f32", "lr": 1e-4, "workspace_GB": round(ws_bytes / 1e9, 2),
             "loss_first_last": [round(float(losses[0].item()), 5), round(float(losses[-1].item()), 5)]}
+    if rows_per_step and winners_per_step:
+        fl = train_flops(w, rows_per_step, 2 * B, winners_per_step)
+        rep_["contraction_GFLOP_per_step"] = round(fl / 1e9, 2)
+        rep_["fp32_mfma_frac_of_peak"] = round(fl / (dt / n) / 1e12 / FP32_MFMA_PEAK_TFLOPS, 4)
     if cpu_steps > 0:
         from threadpoolctl import threadpool_limits
         from oracle import tig_oracle as O
@@ -672,7 +694,8 @@ def main():
         del ctx
         torch.cuda.empty_cache()
         train_report = bench_train(S, tig, torch, w, g, weights, B, batches, negs, negs_np, mem0, lu0, W_,
-                                   cpu_steps=0 if args.no_cpu_baseline else 1)
+                                   cpu_steps=0 if args.no_cpu_baseline else 1, rows_per_step=rows_sum / n_prof,
+                                   winners_per_step=win_sum / n_prof)
         ctx = None
 
     modules_report = None
