@@ -59,15 +59,25 @@ def resolve_relu_ties(got, grads, ties, rerun):
     return rerun(frozenset(chosen))
 
 
-def run_training(bundle, batches, lr, order, warm_at, then_eval=0):
+def run_training(bundle, batches, lr, order, warm_at, then_eval=0, first_eval=()):
     import torch
     w, g, W0, ix = bundle.w, bundle.g, bundle.W, bundle.ix
     deferred = order == "deferred"
     W = {k: v.copy() for k, v in W0.items()}
-    ctx = make_ctx(w, g, W, "fp32", max(c for _, c in batches), order)
+    ctx = make_ctx(w, g, W, "fp32", max(c for _, c in list(batches) + list(first_eval)), order)
     ctx.train_attach(W)
     st = O.OracleState(*S.make_warm_state(w, g, warm_at))
     ctx.state_import(st.mem, st.last_update)
+    # ordinary steps ahead of the training steps: they prepare the next batch (and, in the deferred
+    # order, run its state update) ahead; a training step must not take that state update over
+    for first, count in first_eval:
+        neg = S.make_negatives(w, g, first, count)
+        ref = O.step(st, g.src, g.dst, g.ts, g.edge_feat, W, first, count, neg, w.num_neighbors, w.num_heads, index=ix,
+                     deferred=deferred)
+        out = ctx.alloc_outputs(count, inspect=True)
+        ctx.step(first, count, torch.from_numpy(neg).to("cuda:0"), out)
+        torch.cuda.synchronize()
+        compare_step(ctx, out, ref, st, 1e-4)
     for n, (first, count) in enumerate(batches):
         print(f"[train {w.name} {order}] step first_eid={first} count={count} lr={lr}", flush=True)
         neg = S.make_negatives(w, g, first, count)
@@ -132,6 +142,14 @@ def test_c1_gradients(c1, order):
 @pytest.mark.parametrize("order", ["update_first", "deferred"])
 def test_c1_sgd_steps_then_evaluation(c1, order):
     run_training(c1, [(6000, 200), (6200, 200), (6400, 200)], 0.01, order, warm_at=6000, then_eval=3)
+
+
+@pytest.mark.parametrize("order", ["update_first", "deferred"])
+def test_c1_evaluation_then_training(c1, order):
+    # consecutive ordinary steps (the second finds its batch prepared, its state update done ahead), then
+    # training steps that continue the stream: gradients, state and outputs as from a cold start
+    run_training(c1, [(6400, 200), (6600, 200)], 0.01, order, warm_at=6000, first_eval=[(6000, 200), (6200, 200)],
+                 then_eval=1)
 
 
 def test_c1_from_reset(c1):
