@@ -21,10 +21,9 @@
 //                   rows added into the distinct embedding rows' gradients
 //   k_tr_scatter    the gradient w.r.t. state rows that this step's GRU wrote goes to those rows;
 //                   time-encoding partial sums per query
-//   k_tr_gru_msg / k_tr_gru_gates / k_tr_gru_time   the GRU's backward pass over the applied
-//                   winners: message rows from the memory as the step found it, gradients of the
-//                   gate pre-activations (the gates themselves are left by the step's GRU launch),
-//                   time-encoding gradient
+//   k_tr_gru_gates / k_tr_gru_time   the GRU's backward pass over the applied winners: message rows
+//                   from the memory as the step found it, gradients of the gate pre-activations (the
+//                   gates themselves are left by the step's GRU launch), time-encoding gradient
 //   k_gemm_tn       every weight gradient is dW = D^T X over the rows' stored (delta, input) pairs:
 //                   a [out x in] contraction over thousands of rows on the matrix cores (fp32
 //                   16x16x4), split over the row range, partial results added with atomics; they run
@@ -625,18 +624,17 @@ __global__ void __launch_bounds__(kTrScatterThreads) k_tr_scatter(StepArgs a, Pa
 }
 
 // ------------------------------------------------------------------------------------------
-// The GRU's backward pass runs as contractions over the applied winners' rows with three small
-// kernels around them (one wavefront per winner): the message rows as the step found the memory
-// (k_tr_gru_msg); after GI = MSG W_i^T + b_i and GH = MSG[:, :M] W_h^T + b_h the gates and the
-// gradients of their pre-activations (k_tr_gru_gates); after DPHI = DGI W_i[:, 2M : 2M + T] the
-// time encoding's gradient (k_tr_gru_time).
+// The GRU's backward pass over the applied winners' rows: the message rows as the step found the
+// memory and the gradients of the gate pre-activations (k_tr_gru_gates, one wavefront per winner; the
+// gates themselves were left by the step's GRU launch); after DPHI = DGI W_i[:, 2M : 2M + T] the time
+// encoding's gradient (k_tr_gru_time).
 __device__ inline bool win_ok(const StepArgs &a, const WinDesc &w)
 {
     return w.node >= 0 && (int64_t)w.node < a.num_nodes && w.other >= 0 && (int64_t)w.other < a.num_nodes &&
            w.entry >= 0 && w.entry < 2 * a.msg_count && w.b >= 0 && w.b < a.msg_count;
 }
 
-__global__ void __launch_bounds__(kTrThreads) k_tr_gru_msg(StepArgs a, PackedWeights pw, TrainDims d, TrainBufs t)
+__global__ void __launch_bounds__(kTrThreads) k_tr_gru_gates(StepArgs a, PackedWeights pw, TrainDims d, TrainBufs t)
 {
     int n_win = *a.n_win;
     n_win = n_win < 2 * a.msg_count ? n_win : 2 * a.msg_count;
@@ -645,6 +643,7 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_gru_msg(StepArgs a, PackedWei
     for (int r = (int)blockIdx.x * kRowWaves + wave_id(); r < n_win; r += (int)gridDim.x * kRowWaves) {
         const WinDesc w = a.win[r];
         const bool ok = win_ok(a, w);
+        // the winner's message row from the memory as the step found it (the weight gradients' input rows)
         const double dt = ok ? w.t - a.lu[w.node] : 0.0;
         for (int j = lane; j < D; j += kWave) {
             float v = 0.0f;
@@ -660,25 +659,15 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_gru_msg(StepArgs a, PackedWei
             }
             t.MSG[(size_t)r * D + j] = v;
         }
-    }
-}
-
-__global__ void __launch_bounds__(kTrThreads) k_tr_gru_gates(StepArgs a, TrainDims d, TrainBufs t)
-{
-    int n_win = *a.n_win;
-    n_win = n_win < 2 * a.msg_count ? n_win : 2 * a.msg_count;
-    const int M = d.M, D = d.Dmsg;
-    const int lane = lane_id();
-    for (int r = (int)blockIdx.x * kRowWaves + wave_id(); r < n_win; r += (int)gridDim.x * kRowWaves) {
-        const WinDesc w = a.win[r];
-        const bool ok = win_ok(a, w);
+        // gradients of the gate pre-activations
         const float *gt = t.GATES + (size_t)r * 4 * M;  // r, z, n, W_hn h + b_hn as the step's GRU launch left them
         float *dgi = t.DGI + (size_t)r * 3 * M, *dgh = t.DGH + (size_t)r * 3 * M;
         for (int j = lane; j < M; j += kWave) {
             const float rg = gt[j], zg = gt[M + j], ng = gt[2 * M + j], ghn = gt[3 * M + j];
             const float dh = ok ? t.D_STAG[(size_t)w.entry * M + j] : 0.0f;
+            const float h = ok ? a.mem[(size_t)w.node * M + j] : 0.0f;  // s_self = the first M entries of the message
             const float dn = dh * (1.0f - zg);
-            const float dz = dh * (t.MSG[(size_t)r * D + j] - ng);  // h = s_self = the first M entries of the message
+            const float dz = dh * (h - ng);
             const float dpre_n = dn * (1.0f - ng * ng);
             const float dpre_r = dpre_n * ghn * rg * (1.0f - rg);
             const float dpre_z = dz * zg * (1.0f - zg);
@@ -1255,8 +1244,7 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
         // GRU backward over the applied winners (their number is known on the device only)
         const int wg = (2 * a.msg_count + kRowWaves - 1) / kRowWaves;
         const dim3 per_win(wg < 256 ? wg : 256);
-        hipLaunchKernelGGL(k_tr_gru_msg, per_win, dim3(kTrThreads), 0, s, a, pwv, td, b);
-        hipLaunchKernelGGL(k_tr_gru_gates, per_win, dim3(kTrThreads), 0, s, a, td, b);
+        hipLaunchKernelGGL(k_tr_gru_gates, per_win, dim3(kTrThreads), 0, s, a, pwv, td, b);
         fork(4);  // state update
         gemm(L.g.W_i, L.g.b_i, 3 * M, D, b.DGI, b.MSG, wins);
         gemm(L.g.W_h, L.g.b_h, 3 * M, M, b.DGH, b.MSG, wins, D);  // h = the first M columns of the message rows
