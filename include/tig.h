@@ -254,20 +254,28 @@ TIG_API int tig_step_static(tig_ctx *ctx, const tig_batch *batch, const tig_out 
 
 /* Size of the training workspace of a configuration (device memory the caller allocates):
  * master weights, gradients and the buffers of the backward pass, about
- * 12 * max_batch * num_neighbors * (mem + feat + time + 4 * (mem + time)) bytes.
- * TIG_EINVAL for a precision other than TIG_FP32 or a row shape the backward kernels cannot hold. */
+ * 12 * max_batch * ((2 * num_neighbors + 4 * num_heads) * (mem + feat + time) + 14 * (mem + time)) bytes
+ * (the raw key / value rows of the neighbour slots and their gradients, and per-query rows).
+ * TIG_EINVAL for a precision other than TIG_FP32 or a row shape the backward kernels cannot hold
+ * (more than 4 heads, heads * neighbours above 64, key / value rows above 512 columns). */
 TIG_API int tig_train_workspace_bytes(const tig_config *cfg, size_t *bytes);
 
 /* Makes a context trainable: `weights` (host or device, as in tig_init; normally the same values)
  * become the master weights in `workspace` (device, 256-byte aligned, owned by the caller until
- * tig_destroy), and the context's prepared weights are rebuilt from them.  Synchronous. */
+ * tig_destroy), and the context's prepared weights are rebuilt from them.  Synchronous.
+ * The first call on a context also creates one HIP stream (default priority, non-blocking) and a few
+ * events, which tig_destroy releases: no device memory, but host-side runtime objects. */
 TIG_API int tig_train_attach(tig_ctx *ctx, const tig_weights *weights, void *workspace, size_t workspace_bytes);
 
 /* One training step on a batch: the step of tig_step (same outputs, same state update, in the
  * context's message order), the loss, the gradient of every weight, and the SGD update with
  * learning rate lr >= 0 (0: gradients only, weights untouched).  batch->neg_dst is required.
- * loss_out: device pointer to one float, or NULL.  Enqueued on the context's stream.  The call
- * prepares its batch itself and leaves nothing prepared for a following call. */
+ * loss_out: device pointer to one float, or NULL.  Enqueued on the context's stream; the weight-gradient
+ * contractions run on the stream that tig_train_attach created, ordered against the context's stream
+ * by events on both ends (they start when their inputs are complete and the context's stream waits for
+ * them ahead of the update), so whatever the caller orders against the context's stream -- later
+ * calls, copies, events -- sees the finished step.  The call prepares its batch itself and leaves
+ * nothing prepared for a following call. */
 TIG_API int tig_train_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, float lr, float *loss_out);
 
 /* Copies the master weights (what = 0) or the gradients of the last training step (what = 1) to
@@ -336,7 +344,13 @@ typedef struct tig_modules {
  * copies of the weights and, if node features are given, a copy of them.  TIG_EINVAL for a
  * precision other than TIG_FP32, an unknown selector, emb_dim != mem_dim with an embedding that
  * needs it, two layers without the attention embedding or without `layer2`, or rows the kernels
- * cannot hold.  Two layers add the second hop's neighbour tables and the first layer's rows:
+ * cannot hold (attention: more than 4 heads, heads * K above 64, key / value rows above 512 columns;
+ * two layers: K above 63).  The attention embedding with node features or two layers runs as
+ * contractions over all items of a layer (distinct queries; first of two layers: also their used
+ * neighbour slots) and keeps the items' matrices here: about items * 4 * (5 * (w + T) + 4 * H *
+ * (w + F + T) + E) bytes with w = max(mem_dim, emb_dim) and items = 3 * max_batch * (K + 1) for two
+ * layers (1 GB at 2.6 M nodes' shape with batch 4000, K = 10), 3 * max_batch for one.  Two layers also
+ * add the second hop's neighbour tables and the first layer's rows:
  * 3 * max_batch * (K * K * 16 + (K + 1) * 4 * E) bytes. */
 TIG_API int tig_modules_workspace_bytes(const tig_config *cfg, const tig_modules *modules, int64_t num_nodes,
                                         size_t *bytes);
