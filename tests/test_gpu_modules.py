@@ -191,6 +191,17 @@ def test_c3_two_layers_twenty_neighbours():
     c.close()
 
 
+@pytest.mark.parametrize("layers", [1, 2])
+def test_c1_four_heads_with_node_features(layers):
+    """Four attention heads (the kernels keep per-head rows in registers: another instantiation) over
+    K = 12 neighbours, node features on, one and two layers."""
+    w = S.WORKLOADS["c1_tiny"].scaled(num_heads=4, num_neighbors=12)
+    c = Case(w, INSTANCES["headline"], True, layers=layers)
+    c.run(list(S.batches(w.num_events, 136))[:4])
+    c.run([(5000, 200), (5200, 77)], warm_at=5000)
+    c.close()
+
+
 def test_two_layers_need_the_attention_embedding_and_their_weights():
     import ctypes
     from paper_2308_14129_amd import tig

@@ -188,6 +188,13 @@ def test_c5_shape_gradients():
     run_training(b, [(30000, 1000), (31000, 1000), (32000, 1000)], 1e-3, "update_first", warm_at=30000)
 
 
+def test_four_heads_gradients():
+    # four attention heads over twelve neighbours (the attention kernels' other instantiation)
+    b = Bundle(S.WORKLOADS["c1_tiny"].scaled(num_heads=4, num_neighbors=12))
+    run_training(b, [(4000, 136), (4136, 200)], 0.0, "deferred", warm_at=4000)
+    run_training(b, [(6000, 150), (6150, 150)], 0.01, "update_first", warm_at=6000, then_eval=1)
+
+
 def test_training_needs_fp32_negatives_and_a_workspace(c1):
     import torch
     from paper_2308_14129_amd import tig
