@@ -78,6 +78,18 @@ hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeight
         mark += marks ? 2 : 0;
         return stamp();
     }
+    if (sp.train && sp.train_side && (sp.side_sel || sp.side_ded)) {
+        // beside the step, ordered after whatever this step prepared for itself (the jobs share the
+        // claim table); the step's stream waits for the side stream ahead of its update
+        const TrainSide &ts = *sp.train_side;
+        const SelectJob no_sel = {};
+        const DedupJob no_ded = {};
+        if ((e = hipEventRecord(ts.fork[kTrainForks - 1], s)) != hipSuccess ||
+            (e = hipStreamWaitEvent(ts.stream, ts.fork[kTrainForks - 1], 0)) != hipSuccess ||
+            (e = launch_prepare(a, sp.side_sel ? *sp.side_sel : no_sel, sp.side_ded ? *sp.side_ded : no_ded, d.K,
+                                ts.stream)) != hipSuccess)
+            return e;
+    }
     if (sp.gru_now && (e = launch_gru(d, plan, pw, a, s)) != hipSuccess)
         return e;
     if ((e = stamp()) != hipSuccess)

@@ -608,13 +608,15 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     };
 
     StepPlan sp = {};
-    SelectJob sel_now = {};
-    DedupJob ded_now = {};
+    SelectJob sel_now = {}, sel_side = {};
+    DedupJob ded_now = {}, ded_side = {};
+    // a training step has no embedding launch to carry such work: it goes to the step's second stream
+    const bool side_prep = train && ctx->have_train_side;
     int launches = 2;  // embedding, closing
 
     // ---- the distinct queries of this batch: prepared by the previous step's embedding launch if
     // that step guessed this batch (it reads the event stream and the adjacency only), else now
-    const bool q_ready = !use_static && !solo && ctx->ahead_q_valid && ctx->ahead_q_first == first &&
+    const bool q_ready = !use_static && !general && ctx->ahead_q_valid && ctx->ahead_q_first == first &&
                          ctx->ahead_q_count == count;
     const int qi = use_static ? 0 : (q_ready ? ctx->qcur ^ 1 : ctx->qcur);
     a.qs = st.qs[qi];
@@ -652,6 +654,9 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
                                          ctx->key[wi ^ 1]};
         if (spare > 0 && one_wg) {
             a.sel = mine;
+        } else if (side_prep && one_wg) {
+            sel_side = mine;
+            sp.side_sel = &sel_side;
         } else {
             sel_now = mine;
             (one_wg ? sp.prep_sel : sp.big_sel) = &sel_now;
@@ -704,6 +709,19 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
             a.fin_msg_key = ctx->key[wi ^ 1];
         }
     }
+    if (side_prep && next_first < ctx->num_events) {
+        const int64_t left = ctx->num_events - next_first;
+        const int32_t guess = left < count ? (int32_t)left : count;
+        if (winners_in_one_launch(guess)) {
+            // (the step that takes the set finishes it: slots, row references)
+            ded_side = make_dedup(st, st.qs[qi ^ 1], next_first, guess, next_epoch(), true);
+            sp.side_ded = &ded_side;
+            if (!q_ready)
+                sp.clear_first = st.qs[qi ^ 1].n_u;
+        }
+    }
+    if (sp.side_sel || sp.side_ded)
+        launches += 1;
     // ---- The closing launch also runs the GRU of the batch the next step applies, once that batch's
     // winners are known: in the update-first order the guessed batch (selected by this step's
     // embedding launch), in the deferred order this step's own batch (whatever comes next).
@@ -713,7 +731,7 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
         else if (d.deferred)
             sp.ahead = GruAhead{first, count, st.win[wi ^ 1], st.n_win[wi ^ 1]};
     }
-    if (clear_tab && !sp.prep_ded && a.ded.count > 0) {
+    if (clear_tab && !sp.prep_ded && (a.ded.count > 0 || sp.side_ded)) {
         // the epoch wrapped and only the side job uses the table: clear it ahead of everything
         const hipError_t e = launch_fill_zero(st.tab, sizeof(unsigned long long) * (size_t)st.tab_slots, ctx->stream);
         if (e != hipSuccess)
@@ -763,10 +781,11 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
         return TIG_OK;  // the context's own lists and sets are untouched: winners and queries prepared ahead stay usable
     ctx->epoch = epoch;
     ctx->qcur = qi;
-    ctx->ahead_q_valid = a.ded.count > 0;
+    const DedupJob &ded_ahead = sp.side_ded ? ded_side : a.ded;
+    ctx->ahead_q_valid = ded_ahead.count > 0;
     ctx->ahead_q_finished = a.fin_count > 0;
-    ctx->ahead_q_first = a.ded.first_eid;
-    ctx->ahead_q_count = a.ded.count;
+    ctx->ahead_q_first = ded_ahead.first_eid;
+    ctx->ahead_q_count = ded_ahead.count;
     if (d.deferred) {
         ctx->wcur = wi ^ 1;  // the list just selected is the one the next step applies
         ctx->pend_valid = true;

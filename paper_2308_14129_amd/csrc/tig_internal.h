@@ -257,6 +257,10 @@ struct StepPlan {
     float lr;
     float *loss_out;
     const struct TrainSide *train_side;  // NULL, or the side stream of the weight-gradient contractions
+    // a training step with a side stream: preparation that nothing of this step reads (this batch's
+    // selection in the deferred order, the next batch's queries), launched on that stream; or NULL
+    const SelectJob *side_sel;
+    const DedupJob *side_ded;
     int32_t *clear_first;       // a counter to clear ahead of everything, or NULL
     GruAhead ahead;             // GRU workgroups of the closing launch
     const struct ModParams *mods;  // a context with a module selection: its kernels instead of GRU, embedding and closing launches
@@ -287,7 +291,7 @@ hipError_t train_copy_out(const Dims &d, void *workspace, bool grads, const tig_
 // but their own (delta, input) rows, so they run beside the rest of the backward pass; `fork[i]` is
 // recorded on the step's stream when the rows of group i are complete, `join` on the side stream
 // after the last contraction (the step's stream waits for it ahead of the update).
-constexpr int kTrainForks = 6;
+constexpr int kTrainForks = 7;  // (the last one: the preparation launched beside the step)
 struct TrainSide {
     hipStream_t stream;
     hipEvent_t fork[kTrainForks], join;
