@@ -124,8 +124,16 @@ __global__ void __launch_bounds__(kGatherWaves *kWave) k_tr_gather(StepArgs a, P
     int n_u = *a.qs.n_u;
     n_u = n_u < 2 * a.count ? n_u : 2 * a.count;
     const int n_rows = n_u + a.count;
-    if (blockIdx.x == 0 && threadIdx.x == 0)
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
         *t.n_rows = n_rows;
+        if (a.rows_seen) {
+            // hints for the host, as the embedding launch of an ordinary step leaves them: they size
+            // the next step's launches (the GRU's column slices follow the winner count)
+            a.rows_seen[0] = n_rows;
+            if (a.msg_count > 0)
+                a.rows_seen[1] = *a.n_win;
+        }
+    }
     const int x = (int)blockIdx.x * kGatherWaves + wave_id();
     const bool live_row = x < n_rows;  // (uniform over the wavefront; every wavefront reaches the barriers)
     const int lane = lane_id();
