@@ -432,7 +432,7 @@ hipError_t launch_closing(const Dims &d, const LaunchPlan &plan, const PackedWei
     g.clear = a.qs.n_u;
     DecodeParams p = no_closing(d);
     p.n_event_blocks = events ? (a.count + kGruWaves - 1) / kGruWaves : 0;  // (a training step decodes itself)
-    const bool expand = a.out_nbr_node || a.out_nbr_eid || a.out_nbr_ts || a.out_nbr_cnt || a.out_is_winner;
+    const bool expand = wants_inspection(a);
     p.n_expand_blocks = expand ? (a.roles * a.count + kGruWaves - 1) / kGruWaves : 0;
     if (a.fin_count > 0) {
         p.n_fin_row_blocks = (2 * a.fin_count + kGruWaves - 1) / kGruWaves;

@@ -98,10 +98,10 @@ hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeight
         if ((e = launch_train(d, a, sp.train_ws, sp.packed, sp.pw_out, sp.lr, sp.loss_out, s, sp.train_side)) != hipSuccess ||
             (e = stamp()) != hipSuccess)
             return e;
-        // inspection outputs, and the query set's counter cleared for its next preparation
-        if ((e = launch_closing(d, plan, *sp.pw_out, a, GruAhead{}, s, false)) != hipSuccess || (e = stamp()) != hipSuccess)
+        // inspection outputs, if any are asked for (the training step has cleared its query set's counter)
+        if (wants_inspection(a) && (e = launch_closing(d, plan, *sp.pw_out, a, GruAhead{}, s, false)) != hipSuccess)
             return e;
-        return hipSuccess;
+        return stamp();
     }
     if ((e = launch_embed(d, plan, pw, a, s)) != hipSuccess || (e = stamp()) != hipSuccess)
         return e;

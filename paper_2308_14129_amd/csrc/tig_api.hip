@@ -758,7 +758,7 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
     // bit i: the interval between marks i and i + 1 held a kernel (a module selection's kernels fill
     // intervals 3 and 4)
     ctx->last_ran = (sp.big_sel ? 3u : 0u) | ((sp.prep_sel || sp.prep_ded) ? 4u : 0u) |
-                    ((sp.mods || sp.gru_now) ? 8u : 0u) | 16u | (sp.mods ? 0u : 32u);
+                    ((sp.mods || sp.gru_now) ? 8u : 0u) | 16u | ((sp.mods || (train && !wants_inspection(a))) ? 0u : 32u);
     if (e != hipSuccess) {
         // kernels of this step may already be enqueued: nothing prepared ahead is trusted any more,
         // and the model state is undefined until tig_reset / tig_state_import

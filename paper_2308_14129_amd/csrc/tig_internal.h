@@ -265,6 +265,11 @@ struct StepPlan {
     GruAhead ahead;             // GRU workgroups of the closing launch
     const struct ModParams *mods;  // a context with a module selection: its kernels instead of GRU, embedding and closing launches
 };
+// does the step copy neighbour lists or winner flags out
+inline bool wants_inspection(const StepArgs &a)
+{
+    return a.out_nbr_node || a.out_nbr_eid || a.out_nbr_ts || a.out_nbr_cnt || a.out_is_winner;
+}
 hipError_t launch_step(const Dims &d, const LaunchPlan &plan, const PackedWeights &pw,
                        const StepArgs &a, const StepPlan &sp, hipStream_t s, hipEvent_t *marks);
 hipError_t launch_fill_zero(void *ptr, size_t bytes, hipStream_t s);

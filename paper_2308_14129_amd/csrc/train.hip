@@ -845,13 +845,6 @@ __global__ void __launch_bounds__(256) k_colsum(float *out, const float *A, int 
         atomicAdd(&out[j], acc);
 }
 
-__global__ void k_sgd(float *P, const float *G, size_t n, float lr)
-{
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
-        P[i] -= lr * G[i];
-}
-
 // The transposed copies of all weight matrices in one launch: blockIdx.y names the matrix.
 struct TransposeJobs {
     float *dst[9];
@@ -871,14 +864,25 @@ __global__ void k_transpose(TransposeJobs J)  // dst[c][r] = src[r][c]
     }
 }
 
-// The step's last kernel: the memory overwrite (the GRU's backward read the memory as the step found
-// it); one more workgroup adds up the loss terms (terms != NULL).
-__global__ void __launch_bounds__(256) k_tr_commit(StepArgs a, int M, int commit_blocks, const float *terms, int n_terms,
-                                                   float *loss_out)
+// The memory overwrite (the GRU's backward read the memory as the step found it), the sum of the loss
+// terms (one workgroup, if terms != NULL) and the SGD update (the workgroups beyond, if lr != 0), which
+// share nothing; the step's query set is empty again afterwards (its counter is cleared for the set's
+// next preparation).
+__global__ void __launch_bounds__(256) k_tr_update(StepArgs a, int M, int commit_blocks, const float *terms, int n_terms,
+                                                   float *loss_out, float *P, const float *G, size_t n_params, float lr)
 {
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+        *a.qs.n_u = 0;
     if ((int)blockIdx.x < commit_blocks) {
         overwrite_memory(a, M, (int)(blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave),
                          (int)(commit_blocks * (blockDim.x / kWave)));
+        return;
+    }
+    const int loss_blocks = loss_out ? 1 : 0;
+    if ((int)blockIdx.x >= commit_blocks + loss_blocks) {
+        const size_t i = (size_t)((int)blockIdx.x - commit_blocks - loss_blocks) * blockDim.x + threadIdx.x;
+        if (lr != 0.0f && i < n_params)
+            P[i] -= lr * G[i];
         return;
     }
     __shared__ float red[256];
@@ -1271,16 +1275,15 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
     // the memory overwrite comes last: the GRU's backward read the memory as the step found it
     {
         const int commit_blocks = a.msg_count > 0 ? 32 : 0;
-        if (commit_blocks + (loss_out ? 1 : 0) > 0)
-            hipLaunchKernelGGL(k_tr_commit, dim3(commit_blocks + (loss_out ? 1 : 0)), dim3(256), 0, s, a, M, commit_blocks,
-                               b.LOSS, 2 * B, loss_out);
+        const int sgd_blocks = lr != 0.0f ? (int)((L.n_params + 255) / 256) : 0;
+        int blocks = commit_blocks + (loss_out ? 1 : 0) + sgd_blocks;
+        blocks = blocks > 0 ? blocks : 1;  // (block 0 clears the query set's counter whatever else there is to do)
+        hipLaunchKernelGGL(k_tr_update, dim3(blocks), dim3(256), 0, s, a, M, commit_blocks, b.LOSS, 2 * B, loss_out, L.P,
+                           L.G, L.n_params, lr);
     }
     if ((e = hipGetLastError()) != hipSuccess)
         return e;
     if (lr != 0.0f) {
-        hipLaunchKernelGGL(k_sgd, dim3((unsigned)((L.n_params + 255) / 256)), dim3(256), 0, s, L.P, L.G, L.n_params, lr);
-        if ((e = hipGetLastError()) != hipSuccess)
-            return e;
         if ((e = transpose_all(d, L, s)) != hipSuccess)
             return e;
         // the step's own forward pass reads the masters and their transposes; of the prepared weights

@@ -29,7 +29,7 @@ CSRC = os.path.join(HERE, "csrc")
 STEP_KERNELS = ("k_scatter", "k_select", "k_prepare", "k_gru", "k_embed", "k_centrality", "k_topk_keys", "k_topk_flags",
                 "k_tr_gather", "k_rowgemm", "k_tr_attn_fwd", "k_tr_attn_bwd", "k_tr_scatter", "k_tr_pairs", "k_tr_logit",
                 "k_tr_pair_scatter", "k_tr_gru_gates", "k_tr_gru_time", "k_gemm_tn", "k_colsum", "k_gemm64",
-                "k_pack_gru", "k_pack", "k_sgd", "k_transpose", "k_tr_commit",
+                "k_pack_gru", "k_pack", "k_transpose", "k_tr_update",
                 "k_mod_msgsum", "k_mod_update", "k_mod_commit", "k_mod_simple", "k_mod_hop2", "k_mr_items", "k_mr_attn",
                 "k_mod_decode")
 COPY_KIB = 256 * 1024  # one calibration copy reads and writes this much

@@ -152,6 +152,15 @@ def test_c1_evaluation_then_training(c1, order):
                  then_eval=1)
 
 
+@pytest.mark.parametrize("order", ["update_first", "deferred"])
+def test_c1_training_across_a_gap(c1, order):
+    # a training step prepares the queries of the batch it expects next beside its own work: steps that
+    # find that batch prepared (the second and the fourth), one that skips part of the stream and one
+    # with another batch size (the third and the fifth: what was prepared for them is dropped)
+    run_training(c1, [(4000, 100), (4100, 100), (4300, 100), (4400, 100), (4500, 60)], 0.01, order, warm_at=4000,
+                 then_eval=1)
+
+
 def test_c1_from_reset(c1):
     import torch
     # nothing in memory, no neighbours for the first events: empty neighbourhoods and zero rows
