@@ -274,8 +274,9 @@ TIG_API int tig_train_attach(tig_ctx *ctx, const tig_weights *weights, void *wor
  * contractions run on the stream that tig_train_attach created, ordered against the context's stream
  * by events on both ends (they start when their inputs are complete and the context's stream waits for
  * them ahead of the update), so whatever the caller orders against the context's stream -- later
- * calls, copies, events -- sees the finished step.  The call prepares its batch itself and leaves
- * nothing prepared for a following call. */
+ * calls, copies, events -- sees the finished step.  On that stream the call also prepares the queries
+ * of the batch it expects next (the same number of events, continuing where this one ends), as tig_step
+ * does; a following tig_step or tig_train_step on another batch prepares its own. */
 TIG_API int tig_train_step(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, float lr, float *loss_out);
 
 /* Copies the master weights (what = 0) or the gradients of the last training step (what = 1) to
