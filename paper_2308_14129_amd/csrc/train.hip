@@ -232,20 +232,22 @@ __global__ void __launch_bounds__(kGatherWaves *kWave) k_tr_gather(StepArgs a, P
 // is then a product over QUERIES (q~, the output, and in the backward pass their transposes) instead
 // of over the three times as many filled neighbour slots; what is left per slot are dot products
 // and weighted sums of the raw key / value rows, done here by one wavefront per query: the lanes lie
-// along the row (coalesced loads), kAttnCH slots' rows are requested together, and a dot product is
+// along the row (coalesced loads), CH slots' rows are requested together, and a dot product is
 // one wave reduction.
 constexpr int kMaxTrainHeads = 4;
-constexpr int kAttnCH = 4;  // slots per register chunk
-constexpr int kAttnCC = 8;  // 64-column pieces of a row a lane can hold: rows of up to 512 columns
+// CC: 64-column pieces of a row that a lane holds; CH: slots per register chunk.  Instantiated for rows
+// of up to 256 columns with ten slots in flight and for rows of up to 512 columns with four.
+constexpr int kAttnMaxCC = 8;
 
 // kvr[u][c] = column c * 64 + lane of the raw row of slot k0 + u (the last filled slot again beyond cnt)
-__device__ inline void load_kv_chunk(float (&kvr)[kAttnCH][kAttnCC], const float *KV, size_t sb, int k0, int cnt, int dkv, int lane)
+template <int CC, int CH>
+__device__ inline void load_kv_chunk(float (&kvr)[CH][CC], const float *KV, size_t sb, int k0, int cnt, int dkv, int lane)
 {
 #pragma unroll
-    for (int u = 0; u < kAttnCH; ++u) {
+    for (int u = 0; u < CH; ++u) {
         const int k = k0 + u < cnt ? k0 + u : cnt - 1;
 #pragma unroll
-        for (int c = 0; c < kAttnCC; ++c) {
+        for (int c = 0; c < CC; ++c) {
             const int i = c * kWave + lane;
             kvr[u][c] = c * kWave < dkv && i < dkv ? KV[(sb + k) * dkv + i] : 0.0f;  // (the first test is uniform)
         }
@@ -253,35 +255,35 @@ __device__ inline void load_kv_chunk(float (&kvr)[kAttnCH][kAttnCC], const float
 }
 
 // v[h][c] = column c * 64 + lane of head h's row of a per-query [H x dkv] array
-template <int HT>
-__device__ inline void load_head_rows(float (&v)[HT][kAttnCC], const float *rows, int H, int dkv, int lane)
+template <int HT, int CC>
+__device__ inline void load_head_rows(float (&v)[HT][CC], const float *rows, int H, int dkv, int lane)
 {
 #pragma unroll
     for (int h = 0; h < HT; ++h)
 #pragma unroll
-        for (int c = 0; c < kAttnCC; ++c) {
+        for (int c = 0; c < CC; ++c) {
             const int i = c * kWave + lane;
             v[h][c] = h < H && c * kWave < dkv && i < dkv ? rows[(size_t)h * dkv + i] : 0.0f;
         }
 }
 
 // lane h * K + k: <head h's row of v, raw row of slot k> for k < cnt (other lanes: `other`)
-template <int HT>
-__device__ inline float slot_dots(const float (&v)[HT][kAttnCC], const float *KV, size_t sb, int cnt, int H, int K, int dkv,
+template <int HT, int CC, int CH>
+__device__ inline float slot_dots(const float (&v)[HT][CC], const float *KV, size_t sb, int cnt, int H, int K, int dkv,
                                   int lane, float other)
 {
     float res = other;
-    for (int k0 = 0; k0 < cnt; k0 += kAttnCH) {
-        float kvr[kAttnCH][kAttnCC];
-        load_kv_chunk(kvr, KV, sb, k0, cnt, dkv, lane);
+    for (int k0 = 0; k0 < cnt; k0 += CH) {
+        float kvr[CH][CC];
+        load_kv_chunk<CC, CH>(kvr, KV, sb, k0, cnt, dkv, lane);
 #pragma unroll
-        for (int u = 0; u < kAttnCH; ++u)
+        for (int u = 0; u < CH; ++u)
 #pragma unroll
             for (int h = 0; h < HT; ++h)
                 if (h < H && k0 + u < cnt) {  // (uniform)
                     float part = 0.0f;
 #pragma unroll
-                    for (int c = 0; c < kAttnCC; ++c)
+                    for (int c = 0; c < CC; ++c)
                         part += v[h][c] * kvr[u][c];
                     const float sum = wave_sum_uniform(part);
                     if (lane == h * K + k0 + u)
@@ -293,7 +295,7 @@ __device__ inline float slot_dots(const float (&v)[HT][kAttnCC], const float *KV
 
 // Scores, softmax, and the weighted sums KVB[x][h] = sum_k p_hk kv_k of one query per wavefront, from
 // QT = q~ and the raw rows KV of its filled slots: lane h * K + k holds slot k of head h.
-template <int HT>
+template <int HT, int CC, int CH>
 __global__ void __launch_bounds__(kTrThreads) k_tr_attn_fwd(StepArgs a, TrainDims d, TrainBufs t)
 {
     int n_u = *a.qs.n_u;
@@ -319,9 +321,9 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_fwd(StepArgs a, TrainDim
     const float scale = 1.0f / sqrtf((float)dh);
     float sc;
     {
-        float qtr[HT][kAttnCC];
-        load_head_rows<HT>(qtr, t.QT + (size_t)x * H * dkv, H, dkv, lane);
-        sc = slot_dots<HT>(qtr, t.KV, sb, cnt, H, K, dkv, lane, -INFINITY) * scale;
+        float qtr[HT][CC];
+        load_head_rows<HT, CC>(qtr, t.QT + (size_t)x * H * dkv, H, dkv, lane);
+        sc = slot_dots<HT, CC, CH>(qtr, t.KV, sb, cnt, H, K, dkv, lane, -INFINITY) * scale;
     }
     // softmax over the filled slots of the lane's head (every lane walks the head of lane % (H * K))
     const int hl = (lane % (H * K)) / K;
@@ -336,30 +338,30 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_fwd(StepArgs a, TrainDim
     const float pr = mine ? ex / sum : 0.0f;
     if (lane < H * K)
         t.PROB[(size_t)x * H * K + lane] = pr;
-    float acc[HT][kAttnCC];
+    float acc[HT][CC];
 #pragma unroll
     for (int h = 0; h < HT; ++h)
 #pragma unroll
-        for (int c = 0; c < kAttnCC; ++c)
+        for (int c = 0; c < CC; ++c)
             acc[h][c] = 0.0f;
-    for (int k0 = 0; k0 < cnt; k0 += kAttnCH) {
-        float kvr[kAttnCH][kAttnCC];
-        load_kv_chunk(kvr, t.KV, sb, k0, cnt, dkv, lane);
+    for (int k0 = 0; k0 < cnt; k0 += CH) {
+        float kvr[CH][CC];
+        load_kv_chunk<CC, CH>(kvr, t.KV, sb, k0, cnt, dkv, lane);
 #pragma unroll
-        for (int u = 0; u < kAttnCH; ++u)
+        for (int u = 0; u < CH; ++u)
 #pragma unroll
             for (int h = 0; h < HT; ++h)
                 if (h < H && k0 + u < cnt) {  // (uniform: the shuffles are executed by every lane)
                     const float p = __shfl(pr, h * K + k0 + u);
 #pragma unroll
-                    for (int c = 0; c < kAttnCC; ++c)
+                    for (int c = 0; c < CC; ++c)
                         acc[h][c] += p * kvr[u][c];
                 }
     }
 #pragma unroll
     for (int h = 0; h < HT; ++h)
 #pragma unroll
-        for (int c = 0; c < kAttnCC; ++c)
+        for (int c = 0; c < CC; ++c)
             if (h < H && c * kWave + lane < dkv)
                 kvb[(size_t)h * dkv + c * kWave + lane] = acc[h][c];
 }
@@ -453,7 +455,7 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_pair_scatter(StepArgs a, Trai
 // Backward of scores / softmax / weighted sums of one query per wavefront: from the gradient of the
 // weighted sums (DKVB) to the gradient of q~ (DQT) and to the gradients of the raw key / value rows of
 // its filled slots (DKV), which are complete with it.
-template <int HT>
+template <int HT, int CC, int CH>
 __global__ void __launch_bounds__(kTrThreads) k_tr_attn_bwd(StepArgs a, TrainDims d, TrainBufs t)
 {
     int n_u = *a.qs.n_u;
@@ -475,45 +477,45 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_bwd(StepArgs a, TrainDim
         return;
     }
     const float scale = 1.0f / sqrtf((float)dh);
-    float g_kvb[HT][kAttnCC];
-    load_head_rows<HT>(g_kvb, t.DKVB + (size_t)x * H * dkv, H, dkv, lane);
+    float g_kvb[HT][CC];
+    load_head_rows<HT, CC>(g_kvb, t.DKVB + (size_t)x * H * dkv, H, dkv, lane);
     // lane h * K + k: d p_hk = <kv_k, d KVB_h>
-    const float dp = slot_dots<HT>(g_kvb, t.KV, sb, cnt, H, K, dkv, lane, 0.0f);
+    const float dp = slot_dots<HT, CC, CH>(g_kvb, t.KV, sb, cnt, H, K, dkv, lane, 0.0f);
     const float pr = lane < H * K ? t.PROB[(size_t)x * H * K + lane] : 0.0f;  // (zero beyond the filled slots)
     const int hl = (lane % (H * K)) / K;
     float dot = 0.0f;
     for (int k = 0; k < cnt; ++k)
         dot += __shfl(pr, hl * K + k) * __shfl(dp, hl * K + k);
     const float dsv = pr * (dp - dot) * scale;  // gradient of <q~_h, kv_k>
-    float g_qt[HT][kAttnCC], acc[HT][kAttnCC];
-    load_head_rows<HT>(g_qt, t.QT + (size_t)x * H * dkv, H, dkv, lane);
+    float g_qt[HT][CC], acc[HT][CC];
+    load_head_rows<HT, CC>(g_qt, t.QT + (size_t)x * H * dkv, H, dkv, lane);
 #pragma unroll
     for (int h = 0; h < HT; ++h)
 #pragma unroll
-        for (int c = 0; c < kAttnCC; ++c)
+        for (int c = 0; c < CC; ++c)
             acc[h][c] = 0.0f;
-    for (int k0 = 0; k0 < cnt; k0 += kAttnCH) {
-        float kvr[kAttnCH][kAttnCC];
-        load_kv_chunk(kvr, t.KV, sb, k0, cnt, dkv, lane);
+    for (int k0 = 0; k0 < cnt; k0 += CH) {
+        float kvr[CH][CC];
+        load_kv_chunk<CC, CH>(kvr, t.KV, sb, k0, cnt, dkv, lane);
 #pragma unroll
-        for (int u = 0; u < kAttnCH; ++u)
+        for (int u = 0; u < CH; ++u)
             if (k0 + u < cnt) {  // (uniform: the shuffles are executed by every lane)
-                float dk[kAttnCC];  // d kv_k = sum_h p_hk d KVB_h + d s_hk q~_h
+                float dk[CC];  // d kv_k = sum_h p_hk d KVB_h + d s_hk q~_h
 #pragma unroll
-                for (int c = 0; c < kAttnCC; ++c)
+                for (int c = 0; c < CC; ++c)
                     dk[c] = 0.0f;
 #pragma unroll
                 for (int h = 0; h < HT; ++h)
                     if (h < H) {
                         const float ds = __shfl(dsv, h * K + k0 + u), p = __shfl(pr, h * K + k0 + u);
 #pragma unroll
-                        for (int c = 0; c < kAttnCC; ++c) {
+                        for (int c = 0; c < CC; ++c) {
                             acc[h][c] += ds * kvr[u][c];
                             dk[c] += p * g_kvb[h][c] + ds * g_qt[h][c];
                         }
                     }
 #pragma unroll
-                for (int c = 0; c < kAttnCC; ++c)
+                for (int c = 0; c < CC; ++c)
                     if (c * kWave + lane < dkv)
                         t.DKV[(sb + k0 + u) * dkv + c * kWave + lane] = dk[c];
             }
@@ -521,7 +523,7 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_bwd(StepArgs a, TrainDim
 #pragma unroll
     for (int h = 0; h < HT; ++h)
 #pragma unroll
-        for (int c = 0; c < kAttnCC; ++c)
+        for (int c = 0; c < CC; ++c)
             if (h < H && c * kWave + lane < dkv)
                 dqt[(size_t)h * dkv + c * kWave + lane] = acc[h][c];
 }
@@ -610,12 +612,20 @@ __global__ void __launch_bounds__(kTrScatterThreads) k_tr_scatter(StepArgs a, Pa
             float gw = 0.0f, gb = 0.0f;
             if (cnt > 0)  // Phi(0)_j = cos(b_j): only the phase takes a gradient from the query row
                 gb += -time_enc_sin(pw.time_w_rev[j], pw.time_b_rev[j], 0.0) * t.DQIN[(size_t)x * da + M + j];
-            for (int k = 0; k < cnt; ++k) {
-                const double dt = shfl_f64(my_dt, k);
-                const float g = t.DKV[(sb + k) * dkv + M + F + j];
-                const float sn = time_enc_sin(pw.time_w_rev[j], pw.time_b_rev[j], dt);
-                gw += -sn * (float)dt * g;
-                gb += -sn * g;
+            constexpr int kTC = 10;  // slots whose gradient values are requested together (their round trips overlap)
+            for (int k0 = 0; k0 < cnt; k0 += kTC) {
+                float g[kTC];
+#pragma unroll
+                for (int u = 0; u < kTC; ++u)
+                    g[u] = k0 + u < cnt ? t.DKV[(sb + k0 + u) * dkv + M + F + j] : 0.0f;
+#pragma unroll
+                for (int u = 0; u < kTC; ++u)
+                    if (k0 + u < cnt) {  // (uniform: the shuffle is executed by every lane)
+                        const double dt = shfl_f64(my_dt, k0 + u);
+                        const float sn = time_enc_sin(pw.time_w_rev[j], pw.time_b_rev[j], dt);
+                        gw += -sn * (float)dt * g[u];
+                        gb += -sn * g[u];
+                    }
             }
             if (in) {
                 t.TG[(size_t)x * 2 * T + j] = gw;
@@ -1031,7 +1041,7 @@ hipError_t prepare_train(const Dims &d)
 bool train_supported(const Dims &d)
 {
     // (the attention kernels keep slot k of head h in lane h * K + k of a query's wavefront)
-    return d.prec == TIG_FP32 && scatter_lds(d) <= 64 * 1024 && d.H * d.K <= kWave && d.H <= kMaxTrainHeads && d.dkv <= kAttnCC * kWave;
+    return d.prec == TIG_FP32 && scatter_lds(d) <= 64 * 1024 && d.H * d.K <= kWave && d.H <= kMaxTrainHeads && d.dkv <= kAttnMaxCC * kWave;
 }
 
 static hipError_t transpose_all(const Dims &d, const TrainLayout &L, hipStream_t s)
@@ -1168,10 +1178,15 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
         g.vecA = g.vecA && dh % 4 == 0, g.vecW = g.vecW && dh % 4 == 0;
         run(g, H);
     }
-    if (H <= 2)
-        hipLaunchKernelGGL(k_tr_attn_fwd<2>, per_row, dim3(kTrThreads), 0, s, a, td, b);
+    const bool narrow = dkv <= 4 * kWave;
+    if (H <= 2 && narrow)
+        hipLaunchKernelGGL((k_tr_attn_fwd<2, 4, 10>), per_row, dim3(kTrThreads), 0, s, a, td, b);
+    else if (H <= 2)
+        hipLaunchKernelGGL((k_tr_attn_fwd<2, kAttnMaxCC, 4>), per_row, dim3(kTrThreads), 0, s, a, td, b);
+    else if (narrow)
+        hipLaunchKernelGGL((k_tr_attn_fwd<kMaxTrainHeads, 4, 6>), per_row, dim3(kTrThreads), 0, s, a, td, b);
     else
-        hipLaunchKernelGGL(k_tr_attn_fwd<kMaxTrainHeads>, per_row, dim3(kTrThreads), 0, s, a, td, b);
+        hipLaunchKernelGGL((k_tr_attn_fwd<kMaxTrainHeads, kAttnMaxCC, 4>), per_row, dim3(kTrThreads), 0, s, a, td, b);
     {   // o_h = W_V,h KVB_h + b_V,h
         RowGemm g = layer(b.O_, da, b.KVB, H * dkv, b.W_V, dkv, b.b_V, dh, dkv);
         g.zA = dkv, g.zW = dh * dkv, g.zC = dh, g.zBias = dh;
@@ -1231,10 +1246,14 @@ hipError_t launch_train(const Dims &d, const StepArgs &a, void *workspace, void 
         g.vecA = g.vecA && dh % 4 == 0, g.vecW = g.vecW && dh % 4 == 0;
         run(g, H);
     }
-    if (H <= 2)
-        hipLaunchKernelGGL(k_tr_attn_bwd<2>, per_row, dim3(kTrThreads), 0, s, a, td, b);
+    if (H <= 2 && narrow)
+        hipLaunchKernelGGL((k_tr_attn_bwd<2, 4, 10>), per_row, dim3(kTrThreads), 0, s, a, td, b);
+    else if (H <= 2)
+        hipLaunchKernelGGL((k_tr_attn_bwd<2, kAttnMaxCC, 4>), per_row, dim3(kTrThreads), 0, s, a, td, b);
+    else if (narrow)
+        hipLaunchKernelGGL((k_tr_attn_bwd<kMaxTrainHeads, 4, 6>), per_row, dim3(kTrThreads), 0, s, a, td, b);
     else
-        hipLaunchKernelGGL(k_tr_attn_bwd<kMaxTrainHeads>, per_row, dim3(kTrThreads), 0, s, a, td, b);
+        hipLaunchKernelGGL((k_tr_attn_bwd<kMaxTrainHeads, kAttnMaxCC, 4>), per_row, dim3(kTrThreads), 0, s, a, td, b);
     fork(2);  // attention: dW_V,h = d o_h^T KVB_h, dW_K,h = Qv_h^T d q~_h over the queries (the key bias takes no gradient)
     gemm(L.g.W_O, L.g.b_O, da, da, b.D_ATTN, b.O_, rows);
     gemm(L.g.W_V, L.g.b_V, dh, dkv, b.DOUT, b.KVB, rows, H * dkv, da, H, TnBatch{dh * dkv, dh, dkv, dh});
