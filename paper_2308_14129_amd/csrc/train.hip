@@ -534,9 +534,10 @@ __global__ void __launch_bounds__(kTrThreads) k_tr_attn_bwd(StepArgs a, TrainDim
 // gradients; the time-encoding partial sums [gw | gb] of the row are written out.
 // A hub node's staged row is a neighbour of most queries of a batch: its thousands of row additions
 // would queue up on the same addresses.  A workgroup therefore collects the additions of its
-// kScatterRows queries (one per wavefront) in an LDS table of kScatterSlots rows (direct-mapped by staged row; a row
-// whose place is taken goes to memory directly) and adds every table row to memory once.
-constexpr int kScatterRows = 16, kScatterSlots = 64, kTrScatterThreads = 1024;
+// kScatterRows queries (one per wavefront) in an LDS table of kScatterSlots rows (open addressing by staged row with a
+// few probes: a hub's row that lost its place to another row would send all its additions to memory; a row that
+// finds no place goes to memory directly) and adds every table row to memory once.
+constexpr int kScatterRows = 16, kScatterSlots = 64, kScatterProbes = 8, kTrScatterThreads = 1024;
 
 __global__ void __launch_bounds__(kTrScatterThreads) k_tr_scatter(StepArgs a, PackedWeights pw, TrainDims d, TrainBufs t)
 {
@@ -558,11 +559,12 @@ __global__ void __launch_bounds__(kTrScatterThreads) k_tr_scatter(StepArgs a, Pa
         const int q = x < n_u ? x : 2 * a.count + (x - n_u);
         int cnt = a.qs.cnt[q];
         cnt = cnt < 0 ? 0 : (cnt > K ? K : cnt);
-        const size_t sb = slot_rows(a, t, x, K, cnt);
+        const size_t sb = (size_t)__builtin_amdgcn_readfirstlane((int)slot_rows(a, t, x, K, cnt));
+        cnt = __builtin_amdgcn_readfirstlane(cnt);  // (both are the same in every lane: scalars from here on)
         const double t_q = a.qs.t[q];
         // lane k < cnt: neighbour slot k, lane cnt: the query's own row.  Each claims the table row of
         // its staged row (or finds it claimed by another staged row: then the additions go to memory).
-        int my_srow = -1, my_lds = 0;
+        int my_srow = -1, my_lds = -1;  // staged row; its row of the table, or -1: additions go to memory
         double my_dt = 0.0;
         if (lane <= cnt) {
             const int32_t rf = lane < cnt ? a.qs.ref[(size_t)q * K + lane] : a.qs.self_ref[q];
@@ -570,66 +572,113 @@ __global__ void __launch_bounds__(kTrScatterThreads) k_tr_scatter(StepArgs a, Pa
                 my_dt = t_q - a.qs.ts[(size_t)q * K + lane];
             if (rf < 0 && rf != kRefNone && ~rf < 2 * a.msg_count) {
                 my_srow = ~rf;
-                const int old = atomicCAS(&tag[my_srow & (kScatterSlots - 1)], -1, my_srow);
-                my_lds = old == -1 || old == my_srow;
-            }
-        }
-        const int n_el = (cnt + 1) * M;
-        constexpr int kSC = 6;  // values a lane loads before it adds the first (their round trips overlap)
-        for (int e0 = 0; e0 < n_el; e0 += kSC * kWave) {  // (every lane stays in the loop: the shuffles read lanes up to cnt)
-            float v[kSC];
-            int srow[kSC], lds[kSC], col[kSC];
-#pragma unroll
-            for (int u = 0; u < kSC; ++u) {
-                const bool in = e0 + u * kWave + lane < n_el;
-                const int e = in ? e0 + u * kWave + lane : 0;
-                const int k = e / M, i = e - k * M;
-                srow[u] = __shfl(my_srow, k);
-                lds[u] = __shfl(my_lds, k);
-                col[u] = i;
-                if (!in)
-                    srow[u] = -1;
-                v[u] = 0.0f;
-                if (srow[u] >= 0) {
-                    if (k < cnt)
-                        v[u] = t.DKV[(sb + k) * dkv + i];
-                    else
-                        v[u] = t.DSU[(size_t)x * M + i] + (cnt > 0 ? t.DQIN[(size_t)x * da + i] : 0.0f);
+                int h = my_srow & (kScatterSlots - 1);
+                for (int probe = 0; probe < kScatterProbes && my_lds < 0; ++probe) {
+                    const int old = atomicCAS(&tag[h], -1, my_srow);
+                    if (old == -1 || old == my_srow)
+                        my_lds = h;
+                    h = (h + 1) & (kScatterSlots - 1);
                 }
             }
+        }
+        // A lane's memory operations complete in order and a conditional load makes the compiler wait
+        // right behind it: the row's loads are unconditional (clamped indices), requested in batches
+        // ahead of their use, and what follows them in the common case are LDS additions, which the
+        // memory counter does not see.
+        constexpr int kSB = 10, kMP = 2;  // neighbour slots x 64-column pieces of a state row per batch
+        constexpr int kTP = 2, kTC = 10;  // 64-dim pieces of the time encoding x slots per batch of its gradient values
+        if (cnt > 0) {  // (uniform)
+            for (int k0 = 0; k0 < cnt; k0 += kSB)
+                for (int m0 = 0; m0 < M; m0 += kMP * kWave) {
+                    float v[kSB][kMP];
 #pragma unroll
-            for (int u = 0; u < kSC; ++u)
-                if (srow[u] >= 0) {  // (two statements: one LDS and one global instruction, not a flat one)
-                    if (lds[u])
-                        atomicAdd(&acc[(size_t)(srow[u] & (kScatterSlots - 1)) * M + col[u]], v[u]);
-                    else
-                        atomicAdd(&t.D_STAG[(size_t)srow[u] * M + col[u]], v[u]);
+                    for (int u = 0; u < kSB; ++u) {
+                        const int k = k0 + u < cnt ? k0 + u : cnt - 1;
+#pragma unroll
+                        for (int c = 0; c < kMP; ++c) {
+                            const int i = m0 + c * kWave + lane;
+                            v[u][c] = t.DKV[(sb + k) * dkv + (i < M ? i : 0)];
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < kSB; ++u)
+                        if (k0 + u < cnt) {  // (uniform)
+                            const int row = __builtin_amdgcn_readlane(my_lds, k0 + u);
+                            if (row >= 0) {
+#pragma unroll
+                                for (int c = 0; c < kMP; ++c) {
+                                    const int i = m0 + c * kWave + lane;
+                                    if (i < M)
+                                        atomicAdd(&acc[(size_t)row * M + i], v[u][c]);
+                                }
+                            }
+                        }
                 }
         }
-        for (int j0 = 0; j0 < T; j0 += kWave) {
-            const bool in = j0 + lane < T;
-            const int j = in ? j0 + lane : 0;
-            float gw = 0.0f, gb = 0.0f;
-            if (cnt > 0)  // Phi(0)_j = cos(b_j): only the phase takes a gradient from the query row
-                gb += -time_enc_sin(pw.time_w_rev[j], pw.time_b_rev[j], 0.0) * t.DQIN[(size_t)x * da + M + j];
-            constexpr int kTC = 10;  // slots whose gradient values are requested together (their round trips overlap)
+        {   // the query's own row
+            const int srow = __builtin_amdgcn_readlane(my_srow, cnt), row = __builtin_amdgcn_readlane(my_lds, cnt);
+            if (srow >= 0)
+                for (int i = lane; i < M; i += kWave) {
+                    const float v = t.DSU[(size_t)x * M + i] + (cnt > 0 ? t.DQIN[(size_t)x * da + i] : 0.0f);
+                    if (row >= 0)
+                        atomicAdd(&acc[(size_t)row * M + i], v);
+                    else
+                        atomicAdd(&t.D_STAG[(size_t)srow * M + i], v);
+                }
+        }
+        // neighbour rows that found no place in the table (rare): straight to memory
+        for (unsigned long long left = __ballot(lane < cnt && my_srow >= 0 && my_lds < 0); left != 0ull; left &= left - 1ull) {
+            const int k = __ffsll((long long)left) - 1;
+            const int srow = __builtin_amdgcn_readlane(my_srow, k);
+            for (int i = lane; i < M; i += kWave)
+                atomicAdd(&t.D_STAG[(size_t)srow * M + i], t.DKV[(sb + k) * dkv + i]);
+        }
+        for (int j0 = 0; j0 < T; j0 += kTP * kWave) {
+            float gw[kTP], gb[kTP], gq[kTP];
+            double w_rev[kTP], b_rev[kTP];
+#pragma unroll
+            for (int p = 0; p < kTP; ++p) {
+                const int j = j0 + p * kWave + lane < T ? j0 + p * kWave + lane : 0;
+                gq[p] = cnt > 0 ? t.DQIN[(size_t)x * da + M + j] : 0.0f;
+                w_rev[p] = pw.time_w_rev[j];
+                b_rev[p] = pw.time_b_rev[j];
+            }
+#pragma unroll
+            for (int p = 0; p < kTP; ++p) {
+                gw[p] = 0.0f;
+                // Phi(0)_j = cos(b_j): only the phase takes a gradient from the query row
+                gb[p] = cnt > 0 ? -time_enc_sin(w_rev[p], b_rev[p], 0.0) * gq[p] : 0.0f;
+            }
             for (int k0 = 0; k0 < cnt; k0 += kTC) {
-                float g[kTC];
+                float g[kTP][kTC];
 #pragma unroll
-                for (int u = 0; u < kTC; ++u)
-                    g[u] = k0 + u < cnt ? t.DKV[(sb + k0 + u) * dkv + M + F + j] : 0.0f;
+                for (int u = 0; u < kTC; ++u) {
+                    const int k = k0 + u < cnt ? k0 + u : cnt - 1;
+#pragma unroll
+                    for (int p = 0; p < kTP; ++p) {
+                        const int j = j0 + p * kWave + lane < T ? j0 + p * kWave + lane : 0;
+                        g[p][u] = t.DKV[(sb + k) * dkv + M + F + j];
+                    }
+                }
 #pragma unroll
                 for (int u = 0; u < kTC; ++u)
                     if (k0 + u < cnt) {  // (uniform: the shuffle is executed by every lane)
                         const double dt = shfl_f64(my_dt, k0 + u);
-                        const float sn = time_enc_sin(pw.time_w_rev[j], pw.time_b_rev[j], dt);
-                        gw += -sn * (float)dt * g[u];
-                        gb += -sn * g[u];
+#pragma unroll
+                        for (int p = 0; p < kTP; ++p) {
+                            const float sn = time_enc_sin(w_rev[p], b_rev[p], dt);
+                            gw[p] += -sn * (float)dt * g[p][u];
+                            gb[p] += -sn * g[p][u];
+                        }
                     }
             }
-            if (in) {
-                t.TG[(size_t)x * 2 * T + j] = gw;
-                t.TG[(size_t)x * 2 * T + T + j] = gb;
+#pragma unroll
+            for (int p = 0; p < kTP; ++p) {
+                const int j = j0 + p * kWave + lane;
+                if (j < T) {
+                    t.TG[(size_t)x * 2 * T + j] = gw[p];
+                    t.TG[(size_t)x * 2 * T + T + j] = gb[p];
+                }
             }
         }
     }
@@ -1041,7 +1090,7 @@ hipError_t prepare_train(const Dims &d)
 bool train_supported(const Dims &d)
 {
     // (the attention kernels keep slot k of head h in lane h * K + k of a query's wavefront)
-    return d.prec == TIG_FP32 && scatter_lds(d) <= 64 * 1024 && d.H * d.K <= kWave && d.H <= kMaxTrainHeads && d.dkv <= kAttnMaxCC * kWave;
+    return d.prec == TIG_FP32 && scatter_lds(d) <= 64 * 1024 && d.H * d.K <= kWave && d.K < kWave && d.H <= kMaxTrainHeads && d.dkv <= kAttnMaxCC * kWave;
 }
 
 static hipError_t transpose_all(const Dims &d, const TrainLayout &L, hipStream_t s)
