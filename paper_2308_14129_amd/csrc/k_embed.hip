@@ -181,25 +181,36 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
         return;  // fewer distinct queries than the grid was sized for
     TIG_MARK(0);
     // ---- A. query rows ------------------------------------------------------------------------
+    // Every load of this phase is unconditional (an index that does not apply is replaced by one that
+    // is valid, and the value dropped): a load inside a branch is waited for at the end of the branch,
+    // and the phase would be a chain of round trips instead of two.
+    double tw_w = 0.0, tw_b = 0.0;
+    if ((int)threadIdx.x < p.T) {  // (T <= 512 <= the threads of the workgroup)
+        tw_w = w.time_w_rev[threadIdx.x];
+        tw_b = w.time_b_rev[threadIdx.x];
+    }
     if (threadIdx.x < ROWS) {
         const int r = threadIdx.x;
         const int x = pass + n_passes * r;
-        int q = -1, cnt = 0;
-        int32_t ref = kRefNone;
-        double t = 0.0;
-        if (x < n_u) {
-            q = x;
-            ref = a.qs.self_ref[q];
-            cnt = a.qs.cnt[q];
-            t = a.qs.t[q];
-        } else if (x < n_rows) {
-            // a negative: node and time from the call.  For now the reference is the node's own
-            // memory row; the gather below checks whether this step updates the node.
-            const int b = x - n_u;
-            q = neg_row0 + b;
-            ref = a.neg[b];
+        const bool is_rep = x < n_u, is_neg = !is_rep && x < n_rows;
+        // a negative: node and time from the call.  For now the reference is the node's own memory
+        // row; the gather below checks whether this step updates the node.
+        const int b = is_neg ? x - n_u : 0, qq = is_rep ? x : 0;
+        const int32_t *ref_p = is_neg ? a.neg + b : a.qs.self_ref + qq;
+        const double *t_p = is_neg ? a.ts + a.first_eid + b : a.qs.t + qq;
+        int32_t ref = *ref_p;
+        double t = *t_p;
+        int cnt = a.qs.cnt[qq];
+        int q = is_rep ? x : neg_row0 + b;
+        if (is_neg) {
             ref = ref >= 0 ? ref : kRefNone;
-            t = a.ts[a.first_eid + b];
+            cnt = 0;
+        }
+        if (!is_rep && !is_neg) {
+            q = -1;
+            ref = kRefNone;
+            cnt = 0;
+            t = 0.0;
         }
         row_q[r] = q;
         row_ref[r] = checked_ref(ref);
@@ -209,9 +220,9 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
     }
     if (threadIdx.x == 0)
         *next_row = 0;
-    for (int j = threadIdx.x; j < p.T; j += kEmbedThreads) {
-        tw_tab[2 * j] = w.time_w_rev[j];
-        tw_tab[2 * j + 1] = w.time_b_rev[j];
+    if ((int)threadIdx.x < p.T) {
+        tw_tab[2 * threadIdx.x] = tw_w;
+        tw_tab[2 * threadIdx.x + 1] = tw_b;
     }
     __syncthreads();
     {
@@ -222,38 +233,38 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
         // needs no lookup; the others are looked up by the wavefront that takes the row in phase C.
         constexpr int kRowsPerWave = (ROWS + kEmbedWaves - 1) / kEmbedWaves;
         constexpr int kAhead = 2;  // 128 floats of a row per lane pair of loads
+        // A row is read through a buffer descriptor in scalar registers (base = the row, extent = the
+        // row, or nothing for a missing reference): lanes beyond the row read 0, no load sits inside a
+        // branch (the compiler waits for such a load at the end of its branch: a round trip per load),
+        // and a wavefront's rows are all in flight together.
         float v[kRowsPerWave][kAhead];
-        const float *src_row[kRowsPerWave];
+        __amdgpu_buffer_rsrc_t src_row[kRowsPerWave];
         int32_t neg_u[kRowsPerWave], neg_ref[kRowsPerWave];  // node / checked row reference of a negative, else kRefNone
         unsigned long long neg_key[kRowsPerWave];
         int64_t deg_lo[kRowsPerWave], deg_hi[kRowsPerWave];
         const RefCtx rc = ref_ctx(a);
-        auto row_ptr = [&](int32_t ref) -> const float * {
-            return ref == kRefNone ? nullptr
-                                   : (ref >= 0 ? a.mem + (size_t)ref * p.M : a.staging + (size_t)(~ref) * p.M);
+        auto row_rsrc = [&](int32_t ref) -> __amdgpu_buffer_rsrc_t {  // ref: the same in every lane
+            const float *row = ref >= 0 ? a.mem + (size_t)ref * p.M : a.staging + (size_t)(ref == kRefNone ? 0 : ~ref) * p.M;
+            return __builtin_amdgcn_make_buffer_rsrc((void *)row, 0, ref == kRefNone ? 0 : p.M * 4, kBufferFlags);
         };
+        // (with no batch applied the key array may not exist: any readable 8 bytes stand in)
+        const unsigned long long *key_tab = rc.count > 0 ? rc.key : (const unsigned long long *)a.indptr;
 #pragma unroll
         for (int i = 0; i < kRowsPerWave; ++i) {
             const int r = wave + i * kEmbedWaves;
-            const int ref = r < ROWS ? row_ref[r] : kRefNone;
-            const bool is_neg = r < ROWS && row_q[r] >= neg_row0;
-            src_row[i] = row_ptr(ref);
+            const int ref = __builtin_amdgcn_readfirstlane(r < ROWS ? row_ref[r] : kRefNone);
+            const bool is_neg = r < ROWS && __builtin_amdgcn_readfirstlane(row_q[r < ROWS ? r : 0]) >= neg_row0;
+            src_row[i] = row_rsrc(ref);
 #pragma unroll
-            for (int u = 0; u < kAhead; ++u) {
-                const int j = lane + kWave * u;
-                v[i][u] = 0.0f;
-                if (src_row[i] && j < p.M)
-                    v[i][u] = src_row[i][j];
-            }
+            for (int u = 0; u < kAhead; ++u)
+                v[i][u] = buffer_load_f32(src_row[i], (uint32_t)(lane + kWave * u) * 4u);
             neg_u[i] = is_neg ? ref : kRefNone;
-            neg_key[i] = 0ull;
-            deg_lo[i] = deg_hi[i] = 0;
-            if (neg_u[i] != kRefNone) {  // (a valid node id: checked above)
-                if (rc.count > 0)
-                    neg_key[i] = rc.key[neg_u[i]];
-                deg_lo[i] = a.indptr[neg_u[i]];
-                deg_hi[i] = a.indptr[neg_u[i] + 1];
-            }
+            const int32_t nu = neg_u[i] != kRefNone ? neg_u[i] : 0;  // (a valid node id: checked above)
+            const unsigned long long got_key = key_tab[nu];
+            const int64_t got_lo = a.indptr[nu], got_hi = a.indptr[nu + 1];
+            neg_key[i] = neg_u[i] != kRefNone && rc.count > 0 ? got_key : 0ull;
+            deg_lo[i] = neg_u[i] != kRefNone ? got_lo : 0;
+            deg_hi[i] = neg_u[i] != kRefNone ? got_hi : 0;
         }
 #pragma unroll
         for (int i = 0; i < kRowsPerWave; ++i)
@@ -262,13 +273,11 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
         for (int i = 0; i < kRowsPerWave; ++i) {
             const int r = wave + i * kEmbedWaves;
             if (r < ROWS) {
-                if (neg_ref[i] != neg_u[i]) {  // a negative this step updates: the staged row instead
-                    src_row[i] = row_ptr(neg_ref[i]);
+                if (neg_ref[i] != neg_u[i]) {  // a negative this step updates: the staged row instead (uniform)
+                    src_row[i] = row_rsrc(__builtin_amdgcn_readfirstlane(neg_ref[i]));
 #pragma unroll
-                    for (int u = 0; u < kAhead; ++u) {
-                        const int j = lane + kWave * u;
-                        v[i][u] = src_row[i] && j < p.M ? src_row[i][j] : 0.0f;
-                    }
+                    for (int u = 0; u < kAhead; ++u)
+                        v[i][u] = buffer_load_f32(src_row[i], (uint32_t)(lane + kWave * u) * 4u);
                     if (lane == 0)
                         row_ref[r] = neg_ref[i];
                 }
@@ -280,7 +289,7 @@ k_embed(StepArgs a, PackedWeights w, EmbedParams p)
                     if (lane + kWave * u < p.Mq)
                         P::store_a(dst, lane + kWave * u, v[i][u]);
                 for (int j = lane + kWave * kAhead; j < p.Mq; j += kWave)  // rows beyond 128 floats
-                    P::store_a(dst, j, src_row[i] && j < p.M ? src_row[i][j] : 0.0f);
+                    P::store_a(dst, j, buffer_load_f32(src_row[i], (uint32_t)j * 4u));
             }
         }
     }
