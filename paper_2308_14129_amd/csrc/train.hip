@@ -192,35 +192,50 @@ __global__ void __launch_bounds__(kGatherWaves *kWave) k_tr_gather(StepArgs a, P
         if (j < M)
             t.X1[(size_t)x * (da + M) + da + j] = v;
     }
-    // kGC slots at a time: all their loads are issued before the first store (a store between two
-    // slots' loads would make every slot wait for its own round trip)
-    constexpr int kGC = 5;
+    // kGC slots at a time, every piece of their rows requested before the first store: a lane's memory
+    // operations complete in order (a load behind a store waits for the store's round trip), and a load
+    // inside a branch is waited for at the end of the branch, so every load here is unconditional (from
+    // an address that is valid in any case, the value dropped) and the slots' references are scalars.
+    constexpr int kGC = 5, kGP = 4;  // slots x 64-column pieces of a row per batch
     for (int k0 = 0; k0 < cnt; k0 += kGC) {
-        const float *row[kGC];
-        int32_t eid[kGC];
+        const float *row[kGC];   // (scalar registers: k is the same in every lane)
+        const float *feat[kGC];
         double dt[kGC];
 #pragma unroll
         for (int u = 0; u < kGC; ++u) {
-            const int k = k0 + u < cnt ? k0 + u : cnt - 1;  // (uniform; the shuffles are executed by every lane)
-            row[u] = state_row(a, M, __shfl(my_ref, k));
-            eid[u] = __shfl(my_eid, k);
-            dt[u] = t_q - shfl_f64(my_ts, k);
+            const int k = k0 + u < cnt ? k0 + u : cnt - 1;
+            row[u] = state_row(a, M, __builtin_amdgcn_readlane(my_ref, k));
+            const int32_t eid = __builtin_amdgcn_readlane(my_eid, k);
+            feat[u] = eid >= 0 ? a.edge_feat + (size_t)eid * F : nullptr;
+            dt[u] = t_q - readlane_f64(my_ts, k);
         }
-        for (int i = lane; i < dkv; i += kWave) {
-            float v[kGC];
+        for (int i0 = 0; i0 < dkv; i0 += kGP * kWave) {
+            float v[kGC][kGP];
+            double tw[kGP], tb[kGP];
 #pragma unroll
-            for (int u = 0; u < kGC; ++u) {
-                if (i < M)
-                    v[u] = row[u] ? row[u][i] : 0.0f;
-                else if (i < M + F)
-                    v[u] = eid[u] >= 0 ? a.edge_feat[(size_t)eid[u] * F + (i - M)] : 0.0f;
-                else
-                    v[u] = time_enc(pw.time_w_rev[i - M - F], pw.time_b_rev[i - M - F], dt[u]);
+            for (int c = 0; c < kGP; ++c) {
+                const int i = i0 + c * kWave + lane;
+                const bool is_state = i < M, is_feat = i >= M && i < M + F, is_time = i >= M + F && i < dkv;
+                const int jt = is_time ? i - M - F : 0;
+                tw[c] = pw.time_w_rev[jt];
+                tb[c] = pw.time_b_rev[jt];
+#pragma unroll
+                for (int u = 0; u < kGC; ++u) {
+                    const float *src = is_state ? row[u] : (is_feat ? feat[u] : nullptr);
+                    const int off = is_state ? i : i - M;
+                    const float got = (src ? src : a.mem)[src ? off : 0];
+                    v[u][c] = src ? got : 0.0f;
+                }
             }
 #pragma unroll
-            for (int u = 0; u < kGC; ++u)
-                if (k0 + u < cnt)
-                    t.KV[((size_t)sb + k0 + u) * dkv + i] = v[u];
+            for (int c = 0; c < kGP; ++c) {
+                const int i = i0 + c * kWave + lane;
+                const bool is_time = i >= M + F && i < dkv;
+#pragma unroll
+                for (int u = 0; u < kGC; ++u)
+                    if (k0 + u < cnt && i < dkv)
+                        t.KV[((size_t)sb + k0 + u) * dkv + i] = is_time ? time_enc(tw[c], tb[c], dt[u]) : v[u][c];
+            }
         }
     }
 }
