@@ -196,7 +196,7 @@ __global__ void __launch_bounds__(kGatherWaves *kWave) k_tr_gather(StepArgs a, P
     // operations complete in order (a load behind a store waits for the store's round trip), and a load
     // inside a branch is waited for at the end of the branch, so every load here is unconditional (from
     // an address that is valid in any case, the value dropped) and the slots' references are scalars.
-    constexpr int kGC = 5, kGP = 4;  // slots x 64-column pieces of a row per batch
+    constexpr int kGC = 5, kGP = 2;  // slots x 64-column pieces of a row per batch
     for (int k0 = 0; k0 < cnt; k0 += kGC) {
         const float *row[kGC];   // (scalar registers: k is the same in every lane)
         const float *feat[kGC];
