@@ -536,8 +536,8 @@ static int step_impl(tig_ctx *ctx, const tig_batch *batch, const tig_out *out, h
         return fail(ctx, TIG_EINVAL, "tig_step: the context was created without weights and no module selection is attached");
     if (general && (use_static || train))
         return fail(ctx, TIG_EINVAL, "tig_step_static / tig_train_step: the context runs an attached module selection");
-    // a training step or a step of a module selection prepares nothing for a later step and takes
-    // nothing prepared for it
+    // a training step or a step of a module selection has no embedding launch to carry a later
+    // step's preparation (a training step runs it on its second stream instead, see side_prep)
     const bool solo = train || general;
     const bool wants_queries = !general || ctx->mods.emb == TIG_EMB_ATTENTION;
     StepScratch st = ctx->S;

@@ -30,6 +30,7 @@
 //                   on a second stream beside the rest of the backward pass (forked when their rows
 //                   are complete, joined ahead of the update)
 //   k_colsum        bias and time-encoding gradients: column sums of stored per-row values
+//   k_tr_update     memory overwrite, sum of the loss terms and the SGD update in one launch
 // Weight matrices are kept twice, [out x in] and transposed: a thread that owns an output reads
 // the transposed copy, a thread that owns an input the native one, so both directions are
 // coalesced.
