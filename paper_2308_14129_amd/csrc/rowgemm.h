@@ -55,15 +55,20 @@ struct RowGemm {
 };
 
 // Four consecutive k of one operand row.  VEC (rows 16-byte aligned, Kd a multiple of 4): one load,
-// no branch -- a row or k outside the operand reads a valid address and is zeroed afterwards.
+// no branch -- a k outside the operand reads a valid address and is zeroed afterwards (finite values
+// are assumed there: the row's first elements).
 template <bool VEC>
 __device__ inline floatx4 load_k4(const float *row, int k, int Kd, bool ok, int vec)
 {
     floatx4 v = {0.0f, 0.0f, 0.0f, 0.0f};
     if (VEC) {
-        const bool in = ok && k < Kd;
+        // (a load behind a condition is waited for at the end of its branch, and the compiler makes a
+        // branch of a choice between a loaded value and zero: the load is unconditional from a valid
+        // address and a k beyond the row is multiplied away; rows and columns outside the product
+        // read row 0 and are never stored)
         const floatx4 r = *(const floatx4 *)(row + (k < Kd ? k : 0));
-        return in ? r : v;
+        const float m = k < Kd ? 1.0f : 0.0f;
+        return floatx4{r[0] * m, r[1] * m, r[2] * m, r[3] * m};
     }
     if (!ok)
         return v;
@@ -140,50 +145,79 @@ __device__ inline void rowgemm_accumulate(const RowGemm &p, int rows, int r0, in
     }
 }
 
-// Epilogue and store of the 16 x 16 sub-blocks (i, j) with i in [i_lo, i_hi), j in [j_lo, j_hi) of the block.
-__device__ inline void rowgemm_store(const RowGemm &p, int rows, int r0, int tn, int z, const floatx4 (&acc)[2][2], int i_lo,
-                                     int i_hi, int j_lo, int j_hi)
+// Epilogue of one 16 x 16 sub-block (i, j) of a block: the lane holds rows 16 i + 4 g + v (v = 0..3) of
+// column 16 j + c.  What the epilogue reads (bias, gate, row mask) is loaded unconditionally -- from a
+// valid address where the product has no such input, the value then plays no part -- and ahead of
+// the first store, so that a sub-block costs one round trip (a load inside a branch is waited for at
+// the end of the branch: one round trip per load).
+struct RowGemmEpi {
+    float bias, gate[4];
+    int32_t mask[4];
+};
+
+// the output-row remapping's row count (0 without one), requested early
+__device__ inline int rowgemm_remap_count(const RowGemm &p)
+{
+    const int32_t *src = p.remap_nu ? p.remap_nu : (const int32_t *)p.W;
+    const int nu = *src;
+    return p.remap_nu ? (nu < 0 ? 0 : (nu < p.remap_2b ? nu : p.remap_2b)) : 0;
+}
+
+__device__ inline int rowgemm_out_row(const RowGemm &p, int r, int nu)
+{
+    return p.remap_nu ? (r < nu ? r : p.remap_2b + (r - nu)) : r;
+}
+
+__device__ inline RowGemmEpi rowgemm_epi_load(const RowGemm &p, int rows, int r0, int tn, int z, int i, int j, int nu)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int c = lane & 15, g = lane >> 4;
-    const int n0 = tn * 32;
     const int split = p.n_split > 0 ? p.n_split : p.N;
-    int nu = 0;
-    if (p.remap_nu) {
-        nu = *p.remap_nu;
-        nu = nu < 0 ? 0 : (nu < p.remap_2b ? nu : p.remap_2b);
+    const int n = tn * 32 + 16 * j + c;
+    const int nc = n < p.N ? n : 0;
+    const bool hi = nc >= split;
+    const float *bptr = hi ? p.bias_hi : (p.bias ? p.bias + (size_t)z * p.zBias : nullptr);
+    RowGemmEpi e;
+    e.bias = (bptr ? bptr : p.W)[bptr ? (hi ? nc - split : nc) : 0] * (bptr ? 1.0f : 0.0f);
+    const float *gp = p.gate ? p.gate : p.W;
+    const int32_t *mp = p.rowmask ? p.rowmask : (const int32_t *)p.W;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int r = r0 + 16 * i + 4 * g + v;
+        const int rc = r < rows ? r : 0;
+        e.mask[v] = mp[p.rowmask ? rc : 0];
+        e.gate[v] = gp[p.gate ? (size_t)rowgemm_out_row(p, rc, nu) * p.ldg + nc : 0];
     }
+    return e;
+}
+
+__device__ inline void rowgemm_epi_store(const RowGemm &p, int rows, int r0, int tn, int z, const floatx4 &acc, int i, int j,
+                                         int nu, const RowGemmEpi &e)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int c = lane & 15, g = lane >> 4;
+    const int split = p.n_split > 0 ? p.n_split : p.N;
+    const int n = tn * 32 + 16 * j + c;
+    if (n >= p.N)
+        return;
+    const bool hi = n >= split;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int r = r0 + 16 * i + 4 * g + v;
-            if (r >= rows || i < i_lo || i >= i_hi)
-                continue;
-            int orow = r;
-            const bool dead = p.rowmask && p.rowmask[orow] == 0;
-            if (p.remap_nu)
-                orow = r < nu ? r : p.remap_2b + (r - nu);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int n = n0 + 16 * j + c;
-                if (n >= p.N || j < j_lo || j >= j_hi)
-                    continue;
-                const bool hi = n >= split;
-                const float *bias = hi ? p.bias_hi : (p.bias ? p.bias + (size_t)z * p.zBias : nullptr);
-                float val = acc[i][j][v] + (bias ? bias[hi ? n - split : n] : 0.0f);
-                if (p.relu)
-                    val = fmaxf(val, 0.0f);
-                if (p.gate && !(p.gate[(size_t)orow * p.ldg + n] > 0.0f))
-                    val = 0.0f;
-                if (dead && !hi)
-                    val = 0.0f;
-                if (hi)
-                    p.C_hi[(size_t)orow * p.ldc_hi + (n - split)] = val;
-                else
-                    p.C[(size_t)z * p.zC + (size_t)orow * p.ldc + n] = val;
-            }
-        }
+    for (int v = 0; v < 4; ++v) {
+        const int r = r0 + 16 * i + 4 * g + v;
+        if (r >= rows)
+            continue;
+        const int orow = rowgemm_out_row(p, r, nu);
+        float val = acc[v] + e.bias;
+        if (p.relu)
+            val = fmaxf(val, 0.0f);
+        const bool gated_off = (p.gate != nullptr) & !(e.gate[v] > 0.0f);
+        const bool dead = (p.rowmask != nullptr) & (e.mask[v] == 0) & !hi;
+        val = (gated_off | dead) ? 0.0f : val;
+        if (hi)
+            p.C_hi[(size_t)orow * p.ldc_hi + (n - split)] = val;
+        else
+            p.C[(size_t)z * p.zC + (size_t)orow * p.ldc + n] = val;
+    }
 }
 
 template <bool VEC>
@@ -195,9 +229,20 @@ __device__ inline void rowgemm_tile(const RowGemm &p, int rows, int r0, int tn, 
 #pragma unroll
         for (int j = 0; j < 2; ++j)
             acc[i][j] = floatx4{0, 0, 0, 0};
+    const int nu = rowgemm_remap_count(p);
     for (int pass = 0; pass < (p.A2 ? 2 : 1); ++pass)
         rowgemm_accumulate<VEC>(p, rows, r0, tn, z, pass, 0, pass ? p.Kd2 : p.Kd, acc);
-    rowgemm_store(p, rows, r0, tn, z, acc, 0, 2, 0, 2);
+    RowGemmEpi e[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            e[i][j] = rowgemm_epi_load(p, rows, r0, tn, z, i, j, nu);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            rowgemm_epi_store(p, rows, r0, tn, z, acc[i][j], i, j, nu, e[i][j]);
 }
 
 // The same product with the k range of a block split over the four wavefronts of a workgroup
@@ -212,6 +257,7 @@ __global__ void __launch_bounds__(256) k_rowgemm_ks(RowGemm p)
     const int lane = threadIdx.x & (kWave - 1), w = (int)threadIdx.x / kWave;
     const int tn = (int)blockIdx.y, z = (int)blockIdx.z;
     const int kq = ((p.Kd + 3) / 4 + 15) / 16 * 16;  // k per wavefront, a multiple of 16
+    const int nu = rowgemm_remap_count(p);
     for (int r0 = (int)blockIdx.x * 32; r0 < rows; r0 += (int)gridDim.x * 32) {
         floatx4 acc[2][2];
 #pragma unroll
@@ -219,6 +265,8 @@ __global__ void __launch_bounds__(256) k_rowgemm_ks(RowGemm p)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
                 acc[i][j] = floatx4{0, 0, 0, 0};
+        // (what this wavefront's sub-block (w / 2, w % 2) needs for its epilogue is requested ahead of the products)
+        const RowGemmEpi e = rowgemm_epi_load(p, rows, r0, tn, z, w >> 1, w & 1, nu);
         rowgemm_accumulate<VEC>(p, rows, r0, tn, z, 0, w * kq, (w + 1) * kq, acc);
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -229,16 +277,11 @@ __global__ void __launch_bounds__(256) k_rowgemm_ks(RowGemm p)
                     red[w][(i * 2 + j) * 4 + v][lane] = acc[i][j][v];
         __syncthreads();
         const int si = w >> 1, sj = w & 1;
+        floatx4 sum;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (i == si && j == sj)
-                        acc[i][j][v] = (red[0][(i * 2 + j) * 4 + v][lane] + red[1][(i * 2 + j) * 4 + v][lane]) +
-                                       (red[2][(i * 2 + j) * 4 + v][lane] + red[3][(i * 2 + j) * 4 + v][lane]);
-        rowgemm_store(p, rows, r0, tn, z, acc, si, si + 1, sj, sj + 1);
+        for (int v = 0; v < 4; ++v)
+            sum[v] = (red[0][w * 4 + v][lane] + red[1][w * 4 + v][lane]) + (red[2][w * 4 + v][lane] + red[3][w * 4 + v][lane]);
+        rowgemm_epi_store(p, rows, r0, tn, z, sum, si, sj, nu, e);
         __syncthreads();  // (the partial blocks are reused by the next row block)
     }
 }
